@@ -1,0 +1,43 @@
+"""Reference scoring / ranking pass (numpy, fp64).  TEST INFRASTRUCTURE ONLY.
+
+The task is a ranking problem over all entities [Sec. 3.2 "Objective
+Function"]: f(q, e) = gamma - min_b ||y_b - Ef[e]||_1.  Smaller distance is
+better; equal distances rank the lower entity id first.
+"""
+import numpy as np
+
+from .model import dnf, forward, query_tree
+
+
+def query_embeddings(batch, i, M):
+    """[n_branches, d] branch embeddings of query i."""
+    return np.stack([forward(b, M)[0] for b in dnf(query_tree(batch.query_nodes(i)))])
+
+
+def score_candidates(batch, cand, M):
+    """cand [B, C] entity ids -> scores [B, C]."""
+    out = np.empty(cand.shape, np.float64)
+    for i in range(batch.B):
+        Y = query_embeddings(batch, i, M)
+        rows = M.entity(np.asarray(cand[i], np.int64))
+        out[i] = M.gamma - np.abs(Y[:, None, :] - rows[None]).sum(axis=2).min(axis=0)
+    return out
+
+
+def distances_all(batch, i, M, chunk=8192):
+    """L1 distance of query i to every entity, [N]."""
+    Y = query_embeddings(batch, i, M)
+    N = M.P["E"].shape[0]
+    out = np.empty(N, np.float64)
+    for lo in range(0, N, chunk):
+        ids = np.arange(lo, min(N, lo + chunk))
+        rows = M.entity(ids)
+        out[lo:lo + len(ids)] = np.abs(Y[:, None, :] - rows[None]).sum(axis=2).min(axis=0)
+    return out
+
+
+def topk_all(batch, i, M, k):
+    """(ids, distances) of the k nearest entities: full sort, ties by id."""
+    dist = distances_all(batch, i, M)
+    order = np.lexsort((np.arange(dist.shape[0]), dist))[:k]
+    return order.astype(np.int64), dist[order]

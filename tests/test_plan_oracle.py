@@ -1,0 +1,204 @@
+"""Pins of the reference planner: per-template operator census (closed form from
+the 14 query shapes), structural invariants of operator-level scheduling
+(every operator exactly once, only after its inputs; groups homogeneous in type
+and input count), and brute-force checks of the gradient indices."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import model as om
+from oracle import plan as oplan
+
+P, I, N = om.OP_PROJ, om.OP_INTER, om.OP_NEG
+
+# template -> (anchors, roots, {(level, type, nin): count})
+CENSUS = {
+    "1p": (1, 1, {(1, P, 1): 1}),
+    "2p": (1, 1, {(1, P, 1): 1, (2, P, 1): 1}),
+    "3p": (1, 1, {(1, P, 1): 1, (2, P, 1): 1, (3, P, 1): 1}),
+    "2i": (2, 1, {(1, P, 1): 2, (2, I, 2): 1}),
+    "3i": (3, 1, {(1, P, 1): 3, (2, I, 3): 1}),
+    "ip": (2, 1, {(1, P, 1): 2, (2, I, 2): 1, (3, P, 1): 1}),
+    "pi": (2, 1, {(1, P, 1): 2, (2, P, 1): 1, (3, I, 2): 1}),
+    "2u": (2, 2, {(1, P, 1): 2}),
+    "up": (2, 2, {(1, P, 1): 2, (2, P, 1): 2}),
+    "2in": (2, 1, {(1, P, 1): 2, (2, N, 1): 1, (3, I, 2): 1}),
+    "3in": (3, 1, {(1, P, 1): 3, (2, N, 1): 1, (3, I, 3): 1}),
+    "inp": (2, 1, {(1, P, 1): 2, (2, N, 1): 1, (3, I, 2): 1, (4, P, 1): 1}),
+    "pin": (2, 1, {(1, P, 1): 2, (2, P, 1): 1, (2, N, 1): 1, (3, I, 2): 1}),
+    "pni": (2, 1, {(1, P, 1): 2, (2, P, 1): 1, (3, N, 1): 1, (4, I, 2): 1}),
+}
+
+
+@pytest.fixture(scope="module")
+def kg():
+    return wl.make_kg(400, 12, 4000, 2.1, 11)
+
+
+def census_of(plan):
+    return {(int(l), int(t), int(k)): int(n) for l, t, k, n in
+            zip(plan["g_level"], plan["g_type"], plan["g_nin"], plan["g_n"])}
+
+
+@pytest.mark.parametrize("name", sorted(CENSUS))
+def test_single_template_census(kg, name):
+    qb = wl.make_batch(kg, 5, {name: 1.0}, 3)
+    plan = oplan.build_plan(qb)
+    anchors, roots, groups = CENSUS[name]
+    assert plan["n_anchor"] == 5 * anchors
+    assert plan["n_roots"] == 5 * roots
+    assert census_of(plan) == {k: 5 * v for k, v in groups.items()}
+
+
+def test_mixed_batch_census_is_the_sum_over_templates(kg):
+    qb = wl.make_batch(kg, 200, {n: 1.0 for n in CENSUS}, 4)
+    plan = oplan.build_plan(qb)
+    want, anchors, roots = {}, 0, 0
+    for name in qb.names:
+        a, r, g = CENSUS[name]
+        anchors += a
+        roots += r
+        for k, v in g.items():
+            want[k] = want.get(k, 0) + v
+    assert census_of(plan) == want
+    assert plan["n_anchor"] == anchors and plan["n_roots"] == roots
+    assert plan["n_levels"] == 4
+    # the 14-template mean the scope table quotes: 27/14 anchors, 37/14 projections per query
+    tot = {n: CENSUS[n] for n in CENSUS}
+    assert sum(a for a, _, _ in tot.values()) == 27
+    assert sum(v for _, _, g in tot.values() for (l, t, k), v in g.items() if t == P) == 37
+
+
+def check_invariants(qb, plan):
+    S, A = plan["n_slots"], plan["n_anchor"]
+    G = plan["n_groups"]
+    level_of_slot = np.full(S, -1)
+    type_of_slot = np.full(S, -1)
+    seen = np.zeros(S, int)
+    keys = []
+    mlp_rows = {P: [], I: [], N: []}
+    for g in range(G):
+        l, t, k, n = (int(plan[x][g]) for x in ("g_level", "g_type", "g_nin", "g_n"))
+        keys.append((l, t, k))
+        ob = int(plan["g_out_base"][g])
+        seen[ob:ob + n] += 1
+        level_of_slot[ob:ob + n] = l
+        type_of_slot[ob:ob + n] = t
+        mb = int(plan["g_mlp_base"][g])
+        mlp_rows[t].extend(range(mb, mb + n * (k if t == I else 1)))
+    assert keys == sorted(keys) and len(set(keys)) == G          # ordered, one group per key
+    assert np.all(seen == 1)                                     # every operator exactly once
+    assert np.all(np.diff(type_of_slot) >= 0)                    # slots are type-major
+    for t, n in ((P, plan["n_proj"]), (N, plan["n_neg"]), (I, plan["n_int_rows"])):
+        assert sorted(mlp_rows[t]) == list(range(n))
+    consumers = np.zeros(S + A, int)
+    for g in range(G):
+        l, t, k, n = (int(plan[x][g]) for x in ("g_level", "g_type", "g_nin", "g_n"))
+        ro = int(plan["g_ref_off"][g])
+        refs = plan["in_ref"][ro:ro + k * n].reshape(k, n)
+        gs = plan["in_gslot"][ro:ro + k * n].reshape(k, n)
+        lv = np.where(refs >= 0, level_of_slot[np.maximum(refs, 0)], 0)
+        assert np.all(lv < l) and np.all(lv.max(axis=0) == l - 1)    # ASAP levels
+        assert np.all(gs[refs >= 0] == refs[refs >= 0])
+        assert np.all(gs[refs < 0] >= S)
+        assert np.array_equal(plan["anchor_ent"][gs[refs < 0] - S], -1 - refs[refs < 0])
+        np.add.at(consumers, gs.reshape(-1), 1)
+        if t == P:
+            assert k == 1 and plan["g_rel_off"][g] >= 0
+        else:
+            assert plan["g_rel_off"][g] == -1
+    for s in plan["root_slot"]:
+        consumers[s] += 1
+    assert np.all(consumers == 1)                                # trees: one consumer each
+    assert plan["root_off"][0] == 0 and plan["root_off"][-1] == plan["n_roots"]
+    lo = plan["lvl_off"]
+    assert lo[0] == 0 and lo[1] == 0 and lo[-1] == G
+    for l in range(1, plan["n_levels"] + 1):
+        assert np.all(plan["g_level"][lo[l]:lo[l + 1]] == l)
+
+
+def test_plan_invariants_mixed(kg):
+    qb = wl.make_batch(kg, 300, {n: 1.0 for n in CENSUS}, 9)
+    check_invariants(qb, oplan.build_plan(qb))
+
+
+def test_plan_values_through_refs_match_per_query_execution(kg):
+    """Executing the plan's groups level by level with the oracle's operators gives,
+    at every root slot, the per-query branch embedding."""
+    qb = wl.make_batch(kg, 40, {n: 1.0 for n in CENSUS}, 10)
+    plan = oplan.build_plan(qb)
+    p = wl.make_params(400, 12, 8, 16, 5)
+    M = om.Model(p, 12.0)
+    Pm = M.P
+    A = np.zeros((plan["n_slots"], 8))
+    for g in range(plan["n_groups"]):
+        t, k, n = (int(plan[x][g]) for x in ("g_type", "g_nin", "g_n"))
+        ro, ob = int(plan["g_ref_off"][g]), int(plan["g_out_base"][g])
+        refs = plan["in_ref"][ro:ro + k * n].reshape(k, n)
+        for i in range(n):
+            xs = [A[r] if r >= 0 else Pm["E"][-1 - r] for r in refs[:, i]]
+            if t == P:
+                r = int(plan["rel"][int(plan["g_rel_off"][g]) + i])
+                A[ob + i] = om.mlp_forward(xs[0] + Pm["R"][r], Pm["W1"], Pm["b1"], Pm["W2"], Pm["b2"])[0]
+            elif t == N:
+                A[ob + i] = om.mlp_forward(xs[0], Pm["V1"], Pm["c1"], Pm["V2"], Pm["c2"])[0]
+            else:
+                att = np.stack([om.mlp_forward(x, Pm["U1"], Pm["u1"], Pm["U2"], Pm["u2"])[0] for x in xs])
+                w = np.exp(att - att.max(0))
+                w /= w.sum(0)
+                A[ob + i] = (w * np.stack(xs)).sum(0)
+    for q in range(qb.B):
+        br = om.dnf(qb.tree(q))
+        slots = plan["root_slot"][plan["root_off"][q]:plan["root_off"][q + 1]]
+        assert len(br) == len(slots)
+        for b, s in zip(br, slots):
+            np.testing.assert_allclose(A[s], om.forward(b, M)[0], rtol=1e-12, atol=1e-14)
+
+
+def brute_index(keys):
+    uniq = sorted(set(int(k) for k in keys))
+    off, src = [0], []
+    for u in uniq:
+        src.extend(i for i, k in enumerate(keys) if int(k) == u)
+        off.append(len(src))
+    return uniq, off, src
+
+
+def test_gradient_indices_against_brute_force(kg):
+    qb = wl.make_batch(kg, 30, {n: 1.0 for n in CENSUS}, 12)
+    plan = oplan.build_plan(qb)
+    negs = wl.make_negatives(400, 30, 6, 13)
+    negs[:, 0] = negs[0, 0]                      # one entity hit by every query
+    u, off, src = oplan.entity_index(plan, qb.pos, negs)
+    keys = list(plan["anchor_ent"]) + list(qb.pos) + list(negs.reshape(-1))
+    bu, boff, bsrc = brute_index(keys)
+    assert list(u) == bu and list(off) == boff and list(src) == bsrc
+    # relation index: one contribution per projection, source = gradient row of its input
+    S = plan["n_slots"]
+    rel_of_proj, src_of_proj = [None] * plan["n_proj"], [None] * plan["n_proj"]
+    for g in range(plan["n_groups"]):
+        if plan["g_type"][g] != P:
+            continue
+        n, ob, ro, rl = (int(plan[x][g]) for x in ("g_n", "g_out_base", "g_ref_off", "g_rel_off"))
+        for i in range(n):
+            rel_of_proj[ob + i] = int(plan["rel"][rl + i])
+            src_of_proj[ob + i] = int(plan["in_gslot"][ro + i])
+    bu, boff, bsrc = brute_index(rel_of_proj)
+    assert list(plan["r_uniq"]) == bu and list(plan["r_seg_off"]) == boff
+    assert list(plan["r_src"]) == [src_of_proj[i] for i in bsrc]
+    assert all(0 <= s < S + plan["n_anchor"] for s in plan["r_src"])
+
+
+def test_unsupported_and_degenerate():
+    bad = wl.batch_from_trees([("i", ("u", ("p", 0, ("e", 1)), ("p", 1, ("e", 2))), ("p", 0, ("e", 3)))], [0])
+    with pytest.raises(om.Unsupported):
+        oplan.build_plan(bad)
+    with pytest.raises(om.Unsupported):
+        oplan.build_plan(wl.batch_from_trees([("e", 3)], [0]))
+    empty = oplan.build_plan(wl.batch_from_trees([], []))
+    assert empty["n_groups"] == 0 and empty["n_slots"] == 0 and list(empty["root_off"]) == [0]
+    # a union of three branches under two projections
+    q = ("p", 5, ("p", 4, ("u", ("p", 0, ("e", 1)), ("p", 1, ("e", 2)), ("p", 2, ("e", 3)))))
+    pl = oplan.build_plan(wl.batch_from_trees([q], [0]))
+    assert pl["n_roots"] == 3 and pl["n_proj"] == 9 and pl["n_levels"] == 3
+    assert list(pl["rel"]) == [0, 1, 2, 4, 4, 4, 5, 5, 5]
