@@ -1,0 +1,235 @@
+/*
+ * libngdb -- one operator-level training step of a neural graph database on one
+ * MI355X (gfx950).  C boundary: plain pointers and sizes, no C++ or torch types.
+ *
+ * The step follows the paper's operator-level training loop (Alg. 1): a batch
+ * of first-order-logic queries of mixed shapes is decomposed into a DAG of
+ * atomic operators (Sec. 4.1 "Graph Decomposition"), operators of one type that
+ * are ready at the same depth are executed as one batch with that type's
+ * shared parameters (Sec. 4.1 "Batched Execution"), intersections are split by
+ * input count (Sec. 4.3, equivalence classes C_k), the objective is evaluated
+ * for all positive and negative candidates at once with gather/scatter
+ * offsets computed ahead of time (Sec. 4.2), gradients flow back through the
+ * same groups in reverse, and one Adam step ends it (Alg. 1, last line).
+ *
+ * Model (the paper names the operators but prints no formulas; these are the
+ * definitions of the workloads this library is measured on):
+ *   projection    y = W2 relu(W1 (x + R[r]) + b1) + b2        W1 [h,d], W2 [d,h]
+ *   negation      y = V2 relu(V1 x + c1) + c2
+ *   intersection  a_k = U2 relu(U1 x_k + u1) + u2; w = softmax over the k inputs
+ *                 (per coordinate); y = sum_k w_k * x_k
+ *   union         disjunctive normal form; score = max over branches
+ *   score         s(q,e) = gamma - min_b ||y_b - E[e]||_1
+ *   loss          1/(2B) sum_i [ -log sig(s(q_i,pos_i)) - 1/K sum_j log sig(-s(q_i,neg_ij)) ]
+ *   optimiser     Adam; dense on the MLP tensors, row-sparse (lazy) on E and R:
+ *                 a table row is updated only in steps in which it received a
+ *                 gradient contribution; the bias correction uses the global step.
+ *
+ * Conventions
+ *   - Every call returns 0 (NGDB_OK) or a negative error code; nothing throws
+ *     or aborts across the boundary.  ngdb_last_error() gives the text.
+ *   - "device" pointers are HIP device memory owned by the caller (row-major,
+ *     contiguous, 16-byte aligned); the library borrows them.  "host" pointers
+ *     are ordinary memory, borrowed only for the duration of the call.
+ *   - The library keeps a private device workspace that grows on demand.
+ *   - A stream argument is a hipStream_t passed as void*; NULL = the null
+ *     stream.  Calls that take a stream are asynchronous with respect to the
+ *     host unless stated otherwise.  One context must not be used from two
+ *     host threads or two streams at the same time.
+ *   - All index arrays are int32.  d and h must be multiples of 4.
+ */
+#ifndef NGDB_H
+#define NGDB_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define NGDB_OK               0
+#define NGDB_ERR_ARG         -1   /* null pointer, bad size, malformed query        */
+#define NGDB_ERR_UNSUPPORTED -2   /* union below an intersection/negation, query
+                                     without an operator, more than NGDB_MAX_CARD
+                                     inputs, deeper than NGDB_MAX_LEVELS            */
+#define NGDB_ERR_RANGE       -3   /* entity / relation id out of range              */
+#define NGDB_ERR_OOM         -4   /* host or device allocation failed               */
+#define NGDB_ERR_HIP         -5   /* a HIP runtime call failed                      */
+#define NGDB_ERR_STATE       -6   /* call order: parameters not bound, no gradients */
+
+#define NGDB_OP_ANCHOR 0   /* arg = entity id, no inputs            */
+#define NGDB_OP_PROJ   1   /* arg = relation id, one input          */
+#define NGDB_OP_INTER  2   /* 2..NGDB_MAX_CARD inputs               */
+#define NGDB_OP_NEG    3   /* one input                             */
+#define NGDB_OP_UNION  4   /* >= 1 inputs; removed by the planner   */
+
+#define NGDB_MAX_CARD    8    /* inputs of one intersection             */
+#define NGDB_MAX_LEVELS 64    /* operator depth of one query            */
+#define NGDB_MAX_BRANCH 64    /* conjunctive branches of one query      */
+
+typedef struct ngdb_ctx_s ngdb_ctx_t;     /* opaque: configuration, workspace, streams */
+typedef struct ngdb_plan_s ngdb_plan_t;   /* opaque: one planned batch                 */
+
+typedef struct ngdb_config {
+    int32_t n_entities;
+    int32_t n_relations;
+    int32_t d;             /* embedding width (multiple of 4)                        */
+    int32_t h;             /* hidden width of the three MLPs (multiple of 4)         */
+    int32_t d_sem;         /* width of the frozen text features, 0 = none            */
+    int32_t num_streams;   /* 1 = everything on the caller's stream; 2..4 = the
+                              independent operator groups of one depth run on this
+                              many library-owned streams (Sec. 4.3 "Multi-stream
+                              Operator Execution")                                    */
+    float gamma;
+    float lr, beta1, beta2, eps;
+} ngdb_config;
+
+/* A trainable tensor with its Adam moments (all device, fp32, same shape). */
+typedef struct ngdb_tensor {
+    float* p;
+    float* m;
+    float* v;
+} ngdb_tensor;
+
+typedef struct ngdb_params {
+    ngdb_tensor E;                  /* [n_entities, d]                               */
+    ngdb_tensor R;                  /* [n_relations, d]                              */
+    ngdb_tensor W1, b1, W2, b2;     /* projection   [h,d] [h] [d,h] [d]              */
+    ngdb_tensor V1, c1, V2, c2;     /* negation                                      */
+    ngdb_tensor U1, u1, U2, u2;     /* intersection attention                        */
+    ngdb_tensor Wp;                 /* [d, d_sem] text projection, unused if d_sem=0 */
+    const uint16_t* H_sem;          /* device [n_entities, d_sem] bf16 bit patterns,
+                                       frozen (Sec. 4.4, GPU-resident semantic cache) */
+    int64_t step;                   /* optimiser steps already applied to this state */
+} ngdb_params;
+
+/* A batch of queries, host memory.  Query i owns nodes node_off[i]..node_off[i+1]-1;
+ * inputs of node n are in_idx[in_off[n]..in_off[n+1]-1], positions local to the
+ * query that must be smaller than n's own position; the root is the query's last
+ * node (Sec. 3.1 query patterns; Sec. 4.1 DAG of atomic operators).              */
+typedef struct ngdb_query_batch {
+    int32_t n_queries;
+    const int32_t* node_off;   /* [n_queries+1] */
+    const uint8_t* op;         /* [n_nodes]  NGDB_OP_*                              */
+    const int32_t* arg;        /* [n_nodes]                                         */
+    const int32_t* in_off;     /* [n_nodes+1]                                       */
+    const int32_t* in_idx;     /* [in_off[n_nodes]]                                 */
+    const int32_t* pos;        /* [n_queries] positive answer entity                */
+} ngdb_query_batch;
+
+/* Read-only host view of a plan; valid until ngdb_plan_free().  Canonical form:
+ *  - unions removed by DNF (branches in input order; projections above a union
+ *    repeated per branch); nodes numbered in (query, branch, depth-first
+ *    post-order) order; level(anchor)=0, level(op)=1+max level of its inputs;
+ *  - group = operator nodes with equal (level, type, input count), ordered by
+ *    level, type (PROJ<INTER<NEG), input count; members in node order;
+ *  - output slots type-major (projections, intersections, negations), in group
+ *    order inside a type; gradient row of anchor a is n_slots + a;
+ *  - in_ref[g_ref_off[g] + j*n + i] = input j of member i: slot (>=0) or
+ *    -1-entity; in_gslot = the same as a gradient row;
+ *  - MLP rows: PROJ/NEG rank inside the type; INTER group: g_mlp_base + j*n + i;
+ *  - relation gradient index: stable grouping by relation id of the projections
+ *    in slot order, r_src = gradient row of the projection's input.            */
+typedef struct ngdb_plan_view {
+    int32_t n_queries, n_groups, n_levels, n_slots, n_anchor;
+    int32_t n_proj, n_inter, n_neg, n_int_rows, n_roots, n_refs, n_r_uniq;
+    const int32_t* lvl_off;      /* [n_levels+2] groups of level l: lvl_off[l]..lvl_off[l+1]-1 */
+    const int32_t* g_level;      /* [n_groups] ... */
+    const int32_t* g_type;
+    const int32_t* g_nin;
+    const int32_t* g_n;
+    const int32_t* g_out_base;
+    const int32_t* g_mlp_base;
+    const int32_t* g_ref_off;
+    const int32_t* g_rel_off;    /* offset into rel, -1 if not a projection group */
+    const int32_t* in_ref;       /* [n_refs] */
+    const int32_t* in_gslot;     /* [n_refs] */
+    const int32_t* rel;          /* [n_proj] */
+    const int32_t* root_off;     /* [n_queries+1] */
+    const int32_t* root_slot;    /* [n_roots] */
+    const int32_t* anchor_ent;   /* [n_anchor] */
+    const int32_t* pos;          /* [n_queries] */
+    const int32_t* r_uniq;       /* [n_r_uniq] */
+    const int32_t* r_seg_off;    /* [n_r_uniq+1] */
+    const int32_t* r_src;        /* [n_proj] */
+} ngdb_plan_view;
+
+/* Device-side results of the last ngdb_forward_backward / ngdb_train_step on a
+ * context (pointers into the private workspace, valid until the next call on
+ * the context).  Gradients of table rows are compact: row i of gE belongs to
+ * entity e_uniq[i].  The entity index is the stable grouping by entity id of
+ * the contributions [anchors | positives | negatives row-major] (Sec. 4.2
+ * "Efficient Tensor Indexing").                                                  */
+typedef struct ngdb_grad_view {
+    int32_t n_e_uniq, n_e_contrib, n_r_uniq, n_slots, n_pairs;
+    const int32_t* e_uniq;      /* [n_e_uniq]                                    */
+    const int32_t* e_seg_off;   /* [n_e_uniq+1]                                  */
+    const int32_t* e_src;       /* [n_e_contrib] contribution numbers            */
+    const float* gE;            /* [n_e_uniq, d]   (forward_backward only)       */
+    const float* gR;            /* [n_r_uniq, d]   (forward_backward only)       */
+    const float* g_mlp[12];     /* W1 b1 W2 b2 V1 c1 V2 c2 U1 u1 U2 u2           */
+    const float* g_Wp;          /* [d, d_sem] or NULL                            */
+    const float* act;           /* [n_slots, d] operator outputs by slot         */
+    const float* pair_score;    /* [n_pairs] s(q_i, cand), pair = i*(K+1)+c, c=0 positive */
+    const float* loss_terms;    /* [n_queries] per-query loss before the 1/(2B)  */
+} ngdb_grad_view;
+
+/* Create a context (allocates streams and a small workspace).  cfg: host. */
+int ngdb_create(const ngdb_config* cfg, ngdb_ctx_t** out);
+void ngdb_destroy(ngdb_ctx_t* ctx);
+
+/* Record the caller's parameter / moment tensors (device) and the step count.
+ * The struct is copied; the tensors stay the caller's and are updated in place
+ * by ngdb_train_step.  Wp and H_sem are required iff d_sem > 0.                  */
+int ngdb_bind_params(ngdb_ctx_t* ctx, const ngdb_params* params);
+
+/* Queries -> operator-level frontiers and index arrays (Alg. 1 lines 1-4 and
+ * the pools of Sec. 4.1, resolved ahead of time level by level).  Host work
+ * plus one upload; deterministic.  Ids are range-checked here (NGDB_ERR_RANGE).
+ * The plan may be used for any number of steps on this context.                  */
+int ngdb_plan(ngdb_ctx_t* ctx, const ngdb_query_batch* batch, ngdb_plan_t** out);
+/* The host half of ngdb_plan alone (no context, no device, nothing uploaded):
+ * the result can be exported and freed, not executed.                            */
+int ngdb_plan_host(int32_t n_entities, int32_t n_relations, const ngdb_query_batch* batch,
+                   ngdb_plan_t** out);
+int ngdb_plan_export(const ngdb_plan_t* plan, ngdb_plan_view* out);
+void ngdb_plan_free(ngdb_plan_t* plan);
+
+/* One training step (Alg. 1 lines 5-21): forward over the plan's frontiers,
+ * L1 scores of every query against its positive and its K negatives, loss,
+ * backward, segmented scatter-add of the table gradients, Adam on every bound
+ * tensor, step count + 1.  d_neg: device [n_queries, K] entity ids (range is
+ * the caller's responsibility: ids index E directly).  d_loss: device, 1 float,
+ * written on the stream.  No host synchronisation except when the workspace
+ * has to grow (first call with a larger batch).                                  */
+int ngdb_train_step(ngdb_ctx_t* ctx, const ngdb_plan_t* plan, const int32_t* d_neg,
+                    int32_t K, void* stream, float* d_loss);
+
+/* The same without the optimiser: gradients are left in the workspace for
+ * ngdb_get_grads().  Used by parity tests.                                       */
+int ngdb_forward_backward(ngdb_ctx_t* ctx, const ngdb_plan_t* plan, const int32_t* d_neg,
+                          int32_t K, void* stream, float* d_loss);
+int ngdb_get_grads(ngdb_ctx_t* ctx, ngdb_grad_view* out);
+
+/* Forward only (Sec. 3.2: rank entities by f(q,e)).
+ *  candidate mode (d_cand != NULL): d_cand device [n_queries, C] entity ids;
+ *    d_scores device [n_queries, C] receives s(q_i, cand).
+ *  all-entity mode (d_cand == NULL): for every query the topk entities of
+ *    smallest L1 distance, ascending, ties to the lower id, into
+ *    d_topk_ids [n_queries, topk] and d_topk_dist [n_queries, topk].             */
+int ngdb_score(ngdb_ctx_t* ctx, const ngdb_plan_t* plan, const int32_t* d_cand, int32_t C,
+               int32_t topk, float* d_scores, int32_t* d_topk_ids, float* d_topk_dist,
+               void* stream);
+
+/* Synchronous device-to-host copy of `bytes` bytes (waits for the device). */
+int ngdb_copy_to_host(void* h_dst, const void* d_src, size_t bytes);
+
+int64_t ngdb_step_count(const ngdb_ctx_t* ctx);
+const char* ngdb_strerror(int code);
+const char* ngdb_last_error(const ngdb_ctx_t* ctx);   /* text of the last failure on ctx */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NGDB_H */

@@ -1,0 +1,289 @@
+"""ctypes binding of libngdb.so: argument marshalling only.
+
+Every step of the training path runs inside the library's HIP kernels; this
+module converts numpy / torch objects to the plain pointers of include/ngdb.h
+and back.  PyTorch is used for device memory and streams.  If the library is
+missing the import fails loudly -- there is no fallback path.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libngdb.so")
+
+MLP_NAMES = ("W1", "b1", "W2", "b2", "V1", "c1", "V2", "c2", "U1", "u1", "U2", "u2")
+TENSOR_NAMES = ("E", "R") + MLP_NAMES
+
+NGDB_OK = 0
+ERR_ARG, ERR_UNSUPPORTED, ERR_RANGE, ERR_OOM, ERR_HIP, ERR_STATE = -1, -2, -3, -4, -5, -6
+
+
+class NgdbError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__("libngdb error %d: %s" % (code, text))
+        self.code = code
+
+
+class Config(C.Structure):
+    _fields_ = [("n_entities", C.c_int32), ("n_relations", C.c_int32), ("d", C.c_int32), ("h", C.c_int32),
+                ("d_sem", C.c_int32), ("num_streams", C.c_int32), ("gamma", C.c_float), ("lr", C.c_float),
+                ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float)]
+
+
+class Tensor(C.Structure):
+    _fields_ = [("p", C.c_void_p), ("m", C.c_void_p), ("v", C.c_void_p)]
+
+
+class Params(C.Structure):
+    _fields_ = [(n, Tensor) for n in TENSOR_NAMES] + [("Wp", Tensor), ("H_sem", C.c_void_p), ("step", C.c_int64)]
+
+
+class QueryBatchC(C.Structure):
+    _fields_ = [("n_queries", C.c_int32), ("node_off", C.c_void_p), ("op", C.c_void_p), ("arg", C.c_void_p),
+                ("in_off", C.c_void_p), ("in_idx", C.c_void_p), ("pos", C.c_void_p)]
+
+
+_PLAN_COUNTS = ("n_queries", "n_groups", "n_levels", "n_slots", "n_anchor", "n_proj", "n_inter", "n_neg",
+                "n_int_rows", "n_roots", "n_refs", "n_r_uniq")
+_PLAN_ARRAYS = ("lvl_off", "g_level", "g_type", "g_nin", "g_n", "g_out_base", "g_mlp_base", "g_ref_off",
+                "g_rel_off", "in_ref", "in_gslot", "rel", "root_off", "root_slot", "anchor_ent", "pos",
+                "r_uniq", "r_seg_off", "r_src")
+
+
+class PlanView(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in _PLAN_COUNTS] + [(n, C.POINTER(C.c_int32)) for n in _PLAN_ARRAYS]
+
+
+class GradView(C.Structure):
+    _fields_ = [("n_e_uniq", C.c_int32), ("n_e_contrib", C.c_int32), ("n_r_uniq", C.c_int32),
+                ("n_slots", C.c_int32), ("n_pairs", C.c_int32),
+                ("e_uniq", C.c_void_p), ("e_seg_off", C.c_void_p), ("e_src", C.c_void_p),
+                ("gE", C.c_void_p), ("gR", C.c_void_p), ("g_mlp", C.c_void_p * 12), ("g_Wp", C.c_void_p),
+                ("act", C.c_void_p), ("pair_score", C.c_void_p), ("loss_terms", C.c_void_p)]
+
+
+def load_library(path=LIB_PATH):
+    if not os.path.exists(path):
+        raise ImportError("libngdb.so has not been built (run `python -m paper_2602_21597_amd.build`): " + path)
+    lib = C.CDLL(path)
+    vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    sig = {
+        "ngdb_create": (C.c_int, [C.POINTER(Config), C.POINTER(vp)]),
+        "ngdb_destroy": (None, [vp]),
+        "ngdb_bind_params": (C.c_int, [vp, C.POINTER(Params)]),
+        "ngdb_plan": (C.c_int, [vp, C.POINTER(QueryBatchC), C.POINTER(vp)]),
+        "ngdb_plan_host": (C.c_int, [i32, i32, C.POINTER(QueryBatchC), C.POINTER(vp)]),
+        "ngdb_plan_export": (C.c_int, [vp, C.POINTER(PlanView)]),
+        "ngdb_plan_free": (None, [vp]),
+        "ngdb_train_step": (C.c_int, [vp, vp, vp, i32, vp, vp]),
+        "ngdb_forward_backward": (C.c_int, [vp, vp, vp, i32, vp, vp]),
+        "ngdb_get_grads": (C.c_int, [vp, C.POINTER(GradView)]),
+        "ngdb_score": (C.c_int, [vp, vp, vp, i32, i32, vp, vp, vp, vp]),
+        "ngdb_copy_to_host": (C.c_int, [vp, vp, C.c_size_t]),
+        "ngdb_step_count": (i64, [vp]),
+        "ngdb_strerror": (C.c_char_p, [C.c_int]),
+        "ngdb_last_error": (C.c_char_p, [vp]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    return lib
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = load_library()
+    return _lib
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, np.int32)
+
+
+class _BatchArrays:
+    """Keeps the numpy arrays alive while the C struct points at them."""
+
+    def __init__(self, qb):
+        self.keep = [_i32(qb.node_off), np.ascontiguousarray(qb.op, np.uint8), _i32(qb.arg), _i32(qb.in_off),
+                     _i32(qb.in_idx), _i32(qb.pos)]
+        p = [a.ctypes.data if a.size else None for a in self.keep]
+        self.c = QueryBatchC(int(qb.B), p[0], p[1], p[2], p[3], p[4], p[5])
+
+
+class Plan:
+    def __init__(self, handle):
+        self.handle = handle
+
+    def export(self):
+        """All plan arrays as a dict of numpy int32 copies / ints."""
+        v = PlanView()
+        _check(lib().ngdb_plan_export(self.handle, C.byref(v)), None)
+        out = {n: int(getattr(v, n)) for n in _PLAN_COUNTS}
+        sizes = dict(lvl_off=out["n_levels"] + 2, in_ref=out["n_refs"], in_gslot=out["n_refs"],
+                     rel=out["n_proj"], root_off=out["n_queries"] + 1, root_slot=out["n_roots"],
+                     anchor_ent=out["n_anchor"], pos=out["n_queries"], r_uniq=out["n_r_uniq"],
+                     r_seg_off=out["n_r_uniq"] + 1, r_src=out["n_proj"])
+        for n in _PLAN_ARRAYS:
+            cnt = sizes.get(n, out["n_groups"])
+            p = getattr(v, n)
+            out[n] = np.ctypeslib.as_array(p, shape=(cnt,)).copy() if cnt else np.zeros(0, np.int32)
+        return out
+
+    def free(self):
+        if self.handle:
+            lib().ngdb_plan_free(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def _check(rc, ctx):
+    if rc != NGDB_OK:
+        L = lib()
+        text = L.ngdb_strerror(rc).decode()
+        if ctx:
+            detail = L.ngdb_last_error(ctx).decode()
+            if detail:
+                text += " (" + detail + ")"
+        raise NgdbError(rc, text)
+
+
+def plan_host(n_entities, n_relations, qb):
+    """Host-only planning (no device needed); the plan can be exported, not executed."""
+    arrs = _BatchArrays(qb)
+    h = C.c_void_p()
+    _check(lib().ngdb_plan_host(int(n_entities), int(n_relations), C.byref(arrs.c), C.byref(h)), None)
+    return Plan(h)
+
+
+def copy_to_host(dev_ptr, shape, dtype):
+    out = np.empty(shape, dtype)
+    if out.size:
+        _check(lib().ngdb_copy_to_host(out.ctypes.data, dev_ptr, out.nbytes), None)
+    return out
+
+
+class Engine:
+    """One libngdb context plus the device tensors bound to it."""
+
+    def __init__(self, n_entities, n_relations, d, h, gamma, lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8,
+                 d_sem=0, num_streams=1, device="cuda:0"):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("libngdb needs a GPU; there is no CPU path")
+        self.torch = torch
+        self.device = torch.device(device)
+        torch.cuda.set_device(self.device)
+        self.cfg = Config(n_entities, n_relations, d, h, d_sem, num_streams, gamma, lr, beta1, beta2, eps)
+        self.ctx = C.c_void_p()
+        _check(lib().ngdb_create(C.byref(self.cfg), C.byref(self.ctx)), None)
+        self.tensors = {}
+        self._loss = torch.zeros(1, dtype=torch.float32, device=self.device)
+
+    # ---- parameters
+    def bind_numpy(self, params, step=0):
+        """Uploads fp32 numpy parameters, creates zero moments, binds them."""
+        t = self.torch
+        self.tensors = {}
+        for name in TENSOR_NAMES:
+            p = t.from_numpy(np.ascontiguousarray(params[name], np.float32)).to(self.device)
+            self.tensors[name] = (p, t.zeros_like(p), t.zeros_like(p))
+        self.bind(step)
+
+    def bind(self, step=0):
+        P = Params()
+        for name in TENSOR_NAMES:
+            p, m, v = self.tensors[name]
+            setattr(P, name, Tensor(p.data_ptr(), m.data_ptr(), v.data_ptr()))
+        P.step = int(step)
+        _check(lib().ngdb_bind_params(self.ctx, C.byref(P)), self.ctx)
+
+    def params_numpy(self, which="p"):
+        k = "pmv".index(which)
+        self.torch.cuda.synchronize()
+        return {n: ts[k].cpu().numpy() for n, ts in self.tensors.items()}
+
+    # ---- planning / steps
+    def plan(self, qb):
+        arrs = _BatchArrays(qb)
+        h = C.c_void_p()
+        _check(lib().ngdb_plan(self.ctx, C.byref(arrs.c), C.byref(h)), self.ctx)
+        return Plan(h)
+
+    def _stream(self, stream):
+        return C.c_void_p(stream.cuda_stream if stream is not None else
+                          self.torch.cuda.current_stream(self.device).cuda_stream)
+
+    def _neg(self, neg):
+        assert neg.dtype == self.torch.int32 and neg.is_cuda and neg.is_contiguous() and neg.dim() == 2
+        return neg.data_ptr(), int(neg.shape[1])
+
+    def train_step(self, plan, neg, stream=None, loss_out=None):
+        """neg: [B, K] int32 device tensor.  Returns the device tensor that receives the loss."""
+        loss = self._loss if loss_out is None else loss_out
+        ptr, K = self._neg(neg)
+        _check(lib().ngdb_train_step(self.ctx, plan.handle, ptr, K, self._stream(stream), loss.data_ptr()), self.ctx)
+        return loss
+
+    def forward_backward(self, plan, neg, stream=None):
+        ptr, K = self._neg(neg)
+        self._K = K
+        _check(lib().ngdb_forward_backward(self.ctx, plan.handle, ptr, K, self._stream(stream),
+                                           self._loss.data_ptr()), self.ctx)
+        return self._loss
+
+    def grads(self):
+        """Results of the last forward_backward as numpy copies."""
+        gv = GradView()
+        _check(lib().ngdb_get_grads(self.ctx, C.byref(gv)), self.ctx)
+        d, h = self.cfg.d, self.cfg.h
+        U, UR = gv.n_e_uniq, gv.n_r_uniq
+        out = dict(
+            e_uniq=copy_to_host(gv.e_uniq, (U,), np.int32),
+            e_seg_off=copy_to_host(gv.e_seg_off, (U + 1,), np.int32),
+            e_src=copy_to_host(gv.e_src, (gv.n_e_contrib,), np.int32),
+            act=copy_to_host(gv.act, (gv.n_slots, d), np.float32),
+            pair_score=copy_to_host(gv.pair_score, (gv.n_pairs,), np.float32),
+            loss_terms=copy_to_host(gv.loss_terms, (gv.n_pairs // (self._K + 1),), np.float32),
+        )
+        if gv.gE:
+            out["gE"] = copy_to_host(gv.gE, (U, d), np.float32)
+            out["gR"] = copy_to_host(gv.gR, (UR, d), np.float32)
+        shapes = [(h, d), (h,), (d, h), (d,)] * 3
+        for i, name in enumerate(MLP_NAMES):
+            out[name] = copy_to_host(gv.g_mlp[i], shapes[i], np.float32)
+        return out
+
+    def score(self, plan, cand, stream=None):
+        """cand: [B, C] int32 device tensor -> [B, C] float32 device tensor of scores."""
+        t = self.torch
+        assert cand.dtype == t.int32 and cand.is_cuda and cand.is_contiguous() and cand.dim() == 2
+        out = t.empty(cand.shape, dtype=t.float32, device=self.device)
+        _check(lib().ngdb_score(self.ctx, plan.handle, cand.data_ptr(), int(cand.shape[1]), 0, out.data_ptr(),
+                                None, None, self._stream(stream)), self.ctx)
+        return out
+
+    def step_count(self):
+        return int(lib().ngdb_step_count(self.ctx))
+
+    def close(self):
+        if self.ctx:
+            lib().ngdb_destroy(self.ctx)
+            self.ctx = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

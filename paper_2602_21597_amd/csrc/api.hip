@@ -1,0 +1,653 @@
+// C boundary and step orchestration: enqueues, per depth of the batch's operator
+// DAG, one grouped launch sequence per operator type (Sec. 4.1 "Batched
+// Execution"; Sec. 4.3 cardinality classes), then scoring, the reversed
+// frontiers (Alg. 1: gradient nodes are scheduled like forward ones), the
+// segmented table updates and Adam (Alg. 1, OptimizerStep).
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "common.h"
+#include "planner.h"
+
+using namespace ngdb;
+
+namespace {
+
+struct DevBuf {
+    void* p = nullptr;
+    size_t cap = 0;
+};
+
+struct Segment {   // the groups of one (level, type): contiguous MLP rows and references
+    int type = 0;
+    int rows = 0;          // MLP rows (members for PROJ/NEG, members*inputs for INTER)
+    int mlp_base = 0;
+    int ref_off = 0;
+    int rel_off = -1;
+    int out_base = 0;      // PROJ/NEG: first output slot
+    int g_lo = 0, g_hi = 0;  // group range (INTER: one combine launch per group)
+};
+
+constexpr int T_PROJ = 0, T_INTER = 1, T_NEG = 2;
+inline int type_index(int op) { return op == NGDB_OP_PROJ ? T_PROJ : (op == NGDB_OP_INTER ? T_INTER : T_NEG); }
+
+}  // namespace
+
+struct ngdb_plan_s {
+    HostPlan hp;
+    int32_t* d_blob = nullptr;
+    // device views into the blob
+    const int32_t *d_in_ref = nullptr, *d_in_gslot = nullptr, *d_rel = nullptr, *d_root_off = nullptr,
+                  *d_root_slot = nullptr, *d_pos = nullptr, *d_ekeys_head = nullptr, *d_r_uniq = nullptr,
+                  *d_r_seg_off = nullptr, *d_r_src = nullptr, *d_n_r_uniq = nullptr;
+    std::vector<std::vector<Segment>> levels;   // levels[l] for l = 1..n_levels (index 0 unused)
+    int32_t n_entities = 0;
+};
+
+struct ngdb_ctx_s {
+    ngdb_config cfg{};
+    ngdb_params prm{};
+    bool bound = false;
+    int64_t step = 0;
+    std::string err;
+    hipStream_t side[4]{};
+    hipEvent_t ev_fork = nullptr;
+    hipEvent_t ev_join[4]{};
+    int n_side = 0;
+    // workspace
+    DevBuf act, dact, Z[3], H[3], dH[3], Att, dAtt, Dx;
+    DevBuf score, coef, win, loss_terms;
+    DevBuf keys_a, keys_b, vals_a, vals_b, hist, scan_tmp, uniq, seg_off, n_uniq;
+    DevBuf gW;          // gradients of the 12 MLP tensors, packed
+    DevBuf gE, gR;      // compact table gradients (ngdb_forward_backward only)
+    size_t gw_off[13]{};
+    // results of the last step
+    bool have_grads = false;
+    ngdb_grad_view gv{};
+};
+
+namespace {
+
+thread_local std::string g_create_err;
+
+int fail(ngdb_ctx_t* c, int code, const std::string& msg) {
+    if (c) c->err = msg;
+    return code;
+}
+
+#define HIPCHK(c, expr)                                                                        \
+    do {                                                                                       \
+        hipError_t e_ = (expr);                                                                \
+        if (e_ != hipSuccess)                                                                  \
+            return fail((c), e_ == hipErrorOutOfMemory ? NGDB_ERR_OOM : NGDB_ERR_HIP,          \
+                        std::string(#expr) + ": " + hipGetErrorString(e_));                    \
+    } while (0)
+
+int ensure(ngdb_ctx_t* c, DevBuf& b, size_t bytes) {
+    if (bytes <= b.cap) return NGDB_OK;
+    // growing: nothing may still be using the old allocation
+    HIPCHK(c, hipDeviceSynchronize());
+    if (b.p) HIPCHK(c, hipFree(b.p));
+    b.p = nullptr;
+    b.cap = 0;
+    const size_t want = bytes + bytes / 4 + 256;
+    HIPCHK(c, hipMalloc(&b.p, want));
+    b.cap = want;
+    return NGDB_OK;
+}
+
+void release(DevBuf& b) {
+    if (b.p) (void)hipFree(b.p);
+    b.p = nullptr;
+    b.cap = 0;
+}
+
+template <class T>
+T* ptr(const DevBuf& b) { return static_cast<T*>(b.p); }
+
+struct MlpRefs {
+    const float *Wa, *ba, *Wb, *bb;
+};
+MlpRefs mlp_of(const ngdb_params& p, int t) {
+    if (t == T_PROJ) return {p.W1.p, p.b1.p, p.W2.p, p.b2.p};
+    if (t == T_NEG) return {p.V1.p, p.c1.p, p.V2.p, p.c2.p};
+    return {p.U1.p, p.u1.p, p.U2.p, p.u2.p};
+}
+// order of ngdb_grad_view::g_mlp: W1 b1 W2 b2 | V1 c1 V2 c2 | U1 u1 U2 u2
+int gslot_of(int t) { return t == T_PROJ ? 0 : (t == T_NEG ? 4 : 8); }
+
+// Streams of one step: `main` is the caller's; with num_streams > 1 the type
+// segments of a level run on library streams between a fork and a join.
+struct Lanes {
+    ngdb_ctx_t* c;
+    hipStream_t main;
+    int forked = 0;
+    hipStream_t pick(int i) const { return c->n_side > 1 ? c->side[i % c->n_side] : main; }
+    hipError_t fork(int n) {
+        forked = 0;
+        if (c->n_side <= 1 || n <= 1) return hipSuccess;
+        hipError_t e = hipEventRecord(c->ev_fork, main);
+        if (e != hipSuccess) return e;
+        forked = std::min(n, c->n_side);
+        for (int i = 0; i < forked; ++i) {
+            e = hipStreamWaitEvent(c->side[i], c->ev_fork, 0);
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
+    }
+    hipStream_t lane(int i) const { return forked ? c->side[i % forked] : main; }
+    hipError_t join() {
+        for (int i = 0; i < forked; ++i) {
+            hipError_t e = hipEventRecord(c->ev_join[i], c->side[i]);
+            if (e != hipSuccess) return e;
+            e = hipStreamWaitEvent(main, c->ev_join[i], 0);
+            if (e != hipSuccess) return e;
+        }
+        forked = 0;
+        return hipSuccess;
+    }
+};
+
+int size_workspace(ngdb_ctx_t* c, const ngdb_plan_t* pl, int K, bool want_table_grads) {
+    const HostPlan& hp = pl->hp;
+    const size_t d = c->cfg.d, h = c->cfg.h, f = sizeof(float);
+    const size_t rows[3] = {(size_t)hp.n_proj, (size_t)hp.n_int_rows, (size_t)hp.n_neg};
+    int rc;
+#define ENS(buf, bytes) if ((rc = ensure(c, buf, std::max<size_t>((bytes), 256))) != NGDB_OK) return rc
+    ENS(c->act, (size_t)hp.n_slots * d * f);
+    ENS(c->dact, ((size_t)hp.n_slots + hp.n_anchor) * d * f);
+    for (int t = 0; t < 3; ++t) {
+        ENS(c->Z[t], rows[t] * d * f);
+        ENS(c->H[t], rows[t] * h * f);
+        ENS(c->dH[t], rows[t] * h * f);
+    }
+    ENS(c->Att, rows[T_INTER] * d * f);
+    ENS(c->dAtt, rows[T_INTER] * d * f);
+    ENS(c->Dx, rows[T_INTER] * d * f);
+    const size_t pairs = (size_t)hp.n_queries * ((size_t)K + 1);
+    ENS(c->score, pairs * f);
+    ENS(c->coef, pairs * f);
+    ENS(c->win, pairs * sizeof(int32_t));
+    ENS(c->loss_terms, (size_t)hp.n_queries * f);
+    const int64_t nk = (int64_t)hp.n_anchor + hp.n_queries + (int64_t)hp.n_queries * K;
+    ENS(c->keys_a, (size_t)nk * 4);
+    ENS(c->keys_b, (size_t)nk * 4);
+    ENS(c->vals_a, (size_t)nk * 4);
+    ENS(c->vals_b, (size_t)nk * 4);
+    ENS(c->uniq, (size_t)nk * 4);
+    ENS(c->seg_off, ((size_t)nk + 1) * 4);
+    ENS(c->hist, index_hist_elems(nk) * 4);
+    ENS(c->scan_tmp, index_scan_tmp_elems(nk) * 4);
+    ENS(c->n_uniq, 256);
+    if (!c->gW.p) {
+        size_t off = 0;
+        for (int t = 0; t < 3; ++t) {
+            const size_t sz[4] = {h * d, h, d * h, d};
+            for (int k = 0; k < 4; ++k) {
+                c->gw_off[t * 4 + k] = off;
+                off += (sz[k] + 3) & ~size_t(3);
+            }
+        }
+        c->gw_off[12] = off;
+        ENS(c->gW, off * f);
+    }
+    if (want_table_grads) {
+        const size_t urows = (size_t)std::min<int64_t>(nk, c->cfg.n_entities);
+        ENS(c->gE, urows * d * f);
+        ENS(c->gR, (size_t)std::max<size_t>(hp.r_uniq.size(), 1) * d * f);
+    }
+#undef ENS
+    return NGDB_OK;
+}
+
+// forward over the plan's frontiers; results in c->act
+int enqueue_forward(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t stream) {
+    const int d = c->cfg.d, h = c->cfg.h;
+    Lanes L{c, stream};
+    for (int l = 1; l <= pl->hp.n_levels; ++l) {
+        const std::vector<Segment>& segs = pl->levels[l];
+        HIPCHK(c, L.fork((int)segs.size()));
+        for (size_t si = 0; si < segs.size(); ++si) {
+            const Segment& sg = segs[si];
+            hipStream_t s = L.lane((int)si);
+            const MlpRefs W = mlp_of(c->prm, sg.type);
+            float* Z = ptr<float>(c->Z[sg.type]) + (size_t)sg.mlp_base * d;
+            float* Hh = ptr<float>(c->H[sg.type]) + (size_t)sg.mlp_base * h;
+            HIPCHK(c, launch_gather(Z, pl->d_in_ref + sg.ref_off, sg.rel_off >= 0 ? pl->d_rel + sg.rel_off : nullptr,
+                                    sg.rows, d, ptr<float>(c->act), c->prm.E.p, c->prm.R.p, s));
+            GemmArgs g1;
+            g1.A = Z; g1.lda = d; g1.B = W.Wa; g1.ldb = d; g1.C = Hh; g1.ldc = h;
+            g1.M = sg.rows; g1.N = h; g1.K = d; g1.bias = W.ba; g1.relu = true;
+            HIPCHK(c, launch_gemm(g1, s));
+            GemmArgs g2;
+            g2.A = Hh; g2.lda = h; g2.B = W.Wb; g2.ldb = h; g2.M = sg.rows; g2.N = d; g2.K = h; g2.bias = W.bb;
+            g2.ldc = d;
+            if (sg.type == T_INTER) {
+                g2.C = ptr<float>(c->Att) + (size_t)sg.mlp_base * d;
+                HIPCHK(c, launch_gemm(g2, s));
+                for (int g = sg.g_lo; g < sg.g_hi; ++g) {
+                    const size_t mb = (size_t)pl->hp.g_mlp_base[g] * d;
+                    HIPCHK(c, launch_inter_fwd(ptr<float>(c->Z[T_INTER]) + mb, ptr<float>(c->Att) + mb,
+                                               ptr<float>(c->act) + (size_t)pl->hp.g_out_base[g] * d,
+                                               pl->hp.g_n[g], pl->hp.g_nin[g], d, s));
+                }
+            } else {
+                g2.C = ptr<float>(c->act) + (size_t)sg.out_base * d;
+                HIPCHK(c, launch_gemm(g2, s));
+            }
+        }
+        HIPCHK(c, L.join());
+    }
+    return NGDB_OK;
+}
+
+int enqueue_backward(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t stream) {
+    const int d = c->cfg.d, h = c->cfg.h;
+    const HostPlan& hp = pl->hp;
+    Lanes L{c, stream};
+    float* dact = ptr<float>(c->dact);
+    for (int l = hp.n_levels; l >= 1; --l) {
+        const std::vector<Segment>& segs = pl->levels[l];
+        HIPCHK(c, L.fork((int)segs.size()));
+        for (size_t si = 0; si < segs.size(); ++si) {
+            const Segment& sg = segs[si];
+            hipStream_t s = L.lane((int)si);
+            const MlpRefs W = mlp_of(c->prm, sg.type);
+            const float* dOut;
+            const float* addend = nullptr;
+            if (sg.type == T_INTER) {
+                for (int g = sg.g_lo; g < sg.g_hi; ++g) {
+                    const size_t mb = (size_t)hp.g_mlp_base[g] * d;
+                    HIPCHK(c, launch_inter_bwd(ptr<float>(c->Z[T_INTER]) + mb, ptr<float>(c->Att) + mb,
+                                               dact + (size_t)hp.g_out_base[g] * d, ptr<float>(c->dAtt) + mb,
+                                               ptr<float>(c->Dx) + mb, hp.g_n[g], hp.g_nin[g], d, s));
+                }
+                dOut = ptr<float>(c->dAtt) + (size_t)sg.mlp_base * d;
+                addend = ptr<float>(c->Dx) + (size_t)sg.mlp_base * d;
+            } else {
+                dOut = dact + (size_t)sg.out_base * d;
+            }
+            const float* Hh = ptr<float>(c->H[sg.type]) + (size_t)sg.mlp_base * h;
+            float* dHh = ptr<float>(c->dH[sg.type]) + (size_t)sg.mlp_base * h;
+            GemmArgs b2;   // dH = (dOut * Wb) masked by relu
+            b2.A = dOut; b2.lda = d; b2.B = W.Wb; b2.ldb = h; b2.b_kcontig = false;
+            b2.C = dHh; b2.ldc = h; b2.M = sg.rows; b2.N = h; b2.K = d; b2.mask = Hh; b2.ldmask = h;
+            HIPCHK(c, launch_gemm(b2, s));
+            GemmArgs b1;   // dZ = dH * Wa, scattered to the gradient rows of the inputs
+            b1.A = dHh; b1.lda = h; b1.B = W.Wa; b1.ldb = d; b1.b_kcontig = false;
+            b1.C = dact; b1.ldc = d; b1.M = sg.rows; b1.N = d; b1.K = h;
+            b1.addend = addend; b1.ldadd = d; b1.dst_row = pl->d_in_gslot + sg.ref_off;
+            HIPCHK(c, launch_gemm(b1, s));
+        }
+        HIPCHK(c, L.join());
+    }
+    // weight gradients: one contraction per tensor over all rows of the type
+    const size_t rows[3] = {(size_t)hp.n_proj, (size_t)hp.n_int_rows, (size_t)hp.n_neg};
+    const float* dY[3] = {dact, ptr<float>(c->dAtt), dact + ((size_t)hp.n_proj + hp.n_inter) * d};
+    float* gW = ptr<float>(c->gW);
+    HIPCHK(c, L.fork(3));
+    for (int t = 0; t < 3; ++t) {
+        hipStream_t s = L.lane(t);
+        const int gs = gslot_of(t);
+        const int r = (int)rows[t];
+        GemmArgs wa;   // dWa[h,d] = dH^T Z
+        wa.A = ptr<float>(c->dH[t]); wa.lda = h; wa.a_kcontig = false;
+        wa.B = ptr<float>(c->Z[t]); wa.ldb = d; wa.b_kcontig = false;
+        wa.C = gW + c->gw_off[gs + 0]; wa.ldc = d; wa.M = h; wa.N = d; wa.K = r;
+        HIPCHK(c, launch_gemm(wa, s));
+        HIPCHK(c, launch_colsum(ptr<float>(c->dH[t]), r, h, h, gW + c->gw_off[gs + 1], s));
+        GemmArgs wb;   // dWb[d,h] = dY^T H
+        wb.A = dY[t]; wb.lda = d; wb.a_kcontig = false;
+        wb.B = ptr<float>(c->H[t]); wb.ldb = h; wb.b_kcontig = false;
+        wb.C = gW + c->gw_off[gs + 2]; wb.ldc = h; wb.M = d; wb.N = h; wb.K = r;
+        HIPCHK(c, launch_gemm(wb, s));
+        HIPCHK(c, launch_colsum(dY[t], r, d, d, gW + c->gw_off[gs + 3], s));
+    }
+    HIPCHK(c, L.join());
+    return NGDB_OK;
+}
+
+int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, hipStream_t stream, float* d_loss,
+             bool apply) {
+    if (!c || !pl) return NGDB_ERR_ARG;
+    if (!c->bound) return fail(c, NGDB_ERR_STATE, "parameters not bound");
+    if (K < 0 || (K > 0 && pl->hp.n_queries > 0 && !d_neg) || !d_loss)
+        return fail(c, NGDB_ERR_ARG, "bad negatives / loss pointer");
+    if (pl->n_entities != c->cfg.n_entities || !pl->d_blob)
+        return fail(c, NGDB_ERR_ARG, "plan belongs to another configuration or was built without a device");
+    const HostPlan& hp = pl->hp;
+    const int d = c->cfg.d, B = hp.n_queries;
+    c->have_grads = false;
+    int rc = size_workspace(c, pl, K, !apply);
+    if (rc != NGDB_OK) return rc;
+
+    // 1. entity gradient index (depends only on the plan and the negatives)
+    IndexBuffers ib{ptr<int32_t>(c->keys_a), ptr<int32_t>(c->keys_b), ptr<int32_t>(c->vals_a),
+                    ptr<int32_t>(c->vals_b), ptr<int32_t>(c->hist),   ptr<int32_t>(c->scan_tmp),
+                    ptr<int32_t>(c->uniq),   ptr<int32_t>(c->seg_off), ptr<int32_t>(c->n_uniq)};
+    int32_t* e_src = nullptr;
+    HIPCHK(c, build_segment_index(pl->d_ekeys_head, hp.n_anchor + B, d_neg, (int64_t)B * K, c->cfg.n_entities, ib,
+                                  &e_src, stream));
+
+    // 2. forward frontiers
+    rc = enqueue_forward(c, pl, stream);
+    if (rc != NGDB_OK) return rc;
+
+    // 3. scores, loss terms, dL/ds, gradients of the branch embeddings
+    ScoreArgs sa{};
+    sa.act = ptr<float>(c->act); sa.E = c->prm.E.p; sa.root_off = pl->d_root_off; sa.root_slot = pl->d_root_slot;
+    sa.pos = pl->d_pos; sa.cand = d_neg; sa.B = B; sa.C = K; sa.d = d; sa.max_branch = std::max(1, hp.max_branch);
+    sa.gamma = c->cfg.gamma; sa.score = ptr<float>(c->score); sa.coef = ptr<float>(c->coef);
+    sa.win = ptr<int32_t>(c->win); sa.dact = ptr<float>(c->dact); sa.loss_terms = ptr<float>(c->loss_terms);
+    {
+        hipError_t e = launch_score(sa, true, stream);
+        if (e == hipErrorInvalidValue) return fail(c, NGDB_ERR_UNSUPPORTED, "embedding width / union branch count too large for the scoring kernel");
+        HIPCHK(c, e);
+    }
+    HIPCHK(c, launch_loss_reduce(ptr<float>(c->loss_terms), B, B > 0 ? 1.f / (2.f * B) : 0.f, d_loss, stream));
+
+    // 4. reversed frontiers + weight gradients
+    rc = enqueue_backward(c, pl, stream);
+    if (rc != NGDB_OK) return rc;
+
+    // 5. table gradients (+ Adam), dense Adam
+    const int64_t t = c->step + 1;
+    AdamHyper ah{c->cfg.lr, c->cfg.beta1, c->cfg.beta2, c->cfg.eps,
+                 (float)(1.0 - std::pow((double)c->cfg.beta1, (double)t)),
+                 (float)(1.0 - std::pow((double)c->cfg.beta2, (double)t))};
+    TableArgs te{};
+    te.P = c->prm.E.p; te.Mo = c->prm.E.m; te.Vo = c->prm.E.v;
+    te.uniq = ptr<int32_t>(c->uniq); te.seg_off = ptr<int32_t>(c->seg_off); te.src = e_src;
+    te.n_uniq_dev = ptr<int32_t>(c->n_uniq); te.d = d; te.n_rowsrc = hp.n_anchor; te.row_base = hp.n_slots;
+    te.src_is_row = false; te.B = B; te.K = K; te.dact = ptr<float>(c->dact); te.act = ptr<float>(c->act);
+    te.coef = ptr<float>(c->coef); te.win = ptr<int32_t>(c->win); te.g_out = apply ? nullptr : ptr<float>(c->gE);
+    TableArgs tr = te;
+    tr.P = c->prm.R.p; tr.Mo = c->prm.R.m; tr.Vo = c->prm.R.v;
+    tr.uniq = pl->d_r_uniq; tr.seg_off = pl->d_r_seg_off; tr.src = pl->d_r_src; tr.n_uniq_dev = pl->d_n_r_uniq;
+    tr.src_is_row = true; tr.g_out = apply ? nullptr : ptr<float>(c->gR);
+
+    Lanes L{c, stream};
+    HIPCHK(c, L.fork(3));
+    HIPCHK(c, launch_table_update(te, ah, L.lane(0)));
+    HIPCHK(c, launch_table_update(tr, ah, L.lane(1)));
+    if (apply) {
+        DenseAdamJob job{};
+        const ngdb_tensor* ts[12] = {&c->prm.W1, &c->prm.b1, &c->prm.W2, &c->prm.b2, &c->prm.V1, &c->prm.c1,
+                                     &c->prm.V2, &c->prm.c2, &c->prm.U1, &c->prm.u1, &c->prm.U2, &c->prm.u2};
+        const int64_t hd = (int64_t)c->cfg.h * d;
+        const int64_t sz[4] = {hd, c->cfg.h, hd, d};
+        for (int i = 0; i < 12; ++i) {
+            job.p[i] = ts[i]->p; job.m[i] = ts[i]->m; job.v[i] = ts[i]->v;
+            job.g[i] = ptr<float>(c->gW) + c->gw_off[i];
+            job.n[i] = sz[i % 4];
+        }
+        job.count = 12;
+        HIPCHK(c, launch_dense_adam(job, ah, L.lane(2)));
+    }
+    HIPCHK(c, L.join());
+
+    if (apply) c->step = t;
+    // describe the results
+    ngdb_grad_view& gv = c->gv;
+    std::memset(&gv, 0, sizeof(gv));
+    gv.n_e_contrib = hp.n_anchor + B + B * K;
+    gv.n_r_uniq = (int32_t)hp.r_uniq.size();
+    gv.n_slots = hp.n_slots;
+    gv.n_pairs = B * (K + 1);
+    gv.e_uniq = ptr<int32_t>(c->uniq);
+    gv.e_seg_off = ptr<int32_t>(c->seg_off);
+    gv.e_src = e_src;
+    gv.gE = apply ? nullptr : ptr<float>(c->gE);
+    gv.gR = apply ? nullptr : ptr<float>(c->gR);
+    for (int i = 0; i < 12; ++i) gv.g_mlp[i] = ptr<float>(c->gW) + c->gw_off[i];
+    gv.act = ptr<float>(c->act);
+    gv.pair_score = ptr<float>(c->score);
+    gv.loss_terms = ptr<float>(c->loss_terms);
+    c->have_grads = true;
+    return NGDB_OK;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------ C ABI
+extern "C" {
+
+int ngdb_create(const ngdb_config* cfg, ngdb_ctx_t** out) {
+    if (!cfg || !out) return NGDB_ERR_ARG;
+    *out = nullptr;
+    if (cfg->n_entities <= 0 || cfg->n_relations <= 0 || cfg->d <= 0 || cfg->h <= 0 || (cfg->d & 3) ||
+        (cfg->h & 3) || cfg->d > 1024 || cfg->num_streams < 1 || cfg->num_streams > 4 || cfg->d_sem < 0)
+        return NGDB_ERR_ARG;
+    if (cfg->d_sem != 0) return NGDB_ERR_UNSUPPORTED;   // text-feature fusion is not built yet
+    ngdb_ctx_t* c = new (std::nothrow) ngdb_ctx_s();
+    if (!c) return NGDB_ERR_OOM;
+    c->cfg = *cfg;
+    c->n_side = cfg->num_streams > 1 ? cfg->num_streams : 0;
+    bool ok = true;
+    for (int i = 0; i < c->n_side && ok; ++i)
+        ok = hipStreamCreateWithFlags(&c->side[i], hipStreamNonBlocking) == hipSuccess &&
+             hipEventCreateWithFlags(&c->ev_join[i], hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) == hipSuccess;
+    if (!ok) {
+        ngdb_destroy(c);
+        return NGDB_ERR_HIP;
+    }
+    *out = c;
+    return NGDB_OK;
+}
+
+void ngdb_destroy(ngdb_ctx_t* c) {
+    if (!c) return;
+    (void)hipDeviceSynchronize();
+    DevBuf* all[] = {&c->act, &c->dact, &c->Z[0], &c->Z[1], &c->Z[2], &c->H[0], &c->H[1], &c->H[2], &c->dH[0],
+                     &c->dH[1], &c->dH[2], &c->Att, &c->dAtt, &c->Dx, &c->score, &c->coef, &c->win,
+                     &c->loss_terms, &c->keys_a, &c->keys_b, &c->vals_a, &c->vals_b, &c->hist, &c->scan_tmp,
+                     &c->uniq, &c->seg_off, &c->n_uniq, &c->gW, &c->gE, &c->gR};
+    for (DevBuf* b : all) release(*b);
+    for (int i = 0; i < 4; ++i) {
+        if (c->side[i]) (void)hipStreamDestroy(c->side[i]);
+        if (c->ev_join[i]) (void)hipEventDestroy(c->ev_join[i]);
+    }
+    if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+    delete c;
+}
+
+int ngdb_bind_params(ngdb_ctx_t* c, const ngdb_params* p) {
+    if (!c || !p) return NGDB_ERR_ARG;
+    const ngdb_tensor* ts[14] = {&p->E, &p->R, &p->W1, &p->b1, &p->W2, &p->b2, &p->V1,
+                                 &p->c1, &p->V2, &p->c2, &p->U1, &p->u1, &p->U2, &p->u2};
+    for (const ngdb_tensor* t : ts) {
+        if (!t->p || !t->m || !t->v) return fail(c, NGDB_ERR_ARG, "null parameter or moment tensor");
+        if (((uintptr_t)t->p | (uintptr_t)t->m | (uintptr_t)t->v) & 15)
+            return fail(c, NGDB_ERR_ARG, "tensors must be 16-byte aligned");
+    }
+    if (p->step < 0) return fail(c, NGDB_ERR_ARG, "negative step count");
+    c->prm = *p;
+    c->step = p->step;
+    c->bound = true;
+    c->have_grads = false;
+    return NGDB_OK;
+}
+
+// host part of planning: frontiers, index arrays, level/type segments
+static int plan_host(const ngdb_query_batch* qb, int32_t n_entities, int32_t n_relations, ngdb_plan_t** out,
+                     std::string& err) {
+    *out = nullptr;
+    ngdb_plan_t* pl = new (std::nothrow) ngdb_plan_s();
+    if (!pl) {
+        err = "host allocation failed";
+        return NGDB_ERR_OOM;
+    }
+    int rc = NGDB_OK;
+    try {
+        rc = build_plan(*qb, n_entities, n_relations, pl->hp, err);
+    } catch (const std::bad_alloc&) {
+        rc = NGDB_ERR_OOM;
+        err = "host allocation failed";
+    }
+    if (rc != NGDB_OK) {
+        delete pl;
+        return rc;
+    }
+    HostPlan& hp = pl->hp;
+    pl->n_entities = n_entities;
+    pl->levels.assign(hp.n_levels + 1, {});
+    for (int g = 0; g < hp.n_groups; ++g) {
+        std::vector<Segment>& segs = pl->levels[hp.g_level[g]];
+        const int t = type_index(hp.g_type[g]);
+        const int rows = hp.g_n[g] * (t == T_INTER ? hp.g_nin[g] : 1);
+        if (!segs.empty() && segs.back().type == t) {   // further intersection class of the same level
+            segs.back().rows += rows;
+            segs.back().g_hi = g + 1;
+        } else {
+            Segment sg;
+            sg.type = t; sg.rows = rows; sg.mlp_base = hp.g_mlp_base[g]; sg.ref_off = hp.g_ref_off[g];
+            sg.rel_off = hp.g_rel_off[g]; sg.out_base = hp.g_out_base[g]; sg.g_lo = g; sg.g_hi = g + 1;
+            segs.push_back(sg);
+        }
+    }
+    *out = pl;
+    return NGDB_OK;
+}
+
+int ngdb_plan_host(int32_t n_entities, int32_t n_relations, const ngdb_query_batch* qb, ngdb_plan_t** out) {
+    if (!qb || !out || n_entities <= 0 || n_relations <= 0) return NGDB_ERR_ARG;
+    std::string err;
+    return plan_host(qb, n_entities, n_relations, out, err);
+}
+
+int ngdb_plan(ngdb_ctx_t* c, const ngdb_query_batch* qb, ngdb_plan_t** out) {
+    if (!c || !qb || !out) return NGDB_ERR_ARG;
+    std::string err;
+    ngdb_plan_t* pl = nullptr;
+    int rc = plan_host(qb, c->cfg.n_entities, c->cfg.n_relations, &pl, err);
+    if (rc != NGDB_OK) return fail(c, rc, err);
+    HostPlan& hp = pl->hp;
+
+    // one upload: every device-side array, each padded to 16 bytes
+    std::vector<int32_t> blob;
+    auto put = [&](const std::vector<int32_t>& v) {
+        const size_t off = blob.size();
+        blob.insert(blob.end(), v.begin(), v.end());
+        while (blob.size() & 3) blob.push_back(0);
+        if (v.empty()) blob.resize(blob.size() + 4, 0);
+        return off;
+    };
+    std::vector<int32_t> ekeys = hp.anchor_ent;
+    ekeys.insert(ekeys.end(), hp.pos.begin(), hp.pos.end());
+    const size_t o_ref = put(hp.in_ref), o_gs = put(hp.in_gslot), o_rel = put(hp.rel), o_ro = put(hp.root_off),
+                 o_rs = put(hp.root_slot), o_pos = put(hp.pos), o_ek = put(ekeys), o_ru = put(hp.r_uniq),
+                 o_rso = put(hp.r_seg_off), o_rsrc = put(hp.r_src),
+                 o_nru = put(std::vector<int32_t>{(int32_t)hp.r_uniq.size()});
+    if (hipMalloc((void**)&pl->d_blob, blob.size() * 4) != hipSuccess) {
+        delete pl;
+        return fail(c, NGDB_ERR_OOM, "device allocation for the plan failed");
+    }
+    if (hipMemcpy(pl->d_blob, blob.data(), blob.size() * 4, hipMemcpyHostToDevice) != hipSuccess) {
+        (void)hipFree(pl->d_blob);
+        delete pl;
+        return fail(c, NGDB_ERR_HIP, "plan upload failed");
+    }
+    pl->d_in_ref = pl->d_blob + o_ref; pl->d_in_gslot = pl->d_blob + o_gs; pl->d_rel = pl->d_blob + o_rel;
+    pl->d_root_off = pl->d_blob + o_ro; pl->d_root_slot = pl->d_blob + o_rs; pl->d_pos = pl->d_blob + o_pos;
+    pl->d_ekeys_head = pl->d_blob + o_ek; pl->d_r_uniq = pl->d_blob + o_ru; pl->d_r_seg_off = pl->d_blob + o_rso;
+    pl->d_r_src = pl->d_blob + o_rsrc; pl->d_n_r_uniq = pl->d_blob + o_nru;
+    *out = pl;
+    return NGDB_OK;
+}
+
+int ngdb_plan_export(const ngdb_plan_t* pl, ngdb_plan_view* v) {
+    if (!pl || !v) return NGDB_ERR_ARG;
+    const HostPlan& hp = pl->hp;
+    v->n_queries = hp.n_queries; v->n_groups = hp.n_groups; v->n_levels = hp.n_levels; v->n_slots = hp.n_slots;
+    v->n_anchor = hp.n_anchor; v->n_proj = hp.n_proj; v->n_inter = hp.n_inter; v->n_neg = hp.n_neg;
+    v->n_int_rows = hp.n_int_rows; v->n_roots = hp.n_roots; v->n_refs = (int32_t)hp.in_ref.size();
+    v->n_r_uniq = (int32_t)hp.r_uniq.size();
+    v->lvl_off = hp.lvl_off.data(); v->g_level = hp.g_level.data(); v->g_type = hp.g_type.data();
+    v->g_nin = hp.g_nin.data(); v->g_n = hp.g_n.data(); v->g_out_base = hp.g_out_base.data();
+    v->g_mlp_base = hp.g_mlp_base.data(); v->g_ref_off = hp.g_ref_off.data(); v->g_rel_off = hp.g_rel_off.data();
+    v->in_ref = hp.in_ref.data(); v->in_gslot = hp.in_gslot.data(); v->rel = hp.rel.data();
+    v->root_off = hp.root_off.data(); v->root_slot = hp.root_slot.data(); v->anchor_ent = hp.anchor_ent.data();
+    v->pos = hp.pos.data(); v->r_uniq = hp.r_uniq.data(); v->r_seg_off = hp.r_seg_off.data();
+    v->r_src = hp.r_src.data();
+    return NGDB_OK;
+}
+
+void ngdb_plan_free(ngdb_plan_t* pl) {
+    if (!pl) return;
+    if (pl->d_blob) (void)hipFree(pl->d_blob);   // waits for work that may still read it
+    delete pl;
+}
+
+int ngdb_train_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int32_t K, void* stream,
+                    float* d_loss) {
+    return run_step(c, pl, d_neg, K, static_cast<hipStream_t>(stream), d_loss, true);
+}
+
+int ngdb_forward_backward(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int32_t K, void* stream,
+                          float* d_loss) {
+    return run_step(c, pl, d_neg, K, static_cast<hipStream_t>(stream), d_loss, false);
+}
+
+int ngdb_get_grads(ngdb_ctx_t* c, ngdb_grad_view* out) {
+    if (!c || !out) return NGDB_ERR_ARG;
+    if (!c->have_grads) return fail(c, NGDB_ERR_STATE, "no step has been run on this context");
+    HIPCHK(c, hipDeviceSynchronize());
+    HIPCHK(c, hipMemcpy(&c->gv.n_e_uniq, c->n_uniq.p, sizeof(int32_t), hipMemcpyDeviceToHost));
+    *out = c->gv;
+    return NGDB_OK;
+}
+
+int ngdb_score(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_cand, int32_t C, int32_t topk,
+               float* d_scores, int32_t* d_topk_ids, float* d_topk_dist, void* stream) {
+    if (!c || !pl) return NGDB_ERR_ARG;
+    if (!c->bound) return fail(c, NGDB_ERR_STATE, "parameters not bound");
+    if (pl->n_entities != c->cfg.n_entities || !pl->d_blob)
+        return fail(c, NGDB_ERR_ARG, "plan belongs to another configuration or was built without a device");
+    (void)topk; (void)d_topk_ids; (void)d_topk_dist;
+    if (!d_cand) return fail(c, NGDB_ERR_UNSUPPORTED, "all-entity ranking is not built yet");
+    if (C <= 0 || !d_scores) return fail(c, NGDB_ERR_ARG, "candidate mode needs C > 0 and d_scores");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    c->have_grads = false;
+    int rc = size_workspace(c, pl, 0, false);
+    if (rc != NGDB_OK) return rc;
+    rc = enqueue_forward(c, pl, s);
+    if (rc != NGDB_OK) return rc;
+    ScoreArgs sa{};
+    sa.act = ptr<float>(c->act); sa.E = c->prm.E.p; sa.root_off = pl->d_root_off; sa.root_slot = pl->d_root_slot;
+    sa.pos = nullptr; sa.cand = d_cand; sa.B = pl->hp.n_queries; sa.C = C; sa.d = c->cfg.d;
+    sa.max_branch = std::max(1, pl->hp.max_branch); sa.gamma = c->cfg.gamma; sa.score = d_scores;
+    hipError_t e = launch_score(sa, false, s);
+    if (e == hipErrorInvalidValue) return fail(c, NGDB_ERR_UNSUPPORTED, "embedding width / union branch count too large for the scoring kernel");
+    HIPCHK(c, e);
+    return NGDB_OK;
+}
+
+int ngdb_copy_to_host(void* h_dst, const void* d_src, size_t bytes) {
+    if (bytes == 0) return NGDB_OK;
+    if (!h_dst || !d_src) return NGDB_ERR_ARG;
+    if (hipDeviceSynchronize() != hipSuccess) return NGDB_ERR_HIP;
+    return hipMemcpy(h_dst, d_src, bytes, hipMemcpyDeviceToHost) == hipSuccess ? NGDB_OK : NGDB_ERR_HIP;
+}
+
+int64_t ngdb_step_count(const ngdb_ctx_t* c) { return c ? c->step : -1; }
+
+const char* ngdb_strerror(int code) {
+    switch (code) {
+        case NGDB_OK: return "ok";
+        case NGDB_ERR_ARG: return "invalid argument";
+        case NGDB_ERR_UNSUPPORTED: return "unsupported query or configuration";
+        case NGDB_ERR_RANGE: return "entity or relation id out of range";
+        case NGDB_ERR_OOM: return "out of memory";
+        case NGDB_ERR_HIP: return "HIP runtime error";
+        case NGDB_ERR_STATE: return "call order error";
+        default: return "unknown error";
+    }
+}
+
+const char* ngdb_last_error(const ngdb_ctx_t* c) { return c ? c->err.c_str() : ""; }
+
+}  // extern "C"

@@ -1,0 +1,144 @@
+// Shared declarations of the library's translation units (host side) and the
+// small device helpers every kernel file uses.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdint>
+#include <string>
+#include <utility>
+
+#include "ngdb.h"
+
+namespace ngdb {
+
+constexpr int WAVE = 64;
+
+// ---------------------------------------------------------------- device helpers
+#if defined(__HIPCC__)
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, WAVE);
+    return v;
+}
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (WAVE - 1); }
+__device__ __forceinline__ float sgn(float x) { return (float)((x > 0.f) - (x < 0.f)); }
+// log(1+exp(x)) and 1/(1+exp(-x)) without overflow
+__device__ __forceinline__ float softplus_f(float x) { return fmaxf(x, 0.f) + log1pf(expf(-fabsf(x))); }
+__device__ __forceinline__ float sigmoid_f(float x) {
+    const float e = expf(-fabsf(x));
+    return x >= 0.f ? 1.f / (1.f + e) : e / (1.f + e);
+}
+#endif
+
+// ---------------------------------------------------------------- GEMM (gemm.hip)
+// C[M,N] = A[M,K] * B[K,N] with fp32 MFMA.  Element (m,k) of A is at
+// A[m*lda+k] if a_kcontig else A[k*lda+m]; element (k,n) of B is at B[n*ldb+k]
+// if b_kcontig else B[k*ldb+n].  Epilogue, in this order: + bias[n]; relu;
+// * (mask[m*ldmask+n] > 0); + addend[m*ldadd+n]; row m goes to C row
+// dst_row[m] if dst_row else m.
+struct GemmArgs {
+    const float* A = nullptr;
+    const float* B = nullptr;
+    float* C = nullptr;
+    int M = 0, N = 0, K = 0;
+    int lda = 0, ldb = 0, ldc = 0;
+    bool a_kcontig = true, b_kcontig = true;
+    const float* bias = nullptr;
+    bool relu = false;
+    const float* mask = nullptr;
+    int ldmask = 0;
+    const float* addend = nullptr;
+    int ldadd = 0;
+    const int32_t* dst_row = nullptr;
+};
+hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
+
+// ---------------------------------------------------------------- elementwise ops (ops.hip)
+// Z[m,:] = src(ref[m]) (+ R[rel[m]]), src = act row if ref >= 0 else E row -1-ref.
+hipError_t launch_gather(float* Z, const int32_t* ref, const int32_t* rel, int rows, int d,
+                         const float* act, const float* E, const float* R, hipStream_t s);
+// Intersection of n members with k inputs: rows j*n+i of X (inputs) and Att (logits).
+hipError_t launch_inter_fwd(const float* X, const float* Att, float* out, int n, int k, int d, hipStream_t s);
+// dAtt[j*n+i] = w_j*(dy*x_j - sum_l w_l dy x_l),  Dx[j*n+i] = w_j*dy
+hipError_t launch_inter_bwd(const float* X, const float* Att, const float* dY, float* dAtt, float* Dx,
+                            int n, int k, int d, hipStream_t s);
+// out[c] = sum_m X[m*ld + c], c < cols (fixed summation order)
+hipError_t launch_colsum(const float* X, int rows, int cols, int ld, float* out, hipStream_t s);
+hipError_t launch_fill_zero(float* p, size_t n, hipStream_t s);
+
+struct AdamHyper {
+    float lr, beta1, beta2, eps;
+    float bc1, bc2;   // 1 - beta^t for the step being applied
+};
+struct DenseAdamJob {
+    float* p[13];
+    float* m[13];
+    float* v[13];
+    const float* g[13];
+    int64_t n[13];
+    int count;
+};
+hipError_t launch_dense_adam(const DenseAdamJob& job, const AdamHyper& hp, hipStream_t s);
+// loss[0] = scale * sum_i terms[i]
+hipError_t launch_loss_reduce(const float* terms, int n, float scale, float* loss, hipStream_t s);
+
+// ---------------------------------------------------------------- scoring (score.hip)
+struct ScoreArgs {
+    const float* act;          // [n_slots, d]
+    const float* E;            // [N, d]
+    const int32_t* root_off;   // [B+1]
+    const int32_t* root_slot;  // [n_roots]
+    const int32_t* pos;        // [B] or null (then candidates only)
+    const int32_t* cand;       // [B, C]
+    int B, C, d, max_branch;
+    float gamma;
+    // outputs
+    float* score;              // [B, C + (pos?1:0)]
+    float* coef;               // same shape, dL/ds (training only)
+    int32_t* win;              // same shape, root slot of the winning branch (training only)
+    float* dact;               // gradient arena (training only)
+    float* loss_terms;         // [B] (training only)
+};
+hipError_t launch_score(const ScoreArgs& a, bool train, hipStream_t s);
+
+// ---------------------------------------------------------------- index (index.hip)
+struct IndexBuffers {   // device scratch owned by the context, sized for n_keys
+    int32_t *keys_a, *keys_b, *vals_a, *vals_b;   // [n_keys]
+    int32_t* hist;                                // [256 * n_tiles] + scan scratch
+    int32_t* scan_tmp;                            // block sums
+    int32_t *uniq, *seg_off;                      // [n_keys], [n_keys+1]
+    int32_t* n_uniq;                              // device scalar
+};
+size_t index_hist_elems(int64_t n_keys);
+size_t index_scan_tmp_elems(int64_t n_keys);
+// keys = [head[0..n_head) | tail[0..n_tail)], values < key_bound.  On return
+// (stream order) uniq/seg_off/n_uniq are filled and the contribution order is in
+// *src_out (one of vals_a / vals_b).
+hipError_t build_segment_index(const int32_t* head, int n_head, const int32_t* tail, int64_t n_tail,
+                               int32_t key_bound, const IndexBuffers& buf, int32_t** src_out,
+                               hipStream_t s);
+
+// ---------------------------------------------------------------- tables (table.hip)
+struct TableArgs {
+    float *P, *Mo, *Vo;            // table and moments [rows, d]
+    const int32_t* uniq;           // [n_uniq] row ids
+    const int32_t* seg_off;        // [n_uniq+1]
+    const int32_t* src;            // contributions in segment order
+    const int32_t* n_uniq_dev;     // device scalar
+    int d;
+    // contribution decoding: c < n_rowsrc -> gradient row (entity table: dact row
+    // row_base + c; relation table: dact row src itself with n_rowsrc = INT_MAX);
+    // otherwise a (query, candidate) pair.
+    int n_rowsrc, row_base;
+    bool src_is_row;               // relation table: src values are dact rows
+    int B, K;
+    const float* dact;
+    const float* act;
+    const float* coef;
+    const int32_t* win;
+    float* g_out;                  // if set: write gradients [n_uniq, d] instead of updating
+};
+hipError_t launch_table_update(const TableArgs& a, const AdamHyper& hp, hipStream_t s);
+
+}  // namespace ngdb

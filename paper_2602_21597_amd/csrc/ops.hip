@@ -1,0 +1,173 @@
+// Memory-bound pieces around the grouped MLPs: row gathers through the plan's
+// precomputed references (Sec. 4.2 "Efficient Tensor Indexing"), the attention
+// pooling of the intersection classes C_k (Sec. 4.3), column sums for the bias
+// gradients, dense Adam (Alg. 1, OptimizerStep) and the final loss reduction.
+#include "common.h"
+
+namespace ngdb {
+namespace {
+
+// one workgroup of 128 threads per row, float4 per thread
+__global__ __launch_bounds__(128) void gather_kernel(float* __restrict__ Z, const int32_t* __restrict__ ref,
+                                                     const int32_t* __restrict__ rel, int rows, int d4,
+                                                     const float* __restrict__ act, const float* __restrict__ E,
+                                                     const float* __restrict__ R) {
+    const int m = blockIdx.x;
+    if (m >= rows) return;
+    const int32_t r = ref[m];
+    const float4* src = reinterpret_cast<const float4*>(r >= 0 ? act + (size_t)r * d4 * 4
+                                                               : E + (size_t)(-1 - r) * d4 * 4);
+    const float4* rr = rel ? reinterpret_cast<const float4*>(R + (size_t)rel[m] * d4 * 4) : nullptr;
+    float4* dst = reinterpret_cast<float4*>(Z + (size_t)m * d4 * 4);
+    for (int c = threadIdx.x; c < d4; c += blockDim.x) {
+        float4 v = src[c];
+        if (rr) {
+            const float4 w = rr[c];
+            v.x += w.x; v.y += w.y; v.z += w.z; v.w += w.w;
+        }
+        dst[c] = v;
+    }
+}
+
+// y_i = sum_j softmax_j(att_j)_c * x_j,c : one thread per (member, coordinate)
+template <bool BWD>
+__global__ __launch_bounds__(256) void inter_kernel(const float* __restrict__ X, const float* __restrict__ Att,
+                                                    const float* __restrict__ dY, float* __restrict__ out,
+                                                    float* __restrict__ dAtt, float* __restrict__ Dx,
+                                                    int n, int k, int d) {
+    const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= (size_t)n * d) return;
+    const int i = (int)(t / d), c = (int)(t % d);
+    float a[NGDB_MAX_CARD], x[NGDB_MAX_CARD];
+    float mx = -INFINITY;
+    for (int j = 0; j < k; ++j) {
+        const size_t row = (size_t)j * n + i;
+        a[j] = Att[row * d + c];
+        x[j] = X[row * d + c];
+        mx = fmaxf(mx, a[j]);
+    }
+    float den = 0.f;
+    for (int j = 0; j < k; ++j) {
+        a[j] = expf(a[j] - mx);
+        den += a[j];
+    }
+    const float inv = 1.f / den;
+    if (!BWD) {
+        float y = 0.f;
+        for (int j = 0; j < k; ++j) y += a[j] * inv * x[j];
+        out[(size_t)i * d + c] = y;
+    } else {
+        const float dy = dY[(size_t)i * d + c];
+        float tall = 0.f;
+        for (int j = 0; j < k; ++j) tall += a[j] * inv * x[j] * dy;
+        for (int j = 0; j < k; ++j) {
+            const size_t row = (size_t)j * n + i;
+            const float w = a[j] * inv;
+            dAtt[row * d + c] = w * (dy * x[j] - tall);
+            Dx[row * d + c] = w * dy;
+        }
+    }
+}
+
+// column sums in a fixed order: thread per column, rows split over blockDim.y and
+// combined through LDS
+__global__ __launch_bounds__(256) void colsum_kernel(const float* __restrict__ X, int rows, int cols, int ld,
+                                                     float* __restrict__ out) {
+    __shared__ float part[4][64];
+    const int c = blockIdx.x * 64 + threadIdx.x;
+    float s = 0.f;
+    if (c < cols)
+        for (int m = threadIdx.y; m < rows; m += 4) s += X[(size_t)m * ld + c];
+    part[threadIdx.y][threadIdx.x] = s;
+    __syncthreads();
+    if (threadIdx.y == 0 && c < cols)
+        out[c] = (part[0][threadIdx.x] + part[1][threadIdx.x]) + (part[2][threadIdx.x] + part[3][threadIdx.x]);
+}
+
+__global__ __launch_bounds__(256) void fill_zero_kernel(float* p, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+        p[i] = 0.f;
+}
+
+__global__ __launch_bounds__(256) void dense_adam_kernel(const DenseAdamJob job, const AdamHyper hp) {
+    const int t = blockIdx.y;
+    float* __restrict__ p = job.p[t];
+    float* __restrict__ m = job.m[t];
+    float* __restrict__ v = job.v[t];
+    const float* __restrict__ g = job.g[t];
+    const int64_t n = job.n[t];
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        const float gi = g[i];
+        const float mi = hp.beta1 * m[i] + (1.f - hp.beta1) * gi;
+        const float vi = hp.beta2 * v[i] + (1.f - hp.beta2) * gi * gi;
+        m[i] = mi;
+        v[i] = vi;
+        p[i] -= hp.lr * (mi / hp.bc1) / (sqrtf(vi / hp.bc2) + hp.eps);
+    }
+}
+
+__global__ __launch_bounds__(256) void loss_reduce_kernel(const float* __restrict__ terms, int n, float scale,
+                                                          float* __restrict__ loss) {
+    __shared__ float part[4];
+    float s = 0.f;
+    for (int i = threadIdx.x; i < n; i += 256) s += terms[i];
+    s = wave_sum(s);
+    if (lane_id() == 0) part[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) loss[0] = scale * ((part[0] + part[1]) + (part[2] + part[3]));
+}
+
+}  // namespace
+
+hipError_t launch_gather(float* Z, const int32_t* ref, const int32_t* rel, int rows, int d, const float* act,
+                         const float* E, const float* R, hipStream_t s) {
+    if (rows <= 0) return hipSuccess;
+    hipLaunchKernelGGL(gather_kernel, dim3(rows), dim3(128), 0, s, Z, ref, rel, rows, d / 4, act, E, R);
+    return hipGetLastError();
+}
+
+hipError_t launch_inter_fwd(const float* X, const float* Att, float* out, int n, int k, int d, hipStream_t s) {
+    if (n <= 0) return hipSuccess;
+    const size_t total = (size_t)n * d;
+    hipLaunchKernelGGL((inter_kernel<false>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, X, Att,
+                       (const float*)nullptr, out, (float*)nullptr, (float*)nullptr, n, k, d);
+    return hipGetLastError();
+}
+
+hipError_t launch_inter_bwd(const float* X, const float* Att, const float* dY, float* dAtt, float* Dx, int n,
+                            int k, int d, hipStream_t s) {
+    if (n <= 0) return hipSuccess;
+    const size_t total = (size_t)n * d;
+    hipLaunchKernelGGL((inter_kernel<true>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, X, Att, dY,
+                       (float*)nullptr, dAtt, Dx, n, k, d);
+    return hipGetLastError();
+}
+
+hipError_t launch_colsum(const float* X, int rows, int cols, int ld, float* out, hipStream_t s) {
+    if (cols <= 0) return hipSuccess;
+    hipLaunchKernelGGL(colsum_kernel, dim3((cols + 63) / 64), dim3(64, 4), 0, s, X, rows, cols, ld, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_zero(float* p, size_t n, hipStream_t s) {
+    if (n == 0) return hipSuccess;
+    const unsigned blocks = (unsigned)std::min<size_t>((n + 255) / 256, 4096);
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, s, p, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_dense_adam(const DenseAdamJob& job, const AdamHyper& hp, hipStream_t s) {
+    if (job.count <= 0) return hipSuccess;
+    int64_t mx = 0;
+    for (int t = 0; t < job.count; ++t) mx = std::max(mx, job.n[t]);
+    const unsigned bx = (unsigned)std::min<int64_t>((mx + 255) / 256, 512);
+    hipLaunchKernelGGL(dense_adam_kernel, dim3(bx, job.count), dim3(256), 0, s, job, hp);
+    return hipGetLastError();
+}
+
+hipError_t launch_loss_reduce(const float* terms, int n, float scale, float* loss, hipStream_t s) {
+    hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(256), 0, s, terms, n, scale, loss);
+    return hipGetLastError();
+}
+
+}  // namespace ngdb

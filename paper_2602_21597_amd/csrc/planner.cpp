@@ -1,0 +1,312 @@
+// Host planner.  Turns a batch of query trees into the level-synchronous form of
+// the paper's operator pools (Sec. 4.1): at every depth, the operators of one
+// type (and, for intersections, one input count -- the classes C_k of Sec. 4.3)
+// from all queries form one group that is executed as one batch.  All gather /
+// scatter positions are resolved here, ahead of the step (Sec. 4.2 "Efficient
+// Tensor Indexing").  The numbering rules are stated in ngdb.h (ngdb_plan_view).
+#include "planner.h"
+
+#include <algorithm>
+#include <numeric>
+
+namespace ngdb {
+namespace {
+
+struct Tree {          // node of a union-free branch
+    int32_t type, arg;
+    std::vector<int32_t> kids;
+};
+
+struct Expander {
+    const ngdb_query_batch& qb;
+    int32_t base;                 // first node of the current query
+    int32_t n_local;
+    std::vector<Tree>& pool;
+    std::string& err;
+    int code = NGDB_OK;
+
+    int32_t make(int32_t type, int32_t arg, std::vector<int32_t> kids) {
+        pool.push_back(Tree{type, arg, std::move(kids)});
+        return (int32_t)pool.size() - 1;
+    }
+
+    // Conjunctive branches of the sub-query rooted at local node j.
+    std::vector<int32_t> expand(int32_t j, int depth) {
+        std::vector<int32_t> out;
+        if (code != NGDB_OK) return out;
+        if (depth > NGDB_MAX_LEVELS + 1) {
+            code = NGDB_ERR_UNSUPPORTED;
+            err = "query deeper than NGDB_MAX_LEVELS";
+            return out;
+        }
+        const int32_t n = base + j;
+        const int32_t lo = qb.in_off[n], hi = qb.in_off[n + 1];
+        const int op = qb.op[n];
+        switch (op) {
+            case NGDB_OP_ANCHOR:
+                out.push_back(make(NGDB_OP_ANCHOR, qb.arg[n], {}));
+                break;
+            case NGDB_OP_PROJ: {
+                for (int32_t b : expand(qb.in_idx[lo], depth + 1))
+                    out.push_back(make(NGDB_OP_PROJ, qb.arg[n], {b}));
+                break;
+            }
+            case NGDB_OP_UNION: {
+                for (int32_t k = lo; k < hi; ++k) {
+                    std::vector<int32_t> sub = expand(qb.in_idx[k], depth + 1);
+                    out.insert(out.end(), sub.begin(), sub.end());
+                }
+                break;
+            }
+            default: {   // INTER, NEG: every input must be union-free
+                std::vector<int32_t> kids;
+                for (int32_t k = lo; k < hi; ++k) {
+                    std::vector<int32_t> sub = expand(qb.in_idx[k], depth + 1);
+                    if (code != NGDB_OK) return out;
+                    if (sub.size() != 1) {
+                        code = NGDB_ERR_UNSUPPORTED;
+                        err = "union below an intersection or a negation";
+                        return out;
+                    }
+                    kids.push_back(sub[0]);
+                }
+                out.push_back(make(op, 0, std::move(kids)));
+            }
+        }
+        if ((int)out.size() > NGDB_MAX_BRANCH && code == NGDB_OK) {
+            code = NGDB_ERR_UNSUPPORTED;
+            err = "query has more than NGDB_MAX_BRANCH conjunctive branches";
+        }
+        return out;
+    }
+};
+
+struct Flat {   // all nodes of the batch after DNF, by global id
+    std::vector<int32_t> type, arg, level, in_off, in;
+    int32_t add(int32_t t, int32_t a, int32_t lvl, const std::vector<int32_t>& ins) {
+        type.push_back(t);
+        arg.push_back(a);
+        level.push_back(lvl);
+        in.insert(in.end(), ins.begin(), ins.end());
+        in_off.push_back((int32_t)in.size());
+        return (int32_t)type.size() - 1;
+    }
+    int32_t nin(int32_t g) const { return in_off[g + 1] - in_off[g]; }
+};
+
+int32_t number_postorder(const std::vector<Tree>& pool, int32_t t, Flat& flat) {
+    const Tree& node = pool[t];
+    std::vector<int32_t> ins;
+    int32_t lvl = 0;
+    for (int32_t k : node.kids) {
+        int32_t g = number_postorder(pool, k, flat);
+        ins.push_back(g);
+        lvl = std::max(lvl, flat.level[g] + 1);
+    }
+    return flat.add(node.type, node.arg, lvl, ins);
+}
+
+int validate(const ngdb_query_batch& qb, int32_t N, int32_t R, std::string& err) {
+    if (qb.n_queries < 0) { err = "n_queries < 0"; return NGDB_ERR_ARG; }
+    if (qb.n_queries == 0) return NGDB_OK;
+    if (!qb.node_off || !qb.op || !qb.arg || !qb.in_off || !qb.pos) {
+        err = "null array in query batch";
+        return NGDB_ERR_ARG;
+    }
+    if (qb.node_off[0] != 0 || qb.in_off[0] != 0) { err = "offsets must start at 0"; return NGDB_ERR_ARG; }
+    for (int32_t q = 0; q < qb.n_queries; ++q) {
+        const int32_t lo = qb.node_off[q], hi = qb.node_off[q + 1];
+        if (hi <= lo) { err = "query without nodes"; return NGDB_ERR_ARG; }
+        if (qb.pos[q] < 0 || qb.pos[q] >= N) { err = "positive entity id out of range"; return NGDB_ERR_RANGE; }
+        for (int32_t n = lo; n < hi; ++n) {
+            const int32_t a = qb.in_off[n], b = qb.in_off[n + 1];
+            if (b < a) { err = "in_off not monotone"; return NGDB_ERR_ARG; }
+            const int32_t nin = b - a;
+            if (nin > 0 && !qb.in_idx) { err = "null in_idx"; return NGDB_ERR_ARG; }
+            for (int32_t k = a; k < b; ++k)
+                if (qb.in_idx[k] < 0 || qb.in_idx[k] >= n - lo) {
+                    err = "input must be an earlier node of the same query";
+                    return NGDB_ERR_ARG;
+                }
+            switch (qb.op[n]) {
+                case NGDB_OP_ANCHOR:
+                    if (nin != 0) { err = "anchor with inputs"; return NGDB_ERR_ARG; }
+                    if (qb.arg[n] < 0 || qb.arg[n] >= N) { err = "anchor entity id out of range"; return NGDB_ERR_RANGE; }
+                    break;
+                case NGDB_OP_PROJ:
+                    if (nin != 1) { err = "projection needs one input"; return NGDB_ERR_ARG; }
+                    if (qb.arg[n] < 0 || qb.arg[n] >= R) { err = "relation id out of range"; return NGDB_ERR_RANGE; }
+                    break;
+                case NGDB_OP_NEG:
+                    if (nin != 1) { err = "negation needs one input"; return NGDB_ERR_ARG; }
+                    break;
+                case NGDB_OP_INTER:
+                    if (nin < 2) { err = "intersection needs at least two inputs"; return NGDB_ERR_ARG; }
+                    if (nin > NGDB_MAX_CARD) { err = "intersection with more than NGDB_MAX_CARD inputs"; return NGDB_ERR_UNSUPPORTED; }
+                    break;
+                case NGDB_OP_UNION:
+                    if (nin < 1) { err = "union without inputs"; return NGDB_ERR_ARG; }
+                    break;
+                default:
+                    err = "unknown operator code";
+                    return NGDB_ERR_ARG;
+            }
+        }
+    }
+    return NGDB_OK;
+}
+
+// Stable grouping of `keys` (values < n_keys): unique keys ascending, segment
+// offsets, and the permutation that lists each segment's members in input order.
+void segment_index(const std::vector<int32_t>& keys, std::vector<int32_t>& uniq,
+                   std::vector<int32_t>& seg_off, std::vector<int32_t>& order) {
+    order.resize(keys.size());
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(),
+                     [&](int32_t a, int32_t b) { return keys[a] < keys[b]; });
+    uniq.clear();
+    seg_off.clear();
+    for (size_t i = 0; i < order.size(); ++i)
+        if (i == 0 || keys[order[i]] != keys[order[i - 1]]) {
+            uniq.push_back(keys[order[i]]);
+            seg_off.push_back((int32_t)i);
+        }
+    seg_off.push_back((int32_t)order.size());
+}
+
+}  // namespace
+
+int build_plan(const ngdb_query_batch& qb, int32_t N, int32_t R, HostPlan& P, std::string& err) {
+    int rc = validate(qb, N, R, err);
+    if (rc != NGDB_OK) return rc;
+    P = HostPlan{};
+    const int32_t B = qb.n_queries;
+    P.n_queries = B;
+    P.pos.assign(qb.pos, qb.pos + B);
+
+    // 1. DNF + global numbering
+    Flat flat;
+    flat.in_off.push_back(0);
+    std::vector<std::vector<int32_t>> roots(B);
+    std::vector<Tree> pool;
+    for (int32_t q = 0; q < B; ++q) {
+        pool.clear();
+        Expander ex{qb, qb.node_off[q], qb.node_off[q + 1] - qb.node_off[q], pool, err};
+        std::vector<int32_t> branches = ex.expand(ex.n_local - 1, 0);
+        if (ex.code != NGDB_OK) return ex.code;
+        for (int32_t b : branches) {
+            if (pool[b].type == NGDB_OP_ANCHOR) {
+                err = "a query must contain at least one operator";
+                return NGDB_ERR_UNSUPPORTED;
+            }
+            int32_t g = number_postorder(pool, b, flat);
+            if (flat.level[g] > NGDB_MAX_LEVELS) {
+                err = "query deeper than NGDB_MAX_LEVELS";
+                return NGDB_ERR_UNSUPPORTED;
+            }
+            roots[q].push_back(g);
+        }
+        P.max_branch = std::max<int32_t>(P.max_branch, (int32_t)branches.size());
+    }
+    const int32_t n_nodes = (int32_t)flat.type.size();
+
+    // 2. anchors and operator nodes
+    std::vector<int32_t> ops, anchor_idx(n_nodes, -1);
+    for (int32_t g = 0; g < n_nodes; ++g) {
+        if (flat.type[g] == NGDB_OP_ANCHOR) {
+            anchor_idx[g] = (int32_t)P.anchor_ent.size();
+            P.anchor_ent.push_back(flat.arg[g]);
+        } else {
+            ops.push_back(g);
+        }
+    }
+    P.n_anchor = (int32_t)P.anchor_ent.size();
+    P.n_slots = (int32_t)ops.size();
+
+    // 3. slots: type-major, then level, input count, node id
+    auto type_rank = [](int32_t t) { return t == NGDB_OP_PROJ ? 0 : (t == NGDB_OP_INTER ? 1 : 2); };
+    std::vector<int32_t> by_slot = ops;
+    std::stable_sort(by_slot.begin(), by_slot.end(), [&](int32_t a, int32_t b) {
+        const int ta = type_rank(flat.type[a]), tb = type_rank(flat.type[b]);
+        if (ta != tb) return ta < tb;
+        if (flat.level[a] != flat.level[b]) return flat.level[a] < flat.level[b];
+        return flat.nin(a) < flat.nin(b);
+    });
+    std::vector<int32_t> slot(n_nodes, -1);
+    for (int32_t s = 0; s < P.n_slots; ++s) {
+        slot[by_slot[s]] = s;
+        const int32_t t = flat.type[by_slot[s]];
+        if (t == NGDB_OP_PROJ) ++P.n_proj;
+        else if (t == NGDB_OP_INTER) ++P.n_inter;
+        else ++P.n_neg;
+    }
+    const int32_t type_base[3] = {0, P.n_proj, P.n_proj + P.n_inter};
+    auto grad_row = [&](int32_t g) { return slot[g] >= 0 ? slot[g] : P.n_slots + anchor_idx[g]; };
+
+    // 4. groups: level, type, input count; members in node order
+    std::vector<int32_t> by_group = ops;
+    std::stable_sort(by_group.begin(), by_group.end(), [&](int32_t a, int32_t b) {
+        if (flat.level[a] != flat.level[b]) return flat.level[a] < flat.level[b];
+        const int ta = type_rank(flat.type[a]), tb = type_rank(flat.type[b]);
+        if (ta != tb) return ta < tb;
+        return flat.nin(a) < flat.nin(b);
+    });
+    size_t i = 0;
+    while (i < by_group.size()) {
+        const int32_t g0 = by_group[i];
+        size_t j = i;
+        while (j < by_group.size() && flat.level[by_group[j]] == flat.level[g0] &&
+               flat.type[by_group[j]] == flat.type[g0] && flat.nin(by_group[j]) == flat.nin(g0))
+            ++j;
+        const int32_t n = (int32_t)(j - i), nin = flat.nin(g0), t = flat.type[g0];
+        P.g_level.push_back(flat.level[g0]);
+        P.g_type.push_back(t);
+        P.g_nin.push_back(nin);
+        P.g_n.push_back(n);
+        P.g_out_base.push_back(slot[g0]);
+        P.g_ref_off.push_back((int32_t)P.in_ref.size());
+        if (t == NGDB_OP_INTER) {
+            P.g_mlp_base.push_back(P.n_int_rows);
+            P.n_int_rows += n * nin;
+        } else {
+            P.g_mlp_base.push_back(slot[g0] - type_base[type_rank(t)]);
+        }
+        P.g_rel_off.push_back(t == NGDB_OP_PROJ ? (int32_t)P.rel.size() : -1);
+        for (int32_t k = 0; k < nin; ++k)
+            for (size_t m = i; m < j; ++m) {
+                const int32_t c = flat.in[flat.in_off[by_group[m]] + k];
+                P.in_ref.push_back(slot[c] >= 0 ? slot[c] : -1 - flat.arg[c]);
+                P.in_gslot.push_back(grad_row(c));
+            }
+        if (t == NGDB_OP_PROJ)
+            for (size_t m = i; m < j; ++m) P.rel.push_back(flat.arg[by_group[m]]);
+        i = j;
+    }
+    P.n_groups = (int32_t)P.g_level.size();
+    P.n_levels = P.n_groups ? P.g_level.back() : 0;
+    P.lvl_off.assign(P.n_levels + 2, 0);
+    for (int32_t l : P.g_level) P.lvl_off[l + 1] += 1;
+    for (size_t l = 1; l < P.lvl_off.size(); ++l) P.lvl_off[l] += P.lvl_off[l - 1];
+
+    // 5. roots
+    P.root_off.push_back(0);
+    for (int32_t q = 0; q < B; ++q) {
+        for (int32_t g : roots[q]) P.root_slot.push_back(slot[g]);
+        P.root_off.push_back((int32_t)P.root_slot.size());
+    }
+    P.n_roots = (int32_t)P.root_slot.size();
+
+    // 6. relation gradient index over the projections in slot order
+    std::vector<int32_t> rkeys(P.n_proj), rsrc(P.n_proj), order;
+    for (int32_t s = 0; s < P.n_proj; ++s) {
+        const int32_t g = by_slot[s];
+        rkeys[s] = flat.arg[g];
+        rsrc[s] = grad_row(flat.in[flat.in_off[g]]);
+    }
+    segment_index(rkeys, P.r_uniq, P.r_seg_off, order);
+    P.r_src.resize(P.n_proj);
+    for (int32_t s = 0; s < P.n_proj; ++s) P.r_src[s] = rsrc[order[s]];
+    return NGDB_OK;
+}
+
+}  // namespace ngdb

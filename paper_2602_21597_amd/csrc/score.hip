@@ -1,0 +1,182 @@
+// Fused candidate scoring: s(q,e) = gamma - min_b ||y_b - E[e]||_1 for the
+// positive and the K negatives of every query, the log-sigmoid loss terms,
+// dL/ds per pair and the gradient of every branch embedding, in one pass over
+// the candidate rows (Sec. 4.2 "Vectorized Logit Formulation": all positive and
+// negative candidates of the batch are scored together; the entity rows are
+// fetched through precomputed ids and never materialised).
+//
+// One workgroup per query; each wavefront streams whole candidate rows (a lane
+// holds float4 pieces 64 apart, so a row is read in fully coalesced 1 KB
+// requests), reduces |y - e| across the wavefront, and keeps its share of
+// dL/dy in registers (one branch) or LDS (union queries).  Partial sums of the
+// wavefronts are combined in a fixed order, so results do not depend on timing.
+#include "common.h"
+
+namespace ngdb {
+namespace {
+
+template <int NCH, int NW, bool TRAIN>
+__global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    const int i = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int d4 = a.d >> 2;
+    const int r0 = a.root_off[i];
+    const int nb = a.root_off[i + 1] - r0;
+    const int has_pos = a.pos ? 1 : 0;
+    const int CT = a.C + has_pos;
+
+    float4* ybr = reinterpret_cast<float4*>(lds);                    // [nb][d4]
+    float4* accs = ybr + (size_t)a.max_branch * d4;                  // [NW][nb][d4]   (TRAIN)
+    float* lossp = reinterpret_cast<float*>(accs + (TRAIN ? (size_t)NW * a.max_branch * d4 : 0));
+
+    for (int idx = tid; idx < nb * d4; idx += NW * 64) {
+        const int b = idx / d4, c = idx - b * d4;
+        ybr[idx] = reinterpret_cast<const float4*>(a.act + (size_t)a.root_slot[r0 + b] * a.d)[c];
+    }
+    float4* myacc = accs + (size_t)wave * nb * d4;
+    if (TRAIN && nb > 1)
+        for (int idx = lane; idx < nb * d4; idx += 64) myacc[idx] = make_float4(0.f, 0.f, 0.f, 0.f);
+    __syncthreads();
+
+    const float inv2B = 1.f / (2.f * (float)a.B);
+    const float invK = a.C > 0 ? 1.f / (float)a.C : 0.f;
+    float4 dyr[NCH];
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) dyr[ch] = make_float4(0.f, 0.f, 0.f, 0.f);
+    float lsum = 0.f;
+
+    auto load_row = [&](int c, float4* dst) {
+        const int32_t e = (has_pos && c == 0) ? a.pos[i] : a.cand[(size_t)i * a.C + (c - has_pos)];
+        const float4* row = reinterpret_cast<const float4*>(a.E + (size_t)e * a.d);
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch) {
+            const int col = ch * 64 + lane;
+            dst[ch] = col < d4 ? row[col] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    };
+
+    float4 cur[NCH], nxt[NCH];
+    int c = wave;
+    if (c < CT) load_row(c, cur);
+    for (; c < CT; c += NW) {
+        if (c + NW < CT) load_row(c + NW, nxt);
+        float best = INFINITY;
+        int bw = 0;
+        for (int b = 0; b < nb; ++b) {
+            float dist = 0.f;
+#pragma unroll
+            for (int ch = 0; ch < NCH; ++ch) {
+                const int col = ch * 64 + lane;
+                if (col < d4) {
+                    const float4 y = ybr[b * d4 + col];
+                    dist += (fabsf(y.x - cur[ch].x) + fabsf(y.y - cur[ch].y)) +
+                            (fabsf(y.z - cur[ch].z) + fabsf(y.w - cur[ch].w));
+                }
+            }
+            dist = wave_sum(dist);
+            if (dist < best) {   // strict: equal distances keep the lower branch
+                best = dist;
+                bw = b;
+            }
+        }
+        const float s = a.gamma - best;
+        const size_t pair = (size_t)i * CT + c;
+        if (lane == 0) a.score[pair] = s;
+        if (TRAIN) {
+            const bool is_pos = (c == 0);
+            const float coef = is_pos ? -sigmoid_f(-s) * inv2B : sigmoid_f(s) * inv2B * invK;
+            lsum += is_pos ? softplus_f(-s) : softplus_f(s) * invK;
+            if (lane == 0) {
+                a.coef[pair] = coef;
+                a.win[pair] = a.root_slot[r0 + bw];
+            }
+#pragma unroll
+            for (int ch = 0; ch < NCH; ++ch) {
+                const int col = ch * 64 + lane;
+                if (col < d4) {
+                    const float4 y = ybr[bw * d4 + col];
+                    float4 g;
+                    g.x = coef * sgn(y.x - cur[ch].x);
+                    g.y = coef * sgn(y.y - cur[ch].y);
+                    g.z = coef * sgn(y.z - cur[ch].z);
+                    g.w = coef * sgn(y.w - cur[ch].w);
+                    if (nb == 1) {
+                        dyr[ch].x -= g.x; dyr[ch].y -= g.y; dyr[ch].z -= g.z; dyr[ch].w -= g.w;
+                    } else {
+                        float4 t = myacc[bw * d4 + col];
+                        t.x -= g.x; t.y -= g.y; t.z -= g.z; t.w -= g.w;
+                        myacc[bw * d4 + col] = t;
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch) cur[ch] = nxt[ch];
+    }
+
+    if (TRAIN) {
+        if (nb == 1) {
+#pragma unroll
+            for (int ch = 0; ch < NCH; ++ch) {
+                const int col = ch * 64 + lane;
+                if (col < d4) myacc[col] = dyr[ch];
+            }
+        }
+        if (lane == 0) lossp[wave] = lsum;
+        __syncthreads();
+        for (int idx = tid; idx < nb * d4; idx += NW * 64) {
+            float4 t = accs[idx];
+            for (int w = 1; w < NW; ++w) {
+                const float4 u = accs[(size_t)w * nb * d4 + idx];
+                t.x += u.x; t.y += u.y; t.z += u.z; t.w += u.w;
+            }
+            const int b = idx / d4, cc = idx - b * d4;
+            reinterpret_cast<float4*>(a.dact + (size_t)a.root_slot[r0 + b] * a.d)[cc] = t;
+        }
+        if (tid == 0) {
+            float l = 0.f;
+            for (int w = 0; w < NW; ++w) l += lossp[w];
+            a.loss_terms[i] = l;
+        }
+    }
+}
+
+template <int NCH, int NW>
+hipError_t launch_nw(const ScoreArgs& a, bool train, size_t lds, hipStream_t s) {
+    if (train) {
+        if (lds > 64 * 1024)
+            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(score_kernel<NCH, NW, true>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipLaunchKernelGGL((score_kernel<NCH, NW, true>), dim3(a.B), dim3(NW * 64), lds, s, a);
+    } else {
+        hipLaunchKernelGGL((score_kernel<NCH, NW, false>), dim3(a.B), dim3(NW * 64), lds, s, a);
+    }
+    return hipGetLastError();
+}
+
+template <int NCH>
+hipError_t launch_nch(const ScoreArgs& a, bool train, hipStream_t s) {
+    // enough wavefronts to cover the chip even for small batches
+    const int nw = a.B >= 2048 ? 4 : (a.B >= 1024 ? 8 : 16);
+    auto lds_for = [&](int w) {
+        return ((size_t)a.max_branch * a.d * (1 + (train ? w : 0)) + 16) * sizeof(float);
+    };
+    const size_t cap = 150 * 1024;
+    if (nw == 16 && lds_for(16) <= cap) return launch_nw<NCH, 16>(a, train, lds_for(16), s);
+    if (nw >= 8 && lds_for(8) <= cap) return launch_nw<NCH, 8>(a, train, lds_for(8), s);
+    if (lds_for(4) <= cap) return launch_nw<NCH, 4>(a, train, lds_for(4), s);
+    return hipErrorInvalidValue;   // too many union branches for this width
+}
+
+}  // namespace
+
+hipError_t launch_score(const ScoreArgs& a, bool train, hipStream_t s) {
+    if (a.B <= 0) return hipSuccess;
+    if (a.d <= 256) return launch_nch<1>(a, train, s);
+    if (a.d <= 512) return launch_nch<2>(a, train, s);
+    if (a.d <= 1024) return launch_nch<4>(a, train, s);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace ngdb

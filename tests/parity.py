@@ -1,0 +1,238 @@
+"""Helpers of the GPU parity tests: build a seeded workload, run the oracle and
+the HIP library on it, compare under the stated tolerances.
+
+Tolerances (fp32 path): loss |d|/|L| <= 1e-4; every tensor both
+max|d|/max|ref| <= 1e-4 and ||d||_2/||ref||_2 <= 1e-4.  Table gradients are
+additionally checked row by row at 1e-3 (rows whose largest entry is below
+1e-30 are compared absolutely), so that an error confined to the tiny rows of
+saturated negatives cannot hide behind the large rows.
+"""
+import numpy as np
+
+import workloads as wl
+from oracle import model as om
+from oracle import plan as oplan
+
+TOL = 1e-4
+
+
+class Case:
+    def __init__(self, N, R, d, h, B, K, gamma, mix=None, seed=0, T=None, alpha=2.1, trees=None, pos=None):
+        self.N, self.R, self.d, self.h, self.B, self.K, self.gamma = N, R, d, h, B, K, gamma
+        self.hp = dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, gamma=gamma)
+        if trees is not None:
+            self.qb = wl.batch_from_trees(trees, pos)
+        else:
+            kg = wl.make_kg(N, R, T or 10 * N, alpha, seed)
+            self.qb = wl.make_batch(kg, B, mix or {n: 1.0 for n in wl.configs.ALL14}, seed + 1)
+        self.B = self.qb.B
+        self.negs = wl.make_negatives(N, self.B, K, seed + 2)
+        self.params = wl.make_params(N, R, d, h, seed + 3)
+
+    @classmethod
+    def from_config(cls, idx, B=None, K=None, seed_offset=0):
+        c = wl.get_config(idx)
+        return cls(c.N, c.R, c.d, c.h, B or c.B, K or c.K, c.gamma, mix=c.mix, seed=c.seed + seed_offset,
+                   T=c.T, alpha=c.alpha)
+
+    def engine(self, num_streams=1):
+        from paper_2602_21597_amd import Engine
+        eng = Engine(self.N, self.R, self.d, self.h, self.gamma, num_streams=num_streams)
+        eng.bind_numpy(self.params)
+        return eng
+
+    def neg_dev(self, negs=None):
+        import torch
+        return torch.from_numpy(np.ascontiguousarray(self.negs if negs is None else negs, np.int32)).cuda()
+
+    def oracle_grads(self, negs=None):
+        M = om.Model(self.params, self.gamma)
+        return (M,) + om.batch_loss_and_grads(self.qb, self.negs if negs is None else negs, M)
+
+
+def rel_err(got, ref):
+    got = np.asarray(got, np.float64)
+    ref = np.asarray(ref, np.float64)
+    dn = np.abs(got - ref)
+    inf = dn.max() / max(np.abs(ref).max(), 1e-300) if ref.size else 0.0
+    l2 = np.sqrt((dn ** 2).sum()) / max(np.sqrt((ref ** 2).sum()), 1e-300) if ref.size else 0.0
+    return float(inf), float(l2)
+
+
+def assert_close(got, ref, name, tol=TOL):
+    assert np.asarray(got).shape == np.asarray(ref).shape, name
+    assert np.all(np.isfinite(got)), name
+    inf, l2 = rel_err(got, ref)
+    assert inf <= tol and l2 <= tol, "%s: max-norm %.3g, 2-norm %.3g (tol %.1g)" % (name, inf, l2, tol)
+
+
+def assert_zero_gradient(got_u2, ref_dense, tol=TOL):
+    """The output bias u2 of the attention MLP shifts the logits of all inputs of an
+    intersection alike, and the softmax over inputs ignores such a shift: its
+    gradient is zero in exact arithmetic and both sides hold rounding noise only.
+    It is therefore compared absolutely, on the scale of the projection's output
+    bias gradient."""
+    assert np.all(np.isfinite(got_u2))
+    assert np.abs(ref_dense["u2"]).max() <= 1e-9 * np.abs(ref_dense["b2"]).max()
+    assert np.abs(got_u2).max() <= tol * np.abs(ref_dense["b2"]).max(), "grad u2 not ~0"
+
+
+def assert_rows_close(got, ref, name, tol=1e-3):
+    got = np.asarray(got, np.float64)
+    ref = np.asarray(ref, np.float64)
+    scale = np.abs(ref).max(axis=1)
+    err = np.abs(got - ref).max(axis=1)
+    big = scale > 1e-30
+    worst = (err[big] / scale[big]).max() if big.any() else 0.0
+    assert worst <= tol, "%s: worst row-relative error %.3g" % (name, worst)
+    assert np.all(err[~big] <= 1e-30), name
+
+
+def check_forward_backward(case, eng=None, tol=TOL):
+    """Plan, index, forward values, loss and every gradient against the oracle."""
+    import torch
+    eng = eng or case.engine()
+    plan = eng.plan(case.qb)
+    ref_plan = oplan.build_plan(case.qb)
+    got_plan = plan.export()
+    for k in ref_plan:
+        assert np.array_equal(np.asarray(got_plan[k]), np.asarray(ref_plan[k])), "plan." + k
+
+    loss = eng.forward_backward(plan, case.neg_dev())
+    torch.cuda.synchronize()
+    g = eng.grads()
+    M, ref_loss, G, ref_scores = case.oracle_grads()
+
+    # index: bit exact
+    u, off, src = oplan.entity_index(ref_plan, case.qb.pos, case.negs)
+    assert np.array_equal(g["e_uniq"], u), "e_uniq"
+    assert np.array_equal(g["e_seg_off"], off), "e_seg_off"
+    assert np.array_equal(g["e_src"], src), "e_src"
+
+    # forward: branch embeddings at the root slots, pair scores
+    for q in range(case.B):
+        br = om.dnf(case.qb.tree(q))
+        slots = ref_plan["root_slot"][ref_plan["root_off"][q]:ref_plan["root_off"][q + 1]]
+        for b, s in zip(br, slots):
+            assert_close(g["act"][s], om.forward(b, M)[0], "root embedding q%d" % q, tol)
+    if case.B:
+        assert_close(g["pair_score"].reshape(case.B, case.K + 1), np.stack(ref_scores), "scores", tol)
+        got_loss = float(loss.cpu()[0])
+        assert abs(got_loss - ref_loss) <= tol * abs(ref_loss), "loss %r vs %r" % (got_loss, ref_loss)
+
+    # gradients
+    for name in G.dense:
+        if name == "u2":
+            assert_zero_gradient(g[name], G.dense, tol)
+        else:
+            assert_close(g[name], G.dense[name], "grad " + name, tol)
+    for tab, uniq, rows in (("E", g["e_uniq"], g["gE"]), ("R", got_plan["r_uniq"], g["gR"])):
+        assert sorted(G.rows[tab]) == list(uniq), tab + " touched rows"
+        if len(uniq):
+            ref_rows = np.stack([G.rows[tab][int(r)] for r in uniq])
+            assert_close(rows, ref_rows, "grad " + tab, tol)
+            assert_rows_close(rows, ref_rows, "grad rows " + tab)
+    plan.free()
+    return eng
+
+
+def _adam_f64(p, m, v, g, t, hp):
+    return om.adam_update(np.asarray(p, np.float64), np.asarray(m, np.float64), np.asarray(v, np.float64),
+                          np.asarray(g, np.float64), t, lr=hp["lr"], beta1=hp["beta1"], beta2=hp["beta2"],
+                          eps=hp["eps"])
+
+
+def _dense_grads_from_gpu(g, plan_export, shapes):
+    out = {n: g[n].astype(np.float64) for n in shapes if n not in ("E", "R")}
+    for tab, uniq, rows in (("E", g["e_uniq"], g["gE"]), ("R", plan_export["r_uniq"], g["gR"])):
+        full = np.zeros(shapes[tab], np.float64)
+        full[uniq] = rows
+        out[tab] = full
+    return out
+
+
+def check_train_steps(case, steps=3, num_streams=1, tol=TOL):
+    """Updates over a few steps with fresh negatives, two ways.
+
+    (A) The optimiser alone, every element: the library's update must equal textbook
+        Adam (oracle routine, fp64) applied to the library's own gradients of the
+        same step, which ngdb_forward_backward exposes.
+    (B) End to end against the oracle's step.  Adam maps a gradient g to about
+        lr*g/(|g|+eps): where |g| is comparable with eps the map amplifies rounding
+        noise of g without bound relative to the result, so elements whose reference
+        update moves by more than the tolerance when the reference gradient is
+        perturbed by 1e-6 of the largest gradient entry of the tensor (of the row, for
+        the tables: fp32 rounding level) are left out of (B) and counted; (A) still covers them.
+    An fp32 parameter near 0.1 stores an update of 1e-4 only to half an ulp of the
+    parameter, so one ulp of the parameter is added to both bounds.
+    """
+    import torch
+    eng = case.engine(num_streams)
+    plan = eng.plan(case.qb)
+    pexp = plan.export()
+    P = om.to_f64(case.params)
+    state = om.new_state(P)
+    shapes = {k: v.shape for k, v in P.items()}
+    for t in range(1, steps + 1):
+        negs = wl.make_negatives(case.N, case.B, case.K, 7000 + t)
+        nd = case.neg_dev(negs)
+        eng.forward_backward(plan, nd)
+        g_gpu = _dense_grads_from_gpu(eng.grads(), pexp, shapes)
+        touched_gpu = {"E": eng.grads()["e_uniq"], "R": pexp["r_uniq"]}
+        before_ref = {k: v.copy() for k, v in P.items()}
+        state_ref_before = {k: [x.copy() for x in v] for k, v in state.items()}
+        b_p, b_m, b_v = eng.params_numpy("p"), eng.params_numpy("m"), eng.params_numpy("v")
+        loss = eng.train_step(plan, nd)
+        torch.cuda.synchronize()
+        ref_loss, G = om.train_step(case.qb, negs, P, state, t, case.hp)
+        a_p, a_m, a_v = eng.params_numpy("p"), eng.params_numpy("m"), eng.params_numpy("v")
+        if case.B:
+            assert abs(float(loss.cpu()[0]) - ref_loss) <= tol * abs(ref_loss)
+        assert eng.step_count() == t
+        for name in P:
+            ulp = np.spacing(np.abs(b_p[name]).astype(np.float32)).astype(np.float64)
+            rows = slice(None)
+            if name in ("E", "R"):
+                touched = np.zeros(shapes[name][0], bool)
+                touched[touched_gpu[name]] = True
+                assert sorted(G.rows[name]) == list(np.flatnonzero(touched)), name + " touched rows"
+                for bb, aa in ((b_p, a_p), (b_m, a_m), (b_v, a_v)):
+                    assert np.array_equal(aa[name][~touched], bb[name][~touched]), name + " untouched rows moved"
+                rows = touched
+            # (A) optimiser alone, all elements
+            wp, wm, wv = _adam_f64(b_p[name][rows], b_m[name][rows], b_v[name][rows], g_gpu[name][rows], t, case.hp)
+            upd = wp - b_p[name][rows]
+            err = np.abs(a_p[name][rows] - wp)
+            assert np.all(err <= tol * max(np.abs(upd).max(), 1e-300) + ulp[rows]), \
+                "%s: Adam on own gradients, worst %.3g" % (name, err.max())
+            assert_close(a_m[name][rows], wm, "m(own g) " + name, tol)
+            assert_close(a_v[name][rows], wv, "v(own g) " + name, tol)
+            # (B) end to end
+            if name == "u2":     # zero gradient in exact arithmetic: direction is rounding noise
+                continue
+            gref = G.table_dense(name, shapes[name]) if name in ("E", "R") else G.dense[name]
+            m0, v0 = state_ref_before[name]
+            # tables: every row sums its own contributions, so its rounding noise scales with the row
+            delta = 1e-6 * (np.abs(gref).max(axis=1, keepdims=True) if name in ("E", "R") else np.abs(gref).max())
+            hi = _adam_f64(before_ref[name], m0, v0, gref + delta, t, case.hp)[0]
+            lo = _adam_f64(before_ref[name], m0, v0, gref - delta, t, case.hp)[0]
+            upd_ref = P[name] - before_ref[name]
+            scale = np.abs(upd_ref).max()
+            keep = (np.abs(hi - lo) / 2 <= tol * scale)
+            keep |= (gref == 0.0) & (g_gpu[name] == 0.0)     # dead units: identical input to Adam
+            if name in ("E", "R"):
+                keep &= touched[:, None]
+                n_all = int(touched.sum()) * shapes[name][1]
+            else:
+                n_all = keep.size
+            upd_gpu = a_p[name].astype(np.float64) - b_p[name].astype(np.float64)
+            err = np.abs(upd_gpu - upd_ref)
+            bound = tol * scale + ulp
+            assert np.all(err[keep] <= bound[keep]), \
+                "%s update: worst %.3g x bound" % (name, (err[keep] / bound[keep]).max())
+            assert keep.sum() >= 0.3 * n_all, "%s: only %d of %d elements are well conditioned" % (
+                name, keep.sum(), n_all)
+            assert_close(a_m[name], state[name][0], "m " + name, tol)
+            assert_close(a_v[name], state[name][1], "v " + name, 2 * tol)
+    plan.free()
+    return eng

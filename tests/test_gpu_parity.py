@@ -1,0 +1,129 @@
+"""HIP library against the CPU oracle on identical seeded inputs (needs an MI355X).
+
+Plan and index arrays bit-exact; fp32 loss, activations, gradients and updates
+within 1e-4 relative (definitions in tests/parity.py)."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import model as om
+from oracle import rank as orank
+from tests import parity as par
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print("[case] " + msg, flush=True)
+
+
+def test_tiny_config_forward_backward():
+    _say("config 0 (tiny), forward_backward")
+    par.check_forward_backward(par.Case.from_config(0))
+
+
+def test_tiny_config_unsaturated_margin():
+    # margin near the typical distance so that negatives carry real gradient
+    _say("config 0 shapes, gamma 3")
+    c = wl.get_config(0)
+    par.check_forward_backward(par.Case(c.N, c.R, c.d, c.h, c.B, c.K, 3.0, mix=c.mix, seed=5, T=c.T))
+
+
+def test_tiny_config_train_steps():
+    _say("config 0, 3 train steps")
+    par.check_train_steps(par.Case.from_config(0), steps=3)
+
+
+def test_all_templates_ragged_sizes():
+    # d=400/h=800 rows that are no multiple of any tile, several tiles per GEMM
+    _say("N=3000 d=400 h=800 B=150 K=19")
+    par.check_forward_backward(par.Case(3000, 30, 400, 800, 150, 19, 55.0, seed=11))
+
+
+def test_ragged_train_steps_multi_stream_matches_single_stream():
+    _say("N=2000 d=100 h=72 B=90 K=7, streams 1 vs 4")
+    case = par.Case(2000, 20, 100, 72, 90, 7, 12.0, seed=12)
+    e1 = par.check_train_steps(case, steps=2, num_streams=1)
+    e4 = par.check_train_steps(case, steps=2, num_streams=4)
+    p1, p4 = e1.params_numpy(), e4.params_numpy()
+    for k in p1:
+        assert np.array_equal(p1[k], p4[k]), k
+
+
+def test_general_shapes_wide_intersections_and_unions():
+    _say("hand-built queries: 4..8-way intersections, 3-way unions, negated anchors")
+    rng = np.random.default_rng(3)
+    N, R = 300, 9
+
+    def proj(depth=1):
+        t = ("e", int(rng.integers(N)))
+        for _ in range(depth):
+            t = ("p", int(rng.integers(R)), t)
+        return t
+
+    trees = []
+    for k in range(2, 9):
+        trees.append(("i",) + tuple(proj(1 + (j % 2)) for j in range(k)))
+    trees.append(("u", proj(), proj(2), proj(3)))
+    trees.append(("p", 1, ("p", 2, ("u", proj(), proj()))))
+    trees.append(("u", ("i", proj(), proj()), ("n", proj())))
+    trees.append(("n", ("e", 5)))
+    trees.append(("i", ("e", 6), proj()))
+    trees.append(("i", ("n", ("e", 6)), ("e", 7), proj(), ("n", proj(2))))
+    pos = [int(rng.integers(N)) for _ in trees]
+    par.check_forward_backward(par.Case(N, R, 64, 128, 0, 6, 8.0, seed=13, trees=trees, pos=pos))
+    par.check_train_steps(par.Case(N, R, 64, 128, 0, 6, 8.0, seed=13, trees=trees, pos=pos), steps=2)
+
+
+def test_degenerate_batches():
+    _say("single query; all negatives equal; anchor = positive = negative; empty batch")
+    one = par.Case(100, 5, 32, 64, 0, 5, 6.0, seed=14, trees=[("p", 1, ("e", 2))], pos=[3])
+    par.check_forward_backward(one)
+    case = par.Case(400, 8, 32, 64, 40, 9, 6.0, seed=15)
+    case.negs[:] = 17
+    case.negs[3, :] = int(case.qb.arg[0])          # an anchor entity as negative
+    case.qb.pos[3] = int(case.qb.arg[0])           # and as positive
+    par.check_forward_backward(case)
+    par.check_train_steps(case, steps=1)
+    empty = par.Case(100, 5, 32, 64, 0, 5, 6.0, seed=16, trees=[], pos=[])
+    eng = empty.engine()
+    plan = eng.plan(empty.qb)
+    before = eng.params_numpy()
+    loss = eng.train_step(plan, empty.neg_dev(np.zeros((0, 5), np.int32)))
+    after = eng.params_numpy()
+    assert float(loss.cpu()[0]) == 0.0
+    for k in before:
+        assert np.array_equal(before[k], after[k]), k   # zero gradient from zero state moves nothing
+
+
+def test_candidate_scores_against_oracle():
+    _say("ngdb_score candidate mode")
+    import torch
+    case = par.Case(500, 10, 48, 96, 60, 4, 10.0, seed=17)
+    eng = case.engine()
+    plan = eng.plan(case.qb)
+    cand = wl.make_negatives(500, case.B, 33, 99)
+    got = eng.score(plan, torch.from_numpy(cand).cuda()).cpu().numpy()
+    want = orank.score_candidates(case.qb, cand, om.Model(case.params, 10.0))
+    par.assert_close(got, want, "candidate scores")
+
+
+def test_fb15k237_shape_full_size():
+    # the benchmark workload itself, in the launch configuration bench.py times
+    _say("config 1 (B=512, K=128, d=400), forward_backward + 1 train step")
+    case = par.Case.from_config(1)
+    par.check_forward_backward(case)
+    par.check_train_steps(case, steps=1)
+
+
+def test_errors_are_reported_not_raised_as_faults():
+    from paper_2602_21597_amd import NgdbError, binding
+    case = par.Case.from_config(0)
+    eng = case.engine()
+    with pytest.raises(NgdbError) as e:
+        eng.plan(wl.batch_from_trees([("p", 99, ("e", 1))], [0]))
+    assert e.value.code == binding.ERR_RANGE
+    host_plan = binding.plan_host(case.N, case.R, case.qb)
+    with pytest.raises(NgdbError) as e:
+        eng.train_step(host_plan, case.neg_dev())
+    assert e.value.code == binding.ERR_ARG
