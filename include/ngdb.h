@@ -171,6 +171,8 @@ typedef struct ngdb_grad_view {
     const float* g_mlp[12];     /* W1 b1 W2 b2 V1 c1 V2 c2 U1 u1 U2 u2           */
     const float* g_Wp;          /* [d, d_sem] or NULL                            */
     const float* act;           /* [n_slots, d] operator outputs by slot         */
+    const float* dact;          /* [n_slots + n_anchor, d] dL/d(output) by slot, then dL/d(anchor row) */
+    int32_t n_grad_rows;        /* n_slots + n_anchor                            */
     const float* pair_score;    /* [n_pairs] s(q_i, cand), pair = i*(K+1)+c, c=0 positive */
     const float* loss_terms;    /* [n_queries] per-query loss before the 1/(2B)  */
 } ngdb_grad_view;
@@ -194,6 +196,9 @@ int ngdb_plan(ngdb_ctx_t* ctx, const ngdb_query_batch* batch, ngdb_plan_t** out)
 int ngdb_plan_host(int32_t n_entities, int32_t n_relations, const ngdb_query_batch* batch,
                    ngdb_plan_t** out);
 int ngdb_plan_export(const ngdb_plan_t* plan, ngdb_plan_view* out);
+/* May be called right after the last step that uses the plan has been enqueued:
+ * the plan's device buffer goes back to its context and is reused only after
+ * that step has finished.  Free every plan before destroying its context.     */
 void ngdb_plan_free(ngdb_plan_t* plan);
 
 /* One training step (Alg. 1 lines 5-21): forward over the plan's frontiers,
@@ -221,6 +226,46 @@ int ngdb_get_grads(ngdb_ctx_t* ctx, ngdb_grad_view* out);
 int ngdb_score(ngdb_ctx_t* ctx, const ngdb_plan_t* plan, const int32_t* d_cand, int32_t C,
                int32_t topk, float* d_scores, int32_t* d_topk_ids, float* d_topk_dist,
                void* stream);
+
+/* The contraction kernel of the grouped MLPs on its own (used by tests):
+ * C[M,N] = A[M,K] * B[K,N], all device fp32.  Element (m,k) of A is at
+ * A[m*lda+k] if a_kcontig else A[k*lda+m]; element (k,n) of B at B[n*ldb+k] if
+ * b_kcontig else B[k*ldb+n].  Then, in this order and each only if its pointer
+ * is not NULL (relu: flag): + bias[n]; relu; zero where mask[m*ldmask+n] <= 0;
+ * + addend[m*ldadd+n]; row m is stored at C row dst_row[m].  Leading dimensions
+ * and the contiguous extents must be multiples of 4.                            */
+int ngdb_debug_gemm(const float* A, const float* B, float* C, int32_t M, int32_t N, int32_t K,
+                    int32_t lda, int32_t ldb, int32_t ldc, int32_t a_kcontig, int32_t b_kcontig,
+                    const float* bias, int32_t relu, const float* mask, int32_t ldmask,
+                    const float* addend, int32_t ldadd, const int32_t* dst_row, void* stream);
+
+/* A plain device-to-device copy kernel (16 bytes per thread and step) of `bytes`
+ * bytes, a multiple of 16: the reference point for scaling hardware traffic
+ * counters and for the copy bandwidth of the machine.                           */
+int ngdb_debug_copy(void* d_dst, const void* d_src, size_t bytes, void* stream);
+
+/* Kernel timing with HIP events recorded on the stream each kernel is launched
+ * on.  Classes whose bit is set in class_mask are bracketed by an event pair at
+ * every launch (NGDB_TK_INDEX brackets the whole index build); everything else
+ * runs untouched.  ngdb_get_timing waits for the device, adds the elapsed times
+ * of all brackets recorded since the last call, and optionally clears the sums. */
+#define NGDB_TK_INDEX     0   /* gradient index: radix sort + segment heads        */
+#define NGDB_TK_GATHER    1   /* row gathers of operator inputs                    */
+#define NGDB_TK_GEMM_FWD  2   /* forward MLP contractions                          */
+#define NGDB_TK_INTER     3   /* intersection pooling, forward and backward        */
+#define NGDB_TK_SCORE     4   /* fused L1 score + loss + dL/ds                     */
+#define NGDB_TK_GEMM_BWD  5   /* data-gradient contractions                        */
+#define NGDB_TK_WGRAD     6   /* weight-gradient contractions and bias sums        */
+#define NGDB_TK_TABLE_E   7   /* entity table: segmented scatter-add + Adam        */
+#define NGDB_TK_TABLE_R   8   /* relation table: the same                          */
+#define NGDB_TK_ADAM      9   /* dense Adam on the MLP tensors                     */
+#define NGDB_TK_COUNT    10
+typedef struct ngdb_timing {
+    double ms[NGDB_TK_COUNT];         /* summed elapsed time per class             */
+    int64_t brackets[NGDB_TK_COUNT];  /* number of event pairs per class           */
+} ngdb_timing;
+int ngdb_set_timing(ngdb_ctx_t* ctx, uint32_t class_mask);
+int ngdb_get_timing(ngdb_ctx_t* ctx, ngdb_timing* out, int reset);
 
 /* Synchronous device-to-host copy of `bytes` bytes (waits for the device). */
 int ngdb_copy_to_host(void* h_dst, const void* d_src, size_t bytes);

@@ -61,7 +61,16 @@ class GradView(C.Structure):
                 ("n_slots", C.c_int32), ("n_pairs", C.c_int32),
                 ("e_uniq", C.c_void_p), ("e_seg_off", C.c_void_p), ("e_src", C.c_void_p),
                 ("gE", C.c_void_p), ("gR", C.c_void_p), ("g_mlp", C.c_void_p * 12), ("g_Wp", C.c_void_p),
-                ("act", C.c_void_p), ("pair_score", C.c_void_p), ("loss_terms", C.c_void_p)]
+                ("act", C.c_void_p), ("dact", C.c_void_p), ("n_grad_rows", C.c_int32),
+                ("pair_score", C.c_void_p), ("loss_terms", C.c_void_p)]
+
+
+TIMING_CLASSES = ("index", "gather", "gemm_fwd", "inter", "score", "gemm_bwd", "wgrad", "table_E", "table_R",
+                  "adam")
+
+
+class Timing(C.Structure):
+    _fields_ = [("ms", C.c_double * 10), ("brackets", C.c_int64 * 10)]
 
 
 def load_library(path=LIB_PATH):
@@ -81,6 +90,11 @@ def load_library(path=LIB_PATH):
         "ngdb_forward_backward": (C.c_int, [vp, vp, vp, i32, vp, vp]),
         "ngdb_get_grads": (C.c_int, [vp, C.POINTER(GradView)]),
         "ngdb_score": (C.c_int, [vp, vp, vp, i32, i32, vp, vp, vp, vp]),
+        "ngdb_debug_gemm": (C.c_int, [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, i32, vp, i32, vp, i32,
+                                      vp, vp]),
+        "ngdb_debug_copy": (C.c_int, [vp, vp, C.c_size_t, vp]),
+        "ngdb_set_timing": (C.c_int, [vp, C.c_uint32]),
+        "ngdb_get_timing": (C.c_int, [vp, C.POINTER(Timing), C.c_int]),
         "ngdb_copy_to_host": (C.c_int, [vp, vp, C.c_size_t]),
         "ngdb_step_count": (i64, [vp]),
         "ngdb_strerror": (C.c_char_p, [C.c_int]),
@@ -174,6 +188,29 @@ def copy_to_host(dev_ptr, shape, dtype):
     return out
 
 
+def debug_gemm(A, B, M, N, K, a_kcontig=True, b_kcontig=True, bias=None, relu=False, mask=None, addend=None,
+               dst_row=None, out_rows=None):
+    """Runs the library's contraction kernel on torch device tensors; returns C [out_rows or M, N]."""
+    import torch
+    Cm = torch.zeros((out_rows or M, N), dtype=torch.float32, device=A.device)
+    p = lambda t: t.data_ptr() if t is not None else None
+    ld = lambda t: int(t.stride(0)) if t is not None else 0
+    _check(lib().ngdb_debug_gemm(p(A), p(B), p(Cm), M, N, K, ld(A), ld(B), ld(Cm), int(a_kcontig), int(b_kcontig),
+                                 p(bias), int(relu), p(mask), ld(mask), p(addend), ld(addend), p(dst_row),
+                                 C.c_void_p(torch.cuda.current_stream().cuda_stream)), None)
+    torch.cuda.synchronize()
+    return Cm
+
+
+def debug_copy(dst, src):
+    """Plain copy kernel between two equally sized torch device tensors (bytes multiple of 16)."""
+    import torch
+    nbytes = src.numel() * src.element_size()
+    _check(lib().ngdb_debug_copy(dst.data_ptr(), src.data_ptr(), nbytes,
+                                 C.c_void_p(torch.cuda.current_stream().cuda_stream)), None)
+    return nbytes
+
+
 class Engine:
     """One libngdb context plus the device tensors bound to it."""
 
@@ -254,6 +291,7 @@ class Engine:
             e_seg_off=copy_to_host(gv.e_seg_off, (U + 1,), np.int32),
             e_src=copy_to_host(gv.e_src, (gv.n_e_contrib,), np.int32),
             act=copy_to_host(gv.act, (gv.n_slots, d), np.float32),
+            dact=copy_to_host(gv.dact, (gv.n_grad_rows, d), np.float32),
             pair_score=copy_to_host(gv.pair_score, (gv.n_pairs,), np.float32),
             loss_terms=copy_to_host(gv.loss_terms, (gv.n_pairs // (self._K + 1),), np.float32),
         )
@@ -273,6 +311,25 @@ class Engine:
         _check(lib().ngdb_score(self.ctx, plan.handle, cand.data_ptr(), int(cand.shape[1]), 0, out.data_ptr(),
                                 None, None, self._stream(stream)), self.ctx)
         return out
+
+    def set_timing(self, classes):
+        """classes: iterable of names from TIMING_CLASSES (empty = off)."""
+        mask = 0
+        for n in classes:
+            mask |= 1 << TIMING_CLASSES.index(n)
+        _check(lib().ngdb_set_timing(self.ctx, mask), self.ctx)
+
+    def get_timing(self, reset=True):
+        """{class: (total ms, number of brackets)} since the last reset (waits for the device)."""
+        t = Timing()
+        _check(lib().ngdb_get_timing(self.ctx, C.byref(t), 1 if reset else 0), self.ctx)
+        return {n: (t.ms[i], int(t.brackets[i])) for i, n in enumerate(TIMING_CLASSES)}
+
+    def n_touched_entities(self):
+        """Number of entity rows touched by the last step (waits for the device)."""
+        gv = GradView()
+        _check(lib().ngdb_get_grads(self.ctx, C.byref(gv)), self.ctx)
+        return int(gv.n_e_uniq)
 
     def step_count(self):
         return int(lib().ngdb_step_count(self.ctx))

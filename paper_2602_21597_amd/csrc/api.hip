@@ -36,8 +36,19 @@ inline int type_index(int op) { return op == NGDB_OP_PROJ ? T_PROJ : (op == NGDB
 
 }  // namespace
 
+// Device copy of a plan's arrays plus its pinned staging buffer; recycled through
+// the context so that planning allocates nothing in steady state.
+struct PlanBlob {
+    int32_t* dev = nullptr;
+    int32_t* pinned = nullptr;
+    size_t cap = 0;               // in int32 elements
+    hipEvent_t last_use = nullptr;  // recorded after every step that read the blob
+};
+
 struct ngdb_plan_s {
     HostPlan hp;
+    ngdb_ctx_t* owner = nullptr;
+    PlanBlob blob;
     int32_t* d_blob = nullptr;
     // device views into the blob
     const int32_t *d_in_ref = nullptr, *d_in_gslot = nullptr, *d_rel = nullptr, *d_root_off = nullptr,
@@ -61,9 +72,18 @@ struct ngdb_ctx_s {
     DevBuf act, dact, Z[3], H[3], dH[3], Att, dAtt, Dx;
     DevBuf score, coef, win, loss_terms;
     DevBuf keys_a, keys_b, vals_a, vals_b, hist, scan_tmp, uniq, seg_off, n_uniq;
+    DevBuf colsum_part; // 6 scratch areas of the bias-gradient column sums
     DevBuf gW;          // gradients of the 12 MLP tensors, packed
     DevBuf gE, gR;      // compact table gradients (ngdb_forward_backward only)
     size_t gw_off[13]{};
+    hipStream_t upload = nullptr;        // plan uploads, independent of the compute streams
+    std::vector<PlanBlob> blob_pool;
+    // kernel timing
+    uint32_t timing_mask = 0;
+    struct Bracket { int cls; hipEvent_t a, b; };
+    std::vector<Bracket> brackets;
+    std::vector<hipEvent_t> spare_events;
+    ngdb_timing timing{};
     // results of the last step
     bool have_grads = false;
     ngdb_grad_view gv{};
@@ -85,6 +105,32 @@ int fail(ngdb_ctx_t* c, int code, const std::string& msg) {
             return fail((c), e_ == hipErrorOutOfMemory ? NGDB_ERR_OOM : NGDB_ERR_HIP,          \
                         std::string(#expr) + ": " + hipGetErrorString(e_));                    \
     } while (0)
+
+hipEvent_t take_event(ngdb_ctx_t* c) {
+    if (!c->spare_events.empty()) {
+        hipEvent_t e = c->spare_events.back();
+        c->spare_events.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    return hipEventCreate(&e) == hipSuccess ? e : nullptr;
+}
+
+// Brackets one launch (sequence) with an event pair when its class is being timed.
+struct Timed {
+    ngdb_ctx_t* c;
+    hipStream_t s;
+    hipEvent_t b = nullptr;
+    Timed(ngdb_ctx_t* ctx, int cls, hipStream_t stream) : c(ctx), s(stream) {
+        if (!(c->timing_mask >> cls & 1u)) return;
+        hipEvent_t a = take_event(c);
+        b = take_event(c);
+        if (!a || !b) { b = nullptr; return; }
+        (void)hipEventRecord(a, s);
+        c->brackets.push_back({cls, a, b});
+    }
+    ~Timed() { if (b) (void)hipEventRecord(b, s); }
+};
 
 int ensure(ngdb_ctx_t* c, DevBuf& b, size_t bytes) {
     if (bytes <= b.cap) return NGDB_OK;
@@ -182,6 +228,7 @@ int size_workspace(ngdb_ctx_t* c, const ngdb_plan_t* pl, int K, bool want_table_
     ENS(c->hist, index_hist_elems(nk) * 4);
     ENS(c->scan_tmp, index_scan_tmp_elems(nk) * 4);
     ENS(c->n_uniq, 256);
+    ENS(c->colsum_part, 6 * (size_t)COLSUM_MAX_CHUNKS * std::max(d, h) * f);
     if (!c->gW.p) {
         size_t off = 0;
         for (int t = 0; t < 3; ++t) {
@@ -216,18 +263,20 @@ int enqueue_forward(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t stream) {
             const MlpRefs W = mlp_of(c->prm, sg.type);
             float* Z = ptr<float>(c->Z[sg.type]) + (size_t)sg.mlp_base * d;
             float* Hh = ptr<float>(c->H[sg.type]) + (size_t)sg.mlp_base * h;
-            HIPCHK(c, launch_gather(Z, pl->d_in_ref + sg.ref_off, sg.rel_off >= 0 ? pl->d_rel + sg.rel_off : nullptr,
-                                    sg.rows, d, ptr<float>(c->act), c->prm.E.p, c->prm.R.p, s));
             GemmArgs g1;
-            g1.A = Z; g1.lda = d; g1.B = W.Wa; g1.ldb = d; g1.C = Hh; g1.ldc = h;
+            // first layer reads its rows through the plan's references and leaves a copy in Z
+            g1.a_ref = pl->d_in_ref + sg.ref_off; g1.a_base0 = ptr<float>(c->act); g1.a_base1 = c->prm.E.p;
+            if (sg.rel_off >= 0) { g1.a_add_idx = pl->d_rel + sg.rel_off; g1.a_add = c->prm.R.p; }
+            g1.a_copy = Z; g1.lda = d; g1.B = W.Wa; g1.ldb = d; g1.C = Hh; g1.ldc = h;
             g1.M = sg.rows; g1.N = h; g1.K = d; g1.bias = W.ba; g1.relu = true;
-            HIPCHK(c, launch_gemm(g1, s));
+            { Timed tm(c, NGDB_TK_GEMM_FWD, s); HIPCHK(c, launch_gemm(g1, s)); }
             GemmArgs g2;
             g2.A = Hh; g2.lda = h; g2.B = W.Wb; g2.ldb = h; g2.M = sg.rows; g2.N = d; g2.K = h; g2.bias = W.bb;
             g2.ldc = d;
             if (sg.type == T_INTER) {
                 g2.C = ptr<float>(c->Att) + (size_t)sg.mlp_base * d;
-                HIPCHK(c, launch_gemm(g2, s));
+                { Timed tm(c, NGDB_TK_GEMM_FWD, s); HIPCHK(c, launch_gemm(g2, s)); }
+                Timed tm(c, NGDB_TK_INTER, s);
                 for (int g = sg.g_lo; g < sg.g_hi; ++g) {
                     const size_t mb = (size_t)pl->hp.g_mlp_base[g] * d;
                     HIPCHK(c, launch_inter_fwd(ptr<float>(c->Z[T_INTER]) + mb, ptr<float>(c->Att) + mb,
@@ -236,6 +285,7 @@ int enqueue_forward(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t stream) {
                 }
             } else {
                 g2.C = ptr<float>(c->act) + (size_t)sg.out_base * d;
+                Timed tm(c, NGDB_TK_GEMM_FWD, s);
                 HIPCHK(c, launch_gemm(g2, s));
             }
         }
@@ -259,6 +309,7 @@ int enqueue_backward(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t stream) {
             const float* dOut;
             const float* addend = nullptr;
             if (sg.type == T_INTER) {
+                Timed tm(c, NGDB_TK_INTER, s);
                 for (int g = sg.g_lo; g < sg.g_hi; ++g) {
                     const size_t mb = (size_t)hp.g_mlp_base[g] * d;
                     HIPCHK(c, launch_inter_bwd(ptr<float>(c->Z[T_INTER]) + mb, ptr<float>(c->Att) + mb,
@@ -275,12 +326,12 @@ int enqueue_backward(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t stream) {
             GemmArgs b2;   // dH = (dOut * Wb) masked by relu
             b2.A = dOut; b2.lda = d; b2.B = W.Wb; b2.ldb = h; b2.b_kcontig = false;
             b2.C = dHh; b2.ldc = h; b2.M = sg.rows; b2.N = h; b2.K = d; b2.mask = Hh; b2.ldmask = h;
-            HIPCHK(c, launch_gemm(b2, s));
+            { Timed tm(c, NGDB_TK_GEMM_BWD, s); HIPCHK(c, launch_gemm(b2, s)); }
             GemmArgs b1;   // dZ = dH * Wa, scattered to the gradient rows of the inputs
             b1.A = dHh; b1.lda = h; b1.B = W.Wa; b1.ldb = d; b1.b_kcontig = false;
             b1.C = dact; b1.ldc = d; b1.M = sg.rows; b1.N = d; b1.K = h;
             b1.addend = addend; b1.ldadd = d; b1.dst_row = pl->d_in_gslot + sg.ref_off;
-            HIPCHK(c, launch_gemm(b1, s));
+            { Timed tm(c, NGDB_TK_GEMM_BWD, s); HIPCHK(c, launch_gemm(b1, s)); }
         }
         HIPCHK(c, L.join());
     }
@@ -291,6 +342,7 @@ int enqueue_backward(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t stream) {
     HIPCHK(c, L.fork(3));
     for (int t = 0; t < 3; ++t) {
         hipStream_t s = L.lane(t);
+        Timed tm(c, NGDB_TK_WGRAD, s);
         const int gs = gslot_of(t);
         const int r = (int)rows[t];
         GemmArgs wa;   // dWa[h,d] = dH^T Z
@@ -298,13 +350,15 @@ int enqueue_backward(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t stream) {
         wa.B = ptr<float>(c->Z[t]); wa.ldb = d; wa.b_kcontig = false;
         wa.C = gW + c->gw_off[gs + 0]; wa.ldc = d; wa.M = h; wa.N = d; wa.K = r;
         HIPCHK(c, launch_gemm(wa, s));
-        HIPCHK(c, launch_colsum(ptr<float>(c->dH[t]), r, h, h, gW + c->gw_off[gs + 1], s));
+        float* part = ptr<float>(c->colsum_part) + (size_t)(2 * t) * COLSUM_MAX_CHUNKS * std::max(d, h);
+        HIPCHK(c, launch_colsum(ptr<float>(c->dH[t]), r, h, h, gW + c->gw_off[gs + 1], part, s));
         GemmArgs wb;   // dWb[d,h] = dY^T H
         wb.A = dY[t]; wb.lda = d; wb.a_kcontig = false;
         wb.B = ptr<float>(c->H[t]); wb.ldb = h; wb.b_kcontig = false;
         wb.C = gW + c->gw_off[gs + 2]; wb.ldc = h; wb.M = d; wb.N = h; wb.K = r;
         HIPCHK(c, launch_gemm(wb, s));
-        HIPCHK(c, launch_colsum(dY[t], r, d, d, gW + c->gw_off[gs + 3], s));
+        HIPCHK(c, launch_colsum(dY[t], r, d, d, gW + c->gw_off[gs + 3],
+                                part + (size_t)COLSUM_MAX_CHUNKS * std::max(d, h), s));
     }
     HIPCHK(c, L.join());
     return NGDB_OK;
@@ -329,8 +383,11 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
                     ptr<int32_t>(c->vals_b), ptr<int32_t>(c->hist),   ptr<int32_t>(c->scan_tmp),
                     ptr<int32_t>(c->uniq),   ptr<int32_t>(c->seg_off), ptr<int32_t>(c->n_uniq)};
     int32_t* e_src = nullptr;
-    HIPCHK(c, build_segment_index(pl->d_ekeys_head, hp.n_anchor + B, d_neg, (int64_t)B * K, c->cfg.n_entities, ib,
-                                  &e_src, stream));
+    {
+        Timed tm(c, NGDB_TK_INDEX, stream);
+        HIPCHK(c, build_segment_index(pl->d_ekeys_head, hp.n_anchor + B, d_neg, (int64_t)B * K, c->cfg.n_entities,
+                                      ib, &e_src, stream));
+    }
 
     // 2. forward frontiers
     rc = enqueue_forward(c, pl, stream);
@@ -343,6 +400,7 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
     sa.gamma = c->cfg.gamma; sa.score = ptr<float>(c->score); sa.coef = ptr<float>(c->coef);
     sa.win = ptr<int32_t>(c->win); sa.dact = ptr<float>(c->dact); sa.loss_terms = ptr<float>(c->loss_terms);
     {
+        Timed tm(c, NGDB_TK_SCORE, stream);
         hipError_t e = launch_score(sa, true, stream);
         if (e == hipErrorInvalidValue) return fail(c, NGDB_ERR_UNSUPPORTED, "embedding width / union branch count too large for the scoring kernel");
         HIPCHK(c, e);
@@ -371,8 +429,8 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
 
     Lanes L{c, stream};
     HIPCHK(c, L.fork(3));
-    HIPCHK(c, launch_table_update(te, ah, L.lane(0)));
-    HIPCHK(c, launch_table_update(tr, ah, L.lane(1)));
+    { Timed tm(c, NGDB_TK_TABLE_E, L.lane(0)); HIPCHK(c, launch_table_update(te, ah, L.lane(0))); }
+    { Timed tm(c, NGDB_TK_TABLE_R, L.lane(1)); HIPCHK(c, launch_table_update(tr, ah, L.lane(1))); }
     if (apply) {
         DenseAdamJob job{};
         const ngdb_tensor* ts[12] = {&c->prm.W1, &c->prm.b1, &c->prm.W2, &c->prm.b2, &c->prm.V1, &c->prm.c1,
@@ -385,10 +443,12 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
             job.n[i] = sz[i % 4];
         }
         job.count = 12;
+        Timed tm(c, NGDB_TK_ADAM, L.lane(2));
         HIPCHK(c, launch_dense_adam(job, ah, L.lane(2)));
     }
     HIPCHK(c, L.join());
 
+    HIPCHK(c, hipEventRecord(pl->blob.last_use, stream));
     if (apply) c->step = t;
     // describe the results
     ngdb_grad_view& gv = c->gv;
@@ -404,6 +464,8 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
     gv.gR = apply ? nullptr : ptr<float>(c->gR);
     for (int i = 0; i < 12; ++i) gv.g_mlp[i] = ptr<float>(c->gW) + c->gw_off[i];
     gv.act = ptr<float>(c->act);
+    gv.dact = ptr<float>(c->dact);
+    gv.n_grad_rows = hp.n_slots + hp.n_anchor;
     gv.pair_score = ptr<float>(c->score);
     gv.loss_terms = ptr<float>(c->loss_terms);
     c->have_grads = true;
@@ -431,6 +493,7 @@ int ngdb_create(const ngdb_config* cfg, ngdb_ctx_t** out) {
         ok = hipStreamCreateWithFlags(&c->side[i], hipStreamNonBlocking) == hipSuccess &&
              hipEventCreateWithFlags(&c->ev_join[i], hipEventDisableTiming) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipStreamCreateWithFlags(&c->upload, hipStreamNonBlocking) == hipSuccess;
     if (!ok) {
         ngdb_destroy(c);
         return NGDB_ERR_HIP;
@@ -445,13 +508,24 @@ void ngdb_destroy(ngdb_ctx_t* c) {
     DevBuf* all[] = {&c->act, &c->dact, &c->Z[0], &c->Z[1], &c->Z[2], &c->H[0], &c->H[1], &c->H[2], &c->dH[0],
                      &c->dH[1], &c->dH[2], &c->Att, &c->dAtt, &c->Dx, &c->score, &c->coef, &c->win,
                      &c->loss_terms, &c->keys_a, &c->keys_b, &c->vals_a, &c->vals_b, &c->hist, &c->scan_tmp,
-                     &c->uniq, &c->seg_off, &c->n_uniq, &c->gW, &c->gE, &c->gR};
+                     &c->uniq, &c->seg_off, &c->n_uniq, &c->gW, &c->gE, &c->gR, &c->colsum_part};
     for (DevBuf* b : all) release(*b);
     for (int i = 0; i < 4; ++i) {
         if (c->side[i]) (void)hipStreamDestroy(c->side[i]);
         if (c->ev_join[i]) (void)hipEventDestroy(c->ev_join[i]);
     }
     if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+    if (c->upload) (void)hipStreamDestroy(c->upload);
+    for (PlanBlob& b : c->blob_pool) {
+        if (b.dev) (void)hipFree(b.dev);
+        if (b.pinned) (void)hipHostFree(b.pinned);
+        if (b.last_use) (void)hipEventDestroy(b.last_use);
+    }
+    for (const ngdb_ctx_s::Bracket& b : c->brackets) {
+        (void)hipEventDestroy(b.a);
+        (void)hipEventDestroy(b.b);
+    }
+    for (hipEvent_t e : c->spare_events) (void)hipEventDestroy(e);
     delete c;
 }
 
@@ -542,15 +616,38 @@ int ngdb_plan(ngdb_ctx_t* c, const ngdb_query_batch* qb, ngdb_plan_t** out) {
                  o_rs = put(hp.root_slot), o_pos = put(hp.pos), o_ek = put(ekeys), o_ru = put(hp.r_uniq),
                  o_rso = put(hp.r_seg_off), o_rsrc = put(hp.r_src),
                  o_nru = put(std::vector<int32_t>{(int32_t)hp.r_uniq.size()});
-    if (hipMalloc((void**)&pl->d_blob, blob.size() * 4) != hipSuccess) {
+    // a recycled blob (its last reader has finished) or a new one
+    PlanBlob pb;
+    for (size_t i = 0; i < c->blob_pool.size(); ++i)
+        if (c->blob_pool[i].cap >= blob.size()) {
+            pb = c->blob_pool[i];
+            c->blob_pool.erase(c->blob_pool.begin() + i);
+            break;
+        }
+    if (!pb.dev) {
+        pb.cap = blob.size() + blob.size() / 2 + 1024;
+        if (hipMalloc((void**)&pb.dev, pb.cap * 4) != hipSuccess ||
+            hipHostMalloc((void**)&pb.pinned, pb.cap * 4, hipHostMallocDefault) != hipSuccess ||
+            hipEventCreateWithFlags(&pb.last_use, hipEventDisableTiming) != hipSuccess) {
+            if (pb.dev) (void)hipFree(pb.dev);
+            if (pb.pinned) (void)hipHostFree(pb.pinned);
+            delete pl;
+            return fail(c, NGDB_ERR_OOM, "allocation for the plan failed");
+        }
+    } else if (hipEventSynchronize(pb.last_use) != hipSuccess) {
         delete pl;
-        return fail(c, NGDB_ERR_OOM, "device allocation for the plan failed");
+        return fail(c, NGDB_ERR_HIP, "waiting for a recycled plan buffer failed");
     }
-    if (hipMemcpy(pl->d_blob, blob.data(), blob.size() * 4, hipMemcpyHostToDevice) != hipSuccess) {
-        (void)hipFree(pl->d_blob);
+    std::memcpy(pb.pinned, blob.data(), blob.size() * 4);
+    if (hipMemcpyAsync(pb.dev, pb.pinned, blob.size() * 4, hipMemcpyHostToDevice, c->upload) != hipSuccess ||
+        hipStreamSynchronize(c->upload) != hipSuccess) {
+        c->blob_pool.push_back(pb);
         delete pl;
         return fail(c, NGDB_ERR_HIP, "plan upload failed");
     }
+    pl->owner = c;
+    pl->blob = pb;
+    pl->d_blob = pb.dev;
     pl->d_in_ref = pl->d_blob + o_ref; pl->d_in_gslot = pl->d_blob + o_gs; pl->d_rel = pl->d_blob + o_rel;
     pl->d_root_off = pl->d_blob + o_ro; pl->d_root_slot = pl->d_blob + o_rs; pl->d_pos = pl->d_blob + o_pos;
     pl->d_ekeys_head = pl->d_blob + o_ek; pl->d_r_uniq = pl->d_blob + o_ru; pl->d_r_seg_off = pl->d_blob + o_rso;
@@ -578,7 +675,7 @@ int ngdb_plan_export(const ngdb_plan_t* pl, ngdb_plan_view* v) {
 
 void ngdb_plan_free(ngdb_plan_t* pl) {
     if (!pl) return;
-    if (pl->d_blob) (void)hipFree(pl->d_blob);   // waits for work that may still read it
+    if (pl->owner && pl->blob.dev) pl->owner->blob_pool.push_back(pl->blob);   // reused once last_use has passed
     delete pl;
 }
 
@@ -620,9 +717,54 @@ int ngdb_score(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_cand, int3
     sa.act = ptr<float>(c->act); sa.E = c->prm.E.p; sa.root_off = pl->d_root_off; sa.root_slot = pl->d_root_slot;
     sa.pos = nullptr; sa.cand = d_cand; sa.B = pl->hp.n_queries; sa.C = C; sa.d = c->cfg.d;
     sa.max_branch = std::max(1, pl->hp.max_branch); sa.gamma = c->cfg.gamma; sa.score = d_scores;
-    hipError_t e = launch_score(sa, false, s);
+    hipError_t e;
+    { Timed tm(c, NGDB_TK_SCORE, s); e = launch_score(sa, false, s); }
     if (e == hipErrorInvalidValue) return fail(c, NGDB_ERR_UNSUPPORTED, "embedding width / union branch count too large for the scoring kernel");
     HIPCHK(c, e);
+    HIPCHK(c, hipEventRecord(pl->blob.last_use, s));
+    return NGDB_OK;
+}
+
+int ngdb_debug_gemm(const float* A, const float* B, float* C, int32_t M, int32_t N, int32_t K, int32_t lda,
+                    int32_t ldb, int32_t ldc, int32_t a_kcontig, int32_t b_kcontig, const float* bias, int32_t relu,
+                    const float* mask, int32_t ldmask, const float* addend, int32_t ldadd, const int32_t* dst_row,
+                    void* stream) {
+    if (!A || !B || !C || M < 0 || N < 0 || K < 0) return NGDB_ERR_ARG;
+    GemmArgs g;
+    g.A = A; g.B = B; g.C = C; g.M = M; g.N = N; g.K = K; g.lda = lda; g.ldb = ldb; g.ldc = ldc;
+    g.a_kcontig = a_kcontig != 0; g.b_kcontig = b_kcontig != 0; g.bias = bias; g.relu = relu != 0;
+    g.mask = mask; g.ldmask = ldmask; g.addend = addend; g.ldadd = ldadd; g.dst_row = dst_row;
+    const hipError_t e = launch_gemm(g, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? NGDB_OK : (e == hipErrorInvalidValue ? NGDB_ERR_ARG : NGDB_ERR_HIP);
+}
+
+int ngdb_debug_copy(void* d_dst, const void* d_src, size_t bytes, void* stream) {
+    if (!d_dst || !d_src) return NGDB_ERR_ARG;
+    const hipError_t e = launch_copy(d_dst, d_src, bytes, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? NGDB_OK : (e == hipErrorInvalidValue ? NGDB_ERR_ARG : NGDB_ERR_HIP);
+}
+
+int ngdb_set_timing(ngdb_ctx_t* c, uint32_t class_mask) {
+    if (!c) return NGDB_ERR_ARG;
+    c->timing_mask = class_mask & ((1u << NGDB_TK_COUNT) - 1u);
+    return NGDB_OK;
+}
+
+int ngdb_get_timing(ngdb_ctx_t* c, ngdb_timing* out, int reset) {
+    if (!c || !out) return NGDB_ERR_ARG;
+    HIPCHK(c, hipDeviceSynchronize());
+    for (const ngdb_ctx_s::Bracket& b : c->brackets) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, b.a, b.b) == hipSuccess) {
+            c->timing.ms[b.cls] += ms;
+            c->timing.brackets[b.cls] += 1;
+        }
+        c->spare_events.push_back(b.a);
+        c->spare_events.push_back(b.b);
+    }
+    c->brackets.clear();
+    *out = c->timing;
+    if (reset) c->timing = ngdb_timing{};
     return NGDB_OK;
 }
 

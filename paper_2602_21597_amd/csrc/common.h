@@ -37,7 +37,17 @@ __device__ __forceinline__ float sigmoid_f(float x) {
 // if b_kcontig else B[k*ldb+n].  Epilogue, in this order: + bias[n]; relu;
 // * (mask[m*ldmask+n] > 0); + addend[m*ldadd+n]; row m goes to C row
 // dst_row[m] if dst_row else m.
+// Fused gather (k-contiguous A only): if a_ref is set, row m of A is
+// a_base0 + a_ref[m]*lda for a_ref[m] >= 0, else a_base1 + (-1-a_ref[m])*lda, plus
+// row a_add_idx[m] of a_add if a_add_idx is set; the assembled rows are also
+// written to a_copy (same leading dimension) if it is set.
 struct GemmArgs {
+    const int32_t* a_ref = nullptr;
+    const float* a_base0 = nullptr;
+    const float* a_base1 = nullptr;
+    const int32_t* a_add_idx = nullptr;
+    const float* a_add = nullptr;
+    float* a_copy = nullptr;
     const float* A = nullptr;
     const float* B = nullptr;
     float* C = nullptr;
@@ -63,9 +73,12 @@ hipError_t launch_inter_fwd(const float* X, const float* Att, float* out, int n,
 // dAtt[j*n+i] = w_j*(dy*x_j - sum_l w_l dy x_l),  Dx[j*n+i] = w_j*dy
 hipError_t launch_inter_bwd(const float* X, const float* Att, const float* dY, float* dAtt, float* Dx,
                             int n, int k, int d, hipStream_t s);
-// out[c] = sum_m X[m*ld + c], c < cols (fixed summation order)
-hipError_t launch_colsum(const float* X, int rows, int cols, int ld, float* out, hipStream_t s);
+// out[c] = sum_m X[m*ld + c], c < cols (fixed summation order); `partial` is scratch
+// of COLSUM_MAX_CHUNKS * cols floats
+constexpr int COLSUM_MAX_CHUNKS = 128;
+hipError_t launch_colsum(const float* X, int rows, int cols, int ld, float* out, float* partial, hipStream_t s);
 hipError_t launch_fill_zero(float* p, size_t n, hipStream_t s);
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 
 struct AdamHyper {
     float lr, beta1, beta2, eps;

@@ -1,9 +1,16 @@
 // fp32 MFMA GEMM for the grouped operator MLPs (forward, data-gradient and
-// weight-gradient contractions of Sec. 4.1's batched kernels).  One workgroup of
-// four wavefronts computes a BM x BN tile; every wavefront owns a (BM/2) x (BN/2)
-// sub-tile made of 32x32 MFMA blocks (v_mfma_f32_32x32x2_f32).  Operand tiles go
-// through LDS k-major, double buffered, so that each MFMA operand is one
-// conflict-free 4-byte LDS read per lane.
+// weight-gradient contractions of Sec. 4.1's batched kernels).
+//
+// The groups of one batch are small next to the chip (a few hundred to a few
+// thousand rows against 256 compute units), so a contraction is latency bound,
+// not throughput bound: what matters is the length of the dependent chain
+// "global load -> LDS -> MFMA" of one workgroup.  Therefore the k extent is
+// split over the wavefronts of a workgroup: every wavefront walks its own
+// k-tiles (tile w, w+NW, ...) through a private LDS staging area and
+// accumulates the whole BM x BN output tile with 32x32x2 MFMA blocks; the NW
+// partial tiles are then summed through LDS in a fixed order (deterministic) and
+// the epilogue is applied to the sum.  The A operand can be assembled on the fly
+// from row references (gather of operator inputs fused into the first layer).
 #include "common.h"
 
 namespace ngdb {
@@ -11,23 +18,107 @@ namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int BK = 16;    // k extent of one LDS tile
-constexpr int PAD = 4;    // keeps rows 16-byte aligned and spreads banks
+constexpr int BK = 16;    // k extent of one staged tile
+constexpr int PAD = 4;    // keeps LDS rows 16-byte aligned and spreads banks
 
-template <int BM, int BN, bool AK, bool BKC>
-__global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a) {
-    __shared__ __attribute__((aligned(16))) float As[2][BK][BM + PAD];
-    __shared__ __attribute__((aligned(16))) float Bs[2][BK][BN + PAD];
+template <int BM, int BN, int NW>
+struct Smem {
+    static constexpr int STAGE = NW * BK * (BM + PAD + BN + PAD);      // floats
+    static constexpr int NR = NW > 4 ? NW / 2 : NW;                    // partial tiles held in LDS at once
+    static constexpr int REDUCE = NR * BM * (BN + 1);
+    static constexpr int FLOATS = STAGE > REDUCE ? STAGE : REDUCE;
+};
 
+// Operand staging is written as force-inlined functions over register arrays of
+// compile-time size (no lambdas, no run-time indices) so that the tiles in
+// flight stay in VGPRs.
+// Loads never branch on the bounds: the address is clamped into the operand and
+// the value is zeroed afterwards, so every load is a plain global load.
+template <int BM, int LA, bool AK>
+__device__ __forceinline__ void load_a(const GemmArgs& a, int lane, int m0, int k0, bool first_n_tile,
+                                       const float* const (&arow)[LA], const float* const (&aadd)[LA],
+                                       const bool (&avalid)[LA], float4 (&ra)[LA]) {
+#pragma unroll
+    for (int i = 0; i < LA; ++i) {
+        const int idx = lane + i * 64;
+        if (AK) {
+            const int gk = k0 + (idx % (BK / 4)) * 4;
+            const bool ok = avalid[i] && gk < a.K;
+            const int gkc = min(gk, a.K - 4);
+            float4 v = *reinterpret_cast<const float4*>(arow[i] + gkc);
+            if (aadd[i]) {
+                const float4 w = *reinterpret_cast<const float4*>(aadd[i] + gkc);
+                v.x += w.x; v.y += w.y; v.z += w.z; v.w += w.w;
+            }
+            if (!ok) v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (ok && a.a_copy && first_n_tile)
+                *reinterpret_cast<float4*>(a.a_copy + (size_t)(m0 + idx / (BK / 4)) * a.lda + gk) = v;
+            ra[i] = v;
+        } else {
+            const int k = idx / (BM / 4), mq = idx % (BM / 4);
+            const int gk = k0 + k, gm = m0 + mq * 4;
+            const bool ok = gk < a.K && gm < a.M;
+            float4 v = *reinterpret_cast<const float4*>(a.A + (size_t)min(gk, a.K - 1) * a.lda + min(gm, a.M - 4));
+            if (!ok) v = make_float4(0.f, 0.f, 0.f, 0.f);
+            ra[i] = v;
+        }
+    }
+}
+
+template <int BN, int LB, bool BKC>
+__device__ __forceinline__ void load_b(const GemmArgs& a, int lane, int n0, int k0, float4 (&rb)[LB]) {
+#pragma unroll
+    for (int i = 0; i < LB; ++i) {
+        const int idx = lane + i * 64;
+        int gn, gk;
+        const float* p;
+        if (BKC) {
+            gn = n0 + idx / (BK / 4);
+            gk = k0 + (idx % (BK / 4)) * 4;
+            p = a.B + (size_t)min(gn, a.N - 1) * a.ldb + min(gk, a.K - 4);
+        } else {
+            gk = k0 + idx / (BN / 4);
+            gn = n0 + (idx % (BN / 4)) * 4;
+            p = a.B + (size_t)min(gk, a.K - 1) * a.ldb + min(gn, a.N - 4);
+        }
+        float4 v = *reinterpret_cast<const float4*>(p);
+        if (!(gn < a.N && gk < a.K)) v = make_float4(0.f, 0.f, 0.f, 0.f);
+        rb[i] = v;
+    }
+}
+
+// registers -> this wavefront's LDS tile [BK][LD]; KC: the registers hold 4 consecutive k of one row
+template <int BX, int LX, int LD, bool KC>
+__device__ __forceinline__ void stage(float* __restrict__ dst, int lane, const float4 (&r)[LX]) {
+#pragma unroll
+    for (int i = 0; i < LX; ++i) {
+        const int idx = lane + i * 64;
+        if (KC) {
+            const int m = idx / (BK / 4), kq = idx % (BK / 4);
+            dst[(kq * 4 + 0) * LD + m] = r[i].x;
+            dst[(kq * 4 + 1) * LD + m] = r[i].y;
+            dst[(kq * 4 + 2) * LD + m] = r[i].z;
+            dst[(kq * 4 + 3) * LD + m] = r[i].w;
+        } else {
+            const int k = idx / (BX / 4), mq = idx % (BX / 4);
+            *reinterpret_cast<float4*>(&dst[k * LD + mq * 4]) = r[i];
+        }
+    }
+}
+
+template <int BM, int BN, int NW, bool AK, bool BKC>
+__global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmArgs a) {
+    __shared__ __attribute__((aligned(16))) float smem[Smem<BM, BN, NW>::FLOATS];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int m0 = blockIdx.y * BM;
     const int n0 = blockIdx.x * BN;
-    constexpr int WM = BM / 2, WN = BN / 2;
-    constexpr int TM = WM / 32, TN = WN / 32;
-    const int wm0 = (wave >> 1) * WM;
-    const int wn0 = (wave & 1) * WN;
+    const bool first_n_tile = blockIdx.x == 0;
+    constexpr int TM = BM / 32, TN = BN / 32;
+    constexpr int LDA = BM + PAD, LDB = BN + PAD;
+    float* As = smem + wave * BK * (LDA + LDB);     // [BK][LDA] of this wavefront
+    float* Bs = As + BK * LDA;                      // [BK][LDB]
 
     floatx16 acc[TM][TN];
 #pragma unroll
@@ -37,135 +128,127 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    constexpr int LA = BM * BK / 4 / 256;
-    constexpr int LB = BN * BK / 4 / 256;
-    static_assert(LA >= 1 && LB >= 1, "tile too small for 256 threads");
+    constexpr int LA = BM * BK / 4 / 64;   // float4 per lane per tile
+    constexpr int LB = BN * BK / 4 / 64;
     float4 ra[LA], rb[LB];
-    const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
 
-    auto load_tiles = [&](int k0) {
+    // rows of A (k-contiguous layout), possibly assembled from references: resolved once
+    // per lane; rows past M point at row M-1 and are zeroed after the load
+    const float* arow[LA];
+    const float* aadd[LA];
+    bool avalid[LA];
 #pragma unroll
-        for (int i = 0; i < LA; ++i) {
-            const int idx = tid + i * 256;
-            if (AK) {
-                const int m = idx / (BK / 4), kq = idx % (BK / 4);
-                const int gm = m0 + m, gk = k0 + kq * 4;
-                ra[i] = (gm < a.M && gk < a.K)
-                            ? *reinterpret_cast<const float4*>(a.A + (size_t)gm * a.lda + gk) : zero4;
+    for (int i = 0; i < LA; ++i) {
+        arow[i] = a.A;
+        aadd[i] = nullptr;
+        avalid[i] = false;
+        if (AK) {
+            const int gm = m0 + (lane + i * 64) / (BK / 4);
+            avalid[i] = gm < a.M;
+            const int gmc = min(gm, a.M - 1);
+            if (a.a_ref) {
+                const int32_t r = a.a_ref[gmc];
+                arow[i] = r >= 0 ? a.a_base0 + (size_t)r * a.lda : a.a_base1 + (size_t)(-1 - r) * a.lda;
+                if (a.a_add_idx) aadd[i] = a.a_add + (size_t)a.a_add_idx[gmc] * a.lda;
             } else {
-                const int k = idx / (BM / 4), mq = idx % (BM / 4);
-                const int gk = k0 + k, gm = m0 + mq * 4;
-                ra[i] = (gk < a.K && gm < a.M)
-                            ? *reinterpret_cast<const float4*>(a.A + (size_t)gk * a.lda + gm) : zero4;
+                arow[i] = a.A + (size_t)gmc * a.lda;
             }
         }
-#pragma unroll
-        for (int i = 0; i < LB; ++i) {
-            const int idx = tid + i * 256;
-            if (BKC) {
-                const int n = idx / (BK / 4), kq = idx % (BK / 4);
-                const int gn = n0 + n, gk = k0 + kq * 4;
-                rb[i] = (gn < a.N && gk < a.K)
-                            ? *reinterpret_cast<const float4*>(a.B + (size_t)gn * a.ldb + gk) : zero4;
-            } else {
-                const int k = idx / (BN / 4), nq = idx % (BN / 4);
-                const int gk = k0 + k, gn = n0 + nq * 4;
-                rb[i] = (gk < a.K && gn < a.N)
-                            ? *reinterpret_cast<const float4*>(a.B + (size_t)gk * a.ldb + gn) : zero4;
-            }
-        }
-    };
-    auto store_tiles = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < LA; ++i) {
-            const int idx = tid + i * 256;
-            if (AK) {
-                const int m = idx / (BK / 4), kq = idx % (BK / 4);
-                As[buf][kq * 4 + 0][m] = ra[i].x;
-                As[buf][kq * 4 + 1][m] = ra[i].y;
-                As[buf][kq * 4 + 2][m] = ra[i].z;
-                As[buf][kq * 4 + 3][m] = ra[i].w;
-            } else {
-                const int k = idx / (BM / 4), mq = idx % (BM / 4);
-                *reinterpret_cast<float4*>(&As[buf][k][mq * 4]) = ra[i];
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < LB; ++i) {
-            const int idx = tid + i * 256;
-            if (BKC) {
-                const int n = idx / (BK / 4), kq = idx % (BK / 4);
-                Bs[buf][kq * 4 + 0][n] = rb[i].x;
-                Bs[buf][kq * 4 + 1][n] = rb[i].y;
-                Bs[buf][kq * 4 + 2][n] = rb[i].z;
-                Bs[buf][kq * 4 + 3][n] = rb[i].w;
-            } else {
-                const int k = idx / (BN / 4), nq = idx % (BN / 4);
-                *reinterpret_cast<float4*>(&Bs[buf][k][nq * 4]) = rb[i];
-            }
-        }
-    };
+    }
 
+    // every wavefront runs the same number of rounds (tiles past the end load zeros),
+    // so that the workgroup barriers below are reached by all
     const int nk = (a.K + BK - 1) / BK;
-    load_tiles(0);
-    store_tiles(0);
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < nk) load_tiles((kt + 1) * BK);
+    const int rounds = (nk + NW - 1) / NW;     // K == 0: no round, no load
+    if (rounds > 0) {
+        load_a<BM, LA, AK>(a, lane, m0, wave * BK, first_n_tile, arow, aadd, avalid, ra);
+        load_b<BN, LB, BKC>(a, lane, n0, wave * BK, rb);
+    }
+    for (int it = 0; it < rounds; ++it) {
+        stage<BM, LA, LDA, AK>(As, lane, ra);
+        stage<BN, LB, LDB, BKC>(Bs, lane, rb);
+        __syncthreads();
+        if (it + 1 < rounds) {
+            const int k0 = ((it + 1) * NW + wave) * BK;
+            load_a<BM, LA, AK>(a, lane, m0, k0, first_n_tile, arow, aadd, avalid, ra);
+            load_b<BN, LB, BKC>(a, lane, n0, k0, rb);
+        }
 #pragma unroll
         for (int kk = 0; kk < BK / 2; ++kk) {
             const int krow = kk * 2 + (lane >> 5);
             float av[TM], bv[TN];
 #pragma unroll
-            for (int i = 0; i < TM; ++i) av[i] = As[buf][krow][wm0 + i * 32 + (lane & 31)];
+            for (int i = 0; i < TM; ++i) av[i] = As[krow * LDA + i * 32 + (lane & 31)];
 #pragma unroll
-            for (int j = 0; j < TN; ++j) bv[j] = Bs[buf][krow][wn0 + j * 32 + (lane & 31)];
+            for (int j = 0; j < TN; ++j) bv[j] = Bs[krow * LDB + j * 32 + (lane & 31)];
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
         }
-        if (kt + 1 < nk) store_tiles(buf ^ 1);
         __syncthreads();
     }
 
-    // accumulator layout of the 32x32 block: lane owns column (lane & 31) and the
-    // rows 8*(r/4) + 4*(lane/32) + r%4, r = 0..15
+    // partial tiles -> LDS.  Accumulator layout of a 32x32 block: lane owns column
+    // (lane & 31) and rows 8*(r/4) + 4*(lane/32) + r%4, r = 0..15.
+    constexpr int NR = Smem<BM, BN, NW>::NR;
+    float* red = smem + (wave % NR) * BM * (BN + 1);
+#define NGDB_ACC_TO_LDS()                                                                   \
+    _Pragma("unroll") for (int i = 0; i < TM; ++i)                                         \
+    _Pragma("unroll") for (int j = 0; j < TN; ++j)                                         \
+    _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                       \
+        const int row = i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);                  \
+        red[row * (BN + 1) + j * 32 + (lane & 31)] = acc[i][j][r];                          \
+    }
+    if (NW > NR) {   // fold the upper half of the wavefronts into the lower half first
+        if (wave >= NR) { NGDB_ACC_TO_LDS() }
+        __syncthreads();
+        if (wave < NR) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+            for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int col = n0 + wn0 + j * 32 + (lane & 31);
-            if (col >= a.N) continue;
-            const float bias = a.bias ? a.bias[col] : 0.f;
+                for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = m0 + wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-                if (row >= a.M) continue;
-                float v = acc[i][j][r] + bias;
-                if (a.relu) v = fmaxf(v, 0.f);
-                if (a.mask) v = a.mask[(size_t)row * a.ldmask + col] > 0.f ? v : 0.f;
-                if (a.addend) v += a.addend[(size_t)row * a.ldadd + col];
-                const int orow = a.dst_row ? a.dst_row[row] : row;
-                a.C[(size_t)orow * a.ldc + col] = v;
-            }
+                    for (int r = 0; r < 16; ++r) {
+                        const int row = i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+                        acc[i][j][r] += red[row * (BN + 1) + j * 32 + (lane & 31)];
+                    }
         }
+        __syncthreads();
+    }
+    if (wave < NR) { NGDB_ACC_TO_LDS() }
+#undef NGDB_ACC_TO_LDS
+    __syncthreads();
+
+    for (int e = tid; e < BM * BN; e += NW * 64) {
+        const int lr = e / BN, lc = e - lr * BN;
+        const int row = m0 + lr, col = n0 + lc;
+        if (row >= a.M || col >= a.N) continue;
+        float v = smem[lr * (BN + 1) + lc];
+#pragma unroll
+        for (int w = 1; w < NR; ++w) v += smem[w * BM * (BN + 1) + lr * (BN + 1) + lc];
+        if (a.bias) v += a.bias[col];
+        if (a.relu) v = fmaxf(v, 0.f);
+        if (a.mask) v = a.mask[(size_t)row * a.ldmask + col] > 0.f ? v : 0.f;
+        if (a.addend) v += a.addend[(size_t)row * a.ldadd + col];
+        const int orow = a.dst_row ? a.dst_row[row] : row;
+        a.C[(size_t)orow * a.ldc + col] = v;
+    }
 }
 
-template <int BM, int BN>
+template <int BM, int BN, int NW>
 hipError_t dispatch_layout(const GemmArgs& a, hipStream_t s) {
     dim3 grid((a.N + BN - 1) / BN, (a.M + BM - 1) / BM);
-    dim3 block(256);
+    dim3 block(NW * 64);
     if (a.a_kcontig && a.b_kcontig)
-        hipLaunchKernelGGL((gemm_kernel<BM, BN, true, true>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((gemm_kernel<BM, BN, NW, true, true>), grid, block, 0, s, a);
     else if (a.a_kcontig && !a.b_kcontig)
-        hipLaunchKernelGGL((gemm_kernel<BM, BN, true, false>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((gemm_kernel<BM, BN, NW, true, false>), grid, block, 0, s, a);
     else if (!a.a_kcontig && !a.b_kcontig)
-        hipLaunchKernelGGL((gemm_kernel<BM, BN, false, false>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((gemm_kernel<BM, BN, NW, false, false>), grid, block, 0, s, a);
     else
-        hipLaunchKernelGGL((gemm_kernel<BM, BN, false, true>), grid, block, 0, s, a);
+        return hipErrorInvalidValue;
     return hipGetLastError();
 }
 
@@ -177,10 +260,11 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
     if ((a.lda & 3) || (a.ldb & 3)) return hipErrorInvalidValue;
     if ((a.a_kcontig ? a.K : a.M) & 3) return hipErrorInvalidValue;
     if ((a.b_kcontig ? a.K : a.N) & 3) return hipErrorInvalidValue;
-    // larger row tile once there are enough tiles to cover the 256 compute units
-    const long tiles128 = (long)((a.M + 127) / 128) * ((a.N + 63) / 64);
-    if (tiles128 >= 512) return dispatch_layout<128, 64>(a, s);
-    return dispatch_layout<64, 64>(a, s);
+    if (a.a_ref && !a.a_kcontig) return hipErrorInvalidValue;
+    const long blocks_small = (long)((a.M + 31) / 32) * ((a.N + 63) / 64);
+    if (blocks_small >= 2048) return dispatch_layout<64, 64, 4>(a, s);
+    if (a.K >= 512) return dispatch_layout<32, 64, 8>(a, s);
+    return dispatch_layout<32, 64, 4>(a, s);
 }
 
 }  // namespace ngdb

@@ -69,24 +69,40 @@ __global__ __launch_bounds__(256) void inter_kernel(const float* __restrict__ X,
     }
 }
 
-// column sums in a fixed order: thread per column, rows split over blockDim.y and
-// combined through LDS
-__global__ __launch_bounds__(256) void colsum_kernel(const float* __restrict__ X, int rows, int cols, int ld,
-                                                     float* __restrict__ out) {
-    __shared__ float part[4][64];
+// column sums in a fixed order, two steps: partial sums over chunks of rows (one
+// workgroup per 64 columns x chunk), then the chunks are added up per column
+__global__ __launch_bounds__(256) void colsum_part_kernel(const float* __restrict__ X, int rows, int cols, int ld,
+                                                          int chunk_rows, float* __restrict__ part) {
+    __shared__ float red[4][64];
     const int c = blockIdx.x * 64 + threadIdx.x;
+    const int lo = blockIdx.y * chunk_rows, hi = min(rows, lo + chunk_rows);
     float s = 0.f;
     if (c < cols)
-        for (int m = threadIdx.y; m < rows; m += 4) s += X[(size_t)m * ld + c];
-    part[threadIdx.y][threadIdx.x] = s;
+        for (int m = lo + threadIdx.y; m < hi; m += 4) s += X[(size_t)m * ld + c];
+    red[threadIdx.y][threadIdx.x] = s;
     __syncthreads();
     if (threadIdx.y == 0 && c < cols)
-        out[c] = (part[0][threadIdx.x] + part[1][threadIdx.x]) + (part[2][threadIdx.x] + part[3][threadIdx.x]);
+        part[(size_t)blockIdx.y * cols + c] =
+            (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+}
+
+__global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restrict__ part, int chunks, int cols,
+                                                           float* __restrict__ out) {
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= cols) return;
+    float s = 0.f;
+    for (int k = 0; k < chunks; ++k) s += part[(size_t)k * cols + c];
+    out[c] = s;
 }
 
 __global__ __launch_bounds__(256) void fill_zero_kernel(float* p, size_t n) {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
         p[i] = 0.f;
+}
+
+__global__ __launch_bounds__(256) void copy_kernel(float4* __restrict__ dst, const float4* __restrict__ src, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+        dst[i] = src[i];
 }
 
 __global__ __launch_bounds__(256) void dense_adam_kernel(const DenseAdamJob job, const AdamHyper hp) {
@@ -143,9 +159,14 @@ hipError_t launch_inter_bwd(const float* X, const float* Att, const float* dY, f
     return hipGetLastError();
 }
 
-hipError_t launch_colsum(const float* X, int rows, int cols, int ld, float* out, hipStream_t s) {
+hipError_t launch_colsum(const float* X, int rows, int cols, int ld, float* out, float* partial, hipStream_t s) {
     if (cols <= 0) return hipSuccess;
-    hipLaunchKernelGGL(colsum_kernel, dim3((cols + 63) / 64), dim3(64, 4), 0, s, X, rows, cols, ld, out);
+    const int chunk_rows = std::max(32, (rows + COLSUM_MAX_CHUNKS - 1) / COLSUM_MAX_CHUNKS);
+    const int chunks = std::max(1, (rows + chunk_rows - 1) / chunk_rows);
+    hipLaunchKernelGGL(colsum_part_kernel, dim3((cols + 63) / 64, chunks), dim3(64, 4), 0, s, X, rows, cols, ld,
+                       chunk_rows, partial);
+    hipLaunchKernelGGL(colsum_final_kernel, dim3((cols + 255) / 256), dim3(256), 0, s, (const float*)partial, chunks,
+                       cols, out);
     return hipGetLastError();
 }
 
@@ -153,6 +174,16 @@ hipError_t launch_fill_zero(float* p, size_t n, hipStream_t s) {
     if (n == 0) return hipSuccess;
     const unsigned blocks = (unsigned)std::min<size_t>((n + 255) / 256, 4096);
     hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, s, p, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s) {
+    if (bytes == 0) return hipSuccess;
+    if (bytes & 15) return hipErrorInvalidValue;
+    const size_t n = bytes / 16;
+    const unsigned blocks = (unsigned)std::min<size_t>((n + 255) / 256, 256 * 32);
+    hipLaunchKernelGGL(copy_kernel, dim3(blocks), dim3(256), 0, s, static_cast<float4*>(dst),
+                       static_cast<const float4*>(src), n);
     return hipGetLastError();
 }
 

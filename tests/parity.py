@@ -14,26 +14,43 @@ from oracle import model as om
 from oracle import plan as oplan
 
 TOL = 1e-4
+# Distance the seeded inputs keep from the kinks of the model (ReLU at 0, |.| at 0,
+# ties of the min over union branches): there the result is decided by the last
+# bits of an fp32 sum, two correct implementations may differ, and the paper's
+# method says nothing about which side to take.  fp32 rounding moves a
+# pre-activation or a coordinate difference by about 1e-7 on these workloads.
+TAU_PRE, TAU_ABS, TAU_TIE = 1e-6, 5e-7, 1e-4
 
 
 class Case:
     def __init__(self, N, R, d, h, B, K, gamma, mix=None, seed=0, T=None, alpha=2.1, trees=None, pos=None):
         self.N, self.R, self.d, self.h, self.B, self.K, self.gamma = N, R, d, h, B, K, gamma
         self.hp = dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, gamma=gamma)
+        self.params = wl.make_params(N, R, d, h, seed + 3)
         if trees is not None:
-            self.qb = wl.batch_from_trees(trees, pos)
+            qb = wl.batch_from_trees(trees, pos)
+            want = qb.B
         else:
             kg = wl.make_kg(N, R, T or 10 * N, alpha, seed)
-            self.qb = wl.make_batch(kg, B, mix or {n: 1.0 for n in wl.configs.ALL14}, seed + 1)
+            want = B
+            qb = wl.make_batch(kg, B + B // 4 + 8, mix or {n: 1.0 for n in wl.configs.ALL14}, seed + 1)
+        negs = wl.make_negatives(N, qb.B, K, seed + 2)
+        self.qb, self.negs, self.n_redrawn = keep_clear_of_kinks(qb, negs, self.params, gamma, N, want, seed + 4,
+                                                                 strict=trees is None)
         self.B = self.qb.B
-        self.negs = wl.make_negatives(N, self.B, K, seed + 2)
-        self.params = wl.make_params(N, R, d, h, seed + 3)
 
     @classmethod
     def from_config(cls, idx, B=None, K=None, seed_offset=0):
         c = wl.get_config(idx)
         return cls(c.N, c.R, c.d, c.h, B or c.B, K or c.K, c.gamma, mix=c.mix, seed=c.seed + seed_offset,
                    T=c.T, alpha=c.alpha)
+
+    def fresh_negs(self, seed):
+        """Another [B, K] draw of negatives, kept clear of the |.| kinks like the first."""
+        negs = wl.make_negatives(self.N, self.B, self.K, seed)
+        _, negs, _ = keep_clear_of_kinks(self.qb, negs, self.params, self.gamma, self.N, self.B, seed + 1,
+                                         strict=False, queries_are_clean=True)
+        return negs
 
     def engine(self, num_streams=1):
         from paper_2602_21597_amd import Engine
@@ -48,6 +65,42 @@ class Case:
     def oracle_grads(self, negs=None):
         M = om.Model(self.params, self.gamma)
         return (M,) + om.batch_loss_and_grads(self.qb, self.negs if negs is None else negs, M)
+
+
+def keep_clear_of_kinks(qb, negs, params, gamma, N, want, seed, strict=True, queries_are_clean=False):
+    """First `want` queries of qb that stay clear of every kink, with negatives
+    that sit on an |.| kink redrawn.  Uses the oracle's forward pass only."""
+    M = om.Model(params, gamma)
+    rng = np.random.default_rng(seed)
+    negs = negs.copy()
+    keep, redrawn = [], 0
+    for i in range(qb.B):
+        if len(keep) == want:
+            break
+        fw = [om.forward(b, M) for b in om.dnf(qb.tree(i))]
+        Y = np.stack([y for y, _ in fw])
+        ok = min(om.min_abs_preactivation(t) for _, t in fw) >= TAU_PRE
+
+        def clear(e):
+            dist = np.abs(Y - M.entity(e)[None]).sum(axis=1)
+            w = int(np.argmin(dist))
+            tie = len(dist) > 1 and np.sort(dist)[1] - dist[w] < TAU_TIE
+            return (not tie) and np.abs(Y[w] - M.entity(e)).min() >= TAU_ABS
+
+        ok = queries_are_clean or (ok and clear(int(qb.pos[i])))
+        if ok:
+            for j in range(negs.shape[1]):
+                tries = 0
+                while not clear(int(negs[i, j])):
+                    negs[i, j] = rng.integers(0, N)
+                    redrawn += 1
+                    tries += 1
+                    assert tries < 100
+            keep.append(i)
+        elif not strict:
+            raise AssertionError("hand-built query %d sits on a kink; change the test's constants" % i)
+    assert len(keep) == want, "not enough kink-free queries: %d of %d" % (len(keep), want)
+    return qb.select(keep), negs[keep], redrawn
 
 
 def rel_err(got, ref):
@@ -174,7 +227,7 @@ def check_train_steps(case, steps=3, num_streams=1, tol=TOL):
     state = om.new_state(P)
     shapes = {k: v.shape for k, v in P.items()}
     for t in range(1, steps + 1):
-        negs = wl.make_negatives(case.N, case.B, case.K, 7000 + t)
+        negs = case.fresh_negs(7000 + t)
         nd = case.neg_dev(negs)
         eng.forward_backward(plan, nd)
         g_gpu = _dense_grads_from_gpu(eng.grads(), pexp, shapes)

@@ -1,0 +1,51 @@
+"""Single kernels of the library against numpy (needs an MI355X)."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+
+def _gemm_case(M, N, K, a_k, b_k, seed, epilogue):
+    import torch
+    from paper_2602_21597_amd import binding
+    rng = np.random.default_rng(seed)
+    A = rng.standard_normal((M, K)).astype(np.float32)
+    B = rng.standard_normal((K, N)).astype(np.float32)
+    want = A.astype(np.float64) @ B.astype(np.float64)
+    At = torch.from_numpy(np.ascontiguousarray(A if a_k else A.T)).cuda()      # [M,K] or [K,M]
+    Bt = torch.from_numpy(np.ascontiguousarray(B.T if b_k else B)).cuda()      # [N,K] or [K,N]
+    kw = {}
+    out_rows = None
+    if epilogue:
+        bias = rng.standard_normal(N).astype(np.float32)
+        mask = rng.standard_normal((M, N)).astype(np.float32)
+        addend = rng.standard_normal((M, N)).astype(np.float32)
+        perm = rng.permutation(M + 5)[:M].astype(np.int32)
+        want = np.maximum(want + bias, 0.0)
+        want = np.where(mask > 0, want, 0.0) + addend
+        full = np.zeros((M + 5, N))
+        full[perm] = want
+        want = full
+        out_rows = M + 5
+        kw = dict(bias=torch.from_numpy(bias).cuda(), relu=True, mask=torch.from_numpy(mask).cuda(),
+                  addend=torch.from_numpy(addend).cuda(), dst_row=torch.from_numpy(perm).cuda())
+    got = binding.debug_gemm(At, Bt, M, N, K, a_kcontig=a_k, b_kcontig=b_k, out_rows=out_rows, **kw).cpu().numpy()
+    err = np.abs(got - want).max() / np.abs(want).max()
+    assert err < 2e-6 * max(1.0, np.sqrt(K) / 8), (M, N, K, a_k, b_k, epilogue, err)
+
+
+@pytest.mark.parametrize("layout", [(True, True), (True, False), (False, False)])
+def test_contraction_kernel_all_layouts_and_tile_paths(layout):
+    a_k, b_k = layout
+    shapes = [(1, 64, 32), (37, 800, 400), (290, 800, 400), (392, 400, 800), (987, 800, 400),
+              (64, 32, 64), (33, 36, 20), (5000, 800, 400), (130, 400, 1352)]
+    for i, (M, N, K) in enumerate(shapes):
+        if not a_k:
+            M = (M + 3) // 4 * 4        # the m-contiguous A layout needs M % 4 == 0
+        if not b_k:
+            N = (N + 3) // 4 * 4
+        if a_k or b_k:
+            K = (K + 3) // 4 * 4
+        print("[case] gemm", M, N, K, layout, flush=True)
+        _gemm_case(M, N, K, a_k, b_k, seed=i, epilogue=False)
+        _gemm_case(M, N, K, a_k, b_k, seed=100 + i, epilogue=True)
