@@ -66,6 +66,7 @@ struct ngdb_ctx_s {
     std::string err;
     hipStream_t side[4]{};
     hipEvent_t ev_fork = nullptr;
+    hipEvent_t ev_index = nullptr;
     hipEvent_t ev_join[4]{};
     int n_side = 0;
     // workspace
@@ -250,61 +251,56 @@ int size_workspace(ngdb_ctx_t* c, const ngdb_plan_t* pl, int K, bool want_table_
     return NGDB_OK;
 }
 
-// forward over the plan's frontiers; results in c->act
-int enqueue_forward(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t stream) {
+// forward over the plan's frontiers; results in c->act.  The type segments of one
+// depth are independent: they share one grouped launch per MLP layer.
+int enqueue_forward(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t s) {
     const int d = c->cfg.d, h = c->cfg.h;
-    Lanes L{c, stream};
     for (int l = 1; l <= pl->hp.n_levels; ++l) {
         const std::vector<Segment>& segs = pl->levels[l];
-        HIPCHK(c, L.fork((int)segs.size()));
-        for (size_t si = 0; si < segs.size(); ++si) {
-            const Segment& sg = segs[si];
-            hipStream_t s = L.lane((int)si);
+        GemmArgs g1[3], g2[3];
+        int n = 0;
+        for (const Segment& sg : segs) {
             const MlpRefs W = mlp_of(c->prm, sg.type);
             float* Z = ptr<float>(c->Z[sg.type]) + (size_t)sg.mlp_base * d;
             float* Hh = ptr<float>(c->H[sg.type]) + (size_t)sg.mlp_base * h;
-            GemmArgs g1;
+            GemmArgs& a = g1[n];
             // first layer reads its rows through the plan's references and leaves a copy in Z
-            g1.a_ref = pl->d_in_ref + sg.ref_off; g1.a_base0 = ptr<float>(c->act); g1.a_base1 = c->prm.E.p;
-            if (sg.rel_off >= 0) { g1.a_add_idx = pl->d_rel + sg.rel_off; g1.a_add = c->prm.R.p; }
-            g1.a_copy = Z; g1.lda = d; g1.B = W.Wa; g1.ldb = d; g1.C = Hh; g1.ldc = h;
-            g1.M = sg.rows; g1.N = h; g1.K = d; g1.bias = W.ba; g1.relu = true;
-            { Timed tm(c, NGDB_TK_GEMM_FWD, s); HIPCHK(c, launch_gemm(g1, s)); }
-            GemmArgs g2;
-            g2.A = Hh; g2.lda = h; g2.B = W.Wb; g2.ldb = h; g2.M = sg.rows; g2.N = d; g2.K = h; g2.bias = W.bb;
-            g2.ldc = d;
-            if (sg.type == T_INTER) {
-                g2.C = ptr<float>(c->Att) + (size_t)sg.mlp_base * d;
-                { Timed tm(c, NGDB_TK_GEMM_FWD, s); HIPCHK(c, launch_gemm(g2, s)); }
-                Timed tm(c, NGDB_TK_INTER, s);
-                for (int g = sg.g_lo; g < sg.g_hi; ++g) {
-                    const size_t mb = (size_t)pl->hp.g_mlp_base[g] * d;
-                    HIPCHK(c, launch_inter_fwd(ptr<float>(c->Z[T_INTER]) + mb, ptr<float>(c->Att) + mb,
-                                               ptr<float>(c->act) + (size_t)pl->hp.g_out_base[g] * d,
-                                               pl->hp.g_n[g], pl->hp.g_nin[g], d, s));
-                }
-            } else {
-                g2.C = ptr<float>(c->act) + (size_t)sg.out_base * d;
-                Timed tm(c, NGDB_TK_GEMM_FWD, s);
-                HIPCHK(c, launch_gemm(g2, s));
+            a.a_ref = pl->d_in_ref + sg.ref_off; a.a_base0 = ptr<float>(c->act); a.a_base1 = c->prm.E.p;
+            if (sg.rel_off >= 0) { a.a_add_idx = pl->d_rel + sg.rel_off; a.a_add = c->prm.R.p; }
+            a.a_copy = Z; a.lda = d; a.B = W.Wa; a.ldb = d; a.C = Hh; a.ldc = h;
+            a.M = sg.rows; a.N = h; a.K = d; a.bias = W.ba; a.relu = true;
+            GemmArgs& b = g2[n];
+            b.A = Hh; b.lda = h; b.B = W.Wb; b.ldb = h; b.M = sg.rows; b.N = d; b.K = h; b.bias = W.bb; b.ldc = d;
+            b.C = sg.type == T_INTER ? ptr<float>(c->Att) + (size_t)sg.mlp_base * d
+                                     : ptr<float>(c->act) + (size_t)sg.out_base * d;
+            ++n;
+        }
+        { Timed tm(c, NGDB_TK_GEMM_FWD, s); HIPCHK(c, launch_gemm_group(g1, n, s)); }
+        { Timed tm(c, NGDB_TK_GEMM_FWD, s); HIPCHK(c, launch_gemm_group(g2, n, s)); }
+        for (const Segment& sg : segs) {
+            if (sg.type != T_INTER) continue;
+            Timed tm(c, NGDB_TK_INTER, s);
+            for (int g = sg.g_lo; g < sg.g_hi; ++g) {
+                const size_t mb = (size_t)pl->hp.g_mlp_base[g] * d;
+                HIPCHK(c, launch_inter_fwd(ptr<float>(c->Z[T_INTER]) + mb, ptr<float>(c->Att) + mb,
+                                           ptr<float>(c->act) + (size_t)pl->hp.g_out_base[g] * d, pl->hp.g_n[g],
+                                           pl->hp.g_nin[g], d, s));
             }
         }
-        HIPCHK(c, L.join());
     }
     return NGDB_OK;
 }
 
-int enqueue_backward(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t stream) {
+// reversed frontiers, then the weight gradients of all three MLPs in one grouped launch
+int enqueue_backward(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t s) {
     const int d = c->cfg.d, h = c->cfg.h;
     const HostPlan& hp = pl->hp;
-    Lanes L{c, stream};
     float* dact = ptr<float>(c->dact);
     for (int l = hp.n_levels; l >= 1; --l) {
         const std::vector<Segment>& segs = pl->levels[l];
-        HIPCHK(c, L.fork((int)segs.size()));
-        for (size_t si = 0; si < segs.size(); ++si) {
-            const Segment& sg = segs[si];
-            hipStream_t s = L.lane((int)si);
+        GemmArgs b2[3], b1[3];
+        int n = 0;
+        for (const Segment& sg : segs) {
             const MlpRefs W = mlp_of(c->prm, sg.type);
             const float* dOut;
             const float* addend = nullptr;
@@ -323,44 +319,47 @@ int enqueue_backward(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t stream) {
             }
             const float* Hh = ptr<float>(c->H[sg.type]) + (size_t)sg.mlp_base * h;
             float* dHh = ptr<float>(c->dH[sg.type]) + (size_t)sg.mlp_base * h;
-            GemmArgs b2;   // dH = (dOut * Wb) masked by relu
-            b2.A = dOut; b2.lda = d; b2.B = W.Wb; b2.ldb = h; b2.b_kcontig = false;
-            b2.C = dHh; b2.ldc = h; b2.M = sg.rows; b2.N = h; b2.K = d; b2.mask = Hh; b2.ldmask = h;
-            { Timed tm(c, NGDB_TK_GEMM_BWD, s); HIPCHK(c, launch_gemm(b2, s)); }
-            GemmArgs b1;   // dZ = dH * Wa, scattered to the gradient rows of the inputs
-            b1.A = dHh; b1.lda = h; b1.B = W.Wa; b1.ldb = d; b1.b_kcontig = false;
-            b1.C = dact; b1.ldc = d; b1.M = sg.rows; b1.N = d; b1.K = h;
-            b1.addend = addend; b1.ldadd = d; b1.dst_row = pl->d_in_gslot + sg.ref_off;
-            { Timed tm(c, NGDB_TK_GEMM_BWD, s); HIPCHK(c, launch_gemm(b1, s)); }
+            GemmArgs& x = b2[n];   // dH = (dOut * Wb) masked by relu
+            x.A = dOut; x.lda = d; x.B = W.Wb; x.ldb = h; x.b_kcontig = false;
+            x.C = dHh; x.ldc = h; x.M = sg.rows; x.N = h; x.K = d; x.mask = Hh; x.ldmask = h;
+            GemmArgs& y = b1[n];   // dZ = dH * Wa, scattered to the gradient rows of the inputs
+            y.A = dHh; y.lda = h; y.B = W.Wa; y.ldb = d; y.b_kcontig = false;
+            y.C = dact; y.ldc = d; y.M = sg.rows; y.N = d; y.K = h;
+            y.addend = addend; y.ldadd = d; y.dst_row = pl->d_in_gslot + sg.ref_off;
+            ++n;
         }
-        HIPCHK(c, L.join());
+        { Timed tm(c, NGDB_TK_GEMM_BWD, s); HIPCHK(c, launch_gemm_group(b2, n, s)); }
+        { Timed tm(c, NGDB_TK_GEMM_BWD, s); HIPCHK(c, launch_gemm_group(b1, n, s)); }
     }
     // weight gradients: one contraction per tensor over all rows of the type
     const size_t rows[3] = {(size_t)hp.n_proj, (size_t)hp.n_int_rows, (size_t)hp.n_neg};
     const float* dY[3] = {dact, ptr<float>(c->dAtt), dact + ((size_t)hp.n_proj + hp.n_inter) * d};
     float* gW = ptr<float>(c->gW);
-    HIPCHK(c, L.fork(3));
+    Timed tm(c, NGDB_TK_WGRAD, s);
+    GemmArgs w[6];
     for (int t = 0; t < 3; ++t) {
-        hipStream_t s = L.lane(t);
-        Timed tm(c, NGDB_TK_WGRAD, s);
         const int gs = gslot_of(t);
         const int r = (int)rows[t];
-        GemmArgs wa;   // dWa[h,d] = dH^T Z
+        GemmArgs& wa = w[2 * t];       // dWa[h,d] = dH^T Z
         wa.A = ptr<float>(c->dH[t]); wa.lda = h; wa.a_kcontig = false;
         wa.B = ptr<float>(c->Z[t]); wa.ldb = d; wa.b_kcontig = false;
         wa.C = gW + c->gw_off[gs + 0]; wa.ldc = d; wa.M = h; wa.N = d; wa.K = r;
-        HIPCHK(c, launch_gemm(wa, s));
-        float* part = ptr<float>(c->colsum_part) + (size_t)(2 * t) * COLSUM_MAX_CHUNKS * std::max(d, h);
-        HIPCHK(c, launch_colsum(ptr<float>(c->dH[t]), r, h, h, gW + c->gw_off[gs + 1], part, s));
-        GemmArgs wb;   // dWb[d,h] = dY^T H
+        GemmArgs& wb = w[2 * t + 1];   // dWb[d,h] = dY^T H
         wb.A = dY[t]; wb.lda = d; wb.a_kcontig = false;
         wb.B = ptr<float>(c->H[t]); wb.ldb = h; wb.b_kcontig = false;
         wb.C = gW + c->gw_off[gs + 2]; wb.ldc = h; wb.M = d; wb.N = h; wb.K = r;
-        HIPCHK(c, launch_gemm(wb, s));
-        HIPCHK(c, launch_colsum(dY[t], r, d, d, gW + c->gw_off[gs + 3],
-                                part + (size_t)COLSUM_MAX_CHUNKS * std::max(d, h), s));
     }
-    HIPCHK(c, L.join());
+    HIPCHK(c, launch_gemm_group(w, 6, s));
+    ColsumJobs cs{};
+    for (int t = 0; t < 3; ++t) {
+        const int gs = gslot_of(t);
+        const int r = (int)rows[t];
+        float* part = ptr<float>(c->colsum_part) + (size_t)(2 * t) * COLSUM_MAX_CHUNKS * std::max(d, h);
+        cs.job[cs.count++] = ColsumJob{ptr<float>(c->dH[t]), gW + c->gw_off[gs + 1], part, r, h, h, 0, 0};
+        cs.job[cs.count++] = ColsumJob{dY[t], gW + c->gw_off[gs + 3], part + (size_t)COLSUM_MAX_CHUNKS * std::max(d, h),
+                                       r, d, d, 0, 0};
+    }
+    HIPCHK(c, launch_colsums(cs, s));
     return NGDB_OK;
 }
 
@@ -383,11 +382,18 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
                     ptr<int32_t>(c->vals_b), ptr<int32_t>(c->hist),   ptr<int32_t>(c->scan_tmp),
                     ptr<int32_t>(c->uniq),   ptr<int32_t>(c->seg_off), ptr<int32_t>(c->n_uniq)};
     int32_t* e_src = nullptr;
-    {
-        Timed tm(c, NGDB_TK_INDEX, stream);
-        HIPCHK(c, build_segment_index(pl->d_ekeys_head, hp.n_anchor + B, d_neg, (int64_t)B * K, c->cfg.n_entities,
-                                      ib, &e_src, stream));
+    // the index is independent of the forward/backward passes: with library streams it runs beside them
+    hipStream_t s_idx = c->n_side ? c->side[0] : stream;
+    if (c->n_side) {
+        HIPCHK(c, hipEventRecord(c->ev_fork, stream));
+        HIPCHK(c, hipStreamWaitEvent(s_idx, c->ev_fork, 0));
     }
+    {
+        Timed tm(c, NGDB_TK_INDEX, s_idx);
+        HIPCHK(c, build_segment_index(pl->d_ekeys_head, hp.n_anchor + B, d_neg, (int64_t)B * K, c->cfg.n_entities,
+                                      ib, &e_src, s_idx));
+    }
+    if (c->n_side) HIPCHK(c, hipEventRecord(c->ev_index, s_idx));
 
     // 2. forward frontiers
     rc = enqueue_forward(c, pl, stream);
@@ -427,6 +433,7 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
     tr.uniq = pl->d_r_uniq; tr.seg_off = pl->d_r_seg_off; tr.src = pl->d_r_src; tr.n_uniq_dev = pl->d_n_r_uniq;
     tr.src_is_row = true; tr.g_out = apply ? nullptr : ptr<float>(c->gR);
 
+    if (c->n_side) HIPCHK(c, hipStreamWaitEvent(stream, c->ev_index, 0));
     Lanes L{c, stream};
     HIPCHK(c, L.fork(3));
     { Timed tm(c, NGDB_TK_TABLE_E, L.lane(0)); HIPCHK(c, launch_table_update(te, ah, L.lane(0))); }
@@ -493,6 +500,7 @@ int ngdb_create(const ngdb_config* cfg, ngdb_ctx_t** out) {
         ok = hipStreamCreateWithFlags(&c->side[i], hipStreamNonBlocking) == hipSuccess &&
              hipEventCreateWithFlags(&c->ev_join[i], hipEventDisableTiming) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&c->ev_index, hipEventDisableTiming) == hipSuccess;
     ok = ok && hipStreamCreateWithFlags(&c->upload, hipStreamNonBlocking) == hipSuccess;
     if (!ok) {
         ngdb_destroy(c);
@@ -515,6 +523,7 @@ void ngdb_destroy(ngdb_ctx_t* c) {
         if (c->ev_join[i]) (void)hipEventDestroy(c->ev_join[i]);
     }
     if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+    if (c->ev_index) (void)hipEventDestroy(c->ev_index);
     if (c->upload) (void)hipStreamDestroy(c->upload);
     for (PlanBlob& b : c->blob_pool) {
         if (b.dev) (void)hipFree(b.dev);

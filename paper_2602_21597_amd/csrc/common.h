@@ -63,6 +63,15 @@ struct GemmArgs {
     const int32_t* dst_row = nullptr;
 };
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
+// Up to GEMM_MAX_GROUP independent contractions with the same operand layout in one
+// launch (the operator groups of one depth, or the weight gradients of all types).
+constexpr int GEMM_MAX_GROUP = 6;
+struct GemmGroup {
+    int count;
+    int tile_start[GEMM_MAX_GROUP + 1];   // first workgroup of every problem
+    GemmArgs p[GEMM_MAX_GROUP];
+};
+hipError_t launch_gemm_group(const GemmArgs* problems, int count, hipStream_t s);
 
 // ---------------------------------------------------------------- elementwise ops (ops.hip)
 // Z[m,:] = src(ref[m]) (+ R[rel[m]]), src = act row if ref >= 0 else E row -1-ref.
@@ -73,10 +82,22 @@ hipError_t launch_inter_fwd(const float* X, const float* Att, float* out, int n,
 // dAtt[j*n+i] = w_j*(dy*x_j - sum_l w_l dy x_l),  Dx[j*n+i] = w_j*dy
 hipError_t launch_inter_bwd(const float* X, const float* Att, const float* dY, float* dAtt, float* Dx,
                             int n, int k, int d, hipStream_t s);
-// out[c] = sum_m X[m*ld + c], c < cols (fixed summation order); `partial` is scratch
-// of COLSUM_MAX_CHUNKS * cols floats
+// out[c] = sum_m X[m*ld + c], c < cols, for several matrices in one launch pair (fixed
+// summation order); `part` is scratch of COLSUM_MAX_CHUNKS * cols floats per matrix
 constexpr int COLSUM_MAX_CHUNKS = 128;
-hipError_t launch_colsum(const float* X, int rows, int cols, int ld, float* out, float* partial, hipStream_t s);
+constexpr int COLSUM_MAX_JOBS = 6;
+struct ColsumJob {
+    const float* X;
+    float* out;
+    float* part;
+    int rows, cols, ld;
+    int chunk_rows, chunks;   // filled by launch_colsums
+};
+struct ColsumJobs {
+    int count;
+    ColsumJob job[COLSUM_MAX_JOBS];
+};
+hipError_t launch_colsums(ColsumJobs& jobs, hipStream_t s);
 hipError_t launch_fill_zero(float* p, size_t n, hipStream_t s);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 

@@ -107,14 +107,25 @@ __device__ __forceinline__ void stage(float* __restrict__ dst, int lane, const f
 }
 
 template <int BM, int BN, int NW, bool AK, bool BKC>
-__global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmArgs a) {
+__global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
     __shared__ __attribute__((aligned(16))) float smem[Smem<BM, BN, NW>::FLOATS];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const int m0 = blockIdx.y * BM;
-    const int n0 = blockIdx.x * BN;
-    const bool first_n_tile = blockIdx.x == 0;
+    // which problem of the group this workgroup works on (uniform, stays in scalar registers)
+    int p = 0;
+#pragma unroll
+    for (int i = 1; i < GEMM_MAX_GROUP; ++i)
+        if (i < g.count && (int)blockIdx.x >= g.tile_start[i]) p = i;
+    GemmArgs a = g.p[0];
+#pragma unroll
+    for (int i = 1; i < GEMM_MAX_GROUP; ++i)
+        if (i == p) a = g.p[i];
+    const int tile = (int)blockIdx.x - g.tile_start[p];
+    const int tiles_n = (a.N + BN - 1) / BN;
+    const int m0 = (tile / tiles_n) * BM;
+    const int n0 = (tile % tiles_n) * BN;
+    const bool first_n_tile = n0 == 0;
     constexpr int TM = BM / 32, TN = BN / 32;
     constexpr int LDA = BM + PAD, LDB = BN + PAD;
     float* As = smem + wave * BK * (LDA + LDB);     // [BK][LDA] of this wavefront
@@ -221,32 +232,54 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmArgs a) {
 #undef NGDB_ACC_TO_LDS
     __syncthreads();
 
-    for (int e = tid; e < BM * BN; e += NW * 64) {
-        const int lr = e / BN, lc = e - lr * BN;
-        const int row = m0 + lr, col = n0 + lc;
-        if (row >= a.M || col >= a.N) continue;
+    // epilogue: all global operands of a thread's elements are requested first (clamped
+    // addresses, uniform flags), then the partial tiles are summed, then stored
+    constexpr int EPT = BM * BN / (NW * 64);
+    float e_bias[EPT], e_mask[EPT], e_add[EPT];
+    int e_orow[EPT];
+    const bool has_bias = a.bias != nullptr, has_mask = a.mask != nullptr, has_addend = a.addend != nullptr,
+               has_dst = a.dst_row != nullptr;
+#pragma unroll
+    for (int q = 0; q < EPT; ++q) {
+        const int e = tid + q * NW * 64;
+        const int lr = e / BN, lc = e % BN;
+        const int row = min(m0 + lr, a.M - 1), col = min(n0 + lc, a.N - 1);
+        e_bias[q] = has_bias ? a.bias[col] : 0.f;
+        e_mask[q] = has_mask ? a.mask[(size_t)row * a.ldmask + col] : 1.f;
+        e_add[q] = has_addend ? a.addend[(size_t)row * a.ldadd + col] : 0.f;
+        e_orow[q] = has_dst ? a.dst_row[row] : row;
+    }
+#pragma unroll
+    for (int q = 0; q < EPT; ++q) {
+        const int e = tid + q * NW * 64;
+        const int lr = e / BN, lc = e % BN;
         float v = smem[lr * (BN + 1) + lc];
 #pragma unroll
         for (int w = 1; w < NR; ++w) v += smem[w * BM * (BN + 1) + lr * (BN + 1) + lc];
-        if (a.bias) v += a.bias[col];
+        v += e_bias[q];
         if (a.relu) v = fmaxf(v, 0.f);
-        if (a.mask) v = a.mask[(size_t)row * a.ldmask + col] > 0.f ? v : 0.f;
-        if (a.addend) v += a.addend[(size_t)row * a.ldadd + col];
-        const int orow = a.dst_row ? a.dst_row[row] : row;
-        a.C[(size_t)orow * a.ldc + col] = v;
+        v = e_mask[q] > 0.f ? v : 0.f;
+        v += e_add[q];
+        if (m0 + lr < a.M && n0 + lc < a.N) a.C[(size_t)e_orow[q] * a.ldc + n0 + lc] = v;
     }
 }
 
 template <int BM, int BN, int NW>
-hipError_t dispatch_layout(const GemmArgs& a, hipStream_t s) {
-    dim3 grid((a.N + BN - 1) / BN, (a.M + BM - 1) / BM);
-    dim3 block(NW * 64);
+hipError_t dispatch_layout(GemmGroup& g, hipStream_t s) {
+    int tiles = 0;
+    for (int i = 0; i < g.count; ++i) {
+        g.tile_start[i] = tiles;
+        tiles += ((g.p[i].M + BM - 1) / BM) * ((g.p[i].N + BN - 1) / BN);
+    }
+    for (int i = g.count; i <= GEMM_MAX_GROUP; ++i) g.tile_start[i] = tiles;
+    dim3 grid(tiles), block(NW * 64);
+    const GemmArgs& a = g.p[0];
     if (a.a_kcontig && a.b_kcontig)
-        hipLaunchKernelGGL((gemm_kernel<BM, BN, NW, true, true>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((gemm_kernel<BM, BN, NW, true, true>), grid, block, 0, s, g);
     else if (a.a_kcontig && !a.b_kcontig)
-        hipLaunchKernelGGL((gemm_kernel<BM, BN, NW, true, false>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((gemm_kernel<BM, BN, NW, true, false>), grid, block, 0, s, g);
     else if (!a.a_kcontig && !a.b_kcontig)
-        hipLaunchKernelGGL((gemm_kernel<BM, BN, NW, false, false>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((gemm_kernel<BM, BN, NW, false, false>), grid, block, 0, s, g);
     else
         return hipErrorInvalidValue;
     return hipGetLastError();
@@ -254,17 +287,31 @@ hipError_t dispatch_layout(const GemmArgs& a, hipStream_t s) {
 
 }  // namespace
 
-hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
-    if (a.M <= 0 || a.N <= 0) return hipSuccess;
-    // float4 operand loads: leading dimensions and the contiguous extents must be multiples of 4
-    if ((a.lda & 3) || (a.ldb & 3)) return hipErrorInvalidValue;
-    if ((a.a_kcontig ? a.K : a.M) & 3) return hipErrorInvalidValue;
-    if ((a.b_kcontig ? a.K : a.N) & 3) return hipErrorInvalidValue;
-    if (a.a_ref && !a.a_kcontig) return hipErrorInvalidValue;
-    const long blocks_small = (long)((a.M + 31) / 32) * ((a.N + 63) / 64);
-    if (blocks_small >= 2048) return dispatch_layout<64, 64, 4>(a, s);
-    if (a.K >= 512) return dispatch_layout<32, 64, 8>(a, s);
-    return dispatch_layout<32, 64, 4>(a, s);
+hipError_t launch_gemm_group(const GemmArgs* problems, int count, hipStream_t s) {
+    GemmGroup g{};
+    long blocks_small = 0;
+    int max_k = 0;
+    for (int i = 0; i < count; ++i) {
+        const GemmArgs& a = problems[i];
+        if (a.M <= 0 || a.N <= 0) continue;
+        if (g.count == GEMM_MAX_GROUP) return hipErrorInvalidValue;
+        // float4 operand loads: leading dimensions and the contiguous extents must be multiples of 4
+        if ((a.lda & 3) || (a.ldb & 3)) return hipErrorInvalidValue;
+        if ((a.a_kcontig ? a.K : a.M) & 3) return hipErrorInvalidValue;
+        if ((a.b_kcontig ? a.K : a.N) & 3) return hipErrorInvalidValue;
+        if (a.a_ref && !a.a_kcontig) return hipErrorInvalidValue;
+        if (g.count && (a.a_kcontig != g.p[0].a_kcontig || a.b_kcontig != g.p[0].b_kcontig))
+            return hipErrorInvalidValue;   // one operand layout per launch
+        g.p[g.count++] = a;
+        blocks_small += (long)((a.M + 31) / 32) * ((a.N + 63) / 64);
+        max_k = std::max(max_k, a.K);
+    }
+    if (g.count == 0) return hipSuccess;
+    if (blocks_small >= 2048) return dispatch_layout<64, 64, 4>(g, s);
+    if (max_k >= 512) return dispatch_layout<32, 64, 8>(g, s);
+    return dispatch_layout<32, 64, 4>(g, s);
 }
+
+hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) { return launch_gemm_group(&a, 1, s); }
 
 }  // namespace ngdb

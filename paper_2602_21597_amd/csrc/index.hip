@@ -13,7 +13,7 @@ namespace {
 constexpr int RADIX_BITS = 8;
 constexpr int RADIX = 1 << RADIX_BITS;
 constexpr int SORT_THREADS = 256;
-constexpr int SORT_ITEMS = 16;                       // keys per thread
+constexpr int SORT_ITEMS = 4;                        // keys per thread
 constexpr int SORT_TILE = SORT_THREADS * SORT_ITEMS; // keys per workgroup
 constexpr int SCAN_THREADS = 256;
 constexpr int SCAN_ITEMS = 8;

@@ -69,30 +69,38 @@ __global__ __launch_bounds__(256) void inter_kernel(const float* __restrict__ X,
     }
 }
 
-// column sums in a fixed order, two steps: partial sums over chunks of rows (one
-// workgroup per 64 columns x chunk), then the chunks are added up per column
-__global__ __launch_bounds__(256) void colsum_part_kernel(const float* __restrict__ X, int rows, int cols, int ld,
-                                                          int chunk_rows, float* __restrict__ part) {
+// column sums of up to COLSUM_MAX_JOBS matrices in a fixed order, two steps: partial
+// sums over chunks of rows (one workgroup per 64 columns x chunk x matrix), then the
+// chunks are added up per column
+__global__ __launch_bounds__(256) void colsum_part_kernel(const ColsumJobs jobs) {
     __shared__ float red[4][64];
+    const ColsumJob j = jobs.job[blockIdx.z];
     const int c = blockIdx.x * 64 + threadIdx.x;
-    const int lo = blockIdx.y * chunk_rows, hi = min(rows, lo + chunk_rows);
-    float s = 0.f;
-    if (c < cols)
-        for (int m = lo + threadIdx.y; m < hi; m += 4) s += X[(size_t)m * ld + c];
-    red[threadIdx.y][threadIdx.x] = s;
+    const int lo = blockIdx.y * j.chunk_rows, hi = min(j.rows, lo + j.chunk_rows);
+    if (blockIdx.y >= j.chunks || blockIdx.x * 64 >= j.cols) return;     // uniform per workgroup
+    float s0 = 0.f, s1 = 0.f;
+    if (c < j.cols) {
+        int m = lo + threadIdx.y;
+        for (; m + 4 < hi; m += 8) {
+            s0 += j.X[(size_t)m * j.ld + c];
+            s1 += j.X[(size_t)(m + 4) * j.ld + c];
+        }
+        if (m < hi) s0 += j.X[(size_t)m * j.ld + c];
+    }
+    red[threadIdx.y][threadIdx.x] = s0 + s1;
     __syncthreads();
-    if (threadIdx.y == 0 && c < cols)
-        part[(size_t)blockIdx.y * cols + c] =
+    if (threadIdx.y == 0 && c < j.cols)
+        j.part[(size_t)blockIdx.y * j.cols + c] =
             (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
 }
 
-__global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restrict__ part, int chunks, int cols,
-                                                           float* __restrict__ out) {
+__global__ __launch_bounds__(256) void colsum_final_kernel(const ColsumJobs jobs) {
+    const ColsumJob j = jobs.job[blockIdx.y];
     const int c = blockIdx.x * 256 + threadIdx.x;
-    if (c >= cols) return;
+    if (c >= j.cols) return;
     float s = 0.f;
-    for (int k = 0; k < chunks; ++k) s += part[(size_t)k * cols + c];
-    out[c] = s;
+    for (int k = 0; k < j.chunks; ++k) s += j.part[(size_t)k * j.cols + c];
+    j.out[c] = s;
 }
 
 __global__ __launch_bounds__(256) void fill_zero_kernel(float* p, size_t n) {
@@ -159,14 +167,18 @@ hipError_t launch_inter_bwd(const float* X, const float* Att, const float* dY, f
     return hipGetLastError();
 }
 
-hipError_t launch_colsum(const float* X, int rows, int cols, int ld, float* out, float* partial, hipStream_t s) {
-    if (cols <= 0) return hipSuccess;
-    const int chunk_rows = std::max(32, (rows + COLSUM_MAX_CHUNKS - 1) / COLSUM_MAX_CHUNKS);
-    const int chunks = std::max(1, (rows + chunk_rows - 1) / chunk_rows);
-    hipLaunchKernelGGL(colsum_part_kernel, dim3((cols + 63) / 64, chunks), dim3(64, 4), 0, s, X, rows, cols, ld,
-                       chunk_rows, partial);
-    hipLaunchKernelGGL(colsum_final_kernel, dim3((cols + 255) / 256), dim3(256), 0, s, (const float*)partial, chunks,
-                       cols, out);
+hipError_t launch_colsums(ColsumJobs& jobs, hipStream_t s) {
+    if (jobs.count <= 0) return hipSuccess;
+    int max_cols = 0, max_chunks = 1;
+    for (int i = 0; i < jobs.count; ++i) {
+        ColsumJob& j = jobs.job[i];
+        j.chunk_rows = std::max(32, (j.rows + COLSUM_MAX_CHUNKS - 1) / COLSUM_MAX_CHUNKS);
+        j.chunks = std::max(1, (j.rows + j.chunk_rows - 1) / j.chunk_rows);
+        max_cols = std::max(max_cols, j.cols);
+        max_chunks = std::max(max_chunks, j.chunks);
+    }
+    hipLaunchKernelGGL(colsum_part_kernel, dim3((max_cols + 63) / 64, max_chunks, jobs.count), dim3(64, 4), 0, s, jobs);
+    hipLaunchKernelGGL(colsum_final_kernel, dim3((max_cols + 255) / 256, jobs.count), dim3(256), 0, s, jobs);
     return hipGetLastError();
 }
 
