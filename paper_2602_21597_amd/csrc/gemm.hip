@@ -11,6 +11,8 @@
 // partial tiles are then summed through LDS in a fixed order (deterministic) and
 // the epilogue is applied to the sum.  The A operand can be assembled on the fly
 // from row references (gather of operator inputs fused into the first layer).
+#include <cstdlib>
+
 #include "common.h"
 
 namespace ngdb {
@@ -31,77 +33,95 @@ struct Smem {
 
 // Operand staging is written as force-inlined functions over register arrays of
 // compile-time size (no lambdas, no run-time indices) so that the tiles in
-// flight stay in VGPRs.
-// Loads never branch on the bounds: the address is clamped into the operand and
-// the value is zeroed afterwards, so every load is a plain global load.
+// flight stay in VGPRs.  Issuing a tile is nothing but address arithmetic and
+// loads: addresses are clamped into the operand, never branched on, and nothing
+// touches the loaded values before the tile is staged, so the loads of the next
+// tile stay in flight while the current one is multiplied.
 template <int BM, int LA, bool AK>
-__device__ __forceinline__ void load_a(const GemmArgs& a, int lane, int m0, int k0, bool first_n_tile,
-                                       const float* const (&arow)[LA], const float* const (&aadd)[LA],
-                                       const bool (&avalid)[LA], float4 (&ra)[LA]) {
+__device__ __forceinline__ void issue_a(const GemmArgs& a, int lane, int m0, int k0, bool has_add,
+                                        const float* const (&arow)[LA], const float* const (&aadd)[LA],
+                                        float4 (&ra)[LA], float4 (&rd)[LA]) {
 #pragma unroll
     for (int i = 0; i < LA; ++i) {
         const int idx = lane + i * 64;
         if (AK) {
-            const int gk = k0 + (idx % (BK / 4)) * 4;
-            const bool ok = avalid[i] && gk < a.K;
-            const int gkc = min(gk, a.K - 4);
-            float4 v = *reinterpret_cast<const float4*>(arow[i] + gkc);
-            if (aadd[i]) {
-                const float4 w = *reinterpret_cast<const float4*>(aadd[i] + gkc);
-                v.x += w.x; v.y += w.y; v.z += w.z; v.w += w.w;
-            }
-            if (!ok) v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (ok && a.a_copy && first_n_tile)
-                *reinterpret_cast<float4*>(a.a_copy + (size_t)(m0 + idx / (BK / 4)) * a.lda + gk) = v;
-            ra[i] = v;
+            const int gkc = min(k0 + (idx % (BK / 4)) * 4, a.K - 4);
+            ra[i] = *reinterpret_cast<const float4*>(arow[i] + gkc);
+            if (has_add) rd[i] = *reinterpret_cast<const float4*>(aadd[i] + gkc);
         } else {
-            const int k = idx / (BM / 4), mq = idx % (BM / 4);
-            const int gk = k0 + k, gm = m0 + mq * 4;
-            const bool ok = gk < a.K && gm < a.M;
-            float4 v = *reinterpret_cast<const float4*>(a.A + (size_t)min(gk, a.K - 1) * a.lda + min(gm, a.M - 4));
-            if (!ok) v = make_float4(0.f, 0.f, 0.f, 0.f);
-            ra[i] = v;
+            const int gk = k0 + idx / (BM / 4), gm = m0 + (idx % (BM / 4)) * 4;
+            ra[i] = *reinterpret_cast<const float4*>(a.A + (size_t)min(gk, a.K - 1) * a.lda + min(gm, a.M - 4));
         }
     }
 }
 
 template <int BN, int LB, bool BKC>
-__device__ __forceinline__ void load_b(const GemmArgs& a, int lane, int n0, int k0, float4 (&rb)[LB]) {
+__device__ __forceinline__ void issue_b(const GemmArgs& a, int lane, int n0, int k0, float4 (&rb)[LB]) {
 #pragma unroll
     for (int i = 0; i < LB; ++i) {
         const int idx = lane + i * 64;
-        int gn, gk;
         const float* p;
         if (BKC) {
-            gn = n0 + idx / (BK / 4);
-            gk = k0 + (idx % (BK / 4)) * 4;
+            const int gn = n0 + idx / (BK / 4), gk = k0 + (idx % (BK / 4)) * 4;
             p = a.B + (size_t)min(gn, a.N - 1) * a.ldb + min(gk, a.K - 4);
         } else {
-            gk = k0 + idx / (BN / 4);
-            gn = n0 + (idx % (BN / 4)) * 4;
+            const int gk = k0 + idx / (BN / 4), gn = n0 + (idx % (BN / 4)) * 4;
             p = a.B + (size_t)min(gk, a.K - 1) * a.ldb + min(gn, a.N - 4);
         }
-        float4 v = *reinterpret_cast<const float4*>(p);
-        if (!(gn < a.N && gk < a.K)) v = make_float4(0.f, 0.f, 0.f, 0.f);
-        rb[i] = v;
+        rb[i] = *reinterpret_cast<const float4*>(p);
     }
 }
 
-// registers -> this wavefront's LDS tile [BK][LD]; KC: the registers hold 4 consecutive k of one row
-template <int BX, int LX, int LD, bool KC>
-__device__ __forceinline__ void stage(float* __restrict__ dst, int lane, const float4 (&r)[LX]) {
+// registers -> this wavefront's LDS tile [BK][LD].  Here the values are completed:
+// relation row added, entries outside the operand zeroed, assembled A rows copied out.
+template <int BM, int LA, int LD, bool AK>
+__device__ __forceinline__ void stage_a(const GemmArgs& a, float* __restrict__ dst, int lane, int m0, int k0,
+                                        bool has_add, bool copy_out, const bool (&avalid)[LA],
+                                        const float4 (&ra)[LA], const float4 (&rd)[LA]) {
 #pragma unroll
-    for (int i = 0; i < LX; ++i) {
+    for (int i = 0; i < LA; ++i) {
         const int idx = lane + i * 64;
-        if (KC) {
+        float4 v = ra[i];
+        if (AK) {
             const int m = idx / (BK / 4), kq = idx % (BK / 4);
-            dst[(kq * 4 + 0) * LD + m] = r[i].x;
-            dst[(kq * 4 + 1) * LD + m] = r[i].y;
-            dst[(kq * 4 + 2) * LD + m] = r[i].z;
-            dst[(kq * 4 + 3) * LD + m] = r[i].w;
+            const int gk = k0 + kq * 4;
+            if (has_add) { v.x += rd[i].x; v.y += rd[i].y; v.z += rd[i].z; v.w += rd[i].w; }
+            const bool ok = avalid[i] && gk < a.K;
+            v.x = ok ? v.x : 0.f; v.y = ok ? v.y : 0.f; v.z = ok ? v.z : 0.f; v.w = ok ? v.w : 0.f;
+            if (copy_out && ok) *reinterpret_cast<float4*>(a.a_copy + (size_t)(m0 + m) * a.lda + gk) = v;
+            dst[(kq * 4 + 0) * LD + m] = v.x;
+            dst[(kq * 4 + 1) * LD + m] = v.y;
+            dst[(kq * 4 + 2) * LD + m] = v.z;
+            dst[(kq * 4 + 3) * LD + m] = v.w;
         } else {
-            const int k = idx / (BX / 4), mq = idx % (BX / 4);
-            *reinterpret_cast<float4*>(&dst[k * LD + mq * 4]) = r[i];
+            const int k = idx / (BM / 4), mq = idx % (BM / 4);
+            const bool ok = k0 + k < a.K && m0 + mq * 4 < a.M;
+            v.x = ok ? v.x : 0.f; v.y = ok ? v.y : 0.f; v.z = ok ? v.z : 0.f; v.w = ok ? v.w : 0.f;
+            *reinterpret_cast<float4*>(&dst[k * LD + mq * 4]) = v;
+        }
+    }
+}
+
+template <int BN, int LB, int LD, bool BKC>
+__device__ __forceinline__ void stage_b(const GemmArgs& a, float* __restrict__ dst, int lane, int n0, int k0,
+                                        const float4 (&rb)[LB]) {
+#pragma unroll
+    for (int i = 0; i < LB; ++i) {
+        const int idx = lane + i * 64;
+        float4 v = rb[i];
+        if (BKC) {
+            const int n = idx / (BK / 4), kq = idx % (BK / 4);
+            const bool ok = n0 + n < a.N && k0 + kq * 4 < a.K;
+            v.x = ok ? v.x : 0.f; v.y = ok ? v.y : 0.f; v.z = ok ? v.z : 0.f; v.w = ok ? v.w : 0.f;
+            dst[(kq * 4 + 0) * LD + n] = v.x;
+            dst[(kq * 4 + 1) * LD + n] = v.y;
+            dst[(kq * 4 + 2) * LD + n] = v.z;
+            dst[(kq * 4 + 3) * LD + n] = v.w;
+        } else {
+            const int k = idx / (BN / 4), nq = idx % (BN / 4);
+            const bool ok = k0 + k < a.K && n0 + nq * 4 < a.N;
+            v.x = ok ? v.x : 0.f; v.y = ok ? v.y : 0.f; v.z = ok ? v.z : 0.f; v.w = ok ? v.w : 0.f;
+            *reinterpret_cast<float4*>(&dst[k * LD + nq * 4]) = v;
         }
     }
 }
@@ -141,7 +161,9 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
 
     constexpr int LA = BM * BK / 4 / 64;   // float4 per lane per tile
     constexpr int LB = BN * BK / 4 / 64;
-    float4 ra[LA], rb[LB];
+    float4 ra[LA], rd[LA], rb[LB];
+    const bool has_add = AK && a.a_ref != nullptr && a.a_add_idx != nullptr;   // uniform
+    const bool copy_out = AK && a.a_copy != nullptr && first_n_tile;           // uniform
 
     // rows of A (k-contiguous layout), possibly assembled from references: resolved once
     // per lane; rows past M point at row M-1 and are zeroed after the load
@@ -151,7 +173,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
 #pragma unroll
     for (int i = 0; i < LA; ++i) {
         arow[i] = a.A;
-        aadd[i] = nullptr;
+        aadd[i] = a.A;
         avalid[i] = false;
         if (AK) {
             const int gm = m0 + (lane + i * 64) / (BK / 4);
@@ -171,33 +193,39 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
     // so that the workgroup barriers below are reached by all
     const int nk = (a.K + BK - 1) / BK;
     const int rounds = (nk + NW - 1) / NW;     // K == 0: no round, no load
+    int kcur = wave * BK;
     if (rounds > 0) {
-        load_a<BM, LA, AK>(a, lane, m0, wave * BK, first_n_tile, arow, aadd, avalid, ra);
-        load_b<BN, LB, BKC>(a, lane, n0, wave * BK, rb);
+        issue_a<BM, LA, AK>(a, lane, m0, kcur, has_add, arow, aadd, ra, rd);
+        issue_b<BN, LB, BKC>(a, lane, n0, kcur, rb);
     }
     for (int it = 0; it < rounds; ++it) {
-        stage<BM, LA, LDA, AK>(As, lane, ra);
-        stage<BN, LB, LDB, BKC>(Bs, lane, rb);
+        stage_a<BM, LA, LDA, AK>(a, As, lane, m0, kcur, has_add, copy_out, avalid, ra, rd);
+        stage_b<BN, LB, LDB, BKC>(a, Bs, lane, n0, kcur, rb);
         __syncthreads();
         if (it + 1 < rounds) {
-            const int k0 = ((it + 1) * NW + wave) * BK;
-            load_a<BM, LA, AK>(a, lane, m0, k0, first_n_tile, arow, aadd, avalid, ra);
-            load_b<BN, LB, BKC>(a, lane, n0, k0, rb);
+            kcur = ((it + 1) * NW + wave) * BK;
+            issue_a<BM, LA, AK>(a, lane, m0, kcur, has_add, arow, aadd, ra, rd);
+            issue_b<BN, LB, BKC>(a, lane, n0, kcur, rb);
         }
+        // all LDS operand reads of the tile are issued before the first MFMA, so that the
+        // matrix pipe never waits for an LDS round trip between k steps
+        float av[BK / 2][TM], bv[BK / 2][TN];
 #pragma unroll
         for (int kk = 0; kk < BK / 2; ++kk) {
             const int krow = kk * 2 + (lane >> 5);
-            float av[TM], bv[TN];
 #pragma unroll
-            for (int i = 0; i < TM; ++i) av[i] = As[krow * LDA + i * 32 + (lane & 31)];
+            for (int i = 0; i < TM; ++i) av[kk][i] = As[krow * LDA + i * 32 + (lane & 31)];
 #pragma unroll
-            for (int j = 0; j < TN; ++j) bv[j] = Bs[krow * LDB + j * 32 + (lane & 31)];
+            for (int j = 0; j < TN; ++j) bv[kk][j] = Bs[krow * LDB + j * 32 + (lane & 31)];
+        }
+        __builtin_amdgcn_sched_barrier(0);      // keep the reads ahead of the MFMAs
+#pragma unroll
+        for (int kk = 0; kk < BK / 2; ++kk)
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
-        }
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[kk][i], bv[kk][j], acc[i][j], 0, 0, 0);
         __syncthreads();
     }
 
@@ -308,6 +336,10 @@ hipError_t launch_gemm_group(const GemmArgs* problems, int count, hipStream_t s)
     }
     if (g.count == 0) return hipSuccess;
     if (blocks_small >= 2048) return dispatch_layout<64, 64, 4>(g, s);
+    const char* t = getenv("NGDB_GEMM_NW");
+    const int nw = t ? atoi(t) : 0;
+    if (nw == 4) return dispatch_layout<32, 64, 4>(g, s);
+    if (nw == 8) return dispatch_layout<32, 64, 8>(g, s);
     if (max_k >= 512) return dispatch_layout<32, 64, 8>(g, s);
     return dispatch_layout<32, 64, 4>(g, s);
 }
