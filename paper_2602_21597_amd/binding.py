@@ -280,6 +280,20 @@ class Engine:
                                            self._loss.data_ptr()), self.ctx)
         return self._loss
 
+    def grad_view(self):
+        """The raw ngdb_grad_view of the last step (device pointers; waits for the device)."""
+        gv = GradView()
+        _check(lib().ngdb_get_grads(self.ctx, C.byref(gv)), self.ctx)
+        return gv
+
+    def read_rows(self, dev_ptr, rows, width, dtype=np.float32):
+        """Rows `rows` of a device matrix [*, width] as a numpy copy (one small copy per row)."""
+        item = np.dtype(dtype).itemsize
+        out = np.empty((len(rows), width), dtype)
+        for i, r in enumerate(rows):
+            out[i] = copy_to_host(dev_ptr + int(r) * width * item, (width,), dtype)
+        return out
+
     def grads(self):
         """Results of the last forward_backward as numpy copies."""
         gv = GradView()
