@@ -53,7 +53,7 @@ struct ngdb_plan_s {
     // device views into the blob
     const int32_t *d_in_ref = nullptr, *d_in_gslot = nullptr, *d_rel = nullptr, *d_root_off = nullptr,
                   *d_root_slot = nullptr, *d_pos = nullptr, *d_ekeys_head = nullptr, *d_r_uniq = nullptr,
-                  *d_r_seg_off = nullptr, *d_r_src = nullptr, *d_n_r_uniq = nullptr;
+                  *d_r_seg_off = nullptr, *d_r_src = nullptr, *d_r_rec = nullptr, *d_n_r_uniq = nullptr;
     std::vector<std::vector<Segment>> levels;   // levels[l] for l = 1..n_levels (index 0 unused)
     int32_t n_entities = 0;
 };
@@ -71,7 +71,7 @@ struct ngdb_ctx_s {
     int n_side = 0;
     // workspace
     DevBuf act, dact, Z[3], H[3], dH[3], Att, dAtt, Dx;
-    DevBuf score, coef, win, loss_terms;
+    DevBuf score, coef, win, loss_terms, rec_coef, rec_row;
     DevBuf keys_a, keys_b, vals_a, vals_b, hist, scan_tmp, uniq, seg_off, n_uniq;
     DevBuf colsum_part; // 6 scratch areas of the bias-gradient column sums
     DevBuf gW;          // gradients of the 12 MLP tensors, packed
@@ -219,6 +219,8 @@ int size_workspace(ngdb_ctx_t* c, const ngdb_plan_t* pl, int K, bool want_table_
     ENS(c->coef, pairs * f);
     ENS(c->win, pairs * sizeof(int32_t));
     ENS(c->loss_terms, (size_t)hp.n_queries * f);
+    ENS(c->rec_coef, ((size_t)hp.n_anchor + pairs) * f);
+    ENS(c->rec_row, ((size_t)hp.n_anchor + pairs) * sizeof(int32_t));
     const int64_t nk = (int64_t)hp.n_anchor + hp.n_queries + (int64_t)hp.n_queries * K;
     ENS(c->keys_a, (size_t)nk * 4);
     ENS(c->keys_b, (size_t)nk * 4);
@@ -422,18 +424,20 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
     AdamHyper ah{c->cfg.lr, c->cfg.beta1, c->cfg.beta2, c->cfg.eps,
                  (float)(1.0 - std::pow((double)c->cfg.beta1, (double)t)),
                  (float)(1.0 - std::pow((double)c->cfg.beta2, (double)t))};
+    if (c->n_side) HIPCHK(c, hipStreamWaitEvent(stream, c->ev_index, 0));
+    const int64_t n_contrib = (int64_t)hp.n_anchor + B + (int64_t)B * K;
+    HIPCHK(c, launch_resolve(e_src, n_contrib, hp.n_anchor, hp.n_slots, B, K, ptr<float>(c->coef),
+                             ptr<int32_t>(c->win), ptr<float>(c->rec_coef), ptr<int32_t>(c->rec_row), stream));
     TableArgs te{};
     te.P = c->prm.E.p; te.Mo = c->prm.E.m; te.Vo = c->prm.E.v;
-    te.uniq = ptr<int32_t>(c->uniq); te.seg_off = ptr<int32_t>(c->seg_off); te.src = e_src;
-    te.n_uniq_dev = ptr<int32_t>(c->n_uniq); te.d = d; te.n_rowsrc = hp.n_anchor; te.row_base = hp.n_slots;
-    te.src_is_row = false; te.B = B; te.K = K; te.dact = ptr<float>(c->dact); te.act = ptr<float>(c->act);
-    te.coef = ptr<float>(c->coef); te.win = ptr<int32_t>(c->win); te.g_out = apply ? nullptr : ptr<float>(c->gE);
+    te.uniq = ptr<int32_t>(c->uniq); te.seg_off = ptr<int32_t>(c->seg_off);
+    te.n_uniq_dev = ptr<int32_t>(c->n_uniq); te.d = d;
+    te.rec_coef = ptr<float>(c->rec_coef); te.rec_row = ptr<int32_t>(c->rec_row);
+    te.dact = ptr<float>(c->dact); te.act = ptr<float>(c->act); te.g_out = apply ? nullptr : ptr<float>(c->gE);
     TableArgs tr = te;
     tr.P = c->prm.R.p; tr.Mo = c->prm.R.m; tr.Vo = c->prm.R.v;
-    tr.uniq = pl->d_r_uniq; tr.seg_off = pl->d_r_seg_off; tr.src = pl->d_r_src; tr.n_uniq_dev = pl->d_n_r_uniq;
-    tr.src_is_row = true; tr.g_out = apply ? nullptr : ptr<float>(c->gR);
-
-    if (c->n_side) HIPCHK(c, hipStreamWaitEvent(stream, c->ev_index, 0));
+    tr.uniq = pl->d_r_uniq; tr.seg_off = pl->d_r_seg_off; tr.n_uniq_dev = pl->d_n_r_uniq;
+    tr.rec_coef = nullptr; tr.rec_row = pl->d_r_rec; tr.g_out = apply ? nullptr : ptr<float>(c->gR);
     Lanes L{c, stream};
     HIPCHK(c, L.fork(3));
     { Timed tm(c, NGDB_TK_TABLE_E, L.lane(0)); HIPCHK(c, launch_table_update(te, ah, L.lane(0))); }
@@ -515,7 +519,7 @@ void ngdb_destroy(ngdb_ctx_t* c) {
     (void)hipDeviceSynchronize();
     DevBuf* all[] = {&c->act, &c->dact, &c->Z[0], &c->Z[1], &c->Z[2], &c->H[0], &c->H[1], &c->H[2], &c->dH[0],
                      &c->dH[1], &c->dH[2], &c->Att, &c->dAtt, &c->Dx, &c->score, &c->coef, &c->win,
-                     &c->loss_terms, &c->keys_a, &c->keys_b, &c->vals_a, &c->vals_b, &c->hist, &c->scan_tmp,
+                     &c->loss_terms, &c->rec_coef, &c->rec_row, &c->keys_a, &c->keys_b, &c->vals_a, &c->vals_b, &c->hist, &c->scan_tmp,
                      &c->uniq, &c->seg_off, &c->n_uniq, &c->gW, &c->gE, &c->gR, &c->colsum_part};
     for (DevBuf* b : all) release(*b);
     for (int i = 0; i < 4; ++i) {
@@ -619,11 +623,13 @@ int ngdb_plan(ngdb_ctx_t* c, const ngdb_query_batch* qb, ngdb_plan_t** out) {
         if (v.empty()) blob.resize(blob.size() + 4, 0);
         return off;
     };
+    std::vector<int32_t> r_rec(hp.r_src.size());     // relation contributions are gradient rows
+    for (size_t i = 0; i < r_rec.size(); ++i) r_rec[i] = -1 - hp.r_src[i];
     std::vector<int32_t> ekeys = hp.anchor_ent;
     ekeys.insert(ekeys.end(), hp.pos.begin(), hp.pos.end());
     const size_t o_ref = put(hp.in_ref), o_gs = put(hp.in_gslot), o_rel = put(hp.rel), o_ro = put(hp.root_off),
                  o_rs = put(hp.root_slot), o_pos = put(hp.pos), o_ek = put(ekeys), o_ru = put(hp.r_uniq),
-                 o_rso = put(hp.r_seg_off), o_rsrc = put(hp.r_src),
+                 o_rso = put(hp.r_seg_off), o_rsrc = put(hp.r_src), o_rrec = put(r_rec),
                  o_nru = put(std::vector<int32_t>{(int32_t)hp.r_uniq.size()});
     // a recycled blob (its last reader has finished) or a new one
     PlanBlob pb;
@@ -660,7 +666,7 @@ int ngdb_plan(ngdb_ctx_t* c, const ngdb_query_batch* qb, ngdb_plan_t** out) {
     pl->d_in_ref = pl->d_blob + o_ref; pl->d_in_gslot = pl->d_blob + o_gs; pl->d_rel = pl->d_blob + o_rel;
     pl->d_root_off = pl->d_blob + o_ro; pl->d_root_slot = pl->d_blob + o_rs; pl->d_pos = pl->d_blob + o_pos;
     pl->d_ekeys_head = pl->d_blob + o_ek; pl->d_r_uniq = pl->d_blob + o_ru; pl->d_r_seg_off = pl->d_blob + o_rso;
-    pl->d_r_src = pl->d_blob + o_rsrc; pl->d_n_r_uniq = pl->d_blob + o_nru;
+    pl->d_r_src = pl->d_blob + o_rsrc; pl->d_r_rec = pl->d_blob + o_rrec; pl->d_n_r_uniq = pl->d_blob + o_nru;
     *out = pl;
     return NGDB_OK;
 }

@@ -158,21 +158,21 @@ struct TableArgs {
     float *P, *Mo, *Vo;            // table and moments [rows, d]
     const int32_t* uniq;           // [n_uniq] row ids
     const int32_t* seg_off;        // [n_uniq+1]
-    const int32_t* src;            // contributions in segment order
     const int32_t* n_uniq_dev;     // device scalar
     int d;
-    // contribution decoding: c < n_rowsrc -> gradient row (entity table: dact row
-    // row_base + c; relation table: dact row src itself with n_rowsrc = INT_MAX);
-    // otherwise a (query, candidate) pair.
-    int n_rowsrc, row_base;
-    bool src_is_row;               // relation table: src values are dact rows
-    int B, K;
+    // contribution records in segment order: rec_row[t] >= 0 is a row of act and
+    // the contribution is rec_coef[t] * sign(act row - table row); rec_row[t] < 0 is
+    // row -1-rec_row[t] of dact, added as it is (rec_coef may be null if all are)
+    const float* rec_coef;
+    const int32_t* rec_row;
     const float* dact;
     const float* act;
-    const float* coef;
-    const int32_t* win;
     float* g_out;                  // if set: write gradients [n_uniq, d] instead of updating
 };
+// sorted contribution numbers -> records: c < n_rowsrc is gradient row row_base + c,
+// otherwise a (query, candidate) pair in the order [B positives | B*K negatives]
+hipError_t launch_resolve(const int32_t* src, int64_t n, int n_rowsrc, int row_base, int B, int K, const float* coef,
+                          const int32_t* win, float* rec_coef, int32_t* rec_row, hipStream_t s);
 hipError_t launch_table_update(const TableArgs& a, const AdamHyper& hp, hipStream_t s);
 
 }  // namespace ngdb

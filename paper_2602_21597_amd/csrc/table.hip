@@ -1,19 +1,51 @@
 // Segmented scatter-add of embedding-table gradients fused with the row-sparse
 // Adam update (Sec. 4.2: scatter through precomputed offsets; Alg. 1,
-// OptimizerStep).  One wavefront owns one touched row: it reads the row once,
-// sums the row's contributions in index order (no atomics), and writes the
-// parameter and both moments back -- 6 row transfers per touched row, which is
-// the algorithmic minimum for Adam.
+// OptimizerStep).  One wavefront owns one touched row: it reads the row and its
+// two moments once, sums the row's contributions in index order (no atomics),
+// and writes all three back -- 6 row transfers per touched row, the algorithmic
+// minimum for Adam.
 //
 // A contribution is either a gradient row of the arena (anchors; projections
 // for the relation table) or a (query, candidate) pair of the scoring pass, for
 // which dL/dE[e] = coef * sign(y_win - E[e]) is rebuilt from the 4-byte
 // coefficient, the winning branch's embedding (cache resident) and the row the
-// wavefront already holds.
+// wavefront already holds.  A small kernel first resolves the sorted
+// contribution numbers into (coefficient, source row) records laid out in
+// segment order, so that the row kernel reads them with one coalesced load per
+// 64 contributions instead of chasing three dependent indices per contribution;
+// source rows are then fetched four at a time before they are consumed.
 #include "common.h"
 
 namespace ngdb {
 namespace {
+
+// rec_row[t] >= 0: row of act (pair contribution, rec_coef[t] = dL/ds);
+// rec_row[t] < 0: row -1-rec_row[t] of dact (gradient row, added as is)
+__global__ __launch_bounds__(256) void resolve_kernel(const int32_t* __restrict__ src, int64_t n, int n_rowsrc,
+                                                      int row_base, int B, int K, const float* __restrict__ coef,
+                                                      const int32_t* __restrict__ win, float* __restrict__ rec_coef,
+                                                      int32_t* __restrict__ rec_row) {
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < n; t += (int64_t)gridDim.x * blockDim.x) {
+        const int32_t c = src[t];
+        if (c < n_rowsrc) {
+            rec_coef[t] = 0.f;
+            rec_row[t] = -1 - (row_base + c);
+        } else {
+            const int r = c - n_rowsrc;
+            int pair;
+            if (r < B) {
+                pair = r * (K + 1);                       // the query's positive
+            } else {
+                const int q = (r - B) / K;
+                pair = q * (K + 1) + 1 + ((r - B) - q * K);
+            }
+            rec_coef[t] = coef[pair];
+            rec_row[t] = win[pair];
+        }
+    }
+}
+
+constexpr int G = 4;   // source rows in flight per wavefront
 
 template <int NCH>
 __global__ __launch_bounds__(256) void table_kernel(const TableArgs a, const AdamHyper hp) {
@@ -23,87 +55,109 @@ __global__ __launch_bounds__(256) void table_kernel(const TableArgs a, const Ada
     const int wave_global = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int n_waves = (gridDim.x * blockDim.x) >> 6;
     const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    const bool update = a.g_out == nullptr;
+    bool col_ok[NCH];
+    int colc[NCH];
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) {
+        col_ok[ch] = ch * 64 + lane < d4;
+        colc[ch] = min(ch * 64 + lane, d4 - 1);       // clamped: loads never branch
+    }
 
     for (int u = wave_global; u < n_uniq; u += n_waves) {
         const int32_t row = a.uniq[u];
         const int t0 = a.seg_off[u], t1 = a.seg_off[u + 1];
         float4* prow = reinterpret_cast<float4*>(a.P + (size_t)row * a.d);
-        float4 p[NCH], g[NCH];
-#pragma unroll
-        for (int ch = 0; ch < NCH; ++ch) {
-            const int col = ch * 64 + lane;
-            p[ch] = col < d4 ? prow[col] : zero4;
-            g[ch] = zero4;
-        }
-        for (int t = t0; t < t1; ++t) {
-            const int32_t c = a.src[t];
-            if (a.src_is_row || c < a.n_rowsrc) {
-                const float4* grow =
-                    reinterpret_cast<const float4*>(a.dact + (size_t)(a.src_is_row ? c : a.row_base + c) * a.d);
-#pragma unroll
-                for (int ch = 0; ch < NCH; ++ch) {
-                    const int col = ch * 64 + lane;
-                    if (col < d4) {
-                        const float4 x = grow[col];
-                        g[ch].x += x.x; g[ch].y += x.y; g[ch].z += x.z; g[ch].w += x.w;
-                    }
-                }
-            } else {
-                int pair;
-                const int r = c - a.n_rowsrc;
-                if (r < a.B) {
-                    pair = r * (a.K + 1);                      // the query's positive
-                } else {
-                    const int q = (r - a.B) / a.K;
-                    pair = q * (a.K + 1) + 1 + ((r - a.B) - q * a.K);
-                }
-                const float coef = a.coef[pair];
-                const float4* y = reinterpret_cast<const float4*>(a.act + (size_t)a.win[pair] * a.d);
-#pragma unroll
-                for (int ch = 0; ch < NCH; ++ch) {
-                    const int col = ch * 64 + lane;
-                    if (col < d4) {
-                        const float4 yy = y[col];
-                        g[ch].x += coef * sgn(yy.x - p[ch].x);
-                        g[ch].y += coef * sgn(yy.y - p[ch].y);
-                        g[ch].z += coef * sgn(yy.z - p[ch].z);
-                        g[ch].w += coef * sgn(yy.w - p[ch].w);
-                    }
-                }
-            }
-        }
-        if (a.g_out) {
-            float4* orow = reinterpret_cast<float4*>(a.g_out + (size_t)u * a.d);
-#pragma unroll
-            for (int ch = 0; ch < NCH; ++ch) {
-                const int col = ch * 64 + lane;
-                if (col < d4) orow[col] = g[ch];
-            }
-            continue;
-        }
         float4* mrow = reinterpret_cast<float4*>(a.Mo + (size_t)row * a.d);
         float4* vrow = reinterpret_cast<float4*>(a.Vo + (size_t)row * a.d);
+        float4 p[NCH], m[NCH], v[NCH], g[NCH];
 #pragma unroll
         for (int ch = 0; ch < NCH; ++ch) {
-            const int col = ch * 64 + lane;
-            if (col < d4) {
-                float4 m = mrow[col], v = vrow[col];
+            p[ch] = prow[colc[ch]];
+            if (update) {
+                m[ch] = mrow[colc[ch]];
+                v[ch] = vrow[colc[ch]];
+            }
+            g[ch] = zero4;
+        }
+        for (int base = t0; base < t1; base += 64) {
+            const int n = min(64, t1 - base);
+            const int tl = base + min(lane, n - 1);
+            const int32_t my_row = a.rec_row[tl];
+            const float my_coef = a.rec_coef ? a.rec_coef[tl] : 0.f;
+            for (int j0 = 0; j0 < n; j0 += G) {
+                float4 x[G][NCH];
+                float cf[G];
+                bool is_pair[G];
+                float wgt[G];
+#pragma unroll
+                for (int q = 0; q < G; ++q) {
+                    const int j = min(j0 + q, n - 1);
+                    const int32_t r = __shfl(my_row, j, 64);
+                    cf[q] = __shfl(my_coef, j, 64);
+                    is_pair[q] = r >= 0;
+                    wgt[q] = j0 + q < n ? 1.f : 0.f;        // padding entries of the last group add nothing
+                    const float4* srow = reinterpret_cast<const float4*>(
+                        r >= 0 ? a.act + (size_t)r * a.d : a.dact + (size_t)(-1 - r) * a.d);
+#pragma unroll
+                    for (int ch = 0; ch < NCH; ++ch) x[q][ch] = srow[colc[ch]];
+                }
+#pragma unroll
+                for (int q = 0; q < G; ++q) {
+                    const float c = cf[q] * wgt[q];
+#pragma unroll
+                    for (int ch = 0; ch < NCH; ++ch) {
+                        const float4 y = x[q][ch];
+                        if (is_pair[q]) {
+                            g[ch].x += c * sgn(y.x - p[ch].x);
+                            g[ch].y += c * sgn(y.y - p[ch].y);
+                            g[ch].z += c * sgn(y.z - p[ch].z);
+                            g[ch].w += c * sgn(y.w - p[ch].w);
+                        } else {
+                            g[ch].x += wgt[q] * y.x;
+                            g[ch].y += wgt[q] * y.y;
+                            g[ch].z += wgt[q] * y.z;
+                            g[ch].w += wgt[q] * y.w;
+                        }
+                    }
+                }
+            }
+        }
+        if (!update) {
+            float4* orow = reinterpret_cast<float4*>(a.g_out + (size_t)u * a.d);
+#pragma unroll
+            for (int ch = 0; ch < NCH; ++ch)
+                if (col_ok[ch]) orow[ch * 64 + lane] = g[ch];
+            continue;
+        }
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch) {
+            if (col_ok[ch]) {
                 const float b1 = hp.beta1, b2 = hp.beta2;
 #define NGDB_ADAM(F)                                                             \
-    m.F = b1 * m.F + (1.f - b1) * g[ch].F;                                       \
-    v.F = b2 * v.F + (1.f - b2) * g[ch].F * g[ch].F;                             \
-    p[ch].F -= hp.lr * (m.F / hp.bc1) / (sqrtf(v.F / hp.bc2) + hp.eps);
+    m[ch].F = b1 * m[ch].F + (1.f - b1) * g[ch].F;                               \
+    v[ch].F = b2 * v[ch].F + (1.f - b2) * g[ch].F * g[ch].F;                     \
+    p[ch].F -= hp.lr * (m[ch].F / hp.bc1) / (sqrtf(v[ch].F / hp.bc2) + hp.eps);
                 NGDB_ADAM(x) NGDB_ADAM(y) NGDB_ADAM(z) NGDB_ADAM(w)
 #undef NGDB_ADAM
-                mrow[col] = m;
-                vrow[col] = v;
-                prow[col] = p[ch];
+                mrow[ch * 64 + lane] = m[ch];
+                vrow[ch * 64 + lane] = v[ch];
+                prow[ch * 64 + lane] = p[ch];
             }
         }
     }
 }
 
 }  // namespace
+
+hipError_t launch_resolve(const int32_t* src, int64_t n, int n_rowsrc, int row_base, int B, int K, const float* coef,
+                          const int32_t* win, float* rec_coef, int32_t* rec_row, hipStream_t s) {
+    if (n <= 0) return hipSuccess;
+    const unsigned blocks = (unsigned)std::min<int64_t>((n + 255) / 256, 4096);
+    hipLaunchKernelGGL(resolve_kernel, dim3(blocks), dim3(256), 0, s, src, n, n_rowsrc, row_base, B, K, coef, win,
+                       rec_coef, rec_row);
+    return hipGetLastError();
+}
 
 hipError_t launch_table_update(const TableArgs& a, const AdamHyper& hp, hipStream_t s) {
     // the number of touched rows is only known on the device: a fixed grid walks them
