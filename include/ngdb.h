@@ -67,6 +67,7 @@ extern "C" {
 #define NGDB_MAX_CARD    8    /* inputs of one intersection             */
 #define NGDB_MAX_LEVELS 64    /* operator depth of one query            */
 #define NGDB_MAX_BRANCH 64    /* conjunctive branches of one query      */
+#define NGDB_MAX_TOPK   16    /* entities returned per query by the all-entity ranking */
 
 typedef struct ngdb_ctx_s ngdb_ctx_t;     /* opaque: configuration, workspace, streams */
 typedef struct ngdb_plan_s ngdb_plan_t;   /* opaque: one planned batch                 */

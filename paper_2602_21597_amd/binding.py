@@ -345,6 +345,16 @@ class Engine:
         _check(lib().ngdb_get_grads(self.ctx, C.byref(gv)), self.ctx)
         return int(gv.n_e_uniq)
 
+    def rank_all(self, plan, k, stream=None):
+        """All-entity ranking: ([B, k] int32 ids, [B, k] float32 L1 distances), ascending, device tensors."""
+        t = self.torch
+        B = plan.export()["n_queries"]
+        ids = t.empty((B, k), dtype=t.int32, device=self.device)
+        dist = t.empty((B, k), dtype=t.float32, device=self.device)
+        _check(lib().ngdb_score(self.ctx, plan.handle, None, 0, int(k), None, ids.data_ptr(), dist.data_ptr(),
+                                self._stream(stream)), self.ctx)
+        return ids, dist
+
     def step_count(self):
         return int(lib().ngdb_step_count(self.ctx))
 

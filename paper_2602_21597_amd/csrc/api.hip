@@ -73,6 +73,7 @@ struct ngdb_ctx_s {
     DevBuf act, dact, Z[3], H[3], dH[3], Att, dAtt, Dx;
     DevBuf score, coef, win, loss_terms, rec_coef, rec_row;
     DevBuf keys_a, keys_b, vals_a, vals_b, hist, scan_tmp, uniq, seg_off, n_uniq;
+    DevBuf rank_dist;   // distances of one entity chunk in the all-entity ranking
     DevBuf colsum_part; // 6 scratch areas of the bias-gradient column sums
     DevBuf gW;          // gradients of the 12 MLP tensors, packed
     DevBuf gE, gR;      // compact table gradients (ngdb_forward_backward only)
@@ -520,7 +521,7 @@ void ngdb_destroy(ngdb_ctx_t* c) {
     DevBuf* all[] = {&c->act, &c->dact, &c->Z[0], &c->Z[1], &c->Z[2], &c->H[0], &c->H[1], &c->H[2], &c->dH[0],
                      &c->dH[1], &c->dH[2], &c->Att, &c->dAtt, &c->Dx, &c->score, &c->coef, &c->win,
                      &c->loss_terms, &c->rec_coef, &c->rec_row, &c->keys_a, &c->keys_b, &c->vals_a, &c->vals_b, &c->hist, &c->scan_tmp,
-                     &c->uniq, &c->seg_off, &c->n_uniq, &c->gW, &c->gE, &c->gR, &c->colsum_part};
+                     &c->uniq, &c->seg_off, &c->n_uniq, &c->gW, &c->gE, &c->gR, &c->colsum_part, &c->rank_dist};
     for (DevBuf* b : all) release(*b);
     for (int i = 0; i < 4; ++i) {
         if (c->side[i]) (void)hipStreamDestroy(c->side[i]);
@@ -719,23 +720,42 @@ int ngdb_score(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_cand, int3
     if (!c->bound) return fail(c, NGDB_ERR_STATE, "parameters not bound");
     if (pl->n_entities != c->cfg.n_entities || !pl->d_blob)
         return fail(c, NGDB_ERR_ARG, "plan belongs to another configuration or was built without a device");
-    (void)topk; (void)d_topk_ids; (void)d_topk_dist;
-    if (!d_cand) return fail(c, NGDB_ERR_UNSUPPORTED, "all-entity ranking is not built yet");
-    if (C <= 0 || !d_scores) return fail(c, NGDB_ERR_ARG, "candidate mode needs C > 0 and d_scores");
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (d_cand) {
+        if (C <= 0 || !d_scores) return fail(c, NGDB_ERR_ARG, "candidate mode needs C > 0 and d_scores");
+    } else if (topk < 1 || topk > NGDB_MAX_TOPK || !d_topk_ids || !d_topk_dist) {
+        return fail(c, NGDB_ERR_ARG, "all-entity mode needs 1 <= topk <= NGDB_MAX_TOPK and both output arrays");
+    }
     c->have_grads = false;
     int rc = size_workspace(c, pl, 0, false);
     if (rc != NGDB_OK) return rc;
     rc = enqueue_forward(c, pl, s);
     if (rc != NGDB_OK) return rc;
-    ScoreArgs sa{};
-    sa.act = ptr<float>(c->act); sa.E = c->prm.E.p; sa.root_off = pl->d_root_off; sa.root_slot = pl->d_root_slot;
-    sa.pos = nullptr; sa.cand = d_cand; sa.B = pl->hp.n_queries; sa.C = C; sa.d = c->cfg.d;
-    sa.max_branch = std::max(1, pl->hp.max_branch); sa.gamma = c->cfg.gamma; sa.score = d_scores;
-    hipError_t e;
-    { Timed tm(c, NGDB_TK_SCORE, s); e = launch_score(sa, false, s); }
-    if (e == hipErrorInvalidValue) return fail(c, NGDB_ERR_UNSUPPORTED, "embedding width / union branch count too large for the scoring kernel");
-    HIPCHK(c, e);
+    if (d_cand) {
+        ScoreArgs sa{};
+        sa.act = ptr<float>(c->act); sa.E = c->prm.E.p; sa.root_off = pl->d_root_off; sa.root_slot = pl->d_root_slot;
+        sa.pos = nullptr; sa.cand = d_cand; sa.B = pl->hp.n_queries; sa.C = C; sa.d = c->cfg.d;
+        sa.max_branch = std::max(1, pl->hp.max_branch); sa.gamma = c->cfg.gamma; sa.score = d_scores;
+        hipError_t e;
+        { Timed tm(c, NGDB_TK_SCORE, s); e = launch_score(sa, false, s); }
+        if (e == hipErrorInvalidValue) return fail(c, NGDB_ERR_UNSUPPORTED, "embedding width / union branch count too large for the scoring kernel");
+        HIPCHK(c, e);
+    } else {
+        // entity chunks: distances of every branch row to the chunk, then the running top-k
+        const int N = c->cfg.n_entities, d = c->cfg.d, R = pl->hp.n_roots;
+        const int chunk = std::min(N, 1 << 16);
+        const int ld = (chunk + 3) & ~3;
+        rc = ensure(c, c->rank_dist, std::max<size_t>((size_t)R * ld * sizeof(float), 256));
+        if (rc != NGDB_OK) return rc;
+        Timed tm(c, NGDB_TK_SCORE, s);
+        for (int e0 = 0; e0 < N; e0 += chunk) {
+            const int cnt = std::min(chunk, N - e0);
+            HIPCHK(c, launch_l1_tile(ptr<float>(c->act), pl->d_root_slot, R, c->prm.E.p + (size_t)e0 * d, cnt, d,
+                                     ptr<float>(c->rank_dist), ld, s));
+            HIPCHK(c, launch_topk_merge(ptr<float>(c->rank_dist), ld, pl->d_root_off, pl->hp.n_queries, e0, cnt, topk,
+                                        e0 == 0, d_topk_dist, d_topk_ids, s));
+        }
+    }
     HIPCHK(c, hipEventRecord(pl->blob.last_use, s));
     return NGDB_OK;
 }

@@ -136,6 +136,15 @@ struct ScoreArgs {
 };
 hipError_t launch_score(const ScoreArgs& a, bool train, hipStream_t s);
 
+// ---------------------------------------------------------------- ranking (rank.hip)
+// dist[r*ld + e] = ||act[row_ids[r]] - Emat[e]||_1 for r < n_rows, e < n_ent
+hipError_t launch_l1_tile(const float* act, const int32_t* row_ids, int n_rows, const float* Emat, int n_ent, int d,
+                          float* dist, int ld, hipStream_t s);
+// per query q: entity value = min over rows root_off[q]..root_off[q+1]-1 of dist; merges the
+// k best (value, ent_base + e) of this chunk into out_dist/out_ids [n_queries, k]
+hipError_t launch_topk_merge(const float* dist, int ld, const int32_t* root_off, int n_queries, int ent_base, int n_ent,
+                             int k, bool first_chunk, float* out_dist, int32_t* out_ids, hipStream_t s);
+
 // ---------------------------------------------------------------- index (index.hip)
 struct IndexBuffers {   // device scratch owned by the context, sized for n_keys
     int32_t *keys_a, *keys_b, *vals_a, *vals_b;   // [n_keys]

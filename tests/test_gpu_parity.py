@@ -108,6 +108,39 @@ def test_candidate_scores_against_oracle():
     par.assert_close(got, want, "candidate scores")
 
 
+def _check_topk(case, k, n_check):
+    import torch
+    eng = case.engine()
+    plan = eng.plan(case.qb)
+    ids, dist = eng.rank_all(plan, k)
+    torch.cuda.synchronize()
+    ids, dist = ids.cpu().numpy(), dist.cpu().numpy()
+    M = om.Model(case.params, case.gamma)
+    assert np.all(np.diff(dist, axis=1) >= 0)
+    for q in np.random.default_rng(1).choice(case.B, min(n_check, case.B), replace=False):
+        full = orank.distances_all(case.qb, int(q), M)
+        ref_ids, ref_d = orank.topk_all(case.qb, int(q), M, k)
+        par.assert_close(dist[q], ref_d, "top-k distances q%d" % q)
+        # a returned id is right if its true distance is within the k-th best (fp32 may swap near ties)
+        assert len(set(ids[q])) == k and ids[q].min() >= 0
+        assert np.all(full[ids[q]] <= ref_d[-1] * (1 + 1e-4)), "q%d" % q
+        par.assert_close(dist[q], full[ids[q]], "returned distances belong to returned ids q%d" % q)
+    plan.free()
+
+
+def test_all_entity_topk_small_and_ragged():
+    _say("ngdb_score all-entity mode: N=1000 (one ragged chunk), k=10 and k=16; N=300 d=64, k=1")
+    _check_topk(par.Case.from_config(0), 10, 64)
+    _check_topk(par.Case.from_config(0), 16, 16)
+    _check_topk(par.Case(300, 9, 64, 128, 20, 2, 8.0, seed=31), 1, 20)
+
+
+def test_all_entity_topk_many_chunks():
+    _say("ngdb_score all-entity mode: N=150000 (3 chunks), d=400, 200 queries incl. unions, k=10")
+    case = par.Case(150000, 40, 400, 800, 200, 2, 24.0, seed=32, T=400000)
+    _check_topk(case, 10, 12)
+
+
 def test_fb15k237_shape_full_size():
     # the benchmark workload itself, in the launch configuration bench.py times
     _say("config 1 (B=512, K=128, d=400), forward_backward + 1 train step")
