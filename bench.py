@@ -103,7 +103,7 @@ def main():
     torch.cuda.synchronize()
 
     timed = ("score", "table_E") if not args.all_classes else \
-        ("index", "gather", "gemm_fwd", "inter", "score", "gemm_bwd", "wgrad", "table_E", "table_R", "adam")
+        ("index", "sem", "gemm_fwd", "inter", "score", "gemm_bwd", "wgrad", "table_E", "table_R", "adam")
     eng.set_timing(timed)
     eng.get_timing(reset=True)
     touched = 0

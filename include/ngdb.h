@@ -21,6 +21,12 @@
  *   union         disjunctive normal form; score = max over branches
  *   score         s(q,e) = gamma - min_b ||y_b - E[e]||_1
  *   loss          1/(2B) sum_i [ -log sig(s(q_i,pos_i)) - 1/K sum_j log sig(-s(q_i,neg_ij)) ]
+ *   entity row    with text features (d_sem > 0) every entity row that is read --
+ *                 anchors, positives, negatives, ranking -- is
+ *                 Ef[e] = E[e] + bf16(Wp) H_sem[e]  (Sec. 4.4: cached encoder
+ *                 outputs, gathered per batch, linear projection to width d);
+ *                 bf16 products accumulated in fp32; H_sem is frozen, Wp is kept
+ *                 in fp32, rounded to bf16 for every step and trained with Adam
  *   optimiser     Adam; dense on the MLP tensors, row-sparse (lazy) on E and R:
  *                 a table row is updated only in steps in which it received a
  *                 gradient contribution; the bias correction uses the global step.
@@ -77,7 +83,8 @@ typedef struct ngdb_config {
     int32_t n_relations;
     int32_t d;             /* embedding width (multiple of 4)                        */
     int32_t h;             /* hidden width of the three MLPs (multiple of 4)         */
-    int32_t d_sem;         /* width of the frozen text features, 0 = none            */
+    int32_t d_sem;         /* width of the frozen text features, 0 = none; otherwise
+                              a multiple of 64, and d a multiple of 8                */
     int32_t num_streams;   /* 1 = everything on the caller's stream; 2..4 = the
                               independent operator groups of one depth run on this
                               many library-owned streams (Sec. 4.3 "Multi-stream
@@ -251,7 +258,7 @@ int ngdb_debug_copy(void* d_dst, const void* d_src, size_t bytes, void* stream);
  * runs untouched.  ngdb_get_timing waits for the device, adds the elapsed times
  * of all brackets recorded since the last call, and optionally clears the sums. */
 #define NGDB_TK_INDEX     0   /* gradient index: radix sort + segment heads        */
-#define NGDB_TK_GATHER    1   /* row gathers of operator inputs                    */
+#define NGDB_TK_SEM       1   /* text features: fused rows and projection gradient */
 #define NGDB_TK_GEMM_FWD  2   /* forward MLP contractions                          */
 #define NGDB_TK_INTER     3   /* intersection pooling, forward and backward        */
 #define NGDB_TK_SCORE     4   /* fused L1 score + loss + dL/ds                     */

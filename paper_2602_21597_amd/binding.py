@@ -65,7 +65,7 @@ class GradView(C.Structure):
                 ("pair_score", C.c_void_p), ("loss_terms", C.c_void_p)]
 
 
-TIMING_CLASSES = ("index", "gather", "gemm_fwd", "inter", "score", "gemm_bwd", "wgrad", "table_E", "table_R",
+TIMING_CLASSES = ("index", "sem", "gemm_fwd", "inter", "score", "gemm_bwd", "wgrad", "table_E", "table_R",
                   "adam")
 
 
@@ -229,20 +229,32 @@ class Engine:
         self._loss = torch.zeros(1, dtype=torch.float32, device=self.device)
 
     # ---- parameters
-    def bind_numpy(self, params, step=0):
-        """Uploads fp32 numpy parameters, creates zero moments, binds them."""
+    def tensor_names(self):
+        return TENSOR_NAMES + (("Wp",) if self.cfg.d_sem else ())
+
+    def bind_numpy(self, params, step=0, sem_bits=None):
+        """Uploads fp32 numpy parameters, creates zero moments, binds them.  With text features
+        (d_sem > 0) params holds "Wp" and sem_bits is the [N, d_sem] uint16 array of bf16 patterns."""
         t = self.torch
         self.tensors = {}
-        for name in TENSOR_NAMES:
+        for name in self.tensor_names():
             p = t.from_numpy(np.ascontiguousarray(params[name], np.float32)).to(self.device)
             self.tensors[name] = (p, t.zeros_like(p), t.zeros_like(p))
+        self.H_sem = None
+        if self.cfg.d_sem:
+            assert sem_bits is not None and sem_bits.dtype == np.uint16
+            assert sem_bits.shape == (self.cfg.n_entities, self.cfg.d_sem)
+            # int16 carries the bit patterns: torch has no uint16 arithmetic, none is needed
+            self.H_sem = t.from_numpy(np.ascontiguousarray(sem_bits).view(np.int16)).to(self.device)
         self.bind(step)
 
     def bind(self, step=0):
         P = Params()
-        for name in TENSOR_NAMES:
+        for name in self.tensor_names():
             p, m, v = self.tensors[name]
             setattr(P, name, Tensor(p.data_ptr(), m.data_ptr(), v.data_ptr()))
+        if self.H_sem is not None:
+            P.H_sem = self.H_sem.data_ptr()
         P.step = int(step)
         _check(lib().ngdb_bind_params(self.ctx, C.byref(P)), self.ctx)
 
@@ -315,6 +327,8 @@ class Engine:
         shapes = [(h, d), (h,), (d, h), (d,)] * 3
         for i, name in enumerate(MLP_NAMES):
             out[name] = copy_to_host(gv.g_mlp[i], shapes[i], np.float32)
+        if gv.g_Wp:
+            out["Wp"] = copy_to_host(gv.g_Wp, (d, self.cfg.d_sem), np.float32)
         return out
 
     def score(self, plan, cand, stream=None):

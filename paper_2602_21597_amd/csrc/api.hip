@@ -77,6 +77,10 @@ struct ngdb_ctx_s {
     DevBuf colsum_part; // 6 scratch areas of the bias-gradient column sums
     DevBuf gW;          // gradients of the 12 MLP tensors, packed
     DevBuf gE, gR;      // compact table gradients (ngdb_forward_backward only)
+    // text-feature fusion: bf16 copy of Wp, fused rows of the touched entities, position of every
+    // contribution's entity in that list, operator references redirected to it, bf16 row gradients,
+    // split-wise partial sums and the gradient of Wp, fused rows of one ranking chunk
+    DevBuf Wb, Ef, inv, refs_sem, g_bf16, wp_partial, gWp, rank_ef;
     size_t gw_off[13]{};
     hipStream_t upload = nullptr;        // plan uploads, independent of the compute streams
     std::vector<PlanBlob> blob_pool;
@@ -245,6 +249,17 @@ int size_workspace(ngdb_ctx_t* c, const ngdb_plan_t* pl, int K, bool want_table_
         c->gw_off[12] = off;
         ENS(c->gW, off * f);
     }
+    if (c->cfg.d_sem > 0) {
+        const size_t ds = c->cfg.d_sem;
+        const size_t urows = (size_t)std::min<int64_t>(nk, c->cfg.n_entities);
+        ENS(c->Wb, d * ds * sizeof(uint16_t));
+        ENS(c->Ef, urows * d * f);
+        ENS(c->inv, (size_t)nk * 4);
+        ENS(c->refs_sem, hp.in_ref.size() * 4);
+        ENS(c->g_bf16, urows * d * sizeof(uint16_t));
+        ENS(c->wp_partial, (size_t)sem_wgrad_splits((int64_t)urows, (int)d, (int)ds) * d * ds * f);
+        ENS(c->gWp, d * ds * f);
+    }
     if (want_table_grads) {
         const size_t urows = (size_t)std::min<int64_t>(nk, c->cfg.n_entities);
         ENS(c->gE, urows * d * f);
@@ -254,9 +269,55 @@ int size_workspace(ngdb_ctx_t* c, const ngdb_plan_t* pl, int K, bool want_table_
     return NGDB_OK;
 }
 
+// Where the entity rows of one call come from: the table itself, or (text-feature fusion) the
+// fused rows of the touched entities, addressed by position in that list.
+struct EntRows {
+    const float* rows;
+    const int32_t* refs;   // operator input references (anchors as -1-row)
+    const int32_t* pos;    // [B] row of every query's positive
+    const int32_t* cand;   // [B, C] rows of the candidates
+};
+
+// Builds the index over [anchors | positives | tail] and, with text features, the fused rows
+// of its distinct entities and the references into them.  The index is left in the context's
+// buffers; *e_src receives the sorted contribution numbers.
+int prepare_entities(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_tail, int64_t n_tail, hipStream_t s_idx,
+                     hipStream_t stream, int32_t** e_src, EntRows* er) {
+    const HostPlan& hp = pl->hp;
+    const int B = hp.n_queries, d = c->cfg.d, ds = c->cfg.d_sem;
+    IndexBuffers ib{ptr<int32_t>(c->keys_a), ptr<int32_t>(c->keys_b), ptr<int32_t>(c->vals_a),
+                    ptr<int32_t>(c->vals_b), ptr<int32_t>(c->hist),   ptr<int32_t>(c->scan_tmp),
+                    ptr<int32_t>(c->uniq),   ptr<int32_t>(c->seg_off), ptr<int32_t>(c->n_uniq)};
+    {
+        Timed tm(c, NGDB_TK_INDEX, s_idx);
+        HIPCHK(c, build_segment_index(pl->d_ekeys_head, hp.n_anchor + B, d_tail, n_tail, c->cfg.n_entities, ib, e_src,
+                                      s_idx));
+    }
+    if (ds == 0) {
+        *er = EntRows{c->prm.E.p, pl->d_in_ref, pl->d_pos, d_tail};
+        return NGDB_OK;
+    }
+    // s_idx == stream in this mode: everything below needs the index
+    const int64_t n_contrib = (int64_t)hp.n_anchor + B + n_tail;
+    Timed tm(c, NGDB_TK_SEM, stream);
+    HIPCHK(c, launch_cast_bf16(c->prm.Wp.p, ptr<uint16_t>(c->Wb), (int64_t)d * ds, stream));
+    HIPCHK(c, launch_inverse_index(*e_src, ptr<int32_t>(c->seg_off), ptr<int32_t>(c->n_uniq), n_contrib,
+                                   ptr<int32_t>(c->inv), stream));
+    SemFuseArgs fa{};
+    fa.H = c->prm.H_sem; fa.Wb = ptr<uint16_t>(c->Wb); fa.E = c->prm.E.p; fa.ids = ptr<int32_t>(c->uniq);
+    fa.n_rows_dev = ptr<int32_t>(c->n_uniq); fa.n_rows = (int)std::min<int64_t>(n_contrib, c->cfg.n_entities);
+    fa.d = d; fa.ds = ds; fa.out = ptr<float>(c->Ef);
+    HIPCHK(c, launch_sem_fuse(fa, stream));
+    HIPCHK(c, launch_translate_refs(pl->d_in_ref, pl->d_in_gslot, (int)hp.in_ref.size(), hp.n_slots,
+                                    ptr<int32_t>(c->inv), ptr<int32_t>(c->refs_sem), stream));
+    *er = EntRows{ptr<float>(c->Ef), ptr<int32_t>(c->refs_sem), ptr<int32_t>(c->inv) + hp.n_anchor,
+                  ptr<int32_t>(c->inv) + hp.n_anchor + B};
+    return NGDB_OK;
+}
+
 // forward over the plan's frontiers; results in c->act.  The type segments of one
 // depth are independent: they share one grouped launch per MLP layer.
-int enqueue_forward(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t s) {
+int enqueue_forward(ngdb_ctx_t* c, const ngdb_plan_t* pl, const EntRows& er, hipStream_t s) {
     const int d = c->cfg.d, h = c->cfg.h;
     for (int l = 1; l <= pl->hp.n_levels; ++l) {
         const std::vector<Segment>& segs = pl->levels[l];
@@ -268,7 +329,7 @@ int enqueue_forward(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t s) {
             float* Hh = ptr<float>(c->H[sg.type]) + (size_t)sg.mlp_base * h;
             GemmArgs& a = g1[n];
             // first layer reads its rows through the plan's references and leaves a copy in Z
-            a.a_ref = pl->d_in_ref + sg.ref_off; a.a_base0 = ptr<float>(c->act); a.a_base1 = c->prm.E.p;
+            a.a_ref = er.refs + sg.ref_off; a.a_base0 = ptr<float>(c->act); a.a_base1 = er.rows;
             if (sg.rel_off >= 0) { a.a_add_idx = pl->d_rel + sg.rel_off; a.a_add = c->prm.R.p; }
             a.a_copy = Z; a.lda = d; a.B = W.Wa; a.ldb = d; a.C = Hh; a.ldc = h;
             a.M = sg.rows; a.N = h; a.K = d; a.bias = W.ba; a.relu = true;
@@ -381,31 +442,29 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
     if (rc != NGDB_OK) return rc;
 
     // 1. entity gradient index (depends only on the plan and the negatives)
-    IndexBuffers ib{ptr<int32_t>(c->keys_a), ptr<int32_t>(c->keys_b), ptr<int32_t>(c->vals_a),
-                    ptr<int32_t>(c->vals_b), ptr<int32_t>(c->hist),   ptr<int32_t>(c->scan_tmp),
-                    ptr<int32_t>(c->uniq),   ptr<int32_t>(c->seg_off), ptr<int32_t>(c->n_uniq)};
     int32_t* e_src = nullptr;
-    // the index is independent of the forward/backward passes: with library streams it runs beside them
-    hipStream_t s_idx = c->n_side ? c->side[0] : stream;
-    if (c->n_side) {
+    // without text features the index is independent of the forward/backward passes: with library
+    // streams it runs beside them
+    const bool sem = c->cfg.d_sem > 0;
+    const bool idx_aside = c->n_side && !sem;
+    hipStream_t s_idx = idx_aside ? c->side[0] : stream;
+    if (idx_aside) {
         HIPCHK(c, hipEventRecord(c->ev_fork, stream));
         HIPCHK(c, hipStreamWaitEvent(s_idx, c->ev_fork, 0));
     }
-    {
-        Timed tm(c, NGDB_TK_INDEX, s_idx);
-        HIPCHK(c, build_segment_index(pl->d_ekeys_head, hp.n_anchor + B, d_neg, (int64_t)B * K, c->cfg.n_entities,
-                                      ib, &e_src, s_idx));
-    }
-    if (c->n_side) HIPCHK(c, hipEventRecord(c->ev_index, s_idx));
+    EntRows er{};
+    rc = prepare_entities(c, pl, d_neg, (int64_t)B * K, s_idx, stream, &e_src, &er);
+    if (rc != NGDB_OK) return rc;
+    if (idx_aside) HIPCHK(c, hipEventRecord(c->ev_index, s_idx));
 
     // 2. forward frontiers
-    rc = enqueue_forward(c, pl, stream);
+    rc = enqueue_forward(c, pl, er, stream);
     if (rc != NGDB_OK) return rc;
 
     // 3. scores, loss terms, dL/ds, gradients of the branch embeddings
     ScoreArgs sa{};
-    sa.act = ptr<float>(c->act); sa.E = c->prm.E.p; sa.root_off = pl->d_root_off; sa.root_slot = pl->d_root_slot;
-    sa.pos = pl->d_pos; sa.cand = d_neg; sa.B = B; sa.C = K; sa.d = d; sa.max_branch = std::max(1, hp.max_branch);
+    sa.act = ptr<float>(c->act); sa.E = er.rows; sa.root_off = pl->d_root_off; sa.root_slot = pl->d_root_slot;
+    sa.pos = er.pos; sa.cand = er.cand; sa.B = B; sa.C = K; sa.d = d; sa.max_branch = std::max(1, hp.max_branch);
     sa.gamma = c->cfg.gamma; sa.score = ptr<float>(c->score); sa.coef = ptr<float>(c->coef);
     sa.win = ptr<int32_t>(c->win); sa.dact = ptr<float>(c->dact); sa.loss_terms = ptr<float>(c->loss_terms);
     {
@@ -425,7 +484,7 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
     AdamHyper ah{c->cfg.lr, c->cfg.beta1, c->cfg.beta2, c->cfg.eps,
                  (float)(1.0 - std::pow((double)c->cfg.beta1, (double)t)),
                  (float)(1.0 - std::pow((double)c->cfg.beta2, (double)t))};
-    if (c->n_side) HIPCHK(c, hipStreamWaitEvent(stream, c->ev_index, 0));
+    if (idx_aside) HIPCHK(c, hipStreamWaitEvent(stream, c->ev_index, 0));
     const int64_t n_contrib = (int64_t)hp.n_anchor + B + (int64_t)B * K;
     HIPCHK(c, launch_resolve(e_src, n_contrib, hp.n_anchor, hp.n_slots, B, K, ptr<float>(c->coef),
                              ptr<int32_t>(c->win), ptr<float>(c->rec_coef), ptr<int32_t>(c->rec_row), stream));
@@ -435,7 +494,9 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
     te.n_uniq_dev = ptr<int32_t>(c->n_uniq); te.d = d;
     te.rec_coef = ptr<float>(c->rec_coef); te.rec_row = ptr<int32_t>(c->rec_row);
     te.dact = ptr<float>(c->dact); te.act = ptr<float>(c->act); te.g_out = apply ? nullptr : ptr<float>(c->gE);
+    if (sem) { te.ref_rows = ptr<float>(c->Ef); te.g_bf16 = ptr<uint16_t>(c->g_bf16); }
     TableArgs tr = te;
+    tr.ref_rows = nullptr; tr.g_bf16 = nullptr;
     tr.P = c->prm.R.p; tr.Mo = c->prm.R.m; tr.Vo = c->prm.R.v;
     tr.uniq = pl->d_r_uniq; tr.seg_off = pl->d_r_seg_off; tr.n_uniq_dev = pl->d_n_r_uniq;
     tr.rec_coef = nullptr; tr.rec_row = pl->d_r_rec; tr.g_out = apply ? nullptr : ptr<float>(c->gR);
@@ -459,6 +520,22 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
         HIPCHK(c, launch_dense_adam(job, ah, L.lane(2)));
     }
     HIPCHK(c, L.join());
+    if (sem) {
+        // gradient of the text projection over the touched rows, then its Adam step
+        Timed tm(c, NGDB_TK_SEM, stream);
+        const int ds = c->cfg.d_sem;
+        SemWgradArgs wa{};
+        wa.H = c->prm.H_sem; wa.ids = ptr<int32_t>(c->uniq); wa.G = ptr<uint16_t>(c->g_bf16);
+        wa.n_rows_dev = ptr<int32_t>(c->n_uniq); wa.n_rows = (int)std::min<int64_t>(n_contrib, c->cfg.n_entities);
+        wa.d = d; wa.ds = ds; wa.n_splits = sem_wgrad_splits(wa.n_rows, d, ds); wa.partial = ptr<float>(c->wp_partial);
+        HIPCHK(c, launch_sem_wgrad(wa, ptr<float>(c->gWp), stream));
+        if (apply) {
+            DenseAdamJob job{};
+            job.p[0] = c->prm.Wp.p; job.m[0] = c->prm.Wp.m; job.v[0] = c->prm.Wp.v;
+            job.g[0] = ptr<float>(c->gWp); job.n[0] = (int64_t)d * ds; job.count = 1;
+            HIPCHK(c, launch_dense_adam(job, ah, stream));
+        }
+    }
 
     HIPCHK(c, hipEventRecord(pl->blob.last_use, stream));
     if (apply) c->step = t;
@@ -475,6 +552,7 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
     gv.gE = apply ? nullptr : ptr<float>(c->gE);
     gv.gR = apply ? nullptr : ptr<float>(c->gR);
     for (int i = 0; i < 12; ++i) gv.g_mlp[i] = ptr<float>(c->gW) + c->gw_off[i];
+    gv.g_Wp = sem ? ptr<float>(c->gWp) : nullptr;
     gv.act = ptr<float>(c->act);
     gv.dact = ptr<float>(c->dact);
     gv.n_grad_rows = hp.n_slots + hp.n_anchor;
@@ -495,7 +573,7 @@ int ngdb_create(const ngdb_config* cfg, ngdb_ctx_t** out) {
     if (cfg->n_entities <= 0 || cfg->n_relations <= 0 || cfg->d <= 0 || cfg->h <= 0 || (cfg->d & 3) ||
         (cfg->h & 3) || cfg->d > 1024 || cfg->num_streams < 1 || cfg->num_streams > 4 || cfg->d_sem < 0)
         return NGDB_ERR_ARG;
-    if (cfg->d_sem != 0) return NGDB_ERR_UNSUPPORTED;   // text-feature fusion is not built yet
+    if (cfg->d_sem != 0 && ((cfg->d_sem & 63) || (cfg->d & 7))) return NGDB_ERR_ARG;
     ngdb_ctx_t* c = new (std::nothrow) ngdb_ctx_s();
     if (!c) return NGDB_ERR_OOM;
     c->cfg = *cfg;
@@ -521,7 +599,8 @@ void ngdb_destroy(ngdb_ctx_t* c) {
     DevBuf* all[] = {&c->act, &c->dact, &c->Z[0], &c->Z[1], &c->Z[2], &c->H[0], &c->H[1], &c->H[2], &c->dH[0],
                      &c->dH[1], &c->dH[2], &c->Att, &c->dAtt, &c->Dx, &c->score, &c->coef, &c->win,
                      &c->loss_terms, &c->rec_coef, &c->rec_row, &c->keys_a, &c->keys_b, &c->vals_a, &c->vals_b, &c->hist, &c->scan_tmp,
-                     &c->uniq, &c->seg_off, &c->n_uniq, &c->gW, &c->gE, &c->gR, &c->colsum_part, &c->rank_dist};
+                     &c->uniq, &c->seg_off, &c->n_uniq, &c->gW, &c->gE, &c->gR, &c->colsum_part, &c->rank_dist,
+                     &c->Wb, &c->Ef, &c->inv, &c->refs_sem, &c->g_bf16, &c->wp_partial, &c->gWp, &c->rank_ef};
     for (DevBuf* b : all) release(*b);
     for (int i = 0; i < 4; ++i) {
         if (c->side[i]) (void)hipStreamDestroy(c->side[i]);
@@ -550,6 +629,12 @@ int ngdb_bind_params(ngdb_ctx_t* c, const ngdb_params* p) {
     for (const ngdb_tensor* t : ts) {
         if (!t->p || !t->m || !t->v) return fail(c, NGDB_ERR_ARG, "null parameter or moment tensor");
         if (((uintptr_t)t->p | (uintptr_t)t->m | (uintptr_t)t->v) & 15)
+            return fail(c, NGDB_ERR_ARG, "tensors must be 16-byte aligned");
+    }
+    if (c->cfg.d_sem > 0) {
+        if (!p->Wp.p || !p->Wp.m || !p->Wp.v || !p->H_sem)
+            return fail(c, NGDB_ERR_ARG, "text features configured: Wp (with moments) and H_sem are required");
+        if (((uintptr_t)p->Wp.p | (uintptr_t)p->Wp.m | (uintptr_t)p->Wp.v | (uintptr_t)p->H_sem) & 15)
             return fail(c, NGDB_ERR_ARG, "tensors must be 16-byte aligned");
     }
     if (p->step < 0) return fail(c, NGDB_ERR_ARG, "negative step count");
@@ -727,14 +812,21 @@ int ngdb_score(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_cand, int3
         return fail(c, NGDB_ERR_ARG, "all-entity mode needs 1 <= topk <= NGDB_MAX_TOPK and both output arrays");
     }
     c->have_grads = false;
-    int rc = size_workspace(c, pl, 0, false);
+    const bool sem = c->cfg.d_sem > 0;
+    int rc = size_workspace(c, pl, d_cand ? C : 0, false);
     if (rc != NGDB_OK) return rc;
-    rc = enqueue_forward(c, pl, s);
+    EntRows er{c->prm.E.p, pl->d_in_ref, pl->d_pos, d_cand};
+    if (sem) {   // fused rows of the anchors (and candidates) first
+        int32_t* e_src = nullptr;
+        rc = prepare_entities(c, pl, d_cand, d_cand ? (int64_t)pl->hp.n_queries * C : 0, s, s, &e_src, &er);
+        if (rc != NGDB_OK) return rc;
+    }
+    rc = enqueue_forward(c, pl, er, s);
     if (rc != NGDB_OK) return rc;
     if (d_cand) {
         ScoreArgs sa{};
-        sa.act = ptr<float>(c->act); sa.E = c->prm.E.p; sa.root_off = pl->d_root_off; sa.root_slot = pl->d_root_slot;
-        sa.pos = nullptr; sa.cand = d_cand; sa.B = pl->hp.n_queries; sa.C = C; sa.d = c->cfg.d;
+        sa.act = ptr<float>(c->act); sa.E = er.rows; sa.root_off = pl->d_root_off; sa.root_slot = pl->d_root_slot;
+        sa.pos = nullptr; sa.cand = er.cand; sa.B = pl->hp.n_queries; sa.C = C; sa.d = c->cfg.d;
         sa.max_branch = std::max(1, pl->hp.max_branch); sa.gamma = c->cfg.gamma; sa.score = d_scores;
         hipError_t e;
         { Timed tm(c, NGDB_TK_SCORE, s); e = launch_score(sa, false, s); }
@@ -747,10 +839,22 @@ int ngdb_score(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_cand, int3
         const int ld = (chunk + 3) & ~3;
         rc = ensure(c, c->rank_dist, std::max<size_t>((size_t)R * ld * sizeof(float), 256));
         if (rc != NGDB_OK) return rc;
+        if (sem) {
+            rc = ensure(c, c->rank_ef, (size_t)chunk * d * sizeof(float));
+            if (rc != NGDB_OK) return rc;
+        }
         Timed tm(c, NGDB_TK_SCORE, s);
         for (int e0 = 0; e0 < N; e0 += chunk) {
             const int cnt = std::min(chunk, N - e0);
-            HIPCHK(c, launch_l1_tile(ptr<float>(c->act), pl->d_root_slot, R, c->prm.E.p + (size_t)e0 * d, cnt, d,
+            const float* rows = c->prm.E.p + (size_t)e0 * d;
+            if (sem) {   // the chunk's fused rows
+                SemFuseArgs fa{};
+                fa.H = c->prm.H_sem; fa.Wb = ptr<uint16_t>(c->Wb); fa.E = c->prm.E.p; fa.id_base = e0;
+                fa.n_rows = cnt; fa.d = d; fa.ds = c->cfg.d_sem; fa.out = ptr<float>(c->rank_ef);
+                HIPCHK(c, launch_sem_fuse(fa, s));
+                rows = ptr<float>(c->rank_ef);
+            }
+            HIPCHK(c, launch_l1_tile(ptr<float>(c->act), pl->d_root_slot, R, rows, cnt, d,
                                      ptr<float>(c->rank_dist), ld, s));
             HIPCHK(c, launch_topk_merge(ptr<float>(c->rank_dist), ld, pl->d_root_off, pl->hp.n_queries, e0, cnt, topk,
                                         e0 == 0, d_topk_dist, d_topk_ids, s));

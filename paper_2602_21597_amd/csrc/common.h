@@ -74,9 +74,6 @@ struct GemmGroup {
 hipError_t launch_gemm_group(const GemmArgs* problems, int count, hipStream_t s);
 
 // ---------------------------------------------------------------- elementwise ops (ops.hip)
-// Z[m,:] = src(ref[m]) (+ R[rel[m]]), src = act row if ref >= 0 else E row -1-ref.
-hipError_t launch_gather(float* Z, const int32_t* ref, const int32_t* rel, int rows, int d,
-                         const float* act, const float* E, const float* R, hipStream_t s);
 // Intersection of n members with k inputs: rows j*n+i of X (inputs) and Att (logits).
 hipError_t launch_inter_fwd(const float* X, const float* Att, float* out, int n, int k, int d, hipStream_t s);
 // dAtt[j*n+i] = w_j*(dy*x_j - sum_l w_l dy x_l),  Dx[j*n+i] = w_j*dy
@@ -177,11 +174,51 @@ struct TableArgs {
     const float* dact;
     const float* act;
     float* g_out;                  // if set: write gradients [n_uniq, d] instead of updating
+    // text-feature fusion: the entity row a pair is scored against is ref_rows[u] (row of the
+    // touched-row list) instead of the table row, and the row gradient is also left in
+    // g_bf16 [n_uniq, d] (bf16 bit patterns) for the gradient of the projection
+    const float* ref_rows = nullptr;
+    uint16_t* g_bf16 = nullptr;
 };
 // sorted contribution numbers -> records: c < n_rowsrc is gradient row row_base + c,
 // otherwise a (query, candidate) pair in the order [B positives | B*K negatives]
 hipError_t launch_resolve(const int32_t* src, int64_t n, int n_rowsrc, int row_base, int B, int K, const float* coef,
                           const int32_t* win, float* rec_coef, int32_t* rec_row, hipStream_t s);
 hipError_t launch_table_update(const TableArgs& a, const AdamHyper& hp, hipStream_t s);
+
+// ---------------------------------------------------------------- text-feature fusion (sem.hip)
+hipError_t launch_cast_bf16(const float* x, uint16_t* y, int64_t n, hipStream_t s);
+// inv[src[t]] = u for seg_off[u] <= t < seg_off[u+1]
+hipError_t launch_inverse_index(const int32_t* src, const int32_t* seg_off, const int32_t* n_uniq_dev, int64_t n,
+                                int32_t* inv, hipStream_t s);
+// out[i] = in_ref[i] if it is a slot, else -1 - inv[in_gslot[i] - n_slots] (anchor -> its touched-row position)
+hipError_t launch_translate_refs(const int32_t* in_ref, const int32_t* in_gslot, int n, int n_slots,
+                                 const int32_t* inv, int32_t* out, hipStream_t s);
+// out[u, :] = E[id(u), :] + Wb * H[id(u), :] for u < n_rows; id(u) = ids[u] or id_base + u
+struct SemFuseArgs {
+    const uint16_t* H;          // [N, ds] bf16
+    const uint16_t* Wb;         // [d, ds] bf16
+    const float* E;             // [N, d]
+    const int32_t* ids;         // [n_rows] or null
+    int64_t id_base;
+    const int32_t* n_rows_dev;  // device scalar (then n_rows is an upper bound) or null
+    int n_rows;
+    int d, ds;                  // ds a multiple of 64
+    float* out;                 // [n_rows, d]
+};
+hipError_t launch_sem_fuse(const SemFuseArgs& a, hipStream_t s);
+// out[m, n] = sum_u G[u, m] * H[ids[u], n] over u < *n_rows_dev
+struct SemWgradArgs {
+    const uint16_t* H;
+    const int32_t* ids;
+    const uint16_t* G;          // [n_rows, d] bf16, d a multiple of 8
+    const int32_t* n_rows_dev;
+    int n_rows;                 // upper bound
+    int d, ds;
+    int n_splits;               // from sem_wgrad_splits
+    float* partial;             // [n_splits, d, ds]
+};
+int sem_wgrad_splits(int64_t n_rows_bound, int d, int ds);
+hipError_t launch_sem_wgrad(const SemWgradArgs& a, float* out, hipStream_t s);
 
 }  // namespace ngdb

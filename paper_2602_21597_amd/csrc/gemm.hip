@@ -11,8 +11,6 @@
 // partial tiles are then summed through LDS in a fixed order (deterministic) and
 // the epilogue is applied to the sum.  The A operand can be assembled on the fly
 // from row references (gather of operator inputs fused into the first layer).
-#include <cstdlib>
-
 #include "common.h"
 
 namespace ngdb {
@@ -336,10 +334,6 @@ hipError_t launch_gemm_group(const GemmArgs* problems, int count, hipStream_t s)
     }
     if (g.count == 0) return hipSuccess;
     if (blocks_small >= 2048) return dispatch_layout<64, 64, 4>(g, s);
-    const char* t = getenv("NGDB_GEMM_NW");
-    const int nw = t ? atoi(t) : 0;
-    if (nw == 4) return dispatch_layout<32, 64, 4>(g, s);
-    if (nw == 8) return dispatch_layout<32, 64, 8>(g, s);
     if (max_k >= 512) return dispatch_layout<32, 64, 8>(g, s);
     return dispatch_layout<32, 64, 4>(g, s);
 }

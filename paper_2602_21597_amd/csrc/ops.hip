@@ -1,33 +1,12 @@
-// Memory-bound pieces around the grouped MLPs: row gathers through the plan's
-// precomputed references (Sec. 4.2 "Efficient Tensor Indexing"), the attention
+// Memory-bound pieces around the grouped MLPs (the row gathers through the plan's
+// precomputed references, Sec. 4.2 "Efficient Tensor Indexing", are fused into the
+// contraction kernel's operand loads): the attention
 // pooling of the intersection classes C_k (Sec. 4.3), column sums for the bias
 // gradients, dense Adam (Alg. 1, OptimizerStep) and the final loss reduction.
 #include "common.h"
 
 namespace ngdb {
 namespace {
-
-// one workgroup of 128 threads per row, float4 per thread
-__global__ __launch_bounds__(128) void gather_kernel(float* __restrict__ Z, const int32_t* __restrict__ ref,
-                                                     const int32_t* __restrict__ rel, int rows, int d4,
-                                                     const float* __restrict__ act, const float* __restrict__ E,
-                                                     const float* __restrict__ R) {
-    const int m = blockIdx.x;
-    if (m >= rows) return;
-    const int32_t r = ref[m];
-    const float4* src = reinterpret_cast<const float4*>(r >= 0 ? act + (size_t)r * d4 * 4
-                                                               : E + (size_t)(-1 - r) * d4 * 4);
-    const float4* rr = rel ? reinterpret_cast<const float4*>(R + (size_t)rel[m] * d4 * 4) : nullptr;
-    float4* dst = reinterpret_cast<float4*>(Z + (size_t)m * d4 * 4);
-    for (int c = threadIdx.x; c < d4; c += blockDim.x) {
-        float4 v = src[c];
-        if (rr) {
-            const float4 w = rr[c];
-            v.x += w.x; v.y += w.y; v.z += w.z; v.w += w.w;
-        }
-        dst[c] = v;
-    }
-}
 
 // y_i = sum_j softmax_j(att_j)_c * x_j,c : one thread per (member, coordinate)
 template <bool BWD>
@@ -142,13 +121,6 @@ __global__ __launch_bounds__(256) void loss_reduce_kernel(const float* __restric
 }
 
 }  // namespace
-
-hipError_t launch_gather(float* Z, const int32_t* ref, const int32_t* rel, int rows, int d, const float* act,
-                         const float* E, const float* R, hipStream_t s) {
-    if (rows <= 0) return hipSuccess;
-    hipLaunchKernelGGL(gather_kernel, dim3(rows), dim3(128), 0, s, Z, ref, rel, rows, d / 4, act, E, R);
-    return hipGetLastError();
-}
 
 hipError_t launch_inter_fwd(const float* X, const float* Att, float* out, int n, int k, int d, hipStream_t s) {
     if (n <= 0) return hipSuccess;

@@ -47,7 +47,14 @@ __global__ __launch_bounds__(256) void resolve_kernel(const int32_t* __restrict_
 
 constexpr int G = 4;   // source rows in flight per wavefront
 
-template <int NCH>
+__device__ __forceinline__ uint32_t bf16_bits(float x) {   // round to nearest, ties to even
+    const uint32_t b = __float_as_uint(x);
+    return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
+}
+
+// SEM: pairs are scored against the fused row of the touched-row list (text-feature
+// fusion) and the row gradient is also stored as bf16 for the projection's gradient.
+template <int NCH, bool SEM>
 __global__ __launch_bounds__(256) void table_kernel(const TableArgs a, const AdamHyper hp) {
     const int lane = threadIdx.x & 63;
     const int d4 = a.d >> 2;
@@ -70,10 +77,11 @@ __global__ __launch_bounds__(256) void table_kernel(const TableArgs a, const Ada
         float4* prow = reinterpret_cast<float4*>(a.P + (size_t)row * a.d);
         float4* mrow = reinterpret_cast<float4*>(a.Mo + (size_t)row * a.d);
         float4* vrow = reinterpret_cast<float4*>(a.Vo + (size_t)row * a.d);
-        float4 p[NCH], m[NCH], v[NCH], g[NCH];
+        float4 p[NCH], m[NCH], v[NCH], g[NCH], ef[NCH];
 #pragma unroll
         for (int ch = 0; ch < NCH; ++ch) {
             p[ch] = prow[colc[ch]];
+            if (SEM) ef[ch] = reinterpret_cast<const float4*>(a.ref_rows + (size_t)u * a.d)[colc[ch]];
             if (update) {
                 m[ch] = mrow[colc[ch]];
                 v[ch] = vrow[colc[ch]];
@@ -108,11 +116,12 @@ __global__ __launch_bounds__(256) void table_kernel(const TableArgs a, const Ada
 #pragma unroll
                     for (int ch = 0; ch < NCH; ++ch) {
                         const float4 y = x[q][ch];
+                        const float4 e = SEM ? ef[ch] : p[ch];
                         if (is_pair[q]) {
-                            g[ch].x += c * sgn(y.x - p[ch].x);
-                            g[ch].y += c * sgn(y.y - p[ch].y);
-                            g[ch].z += c * sgn(y.z - p[ch].z);
-                            g[ch].w += c * sgn(y.w - p[ch].w);
+                            g[ch].x += c * sgn(y.x - e.x);
+                            g[ch].y += c * sgn(y.y - e.y);
+                            g[ch].z += c * sgn(y.z - e.z);
+                            g[ch].w += c * sgn(y.w - e.w);
                         } else {
                             g[ch].x += wgt[q] * y.x;
                             g[ch].y += wgt[q] * y.y;
@@ -122,6 +131,14 @@ __global__ __launch_bounds__(256) void table_kernel(const TableArgs a, const Ada
                     }
                 }
             }
+        }
+        if (SEM) {
+            uint2* brow = reinterpret_cast<uint2*>(a.g_bf16 + (size_t)u * a.d);
+#pragma unroll
+            for (int ch = 0; ch < NCH; ++ch)
+                if (col_ok[ch])
+                    brow[ch * 64 + lane] = make_uint2(bf16_bits(g[ch].x) | (bf16_bits(g[ch].y) << 16),
+                                                      bf16_bits(g[ch].z) | (bf16_bits(g[ch].w) << 16));
         }
         if (!update) {
             float4* orow = reinterpret_cast<float4*>(a.g_out + (size_t)u * a.d);
@@ -162,10 +179,17 @@ hipError_t launch_resolve(const int32_t* src, int64_t n, int n_rowsrc, int row_b
 hipError_t launch_table_update(const TableArgs& a, const AdamHyper& hp, hipStream_t s) {
     // the number of touched rows is only known on the device: a fixed grid walks them
     const int blocks = 256 * 8;
-    if (a.d <= 256) hipLaunchKernelGGL(table_kernel<1>, dim3(blocks), dim3(256), 0, s, a, hp);
-    else if (a.d <= 512) hipLaunchKernelGGL(table_kernel<2>, dim3(blocks), dim3(256), 0, s, a, hp);
-    else if (a.d <= 1024) hipLaunchKernelGGL(table_kernel<4>, dim3(blocks), dim3(256), 0, s, a, hp);
-    else return hipErrorInvalidValue;
+    if ((a.ref_rows == nullptr) != (a.g_bf16 == nullptr) || a.d > 1024) return hipErrorInvalidValue;
+    const bool sem = a.ref_rows != nullptr;
+#define NGDB_TABLE(NCH)                                                                              \
+    do {                                                                                             \
+        if (sem) hipLaunchKernelGGL((table_kernel<NCH, true>), dim3(blocks), dim3(256), 0, s, a, hp); \
+        else hipLaunchKernelGGL((table_kernel<NCH, false>), dim3(blocks), dim3(256), 0, s, a, hp);   \
+    } while (0)
+    if (a.d <= 256) NGDB_TABLE(1);
+    else if (a.d <= 512) NGDB_TABLE(2);
+    else NGDB_TABLE(4);
+#undef NGDB_TABLE
     return hipGetLastError();
 }
 

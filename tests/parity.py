@@ -20,13 +20,26 @@ TOL = 1e-4
 # method says nothing about which side to take.  fp32 rounding moves a
 # pre-activation or a coordinate difference by about 1e-7 on these workloads.
 TAU_PRE, TAU_ABS, TAU_TIE = 1e-6, 5e-7, 1e-4
+# Text-feature fusion: products of bf16 values are exact in fp32 and are summed in fp32, so
+# fused rows, scores, loss and table gradients stay under the fp32 bar.  Only the gradient of
+# the projection Wp passes through bf16 (every touched row's gradient is rounded to bf16,
+# relative error <= 2^-9 per element, before the contraction with the bf16 features) and is
+# held to the bf16 bar.
+TOL_BF16 = 2e-2
+
+
+def tol_of(name, tol):
+    return TOL_BF16 if name == "Wp" else tol
 
 
 class Case:
-    def __init__(self, N, R, d, h, B, K, gamma, mix=None, seed=0, T=None, alpha=2.1, trees=None, pos=None):
+    def __init__(self, N, R, d, h, B, K, gamma, mix=None, seed=0, T=None, alpha=2.1, trees=None, pos=None,
+                 d_sem=0):
         self.N, self.R, self.d, self.h, self.B, self.K, self.gamma = N, R, d, h, B, K, gamma
+        self.d_sem = d_sem
         self.hp = dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, gamma=gamma)
-        self.params = wl.make_params(N, R, d, h, seed + 3)
+        self.params = wl.make_params(N, R, d, h, seed + 3, d_sem=d_sem)
+        self.sem_bits = wl.make_sem_features(N, d_sem, seed + 5) if d_sem else None
         if trees is not None:
             qb = wl.batch_from_trees(trees, pos)
             want = qb.B
@@ -36,7 +49,7 @@ class Case:
             qb = wl.make_batch(kg, B + B // 4 + 8, mix or {n: 1.0 for n in wl.configs.ALL14}, seed + 1)
         negs = wl.make_negatives(N, qb.B, K, seed + 2)
         self.qb, self.negs, self.n_redrawn = keep_clear_of_kinks(qb, negs, self.params, gamma, N, want, seed + 4,
-                                                                 strict=trees is None)
+                                                                 strict=trees is None, sem_bits=self.sem_bits)
         self.B = self.qb.B
 
     @classmethod
@@ -49,13 +62,13 @@ class Case:
         """Another [B, K] draw of negatives, kept clear of the |.| kinks like the first."""
         negs = wl.make_negatives(self.N, self.B, self.K, seed)
         _, negs, _ = keep_clear_of_kinks(self.qb, negs, self.params, self.gamma, self.N, self.B, seed + 1,
-                                         strict=False, queries_are_clean=True)
+                                         strict=False, queries_are_clean=True, sem_bits=self.sem_bits)
         return negs
 
     def engine(self, num_streams=1):
         from paper_2602_21597_amd import Engine
-        eng = Engine(self.N, self.R, self.d, self.h, self.gamma, num_streams=num_streams)
-        eng.bind_numpy(self.params)
+        eng = Engine(self.N, self.R, self.d, self.h, self.gamma, num_streams=num_streams, d_sem=self.d_sem)
+        eng.bind_numpy(self.params, sem_bits=self.sem_bits)
         return eng
 
     def neg_dev(self, negs=None):
@@ -63,14 +76,15 @@ class Case:
         return torch.from_numpy(np.ascontiguousarray(self.negs if negs is None else negs, np.int32)).cuda()
 
     def oracle_grads(self, negs=None):
-        M = om.Model(self.params, self.gamma)
+        M = om.Model(self.params, self.gamma, self.sem_bits)
         return (M,) + om.batch_loss_and_grads(self.qb, self.negs if negs is None else negs, M)
 
 
-def keep_clear_of_kinks(qb, negs, params, gamma, N, want, seed, strict=True, queries_are_clean=False):
+def keep_clear_of_kinks(qb, negs, params, gamma, N, want, seed, strict=True, queries_are_clean=False,
+                        sem_bits=None):
     """First `want` queries of qb that stay clear of every kink, with negatives
     that sit on an |.| kink redrawn.  Uses the oracle's forward pass only."""
-    M = om.Model(params, gamma)
+    M = om.Model(params, gamma, sem_bits)
     rng = np.random.default_rng(seed)
     negs = negs.copy()
     keep, redrawn = [], 0
@@ -178,7 +192,7 @@ def check_forward_backward(case, eng=None, tol=TOL):
         if name == "u2":
             assert_zero_gradient(g[name], G.dense, tol)
         else:
-            assert_close(g[name], G.dense[name], "grad " + name, tol)
+            assert_close(g[name], G.dense[name], "grad " + name, tol_of(name, tol))
     for tab, uniq, rows in (("E", g["e_uniq"], g["gE"]), ("R", got_plan["r_uniq"], g["gR"])):
         assert sorted(G.rows[tab]) == list(uniq), tab + " touched rows"
         if len(uniq):
@@ -237,7 +251,7 @@ def check_train_steps(case, steps=3, num_streams=1, tol=TOL):
         b_p, b_m, b_v = eng.params_numpy("p"), eng.params_numpy("m"), eng.params_numpy("v")
         loss = eng.train_step(plan, nd)
         torch.cuda.synchronize()
-        ref_loss, G = om.train_step(case.qb, negs, P, state, t, case.hp)
+        ref_loss, G = om.train_step(case.qb, negs, P, state, t, case.hp, case.sem_bits)
         a_p, a_m, a_v = eng.params_numpy("p"), eng.params_numpy("m"), eng.params_numpy("v")
         if case.B:
             assert abs(float(loss.cpu()[0]) - ref_loss) <= tol * abs(ref_loss)
@@ -263,10 +277,12 @@ def check_train_steps(case, steps=3, num_streams=1, tol=TOL):
             # (B) end to end
             if name == "u2":     # zero gradient in exact arithmetic: direction is rounding noise
                 continue
+            tol_a, tol = tol, tol_of(name, tol)
             gref = G.table_dense(name, shapes[name]) if name in ("E", "R") else G.dense[name]
             m0, v0 = state_ref_before[name]
             # tables: every row sums its own contributions, so its rounding noise scales with the row
-            delta = 1e-6 * (np.abs(gref).max(axis=1, keepdims=True) if name in ("E", "R") else np.abs(gref).max())
+            noise = 4e-3 if name == "Wp" else 1e-6        # bf16 / fp32 rounding level of the gradient
+            delta = noise * (np.abs(gref).max(axis=1, keepdims=True) if name in ("E", "R") else np.abs(gref).max())
             hi = _adam_f64(before_ref[name], m0, v0, gref + delta, t, case.hp)[0]
             lo = _adam_f64(before_ref[name], m0, v0, gref - delta, t, case.hp)[0]
             upd_ref = P[name] - before_ref[name]
@@ -287,5 +303,6 @@ def check_train_steps(case, steps=3, num_streams=1, tol=TOL):
                 name, keep.sum(), n_all)
             assert_close(a_m[name], state[name][0], "m " + name, tol)
             assert_close(a_v[name], state[name][1], "v " + name, 2 * tol)
+            tol = tol_a
     plan.free()
     return eng

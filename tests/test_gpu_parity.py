@@ -115,7 +115,7 @@ def _check_topk(case, k, n_check):
     ids, dist = eng.rank_all(plan, k)
     torch.cuda.synchronize()
     ids, dist = ids.cpu().numpy(), dist.cpu().numpy()
-    M = om.Model(case.params, case.gamma)
+    M = om.Model(case.params, case.gamma, case.sem_bits)
     assert np.all(np.diff(dist, axis=1) >= 0)
     for q in np.random.default_rng(1).choice(case.B, min(n_check, case.B), replace=False):
         full = orank.distances_all(case.qb, int(q), M)
@@ -139,6 +139,59 @@ def test_all_entity_topk_many_chunks():
     _say("ngdb_score all-entity mode: N=150000 (3 chunks), d=400, 200 queries incl. unions, k=10")
     case = par.Case(150000, 40, 400, 800, 200, 2, 24.0, seed=32, T=400000)
     _check_topk(case, 10, 12)
+
+
+# ---------------------------------------------------------------- text-feature fusion
+def test_text_features_forward_backward():
+    _say("d_sem=128: N=1200 d=64 h=128 B=70 K=9")
+    par.check_forward_backward(par.Case(1200, 12, 64, 128, 70, 9, 8.0, seed=41, d_sem=128))
+
+
+def test_text_features_ragged_tiles():
+    # d=104: coordinate tiles of 80 + 24; d_sem=320: feature tiles of 256 + 64; ~700 touched rows: 3 row tiles
+    _say("d_sem=320: N=700 d=104 h=72 B=120 K=11")
+    par.check_forward_backward(par.Case(700, 9, 104, 72, 120, 11, 12.0, seed=42, d_sem=320))
+
+
+def test_text_features_train_steps():
+    _say("d_sem=64: N=900 d=32 h=64 B=60 K=8, 3 train steps; streams 1 vs 3 bit-identical")
+    case = par.Case(900, 10, 32, 64, 60, 8, 5.0, seed=43, d_sem=64)
+    e1 = par.check_train_steps(case, steps=3)
+    e3 = par.check_train_steps(case, steps=3, num_streams=3)
+    p1, p3 = e1.params_numpy(), e3.params_numpy()
+    for k in p1:
+        assert np.array_equal(p1[k], p3[k]), k
+
+
+def test_text_features_workload_widths():
+    # the widths of the text-feature workload (d=400, h=800, d_sem=1024) on a small graph
+    _say("d_sem=1024: N=6000 d=400 h=800 B=96 K=24, forward_backward + 1 train step")
+    case = par.Case(6000, 30, 400, 800, 96, 24, 30.0, seed=44, d_sem=1024)
+    par.check_forward_backward(case)
+    par.check_train_steps(case, steps=1)
+
+
+def test_text_features_scores_and_ranking():
+    import torch
+    _say("d_sem=128: candidate scores and all-entity top-k")
+    case = par.Case(1500, 10, 48, 96, 50, 4, 6.0, seed=45, d_sem=128)
+    eng = case.engine()
+    plan = eng.plan(case.qb)
+    cand = wl.make_negatives(case.N, case.B, 21, 98)
+    got = eng.score(plan, torch.from_numpy(cand).cuda()).cpu().numpy()
+    want = orank.score_candidates(case.qb, cand, om.Model(case.params, case.gamma, case.sem_bits))
+    par.assert_close(got, want, "candidate scores with text features")
+    plan.free()
+    _check_topk(case, 10, 16)
+    _check_topk(par.Case(70000, 10, 64, 128, 30, 2, 8.0, seed=46, T=200000, d_sem=64), 5, 6)   # 2 entity chunks
+
+
+def test_text_features_bad_widths_are_rejected():
+    from paper_2602_21597_amd import Engine, NgdbError, binding
+    for d, d_sem in ((64, 100), (36, 64)):
+        with pytest.raises(NgdbError) as e:
+            Engine(100, 5, d, 64, 6.0, d_sem=d_sem)
+        assert e.value.code == binding.ERR_ARG
 
 
 def test_fb15k237_shape_full_size():
