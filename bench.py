@@ -24,10 +24,16 @@ sys.path.insert(0, ROOT)
 import workloads as wl  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published
+MFMA_F32_PEAK_TF = 157.3  # dense fp32 matrix, published
+MFMA_BF16_PEAK_TF = 2500.0
 N_BATCHES = 8
+CLASSES = ("index", "sem", "gemm_fwd", "inter", "score", "gemm_bwd", "wgrad", "table_E", "table_R", "adam")
+# HBM bytes per launch of a workload's dominant kernel from the rocprofv3 --pmc runs summarised
+# under profiles/ (FETCH_SIZE + WRITE_SIZE, scaled by the copy kernel): {(config, kernel): bytes}
+MEASURED_TRAFFIC = {}
 
 
-def cpu_baseline(cfg, kg, sample):
+def cpu_baseline(cfg, kg, sample, sem_bits):
     """The oracle as it stands, one full step (loss, gradients, Adam) on `sample` queries,
     single process with BLAS held to one thread."""
     from oracle import model as om
@@ -37,13 +43,13 @@ def cpu_baseline(cfg, kg, sample):
         threadpool_limits = None
     qb = wl.make_batch(kg, sample, cfg.mix, cfg.seed + 100)
     negs = wl.make_negatives(cfg.N, sample, cfg.K, cfg.seed + 200)
-    P = om.to_f64(wl.make_params(cfg.N, cfg.R, cfg.d, cfg.h, cfg.seed + 3))
+    P = om.to_f64(wl.make_params(cfg.N, cfg.R, cfg.d, cfg.h, cfg.seed + 3, d_sem=cfg.d_sem))
     st = om.new_state(P)
     hp = dict(lr=cfg.lr, beta1=cfg.beta1, beta2=cfg.beta2, eps=cfg.eps, gamma=cfg.gamma)
 
     def run():
         t0 = time.perf_counter()
-        om.train_step(qb, negs, P, st, 1, hp)
+        om.train_step(qb, negs, P, st, 1, hp, sem_bits)
         return time.perf_counter() - t0
 
     if threadpool_limits is not None:
@@ -56,6 +62,41 @@ def cpu_baseline(cfg, kg, sample):
                       "(per-query fp64 numpy forward, loss, backward, Adam), %.1f s" % (sample, cfg.K, dt)}
 
 
+def say(msg):
+    """Progress on stderr (the JSON line on stdout stays alone)."""
+    print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
+def kernel_models(cfg, pexp, touched):
+    """Algorithmic work of one step per kernel class: what the method itself has to move or
+    multiply, whatever the kernels do.  Returns {class: (bound, amount, peak, unit)} with
+    amounts in bytes (hbm) or flops (mfma)."""
+    row = 4 * cfg.d
+    pairs = cfg.B * (cfg.K + 1)
+    n_contrib = pexp["n_anchor"] + cfg.B + cfg.B * cfg.K
+    mlp_rows = pexp["n_proj"] + pexp["n_int_rows"] + pexp["n_neg"]
+    sem = cfg.d_sem > 0
+    # every pair: one entity row, its index, 12 bytes of (score, dL/ds, winning branch); every branch
+    # embedding read once and its gradient written once
+    score_bytes = pairs * (row + 4 + 12) + pexp["n_roots"] * 2 * row
+    # every touched row: p, m, v read and written; every contribution: 12 bytes of record; anchor
+    # gradient rows read; with text features also the fused row read and the bf16 gradient written
+    table_bytes = touched * 6 * row + n_contrib * 12 + pexp["n_anchor"] * row
+    if sem:
+        table_bytes += touched * (row + 2 * cfg.d)
+    mlp_flops = 4 * cfg.d * cfg.h * mlp_rows       # two layers, 2 flops per multiply-add
+    models = {
+        "score": ("hbm", score_bytes, HBM_PEAK_GBS, "GB/s"),
+        "table_E": ("hbm", table_bytes, HBM_PEAK_GBS, "GB/s"),
+        "gemm_fwd": ("mfma", mlp_flops, MFMA_F32_PEAK_TF, "TFLOP/s"),
+        "gemm_bwd": ("mfma", mlp_flops, MFMA_F32_PEAK_TF, "TFLOP/s"),
+        "wgrad": ("mfma", mlp_flops, MFMA_F32_PEAK_TF, "TFLOP/s"),
+    }
+    if sem:   # projection of the touched rows and its weight gradient, 2 flops per multiply-add each
+        models["sem"] = ("mfma", 4 * touched * cfg.d * cfg.d_sem, MFMA_BF16_PEAK_TF, "TFLOP/s")
+    return models
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -64,7 +105,6 @@ def main():
     ap.add_argument("--config", type=int, default=1)
     ap.add_argument("--streams", type=int, default=0, help="0 = the workload's default")
     ap.add_argument("--cpu-sample", type=int, default=-1, help="queries timed on the CPU oracle (0 = skip)")
-    ap.add_argument("--all-classes", action="store_true", help="time every kernel class (perturbs the step time)")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="also run the library's plain copy kernel on this many MiB, 5 times (reference "
                          "for scaling rocprofv3 traffic counters)")
@@ -75,21 +115,28 @@ def main():
         sys.exit(2)
 
     cfg = wl.get_config(args.config)
+    say("generating the graph (N=%d, T=%d)" % (cfg.N, cfg.T))
     kg = wl.make_kg(cfg.N, cfg.R, cfg.T, cfg.alpha, cfg.seed)
+    say("generating %d batches of %d queries, negatives, parameters" % (N_BATCHES, cfg.B))
     batches = [wl.make_batch(kg, cfg.B, cfg.mix, cfg.seed + 10 + i) for i in range(N_BATCHES)]
     negs_np = [wl.make_negatives(cfg.N, cfg.B, cfg.K, cfg.seed + 50 + i) for i in range(N_BATCHES)]
-    params = wl.make_params(cfg.N, cfg.R, cfg.d, cfg.h, cfg.seed + 3)
+    params = wl.make_params(cfg.N, cfg.R, cfg.d, cfg.h, cfg.seed + 3, d_sem=cfg.d_sem)
+    sem_bits = wl.make_sem_features(cfg.N, cfg.d_sem, cfg.seed + 5) if cfg.d_sem else None
 
     # CPU oracle first, before this process touches the GPU
-    sample = args.cpu_sample if args.cpu_sample >= 0 else min(cfg.B, 512 if cfg.K <= 128 else 64)
-    cpu = cpu_baseline(cfg, kg, sample) if sample > 0 else None
+    default_sample = 512 if cfg.K <= 128 else (8 if cfg.d_sem else 64)
+    sample = args.cpu_sample if args.cpu_sample >= 0 else min(cfg.B, default_sample)
+    say("CPU oracle on %d queries" % sample)
+    cpu = cpu_baseline(cfg, kg, sample, sem_bits) if sample > 0 else None
+    say("uploading parameters")
 
     import torch
     from paper_2602_21597_amd import Engine
     streams = args.streams or cfg.streams
     eng = Engine(cfg.N, cfg.R, cfg.d, cfg.h, cfg.gamma, lr=cfg.lr, beta1=cfg.beta1, beta2=cfg.beta2, eps=cfg.eps,
-                 num_streams=streams)
-    eng.bind_numpy(params)
+                 num_streams=streams, d_sem=cfg.d_sem)
+    eng.bind_numpy(params, sem_bits=sem_bits)
+    del params, sem_bits
     negs = [torch.from_numpy(n).cuda() for n in negs_np]
     stream = torch.cuda.current_stream()
 
@@ -98,23 +145,18 @@ def main():
         eng.train_step(plan, negs[i % N_BATCHES], stream)
         plan.free()        # the library recycles the plan's buffers once the step has finished
 
+    say("warm-up")
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
+    say("timing %d steps" % args.steps)
 
-    timed = ("score", "table_E") if not args.all_classes else \
-        ("index", "sem", "gemm_fwd", "inter", "score", "gemm_bwd", "wgrad", "table_E", "table_R", "adam")
-    eng.set_timing(timed)
-    eng.get_timing(reset=True)
-    touched = 0
-    torch.cuda.synchronize()
+    # the timed region: K whole steps, nothing else on the device
     t0 = time.perf_counter()
     for i in range(args.steps):
         step(args.warmup + i)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    timing = eng.get_timing(reset=True)
-    eng.set_timing(())
 
     # device-only time of the same steps with plans prebuilt (context figure)
     plans = [eng.plan(b) for b in batches]
@@ -124,6 +166,15 @@ def main():
         eng.train_step(plans[i % N_BATCHES], negs[i % N_BATCHES], stream)
     torch.cuda.synchronize()
     dt_dev = time.perf_counter() - t1
+
+    say("kernel classes")
+    # the same steps once more with every kernel class bracketed by HIP events on its own stream
+    eng.set_timing(CLASSES)
+    eng.get_timing(reset=True)
+    for i in range(args.steps):
+        eng.train_step(plans[i % N_BATCHES], negs[i % N_BATCHES], stream)
+    timing = eng.get_timing(reset=True)
+    eng.set_timing(())
     touched = eng.n_touched_entities()
     pexp = plans[(args.steps - 1) % N_BATCHES].export()
 
@@ -140,23 +191,36 @@ def main():
         torch.cuda.synchronize()
         copy_gbs = 2 * nb * 5 / (time.perf_counter() - tc) / 1e9
 
-    # roofline of the dominant HBM kernels (algorithmic bytes / measured kernel time)
-    row = 4 * cfg.d
-    pairs = cfg.B * (cfg.K + 1)
-    score_bytes = pairs * (row + 4 + 12) + pexp["n_roots"] * 2 * row
-    n_contrib = pexp["n_anchor"] + cfg.B + cfg.B * cfg.K
-    table_bytes = touched * 6 * row + n_contrib * 12 + pexp["n_anchor"] * row
+    # roofline per kernel class: algorithmic work of one step / measured time of the class per step.
+    # The three contraction classes are launches of one kernel and are reported together as "gemm".
+    models = kernel_models(cfg, pexp, touched)
     kern = {}
-    for name, nbytes in (("score", score_bytes), ("table_E", table_bytes)):
+    for name, (bound, amount, peak, unit) in models.items():
         ms, n = timing[name]
         if n:
-            avg = ms / n
-            kern[name] = {"avg_us": 1e3 * avg, "bytes": nbytes, "GBs": nbytes / (avg * 1e-3) / 1e9}
-    dom = max(kern, key=lambda k: kern[k]["avg_us"])
-    roofline = {"bound": "hbm", "kernel": dom, "achieved": kern[dom]["GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": kern[dom]["GBs"] / HBM_PEAK_GBS, "traffic": None,
-                "avg_us": kern[dom]["avg_us"], "algorithmic_bytes": kern[dom]["bytes"],
-                "other": {k: v for k, v in kern.items() if k != dom}}
+            kern[name] = {"bound": bound, "ms_per_step": ms / args.steps, "launches_per_step": n / args.steps,
+                          "avg_us": 1e3 * ms / n, "work_per_step": amount, "unit": unit, "peak": peak}
+    gemm = [kern.pop(k) for k in ("gemm_fwd", "gemm_bwd", "wgrad") if k in kern]
+    if gemm:
+        tot_ms = sum(g["ms_per_step"] for g in gemm)
+        n_l = sum(g["launches_per_step"] for g in gemm)
+        kern["gemm"] = {"bound": "mfma", "ms_per_step": tot_ms, "launches_per_step": n_l,
+                        "avg_us": 1e3 * tot_ms / n_l, "work_per_step": sum(g["work_per_step"] for g in gemm),
+                        "unit": "TFLOP/s", "peak": MFMA_F32_PEAK_TF}
+    for k in kern.values():
+        scale = 1e9 if k["bound"] == "hbm" else 1e12
+        k["achieved"] = k["work_per_step"] / (k["ms_per_step"] * 1e-3) / scale
+        k["frac"] = k["achieved"] / k["peak"]
+    dom = max(kern, key=lambda k: kern[k]["ms_per_step"])
+    kd = kern[dom]
+    traffic = MEASURED_TRAFFIC.get((cfg.index, dom))
+    roofline = {"bound": kd["bound"], "kernel": dom, "achieved": kd["achieved"], "peak": kd["peak"],
+                "unit": kd["unit"], "frac": kd["frac"], "traffic": traffic,
+                "avg_us": kd["avg_us"], "launches_per_step": kd["launches_per_step"],
+                "algorithmic_work_per_launch": kd["work_per_step"] / kd["launches_per_step"],
+                "other": {k: {f: v[f] for f in ("bound", "achieved", "peak", "unit", "frac", "avg_us",
+                                                "launches_per_step", "ms_per_step")}
+                          for k, v in kern.items() if k != dom}}
 
     out = {
         "metric": "training queries/sec (fwd+bwd+Adam) at d=400, K=128 negatives; % of HBM peak",
@@ -171,19 +235,19 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": "configs[%d] %s: N=%d R=%d d=%d h=%d B=%d K=%d, 14-structure mix, gamma=%g"
-                   % (cfg.index, cfg.name, cfg.N, cfg.R, cfg.d, cfg.h, cfg.B, cfg.K, cfg.gamma),
+        "config": {"workload": "configs[%d] %s: N=%d R=%d d=%d h=%d B=%d K=%d%s, 14-structure mix, gamma=%g"
+                   % (cfg.index, cfg.name, cfg.N, cfg.R, cfg.d, cfg.h, cfg.B, cfg.K,
+                      " d_sem=%d (bf16 text features)" % cfg.d_sem if cfg.d_sem else "", cfg.gamma),
                    "streams": streams, "step": "ngdb_plan (host) + ngdb_train_step",
                    "touched_entity_rows": touched},
         "device_only": {"queries_per_s": cfg.B * args.steps / dt_dev, "ms_per_step": 1e3 * dt_dev / args.steps,
                         "note": "same steps with plans prebuilt"},
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "kernel_classes_ms_per_step": {k: v[0] / args.steps for k, v in timing.items()},
     }
     if copy_gbs is not None:
         out["copy_kernel_GBs"] = copy_gbs
-    if args.all_classes:
-        out["kernel_classes_ms_per_step"] = {k: v[0] / args.steps for k, v in timing.items()}
     print(json.dumps(out))
 
 

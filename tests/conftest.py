@@ -10,6 +10,8 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    from tests import parity
+    parity.PYTEST_CONFIG = config      # lets long GPU tests print progress past the output capture
 
 
 def pytest_collection_modifyitems(config, items):

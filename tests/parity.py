@@ -14,6 +14,19 @@ from oracle import model as om
 from oracle import plan as oplan
 
 TOL = 1e-4
+PYTEST_CONFIG = None
+
+
+def say(msg):
+    """Names the case (and the stage of a long one) on the terminal right away, also under
+    pytest's output capture: a GPU run that dies leaves the name of its last case behind."""
+    line = "[case] " + msg
+    capman = PYTEST_CONFIG.pluginmanager.getplugin("capturemanager") if PYTEST_CONFIG is not None else None
+    if capman is None:
+        print(line, flush=True)
+        return
+    with capman.global_and_fixture_disabled():
+        print("\n" + line, flush=True)
 # Distance the seeded inputs keep from the kinks of the model (ReLU at 0, |.| at 0,
 # ties of the min over union branches): there the result is decided by the last
 # bits of an fp32 sum, two correct implementations may differ, and the paper's

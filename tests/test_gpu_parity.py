@@ -13,8 +13,7 @@ from tests import parity as par
 pytestmark = pytest.mark.gpu
 
 
-def _say(msg):
-    print("[case] " + msg, flush=True)
+_say = par.say
 
 
 def test_tiny_config_forward_backward():

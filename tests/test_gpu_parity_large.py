@@ -1,11 +1,14 @@
 """Parity at the full sizes of the larger workloads (needs an MI355X).
 
 NELL shape: everything is compared, as for the benchmark workload.  wikikg2 shape
-(2.5 M entities, 4096 queries x 1024 negatives): plan and index bit-exact in
-full; values on sampled outputs the oracle computes one by one (queries: root
+(2.5 M entities, 4096 queries x 1024 negatives) and text-feature shape (5 M
+entities with 1024 bf16 features each): plan and index bit-exact in full;
+values on sampled outputs the oracle computes one by one (queries: root
 embeddings, all 1025 scores, loss term; entity rows: the gradient summed over
 every query that touches the row); dense gradients and the loss through the
-batch-split property; the optimiser on sampled rows."""
+batch-split property; the optimiser on sampled rows.  With text features also:
+every gradient (the projection's included) of a 24-query batch against the
+oracle, and the all-entity ranking of 1024 queries checked on 16 of them."""
 import numpy as np
 import pytest
 
@@ -17,8 +20,7 @@ from tests import parity as par
 pytestmark = pytest.mark.gpu
 
 
-def _say(msg):
-    print("[case] " + msg, flush=True)
+_say = par.say
 
 
 def test_nell_shape_full_size_multi_stream():
@@ -39,21 +41,28 @@ def _anchor_owner(qb):
 
 
 def test_wikikg2_shape_full_size_sampled():
+    _full_size_sampled(wl.get_config(3), n_sample=48)
+
+
+def test_text_feature_shape_full_size_sampled():
+    _full_size_sampled(wl.get_config(4), n_sample=16)
+
+
+def _full_size_sampled(cfg, n_sample):
     import torch
-    cfg = wl.get_config(3)
-    _say("config 3 (N=2.5M, B=4096, K=1024): building inputs")
+    _say("config %d (N=%d, B=%d, K=%d, d_sem=%d): building inputs" % (cfg.index, cfg.N, cfg.B, cfg.K, cfg.d_sem))
     kg = wl.make_kg(cfg.N, cfg.R, cfg.T, cfg.alpha, cfg.seed)
-    n_sample = 48
     rng = np.random.default_rng(5)
-    params = wl.make_params(cfg.N, cfg.R, cfg.d, cfg.h, cfg.seed + 3)
+    params = wl.make_params(cfg.N, cfg.R, cfg.d, cfg.h, cfg.seed + 3, d_sem=cfg.d_sem)
+    sem_bits = wl.make_sem_features(cfg.N, cfg.d_sem, cfg.seed + 5) if cfg.d_sem else None
     qb = wl.make_batch(kg, cfg.B, cfg.mix, cfg.seed + 1)
     negs = wl.make_negatives(cfg.N, cfg.B, cfg.K, cfg.seed + 2)
-    M = om.Model(params, cfg.gamma)
+    M = om.Model(params, cfg.gamma, sem_bits)
     B, K, d = cfg.B, cfg.K, cfg.d
 
     from paper_2602_21597_amd import Engine
-    eng = Engine(cfg.N, cfg.R, cfg.d, cfg.h, cfg.gamma)
-    eng.bind_numpy(params)
+    eng = Engine(cfg.N, cfg.R, cfg.d, cfg.h, cfg.gamma, d_sem=cfg.d_sem)
+    eng.bind_numpy(params, sem_bits=sem_bits)
     plan = eng.plan(qb)
     _say("plan + index, bit-exact")
     ref_plan = oplan.build_plan(qb)
@@ -96,8 +105,10 @@ def test_wikikg2_shape_full_size_sampled():
         return owner[c] if c < nA else (c - nA if c < nA + B else (c - nA - B) // K)
 
     # rows with a positive or an anchor among their contributions carry the large gradients
-    heavy = [i for i in range(U) if src[off[i]] < nA + B]
-    pick = list(rng.choice(heavy, 12, replace=False)) + list(rng.choice(U, 12, replace=False))
+    # (rows of at most 16 contributions keep the number of queries the oracle has to run small)
+    small = np.flatnonzero(np.diff(off) <= 16)
+    heavy = [int(i) for i in small if src[off[i]] < nA + B]
+    pick = list(rng.choice(heavy, 12, replace=False)) + list(rng.choice(small, 12, replace=False))
     need = sorted(set(int(query_of(int(c))) for i in pick for c in src[off[i]:off[i + 1]]))
     G = om.Grads(M.P)
     for q in need:
@@ -111,6 +122,8 @@ def test_wikikg2_shape_full_size_sampled():
     full_loss = float(loss.cpu()[0])
     full = {n: copy_to_host(gv.g_mlp[i], shp, np.float32).astype(np.float64)
             for i, (n, shp) in enumerate(zip(par_names(), par_shapes(cfg)))}
+    if cfg.d_sem:
+        full["Wp"] = copy_to_host(gv.g_Wp, (d, cfg.d_sem), np.float32).astype(np.float64)
     acc = {n: np.zeros_like(v) for n, v in full.items()}
     acc_loss = 0.0
     for c in range(4):
@@ -122,12 +135,14 @@ def test_wikikg2_shape_full_size_sampled():
         sg = eng.grad_view()
         for i, (n, shp) in enumerate(zip(par_names(), par_shapes(cfg))):
             acc[n] += copy_to_host(sg.g_mlp[i], shp, np.float32) / 4.0
+        if cfg.d_sem:
+            acc["Wp"] += copy_to_host(sg.g_Wp, (d, cfg.d_sem), np.float32) / 4.0
         acc_loss += float(sl.cpu()[0]) / 4.0
         sp.free()
     assert abs(full_loss - acc_loss) <= 1e-4 * abs(acc_loss)
     for n in full:
         if n != "u2":
-            par.assert_close(full[n], acc[n], "split-sum " + n)
+            par.assert_close(full[n], acc[n], "split-sum " + n, par.tol_of(n, par.TOL))
 
     _say("train step: sampled rows follow Adam on the step's own gradients, others untouched")
     touched = rng.choice(U, 64, replace=False)
@@ -153,6 +168,57 @@ def test_wikikg2_shape_full_size_sampled():
     m_after = mE[torch.from_numpy(rows_t).long().cuda()].cpu().numpy()
     par.assert_close(m_after, wm, "m rows")
     plan.free()
+    if not cfg.d_sem:
+        return
+
+    _say("24-query batch on the full tables: every gradient against the oracle")
+    sub = qb.select(np.arange(24))
+    sub_negs = np.ascontiguousarray(negs[:24])
+    eng.bind_numpy(params, sem_bits=sem_bits)          # fresh parameters: the step above moved them
+    sp = eng.plan(sub)
+    sl = eng.forward_backward(sp, torch.from_numpy(sub_negs).cuda())
+    torch.cuda.synchronize()
+    g = eng.grads()
+    ref_loss, G, _ = om.batch_loss_and_grads(sub, sub_negs, M)
+    assert abs(float(sl.cpu()[0]) - ref_loss) <= 1e-4 * abs(ref_loss)
+    for name in G.dense:
+        if name == "u2":
+            par.assert_zero_gradient(g[name], G.dense)
+        else:
+            par.assert_close(g[name], G.dense[name], "grad " + name, par.tol_of(name, par.TOL))
+    assert sorted(G.rows["E"]) == list(g["e_uniq"])
+    ref_rows = np.stack([G.rows["E"][int(r)] for r in g["e_uniq"]])
+    par.assert_close(g["gE"], ref_rows, "grad E")
+    par.assert_rows_close(g["gE"], ref_rows, "grad rows E")
+    sp.free()
+
+    _say("ranking: 1024 queries against all entities, top-10; 16 queries checked")
+    from oracle import rank as orank
+    rq = wl.make_batch(kg, 1024, cfg.mix, cfg.seed + 7)
+    rp = eng.plan(rq)
+    ids, dist = eng.rank_all(rp, 10)
+    torch.cuda.synchronize()
+    ids, dist = ids.cpu().numpy(), dist.cpu().numpy()
+    assert np.all(np.diff(dist, axis=1) >= 0)
+    check = rng.choice(1024, 16, replace=False)
+    Y = [orank.query_embeddings(rq, int(q), M) for q in check]
+    full_d = np.empty((16, cfg.N), np.float64)
+    chunk = 1 << 15
+    for lo in range(0, cfg.N, chunk):
+        e = np.arange(lo, min(cfg.N, lo + chunk))
+        rows = M.entity(e)                               # fused rows of the chunk, once for all 16 queries
+        for j in range(16):
+            full_d[j, lo:lo + len(e)] = np.abs(Y[j][:, None, :] - rows[None]).sum(axis=2).min(axis=0)
+        if (lo // chunk) % 32 == 0:
+            _say("  oracle distances: %d of %d entities" % (lo, cfg.N))
+    for j, q in enumerate(check):
+        order = np.lexsort((np.arange(cfg.N), full_d[j]))[:10]
+        ref_d = full_d[j][order]
+        par.assert_close(dist[q], ref_d, "top-10 distances q%d" % q)
+        assert len(set(ids[q])) == 10 and ids[q].min() >= 0 and ids[q].max() < cfg.N
+        assert np.all(full_d[j][ids[q]] <= ref_d[-1] * (1 + 1e-4)), "q%d" % q
+        par.assert_close(dist[q], full_d[j][ids[q]], "returned distances belong to returned ids q%d" % q)
+    rp.free()
 
 
 def par_names():
