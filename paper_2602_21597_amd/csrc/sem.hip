@@ -23,13 +23,16 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 constexpr int KS = 64;          // k extent of one staged slice (bf16 elements), 8 chunks of 8
 constexpr int TN = 80;          // embedding coordinates per workgroup tile (5 MFMA blocks)
 
+// LDS rows of W bf16 values; the low three bits of the 16-byte chunk index are swizzled by the row
 __device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row ^ (row >> 3)) & 7); }
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+template <int W = KS>
 __device__ __forceinline__ u32x4* lds_chunk(uint16_t* base, int row, int chunk) {
-    return reinterpret_cast<u32x4*>(base + row * KS + swz(row, chunk) * 8);
+    return reinterpret_cast<u32x4*>(base + row * W + swz(row, chunk) * 8);
 }
+template <int W = KS>
 __device__ __forceinline__ bf16x8 frag(const uint16_t* base, int row, int chunk) {
-    return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(base + row * KS + swz(row, chunk) * 8));
+    return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(base + row * W + swz(row, chunk) * 8));
 }
 __device__ __forceinline__ uint32_t to_bf16_bits(float x) {   // round to nearest, ties to even
     const uint32_t b = __float_as_uint(x);
@@ -68,69 +71,87 @@ __global__ __launch_bounds__(256) void translate_refs_kernel(const int32_t* __re
 }
 
 // ------------------------------------------------------------------ forward
-// out[u, :] = E[id(u), :] + Wb * H[id(u), :],  workgroup tile 256 rows x TN coordinates
+// out[u, :] = E[id(u), :] + Wb * H[id(u), :].  Workgroup tile: BU rows x TN coordinates, k
+// slices of KSF; wavefront w owns rows [w*BU/4, (w+1)*BU/4).  The slice width sets how much of
+// a gathered feature row one request covers, BU the registers per lane: the kernel waits on
+// HBM, so the shape is chosen for bytes in flight per compute unit, not for MFMA reuse.
+template <int BU, int KSF>
 __global__ __launch_bounds__(256) void sem_fuse_kernel(const SemFuseArgs a) {
-    __shared__ __attribute__((aligned(16))) uint16_t Hs[256 * KS];
-    __shared__ __attribute__((aligned(16))) uint16_t Ws[96 * KS];   // 3 x 256 chunks, TN rows used
+    constexpr int CPR = KSF / 8;                 // 16-byte chunks per LDS row
+    constexpr int RPP = 256 / CPR;               // rows covered by one pass of the 256 threads
+    constexpr int LH = BU / RPP;                 // feature chunks per thread and slice
+    constexpr int LW = (TN + RPP - 1) / RPP;     // projection chunks per thread and slice
+    constexpr int RB = BU / 64;                  // 16-row MFMA blocks per wavefront
+    __shared__ __attribute__((aligned(16))) uint16_t Hs[BU * KSF];
+    __shared__ __attribute__((aligned(16))) uint16_t Ws[LW * RPP * KSF];   // TN rows used
     const int n_rows = a.n_rows_dev ? min(*a.n_rows_dev, a.n_rows) : a.n_rows;
     const int n_tiles = (a.d + TN - 1) / TN;
     // workgroups are dealt round-robin to the 8 dies: the coordinate tiles of one
     // row tile go to the same die one after the other and share its L2
     const int die = blockIdx.x & 7, j = blockIdx.x >> 3;
-    const int u0 = ((j / n_tiles) * 8 + die) * 256;
+    const int u0 = ((j / n_tiles) * 8 + die) * BU;
     const int n0 = (j % n_tiles) * TN;
     if (u0 >= n_rows) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lrow = tid / CPR, lchunk = tid % CPR;
 
-    const uint16_t* hrow[8];
+    const uint16_t* hrow[LH];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int u = min(u0 + (tid >> 3) + 32 * i, n_rows - 1);
+    for (int i = 0; i < LH; ++i) {
+        const int u = min(u0 + lrow + RPP * i, n_rows - 1);
         const int64_t id = a.ids ? a.ids[u] : a.id_base + u;
-        hrow[i] = a.H + id * a.ds + (tid & 7) * 8;
+        hrow[i] = a.H + id * a.ds + lchunk * 8;
     }
-    const uint16_t* wrow[3];
+    const uint16_t* wrow[LW];
 #pragma unroll
-    for (int i = 0; i < 3; ++i) {
-        const int idx = min(tid + 256 * i, TN * 8 - 1);
-        wrow[i] = a.Wb + (size_t)min(n0 + (idx >> 3), a.d - 1) * a.ds + (idx & 7) * 8;
+    for (int i = 0; i < LW; ++i)
+        wrow[i] = a.Wb + (size_t)min(n0 + min(lrow + RPP * i, TN - 1), a.d - 1) * a.ds + lchunk * 8;
+
+    u32x4 rh[LH], rw[LW];
+#pragma unroll
+    for (int i = 0; i < LH; ++i) rh[i] = *reinterpret_cast<const u32x4*>(hrow[i]);
+#pragma unroll
+    for (int i = 0; i < LW; ++i) rw[i] = *reinterpret_cast<const u32x4*>(wrow[i]);
+
+    // The accumulators start from the structural rows, requested together with the first
+    // slice: a lane holds, per block, 4 consecutive coordinates of one row (clamped addresses;
+    // rows and coordinates past the end are never stored).
+    floatx4 acc[RB][5];
+#pragma unroll
+    for (int bu = 0; bu < RB; ++bu) {
+        const int u = min(u0 + wave * (BU / 4) + bu * 16 + (lane & 15), n_rows - 1);
+        const int64_t id = a.ids ? a.ids[u] : a.id_base + u;
+        const float* erow = a.E + id * a.d;
+#pragma unroll
+        for (int bn = 0; bn < 5; ++bn) {
+            const float4 e = *reinterpret_cast<const float4*>(erow + min(n0 + bn * 16 + (lane >> 4) * 4, a.d - 4));
+            acc[bu][bn] = floatx4{e.x, e.y, e.z, e.w};
+        }
     }
 
-    floatx4 acc[4][5];
+    for (int k0 = 0; k0 < a.ds; k0 += KSF) {
 #pragma unroll
-    for (int bu = 0; bu < 4; ++bu)
+        for (int i = 0; i < LH; ++i) *lds_chunk<KSF>(Hs, lrow + RPP * i, lchunk) = rh[i];
 #pragma unroll
-        for (int bn = 0; bn < 5; ++bn) acc[bu][bn] = floatx4{0.f, 0.f, 0.f, 0.f};
-
-    u32x4 rh[8], rw[3];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) rh[i] = *reinterpret_cast<const u32x4*>(hrow[i]);
-#pragma unroll
-    for (int i = 0; i < 3; ++i) rw[i] = *reinterpret_cast<const u32x4*>(wrow[i]);
-
-    for (int k0 = 0; k0 < a.ds; k0 += KS) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) *lds_chunk(Hs, (tid >> 3) + 32 * i, tid & 7) = rh[i];
-#pragma unroll
-        for (int i = 0; i < 3; ++i) *lds_chunk(Ws, (tid >> 3) + 32 * i, tid & 7) = rw[i];
+        for (int i = 0; i < LW; ++i) *lds_chunk<KSF>(Ws, lrow + RPP * i, lchunk) = rw[i];
         __syncthreads();
         {   // next slice (the last iteration re-reads its own: no branch around the loads)
-            const int kn = min(k0 + KS, a.ds - KS);
+            const int kn = min(k0 + KSF, a.ds - KSF);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) rh[i] = *reinterpret_cast<const u32x4*>(hrow[i] + kn);
+            for (int i = 0; i < LH; ++i) rh[i] = *reinterpret_cast<const u32x4*>(hrow[i] + kn);
 #pragma unroll
-            for (int i = 0; i < 3; ++i) rw[i] = *reinterpret_cast<const u32x4*>(wrow[i] + kn);
+            for (int i = 0; i < LW; ++i) rw[i] = *reinterpret_cast<const u32x4*>(wrow[i] + kn);
         }
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
+        for (int kk = 0; kk < KSF / 32; ++kk) {
             const int chunk = kk * 4 + (lane >> 4);
-            bf16x8 fh[4], fw[5];
+            bf16x8 fh[RB], fw[5];
 #pragma unroll
-            for (int bu = 0; bu < 4; ++bu) fh[bu] = frag(Hs, wave * 64 + bu * 16 + (lane & 15), chunk);
+            for (int bu = 0; bu < RB; ++bu) fh[bu] = frag<KSF>(Hs, wave * (BU / 4) + bu * 16 + (lane & 15), chunk);
 #pragma unroll
-            for (int bn = 0; bn < 5; ++bn) fw[bn] = frag(Ws, bn * 16 + (lane & 15), chunk);
+            for (int bn = 0; bn < 5; ++bn) fw[bn] = frag<KSF>(Ws, bn * 16 + (lane & 15), chunk);
 #pragma unroll
-            for (int bu = 0; bu < 4; ++bu)
+            for (int bu = 0; bu < RB; ++bu)
 #pragma unroll
                 for (int bn = 0; bn < 5; ++bn)
                     acc[bu][bn] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[bn], fh[bu], acc[bu][bn], 0, 0, 0);
@@ -139,19 +160,16 @@ __global__ __launch_bounds__(256) void sem_fuse_kernel(const SemFuseArgs a) {
     }
     // a lane holds, per block, 4 consecutive coordinates of one row
 #pragma unroll
-    for (int bu = 0; bu < 4; ++bu) {
-        const int u = u0 + wave * 64 + bu * 16 + (lane & 15);
+    for (int bu = 0; bu < RB; ++bu) {
+        const int u = u0 + wave * (BU / 4) + bu * 16 + (lane & 15);
         if (u >= n_rows) continue;
-        const int64_t id = a.ids ? a.ids[u] : a.id_base + u;
-        const float* erow = a.E + id * a.d;
         float* orow = a.out + (size_t)u * a.d;
 #pragma unroll
         for (int bn = 0; bn < 5; ++bn) {
             const int n = n0 + bn * 16 + (lane >> 4) * 4;
             if (n >= a.d) continue;
-            const float4 e = *reinterpret_cast<const float4*>(erow + n);
             *reinterpret_cast<float4*>(orow + n) =
-                make_float4(e.x + acc[bu][bn][0], e.y + acc[bu][bn][1], e.z + acc[bu][bn][2], e.w + acc[bu][bn][3]);
+                make_float4(acc[bu][bn][0], acc[bu][bn][1], acc[bu][bn][2], acc[bu][bn][3]);
         }
     }
 }
@@ -323,15 +341,20 @@ hipError_t launch_translate_refs(const int32_t* in_ref, const int32_t* in_gslot,
     return hipGetLastError();
 }
 
-hipError_t launch_sem_fuse(const SemFuseArgs& a, hipStream_t s) {
-    if (a.n_rows <= 0) return hipSuccess;
-    if (a.ds <= 0 || a.ds % KS || a.d % 4) return hipErrorInvalidValue;
-    const int64_t u_tiles = (a.n_rows + 255) / 256;
+template <int BU, int KSF>
+hipError_t launch_sem_fuse_as(const SemFuseArgs& a, hipStream_t s) {
+    const int64_t u_tiles = (a.n_rows + BU - 1) / BU;
     const int64_t n_tiles = (a.d + TN - 1) / TN;
     const int64_t blocks = ((u_tiles + 7) / 8) * 8 * n_tiles;
     if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(sem_fuse_kernel, dim3((unsigned)blocks), dim3(256), 0, s, a);
+    hipLaunchKernelGGL((sem_fuse_kernel<BU, KSF>), dim3((unsigned)blocks), dim3(256), 0, s, a);
     return hipGetLastError();
+}
+
+hipError_t launch_sem_fuse(const SemFuseArgs& a, hipStream_t s) {
+    if (a.n_rows <= 0) return hipSuccess;
+    if (a.ds <= 0 || a.ds % KS || a.d % 4) return hipErrorInvalidValue;
+    return launch_sem_fuse_as<256, 64>(a, s);
 }
 
 int sem_wgrad_splits(int64_t n_rows_bound, int d, int ds) {
