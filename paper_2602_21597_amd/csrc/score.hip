@@ -15,6 +15,16 @@
 namespace ngdb {
 namespace {
 
+__device__ __forceinline__ int32_t cand_id(const ScoreArgs& a, int i, int has_pos, int c) {
+    return (has_pos && c == 0) ? a.pos[i] : a.cand[(size_t)i * a.C + (c - has_pos)];
+}
+template <int NCH>
+__device__ __forceinline__ void load_row(const ScoreArgs& a, int32_t e, int lane, int d4, float4 (&dst)[NCH]) {
+    const float4* row = reinterpret_cast<const float4*>(a.E + (size_t)e * a.d);
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) dst[ch] = row[min(ch * 64 + lane, d4 - 1)];
+}
+
 template <int NCH, int NW, bool TRAIN>
 __global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
     extern __shared__ __attribute__((aligned(16))) float lds[];
@@ -46,21 +56,17 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
     for (int ch = 0; ch < NCH; ++ch) dyr[ch] = make_float4(0.f, 0.f, 0.f, 0.f);
     float lsum = 0.f;
 
-    auto load_row = [&](int c, float4* dst) {
-        const int32_t e = (has_pos && c == 0) ? a.pos[i] : a.cand[(size_t)i * a.C + (c - has_pos)];
-        const float4* row = reinterpret_cast<const float4*>(a.E + (size_t)e * a.d);
-#pragma unroll
-        for (int ch = 0; ch < NCH; ++ch) {
-            const int col = ch * 64 + lane;
-            dst[ch] = col < d4 ? row[col] : make_float4(0.f, 0.f, 0.f, 0.f);
-        }
-    };
-
+    // The id of a candidate is requested two rounds ahead of its use and its row one round
+    // ahead, so that a row request never waits for its id (a second row in flight per
+    // wavefront costs more in occupancy than it hides).  Requests past the end repeat the
+    // last candidate (clamped, no branches around loads).
     float4 cur[NCH], nxt[NCH];
     int c = wave;
-    if (c < CT) load_row(c, cur);
+    int32_t e_nxt = cand_id(a, i, has_pos, min(c + NW, CT - 1));
+    if (c < CT) load_row<NCH>(a, cand_id(a, i, has_pos, c), lane, d4, cur);
     for (; c < CT; c += NW) {
-        if (c + NW < CT) load_row(c + NW, nxt);
+        load_row<NCH>(a, e_nxt, lane, d4, nxt);
+        e_nxt = cand_id(a, i, has_pos, min(c + 2 * NW, CT - 1));
         float best = INFINITY;
         int bw = 0;
         for (int b = 0; b < nb; ++b) {
@@ -173,6 +179,7 @@ hipError_t launch_nch(const ScoreArgs& a, bool train, hipStream_t s) {
 
 hipError_t launch_score(const ScoreArgs& a, bool train, hipStream_t s) {
     if (a.B <= 0) return hipSuccess;
+    if (a.C + (a.pos ? 1 : 0) <= 0) return hipErrorInvalidValue;   // the kernel clamps into a non-empty candidate list
     if (a.d <= 256) return launch_nch<1>(a, train, s);
     if (a.d <= 512) return launch_nch<2>(a, train, s);
     if (a.d <= 1024) return launch_nch<4>(a, train, s);
