@@ -187,10 +187,11 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
         }
     }
 
-    // every wavefront runs the same number of rounds (tiles past the end load zeros),
-    // so that the workgroup barriers below are reached by all
+    // A wavefront stages its tiles in its own LDS area and LDS executes a wavefront's
+    // instructions in order, so the k loop needs no workgroup barrier: wavefronts run
+    // independently (their memory waits do not line up) and only over the tiles they own.
     const int nk = (a.K + BK - 1) / BK;
-    const int rounds = (nk + NW - 1) / NW;     // K == 0: no round, no load
+    const int rounds = nk > wave ? (nk - wave + NW - 1) / NW : 0;
     int kcur = wave * BK;
     if (rounds > 0) {
         issue_a<BM, LA, AK>(a, lane, m0, kcur, has_add, arow, aadd, ra, rd);
@@ -199,7 +200,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
     for (int it = 0; it < rounds; ++it) {
         stage_a<BM, LA, LDA, AK>(a, As, lane, m0, kcur, has_add, copy_out, avalid, ra, rd);
         stage_b<BN, LB, LDB, BKC>(a, Bs, lane, n0, kcur, rb);
-        __syncthreads();
+        __builtin_amdgcn_wave_barrier();        // staged tile before its reads (compiler ordering only)
         if (it + 1 < rounds) {
             kcur = ((it + 1) * NW + wave) * BK;
             issue_a<BM, LA, AK>(a, lane, m0, kcur, has_add, arow, aadd, ra, rd);
@@ -224,8 +225,9 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[kk][i], bv[kk][j], acc[i][j], 0, 0, 0);
-        __syncthreads();
+        __builtin_amdgcn_wave_barrier();        // reads of this tile before the next one is staged
     }
+    __syncthreads();                            // the staging areas are reused for the reduction
 
     // partial tiles -> LDS.  Accumulator layout of a 32x32 block: lane owns column
     // (lane & 31) and rows 8*(r/4) + 4*(lane/32) + r%4, r = 0..15.
