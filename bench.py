@@ -1,6 +1,7 @@
 """Benchmark of the NGDB training hot path on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--streams S]
+    python bench.py --rank 1024 --config 4 --steps 3 --warmup 1      (all-entity ranking pass)
 
 One step = plan one batch (host) + one ngdb_train_step (forward over the
 operator-level frontiers, scoring against 1 positive and K negatives per query,
@@ -97,6 +98,68 @@ def kernel_models(cfg, pexp, touched):
     return models
 
 
+VALU_PEAK_TOPS = 39.3     # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz, one fp32 op per lane and clock
+                          # (packed forms are switched off in this build)
+
+
+def rank_bench(args, cfg, kg, params, sem_bits):
+    """All-entity ranking pass (ngdb_score without candidates): Q queries against every entity,
+    top-10 by L1 distance.  One step = one pass.  Prints ONE JSON line."""
+    from oracle import model as om
+    from oracle import rank as orank
+    Q, k = args.rank, 10
+    qb = wl.make_batch(kg, Q, cfg.mix, cfg.seed + 7)
+    cpu = None
+    sample = args.cpu_sample if args.cpu_sample >= 0 else (2 if cfg.N <= 100000 else 0)
+    if sample > 0:
+        say("CPU oracle ranking of %d queries" % sample)
+        M = om.Model(params, cfg.gamma, sem_bits)
+        t0 = time.perf_counter()
+        for q in range(sample):
+            orank.topk_all(qb, q, M, k)
+        dtc = time.perf_counter() - t0
+        cpu = {"value": sample / dtc, "unit": "queries/s", "cores": os.cpu_count(), "kind": "oracle",
+               "sample": "%d queries against all %d entities (fp64 numpy, BLAS threads as configured), %.1f s"
+                         % (sample, cfg.N, dtc)}
+        del M
+    import torch
+    from paper_2602_21597_amd import Engine
+    eng = Engine(cfg.N, cfg.R, cfg.d, cfg.h, cfg.gamma, d_sem=cfg.d_sem)
+    eng.bind_numpy(params, sem_bits=sem_bits)
+    plan = eng.plan(qb)
+    rows = plan.export()["n_roots"]
+    for _ in range(args.warmup):
+        eng.rank_all(plan, k)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        eng.rank_all(plan, k)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+    eng.set_timing(("score",))
+    eng.get_timing(reset=True)
+    for _ in range(args.steps):
+        eng.rank_all(plan, k)
+    ms, n = eng.get_timing(reset=True)["score"]
+    # subtract and |.|-accumulate per coordinate, branch row and entity
+    ops = 2.0 * rows * cfg.N * cfg.d
+    ach = ops / (ms / n * 1e-3) / 1e12
+    out = {"metric": "all-entity ranking queries/sec (forward + L1 distance to every entity + top-10)",
+           "value": Q / dt, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": 1e3 * dt, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "f32", "data": "synthetic",
+           "config": {"workload": "configs[%d] %s ranking pass: %d queries (%d branch rows) x N=%d entities, d=%d%s, top-%d"
+                      % (cfg.index, cfg.name, Q, rows, cfg.N, cfg.d,
+                         " d_sem=%d" % cfg.d_sem if cfg.d_sem else "", k)},
+           "roofline": {"bound": "alu", "kernel": "rank (distance tiles + top-k merge%s)" % (
+                            " + projection of every entity chunk" if cfg.d_sem else ""),
+                        "achieved": ach, "peak": VALU_PEAK_TOPS, "unit": "Tlane-op/s", "frac": ach / VALU_PEAK_TOPS,
+                        "traffic": None, "avg_us": 1e3 * ms / n,
+                        "algorithmic_work_per_launch": ops},
+           "cpu_baseline": cpu}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -105,6 +168,8 @@ def main():
     ap.add_argument("--config", type=int, default=1)
     ap.add_argument("--streams", type=int, default=0, help="0 = the workload's default")
     ap.add_argument("--cpu-sample", type=int, default=-1, help="queries timed on the CPU oracle (0 = skip)")
+    ap.add_argument("--rank", type=int, default=0, metavar="Q",
+                    help="time the all-entity ranking pass of Q queries instead of the training step")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="also run the library's plain copy kernel on this many MiB, 5 times (reference "
                          "for scaling rocprofv3 traffic counters)")
@@ -117,6 +182,10 @@ def main():
     cfg = wl.get_config(args.config)
     say("generating the graph (N=%d, T=%d)" % (cfg.N, cfg.T))
     kg = wl.make_kg(cfg.N, cfg.R, cfg.T, cfg.alpha, cfg.seed)
+    if args.rank:
+        params = wl.make_params(cfg.N, cfg.R, cfg.d, cfg.h, cfg.seed + 3, d_sem=cfg.d_sem)
+        sem_bits = wl.make_sem_features(cfg.N, cfg.d_sem, cfg.seed + 5) if cfg.d_sem else None
+        return rank_bench(args, cfg, kg, params, sem_bits)
     say("generating %d batches of %d queries, negatives, parameters" % (N_BATCHES, cfg.B))
     batches = [wl.make_batch(kg, cfg.B, cfg.mix, cfg.seed + 10 + i) for i in range(N_BATCHES)]
     negs_np = [wl.make_negatives(cfg.N, cfg.B, cfg.K, cfg.seed + 50 + i) for i in range(N_BATCHES)]
