@@ -131,18 +131,30 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
     const int lane = tid & 63;
     const int wave = tid >> 6;
     // which problem of the group this workgroup works on (uniform, stays in scalar registers)
-    int p = 0;
+    int p = 0, first = g.tile_start[0], last = g.tile_start[1];
 #pragma unroll
     for (int i = 1; i < GEMM_MAX_GROUP; ++i)
-        if (i < g.count && (int)blockIdx.x >= g.tile_start[i]) p = i;
+        if (i < g.count && (int)blockIdx.x >= g.tile_start[i]) {
+            p = i;
+            first = g.tile_start[i];
+            last = g.tile_start[i + 1];
+        }
     GemmArgs a = g.p[0];
 #pragma unroll
     for (int i = 1; i < GEMM_MAX_GROUP; ++i)
         if (i == p) a = g.p[i];
-    const int tile = (int)blockIdx.x - g.tile_start[p];
-    const int tiles_n = (a.N + BN - 1) / BN;
-    const int m0 = (tile / tiles_n) * BM;
-    const int n0 = (tile % tiles_n) * BN;
+    // Workgroups are dealt round-robin to the 8 dies, each with its own L2.  Every problem
+    // owns a multiple of 8 workgroups, and die x takes the x-th eighth of the problem's
+    // tiles, ordered so that this eighth is a slab along the longer output side: a die then
+    // reads one slab of one operand and the whole of the other, not both whole.
+    const int local = (int)blockIdx.x - first;
+    const int per_die = (last - first) >> 3;
+    const int tile = (local & 7) * per_die + (local >> 3);
+    const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
+    if (tile >= tiles_m * tiles_n) return;
+    const bool m_major = a.M >= a.N;
+    const int m0 = (m_major ? tile / tiles_n : tile % tiles_m) * BM;
+    const int n0 = (m_major ? tile % tiles_n : tile / tiles_m) * BN;
     const bool first_n_tile = n0 == 0;
     constexpr int TM = BM / 32, TN = BN / 32;
     constexpr int LDA = BM + PAD, LDB = BN + PAD;
@@ -297,7 +309,7 @@ hipError_t dispatch_layout(GemmGroup& g, hipStream_t s) {
     int tiles = 0;
     for (int i = 0; i < g.count; ++i) {
         g.tile_start[i] = tiles;
-        tiles += ((g.p[i].M + BM - 1) / BM) * ((g.p[i].N + BN - 1) / BN);
+        tiles += (((g.p[i].M + BM - 1) / BM) * ((g.p[i].N + BN - 1) / BN) + 7) / 8 * 8;
     }
     for (int i = g.count; i <= GEMM_MAX_GROUP; ++i) g.tile_start[i] = tiles;
     dim3 grid(tiles), block(NW * 64);

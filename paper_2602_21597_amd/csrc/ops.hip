@@ -77,9 +77,17 @@ __global__ __launch_bounds__(256) void colsum_final_kernel(const ColsumJobs jobs
     const ColsumJob j = jobs.job[blockIdx.y];
     const int c = blockIdx.x * 256 + threadIdx.x;
     if (c >= j.cols) return;
-    float s = 0.f;
-    for (int k = 0; k < j.chunks; ++k) s += j.part[(size_t)k * j.cols + c];
-    j.out[c] = s;
+    // four running sums (fixed assignment of chunks to sums): the loads of a round do not wait for one another
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    int k = 0;
+    for (; k + 4 <= j.chunks; k += 4) {
+        s0 += j.part[(size_t)(k + 0) * j.cols + c];
+        s1 += j.part[(size_t)(k + 1) * j.cols + c];
+        s2 += j.part[(size_t)(k + 2) * j.cols + c];
+        s3 += j.part[(size_t)(k + 3) * j.cols + c];
+    }
+    for (; k < j.chunks; ++k) s0 += j.part[(size_t)k * j.cols + c];
+    j.out[c] = (s0 + s1) + (s2 + s3);
 }
 
 __global__ __launch_bounds__(256) void fill_zero_kernel(float* p, size_t n) {
