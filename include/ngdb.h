@@ -41,7 +41,10 @@
  *   - A stream argument is a hipStream_t passed as void*; NULL = the null
  *     stream.  Calls that take a stream are asynchronous with respect to the
  *     host unless stated otherwise.  One context must not be used from two
- *     host threads or two streams at the same time.
+ *     host threads or two streams at the same time, with one exception:
+ *     ngdb_plan and ngdb_plan_free may run on a second host thread while the
+ *     first enqueues steps (the producer/consumer arrangement of Sec. 4.3:
+ *     batch t+1 is planned while step t runs).
  *   - All index arrays are int32.  d and h must be multiples of 4.
  */
 #ifndef NGDB_H

@@ -6,6 +6,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -84,6 +85,7 @@ struct ngdb_ctx_s {
     size_t gw_off[13]{};
     hipStream_t upload = nullptr;        // plan uploads, independent of the compute streams
     std::vector<PlanBlob> blob_pool;
+    std::mutex mu;                       // guards blob_pool and err: planning may run on a second host thread
     // kernel timing
     uint32_t timing_mask = 0;
     struct Bracket { int cls; hipEvent_t a, b; };
@@ -100,7 +102,10 @@ namespace {
 thread_local std::string g_create_err;
 
 int fail(ngdb_ctx_t* c, int code, const std::string& msg) {
-    if (c) c->err = msg;
+    if (c) {
+        std::lock_guard<std::mutex> lk(c->mu);
+        c->err = msg;
+    }
     return code;
 }
 
@@ -344,12 +349,17 @@ int enqueue_forward(ngdb_ctx_t* c, const ngdb_plan_t* pl, const EntRows& er, hip
         for (const Segment& sg : segs) {
             if (sg.type != T_INTER) continue;
             Timed tm(c, NGDB_TK_INTER, s);
+            InterJobs ij{};
+            ij.d = d;
             for (int g = sg.g_lo; g < sg.g_hi; ++g) {
                 const size_t mb = (size_t)pl->hp.g_mlp_base[g] * d;
-                HIPCHK(c, launch_inter_fwd(ptr<float>(c->Z[T_INTER]) + mb, ptr<float>(c->Att) + mb,
-                                           ptr<float>(c->act) + (size_t)pl->hp.g_out_base[g] * d, pl->hp.g_n[g],
-                                           pl->hp.g_nin[g], d, s));
+                if (ij.count == INTER_MAX_JOBS) return fail(c, NGDB_ERR_UNSUPPORTED, "too many intersection classes in one level");
+                InterJob& jb = ij.job[ij.count++];
+                jb.X = ptr<float>(c->Z[T_INTER]) + mb; jb.Att = ptr<float>(c->Att) + mb;
+                jb.out = ptr<float>(c->act) + (size_t)pl->hp.g_out_base[g] * d;
+                jb.n = pl->hp.g_n[g]; jb.k = pl->hp.g_nin[g];
             }
+            HIPCHK(c, launch_inter(ij, false, s));
         }
     }
     return NGDB_OK;
@@ -370,12 +380,18 @@ int enqueue_backward(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t s) {
             const float* addend = nullptr;
             if (sg.type == T_INTER) {
                 Timed tm(c, NGDB_TK_INTER, s);
+                InterJobs ij{};
+                ij.d = d;
                 for (int g = sg.g_lo; g < sg.g_hi; ++g) {
                     const size_t mb = (size_t)hp.g_mlp_base[g] * d;
-                    HIPCHK(c, launch_inter_bwd(ptr<float>(c->Z[T_INTER]) + mb, ptr<float>(c->Att) + mb,
-                                               dact + (size_t)hp.g_out_base[g] * d, ptr<float>(c->dAtt) + mb,
-                                               ptr<float>(c->Dx) + mb, hp.g_n[g], hp.g_nin[g], d, s));
+                    if (ij.count == INTER_MAX_JOBS) return fail(c, NGDB_ERR_UNSUPPORTED, "too many intersection classes in one level");
+                    InterJob& jb = ij.job[ij.count++];
+                    jb.X = ptr<float>(c->Z[T_INTER]) + mb; jb.Att = ptr<float>(c->Att) + mb;
+                    jb.dY = dact + (size_t)hp.g_out_base[g] * d;
+                    jb.dAtt = ptr<float>(c->dAtt) + mb; jb.Dx = ptr<float>(c->Dx) + mb;
+                    jb.n = hp.g_n[g]; jb.k = hp.g_nin[g];
                 }
+                HIPCHK(c, launch_inter(ij, true, s));
                 dOut = ptr<float>(c->dAtt) + (size_t)sg.mlp_base * d;
                 addend = ptr<float>(c->Dx) + (size_t)sg.mlp_base * d;
             } else {
@@ -719,12 +735,15 @@ int ngdb_plan(ngdb_ctx_t* c, const ngdb_query_batch* qb, ngdb_plan_t** out) {
                  o_nru = put(std::vector<int32_t>{(int32_t)hp.r_uniq.size()});
     // a recycled blob (its last reader has finished) or a new one
     PlanBlob pb;
-    for (size_t i = 0; i < c->blob_pool.size(); ++i)
-        if (c->blob_pool[i].cap >= blob.size()) {
-            pb = c->blob_pool[i];
-            c->blob_pool.erase(c->blob_pool.begin() + i);
-            break;
-        }
+    {
+        std::lock_guard<std::mutex> lk(c->mu);
+        for (size_t i = 0; i < c->blob_pool.size(); ++i)
+            if (c->blob_pool[i].cap >= blob.size()) {
+                pb = c->blob_pool[i];
+                c->blob_pool.erase(c->blob_pool.begin() + i);
+                break;
+            }
+    }
     if (!pb.dev) {
         pb.cap = blob.size() + blob.size() / 2 + 1024;
         if (hipMalloc((void**)&pb.dev, pb.cap * 4) != hipSuccess ||
@@ -742,7 +761,10 @@ int ngdb_plan(ngdb_ctx_t* c, const ngdb_query_batch* qb, ngdb_plan_t** out) {
     std::memcpy(pb.pinned, blob.data(), blob.size() * 4);
     if (hipMemcpyAsync(pb.dev, pb.pinned, blob.size() * 4, hipMemcpyHostToDevice, c->upload) != hipSuccess ||
         hipStreamSynchronize(c->upload) != hipSuccess) {
-        c->blob_pool.push_back(pb);
+        {
+            std::lock_guard<std::mutex> lk(c->mu);
+            c->blob_pool.push_back(pb);
+        }
         delete pl;
         return fail(c, NGDB_ERR_HIP, "plan upload failed");
     }
@@ -776,7 +798,10 @@ int ngdb_plan_export(const ngdb_plan_t* pl, ngdb_plan_view* v) {
 
 void ngdb_plan_free(ngdb_plan_t* pl) {
     if (!pl) return;
-    if (pl->owner && pl->blob.dev) pl->owner->blob_pool.push_back(pl->blob);   // reused once last_use has passed
+    if (pl->owner && pl->blob.dev) {   // reused once last_use has passed
+        std::lock_guard<std::mutex> lk(pl->owner->mu);
+        pl->owner->blob_pool.push_back(pl->blob);
+    }
     delete pl;
 }
 

@@ -74,11 +74,22 @@ struct GemmGroup {
 hipError_t launch_gemm_group(const GemmArgs* problems, int count, hipStream_t s);
 
 // ---------------------------------------------------------------- elementwise ops (ops.hip)
-// Intersection of n members with k inputs: rows j*n+i of X (inputs) and Att (logits).
-hipError_t launch_inter_fwd(const float* X, const float* Att, float* out, int n, int k, int d, hipStream_t s);
-// dAtt[j*n+i] = w_j*(dy*x_j - sum_l w_l dy x_l),  Dx[j*n+i] = w_j*dy
-hipError_t launch_inter_bwd(const float* X, const float* Att, const float* dY, float* dAtt, float* Dx,
-                            int n, int k, int d, hipStream_t s);
+// Intersections of one level, one job per cardinality class: n members with k inputs each,
+// rows j*n+i of X (inputs) and Att (logits).  Forward: out[i] = sum_j w_j x_j, w = softmax over
+// the inputs per coordinate.  Backward: dAtt[j*n+i] = w_j*(dy*x_j - sum_l w_l dy x_l),
+// Dx[j*n+i] = w_j*dy.
+constexpr int INTER_MAX_JOBS = 8;
+struct InterJob {
+    const float *X, *Att, *dY;
+    float *out, *dAtt, *Dx;
+    int n, k;
+};
+struct InterJobs {
+    int count;
+    int d;
+    InterJob job[INTER_MAX_JOBS];
+};
+hipError_t launch_inter(const InterJobs& jobs, bool backward, hipStream_t s);
 // out[c] = sum_m X[m*ld + c], c < cols, for several matrices in one launch pair (fixed
 // summation order); `part` is scratch of COLSUM_MAX_CHUNKS * cols floats per matrix
 constexpr int COLSUM_MAX_CHUNKS = 128;

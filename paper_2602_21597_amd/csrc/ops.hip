@@ -8,42 +8,50 @@
 namespace ngdb {
 namespace {
 
-// y_i = sum_j softmax_j(att_j)_c * x_j,c : one thread per (member, coordinate)
+// y_i = sum_j softmax_j(att_j)_c * x_j,c : one thread per (member, coordinate); the cardinality
+// classes of one level are the jobs of one launch (blockIdx.y).  The loops over inputs run to
+// the compile-time maximum under a predicate, so the per-input values stay in registers.
 template <bool BWD>
-__global__ __launch_bounds__(256) void inter_kernel(const float* __restrict__ X, const float* __restrict__ Att,
-                                                    const float* __restrict__ dY, float* __restrict__ out,
-                                                    float* __restrict__ dAtt, float* __restrict__ Dx,
-                                                    int n, int k, int d) {
+__global__ __launch_bounds__(256) void inter_kernel(const InterJobs jobs) {
+    const InterJob jb = jobs.job[blockIdx.y];
+    const int d = jobs.d, n = jb.n, k = jb.k;
     const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= (size_t)n * d) return;
     const int i = (int)(t / d), c = (int)(t % d);
     float a[NGDB_MAX_CARD], x[NGDB_MAX_CARD];
     float mx = -INFINITY;
-    for (int j = 0; j < k; ++j) {
-        const size_t row = (size_t)j * n + i;
-        a[j] = Att[row * d + c];
-        x[j] = X[row * d + c];
-        mx = fmaxf(mx, a[j]);
+#pragma unroll
+    for (int j = 0; j < NGDB_MAX_CARD; ++j) {
+        const size_t row = (size_t)min(j, k - 1) * n + i;
+        a[j] = jb.Att[row * d + c];
+        x[j] = jb.X[row * d + c];
+        if (j < k) mx = fmaxf(mx, a[j]);
     }
     float den = 0.f;
-    for (int j = 0; j < k; ++j) {
-        a[j] = expf(a[j] - mx);
+#pragma unroll
+    for (int j = 0; j < NGDB_MAX_CARD; ++j) {
+        a[j] = j < k ? expf(a[j] - mx) : 0.f;
         den += a[j];
     }
     const float inv = 1.f / den;
     if (!BWD) {
         float y = 0.f;
-        for (int j = 0; j < k; ++j) y += a[j] * inv * x[j];
-        out[(size_t)i * d + c] = y;
+#pragma unroll
+        for (int j = 0; j < NGDB_MAX_CARD; ++j) y += a[j] * inv * x[j];
+        jb.out[(size_t)i * d + c] = y;
     } else {
-        const float dy = dY[(size_t)i * d + c];
+        const float dy = jb.dY[(size_t)i * d + c];
         float tall = 0.f;
-        for (int j = 0; j < k; ++j) tall += a[j] * inv * x[j] * dy;
-        for (int j = 0; j < k; ++j) {
-            const size_t row = (size_t)j * n + i;
-            const float w = a[j] * inv;
-            dAtt[row * d + c] = w * (dy * x[j] - tall);
-            Dx[row * d + c] = w * dy;
+#pragma unroll
+        for (int j = 0; j < NGDB_MAX_CARD; ++j) tall += a[j] * inv * x[j] * dy;
+#pragma unroll
+        for (int j = 0; j < NGDB_MAX_CARD; ++j) {
+            if (j < k) {
+                const size_t row = (size_t)j * n + i;
+                const float w = a[j] * inv;
+                jb.dAtt[row * d + c] = w * (dy * x[j] - tall);
+                jb.Dx[row * d + c] = w * dy;
+            }
         }
     }
 }
@@ -130,20 +138,17 @@ __global__ __launch_bounds__(256) void loss_reduce_kernel(const float* __restric
 
 }  // namespace
 
-hipError_t launch_inter_fwd(const float* X, const float* Att, float* out, int n, int k, int d, hipStream_t s) {
-    if (n <= 0) return hipSuccess;
-    const size_t total = (size_t)n * d;
-    hipLaunchKernelGGL((inter_kernel<false>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, X, Att,
-                       (const float*)nullptr, out, (float*)nullptr, (float*)nullptr, n, k, d);
-    return hipGetLastError();
-}
-
-hipError_t launch_inter_bwd(const float* X, const float* Att, const float* dY, float* dAtt, float* Dx, int n,
-                            int k, int d, hipStream_t s) {
-    if (n <= 0) return hipSuccess;
-    const size_t total = (size_t)n * d;
-    hipLaunchKernelGGL((inter_kernel<true>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, X, Att, dY,
-                       (float*)nullptr, dAtt, Dx, n, k, d);
+hipError_t launch_inter(const InterJobs& jobs, bool backward, hipStream_t s) {
+    if (jobs.count <= 0) return hipSuccess;
+    if (jobs.count > INTER_MAX_JOBS) return hipErrorInvalidValue;
+    size_t most = 0;
+    for (int i = 0; i < jobs.count; ++i) {
+        if (jobs.job[i].n <= 0 || jobs.job[i].k < 1 || jobs.job[i].k > NGDB_MAX_CARD) return hipErrorInvalidValue;
+        most = std::max(most, (size_t)jobs.job[i].n * jobs.d);
+    }
+    const dim3 grid((unsigned)((most + 255) / 256), jobs.count);
+    if (backward) hipLaunchKernelGGL((inter_kernel<true>), grid, dim3(256), 0, s, jobs);
+    else hipLaunchKernelGGL((inter_kernel<false>), grid, dim3(256), 0, s, jobs);
     return hipGetLastError();
 }
 

@@ -201,6 +201,34 @@ def test_fb15k237_shape_full_size():
     par.check_train_steps(case, steps=1)
 
 
+def test_planning_on_a_second_thread_gives_the_same_parameters():
+    _say("config 0: 12 steps, batch t+1 planned on a second host thread while step t is enqueued")
+    from concurrent.futures import ThreadPoolExecutor
+    import torch
+    case = par.Case.from_config(0)
+    kg = wl.make_kg(case.N, case.R, 10 * case.N, 2.1, 77)
+    c = wl.get_config(0)
+    batches = [wl.make_batch(kg, c.B, c.mix, 80 + i) for i in range(4)]
+    negs = [torch.from_numpy(wl.make_negatives(case.N, c.B, c.K, 90 + i)).cuda() for i in range(4)]
+    serial, threaded = case.engine(), case.engine()
+    for i in range(12):
+        p = serial.plan(batches[i % 4])
+        serial.train_step(p, negs[i % 4])
+        p.free()
+    with ThreadPoolExecutor(1) as ex:
+        nxt = ex.submit(threaded.plan, batches[0])
+        for i in range(12):
+            p = nxt.result()
+            if i + 1 < 12:
+                nxt = ex.submit(threaded.plan, batches[(i + 1) % 4])
+            threaded.train_step(p, negs[i % 4])
+            p.free()
+    a, b = serial.params_numpy(), threaded.params_numpy()
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k
+    assert threaded.step_count() == 12
+
+
 def test_errors_are_reported_not_raised_as_faults():
     from paper_2602_21597_amd import NgdbError, binding
     case = par.Case.from_config(0)
