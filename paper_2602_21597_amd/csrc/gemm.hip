@@ -199,6 +199,24 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
         }
     }
 
+    // Epilogue operands of this thread's output elements are requested here, ahead of the k
+    // loop (clamped addresses, uniform flags): nothing is waited for after the last MFMA.
+    constexpr int EPT = BM * BN / (NW * 64);
+    float e_bias[EPT], e_mask[EPT], e_add[EPT];
+    int e_orow[EPT];
+    const bool has_bias = a.bias != nullptr, has_mask = a.mask != nullptr, has_addend = a.addend != nullptr,
+               has_dst = a.dst_row != nullptr;
+#pragma unroll
+    for (int q = 0; q < EPT; ++q) {
+        const int e = tid + q * NW * 64;
+        const int lr = e / BN, lc = e % BN;
+        const int row = min(m0 + lr, a.M - 1), col = min(n0 + lc, a.N - 1);
+        e_bias[q] = has_bias ? a.bias[col] : 0.f;
+        e_mask[q] = has_mask ? a.mask[(size_t)row * a.ldmask + col] : 1.f;
+        e_add[q] = has_addend ? a.addend[(size_t)row * a.ldadd + col] : 0.f;
+        e_orow[q] = has_dst ? a.dst_row[row] : row;
+    }
+
     // A wavefront stages its tiles in its own LDS area and LDS executes a wavefront's
     // instructions in order, so the k loop needs no workgroup barrier: wavefronts run
     // independently (their memory waits do not line up) and only over the tiles they own.
@@ -272,23 +290,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
 #undef NGDB_ACC_TO_LDS
     __syncthreads();
 
-    // epilogue: all global operands of a thread's elements are requested first (clamped
-    // addresses, uniform flags), then the partial tiles are summed, then stored
-    constexpr int EPT = BM * BN / (NW * 64);
-    float e_bias[EPT], e_mask[EPT], e_add[EPT];
-    int e_orow[EPT];
-    const bool has_bias = a.bias != nullptr, has_mask = a.mask != nullptr, has_addend = a.addend != nullptr,
-               has_dst = a.dst_row != nullptr;
-#pragma unroll
-    for (int q = 0; q < EPT; ++q) {
-        const int e = tid + q * NW * 64;
-        const int lr = e / BN, lc = e % BN;
-        const int row = min(m0 + lr, a.M - 1), col = min(n0 + lc, a.N - 1);
-        e_bias[q] = has_bias ? a.bias[col] : 0.f;
-        e_mask[q] = has_mask ? a.mask[(size_t)row * a.ldmask + col] : 1.f;
-        e_add[q] = has_addend ? a.addend[(size_t)row * a.ldadd + col] : 0.f;
-        e_orow[q] = has_dst ? a.dst_row[row] : row;
-    }
+    // epilogue: the partial tiles are summed, the operands requested before the k loop applied
 #pragma unroll
     for (int q = 0; q < EPT; ++q) {
         const int e = tid + q * NW * 64;
@@ -348,8 +350,11 @@ hipError_t launch_gemm_group(const GemmArgs* problems, int count, hipStream_t s)
     }
     if (g.count == 0) return hipSuccess;
     if (blocks_small >= 2048) return dispatch_layout<64, 64, 4>(g, s);
-    if (max_k >= 512) return dispatch_layout<32, 64, 8>(g, s);
-    return dispatch_layout<32, 64, 4>(g, s);
+    // below that the launches of a step do not fill the chip: the smallest tile the MFMA block
+    // allows spreads a launch over the most compute units (a tile's MFMA work runs on one)
+    // (more than two such tiles per compute unit: 4 wavefronts per tile keep them all resident)
+    if (blocks_small * 2 > 512) return dispatch_layout<32, 32, 4>(g, s);
+    return dispatch_layout<32, 32, 8>(g, s);
 }
 
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) { return launch_gemm_group(&a, 1, s); }
