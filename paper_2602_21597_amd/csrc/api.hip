@@ -72,7 +72,7 @@ struct ngdb_ctx_s {
     int n_side = 0;
     // workspace
     DevBuf act, dact, Z[3], H[3], dH[3], Att, dAtt, Dx;
-    DevBuf score, coef, win, loss_terms, rec_coef, rec_row;
+    DevBuf score, coef, win, mask, loss_terms, rec_coef, rec_row;
     DevBuf keys_a, keys_b, vals_a, vals_b, hist, scan_tmp, uniq, seg_off, n_uniq;
     DevBuf rank_dist;   // distances of one entity chunk in the all-entity ranking
     DevBuf colsum_part; // 6 scratch areas of the bias-gradient column sums
@@ -227,7 +227,11 @@ int size_workspace(ngdb_ctx_t* c, const ngdb_plan_t* pl, int K, bool want_table_
     const size_t pairs = (size_t)hp.n_queries * ((size_t)K + 1);
     ENS(c->score, pairs * f);
     ENS(c->coef, pairs * f);
-    ENS(c->win, pairs * sizeof(int32_t));
+    if (c->cfg.d_sem > 0) {
+        ENS(c->mask, pairs * 64 * (d <= 256 ? 1 : (d <= 512 ? 2 : 4)));   // sign codes, per pair and lane
+    } else {
+        ENS(c->win, pairs * sizeof(int32_t));
+    }
     ENS(c->loss_terms, (size_t)hp.n_queries * f);
     ENS(c->rec_coef, ((size_t)hp.n_anchor + pairs) * f);
     ENS(c->rec_row, ((size_t)hp.n_anchor + pairs) * sizeof(int32_t));
@@ -482,7 +486,7 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
     sa.act = ptr<float>(c->act); sa.E = er.rows; sa.root_off = pl->d_root_off; sa.root_slot = pl->d_root_slot;
     sa.pos = er.pos; sa.cand = er.cand; sa.B = B; sa.C = K; sa.d = d; sa.max_branch = std::max(1, hp.max_branch);
     sa.gamma = c->cfg.gamma; sa.score = ptr<float>(c->score); sa.coef = ptr<float>(c->coef);
-    sa.win = ptr<int32_t>(c->win); sa.dact = ptr<float>(c->dact); sa.loss_terms = ptr<float>(c->loss_terms);
+    sa.win = sem ? nullptr : ptr<int32_t>(c->win); sa.mask = sem ? c->mask.p : nullptr; sa.dact = ptr<float>(c->dact); sa.loss_terms = ptr<float>(c->loss_terms);
     {
         Timed tm(c, NGDB_TK_SCORE, stream);
         hipError_t e = launch_score(sa, true, stream);
@@ -503,16 +507,17 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
     if (idx_aside) HIPCHK(c, hipStreamWaitEvent(stream, c->ev_index, 0));
     const int64_t n_contrib = (int64_t)hp.n_anchor + B + (int64_t)B * K;
     HIPCHK(c, launch_resolve(e_src, n_contrib, hp.n_anchor, hp.n_slots, B, K, ptr<float>(c->coef),
-                             ptr<int32_t>(c->win), ptr<float>(c->rec_coef), ptr<int32_t>(c->rec_row), stream));
+                             sem ? nullptr : ptr<int32_t>(c->win), ptr<float>(c->rec_coef), ptr<int32_t>(c->rec_row),
+                             stream));
     TableArgs te{};
     te.P = c->prm.E.p; te.Mo = c->prm.E.m; te.Vo = c->prm.E.v;
     te.uniq = ptr<int32_t>(c->uniq); te.seg_off = ptr<int32_t>(c->seg_off);
     te.n_uniq_dev = ptr<int32_t>(c->n_uniq); te.d = d;
     te.rec_coef = ptr<float>(c->rec_coef); te.rec_row = ptr<int32_t>(c->rec_row);
     te.dact = ptr<float>(c->dact); te.act = ptr<float>(c->act); te.g_out = apply ? nullptr : ptr<float>(c->gE);
-    if (sem) { te.ref_rows = ptr<float>(c->Ef); te.g_bf16 = ptr<uint16_t>(c->g_bf16); }
+    if (sem) { te.mask = c->mask.p; te.g_bf16 = ptr<uint16_t>(c->g_bf16); }
     TableArgs tr = te;
-    tr.ref_rows = nullptr; tr.g_bf16 = nullptr;
+    tr.g_bf16 = nullptr; tr.mask = nullptr;
     tr.P = c->prm.R.p; tr.Mo = c->prm.R.m; tr.Vo = c->prm.R.v;
     tr.uniq = pl->d_r_uniq; tr.seg_off = pl->d_r_seg_off; tr.n_uniq_dev = pl->d_n_r_uniq;
     tr.rec_coef = nullptr; tr.rec_row = pl->d_r_rec; tr.g_out = apply ? nullptr : ptr<float>(c->gR);
@@ -613,7 +618,7 @@ void ngdb_destroy(ngdb_ctx_t* c) {
     if (!c) return;
     (void)hipDeviceSynchronize();
     DevBuf* all[] = {&c->act, &c->dact, &c->Z[0], &c->Z[1], &c->Z[2], &c->H[0], &c->H[1], &c->H[2], &c->dH[0],
-                     &c->dH[1], &c->dH[2], &c->Att, &c->dAtt, &c->Dx, &c->score, &c->coef, &c->win,
+                     &c->dH[1], &c->dH[2], &c->Att, &c->dAtt, &c->Dx, &c->score, &c->coef, &c->win, &c->mask,
                      &c->loss_terms, &c->rec_coef, &c->rec_row, &c->keys_a, &c->keys_b, &c->vals_a, &c->vals_b, &c->hist, &c->scan_tmp,
                      &c->uniq, &c->seg_off, &c->n_uniq, &c->gW, &c->gE, &c->gR, &c->colsum_part, &c->rank_dist,
                      &c->Wb, &c->Ef, &c->inv, &c->refs_sem, &c->g_bf16, &c->wp_partial, &c->gWp, &c->rank_ef};

@@ -138,7 +138,11 @@ struct ScoreArgs {
     // outputs
     float* score;              // [B, C + (pos?1:0)]
     float* coef;               // same shape, dL/ds (training only)
-    int32_t* win;              // same shape, root slot of the winning branch (training only)
+    int32_t* win;              // same shape, root slot of the winning branch (training, if set)
+    void* mask;                // if set (training with text features): [pairs, 64] sign codes of (winning branch - entity row), 2 bits per
+                               // coordinate; lane l of a wavefront owns coordinates 4l..4l+3 of every
+                               // 256-coordinate chunk: 1, 2 or 4 bytes per lane for d <= 256, 512, 1024
+                               // (one of win / mask is set in training)
     float* dact;               // gradient arena (training only)
     float* loss_terms;         // [B] (training only)
 };
@@ -177,22 +181,25 @@ struct TableArgs {
     const int32_t* seg_off;        // [n_uniq+1]
     const int32_t* n_uniq_dev;     // device scalar
     int d;
-    // contribution records in segment order: rec_row[t] >= 0 is a row of act and
-    // the contribution is rec_coef[t] * sign(act row - table row); rec_row[t] < 0 is
-    // row -1-rec_row[t] of dact, added as it is (rec_coef may be null if all are)
+    // contribution records in segment order, gradient rows before pairs inside a segment:
+    // rec_row[t] < 0 is row -1-rec_row[t] of dact, added as it is; rec_row[t] >= 0 is a
+    // (query, candidate) pair and the contribution is rec_coef[t] * sign: without mask,
+    // rec_row[t] is a row of act and sign = sign(act row - table row); with mask (text
+    // features) it is the pair number and the signs are the pair's entry of mask (layout:
+    // ScoreArgs::mask).  rec_coef may be null if all records are gradient rows.
     const float* rec_coef;
     const int32_t* rec_row;
     const float* dact;
     const float* act;
+    const void* mask;              // set together with g_bf16
     float* g_out;                  // if set: write gradients [n_uniq, d] instead of updating
-    // text-feature fusion: the entity row a pair is scored against is ref_rows[u] (row of the
-    // touched-row list) instead of the table row, and the row gradient is also left in
-    // g_bf16 [n_uniq, d] (bf16 bit patterns) for the gradient of the projection
-    const float* ref_rows = nullptr;
+    // text-feature fusion: the row gradient is also left in g_bf16 [n_uniq, d] (bf16 bit
+    // patterns) for the gradient of the projection
     uint16_t* g_bf16 = nullptr;
 };
 // sorted contribution numbers -> records: c < n_rowsrc is gradient row row_base + c,
 // otherwise a (query, candidate) pair in the order [B positives | B*K negatives]
+// (win: winning rows per pair -> records carry act rows; null -> records carry pair numbers)
 hipError_t launch_resolve(const int32_t* src, int64_t n, int n_rowsrc, int row_base, int B, int K, const float* coef,
                           const int32_t* win, float* rec_coef, int32_t* rec_row, hipStream_t s);
 hipError_t launch_table_update(const TableArgs& a, const AdamHyper& hp, hipStream_t s);

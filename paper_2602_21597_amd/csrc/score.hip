@@ -15,6 +15,7 @@
 namespace ngdb {
 namespace {
 
+__device__ __forceinline__ uint32_t sign_code(float s) { return s > 0.f ? 1u : (s < 0.f ? 2u : 0u); }
 __device__ __forceinline__ int32_t cand_id(const ScoreArgs& a, int i, int has_pos, int c) {
     return (has_pos && c == 0) ? a.pos[i] : a.cand[(size_t)i * a.C + (c - has_pos)];
 }
@@ -25,7 +26,8 @@ __device__ __forceinline__ void load_row(const ScoreArgs& a, int32_t e, int lane
     for (int ch = 0; ch < NCH; ++ch) dst[ch] = row[min(ch * 64 + lane, d4 - 1)];
 }
 
-template <int NCH, int NW, bool TRAIN>
+// MASK (training with text features): sign codes per pair instead of the winning rows
+template <int NCH, int NW, bool TRAIN, bool MASK>
 __global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
     extern __shared__ __attribute__((aligned(16))) float lds[];
     const int i = blockIdx.x;
@@ -95,18 +97,23 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
             lsum += is_pos ? softplus_f(-s) : softplus_f(s) * invK;
             if (lane == 0) {
                 a.coef[pair] = coef;
-                a.win[pair] = a.root_slot[r0 + bw];
+                if (!MASK) a.win[pair] = a.root_slot[r0 + bw];
             }
+            uint32_t bits = 0;      // 2 bits per coordinate of this lane: 1 = positive, 2 = negative difference
 #pragma unroll
             for (int ch = 0; ch < NCH; ++ch) {
                 const int col = ch * 64 + lane;
                 if (col < d4) {
                     const float4 y = ybr[bw * d4 + col];
+                    const float sx = sgn(y.x - cur[ch].x), sy = sgn(y.y - cur[ch].y),
+                                sz = sgn(y.z - cur[ch].z), sw = sgn(y.w - cur[ch].w);
+                    if (MASK)
+                        bits |= (sign_code(sx) | (sign_code(sy) << 2) | (sign_code(sz) << 4) | (sign_code(sw) << 6)) << (8 * ch);
                     float4 g;
-                    g.x = coef * sgn(y.x - cur[ch].x);
-                    g.y = coef * sgn(y.y - cur[ch].y);
-                    g.z = coef * sgn(y.z - cur[ch].z);
-                    g.w = coef * sgn(y.w - cur[ch].w);
+                    g.x = coef * sx;
+                    g.y = coef * sy;
+                    g.z = coef * sz;
+                    g.w = coef * sw;
                     if (nb == 1) {
                         dyr[ch].x -= g.x; dyr[ch].y -= g.y; dyr[ch].z -= g.z; dyr[ch].w -= g.w;
                     } else {
@@ -115,6 +122,13 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
                         myacc[bw * d4 + col] = t;
                     }
                 }
+            }
+            // text features: the signs of the pair, from which the table pass rebuilds coef * sign
+            // (the scored row is not the table row there)
+            if (MASK) {
+                if (NCH == 1) reinterpret_cast<uint8_t*>(a.mask)[pair * 64 + lane] = (uint8_t)bits;
+                else if (NCH == 2) reinterpret_cast<uint16_t*>(a.mask)[pair * 64 + lane] = (uint16_t)bits;
+                else reinterpret_cast<uint32_t*>(a.mask)[pair * 64 + lane] = bits;
             }
         }
 #pragma unroll
@@ -150,13 +164,18 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
 
 template <int NCH, int NW>
 hipError_t launch_nw(const ScoreArgs& a, bool train, size_t lds, hipStream_t s) {
-    if (train) {
+    if (train && a.mask) {
         if (lds > 64 * 1024)
-            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(score_kernel<NCH, NW, true>),
+            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(score_kernel<NCH, NW, true, true>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        hipLaunchKernelGGL((score_kernel<NCH, NW, true>), dim3(a.B), dim3(NW * 64), lds, s, a);
+        hipLaunchKernelGGL((score_kernel<NCH, NW, true, true>), dim3(a.B), dim3(NW * 64), lds, s, a);
+    } else if (train) {
+        if (lds > 64 * 1024)
+            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(score_kernel<NCH, NW, true, false>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipLaunchKernelGGL((score_kernel<NCH, NW, true, false>), dim3(a.B), dim3(NW * 64), lds, s, a);
     } else {
-        hipLaunchKernelGGL((score_kernel<NCH, NW, false>), dim3(a.B), dim3(NW * 64), lds, s, a);
+        hipLaunchKernelGGL((score_kernel<NCH, NW, false, false>), dim3(a.B), dim3(NW * 64), lds, s, a);
     }
     return hipGetLastError();
 }
@@ -180,6 +199,7 @@ hipError_t launch_nch(const ScoreArgs& a, bool train, hipStream_t s) {
 hipError_t launch_score(const ScoreArgs& a, bool train, hipStream_t s) {
     if (a.B <= 0) return hipSuccess;
     if (a.C + (a.pos ? 1 : 0) <= 0) return hipErrorInvalidValue;   // the kernel clamps into a non-empty candidate list
+    if (train && (a.win == nullptr) == (a.mask == nullptr)) return hipErrorInvalidValue;   // exactly one of the two
     if (a.d <= 256) return launch_nch<1>(a, train, s);
     if (a.d <= 512) return launch_nch<2>(a, train, s);
     if (a.d <= 1024) return launch_nch<4>(a, train, s);

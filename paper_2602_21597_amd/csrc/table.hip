@@ -7,20 +7,27 @@
 //
 // A contribution is either a gradient row of the arena (anchors; projections
 // for the relation table) or a (query, candidate) pair of the scoring pass, for
-// which dL/dE[e] = coef * sign(y_win - E[e]) is rebuilt from the 4-byte
-// coefficient, the winning branch's embedding (cache resident) and the row the
-// wavefront already holds.  A small kernel first resolves the sorted
-// contribution numbers into (coefficient, source row) records laid out in
-// segment order, so that the row kernel reads them with one coalesced load per
-// 64 contributions instead of chasing three dependent indices per contribution;
-// source rows are then fetched four at a time before they are consumed.
+// which dL/dE[e] = coef * sign(y_win - Ef[e]) is rebuilt from the 4-byte
+// coefficient and either (plain tables) the winning branch's embedding, which is
+// cache resident, and the row the wavefront already holds, or (text features,
+// where the scored row Ef[e] is not the table row) the sign codes the scoring
+// kernel left, 2 bits per coordinate.  Measured on the 2.5 M-entity shape, the
+// first costs no HBM traffic at all, the second 2 x d/4 bytes per pair but
+// spares reading the fused row.
+// A small kernel first resolves the sorted contribution numbers into
+// (coefficient, source) records laid out in segment order, so that the row
+// kernel reads them with one coalesced load per 64 contributions instead of
+// chasing dependent indices per contribution; inside a segment the gradient rows
+// come first (anchors sort before positives and negatives), so the two kinds are
+// walked by two branch-free loops with several sources in flight.
 #include "common.h"
 
 namespace ngdb {
 namespace {
 
-// rec_row[t] >= 0: row of act (pair contribution, rec_coef[t] = dL/ds);
-// rec_row[t] < 0: row -1-rec_row[t] of dact (gradient row, added as is)
+// rec_row[t] >= 0: pair contribution (rec_coef[t] = dL/ds): the row of act of the pair's
+// winning branch if win is given, else the pair number; rec_row[t] < 0: row -1-rec_row[t]
+// of dact (gradient row, added as is)
 __global__ __launch_bounds__(256) void resolve_kernel(const int32_t* __restrict__ src, int64_t n, int n_rowsrc,
                                                       int row_base, int B, int K, const float* __restrict__ coef,
                                                       const int32_t* __restrict__ win, float* __restrict__ rec_coef,
@@ -40,20 +47,30 @@ __global__ __launch_bounds__(256) void resolve_kernel(const int32_t* __restrict_
                 pair = q * (K + 1) + 1 + ((r - B) - q * K);
             }
             rec_coef[t] = coef[pair];
-            rec_row[t] = win[pair];
+            rec_row[t] = win ? win[pair] : pair;
         }
     }
 }
 
-constexpr int G = 4;   // source rows in flight per wavefront
+constexpr int G = 4;    // gradient rows in flight per wavefront
+constexpr int GP = 8;   // pairs in flight per wavefront
 
 __device__ __forceinline__ uint32_t bf16_bits(float x) {   // round to nearest, ties to even
     const uint32_t b = __float_as_uint(x);
     return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
 }
+// sign code (1 = +, 2 = -, 0 = none) -> c, -c, 0
+__device__ __forceinline__ float signed_coef(uint32_t code, float c) { return code == 1u ? c : (code == 2u ? -c : 0.f); }
 
-// SEM: pairs are scored against the fused row of the touched-row list (text-feature
-// fusion) and the row gradient is also stored as bf16 for the projection's gradient.
+template <int NCH>
+__device__ __forceinline__ uint32_t load_mask(const void* mask, size_t idx) {
+    if (NCH == 1) return reinterpret_cast<const uint8_t*>(mask)[idx];
+    if (NCH == 2) return reinterpret_cast<const uint16_t*>(mask)[idx];
+    return reinterpret_cast<const uint32_t*>(mask)[idx];
+}
+
+// SEM (text-feature fusion): pair signs come from the sign codes, and the row gradient is
+// also stored as bf16 (input of the projection's gradient)
 template <int NCH, bool SEM>
 __global__ __launch_bounds__(256) void table_kernel(const TableArgs a, const AdamHyper hp) {
     const int lane = threadIdx.x & 63;
@@ -77,11 +94,10 @@ __global__ __launch_bounds__(256) void table_kernel(const TableArgs a, const Ada
         float4* prow = reinterpret_cast<float4*>(a.P + (size_t)row * a.d);
         float4* mrow = reinterpret_cast<float4*>(a.Mo + (size_t)row * a.d);
         float4* vrow = reinterpret_cast<float4*>(a.Vo + (size_t)row * a.d);
-        float4 p[NCH], m[NCH], v[NCH], g[NCH], ef[NCH];
+        float4 p[NCH], m[NCH], v[NCH], g[NCH];
 #pragma unroll
         for (int ch = 0; ch < NCH; ++ch) {
-            p[ch] = prow[colc[ch]];
-            if (SEM) ef[ch] = reinterpret_cast<const float4*>(a.ref_rows + (size_t)u * a.d)[colc[ch]];
+            if (update || !SEM) p[ch] = prow[colc[ch]];
             if (update) {
                 m[ch] = mrow[colc[ch]];
                 v[ch] = vrow[colc[ch]];
@@ -93,43 +109,75 @@ __global__ __launch_bounds__(256) void table_kernel(const TableArgs a, const Ada
             const int tl = base + min(lane, n - 1);
             const int32_t my_row = a.rec_row[tl];
             const float my_coef = a.rec_coef ? a.rec_coef[tl] : 0.f;
-            for (int j0 = 0; j0 < n; j0 += G) {
+            // gradient rows come first in a segment
+            const int n_rows = __popcll(__ballot(my_row < 0 && lane < n));
+            for (int j0 = 0; j0 < n_rows; j0 += G) {
                 float4 x[G][NCH];
-                float cf[G];
-                bool is_pair[G];
                 float wgt[G];
 #pragma unroll
                 for (int q = 0; q < G; ++q) {
-                    const int j = min(j0 + q, n - 1);
+                    const int j = min(j0 + q, n_rows - 1);
                     const int32_t r = __shfl(my_row, j, 64);
-                    cf[q] = __shfl(my_coef, j, 64);
-                    is_pair[q] = r >= 0;
-                    wgt[q] = j0 + q < n ? 1.f : 0.f;        // padding entries of the last group add nothing
-                    const float4* srow = reinterpret_cast<const float4*>(
-                        r >= 0 ? a.act + (size_t)r * a.d : a.dact + (size_t)(-1 - r) * a.d);
+                    wgt[q] = j0 + q < n_rows ? 1.f : 0.f;        // padding entries of the last group add nothing
+                    const float4* srow = reinterpret_cast<const float4*>(a.dact + (size_t)(-1 - r) * a.d);
 #pragma unroll
                     for (int ch = 0; ch < NCH; ++ch) x[q][ch] = srow[colc[ch]];
                 }
 #pragma unroll
-                for (int q = 0; q < G; ++q) {
-                    const float c = cf[q] * wgt[q];
+                for (int q = 0; q < G; ++q)
 #pragma unroll
                     for (int ch = 0; ch < NCH; ++ch) {
-                        const float4 y = x[q][ch];
-                        const float4 e = SEM ? ef[ch] : p[ch];
-                        if (is_pair[q]) {
-                            g[ch].x += c * sgn(y.x - e.x);
-                            g[ch].y += c * sgn(y.y - e.y);
-                            g[ch].z += c * sgn(y.z - e.z);
-                            g[ch].w += c * sgn(y.w - e.w);
-                        } else {
-                            g[ch].x += wgt[q] * y.x;
-                            g[ch].y += wgt[q] * y.y;
-                            g[ch].z += wgt[q] * y.z;
-                            g[ch].w += wgt[q] * y.w;
-                        }
+                        g[ch].x += wgt[q] * x[q][ch].x;
+                        g[ch].y += wgt[q] * x[q][ch].y;
+                        g[ch].z += wgt[q] * x[q][ch].z;
+                        g[ch].w += wgt[q] * x[q][ch].w;
                     }
+            }
+            if (!SEM) {
+                for (int j0 = n_rows; j0 < n; j0 += G) {
+                    float4 x[G][NCH];
+                    float cf[G];
+#pragma unroll
+                    for (int q = 0; q < G; ++q) {
+                        const int j = min(j0 + q, n - 1);
+                        const int32_t r = __shfl(my_row, j, 64);
+                        cf[q] = j0 + q < n ? __shfl(my_coef, j, 64) : 0.f;
+                        const float4* srow = reinterpret_cast<const float4*>(a.act + (size_t)r * a.d);
+#pragma unroll
+                        for (int ch = 0; ch < NCH; ++ch) x[q][ch] = srow[colc[ch]];
+                    }
+#pragma unroll
+                    for (int q = 0; q < G; ++q)
+#pragma unroll
+                        for (int ch = 0; ch < NCH; ++ch) {
+                            g[ch].x += cf[q] * sgn(x[q][ch].x - p[ch].x);
+                            g[ch].y += cf[q] * sgn(x[q][ch].y - p[ch].y);
+                            g[ch].z += cf[q] * sgn(x[q][ch].z - p[ch].z);
+                            g[ch].w += cf[q] * sgn(x[q][ch].w - p[ch].w);
+                        }
                 }
+                continue;
+            }
+            for (int j0 = n_rows; j0 < n; j0 += GP) {
+                uint32_t bits[GP];
+                float cf[GP];
+#pragma unroll
+                for (int q = 0; q < GP; ++q) {
+                    const int j = min(j0 + q, n - 1);
+                    const int32_t pair = __shfl(my_row, j, 64);
+                    cf[q] = j0 + q < n ? __shfl(my_coef, j, 64) : 0.f;
+                    bits[q] = load_mask<NCH>(a.mask, (size_t)pair * 64 + lane);
+                }
+#pragma unroll
+                for (int q = 0; q < GP; ++q)
+#pragma unroll
+                    for (int ch = 0; ch < NCH; ++ch) {
+                        const uint32_t b = bits[q] >> (8 * ch);
+                        g[ch].x += signed_coef(b & 3u, cf[q]);
+                        g[ch].y += signed_coef((b >> 2) & 3u, cf[q]);
+                        g[ch].z += signed_coef((b >> 4) & 3u, cf[q]);
+                        g[ch].w += signed_coef((b >> 6) & 3u, cf[q]);
+                    }
             }
         }
         if (SEM) {
@@ -179,8 +227,8 @@ hipError_t launch_resolve(const int32_t* src, int64_t n, int n_rowsrc, int row_b
 hipError_t launch_table_update(const TableArgs& a, const AdamHyper& hp, hipStream_t s) {
     // the number of touched rows is only known on the device: a fixed grid walks them
     const int blocks = 256 * 8;
-    if ((a.ref_rows == nullptr) != (a.g_bf16 == nullptr) || a.d > 1024) return hipErrorInvalidValue;
-    const bool sem = a.ref_rows != nullptr;
+    if (a.d > 1024 || (a.g_bf16 != nullptr) != (a.mask != nullptr)) return hipErrorInvalidValue;
+    const bool sem = a.g_bf16 != nullptr;
 #define NGDB_TABLE(NCH)                                                                              \
     do {                                                                                             \
         if (sem) hipLaunchKernelGGL((table_kernel<NCH, true>), dim3(blocks), dim3(256), 0, s, a, hp); \
