@@ -170,6 +170,9 @@ def main():
     ap.add_argument("--config", type=int, default=1)
     ap.add_argument("--streams", type=int, default=0, help="0 = the workload's default")
     ap.add_argument("--cpu-sample", type=int, default=-1, help="queries timed on the CPU oracle (0 = skip)")
+    ap.add_argument("--schedule", choices=("level", "max_fill"), default="level",
+                    help="order of execution of the operators (max_fill: the ready-set loop of Alg. 1)")
+    ap.add_argument("--bmax", type=int, default=0, help="largest batch of one Max-Fillness step, 0 = unbounded")
     ap.add_argument("--rank", type=int, default=0, metavar="Q",
                     help="time the all-entity ranking pass of Q queries instead of the training step")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
@@ -205,7 +208,8 @@ def main():
     from paper_2602_21597_amd import Engine
     streams = args.streams or cfg.streams
     eng = Engine(cfg.N, cfg.R, cfg.d, cfg.h, cfg.gamma, lr=cfg.lr, beta1=cfg.beta1, beta2=cfg.beta2, eps=cfg.eps,
-                 num_streams=streams, d_sem=cfg.d_sem)
+                 num_streams=streams, d_sem=cfg.d_sem, schedule={"level": 0, "max_fill": 1}[args.schedule],
+                 b_max=args.bmax)
     eng.bind_numpy(params, sem_bits=sem_bits)
     del params, sem_bits
     negs = [torch.from_numpy(n).cuda() for n in negs_np]
@@ -316,6 +320,9 @@ def main():
                    % (cfg.index, cfg.name, cfg.N, cfg.R, cfg.d, cfg.h, cfg.B, cfg.K,
                       " d_sem=%d (bf16 text features)" % cfg.d_sem if cfg.d_sem else "", cfg.gamma),
                    "streams": streams,
+                   "schedule": args.schedule if args.schedule == "level" else "max_fill, B_max=%s" % (args.bmax or "inf"),
+                   "steps_per_batch": pexp["n_levels"], "peak_live_outputs": pexp["peak_live"],
+                   "operator_outputs": pexp["n_slots"],
                    "step": "ngdb_plan of batch t+1 on a second host thread while ngdb_train_step of batch t is enqueued",
                    "touched_entity_rows": touched},
         "device_only": {"queries_per_s": cfg.B * args.steps / dt_dev, "ms_per_step": 1e3 * dt_dev / args.steps,

@@ -78,6 +78,19 @@ extern "C" {
 #define NGDB_MAX_BRANCH 64    /* conjunctive branches of one query      */
 #define NGDB_MAX_TOPK   16    /* entities returned per query by the all-entity ranking */
 
+/* Order in which the operators of a batch are executed (Sec. 4.1 "Dynamic Scheduling").
+ * LEVEL: all operators of one depth are one step; their classes (type, input count)
+ *   run as the groups of one launch sequence.
+ * MAX_FILL: the paper's ready-set loop (Alg. 1), resolved on the host: ready operators
+ *   wait in one pool per class, ordered PROJ < INTER by input count < NEG; each step
+ *   files the newly ready operators into their pools in node order, takes the pool
+ *   with the most entries (fillness = entries / b_max, one b_max for all classes; ties
+ *   to the first class) and runs its first min(entries, b_max) operators (b_max = 0:
+ *   all of them); the loop ends when every pool is empty.  Values do not depend on
+ *   the schedule; only the fp32 summation order of the weight gradients does.        */
+#define NGDB_SCHED_LEVEL    0
+#define NGDB_SCHED_MAX_FILL 1
+
 typedef struct ngdb_ctx_s ngdb_ctx_t;     /* opaque: configuration, workspace, streams */
 typedef struct ngdb_plan_s ngdb_plan_t;   /* opaque: one planned batch                 */
 
@@ -94,6 +107,8 @@ typedef struct ngdb_config {
                               Operator Execution")                                    */
     float gamma;
     float lr, beta1, beta2, eps;
+    int32_t schedule;      /* NGDB_SCHED_* used by ngdb_plan                          */
+    int32_t b_max;         /* largest batch of one Max-Fillness step, 0 = unbounded   */
 } ngdb_config;
 
 /* A trainable tensor with its Adam moments (all device, fp32, same shape). */
@@ -132,7 +147,9 @@ typedef struct ngdb_query_batch {
 /* Read-only host view of a plan; valid until ngdb_plan_free().  Canonical form:
  *  - unions removed by DNF (branches in input order; projections above a union
  *    repeated per branch); nodes numbered in (query, branch, depth-first
- *    post-order) order; level(anchor)=0, level(op)=1+max level of its inputs;
+ *    post-order) order; level(anchor)=0, level(op)=1+max level of its inputs
+ *    (NGDB_SCHED_LEVEL) or the Max-Fillness step in which the operator runs
+ *    (NGDB_SCHED_MAX_FILL; a step then holds exactly one group);
  *  - group = operator nodes with equal (level, type, input count), ordered by
  *    level, type (PROJ<INTER<NEG), input count; members in node order;
  *  - output slots type-major (projections, intersections, negations), in group
@@ -145,6 +162,9 @@ typedef struct ngdb_query_batch {
 typedef struct ngdb_plan_view {
     int32_t n_queries, n_groups, n_levels, n_slots, n_anchor;
     int32_t n_proj, n_inter, n_neg, n_int_rows, n_roots, n_refs, n_r_uniq;
+    int32_t peak_live;           /* most operator outputs alive at once if an output were freed as
+                                    soon as its consumer has run (Sec. 4.3, eager reference
+                                    counting; outputs of roots live until scoring)               */
     const int32_t* lvl_off;      /* [n_levels+2] groups of level l: lvl_off[l]..lvl_off[l+1]-1 */
     const int32_t* g_level;      /* [n_groups] ... */
     const int32_t* g_type;
@@ -206,6 +226,9 @@ int ngdb_plan(ngdb_ctx_t* ctx, const ngdb_query_batch* batch, ngdb_plan_t** out)
  * the result can be exported and freed, not executed.                            */
 int ngdb_plan_host(int32_t n_entities, int32_t n_relations, const ngdb_query_batch* batch,
                    ngdb_plan_t** out);
+/* The same with an explicit schedule (ngdb_plan_host uses NGDB_SCHED_LEVEL). */
+int ngdb_plan_host_sched(int32_t n_entities, int32_t n_relations, const ngdb_query_batch* batch,
+                         int32_t schedule, int32_t b_max, ngdb_plan_t** out);
 int ngdb_plan_export(const ngdb_plan_t* plan, ngdb_plan_view* out);
 /* May be called right after the last step that uses the plan has been enqueued:
  * the plan's device buffer goes back to its context and is reused only after

@@ -12,7 +12,9 @@ planner must reproduce it bit for bit):
 
  1. Unions are removed by disjunctive normal form; branches keep input order.
  2. Nodes get global ids in (query, branch, depth-first post-order) order.
- 3. level(anchor) = 0, level(op) = 1 + max level of its inputs.
+ 3. level(anchor) = 0, level(op) = 1 + max level of its inputs (level-synchronous
+    schedule), or level(op) = the step of the Max-Fillness loop in which the
+    operator runs (see max_fillness_steps); a Max-Fillness step is one group.
  4. A group is the set of operator nodes with the same (level, type, number
     of inputs); groups are ordered by level, then type (projection <
     intersection < negation), then input count; members by global id.
@@ -37,8 +39,73 @@ from .model import OP_ANCHOR, OP_PROJ, OP_INTER, OP_NEG, Unsupported, dnf, query
 _TYPE_OF = {"p": OP_PROJ, "i": OP_INTER, "n": OP_NEG}
 
 
-def build_plan(batch):
-    """Returns a dict of int32 numpy arrays / ints describing the canonical plan."""
+def _class_of(node):
+    """Pool of an operator: projections, intersections by input count (C_2, C_3, ...), negations."""
+    return (node["type"], len(node["ins"]))
+
+
+def max_fillness_steps(nodes, b_max=0):
+    """The scheduling loop of Alg. 1 on the forward operators, in the paper's notation.
+
+    R: operators that became ready in this cycle; P[tau]: pool (queue) of ready operators of
+    class tau; rho(tau) = |P[tau]| / B_max [Sec. 4.1, Eq. for the fillness ratio]; tau* =
+    argmax rho; PopBatch takes the first min(|P[tau*]|, B_max) entries.  Canonical choices the
+    paper leaves open: R is filed into the pools in node order; ties of rho go to the
+    first class in the order projection < intersection (by input count) < negation; b_max = 0
+    means no bound; the loop continues until all pools are empty.
+    Returns ({operator id: step, 1-based}, peak number of live operator outputs under eager
+    reference counting [Sec. 4.3]: an output is freed when its consumer has run, outputs
+    without a consumer -- the roots -- stay).
+    """
+    ops = [g for g, n in enumerate(nodes) if n["type"] != OP_ANCHOR]
+    consumer = {}
+    for g in ops:
+        for c in nodes[g]["ins"]:
+            consumer[c] = g
+    unmet = {g: sum(1 for c in nodes[g]["ins"] if nodes[c]["type"] != OP_ANCHOR) for g in ops}
+    classes = sorted(set(_class_of(nodes[g]) for g in ops))
+    P = {tau: [] for tau in classes}
+    R = [g for g in ops if unmet[g] == 0]
+    step, t, live, peak = {}, 0, 0, 0
+    while True:
+        for v in sorted(R):
+            P[_class_of(nodes[v])].append(v)
+        R = []
+        if not any(P.values()):
+            break
+        tau_star = max(classes, key=lambda tau: (len(P[tau]), -classes.index(tau)))
+        k = len(P[tau_star]) if b_max == 0 else min(len(P[tau_star]), b_max)
+        batch, P[tau_star] = P[tau_star][:k], P[tau_star][k:]
+        t += 1
+        live += len(batch)
+        peak = max(peak, live)
+        for o in batch:
+            step[o] = t
+            live -= sum(1 for c in nodes[o]["ins"] if nodes[c]["type"] != OP_ANCHOR)
+            succ = consumer.get(o)
+            if succ is not None:
+                unmet[succ] -= 1
+                if unmet[succ] == 0:
+                    R.append(succ)
+    return step, peak
+
+
+def level_peak_live(nodes):
+    """Peak of live operator outputs when all operators of one depth are one step."""
+    ops = [g for g, n in enumerate(nodes) if n["type"] != OP_ANCHOR]
+    live = peak = 0
+    for l in sorted(set(nodes[g]["level"] for g in ops)):
+        now = [g for g in ops if nodes[g]["level"] == l]
+        live += len(now)
+        peak = max(peak, live)
+        live -= sum(1 for g in now for c in nodes[g]["ins"] if nodes[c]["type"] != OP_ANCHOR)
+    return peak
+
+
+def build_plan(batch, schedule="level", b_max=0):
+    """Returns a dict of int32 numpy arrays / ints describing the canonical plan.
+
+    schedule: "level" (one step per depth) or "max_fill" (Alg. 1 with B_max = b_max)."""
     nodes = []            # per global id: dict(type, arg, ins, level, query)
     roots = []            # per query: list of root gids
     for q in range(batch.B):
@@ -62,6 +129,14 @@ def build_plan(batch):
 
             qroots.append(visit(br))
         roots.append(qroots)
+
+    if schedule == "max_fill":
+        step, peak_live = max_fillness_steps(nodes, b_max)
+        for g, t in step.items():
+            nodes[g]["level"] = t
+    else:
+        assert schedule == "level"
+        peak_live = level_peak_live(nodes)
 
     ops = [g for g, n in enumerate(nodes) if n["type"] != OP_ANCHOR]
     anchors = [g for g, n in enumerate(nodes) if n["type"] == OP_ANCHOR]
@@ -139,7 +214,7 @@ def build_plan(batch):
     return dict(
         n_groups=len(keys), n_levels=n_levels, n_slots=n_slots, n_anchor=len(anchors),
         n_proj=n_type[0], n_inter=n_type[1], n_neg=n_type[2], n_int_rows=int_rows,
-        n_roots=len(root_slot),
+        n_roots=len(root_slot), peak_live=peak_live,
         lvl_off=i32(lvl_off),
         g_level=i32(g_level), g_type=i32(g_type), g_nin=i32(g_nin), g_n=i32(g_n),
         g_out_base=i32(g_out), g_mlp_base=i32(g_mlp), g_ref_off=i32(g_ref), g_rel_off=i32(g_rel),

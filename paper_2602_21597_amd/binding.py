@@ -29,7 +29,8 @@ class NgdbError(RuntimeError):
 class Config(C.Structure):
     _fields_ = [("n_entities", C.c_int32), ("n_relations", C.c_int32), ("d", C.c_int32), ("h", C.c_int32),
                 ("d_sem", C.c_int32), ("num_streams", C.c_int32), ("gamma", C.c_float), ("lr", C.c_float),
-                ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float)]
+                ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float), ("schedule", C.c_int32),
+                ("b_max", C.c_int32)]
 
 
 class Tensor(C.Structure):
@@ -46,7 +47,8 @@ class QueryBatchC(C.Structure):
 
 
 _PLAN_COUNTS = ("n_queries", "n_groups", "n_levels", "n_slots", "n_anchor", "n_proj", "n_inter", "n_neg",
-                "n_int_rows", "n_roots", "n_refs", "n_r_uniq")
+                "n_int_rows", "n_roots", "n_refs", "n_r_uniq", "peak_live")
+SCHED_LEVEL, SCHED_MAX_FILL = 0, 1
 _PLAN_ARRAYS = ("lvl_off", "g_level", "g_type", "g_nin", "g_n", "g_out_base", "g_mlp_base", "g_ref_off",
                 "g_rel_off", "in_ref", "in_gslot", "rel", "root_off", "root_slot", "anchor_ent", "pos",
                 "r_uniq", "r_seg_off", "r_src")
@@ -84,6 +86,7 @@ def load_library(path=LIB_PATH):
         "ngdb_bind_params": (C.c_int, [vp, C.POINTER(Params)]),
         "ngdb_plan": (C.c_int, [vp, C.POINTER(QueryBatchC), C.POINTER(vp)]),
         "ngdb_plan_host": (C.c_int, [i32, i32, C.POINTER(QueryBatchC), C.POINTER(vp)]),
+        "ngdb_plan_host_sched": (C.c_int, [i32, i32, C.POINTER(QueryBatchC), i32, i32, C.POINTER(vp)]),
         "ngdb_plan_export": (C.c_int, [vp, C.POINTER(PlanView)]),
         "ngdb_plan_free": (None, [vp]),
         "ngdb_train_step": (C.c_int, [vp, vp, vp, i32, vp, vp]),
@@ -173,11 +176,12 @@ def _check(rc, ctx):
         raise NgdbError(rc, text)
 
 
-def plan_host(n_entities, n_relations, qb):
+def plan_host(n_entities, n_relations, qb, schedule=SCHED_LEVEL, b_max=0):
     """Host-only planning (no device needed); the plan can be exported, not executed."""
     arrs = _BatchArrays(qb)
     h = C.c_void_p()
-    _check(lib().ngdb_plan_host(int(n_entities), int(n_relations), C.byref(arrs.c), C.byref(h)), None)
+    _check(lib().ngdb_plan_host_sched(int(n_entities), int(n_relations), C.byref(arrs.c), int(schedule), int(b_max),
+                                      C.byref(h)), None)
     return Plan(h)
 
 
@@ -215,14 +219,15 @@ class Engine:
     """One libngdb context plus the device tensors bound to it."""
 
     def __init__(self, n_entities, n_relations, d, h, gamma, lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8,
-                 d_sem=0, num_streams=1, device="cuda:0"):
+                 d_sem=0, num_streams=1, device="cuda:0", schedule=SCHED_LEVEL, b_max=0):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("libngdb needs a GPU; there is no CPU path")
         self.torch = torch
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
-        self.cfg = Config(n_entities, n_relations, d, h, d_sem, num_streams, gamma, lr, beta1, beta2, eps)
+        self.cfg = Config(n_entities, n_relations, d, h, d_sem, num_streams, gamma, lr, beta1, beta2, eps,
+                          int(schedule), int(b_max))
         self.ctx = C.c_void_p()
         _check(lib().ngdb_create(C.byref(self.cfg), C.byref(self.ctx)), None)
         self.tensors = {}

@@ -595,6 +595,7 @@ int ngdb_create(const ngdb_config* cfg, ngdb_ctx_t** out) {
         (cfg->h & 3) || cfg->d > 1024 || cfg->num_streams < 1 || cfg->num_streams > 4 || cfg->d_sem < 0)
         return NGDB_ERR_ARG;
     if (cfg->d_sem != 0 && ((cfg->d_sem & 63) || (cfg->d & 7))) return NGDB_ERR_ARG;
+    if ((cfg->schedule != NGDB_SCHED_LEVEL && cfg->schedule != NGDB_SCHED_MAX_FILL) || cfg->b_max < 0) return NGDB_ERR_ARG;
     ngdb_ctx_t* c = new (std::nothrow) ngdb_ctx_s();
     if (!c) return NGDB_ERR_OOM;
     c->cfg = *cfg;
@@ -667,8 +668,8 @@ int ngdb_bind_params(ngdb_ctx_t* c, const ngdb_params* p) {
 }
 
 // host part of planning: frontiers, index arrays, level/type segments
-static int plan_host(const ngdb_query_batch* qb, int32_t n_entities, int32_t n_relations, ngdb_plan_t** out,
-                     std::string& err) {
+static int plan_host(const ngdb_query_batch* qb, int32_t n_entities, int32_t n_relations, int32_t schedule,
+                     int32_t b_max, ngdb_plan_t** out, std::string& err) {
     *out = nullptr;
     ngdb_plan_t* pl = new (std::nothrow) ngdb_plan_s();
     if (!pl) {
@@ -677,7 +678,7 @@ static int plan_host(const ngdb_query_batch* qb, int32_t n_entities, int32_t n_r
     }
     int rc = NGDB_OK;
     try {
-        rc = build_plan(*qb, n_entities, n_relations, pl->hp, err);
+        rc = build_plan(*qb, n_entities, n_relations, schedule, b_max, pl->hp, err);
     } catch (const std::bad_alloc&) {
         rc = NGDB_ERR_OOM;
         err = "host allocation failed";
@@ -708,16 +709,21 @@ static int plan_host(const ngdb_query_batch* qb, int32_t n_entities, int32_t n_r
 }
 
 int ngdb_plan_host(int32_t n_entities, int32_t n_relations, const ngdb_query_batch* qb, ngdb_plan_t** out) {
+    return ngdb_plan_host_sched(n_entities, n_relations, qb, NGDB_SCHED_LEVEL, 0, out);
+}
+
+int ngdb_plan_host_sched(int32_t n_entities, int32_t n_relations, const ngdb_query_batch* qb, int32_t schedule,
+                         int32_t b_max, ngdb_plan_t** out) {
     if (!qb || !out || n_entities <= 0 || n_relations <= 0) return NGDB_ERR_ARG;
     std::string err;
-    return plan_host(qb, n_entities, n_relations, out, err);
+    return plan_host(qb, n_entities, n_relations, schedule, b_max, out, err);
 }
 
 int ngdb_plan(ngdb_ctx_t* c, const ngdb_query_batch* qb, ngdb_plan_t** out) {
     if (!c || !qb || !out) return NGDB_ERR_ARG;
     std::string err;
     ngdb_plan_t* pl = nullptr;
-    int rc = plan_host(qb, c->cfg.n_entities, c->cfg.n_relations, &pl, err);
+    int rc = plan_host(qb, c->cfg.n_entities, c->cfg.n_relations, c->cfg.schedule, c->cfg.b_max, &pl, err);
     if (rc != NGDB_OK) return fail(c, rc, err);
     HostPlan& hp = pl->hp;
 
@@ -791,6 +797,7 @@ int ngdb_plan_export(const ngdb_plan_t* pl, ngdb_plan_view* v) {
     v->n_anchor = hp.n_anchor; v->n_proj = hp.n_proj; v->n_inter = hp.n_inter; v->n_neg = hp.n_neg;
     v->n_int_rows = hp.n_int_rows; v->n_roots = hp.n_roots; v->n_refs = (int32_t)hp.in_ref.size();
     v->n_r_uniq = (int32_t)hp.r_uniq.size();
+    v->peak_live = hp.peak_live;
     v->lvl_off = hp.lvl_off.data(); v->g_level = hp.g_level.data(); v->g_type = hp.g_type.data();
     v->g_nin = hp.g_nin.data(); v->g_n = hp.g_n.data(); v->g_out_base = hp.g_out_base.data();
     v->g_mlp_base = hp.g_mlp_base.data(); v->g_ref_off = hp.g_ref_off.data(); v->g_rel_off = hp.g_rel_off.data();

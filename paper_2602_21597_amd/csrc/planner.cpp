@@ -1,9 +1,13 @@
-// Host planner.  Turns a batch of query trees into the level-synchronous form of
-// the paper's operator pools (Sec. 4.1): at every depth, the operators of one
-// type (and, for intersections, one input count -- the classes C_k of Sec. 4.3)
-// from all queries form one group that is executed as one batch.  All gather /
-// scatter positions are resolved here, ahead of the step (Sec. 4.2 "Efficient
-// Tensor Indexing").  The numbering rules are stated in ngdb.h (ngdb_plan_view).
+// Host planner.  Turns a batch of query trees into the paper's operator pools
+// (Sec. 4.1) resolved ahead of time into a sequence of execution steps.  Two
+// schedules: level-synchronous -- at every depth, the operators of one type
+// (and, for intersections, one input count: the classes C_k of Sec. 4.3) from
+// all queries form one group, all groups of a depth are one step; and the
+// paper's Max-Fillness loop (Sec. 4.1 "Dynamic Scheduling", Alg. 1) -- ready
+// operators wait in one pool per class, every step runs up to B_max operators
+// of the fullest pool.  All gather / scatter positions are resolved here, ahead
+// of the step (Sec. 4.2 "Efficient Tensor Indexing").  The numbering rules are
+// stated in ngdb.h (ngdb_plan_view).
 #include "planner.h"
 
 #include <algorithm>
@@ -106,6 +110,64 @@ int32_t number_postorder(const std::vector<Tree>& pool, int32_t t, Flat& flat) {
     return flat.add(node.type, node.arg, lvl, ins);
 }
 
+// Max-Fillness schedule (Alg. 1 without the gradient nodes, which mirror it): returns the step
+// (1-based) in which every operator node runs.  One pool per class (type, input count), in
+// the order PROJ < INTER by input count < NEG.  A cycle files the newly ready operators into
+// their pools in node order, picks the pool with the most entries (fillness = entries / B_max
+// with one B_max for all classes; ties to the first class), and runs its first min(size,
+// B_max) entries; consumers whose inputs are all done become ready for the next cycle.  The
+// loop runs until every pool is empty (the printed loop condition, "ready set not empty",
+// would strand the remainder of a pool that was cut at B_max).  Also returns the largest
+// number of operator outputs alive at once under eager reference counting (Sec. 4.3): an
+// output dies when its consumer has run; the outputs of roots stay for scoring.
+void max_fillness_steps(const Flat& flat, int32_t b_max, std::vector<int32_t>& step, int32_t& peak_live) {
+    const int32_t n = (int32_t)flat.type.size();
+    auto cls = [&](int32_t g) {
+        const int32_t t = flat.type[g];
+        return t == NGDB_OP_PROJ ? 0 : (t == NGDB_OP_INTER ? flat.nin(g) - 1 : NGDB_MAX_CARD);   // 0, 1..7, 8
+    };
+    constexpr int N_CLS = NGDB_MAX_CARD + 1;
+    std::vector<int32_t> consumer(n, -1), waiting(n, 0);
+    for (int32_t g = 0; g < n; ++g)
+        for (int32_t k = flat.in_off[g]; k < flat.in_off[g + 1]; ++k) {
+            consumer[flat.in[k]] = g;
+            if (flat.type[flat.in[k]] != NGDB_OP_ANCHOR) ++waiting[g];
+        }
+    std::vector<std::vector<int32_t>> pool(N_CLS);
+    std::vector<size_t> head(N_CLS, 0);
+    std::vector<int32_t> ready;
+    for (int32_t g = 0; g < n; ++g)
+        if (flat.type[g] != NGDB_OP_ANCHOR && waiting[g] == 0) ready.push_back(g);
+    step.assign(n, 0);
+    int32_t s = 0, live = 0;
+    peak_live = 0;
+    for (;;) {
+        std::sort(ready.begin(), ready.end());
+        for (int32_t g : ready) pool[cls(g)].push_back(g);
+        ready.clear();
+        int best = -1;
+        size_t best_n = 0;
+        for (int c = 0; c < N_CLS; ++c) {
+            const size_t cnt = pool[c].size() - head[c];
+            if (cnt > best_n) { best_n = cnt; best = c; }
+        }
+        if (best < 0) break;
+        const size_t take = b_max > 0 ? std::min<size_t>(best_n, (size_t)b_max) : best_n;
+        ++s;
+        live += (int32_t)take;                       // outputs of this step exist next to their inputs
+        peak_live = std::max(peak_live, live);
+        for (size_t i = 0; i < take; ++i) {
+            const int32_t g = pool[best][head[best] + i];
+            step[g] = s;
+            for (int32_t k = flat.in_off[g]; k < flat.in_off[g + 1]; ++k)
+                if (flat.type[flat.in[k]] != NGDB_OP_ANCHOR) --live;   // its only consumer has run
+            const int32_t c = consumer[g];
+            if (c >= 0 && --waiting[c] == 0) ready.push_back(c);
+        }
+        head[best] += take;
+    }
+}
+
 int validate(const ngdb_query_batch& qb, int32_t N, int32_t R, std::string& err) {
     if (qb.n_queries < 0) { err = "n_queries < 0"; return NGDB_ERR_ARG; }
     if (qb.n_queries == 0) return NGDB_OK;
@@ -176,7 +238,12 @@ void segment_index(const std::vector<int32_t>& keys, std::vector<int32_t>& uniq,
 
 }  // namespace
 
-int build_plan(const ngdb_query_batch& qb, int32_t N, int32_t R, HostPlan& P, std::string& err) {
+int build_plan(const ngdb_query_batch& qb, int32_t N, int32_t R, int32_t schedule, int32_t b_max, HostPlan& P,
+               std::string& err) {
+    if ((schedule != NGDB_SCHED_LEVEL && schedule != NGDB_SCHED_MAX_FILL) || b_max < 0) {
+        err = "unknown schedule or negative b_max";
+        return NGDB_ERR_ARG;
+    }
     int rc = validate(qb, N, R, err);
     if (rc != NGDB_OK) return rc;
     P = HostPlan{};
@@ -209,6 +276,31 @@ int build_plan(const ngdb_query_batch& qb, int32_t N, int32_t R, HostPlan& P, st
         P.max_branch = std::max<int32_t>(P.max_branch, (int32_t)branches.size());
     }
     const int32_t n_nodes = (int32_t)flat.type.size();
+
+    // 1b. execution step of every operator: its depth, or its Max-Fillness step.  From here
+    // on "level" means execution step.  The eager-reclamation peak of the level-synchronous
+    // order is computed the same way: outputs of a step appear, then their inputs die.
+    if (schedule == NGDB_SCHED_MAX_FILL) {
+        std::vector<int32_t> step;
+        max_fillness_steps(flat, b_max, step, P.peak_live);
+        flat.level = step;
+    } else {
+        int32_t max_level = 0;
+        for (int32_t g = 0; g < n_nodes; ++g) max_level = std::max(max_level, flat.level[g]);
+        std::vector<int32_t> born(max_level + 2, 0), dead(max_level + 2, 0);
+        for (int32_t g = 0; g < n_nodes; ++g) {
+            if (flat.type[g] == NGDB_OP_ANCHOR) continue;
+            ++born[flat.level[g]];
+            for (int32_t k = flat.in_off[g]; k < flat.in_off[g + 1]; ++k)
+                if (flat.type[flat.in[k]] != NGDB_OP_ANCHOR) ++dead[flat.level[g]];
+        }
+        int32_t live = 0;
+        for (int32_t l = 1; l <= max_level; ++l) {
+            live += born[l];
+            P.peak_live = std::max(P.peak_live, live);
+            live -= dead[l];
+        }
+    }
 
     // 2. anchors and operator nodes
     std::vector<int32_t> ops, anchor_idx(n_nodes, -1);

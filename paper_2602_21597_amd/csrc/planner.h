@@ -12,6 +12,7 @@ struct HostPlan {
     int32_t n_queries = 0, n_groups = 0, n_levels = 0, n_slots = 0, n_anchor = 0;
     int32_t n_proj = 0, n_inter = 0, n_neg = 0, n_int_rows = 0, n_roots = 0;
     int32_t max_branch = 0;          // largest number of conjunctive branches of a query
+    int32_t peak_live = 0;           // most operator outputs alive at once under eager reference counting
     std::vector<int32_t> lvl_off;
     std::vector<int32_t> g_level, g_type, g_nin, g_n, g_out_base, g_mlp_base, g_ref_off, g_rel_off;
     std::vector<int32_t> in_ref, in_gslot, rel;
@@ -21,7 +22,7 @@ struct HostPlan {
 };
 
 // Returns NGDB_OK or an error code; `err` receives the reason.
-int build_plan(const ngdb_query_batch& qb, int32_t n_entities, int32_t n_relations,
-               HostPlan& out, std::string& err);
+int build_plan(const ngdb_query_batch& qb, int32_t n_entities, int32_t n_relations, int32_t schedule,
+               int32_t b_max, HostPlan& out, std::string& err);
 
 }  // namespace ngdb

@@ -47,9 +47,10 @@ def tol_of(name, tol):
 
 class Case:
     def __init__(self, N, R, d, h, B, K, gamma, mix=None, seed=0, T=None, alpha=2.1, trees=None, pos=None,
-                 d_sem=0):
+                 d_sem=0, schedule="level", b_max=0):
         self.N, self.R, self.d, self.h, self.B, self.K, self.gamma = N, R, d, h, B, K, gamma
         self.d_sem = d_sem
+        self.schedule, self.b_max = schedule, b_max      # order of execution: values must not depend on it
         self.hp = dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, gamma=gamma)
         self.params = wl.make_params(N, R, d, h, seed + 3, d_sem=d_sem)
         self.sem_bits = wl.make_sem_features(N, d_sem, seed + 5) if d_sem else None
@@ -80,7 +81,8 @@ class Case:
 
     def engine(self, num_streams=1):
         from paper_2602_21597_amd import Engine
-        eng = Engine(self.N, self.R, self.d, self.h, self.gamma, num_streams=num_streams, d_sem=self.d_sem)
+        eng = Engine(self.N, self.R, self.d, self.h, self.gamma, num_streams=num_streams, d_sem=self.d_sem,
+                     schedule={"level": 0, "max_fill": 1}[self.schedule], b_max=self.b_max)
         eng.bind_numpy(self.params, sem_bits=self.sem_bits)
         return eng
 
@@ -173,7 +175,7 @@ def check_forward_backward(case, eng=None, tol=TOL):
     import torch
     eng = eng or case.engine()
     plan = eng.plan(case.qb)
-    ref_plan = oplan.build_plan(case.qb)
+    ref_plan = oplan.build_plan(case.qb, case.schedule, case.b_max)
     got_plan = plan.export()
     for k in ref_plan:
         assert np.array_equal(np.asarray(got_plan[k]), np.asarray(ref_plan[k])), "plan." + k

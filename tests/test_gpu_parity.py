@@ -140,6 +140,23 @@ def test_all_entity_topk_many_chunks():
     _check_topk(case, 10, 12)
 
 
+# ---------------------------------------------------------------- Max-Fillness schedule
+def test_max_fillness_schedule_same_values():
+    _say("Max-Fillness steps, B_max = unbounded / 64 / 5: N=3000 d=400 h=800 B=150 K=19; tiny config train steps")
+    for b_max in (0, 64, 5):
+        par.check_forward_backward(par.Case(3000, 30, 400, 800, 150, 19, 55.0, seed=11, schedule="max_fill",
+                                            b_max=b_max))
+    c = wl.get_config(0)
+    par.check_train_steps(par.Case(c.N, c.R, c.d, c.h, c.B, c.K, c.gamma, mix=c.mix, seed=c.seed, T=c.T,
+                                   schedule="max_fill", b_max=16), steps=2)
+
+
+def test_max_fillness_schedule_with_text_features_and_streams():
+    _say("Max-Fillness steps with text features (d_sem=128) and 3 streams")
+    case = par.Case(1200, 12, 64, 128, 70, 9, 8.0, seed=41, d_sem=128, schedule="max_fill", b_max=32)
+    par.check_forward_backward(case, eng=case.engine(num_streams=3))
+
+
 # ---------------------------------------------------------------- text-feature fusion
 def test_text_features_forward_backward():
     _say("d_sem=128: N=1200 d=64 h=128 B=70 K=9")

@@ -57,6 +57,16 @@ def test_host_planner_weighted_mix_and_single_templates(kg):
         same_plan(binding.plan_host(3000, 40, qb).export(), oplan.build_plan(qb))
 
 
+@pytest.mark.parametrize("b_max", [0, 1, 7, 64])
+def test_host_planner_max_fillness_is_bit_exact_with_reference(kg, b_max):
+    qb = wl.make_batch(kg, 300, wl.get_config(1).mix, 12)
+    same_plan(binding.plan_host(3000, 40, qb, binding.SCHED_MAX_FILL, b_max).export(),
+              oplan.build_plan(qb, "max_fill", b_max))
+    qb = wl.make_batch(kg, 64, wl.get_config(3).mix, 13)
+    same_plan(binding.plan_host(3000, 40, qb, binding.SCHED_MAX_FILL, b_max).export(),
+              oplan.build_plan(qb, "max_fill", b_max))
+
+
 def test_host_planner_general_shapes():
     trees = [
         ("p", 5, ("p", 4, ("u", ("p", 0, ("e", 1)), ("p", 1, ("e", 2)), ("p", 2, ("e", 3))))),

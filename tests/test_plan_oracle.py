@@ -69,7 +69,7 @@ def test_mixed_batch_census_is_the_sum_over_templates(kg):
     assert sum(v for _, _, g in tot.values() for (l, t, k), v in g.items() if t == P) == 37
 
 
-def check_invariants(qb, plan):
+def check_invariants(qb, plan, asap=True):
     S, A = plan["n_slots"], plan["n_anchor"]
     G = plan["n_groups"]
     level_of_slot = np.full(S, -1)
@@ -98,7 +98,9 @@ def check_invariants(qb, plan):
         refs = plan["in_ref"][ro:ro + k * n].reshape(k, n)
         gs = plan["in_gslot"][ro:ro + k * n].reshape(k, n)
         lv = np.where(refs >= 0, level_of_slot[np.maximum(refs, 0)], 0)
-        assert np.all(lv < l) and np.all(lv.max(axis=0) == l - 1)    # ASAP levels
+        assert np.all(lv < l)                                        # inputs run in earlier steps
+        if asap:
+            assert np.all(lv.max(axis=0) == l - 1)                   # ASAP levels
         assert np.all(gs[refs >= 0] == refs[refs >= 0])
         assert np.all(gs[refs < 0] >= S)
         assert np.array_equal(plan["anchor_ent"][gs[refs < 0] - S], -1 - refs[refs < 0])
@@ -122,11 +124,12 @@ def test_plan_invariants_mixed(kg):
     check_invariants(qb, oplan.build_plan(qb))
 
 
-def test_plan_values_through_refs_match_per_query_execution(kg):
-    """Executing the plan's groups level by level with the oracle's operators gives,
-    at every root slot, the per-query branch embedding."""
+@pytest.mark.parametrize("schedule,b_max", [("level", 0), ("max_fill", 0), ("max_fill", 7)])
+def test_plan_values_through_refs_match_per_query_execution(kg, schedule, b_max):
+    """Executing the plan's groups step by step with the oracle's operators gives,
+    at every root slot, the per-query branch embedding -- whatever the schedule."""
     qb = wl.make_batch(kg, 40, {n: 1.0 for n in CENSUS}, 10)
-    plan = oplan.build_plan(qb)
+    plan = oplan.build_plan(qb, schedule, b_max)
     p = wl.make_params(400, 12, 8, 16, 5)
     M = om.Model(p, 12.0)
     Pm = M.P
@@ -153,6 +156,93 @@ def test_plan_values_through_refs_match_per_query_execution(kg):
         assert len(br) == len(slots)
         for b, s in zip(br, slots):
             np.testing.assert_allclose(A[s], om.forward(b, M)[0], rtol=1e-12, atol=1e-14)
+
+
+# ---------------------------------------------------------------- Max-Fillness schedule (Alg. 1)
+def test_max_fillness_hand_worked_schedule():
+    """Three queries worked by hand.  Node ids: q0 = p(p(e)): e0 p1 p2; q1 = i(p(e), p(e)):
+    e3 p4 e5 p6 i7; q2 = n(p(e)): e8 p9 n10.
+    Unbounded: cycle 1 files p1 p4 p6 p9 -> step 1 runs all four projections; then p2, i7, n10
+    are ready, one per pool: the tie goes projection, intersection, negation (steps 2, 3, 4).
+    B_max = 3: step 1 takes the first three of the pool (p1 p4 p6), p9 stays; p2 and i7 become
+    ready; the projection pool [p9, p2] is the fullest -> step 2; then n10 is ready next to i7:
+    step 3 intersection, step 4 negation.
+    Live outputs (an output dies when its consumer has run, roots stay): unbounded 4, then
+    +1 (5, the peak) -1, +1 -2, +1 -1; bounded 3, then +2 (5) -1, +1 -2, +1 -1."""
+    trees = [("p", 1, ("p", 0, ("e", 1))), ("i", ("p", 2, ("e", 2)), ("p", 3, ("e", 3))), ("n", ("p", 4, ("e", 4)))]
+    qb = wl.batch_from_trees(trees, [5, 6, 7])
+    for b_max, want_n, want_rel in ((0, [4, 1, 1, 1], [[0, 2, 3, 4], [1]]), (3, [3, 2, 1, 1], [[0, 2, 3], [1, 4]])):
+        plan = oplan.build_plan(qb, "max_fill", b_max)
+        assert list(plan["g_level"]) == [1, 2, 3, 4] and plan["n_levels"] == 4
+        assert list(plan["g_type"]) == [P, P, I, N]
+        assert list(plan["g_n"]) == want_n
+        assert list(plan["rel"][:want_n[0]]) == want_rel[0]
+        assert list(plan["rel"][want_n[0]:]) == want_rel[1]
+        assert plan["peak_live"] == 5
+    # the level-synchronous order of the same batch: 4 projections, then p + i + n together
+    lvl = oplan.build_plan(qb)
+    assert list(lvl["g_level"]) == [1, 2, 2, 2] and lvl["peak_live"] == 7
+
+
+CLASS_ORDER = [(P, 1)] + [(I, k) for k in range(2, 9)] + [(N, 1)]
+
+
+@pytest.mark.parametrize("b_max", [0, 1, 5, 50])
+def test_max_fillness_invariants_and_greedy_choice(kg, b_max):
+    """Every step is one class of at most B_max operators whose inputs ran earlier, and -- replaying
+    the plan -- the class that ran was the fullest pool of that cycle (ties to the first class),
+    cut at B_max."""
+    qb = wl.make_batch(kg, 120, {n: 1.0 for n in CENSUS}, 31)
+    plan = oplan.build_plan(qb, "max_fill", b_max)
+    check_invariants(qb, plan, asap=False)
+    S, G = plan["n_slots"], plan["n_groups"]
+    assert G == plan["n_levels"] and list(plan["g_level"]) == list(range(1, G + 1))   # one group per step
+    step = np.zeros(S, int)
+    cls = [None] * S
+    ready_at = np.ones(S, int)
+    for g in range(G):
+        t, k, n = (int(plan[x][g]) for x in ("g_type", "g_nin", "g_n"))
+        ob, ro = int(plan["g_out_base"][g]), int(plan["g_ref_off"][g])
+        assert b_max == 0 or n <= b_max
+        step[ob:ob + n] = g + 1
+        for i in range(n):
+            cls[ob + i] = (t, k)
+    for g in range(G):
+        t, k, n = (int(plan[x][g]) for x in ("g_type", "g_nin", "g_n"))
+        ob, ro = int(plan["g_out_base"][g]), int(plan["g_ref_off"][g])
+        refs = plan["in_ref"][ro:ro + k * n].reshape(k, n)
+        for i in range(n):
+            ins = [step[r] for r in refs[:, i] if r >= 0]
+            ready_at[ob + i] = 1 + max(ins) if ins else 1
+    for t in range(1, G + 1):
+        waiting = [s for s in range(S) if ready_at[s] <= t <= step[s]]
+        count = {c: sum(1 for s in waiting if cls[s] == c) for c in CLASS_ORDER}
+        best = max(CLASS_ORDER, key=lambda c: (count[c], -CLASS_ORDER.index(c)))
+        ran = (int(plan["g_type"][t - 1]), int(plan["g_nin"][t - 1]))
+        assert ran == best, (t, ran, best, count)
+        assert int(plan["g_n"][t - 1]) == (count[best] if b_max == 0 else min(count[best], b_max))
+    if b_max == 1:
+        assert G == S
+    # an unbounded step never leaves ready operators of its class behind
+    if b_max == 0:
+        for t in range(1, G + 1):
+            assert not any(ready_at[s] <= t < step[s] and cls[s] == cls[np.flatnonzero(step == t)[0]] for s in range(S))
+    # reclamation can only help: never more live outputs than operators
+    assert 0 < plan["peak_live"] <= S
+
+
+def test_max_fillness_single_chain_templates(kg):
+    """Ten 3p chains are 30 projections in one pool.  Unbounded, a step drains the pool, so
+    the steps are the three depths.  With B_max = 4 the single pool is never empty before the
+    end (every step of 4 makes up to 4 successors ready): 7 steps of 4 and one of 2, and the
+    first come first served order mixes depths inside a step."""
+    qb = wl.make_batch(kg, 10, {"3p": 1.0}, 3)
+    assert list(oplan.build_plan(qb, "max_fill", 0)["g_n"]) == [10, 10, 10]
+    plan = oplan.build_plan(qb, "max_fill", 4)
+    assert list(plan["g_n"]) == [4] * 7 + [2]
+    # step 3 holds the last two first-hop projections (anchor inputs) and two second hops
+    ro = int(plan["g_ref_off"][2])
+    assert sorted(int(r) < 0 for r in plan["in_ref"][ro:ro + 4]) == [False, False, True, True]
 
 
 def brute_index(keys):
