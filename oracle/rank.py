@@ -41,3 +41,30 @@ def topk_all(batch, i, M, k):
     dist = distances_all(batch, i, M)
     order = np.lexsort((np.arange(dist.shape[0]), dist))[:k]
     return order.astype(np.int64), dist[order]
+
+
+def filtered_ranks(batch, i, answers, M):
+    """Filtered rank of every listed answer of query i [the evaluation protocol behind the
+    filtered MRR / Hit@k the paper reports, Sec. 5.3 and the large-KG table]: an answer's rank
+    is 1 + the number of entities that are NOT listed answers of the query and lie strictly
+    closer to the query than it does.  Returns (ranks [len(answers)], distances of the answers)."""
+    dist = distances_all(batch, i, M)
+    answers = np.asarray(answers, np.int64)
+    other = np.ones(dist.shape[0], bool)
+    other[answers] = False
+    d_other = np.sort(dist[other])
+    ranks = 1 + np.searchsorted(d_other, dist[answers], side="left")     # strictly smaller
+    return ranks.astype(np.int64), dist[answers]
+
+
+def ranking_metrics(rank_lists, ks=(1, 3, 10)):
+    """Mean reciprocal rank and Hit@k: per query the mean over its ranked answers, then the
+    mean over the queries that have at least one.  Returns [MRR, Hit@k1, Hit@k2, ...]."""
+    per_query = []
+    for r in rank_lists:
+        r = np.asarray(r, np.float64)
+        if r.size:
+            per_query.append([np.mean(1.0 / r)] + [np.mean(r <= k) for k in ks])
+    if not per_query:
+        return np.zeros(1 + len(ks))
+    return np.mean(np.asarray(per_query), axis=0)

@@ -353,3 +353,41 @@ def test_topk_against_python_sort_and_candidate_scores():
         # same numbers as the training-time score of the same pairs
         _, s = om.query_step(qb.query_nodes(i), int(ids[0]), ids[1:], M, 1)
         np.testing.assert_allclose(s, sc[0], rtol=1e-14)
+
+
+# ---------------------------------------------------------------- filtered ranks, MRR, Hit@k
+def test_filtered_ranks_against_python_loops_and_special_cases():
+    from oracle import rank as orank
+    _, qb, _, p, _ = tiny(seed=9, N=60, B=12, K=1, mix={"2u": 1.0, "2i": 1.0, "1p": 1.0})
+    M = om.Model(p, 12.0)
+    rng = np.random.default_rng(3)
+    for q in range(qb.B):
+        dist = orank.distances_all(qb, q, M)
+        answers = [int(a) for a in rng.choice(60, 1 + q % 5, replace=False)]
+        ranks, d_ans = orank.filtered_ranks(qb, q, answers, M)
+        for a, r, da in zip(answers, ranks, d_ans):
+            want = 1
+            for e in range(60):                       # the definition, entity by entity
+                if e not in answers and dist[e] < dist[a]:
+                    want += 1
+            assert r == want and da == dist[a]
+        # the nearest entity alone has rank 1; so has anything once every entity is filtered
+        order = np.argsort(dist, kind="stable")
+        assert orank.filtered_ranks(qb, q, [int(order[0])], M)[0][0] == 1
+        assert np.all(orank.filtered_ranks(qb, q, list(range(60)), M)[0] == 1)
+        # unfiltered (single answer): rank = position in the full sort
+        for pos in (0, 7, 59):
+            assert orank.filtered_ranks(qb, q, [int(order[pos])], M)[0][0] == pos + 1
+        # filtering the k nearest entities lifts the (k+1)-th to rank 1
+        assert orank.filtered_ranks(qb, q, [int(e) for e in order[:6]], M)[0][5] == 1
+
+
+def test_ranking_metrics_closed_forms():
+    from oracle import rank as orank
+    m = orank.ranking_metrics([[1, 2, 4]])
+    assert m[0] == pytest.approx((1 + 0.5 + 0.25) / 3) and list(m[1:]) == [pytest.approx(1 / 3), pytest.approx(2 / 3), 1.0]
+    # per query first, then over queries: not the pooled mean
+    m = orank.ranking_metrics([[1], [10, 100, 1000], []])
+    assert m[0] == pytest.approx((1.0 + (0.1 + 0.01 + 0.001) / 3) / 2)
+    assert m[3] == pytest.approx((1.0 + 1 / 3) / 2) and m[1] == pytest.approx(0.5)
+    assert np.all(orank.ranking_metrics([[], []]) == 0)
