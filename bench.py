@@ -130,30 +130,41 @@ def rank_bench(args, cfg, kg, params, sem_bits):
     eng.bind_numpy(params, sem_bits=sem_bits)
     plan = eng.plan(qb)
     rows = plan.export()["n_roots"]
+    if args.answers > 0:      # evaluation: filtered ranks of A listed answers per query (the positive first)
+        rng = np.random.default_rng(cfg.seed + 9)
+        ans = rng.integers(0, cfg.N, (Q, args.answers)).astype(np.int32)
+        ans[:, 0] = qb.pos
+        ans_off = torch.arange(0, Q * args.answers + 1, args.answers, dtype=torch.int32, device="cuda")
+        ans_dev = torch.from_numpy(ans.reshape(-1)).cuda()
+        run = lambda: eng.rank_answers(plan, ans_off, ans_dev)
+    else:
+        run = lambda: eng.rank_all(plan, k)
     for _ in range(args.warmup):
-        eng.rank_all(plan, k)
+        run()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        eng.rank_all(plan, k)
+        run()
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / args.steps
     eng.set_timing(("score",))
     eng.get_timing(reset=True)
     for _ in range(args.steps):
-        eng.rank_all(plan, k)
+        run()
     ms, n = eng.get_timing(reset=True)["score"]
     # subtract and |.|-accumulate per coordinate, branch row and entity
     ops = 2.0 * rows * cfg.N * cfg.d
     ach = ops / (ms / n * 1e-3) / 1e12
-    out = {"metric": "all-entity ranking queries/sec (forward + L1 distance to every entity + top-10)",
+    what = "top-%d" % k if args.answers <= 0 else "filtered ranks of %d answers per query, MRR, Hit@k" % args.answers
+    out = {"metric": "all-entity ranking queries/sec (forward + L1 distance to every entity + %s)" % what,
            "value": Q / dt, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": 1e3 * dt, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "f32", "data": "synthetic",
            "config": {"workload": "configs[%d] %s ranking pass: %d queries (%d branch rows) x N=%d entities, d=%d%s, top-%d"
                       % (cfg.index, cfg.name, Q, rows, cfg.N, cfg.d,
-                         " d_sem=%d" % cfg.d_sem if cfg.d_sem else "", k)},
-           "roofline": {"bound": "alu", "kernel": "rank (distance tiles + top-k merge%s)" % (
+                         " d_sem=%d" % cfg.d_sem if cfg.d_sem else "", k), "evaluation": what},
+           "roofline": {"bound": "alu", "kernel": "rank (distance tiles + %s%s)" % (
+                            "top-k merge" if args.answers <= 0 else "closer-entity counts",
                             " + projection of every entity chunk" if cfg.d_sem else ""),
                         "achieved": ach, "peak": VALU_PEAK_TOPS, "unit": "Tlane-op/s", "frac": ach / VALU_PEAK_TOPS,
                         "traffic": None, "avg_us": 1e3 * ms / n,
@@ -175,6 +186,8 @@ def main():
     ap.add_argument("--bmax", type=int, default=0, help="largest batch of one Max-Fillness step, 0 = unbounded")
     ap.add_argument("--rank", type=int, default=0, metavar="Q",
                     help="time the all-entity ranking pass of Q queries instead of the training step")
+    ap.add_argument("--answers", type=int, default=0, metavar="A",
+                    help="with --rank: filtered ranks of A listed answers per query instead of the top-10")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="also run the library's plain copy kernel on this many MiB, 5 times (reference "
                          "for scaling rocprofv3 traffic counters)")

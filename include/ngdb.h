@@ -261,6 +261,24 @@ int ngdb_score(ngdb_ctx_t* ctx, const ngdb_plan_t* plan, const int32_t* d_cand, 
                int32_t topk, float* d_scores, int32_t* d_topk_ids, float* d_topk_dist,
                void* stream);
 
+/* Evaluation (the filtered MRR / Hit@k the paper reports, Sec. 5.3): forward, then for
+ * every listed answer of every query its filtered rank
+ *     1 + #{entities that are not listed answers of the query and lie strictly closer}.
+ * d_ans_off: device [n_queries+1], answers of query q are d_ans[d_ans_off[q]..d_ans_off[q+1]-1]
+ * (device, n_ans ids in total; ranges are the caller's responsibility).  d_rank: device
+ * [n_ans].  d_ans_dist: device [n_ans] or NULL, receives the L1 distance of every answer.
+ * Distances are fp32: entities within rounding of an answer's distance may fall on
+ * either side.  At most 65535 queries per call.                                        */
+int ngdb_rank_answers(ngdb_ctx_t* ctx, const ngdb_plan_t* plan, const int32_t* d_ans_off,
+                      const int32_t* d_ans, int32_t n_ans, int32_t* d_rank, float* d_ans_dist,
+                      void* stream);
+/* d_out[0] = mean reciprocal rank, d_out[1..3] = Hit@1, Hit@3, Hit@10 (device, 4 floats):
+ * per query the mean over its first d_n_take[q] listed answers (NULL: all of them -- list
+ * the answers to be scored first, the ones only to be filtered after them), then the mean
+ * over the queries that have at least one.                                              */
+int ngdb_rank_metrics(const int32_t* d_rank, const int32_t* d_ans_off, const int32_t* d_n_take,
+                      int32_t n_queries, float* d_out, void* stream);
+
 /* The contraction kernel of the grouped MLPs on its own (used by tests):
  * C[M,N] = A[M,K] * B[K,N], all device fp32.  Element (m,k) of A is at
  * A[m*lda+k] if a_kcontig else A[k*lda+m]; element (k,n) of B at B[n*ldb+k] if

@@ -93,6 +93,8 @@ def load_library(path=LIB_PATH):
         "ngdb_forward_backward": (C.c_int, [vp, vp, vp, i32, vp, vp]),
         "ngdb_get_grads": (C.c_int, [vp, C.POINTER(GradView)]),
         "ngdb_score": (C.c_int, [vp, vp, vp, i32, i32, vp, vp, vp, vp]),
+        "ngdb_rank_answers": (C.c_int, [vp, vp, vp, vp, i32, vp, vp, vp]),
+        "ngdb_rank_metrics": (C.c_int, [vp, vp, vp, i32, vp, vp]),
         "ngdb_debug_gemm": (C.c_int, [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, i32, vp, i32, vp, i32,
                                       vp, vp]),
         "ngdb_debug_copy": (C.c_int, [vp, vp, C.c_size_t, vp]),
@@ -373,6 +375,25 @@ class Engine:
         _check(lib().ngdb_score(self.ctx, plan.handle, None, 0, int(k), None, ids.data_ptr(), dist.data_ptr(),
                                 self._stream(stream)), self.ctx)
         return ids, dist
+
+    def rank_answers(self, plan, ans_off, ans, n_take=None, stream=None):
+        """Filtered ranks of listed answers.  ans_off [B+1], ans [n_ans]: int32 device tensors;
+        n_take [B] int32 device tensor or None.  Returns (ranks [n_ans] int32, distances [n_ans]
+        float32, metrics [4] float32 = MRR, Hit@1, Hit@3, Hit@10), device tensors."""
+        t = self.torch
+        for x in (ans_off, ans):
+            assert x.dtype == t.int32 and x.is_cuda and x.is_contiguous() and x.dim() == 1
+        n_ans, B = int(ans.shape[0]), int(ans_off.shape[0]) - 1
+        ranks = t.empty(max(n_ans, 1), dtype=t.int32, device=self.device)
+        dist = t.empty(max(n_ans, 1), dtype=t.float32, device=self.device)
+        out = t.empty(4, dtype=t.float32, device=self.device)
+        st = self._stream(stream)
+        _check(lib().ngdb_rank_answers(self.ctx, plan.handle, ans_off.data_ptr(), ans.data_ptr(), n_ans,
+                                       ranks.data_ptr(), dist.data_ptr(), st), self.ctx)
+        _check(lib().ngdb_rank_metrics(ranks.data_ptr(), ans_off.data_ptr(),
+                                       n_take.data_ptr() if n_take is not None else None, B, out.data_ptr(), st),
+               self.ctx)
+        return ranks[:n_ans], dist[:n_ans], out
 
     def step_count(self):
         return int(lib().ngdb_step_count(self.ctx))

@@ -75,6 +75,7 @@ struct ngdb_ctx_s {
     DevBuf score, coef, win, mask, loss_terms, rec_coef, rec_row;
     DevBuf keys_a, keys_b, vals_a, vals_b, hist, scan_tmp, uniq, seg_off, n_uniq;
     DevBuf rank_dist;   // distances of one entity chunk in the all-entity ranking
+    DevBuf rank_thr, rank_count;   // filtered ranks: distance of every listed answer, entities closer than it
     DevBuf colsum_part; // 6 scratch areas of the bias-gradient column sums
     DevBuf gW;          // gradients of the 12 MLP tensors, packed
     DevBuf gE, gR;      // compact table gradients (ngdb_forward_backward only)
@@ -621,7 +622,7 @@ void ngdb_destroy(ngdb_ctx_t* c) {
     DevBuf* all[] = {&c->act, &c->dact, &c->Z[0], &c->Z[1], &c->Z[2], &c->H[0], &c->H[1], &c->H[2], &c->dH[0],
                      &c->dH[1], &c->dH[2], &c->Att, &c->dAtt, &c->Dx, &c->score, &c->coef, &c->win, &c->mask,
                      &c->loss_terms, &c->rec_coef, &c->rec_row, &c->keys_a, &c->keys_b, &c->vals_a, &c->vals_b, &c->hist, &c->scan_tmp,
-                     &c->uniq, &c->seg_off, &c->n_uniq, &c->gW, &c->gE, &c->gR, &c->colsum_part, &c->rank_dist,
+                     &c->uniq, &c->seg_off, &c->n_uniq, &c->gW, &c->gE, &c->gR, &c->colsum_part, &c->rank_dist, &c->rank_thr, &c->rank_count,
                      &c->Wb, &c->Ef, &c->inv, &c->refs_sem, &c->g_bf16, &c->wp_partial, &c->gWp, &c->rank_ef};
     for (DevBuf* b : all) release(*b);
     for (int i = 0; i < 4; ++i) {
@@ -891,7 +892,7 @@ int ngdb_score(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_cand, int3
                 HIPCHK(c, launch_sem_fuse(fa, s));
                 rows = ptr<float>(c->rank_ef);
             }
-            HIPCHK(c, launch_l1_tile(ptr<float>(c->act), pl->d_root_slot, R, rows, cnt, d,
+            HIPCHK(c, launch_l1_tile(ptr<float>(c->act), pl->d_root_slot, R, rows, nullptr, cnt, d,
                                      ptr<float>(c->rank_dist), ld, s));
             HIPCHK(c, launch_topk_merge(ptr<float>(c->rank_dist), ld, pl->d_root_off, pl->hp.n_queries, e0, cnt, topk,
                                         e0 == 0, d_topk_dist, d_topk_ids, s));
@@ -899,6 +900,86 @@ int ngdb_score(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_cand, int3
     }
     HIPCHK(c, hipEventRecord(pl->blob.last_use, s));
     return NGDB_OK;
+}
+
+int ngdb_rank_answers(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_ans_off, const int32_t* d_ans,
+                      int32_t n_ans, int32_t* d_rank, float* d_ans_dist, void* stream) {
+    if (!c || !pl) return NGDB_ERR_ARG;
+    if (!c->bound) return fail(c, NGDB_ERR_STATE, "parameters not bound");
+    if (pl->n_entities != c->cfg.n_entities || !pl->d_blob)
+        return fail(c, NGDB_ERR_ARG, "plan belongs to another configuration or was built without a device");
+    if (n_ans < 0 || !d_ans_off || (n_ans > 0 && (!d_ans || !d_rank)))
+        return fail(c, NGDB_ERR_ARG, "answer lists / rank output missing");
+    if (pl->hp.n_queries > 65535) return fail(c, NGDB_ERR_UNSUPPORTED, "more than 65535 queries in one ranking call");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool sem = c->cfg.d_sem > 0;
+    c->have_grads = false;
+    int rc = size_workspace(c, pl, 0, false);
+    if (rc != NGDB_OK) return rc;
+    EntRows er{c->prm.E.p, pl->d_in_ref, pl->d_pos, nullptr};
+    if (sem) {
+        int32_t* e_src = nullptr;
+        rc = prepare_entities(c, pl, nullptr, 0, s, s, &e_src, &er);
+        if (rc != NGDB_OK) return rc;
+    }
+    rc = enqueue_forward(c, pl, er, s);
+    if (rc != NGDB_OK) return rc;
+    if (n_ans > 0) {
+        const int N = c->cfg.n_entities, d = c->cfg.d, R = pl->hp.n_roots, B = pl->hp.n_queries;
+        const int chunk = std::min(std::max(N, n_ans), 1 << 16);
+        const int ld = (chunk + 3) & ~3;
+        if ((rc = ensure(c, c->rank_dist, std::max<size_t>((size_t)R * ld * sizeof(float), 256))) != NGDB_OK) return rc;
+        if ((rc = ensure(c, c->rank_count, (size_t)n_ans * 4)) != NGDB_OK) return rc;
+        if (!d_ans_dist && (rc = ensure(c, c->rank_thr, (size_t)n_ans * 4)) != NGDB_OK) return rc;
+        if (sem && (rc = ensure(c, c->rank_ef, (size_t)chunk * d * sizeof(float))) != NGDB_OK) return rc;
+        float* thr = d_ans_dist ? d_ans_dist : ptr<float>(c->rank_thr);
+        Timed tm(c, NGDB_TK_SCORE, s);
+        HIPCHK(c, launch_fill_zero_i32(ptr<int32_t>(c->rank_count), n_ans, s));
+        SemFuseArgs fa{};
+        fa.H = c->prm.H_sem; fa.Wb = ptr<uint16_t>(c->Wb); fa.E = c->prm.E.p; fa.d = d; fa.ds = c->cfg.d_sem;
+        fa.out = ptr<float>(c->rank_ef);
+        // distance of every listed answer to its query, by the kernels of the all-entity pass
+        // (the same arithmetic, so an answer compares equal to itself there)
+        for (int a0 = 0; a0 < n_ans; a0 += chunk) {
+            const int cnt = std::min(chunk, n_ans - a0);
+            const float* rows = c->prm.E.p;
+            const int32_t* ids = d_ans + a0;
+            if (sem) {
+                fa.ids = d_ans + a0; fa.id_base = 0; fa.n_rows = cnt;
+                HIPCHK(c, launch_sem_fuse(fa, s));
+                rows = ptr<float>(c->rank_ef);
+                ids = nullptr;
+            }
+            HIPCHK(c, launch_l1_tile(ptr<float>(c->act), pl->d_root_slot, R, rows, ids, cnt, d,
+                                     ptr<float>(c->rank_dist), ld, s));
+            HIPCHK(c, launch_answer_dist(ptr<float>(c->rank_dist), ld, pl->d_root_off, d_ans_off, B, a0, cnt, thr, s));
+        }
+        // entities strictly closer than each answer, chunk by chunk
+        for (int e0 = 0; e0 < N; e0 += chunk) {
+            const int cnt = std::min(chunk, N - e0);
+            const float* rows = c->prm.E.p + (size_t)e0 * d;
+            if (sem) {
+                fa.ids = nullptr; fa.id_base = e0; fa.n_rows = cnt;
+                HIPCHK(c, launch_sem_fuse(fa, s));
+                rows = ptr<float>(c->rank_ef);
+            }
+            HIPCHK(c, launch_l1_tile(ptr<float>(c->act), pl->d_root_slot, R, rows, nullptr, cnt, d,
+                                     ptr<float>(c->rank_dist), ld, s));
+            HIPCHK(c, launch_count_less(ptr<float>(c->rank_dist), ld, pl->d_root_off, d_ans_off, thr, B, cnt,
+                                        ptr<int32_t>(c->rank_count), s));
+        }
+        HIPCHK(c, launch_finish_rank(ptr<int32_t>(c->rank_count), thr, d_ans_off, B, n_ans, d_rank, s));
+    }
+    HIPCHK(c, hipEventRecord(pl->blob.last_use, s));
+    return NGDB_OK;
+}
+
+int ngdb_rank_metrics(const int32_t* d_rank, const int32_t* d_ans_off, const int32_t* d_n_take, int32_t n_queries,
+                      float* d_out, void* stream) {
+    if (!d_ans_off || !d_out || n_queries < 0 || (n_queries > 0 && !d_rank)) return NGDB_ERR_ARG;
+    const hipError_t e = launch_rank_metrics(d_rank, d_ans_off, d_n_take, n_queries, d_out,
+                                             static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? NGDB_OK : NGDB_ERR_HIP;
 }
 
 int ngdb_debug_gemm(const float* A, const float* B, float* C, int32_t M, int32_t N, int32_t K, int32_t lda,

@@ -149,9 +149,23 @@ struct ScoreArgs {
 hipError_t launch_score(const ScoreArgs& a, bool train, hipStream_t s);
 
 // ---------------------------------------------------------------- ranking (rank.hip)
-// dist[r*ld + e] = ||act[row_ids[r]] - Emat[e]||_1 for r < n_rows, e < n_ent
-hipError_t launch_l1_tile(const float* act, const int32_t* row_ids, int n_rows, const float* Emat, int n_ent, int d,
-                          float* dist, int ld, hipStream_t s);
+// dist[r*ld + e] = ||act[row_ids[r]] - Emat[id(e)]||_1 for r < n_rows, e < n_ent; id(e) = ent_ids[e] or e
+hipError_t launch_l1_tile(const float* act, const int32_t* row_ids, int n_rows, const float* Emat,
+                          const int32_t* ent_ids, int n_ent, int d, float* dist, int ld, hipStream_t s);
+// filtered ranks of listed answers (answers of query q: ans_off[q]..ans_off[q+1]-1):
+// thr[a] = distance of answer a (column a - a0 of dist) to its query, min over the query's rows
+hipError_t launch_answer_dist(const float* dist, int ld, const int32_t* root_off, const int32_t* ans_off, int n_queries,
+                              int a0, int cnt, float* thr, hipStream_t s);
+// count[a] += #{entities e < n_ent of this chunk: min over rows dist[row, e] < thr[a]}
+hipError_t launch_count_less(const float* dist, int ld, const int32_t* root_off, const int32_t* ans_off,
+                             const float* thr, int n_queries, int n_ent, int32_t* count, hipStream_t s);
+// rank[a] = 1 + count[a] - #{listed answers b of a's query: thr[b] < thr[a]}
+hipError_t launch_finish_rank(const int32_t* count, const float* thr, const int32_t* ans_off, int n_queries, int n_ans,
+                              int32_t* rank, hipStream_t s);
+// out[0..3] = MRR, Hit@1, Hit@3, Hit@10 over the first n_take[q] (null: all) answers of every query
+hipError_t launch_rank_metrics(const int32_t* rank, const int32_t* ans_off, const int32_t* n_take, int n_queries,
+                               float* out, hipStream_t s);
+hipError_t launch_fill_zero_i32(int32_t* p, int n, hipStream_t s);
 // per query q: entity value = min over rows root_off[q]..root_off[q+1]-1 of dist; merges the
 // k best (value, ent_base + e) of this chunk into out_dist/out_ids [n_queries, k]
 hipError_t launch_topk_merge(const float* dist, int ld, const int32_t* root_off, int n_queries, int ent_base, int n_ent,

@@ -23,8 +23,12 @@ namespace {
 
 constexpr int TQ = 128, TE = 128, DC = 16, LDT = 128 + 4;
 
+// entity e of the tile is row ent_ids[e] of Emat if ent_ids is given, else row e.  The
+// distance of a (row, entity) pair is summed by one lane over the coordinates in ascending
+// order, so its value does not depend on where in a tile, or in which launch, the pair falls.
 __global__ __launch_bounds__(256) void l1_tile_kernel(const float* __restrict__ act, const int32_t* __restrict__ row_ids,
-                                                      int n_rows, const float* __restrict__ Emat, int n_ent, int d,
+                                                      int n_rows, const float* __restrict__ Emat,
+                                                      const int32_t* __restrict__ ent_ids, int n_ent, int d,
                                                       float* __restrict__ dist, int ld) {
     __shared__ __attribute__((aligned(16))) float Ys[2][DC][LDT];
     __shared__ __attribute__((aligned(16))) float Es[2][DC][LDT];
@@ -43,7 +47,8 @@ __global__ __launch_bounds__(256) void l1_tile_kernel(const float* __restrict__ 
         lkq[i] = idx & 3;
         const int r = min(r0 + lrow[i], n_rows - 1);          // clamped rows are computed and never stored
         yrow[i] = act + (size_t)row_ids[r] * d;
-        erow[i] = Emat + (size_t)min(e0 + lrow[i], n_ent - 1) * d;
+        const int ec = min(e0 + lrow[i], n_ent - 1);
+        erow[i] = Emat + (size_t)(ent_ids ? ent_ids[ec] : ec) * d;
     }
     float4 ry[2], re[2];
     auto issue = [&](int k0) {
@@ -205,14 +210,171 @@ __global__ __launch_bounds__(256) void topk_kernel(const float* __restrict__ dis
     }
 }
 
+// ---------------------------------------------------------------- filtered ranks of listed answers
+// query of answer a: largest q with ans_off[q] <= a
+__device__ __forceinline__ int query_of_answer(const int32_t* __restrict__ ans_off, int n_queries, int a) {
+    int lo = 0, hi = n_queries;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (ans_off[mid] <= a) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// thr[a] = min over the branch rows of a's query of dist[row, a - a0], a0 <= a < a0 + cnt
+__global__ __launch_bounds__(256) void answer_dist_kernel(const float* __restrict__ dist, int ld,
+                                                          const int32_t* __restrict__ root_off,
+                                                          const int32_t* __restrict__ ans_off, int n_queries, int a0,
+                                                          int cnt, float* __restrict__ thr) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= cnt) return;
+    const int q = query_of_answer(ans_off, n_queries, a0 + i);
+    float v = INFINITY;
+    for (int r = root_off[q]; r < root_off[q + 1]; ++r) v = fminf(v, dist[(size_t)r * ld + i]);
+    thr[a0 + i] = v;
+}
+
+constexpr int CNT_SLAB = 8192;    // entities per workgroup of the counting pass
+constexpr int CNT_TILE = 256;     // answers whose counters a workgroup holds at once
+
+// count[a] += number of entities of the slab strictly closer to a's query than thr[a].
+// Grid (slabs, queries).  A wavefront compares 64 entities with one threshold at a time and
+// counts by ballot; the per-wavefront counters live in LDS, one integer atomic per answer and
+// workgroup reaches global memory (integer sums do not depend on the order).
+__global__ __launch_bounds__(256) void count_less_kernel(const float* __restrict__ dist, int ld,
+                                                         const int32_t* __restrict__ root_off,
+                                                         const int32_t* __restrict__ ans_off,
+                                                         const float* __restrict__ thr, int n_ent,
+                                                         int32_t* __restrict__ count) {
+    __shared__ float s_thr[CNT_TILE];
+    __shared__ int32_t s_cnt[4][CNT_TILE];
+    const int q = blockIdx.y;
+    const int a_lo = ans_off[q], a_hi = ans_off[q + 1];
+    if (a_lo >= a_hi) return;                                         // uniform
+    const int r_lo = root_off[q], r_hi = root_off[q + 1];
+    const int e_lo = blockIdx.x * CNT_SLAB, e_hi = min(n_ent, e_lo + CNT_SLAB);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int t0 = a_lo; t0 < a_hi; t0 += CNT_TILE) {
+        const int nt = min(CNT_TILE, a_hi - t0);
+        __syncthreads();
+        for (int j = threadIdx.x; j < nt; j += 256) s_thr[j] = thr[t0 + j];
+        for (int j = lane; j < nt; j += 64) s_cnt[wave][j] = 0;
+        __syncthreads();
+        for (int e = e_lo + threadIdx.x; e - (int)threadIdx.x < e_hi; e += 256) {   // whole wavefronts iterate together
+            float v = INFINITY;                                       // entities past the end are closer to nothing
+            if (e < e_hi)
+                for (int r = r_lo; r < r_hi; ++r) v = fminf(v, dist[(size_t)r * ld + e]);
+            for (int j = 0; j < nt; ++j) {
+                const int c = __popcll(__ballot(v < s_thr[j]));
+                if (lane == 0) s_cnt[wave][j] += c;
+            }
+        }
+        __syncthreads();
+        for (int j = threadIdx.x; j < nt; j += 256) {
+            const int c = (s_cnt[0][j] + s_cnt[1][j]) + (s_cnt[2][j] + s_cnt[3][j]);
+            if (c) atomicAdd(&count[t0 + j], c);
+        }
+    }
+}
+
+// rank[a] = 1 + count[a] - #{other listed answers b of the same query with thr[b] < thr[a]}
+__global__ __launch_bounds__(256) void finish_rank_kernel(const int32_t* __restrict__ count,
+                                                          const float* __restrict__ thr,
+                                                          const int32_t* __restrict__ ans_off, int n_queries,
+                                                          int n_ans, int32_t* __restrict__ rank) {
+    const int a = blockIdx.x * blockDim.x + threadIdx.x;
+    if (a >= n_ans) return;
+    const int q = query_of_answer(ans_off, n_queries, a);
+    const float t = thr[a];
+    int closer = 0;
+    for (int b = ans_off[q]; b < ans_off[q + 1]; ++b) closer += thr[b] < t ? 1 : 0;
+    rank[a] = 1 + count[a] - closer;
+}
+
+// out[0] = mean reciprocal rank, out[1..3] = Hit@1, @3, @10: per query the mean over its first
+// n_take[q] listed answers (all if n_take is null), then the mean over the queries that have one.
+// One workgroup, fixed summation order.
+__global__ __launch_bounds__(256) void rank_metrics_kernel(const int32_t* __restrict__ rank,
+                                                           const int32_t* __restrict__ ans_off,
+                                                           const int32_t* __restrict__ n_take, int n_queries,
+                                                           float* __restrict__ out) {
+    __shared__ float part[256][5];
+    float acc[5] = {0.f, 0.f, 0.f, 0.f, 0.f};      // MRR, H@1, H@3, H@10, queries counted
+    for (int q = threadIdx.x; q < n_queries; q += 256) {
+        const int lo = ans_off[q];
+        const int n = n_take ? min(n_take[q], ans_off[q + 1] - lo) : ans_off[q + 1] - lo;
+        if (n <= 0) continue;
+        float rr = 0.f, h1 = 0.f, h3 = 0.f, h10 = 0.f;
+        for (int j = 0; j < n; ++j) {
+            const int r = rank[lo + j];
+            rr += 1.f / (float)r;
+            h1 += r <= 1 ? 1.f : 0.f;
+            h3 += r <= 3 ? 1.f : 0.f;
+            h10 += r <= 10 ? 1.f : 0.f;
+        }
+        const float inv = 1.f / (float)n;
+        acc[0] += rr * inv; acc[1] += h1 * inv; acc[2] += h3 * inv; acc[3] += h10 * inv; acc[4] += 1.f;
+    }
+    for (int k = 0; k < 5; ++k) part[threadIdx.x][k] = acc[k];
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off)
+            for (int k = 0; k < 5; ++k) part[threadIdx.x][k] += part[threadIdx.x + off][k];
+        __syncthreads();
+    }
+    if (threadIdx.x < 4) out[threadIdx.x] = part[0][4] > 0.f ? part[0][threadIdx.x] / part[0][4] : 0.f;
+}
+
+__global__ __launch_bounds__(256) void fill_zero_i32_kernel(int32_t* p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
 }  // namespace
 
-hipError_t launch_l1_tile(const float* act, const int32_t* row_ids, int n_rows, const float* Emat, int n_ent, int d,
-                          float* dist, int ld, hipStream_t s) {
+hipError_t launch_l1_tile(const float* act, const int32_t* row_ids, int n_rows, const float* Emat,
+                          const int32_t* ent_ids, int n_ent, int d, float* dist, int ld, hipStream_t s) {
     if (n_rows <= 0 || n_ent <= 0) return hipSuccess;
     if ((d & 3) || (ld & 3)) return hipErrorInvalidValue;
     dim3 grid((n_ent + TE - 1) / TE, (n_rows + TQ - 1) / TQ);
-    hipLaunchKernelGGL(l1_tile_kernel, grid, dim3(256), 0, s, act, row_ids, n_rows, Emat, n_ent, d, dist, ld);
+    hipLaunchKernelGGL(l1_tile_kernel, grid, dim3(256), 0, s, act, row_ids, n_rows, Emat, ent_ids, n_ent, d, dist, ld);
+    return hipGetLastError();
+}
+
+hipError_t launch_answer_dist(const float* dist, int ld, const int32_t* root_off, const int32_t* ans_off, int n_queries,
+                              int a0, int cnt, float* thr, hipStream_t s) {
+    if (cnt <= 0) return hipSuccess;
+    hipLaunchKernelGGL(answer_dist_kernel, dim3((cnt + 255) / 256), dim3(256), 0, s, dist, ld, root_off, ans_off,
+                       n_queries, a0, cnt, thr);
+    return hipGetLastError();
+}
+
+hipError_t launch_count_less(const float* dist, int ld, const int32_t* root_off, const int32_t* ans_off,
+                             const float* thr, int n_queries, int n_ent, int32_t* count, hipStream_t s) {
+    if (n_queries <= 0 || n_ent <= 0) return hipSuccess;
+    if (n_queries > 65535) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(count_less_kernel, dim3((n_ent + CNT_SLAB - 1) / CNT_SLAB, n_queries), dim3(256), 0, s, dist, ld,
+                       root_off, ans_off, thr, n_ent, count);
+    return hipGetLastError();
+}
+
+hipError_t launch_finish_rank(const int32_t* count, const float* thr, const int32_t* ans_off, int n_queries, int n_ans,
+                              int32_t* rank, hipStream_t s) {
+    if (n_ans <= 0) return hipSuccess;
+    hipLaunchKernelGGL(finish_rank_kernel, dim3((n_ans + 255) / 256), dim3(256), 0, s, count, thr, ans_off, n_queries,
+                       n_ans, rank);
+    return hipGetLastError();
+}
+
+hipError_t launch_rank_metrics(const int32_t* rank, const int32_t* ans_off, const int32_t* n_take, int n_queries,
+                               float* out, hipStream_t s) {
+    hipLaunchKernelGGL(rank_metrics_kernel, dim3(1), dim3(256), 0, s, rank, ans_off, n_take, n_queries, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_zero_i32(int32_t* p, int n, hipStream_t s) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_zero_i32_kernel, dim3((n + 255) / 256), dim3(256), 0, s, p, n);
     return hipGetLastError();
 }
 
