@@ -279,6 +279,28 @@ int ngdb_rank_answers(ngdb_ctx_t* ctx, const ngdb_plan_t* plan, const int32_t* d
 int ngdb_rank_metrics(const int32_t* d_rank, const int32_t* d_ans_off, const int32_t* d_n_take,
                       int32_t n_queries, float* d_out, void* stream);
 
+/* Online query sampler (App. "Stochastic Online Query Sampling"): host only, no device.
+ * Batches are synthesised from the graph on the fly: a template (names out of 1p 2p 3p 2i 3i
+ * ip pi 2u up 2in 3in inp pin pni, comma separated in template_names; weights: one per name
+ * or NULL for uniform) is instantiated by a random walk backwards from the answer, with
+ * rejection of walks that dead-end, of intersections with identical children and of queries
+ * whose end point is not an answer (negation); the accepted end point is the positive.
+ * head/rel/tail: host arrays of n_triples directed triples (copied).  Every query draws from
+ * its own random stream (seed, batch number, query number): batches do not depend on
+ * n_threads.  ngdb_sampler_next fills `batch` (and *neg: host [n_queries, K] uniform entity
+ * ids; *template_id: host [n_queries] index into the names) with arrays owned by the sampler,
+ * valid until the next call on it; the batch can go straight to ngdb_plan.  One sampler must
+ * not be used from two threads at once (it may run beside a context's calls).            */
+typedef struct ngdb_sampler_s ngdb_sampler_t;
+int ngdb_sampler_create(int32_t n_entities, int32_t n_relations, int64_t n_triples,
+                        const int32_t* head, const int32_t* rel, const int32_t* tail,
+                        const char* template_names, const float* weights, uint64_t seed,
+                        int32_t n_threads, ngdb_sampler_t** out);
+int ngdb_sampler_next(ngdb_sampler_t* sampler, int32_t n_queries, int32_t K, ngdb_query_batch* batch,
+                      const int32_t** neg, const uint8_t** template_id);
+void ngdb_sampler_destroy(ngdb_sampler_t* sampler);
+const char* ngdb_sampler_last_error(const ngdb_sampler_t* sampler);
+
 /* The contraction kernel of the grouped MLPs on its own (used by tests):
  * C[M,N] = A[M,K] * B[K,N], all device fp32.  Element (m,k) of A is at
  * A[m*lda+k] if a_kcontig else A[k*lda+m]; element (k,n) of B at B[n*ldb+k] if

@@ -2,5 +2,5 @@
 
 The compute lives in libngdb.so (HIP, gfx950); see include/ngdb.h for the C boundary.
 """
-from .binding import (Engine, NgdbError, Plan, plan_host, lib, load_library, LIB_PATH,  # noqa: F401
+from .binding import (Engine, NgdbError, Plan, Sampler, plan_host, lib, load_library, LIB_PATH,  # noqa: F401
                       MLP_NAMES, TENSOR_NAMES)

@@ -95,6 +95,10 @@ def load_library(path=LIB_PATH):
         "ngdb_score": (C.c_int, [vp, vp, vp, i32, i32, vp, vp, vp, vp]),
         "ngdb_rank_answers": (C.c_int, [vp, vp, vp, vp, i32, vp, vp, vp]),
         "ngdb_rank_metrics": (C.c_int, [vp, vp, vp, i32, vp, vp]),
+        "ngdb_sampler_create": (C.c_int, [i32, i32, i64, vp, vp, vp, C.c_char_p, vp, C.c_uint64, i32, C.POINTER(vp)]),
+        "ngdb_sampler_next": (C.c_int, [vp, i32, i32, C.POINTER(QueryBatchC), C.POINTER(vp), C.POINTER(vp)]),
+        "ngdb_sampler_destroy": (None, [vp]),
+        "ngdb_sampler_last_error": (C.c_char_p, [vp]),
         "ngdb_debug_gemm": (C.c_int, [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, i32, vp, i32, vp, i32,
                                       vp, vp]),
         "ngdb_debug_copy": (C.c_int, [vp, vp, C.c_size_t, vp]),
@@ -215,6 +219,61 @@ def debug_copy(dst, src):
     _check(lib().ngdb_debug_copy(dst.data_ptr(), src.data_ptr(), nbytes,
                                  C.c_void_p(torch.cuda.current_stream().cuda_stream)), None)
     return nbytes
+
+
+class SampledBatch:
+    """A batch the sampler produced, copied out of its buffers: the flat query arrays of the
+    C boundary (same attribute names as workloads.QueryBatch), negatives and template ids."""
+
+    def __init__(self, c, neg_ptr, tmpl_ptr, K, names):
+        B = int(c.n_queries)
+        take = lambda ptr, n, dt: (np.ctypeslib.as_array(C.cast(ptr, C.POINTER(dt)), shape=(n,)).copy() if n
+                                   else np.zeros(0, dt))
+        self.B = B
+        self.node_off = take(c.node_off, B + 1, C.c_int32)
+        n_nodes = int(self.node_off[-1]) if B else 0
+        self.op = take(c.op, n_nodes, C.c_uint8)
+        self.arg = take(c.arg, n_nodes, C.c_int32)
+        self.in_off = take(c.in_off, n_nodes + 1, C.c_int32)
+        self.in_idx = take(c.in_idx, int(self.in_off[-1]), C.c_int32)
+        self.pos = take(c.pos, B, C.c_int32)
+        self.negs = take(neg_ptr, B * K, C.c_int32).reshape(B, K)
+        self.names = [names[int(t)] for t in take(tmpl_ptr, B, C.c_uint8)]
+
+
+class Sampler:
+    """Online query sampler over a graph given as triple arrays (host, no device needed)."""
+
+    def __init__(self, n_entities, n_relations, head, rel, tail, templates, weights=None, seed=0, n_threads=4):
+        self.names = list(templates)
+        self._keep = [_i32(head), _i32(rel), _i32(tail)]
+        w = np.ascontiguousarray(weights, np.float32) if weights is not None else None
+        self.handle = C.c_void_p()
+        _check(lib().ngdb_sampler_create(int(n_entities), int(n_relations), int(self._keep[0].shape[0]),
+                                         self._keep[0].ctypes.data, self._keep[1].ctypes.data,
+                                         self._keep[2].ctypes.data, ",".join(self.names).encode(),
+                                         w.ctypes.data if w is not None else None, int(seed), int(n_threads),
+                                         C.byref(self.handle)), None)
+
+    def next(self, n_queries, K):
+        c = QueryBatchC()
+        neg, tmpl = C.c_void_p(), C.c_void_p()
+        rc = lib().ngdb_sampler_next(self.handle, int(n_queries), int(K), C.byref(c), C.byref(neg), C.byref(tmpl))
+        if rc != NGDB_OK:
+            raise NgdbError(rc, lib().ngdb_strerror(rc).decode() + " (" +
+                            lib().ngdb_sampler_last_error(self.handle).decode() + ")")
+        return SampledBatch(c, neg, tmpl, int(K), self.names)
+
+    def close(self):
+        if self.handle:
+            lib().ngdb_sampler_destroy(self.handle)
+            self.handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 class Engine:
