@@ -193,6 +193,9 @@ def main():
     ap.add_argument("--schedule", choices=("level", "max_fill"), default="level",
                     help="order of execution of the operators (max_fill: the ready-set loop of Alg. 1)")
     ap.add_argument("--bmax", type=int, default=0, help="largest batch of one Max-Fillness step, 0 = unbounded")
+    ap.add_argument("--sampler", type=int, default=0, metavar="THREADS",
+                    help="draw every batch (queries and negatives) inside the run with the library's online sampler "
+                         "on this many threads, instead of cycling pre-generated batches")
     ap.add_argument("--rank", type=int, default=0, metavar="Q",
                     help="time the all-entity ranking pass of Q queries instead of the training step")
     ap.add_argument("--answers", type=int, default=0, metavar="A",
@@ -240,14 +243,40 @@ def main():
     # Producer/consumer (Sec. 4.3): batch t+1 is planned on a second host thread while step t
     # is enqueued and runs; every batch of the run is planned inside the run.
     planner = ThreadPoolExecutor(1)
+    sampler = None
+    if args.sampler:
+        from paper_2602_21597_amd import Sampler
+        names = sorted(cfg.mix)
+        sampler = Sampler(cfg.N, cfg.R, kg.head, kg.rel, kg.tail, names, [cfg.mix[n] for n in names], cfg.seed,
+                          args.sampler)
+        neg_host = [torch.empty((cfg.B, cfg.K), dtype=torch.int32).pin_memory() for _ in range(2)]
+        neg_dev = [torch.empty((cfg.B, cfg.K), dtype=torch.int32, device="cuda") for _ in range(2)]
+        copied = [torch.cuda.Event() for _ in range(2)]     # upload of a pinned buffer has finished
+        for ev in copied:
+            ev.record(stream)
+
+    def produce(i):
+        """Producer side of one step: with the sampler, a fresh batch and its negatives; the plan."""
+        if sampler is None:
+            return eng.plan(batches[i % N_BATCHES]), None
+        c_batch, neg_view = sampler.next_raw(cfg.B, cfg.K)
+        copied[i % 2].synchronize()            # the upload two steps ago has left this buffer
+        neg_host[i % 2].numpy()[:] = neg_view
+        return eng.plan(c_batch), i % 2
 
     def run_steps(first, count):
-        nxt = planner.submit(eng.plan, batches[first % N_BATCHES]) if count > 0 else None
+        nxt = planner.submit(produce, first) if count > 0 else None
         for i in range(first, first + count):
-            plan = nxt.result()
+            plan, slot = nxt.result()
+            if slot is None:
+                neg = negs[i % N_BATCHES]
+            else:                      # negatives of this batch: pinned host -> device on the compute stream
+                neg_dev[slot].copy_(neg_host[slot], non_blocking=True)
+                copied[slot].record(stream)
+                neg = neg_dev[slot]
             if i + 1 < first + count:
-                nxt = planner.submit(eng.plan, batches[(i + 1) % N_BATCHES])
-            eng.train_step(plan, negs[i % N_BATCHES], stream)
+                nxt = planner.submit(produce, i + 1)
+            eng.train_step(plan, neg, stream)
             plan.free()        # the library recycles the plan's buffers once the step has finished
 
     say("warm-up")
@@ -345,7 +374,10 @@ def main():
                    "schedule": args.schedule if args.schedule == "level" else "max_fill, B_max=%s" % (args.bmax or "inf"),
                    "steps_per_batch": pexp["n_levels"], "peak_live_outputs": pexp["peak_live"],
                    "operator_outputs": pexp["n_slots"],
-                   "step": "ngdb_plan of batch t+1 on a second host thread while ngdb_train_step of batch t is enqueued",
+                   "step": ("ngdb_sampler_next + " if args.sampler else "") +
+                           "ngdb_plan of batch t+1 on a second host thread while ngdb_train_step of batch t is enqueued",
+                   "batches": "online sampler, %d threads" % args.sampler if args.sampler else
+                              "%d pre-generated batches cycled" % N_BATCHES,
                    "touched_entity_rows": touched},
         "device_only": {"queries_per_s": cfg.B * args.steps / dt_dev, "ms_per_step": 1e3 * dt_dev / args.steps,
                         "note": "same steps with plans prebuilt"},

@@ -240,6 +240,14 @@ class SampledBatch:
         self.negs = take(neg_ptr, B * K, C.c_int32).reshape(B, K)
         self.names = [names[int(t)] for t in take(tmpl_ptr, B, C.c_uint8)]
 
+    def query_nodes(self, i):
+        """Nodes of query i as a list of (op, arg, [local input indices]), root last."""
+        out = []
+        for n in range(int(self.node_off[i]), int(self.node_off[i + 1])):
+            ins = self.in_idx[int(self.in_off[n]):int(self.in_off[n + 1])]
+            out.append((int(self.op[n]), int(self.arg[n]), [int(x) for x in ins]))
+        return out
+
 
 class Sampler:
     """Online query sampler over a graph given as triple arrays (host, no device needed)."""
@@ -255,14 +263,29 @@ class Sampler:
                                          w.ctypes.data if w is not None else None, int(seed), int(n_threads),
                                          C.byref(self.handle)), None)
 
-    def next(self, n_queries, K):
+    def _next(self, n_queries, K):
         c = QueryBatchC()
         neg, tmpl = C.c_void_p(), C.c_void_p()
         rc = lib().ngdb_sampler_next(self.handle, int(n_queries), int(K), C.byref(c), C.byref(neg), C.byref(tmpl))
         if rc != NGDB_OK:
             raise NgdbError(rc, lib().ngdb_strerror(rc).decode() + " (" +
                             lib().ngdb_sampler_last_error(self.handle).decode() + ")")
+        return c, neg, tmpl
+
+    def next(self, n_queries, K):
+        """A fresh batch copied into numpy arrays (inspection, tests)."""
+        c, neg, tmpl = self._next(n_queries, K)
         return SampledBatch(c, neg, tmpl, int(K), self.names)
+
+    def next_raw(self, n_queries, K):
+        """A fresh batch left in the sampler's buffers: (the C struct, to be passed to Engine.plan
+        as it is; a numpy view [n_queries, K] of the negatives).  Both are valid until the call
+        after the next one on this sampler."""
+        c, neg, _ = self._next(n_queries, K)
+        n = int(n_queries) * int(K)
+        negs = (np.ctypeslib.as_array(C.cast(neg, C.POINTER(C.c_int32)), shape=(n,)).reshape(int(n_queries), int(K))
+                if n else np.zeros((int(n_queries), int(K)), np.int32))
+        return c, negs
 
     def close(self):
         if self.handle:
@@ -331,9 +354,12 @@ class Engine:
 
     # ---- planning / steps
     def plan(self, qb):
-        arrs = _BatchArrays(qb)
+        """qb: an object with the flat query arrays (workloads.QueryBatch, SampledBatch) or the C
+        struct a sampler filled (Sampler.next_raw)."""
+        arrs = None if isinstance(qb, QueryBatchC) else _BatchArrays(qb)    # keeps the numpy arrays alive
+        c = qb if arrs is None else arrs.c
         h = C.c_void_p()
-        _check(lib().ngdb_plan(self.ctx, C.byref(arrs.c), C.byref(h)), self.ctx)
+        _check(lib().ngdb_plan(self.ctx, C.byref(c), C.byref(h)), self.ctx)
         return Plan(h)
 
     def _stream(self, stream):

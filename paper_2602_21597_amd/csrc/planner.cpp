@@ -11,14 +11,15 @@
 #include "planner.h"
 
 #include <algorithm>
+#include <climits>
 #include <numeric>
 
 namespace ngdb {
 namespace {
 
-struct Tree {          // node of a union-free branch
-    int32_t type, arg;
-    std::vector<int32_t> kids;
+struct Tree {          // node of a union-free branch (no heap: at most NGDB_MAX_CARD inputs)
+    int32_t type, arg, n_kids;
+    int32_t kids[NGDB_MAX_CARD];
 };
 
 struct Expander {
@@ -29,69 +30,74 @@ struct Expander {
     std::string& err;
     int code = NGDB_OK;
 
-    int32_t make(int32_t type, int32_t arg, std::vector<int32_t> kids) {
-        pool.push_back(Tree{type, arg, std::move(kids)});
+    int32_t make(int32_t type, int32_t arg, const int32_t* kids, int32_t n_kids) {
+        Tree t;
+        t.type = type; t.arg = arg; t.n_kids = n_kids;
+        for (int32_t k = 0; k < n_kids; ++k) t.kids[k] = kids[k];
+        pool.push_back(t);
         return (int32_t)pool.size() - 1;
     }
 
-    // Conjunctive branches of the sub-query rooted at local node j.
-    std::vector<int32_t> expand(int32_t j, int depth) {
-        std::vector<int32_t> out;
-        if (code != NGDB_OK) return out;
+    // Appends the conjunctive branches of the sub-query rooted at local node j to `out`.
+    void expand(int32_t j, int depth, std::vector<int32_t>& out) {
+        if (code != NGDB_OK) return;
         if (depth > NGDB_MAX_LEVELS + 1) {
             code = NGDB_ERR_UNSUPPORTED;
             err = "query deeper than NGDB_MAX_LEVELS";
-            return out;
+            return;
         }
         const int32_t n = base + j;
         const int32_t lo = qb.in_off[n], hi = qb.in_off[n + 1];
         const int op = qb.op[n];
+        const size_t first = out.size();
         switch (op) {
             case NGDB_OP_ANCHOR:
-                out.push_back(make(NGDB_OP_ANCHOR, qb.arg[n], {}));
+                out.push_back(make(NGDB_OP_ANCHOR, qb.arg[n], nullptr, 0));
                 break;
             case NGDB_OP_PROJ: {
-                for (int32_t b : expand(qb.in_idx[lo], depth + 1))
-                    out.push_back(make(NGDB_OP_PROJ, qb.arg[n], {b}));
+                expand(qb.in_idx[lo], depth + 1, out);          // one projection on top of every branch of the input
+                for (size_t i = first; i < out.size() && code == NGDB_OK; ++i) {
+                    const int32_t kid = out[i];
+                    out[i] = make(NGDB_OP_PROJ, qb.arg[n], &kid, 1);
+                }
                 break;
             }
             case NGDB_OP_UNION: {
-                for (int32_t k = lo; k < hi; ++k) {
-                    std::vector<int32_t> sub = expand(qb.in_idx[k], depth + 1);
-                    out.insert(out.end(), sub.begin(), sub.end());
-                }
+                for (int32_t k = lo; k < hi; ++k) expand(qb.in_idx[k], depth + 1, out);
                 break;
             }
             default: {   // INTER, NEG: every input must be union-free
-                std::vector<int32_t> kids;
+                int32_t kids[NGDB_MAX_CARD];
+                int32_t n_kids = 0;
                 for (int32_t k = lo; k < hi; ++k) {
-                    std::vector<int32_t> sub = expand(qb.in_idx[k], depth + 1);
-                    if (code != NGDB_OK) return out;
-                    if (sub.size() != 1) {
+                    const size_t before = out.size();
+                    expand(qb.in_idx[k], depth + 1, out);
+                    if (code != NGDB_OK) return;
+                    if (out.size() != before + 1) {
                         code = NGDB_ERR_UNSUPPORTED;
                         err = "union below an intersection or a negation";
-                        return out;
+                        return;
                     }
-                    kids.push_back(sub[0]);
+                    kids[n_kids++] = out.back();                // validate() bounds the input count
+                    out.pop_back();
                 }
-                out.push_back(make(op, 0, std::move(kids)));
+                out.push_back(make(op, 0, kids, n_kids));
             }
         }
-        if ((int)out.size() > NGDB_MAX_BRANCH && code == NGDB_OK) {
+        if (out.size() - first > (size_t)NGDB_MAX_BRANCH && code == NGDB_OK) {
             code = NGDB_ERR_UNSUPPORTED;
             err = "query has more than NGDB_MAX_BRANCH conjunctive branches";
         }
-        return out;
     }
 };
 
 struct Flat {   // all nodes of the batch after DNF, by global id
     std::vector<int32_t> type, arg, level, in_off, in;
-    int32_t add(int32_t t, int32_t a, int32_t lvl, const std::vector<int32_t>& ins) {
+    int32_t add(int32_t t, int32_t a, int32_t lvl, const int32_t* ins, int32_t n_ins) {
         type.push_back(t);
         arg.push_back(a);
         level.push_back(lvl);
-        in.insert(in.end(), ins.begin(), ins.end());
+        in.insert(in.end(), ins, ins + n_ins);
         in_off.push_back((int32_t)in.size());
         return (int32_t)type.size() - 1;
     }
@@ -100,14 +106,13 @@ struct Flat {   // all nodes of the batch after DNF, by global id
 
 int32_t number_postorder(const std::vector<Tree>& pool, int32_t t, Flat& flat) {
     const Tree& node = pool[t];
-    std::vector<int32_t> ins;
+    int32_t ins[NGDB_MAX_CARD];
     int32_t lvl = 0;
-    for (int32_t k : node.kids) {
-        int32_t g = number_postorder(pool, k, flat);
-        ins.push_back(g);
-        lvl = std::max(lvl, flat.level[g] + 1);
+    for (int32_t k = 0; k < node.n_kids; ++k) {
+        ins[k] = number_postorder(pool, node.kids[k], flat);
+        lvl = std::max(lvl, flat.level[ins[k]] + 1);
     }
-    return flat.add(node.type, node.arg, lvl, ins);
+    return flat.add(node.type, node.arg, lvl, ins, node.n_kids);
 }
 
 // Max-Fillness schedule (Alg. 1 without the gradient nodes, which mirror it): returns the step
@@ -218,14 +223,27 @@ int validate(const ngdb_query_batch& qb, int32_t N, int32_t R, std::string& err)
     return NGDB_OK;
 }
 
+// order = positions 0..n-1 sorted stably by key[position], keys in [0, key_bound): a counting
+// sort where the key range allows it (the keys here are small composites), else a merge sort.
+void stable_order_by_key(const std::vector<int32_t>& key, int64_t key_bound, std::vector<int32_t>& order) {
+    const size_t n = key.size();
+    order.resize(n);
+    if (key_bound <= (int64_t)(4 * n + 1024)) {
+        std::vector<int32_t> start((size_t)key_bound + 1, 0);
+        for (size_t i = 0; i < n; ++i) ++start[key[i] + 1];
+        for (int64_t k = 0; k < key_bound; ++k) start[k + 1] += start[k];
+        for (size_t i = 0; i < n; ++i) order[start[key[i]]++] = (int32_t)i;
+        return;
+    }
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return key[a] < key[b]; });
+}
+
 // Stable grouping of `keys` (values < n_keys): unique keys ascending, segment
 // offsets, and the permutation that lists each segment's members in input order.
-void segment_index(const std::vector<int32_t>& keys, std::vector<int32_t>& uniq,
+void segment_index(const std::vector<int32_t>& keys, int32_t n_keys, std::vector<int32_t>& uniq,
                    std::vector<int32_t>& seg_off, std::vector<int32_t>& order) {
-    order.resize(keys.size());
-    std::iota(order.begin(), order.end(), 0);
-    std::stable_sort(order.begin(), order.end(),
-                     [&](int32_t a, int32_t b) { return keys[a] < keys[b]; });
+    stable_order_by_key(keys, n_keys, order);
     uniq.clear();
     seg_off.clear();
     for (size_t i = 0; i < order.size(); ++i)
@@ -256,10 +274,12 @@ int build_plan(const ngdb_query_batch& qb, int32_t N, int32_t R, int32_t schedul
     flat.in_off.push_back(0);
     std::vector<std::vector<int32_t>> roots(B);
     std::vector<Tree> pool;
+    std::vector<int32_t> branches;
     for (int32_t q = 0; q < B; ++q) {
         pool.clear();
         Expander ex{qb, qb.node_off[q], qb.node_off[q + 1] - qb.node_off[q], pool, err};
-        std::vector<int32_t> branches = ex.expand(ex.n_local - 1, 0);
+        branches.clear();
+        ex.expand(ex.n_local - 1, 0, branches);
         if (ex.code != NGDB_OK) return ex.code;
         for (int32_t b : branches) {
             if (pool[b].type == NGDB_OP_ANCHOR) {
@@ -317,13 +337,19 @@ int build_plan(const ngdb_query_batch& qb, int32_t N, int32_t R, int32_t schedul
 
     // 3. slots: type-major, then level, input count, node id
     auto type_rank = [](int32_t t) { return t == NGDB_OP_PROJ ? 0 : (t == NGDB_OP_INTER ? 1 : 2); };
-    std::vector<int32_t> by_slot = ops;
-    std::stable_sort(by_slot.begin(), by_slot.end(), [&](int32_t a, int32_t b) {
-        const int ta = type_rank(flat.type[a]), tb = type_rank(flat.type[b]);
-        if (ta != tb) return ta < tb;
-        if (flat.level[a] != flat.level[b]) return flat.level[a] < flat.level[b];
-        return flat.nin(a) < flat.nin(b);
-    });
+    int32_t top_level = 0;
+    for (int32_t g : ops) top_level = std::max(top_level, flat.level[g]);
+    const int64_t n_lvl = (int64_t)top_level + 1, n_card = NGDB_MAX_CARD + 1;
+    std::vector<int32_t> key(ops.size()), order;
+    std::vector<int32_t> by_slot(ops.size());
+    if (3 * n_lvl * n_card > INT32_MAX) {
+        err = "too many execution steps";
+        return NGDB_ERR_UNSUPPORTED;
+    }
+    for (size_t i = 0; i < ops.size(); ++i)
+        key[i] = (int32_t)((type_rank(flat.type[ops[i]]) * n_lvl + flat.level[ops[i]]) * n_card + flat.nin(ops[i]));
+    stable_order_by_key(key, 3 * n_lvl * n_card, order);
+    for (size_t i = 0; i < ops.size(); ++i) by_slot[i] = ops[order[i]];
     std::vector<int32_t> slot(n_nodes, -1);
     for (int32_t s = 0; s < P.n_slots; ++s) {
         slot[by_slot[s]] = s;
@@ -336,13 +362,11 @@ int build_plan(const ngdb_query_batch& qb, int32_t N, int32_t R, int32_t schedul
     auto grad_row = [&](int32_t g) { return slot[g] >= 0 ? slot[g] : P.n_slots + anchor_idx[g]; };
 
     // 4. groups: level, type, input count; members in node order
-    std::vector<int32_t> by_group = ops;
-    std::stable_sort(by_group.begin(), by_group.end(), [&](int32_t a, int32_t b) {
-        if (flat.level[a] != flat.level[b]) return flat.level[a] < flat.level[b];
-        const int ta = type_rank(flat.type[a]), tb = type_rank(flat.type[b]);
-        if (ta != tb) return ta < tb;
-        return flat.nin(a) < flat.nin(b);
-    });
+    std::vector<int32_t> by_group(ops.size());
+    for (size_t i = 0; i < ops.size(); ++i)
+        key[i] = (int32_t)((flat.level[ops[i]] * 3 + type_rank(flat.type[ops[i]])) * n_card + flat.nin(ops[i]));
+    stable_order_by_key(key, 3 * n_lvl * n_card, order);
+    for (size_t i = 0; i < ops.size(); ++i) by_group[i] = ops[order[i]];
     size_t i = 0;
     while (i < by_group.size()) {
         const int32_t g0 = by_group[i];
@@ -389,13 +413,13 @@ int build_plan(const ngdb_query_batch& qb, int32_t N, int32_t R, int32_t schedul
     P.n_roots = (int32_t)P.root_slot.size();
 
     // 6. relation gradient index over the projections in slot order
-    std::vector<int32_t> rkeys(P.n_proj), rsrc(P.n_proj), order;
+    std::vector<int32_t> rkeys(P.n_proj), rsrc(P.n_proj);
     for (int32_t s = 0; s < P.n_proj; ++s) {
         const int32_t g = by_slot[s];
         rkeys[s] = flat.arg[g];
         rsrc[s] = grad_row(flat.in[flat.in_off[g]]);
     }
-    segment_index(rkeys, P.r_uniq, P.r_seg_off, order);
+    segment_index(rkeys, R, P.r_uniq, P.r_seg_off, order);
     P.r_src.resize(P.n_proj);
     for (int32_t s = 0; s < P.n_proj; ++s) P.r_src[s] = rsrc[order[s]];
     return NGDB_OK;

@@ -12,9 +12,13 @@
 // from its own counter-based random stream (seed, batch number, query number),
 // so a batch does not depend on the number of threads.
 #include <algorithm>
+#include <condition_variable>
 #include <cstring>
+#include <functional>
+#include <mutex>
 #include <new>
 #include <numeric>
+#include <memory>
 #include <string>
 #include <thread>
 #include <vector>
@@ -46,6 +50,80 @@ struct Rng {   // splitmix64 over a per-query counter
         }
     }
     double unit() { return (double)(next() >> 11) * (1.0 / 9007199254740992.0); }
+    // two uniform draws in [0, n), n < 2^31, from one 64-bit word (each half: multiply-shift,
+    // redrawn together if either falls into the biased tail)
+    void below32x2(uint32_t n, int32_t* out) {
+        const uint32_t tail = (uint32_t)(-n) % n;
+        for (;;) {
+            const uint64_t x = next();
+            const uint64_t a = (uint64_t)(uint32_t)x * n, b = (x >> 32) * n;
+            if ((uint32_t)a >= tail && (uint32_t)b >= tail) {
+                out[0] = (int32_t)(a >> 32);
+                out[1] = (int32_t)(b >> 32);
+                return;
+            }
+        }
+    }
+};
+
+// Worker threads that live as long as the sampler: a call hands them a function of the
+// worker number and waits for all of them.
+class Workers {
+public:
+    explicit Workers(int n) {
+        for (int i = 0; i < n; ++i) threads_.emplace_back([this, i] { loop(i); });
+    }
+    ~Workers() {
+        {
+            std::lock_guard<std::mutex> lk(mu_);
+            stop_ = true;
+            ++round_;
+        }
+        cv_.notify_all();
+        for (std::thread& t : threads_) t.join();
+    }
+    int size() const { return (int)threads_.size(); }
+    // fn must stay alive until wait() has returned
+    void start(const std::function<void(int)>& fn) {
+        {
+            std::lock_guard<std::mutex> lk(mu_);
+            fn_ = &fn;
+            pending_ = (int)threads_.size();
+            ++round_;
+        }
+        cv_.notify_all();
+    }
+    void wait() {
+        std::unique_lock<std::mutex> lk(mu_);
+        done_.wait(lk, [this] { return pending_ == 0; });
+    }
+
+private:
+    void loop(int i) {
+        uint64_t seen = 0;
+        for (;;) {
+            const std::function<void(int)>* fn;
+            {
+                std::unique_lock<std::mutex> lk(mu_);
+                cv_.wait(lk, [&] { return round_ != seen; });
+                seen = round_;
+                if (stop_) return;
+                fn = fn_;
+            }
+            (*fn)(i);
+            {
+                std::lock_guard<std::mutex> lk(mu_);
+                if (--pending_ == 0) done_.notify_one();
+            }
+        }
+    }
+    std::vector<std::thread> threads_;
+    std::mutex mu_;
+    std::condition_variable cv_, done_;
+    const std::function<void(int)>* fn_ = nullptr;
+    uint64_t round_ = 0;
+    int pending_ = 0;
+    bool stop_ = false;
 };
 
 // ---------------------------------------------------------------- graph
@@ -237,15 +315,20 @@ struct Builder {
 
 }  // namespace
 
+struct BatchArrays {   // what ngdb_sampler_next hands out
+    std::vector<int32_t> node_off, arg, in_off, in_idx, pos, neg;
+    std::vector<uint8_t> op, tmpl;
+};
+
 struct ngdb_sampler_s {
     Graph g;
     std::vector<Template> templates;
     std::vector<double> cdf;
     uint64_t seed = 0, batch_no = 0;
     int n_threads = 1;
-    // the last batch (the arrays ngdb_sampler_next hands out)
-    std::vector<int32_t> node_off, arg, in_off, in_idx, pos, neg;
-    std::vector<uint8_t> op, tmpl;
+    std::unique_ptr<Workers> workers;   // n_threads - 1 helpers; the caller's thread works too
+    std::vector<Query> queries;         // per query scratch, reused
+    BatchArrays out[2];                 // two sets taking turns: a batch stays valid over the next call
     std::string err;
 };
 
@@ -317,6 +400,12 @@ int ngdb_sampler_create(int32_t N, int32_t R, int64_t T, const int32_t* head, co
     }
     s->seed = seed;
     s->n_threads = n_threads;
+    try {
+        if (n_threads > 1) s->workers.reset(new Workers(n_threads - 1));
+    } catch (...) {
+        delete s;
+        return NGDB_ERR_OOM;
+    }
     *out = s;
     return NGDB_OK;
 }
@@ -327,22 +416,25 @@ int ngdb_sampler_next(ngdb_sampler_t* s, int32_t B, int32_t K, ngdb_query_batch*
                       const uint8_t** template_id) {
     if (!s || !batch || B < 0 || K < 0 || (K > 0 && !neg)) return NGDB_ERR_ARG;
     const uint64_t batch_no = s->batch_no++;
-    std::vector<Query> queries((size_t)B);
-    std::vector<int> failed((size_t)B, 0);
+    BatchArrays& o = s->out[batch_no & 1];
+    std::vector<int> failed;
     try {
-        s->pos.assign((size_t)B, 0);
-        s->tmpl.assign((size_t)B, 0);
-        s->neg.resize((size_t)B * K);
+        if ((int)s->queries.size() < B) s->queries.resize((size_t)B);
+        failed.assign((size_t)B, 0);
+        o.pos.assign((size_t)B, 0);
+        o.tmpl.assign((size_t)B, 0);
+        o.neg.resize((size_t)B * K);
     } catch (const std::bad_alloc&) {
         return NGDB_ERR_OOM;
     }
+    std::vector<Query>& queries = s->queries;
     auto work = [&](int lo, int hi) {
         for (int i = lo; i < hi; ++i) {
             Rng rng(s->seed, batch_no, (uint64_t)i);
             const double u = rng.unit();
             size_t t = 0;
             while (t + 1 < s->cdf.size() && u >= s->cdf[t]) ++t;
-            s->tmpl[i] = (uint8_t)t;
+            o.tmpl[i] = (uint8_t)t;
             const Template& tp = s->templates[t];
             Query& q = queries[i];
             bool ok = false;
@@ -353,48 +445,65 @@ int ngdb_sampler_next(ngdb_sampler_t* s, int32_t B, int32_t K, ngdb_query_batch*
                 if (b.grow((int)tp.nodes.size() - 1, v) < 0) continue;
                 b.budget = 20000;
                 if (b.contains((int)q.op.size() - 1, v) != 1) continue;   // e.g. the end point lies in a negated branch
-                s->pos[i] = v;
+                o.pos[i] = v;
                 ok = true;
             }
             failed[i] = !ok;
-            for (int k = 0; k < K; ++k) s->neg[(size_t)i * K + k] = (int32_t)rng.below((uint64_t)s->g.N);
+            int32_t* nrow = o.neg.data() + (size_t)i * K;
+            int k = 0;
+            for (; k + 2 <= K; k += 2) rng.below32x2((uint32_t)s->g.N, nrow + k);
+            if (k < K) nrow[k] = (int32_t)rng.below((uint64_t)s->g.N);
         }
     };
-    const int nt = std::max(1, std::min(s->n_threads, B / 64 + 1));
-    if (nt == 1) {
+    const int parts = s->workers ? std::max(1, std::min(s->workers->size() + 1, B / 32 + 1)) : 1;
+    if (parts == 1) {
         work(0, B);
     } else {
-        std::vector<std::thread> pool;
-        for (int t = 0; t < nt; ++t) pool.emplace_back(work, (int)((int64_t)B * t / nt), (int)((int64_t)B * (t + 1) / nt));
-        for (std::thread& th : pool) th.join();
+        const std::function<void(int)> fn = [&](int w) {      // helper w takes part w + 1
+            if (w + 1 < parts) work((int)((int64_t)B * (w + 1) / parts), (int)((int64_t)B * (w + 2) / parts));
+        };
+        // the helpers run their parts while this thread does part 0
+        s->workers->start(fn);
+        bool oom = false;
+        try {
+            work(0, (int)((int64_t)B / parts));
+        } catch (const std::bad_alloc&) {
+            oom = true;
+        }
+        s->workers->wait();
+        if (oom) return NGDB_ERR_OOM;
     }
     for (int i = 0; i < B; ++i)
         if (failed[i]) {
-            s->err = "query instantiation kept failing for template " + s->templates[s->tmpl[i]].name;
+            s->err = "query instantiation kept failing for template " + s->templates[o.tmpl[i]].name;
             return NGDB_ERR_UNSUPPORTED;
         }
     // concatenate
-    s->node_off.assign(1, 0);
-    s->op.clear(); s->arg.clear(); s->in_idx.clear();
-    s->in_off.assign(1, 0);
-    for (int i = 0; i < B; ++i) {
-        const Query& q = queries[i];
-        s->op.insert(s->op.end(), q.op.begin(), q.op.end());
-        s->arg.insert(s->arg.end(), q.arg.begin(), q.arg.end());
-        const int32_t base = (int32_t)s->in_idx.size();
-        s->in_idx.insert(s->in_idx.end(), q.in_idx.begin(), q.in_idx.end());
-        for (size_t n = 1; n < q.in_off.size(); ++n) s->in_off.push_back(base + q.in_off[n]);
-        s->node_off.push_back((int32_t)s->op.size());
+    try {
+        o.node_off.assign(1, 0);
+        o.op.clear(); o.arg.clear(); o.in_idx.clear();
+        o.in_off.assign(1, 0);
+        for (int i = 0; i < B; ++i) {
+            const Query& q = queries[i];
+            o.op.insert(o.op.end(), q.op.begin(), q.op.end());
+            o.arg.insert(o.arg.end(), q.arg.begin(), q.arg.end());
+            const int32_t base = (int32_t)o.in_idx.size();
+            o.in_idx.insert(o.in_idx.end(), q.in_idx.begin(), q.in_idx.end());
+            for (size_t n = 1; n < q.in_off.size(); ++n) o.in_off.push_back(base + q.in_off[n]);
+            o.node_off.push_back((int32_t)o.op.size());
+        }
+    } catch (const std::bad_alloc&) {
+        return NGDB_ERR_OOM;
     }
     batch->n_queries = B;
-    batch->node_off = s->node_off.data();
-    batch->op = s->op.data();
-    batch->arg = s->arg.data();
-    batch->in_off = s->in_off.data();
-    batch->in_idx = s->in_idx.data();
-    batch->pos = s->pos.data();
-    if (neg) *neg = s->neg.data();
-    if (template_id) *template_id = s->tmpl.data();
+    batch->node_off = o.node_off.data();
+    batch->op = o.op.data();
+    batch->arg = o.arg.data();
+    batch->in_off = o.in_off.data();
+    batch->in_idx = o.in_idx.data();
+    batch->pos = o.pos.data();
+    if (neg) *neg = o.neg.data();
+    if (template_id) *template_id = o.tmpl.data();
     return NGDB_OK;
 }
 

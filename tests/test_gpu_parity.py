@@ -7,6 +7,7 @@ import pytest
 
 import workloads as wl
 from oracle import model as om
+from oracle import plan as oplan
 from oracle import rank as orank
 from tests import parity as par
 
@@ -302,6 +303,33 @@ def test_planning_on_a_second_thread_gives_the_same_parameters():
     for k in a:
         assert np.array_equal(a[k], b[k]), k
     assert threaded.step_count() == 12
+
+
+def test_sampled_batches_train_like_any_other():
+    _say("online sampler -> plan -> forward_backward: plan, scores and loss against the oracle on 3 sampled batches")
+    import torch
+    from paper_2602_21597_amd import Sampler
+    c = wl.get_config(0)
+    kg = wl.make_kg(c.N, c.R, c.T, c.alpha, c.seed)
+    params = wl.make_params(c.N, c.R, c.d, c.h, 3)
+    from paper_2602_21597_amd import Engine
+    eng = Engine(c.N, c.R, c.d, c.h, c.gamma)
+    eng.bind_numpy(params)
+    M = om.Model(params, c.gamma)
+    smp = Sampler(c.N, c.R, kg.head, kg.rel, kg.tail, list(wl.configs.ALL14), None, 7, 4)
+    for _ in range(3):
+        b = smp.next(96, 6)
+        plan = eng.plan(b)
+        ref_plan = oplan.build_plan(b)
+        got_plan = plan.export()
+        for k in ref_plan:
+            assert np.array_equal(np.asarray(got_plan[k]), np.asarray(ref_plan[k])), "plan." + k
+        loss = eng.forward_backward(plan, torch.from_numpy(b.negs).cuda())
+        torch.cuda.synchronize()
+        ref_loss, _, ref_scores = om.batch_loss_and_grads(b, b.negs, M, want_grads=False)
+        par.assert_close(eng.grads()["pair_score"].reshape(b.B, 7), np.stack(ref_scores), "scores")
+        assert abs(float(loss.cpu()[0]) - ref_loss) <= 1e-4 * abs(ref_loss)
+        plan.free()
 
 
 def test_errors_are_reported_not_raised_as_faults():
