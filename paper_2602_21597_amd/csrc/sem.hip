@@ -360,7 +360,9 @@ hipError_t launch_sem_fuse(const SemFuseArgs& a, hipStream_t s) {
 int sem_wgrad_splits(int64_t n_rows_bound, int d, int ds) {
     const int tiles = ((d + TN - 1) / TN) * ((ds + WG_SEM - 1) / WG_SEM);
     const int64_t stages = (n_rows_bound + KS - 1) / KS;
-    const int cap = std::max(8, (768 / tiles) / 8 * 8);     // about one resident workgroup set of the chip
+    // one resident set of workgroups, no second round: 2 workgroups of this kernel fit a compute
+    // unit (224 VGPRs), 256 units
+    const int cap = std::max(8, (512 / tiles) / 8 * 8);
     return (int)std::max<int64_t>(1, std::min<int64_t>(stages / 4, cap));
 }
 
