@@ -343,3 +343,26 @@ def test_errors_are_reported_not_raised_as_faults():
     with pytest.raises(NgdbError) as e:
         eng.train_step(host_plan, case.neg_dev())
     assert e.value.code == binding.ERR_ARG
+    # ranking calls: a plan without a device, top-k out of range, answer lists without output
+    import ctypes as C
+    import torch
+    L = binding.lib()
+    plan = eng.plan(case.qb)
+    ids = torch.empty((case.B, 4), dtype=torch.int32, device="cuda")
+    dist = torch.empty((case.B, 4), dtype=torch.float32, device="cuda")
+    assert L.ngdb_score(eng.ctx, plan.handle, None, 0, 0, None, ids.data_ptr(), dist.data_ptr(), None) == binding.ERR_ARG
+    assert L.ngdb_score(eng.ctx, plan.handle, None, 0, 17, None, ids.data_ptr(), dist.data_ptr(), None) == binding.ERR_ARG
+    assert L.ngdb_score(eng.ctx, host_plan.handle, None, 0, 4, None, ids.data_ptr(), dist.data_ptr(), None) == binding.ERR_ARG
+    off = torch.zeros(case.B + 1, dtype=torch.int32, device="cuda")
+    assert L.ngdb_rank_answers(eng.ctx, plan.handle, off.data_ptr(), None, 3, None, None, None) == binding.ERR_ARG
+    assert L.ngdb_rank_answers(eng.ctx, plan.handle, None, None, 0, None, None, None) == binding.ERR_ARG
+    assert L.ngdb_rank_answers(eng.ctx, plan.handle, off.data_ptr(), None, 0, None, None, None) == binding.NGDB_OK
+    assert L.ngdb_rank_metrics(None, None, None, 0, None, None) == binding.ERR_ARG
+    fresh = binding.Engine(case.N, case.R, case.d, case.h, case.gamma)        # nothing bound yet
+    p2 = fresh.plan(case.qb)
+    with pytest.raises(NgdbError) as e:
+        fresh.train_step(p2, case.neg_dev())
+    assert e.value.code == binding.ERR_STATE
+    with pytest.raises(NgdbError) as e:
+        binding.Engine(case.N, case.R, case.d, case.h, case.gamma, schedule=7)
+    assert e.value.code == binding.ERR_ARG
