@@ -1,7 +1,10 @@
 """The synthetic input generators: determinism, shapes, structure."""
+import os
+
 import numpy as np
 
 import workloads as wl
+from oracle import plan as oplan
 from workloads.queries import OP_ANCHOR, OP_PROJ
 
 
@@ -58,3 +61,42 @@ def test_config_table():
     assert (c.N, c.R, c.d, c.h, c.K, c.B, c.gamma) == (15000, 474, 400, 800, 128, 512, 24.0)
     assert abs(sum(wl.get_config(3).mix.values()) - 1.0) < 1e-12
     assert wl.get_config("tiny").B == 64 and wl.get_config(4).d_sem == 1024
+
+
+def _golden(name):
+    path = os.path.join(os.path.dirname(__file__), "golden", name)
+    with open(path) as f:
+        return [ln.split() for ln in f if ln.strip() and not ln.startswith("#")]
+
+
+def test_pattern_names_are_the_papers_fourteen():
+    """The pattern list of the preliminaries: the workload mix, the hand-written operator
+    census of the planner tests and the structure of every template (one projection per
+    'p' counted with its multiplier, and so on) all refer to exactly these names."""
+    from tests.test_plan_oracle import CENSUS
+    names = [row[0] for row in _golden("query_patterns.txt")]
+    assert len(names) == 14 and len(set(names)) == 14
+    assert set(names) == set(wl.configs.ALL14) == set(CENSUS) == set(wl.configs.TEMPLATES)
+    for c in (1, 2, 3, 4):
+        assert set(wl.get_config(c).mix) == set(names)
+    # what the name itself says about the operators of the pattern
+    for name in names:
+        _, _, groups = CENSUS[name]
+        has = {t for (_, t, _) in groups}
+        assert (oplan.OP_NEG in has) == ("n" in name), name
+        assert (oplan.OP_INTER in has) == ("i" in name), name
+        assert oplan.OP_PROJ in has, name
+        roots = CENSUS[name][1]
+        assert (roots > 1) == ("u" in name), name
+
+
+def test_workload_sizes_follow_the_papers_graph_table():
+    """Entity, relation and edge counts of the synthetic graphs stay within 4 % of the
+    appendix table (relations doubled: one inverse each)."""
+    rows = {r[0]: tuple(int(x) for x in r[1:]) for r in _golden("kg_statistics.txt")}
+    for cfg, key in ((1, "FB15k-237"), (2, "NELL995"), (3, "ogbl-wikikg2")):
+        c = wl.get_config(cfg)
+        n, r, t = rows[key]
+        assert abs(c.N - n) <= 0.04 * n, (key, c.N, n)
+        assert c.R == 2 * r, (key, c.R, r)
+        assert abs(c.T - t) <= 0.04 * t, (key, c.T, t)
