@@ -37,6 +37,8 @@ TEMPLATES: Dict[str, tuple] = {
 
 ALL14 = ("1p", "2p", "3p", "2i", "3i", "ip", "pi", "2u", "up",
          "2in", "3in", "inp", "pin", "pni")
+# the union/intersection/projection patterns (no negation): what the box family can express
+EPFO9 = ("1p", "2p", "3p", "2i", "3i", "ip", "pi", "2u", "up")
 
 
 def _uniform(names):

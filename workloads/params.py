@@ -30,6 +30,25 @@ def make_params(N, R, d, h, seed, d_sem=0, scale=0.1):
     return out
 
 
+BOX_PARAM_NAMES = ("E", "R", "Ro", "V1", "c1", "V2", "c2", "U1", "u1", "U2", "u2")
+
+
+def make_box_params(N, R, d, h, seed, scale=0.1):
+    """Tensors of the box family: E and R (centres), Ro (relation offsets), the offset MLP
+    V1 c1 V2 c2 and the centre-attention MLP U1 u1 U2 u2.  Everything U(-scale, scale) except
+    Ro, which is U(-scale/4, scale) so that most, not all, of its entries are positive."""
+    rng = np.random.default_rng(seed)
+    shapes = {"E": (N, d), "R": (R, d), "Ro": (R, d)}
+    for a, b, c, e in (("V1", "c1", "V2", "c2"), ("U1", "u1", "U2", "u2")):
+        shapes.update({a: (h, d), b: (h,), c: (d, h), e: (d,)})
+    out = {}
+    for name in BOX_PARAM_NAMES:
+        u = rng.random(shapes[name], np.float32)
+        lo = -scale / 4 if name == "Ro" else -scale
+        out[name] = (lo + u * (scale - lo)).astype(np.float32)
+    return out
+
+
 def make_sem_features(N, d_sem, seed, chunk=1 << 16):
     """[N, d_sem] frozen features: N(0,1) rows, L2-normalised, rounded to bf16.
 
