@@ -31,6 +31,24 @@
  *                 a table row is updated only in steps in which it received a
  *                 gradient contribution; the bias correction uses the global step.
  *
+ * Second operator family (cfg.family = NGDB_FAMILY_BOX): box embeddings, one of the
+ * backbones the paper trains on the framework (Sec. 5.1 "Backbone models", Q2B); the
+ * decomposition, scheduling, objective and optimiser are the ones above, the operators are
+ *   state         a box (c, o), centre and non-negative offset, both of width d
+ *   anchor        (E[e], 0)
+ *   projection    (c + R[r], o + relu(Ro[r]))                  no MLP
+ *   intersection  centre: as above (U1 u1 U2 u2 on the centres);
+ *                 offset: o = min_k o_k * sigmoid(mean_k (V2 relu(V1 o_k + c1) + c2))
+ *   negation      not available: ngdb_plan returns NGDB_ERR_UNSUPPORTED
+ *   score         s(q,e) = gamma - min_b [ ||relu(|E[e]-c_b| - o_b)||_1
+ *                                          + box_alpha * ||min(|E[e]-c_b|, o_b)||_1 ]
+ *                 (a coordinate with |e-c| == o counts as inside)
+ *   tensors       E, R, Ro [n_relations, d] (row-sparse Adam), V1 c1 V2 c2, U1 u1 U2 u2;
+ *                 W1 b1 W2 b2, Wp and H_sem are not read.  An intersection input must be
+ *                 an operator output (true of every pattern of Sec. 3.1).
+ *   not available in this family: text features (d_sem must be 0), the all-entity mode
+ *                 of ngdb_score and ngdb_rank_answers (NGDB_ERR_UNSUPPORTED).
+ *
  * Conventions
  *   - Every call returns 0 (NGDB_OK) or a negative error code; nothing throws
  *     or aborts across the boundary.  ngdb_last_error() gives the text.
@@ -91,6 +109,10 @@ extern "C" {
 #define NGDB_SCHED_LEVEL    0
 #define NGDB_SCHED_MAX_FILL 1
 
+/* Operator family: VEC = the vector model above, BOX = box embeddings. */
+#define NGDB_FAMILY_VEC 0
+#define NGDB_FAMILY_BOX 1
+
 typedef struct ngdb_ctx_s ngdb_ctx_t;     /* opaque: configuration, workspace, streams */
 typedef struct ngdb_plan_s ngdb_plan_t;   /* opaque: one planned batch                 */
 
@@ -109,6 +131,8 @@ typedef struct ngdb_config {
     float lr, beta1, beta2, eps;
     int32_t schedule;      /* NGDB_SCHED_* used by ngdb_plan                          */
     int32_t b_max;         /* largest batch of one Max-Fillness step, 0 = unbounded   */
+    int32_t family;        /* NGDB_FAMILY_*                                           */
+    float box_alpha;       /* weight of the inside distance (box family), >= 0        */
 } ngdb_config;
 
 /* A trainable tensor with its Adam moments (all device, fp32, same shape). */
@@ -128,6 +152,7 @@ typedef struct ngdb_params {
     const uint16_t* H_sem;          /* device [n_entities, d_sem] bf16 bit patterns,
                                        frozen (Sec. 4.4, GPU-resident semantic cache) */
     int64_t step;                   /* optimiser steps already applied to this state */
+    ngdb_tensor Ro;                 /* [n_relations, d] relation offsets (box family only) */
 } ngdb_params;
 
 /* A batch of queries, host memory.  Query i owns nodes node_off[i]..node_off[i+1]-1;
@@ -206,6 +231,10 @@ typedef struct ngdb_grad_view {
     int32_t n_grad_rows;        /* n_slots + n_anchor                            */
     const float* pair_score;    /* [n_pairs] s(q_i, cand), pair = i*(K+1)+c, c=0 positive */
     const float* loss_terms;    /* [n_queries] per-query loss before the 1/(2B)  */
+    /* box family only (NULL otherwise): */
+    const float* gRo;           /* [n_r_uniq, d]   (forward_backward only)       */
+    const float* off;           /* [n_slots, d] box offsets by slot (act holds the centres) */
+    const float* doff;          /* [n_slots + n_anchor, d] dL/d(offset) by slot  */
 } ngdb_grad_view;
 
 /* Create a context (allocates streams and a small workspace).  cfg: host. */

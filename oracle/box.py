@@ -87,6 +87,26 @@ def forward(tree, M):
     raise Unsupported("forward() takes conjunctive trees; split unions with dnf()")
 
 
+def kink_margins(tape):
+    """(smallest |pre-activation| of any hidden unit, smallest non-zero gap between the smallest
+    and the second smallest input offset of an intersection) met while evaluating a tree: the
+    distance of the evaluation from a ReLU kink and from a change of the arg-min."""
+    kind = tape[0]
+    if kind == "e":
+        return np.inf, np.inf
+    if kind == "p":
+        return kink_margins(tape[2])
+    _, txs, ctapes, otapes, C, Wt, gate, arg, omin = tape
+    pre = min(float(np.abs(t[1]).min()) for t in ctapes + otapes)
+    O = np.stack([t[0] for t in otapes])                # the inputs' offsets
+    gaps = np.sort(O, axis=0)[1] - omin
+    gap = float(gaps[gaps > 0].min()) if (gaps > 0).any() else np.inf
+    for t in txs:
+        p2, g2 = kink_margins(t)
+        pre, gap = min(pre, p2), min(gap, g2)
+    return pre, gap
+
+
 def backward(tape, dc, do, M, G):
     P = M.P
     kind = tape[0]

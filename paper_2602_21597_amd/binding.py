@@ -15,6 +15,8 @@ LIB_PATH = os.path.join(_HERE, "libngdb.so")
 
 MLP_NAMES = ("W1", "b1", "W2", "b2", "V1", "c1", "V2", "c2", "U1", "u1", "U2", "u2")
 TENSOR_NAMES = ("E", "R") + MLP_NAMES
+BOX_TENSOR_NAMES = ("E", "R", "Ro") + MLP_NAMES[4:]      # the box family has no projection MLP
+FAMILY_VEC, FAMILY_BOX = 0, 1
 
 NGDB_OK = 0
 ERR_ARG, ERR_UNSUPPORTED, ERR_RANGE, ERR_OOM, ERR_HIP, ERR_STATE = -1, -2, -3, -4, -5, -6
@@ -30,7 +32,7 @@ class Config(C.Structure):
     _fields_ = [("n_entities", C.c_int32), ("n_relations", C.c_int32), ("d", C.c_int32), ("h", C.c_int32),
                 ("d_sem", C.c_int32), ("num_streams", C.c_int32), ("gamma", C.c_float), ("lr", C.c_float),
                 ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float), ("schedule", C.c_int32),
-                ("b_max", C.c_int32)]
+                ("b_max", C.c_int32), ("family", C.c_int32), ("box_alpha", C.c_float)]
 
 
 class Tensor(C.Structure):
@@ -38,7 +40,8 @@ class Tensor(C.Structure):
 
 
 class Params(C.Structure):
-    _fields_ = [(n, Tensor) for n in TENSOR_NAMES] + [("Wp", Tensor), ("H_sem", C.c_void_p), ("step", C.c_int64)]
+    _fields_ = [(n, Tensor) for n in TENSOR_NAMES] + [("Wp", Tensor), ("H_sem", C.c_void_p), ("step", C.c_int64),
+                                                       ("Ro", Tensor)]
 
 
 class QueryBatchC(C.Structure):
@@ -64,7 +67,8 @@ class GradView(C.Structure):
                 ("e_uniq", C.c_void_p), ("e_seg_off", C.c_void_p), ("e_src", C.c_void_p),
                 ("gE", C.c_void_p), ("gR", C.c_void_p), ("g_mlp", C.c_void_p * 12), ("g_Wp", C.c_void_p),
                 ("act", C.c_void_p), ("dact", C.c_void_p), ("n_grad_rows", C.c_int32),
-                ("pair_score", C.c_void_p), ("loss_terms", C.c_void_p)]
+                ("pair_score", C.c_void_p), ("loss_terms", C.c_void_p),
+                ("gRo", C.c_void_p), ("off", C.c_void_p), ("doff", C.c_void_p)]
 
 
 TIMING_CLASSES = ("index", "sem", "gemm_fwd", "inter", "score", "gemm_bwd", "wgrad", "table_E", "table_R",
@@ -303,7 +307,8 @@ class Engine:
     """One libngdb context plus the device tensors bound to it."""
 
     def __init__(self, n_entities, n_relations, d, h, gamma, lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8,
-                 d_sem=0, num_streams=1, device="cuda:0", schedule=SCHED_LEVEL, b_max=0):
+                 d_sem=0, num_streams=1, device="cuda:0", schedule=SCHED_LEVEL, b_max=0, family=FAMILY_VEC,
+                 box_alpha=0.02):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("libngdb needs a GPU; there is no CPU path")
@@ -311,7 +316,7 @@ class Engine:
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
         self.cfg = Config(n_entities, n_relations, d, h, d_sem, num_streams, gamma, lr, beta1, beta2, eps,
-                          int(schedule), int(b_max))
+                          int(schedule), int(b_max), int(family), float(box_alpha))
         self.ctx = C.c_void_p()
         _check(lib().ngdb_create(C.byref(self.cfg), C.byref(self.ctx)), None)
         self.tensors = {}
@@ -319,6 +324,8 @@ class Engine:
 
     # ---- parameters
     def tensor_names(self):
+        if self.cfg.family == FAMILY_BOX:
+            return BOX_TENSOR_NAMES
         return TENSOR_NAMES + (("Wp",) if self.cfg.d_sem else ())
 
     def bind_numpy(self, params, step=0, sem_bits=None):
@@ -418,7 +425,13 @@ class Engine:
             out["gR"] = copy_to_host(gv.gR, (UR, d), np.float32)
         shapes = [(h, d), (h,), (d, h), (d,)] * 3
         for i, name in enumerate(MLP_NAMES):
-            out[name] = copy_to_host(gv.g_mlp[i], shapes[i], np.float32)
+            if gv.g_mlp[i]:
+                out[name] = copy_to_host(gv.g_mlp[i], shapes[i], np.float32)
+        if gv.off:
+            out["off"] = copy_to_host(gv.off, (gv.n_slots, d), np.float32)
+            out["doff"] = copy_to_host(gv.doff, (gv.n_grad_rows, d), np.float32)
+        if gv.gRo:
+            out["gRo"] = copy_to_host(gv.gRo, (UR, d), np.float32)
         if gv.g_Wp:
             out["Wp"] = copy_to_host(gv.g_Wp, (d, self.cfg.d_sem), np.float32)
         return out

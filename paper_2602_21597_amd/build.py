@@ -10,7 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libngdb.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
-SOURCES = ["api.hip", "gemm.hip", "ops.hip", "score.hip", "index.hip", "table.hip", "rank.hip", "sem.hip", "planner.cpp", "sampler.cpp"]
+SOURCES = ["api.hip", "gemm.hip", "ops.hip", "score.hip", "index.hip", "table.hip", "rank.hip", "sem.hip", "box.hip", "planner.cpp", "sampler.cpp"]
 # packed-fp32 VALU instruction forms are switched off for every kernel of this library
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

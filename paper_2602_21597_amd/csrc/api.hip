@@ -83,6 +83,10 @@ struct ngdb_ctx_s {
     // contribution's entity in that list, operator references redirected to it, bf16 row gradients,
     // split-wise partial sums and the gradient of Wp, fused rows of one ranking chunk
     DevBuf Wb, Ef, inv, refs_sem, g_bf16, wp_partial, gWp, rank_ef;
+    // box family: offsets and their gradients by slot (act / dact hold the centres), per-input
+    // outputs of the offset MLP with their gradients, direct gradient of the inputs' offsets,
+    // compact gradient of Ro.  The offset MLP (V1 c1 V2 c2) uses the Z/H/dH buffers of index T_NEG.
+    DevBuf off, doff, Gate, dGate, DxO, gRo;
     size_t gw_off[13]{};
     hipStream_t upload = nullptr;        // plan uploads, independent of the compute streams
     std::vector<PlanBlob> blob_pool;
@@ -222,6 +226,17 @@ int size_workspace(ngdb_ctx_t* c, const ngdb_plan_t* pl, int K, bool want_table_
         ENS(c->H[t], rows[t] * h * f);
         ENS(c->dH[t], rows[t] * h * f);
     }
+    const bool box = c->cfg.family == NGDB_FAMILY_BOX;
+    if (box) {
+        ENS(c->off, (size_t)hp.n_slots * d * f);
+        ENS(c->doff, ((size_t)hp.n_slots + hp.n_anchor) * d * f);
+        ENS(c->Z[T_NEG], rows[T_INTER] * d * f);
+        ENS(c->H[T_NEG], rows[T_INTER] * h * f);
+        ENS(c->dH[T_NEG], rows[T_INTER] * h * f);
+        ENS(c->Gate, rows[T_INTER] * d * f);
+        ENS(c->dGate, rows[T_INTER] * d * f);
+        ENS(c->DxO, rows[T_INTER] * d * f);
+    }
     ENS(c->Att, rows[T_INTER] * d * f);
     ENS(c->dAtt, rows[T_INTER] * d * f);
     ENS(c->Dx, rows[T_INTER] * d * f);
@@ -274,6 +289,7 @@ int size_workspace(ngdb_ctx_t* c, const ngdb_plan_t* pl, int K, bool want_table_
         const size_t urows = (size_t)std::min<int64_t>(nk, c->cfg.n_entities);
         ENS(c->gE, urows * d * f);
         ENS(c->gR, (size_t)std::max<size_t>(hp.r_uniq.size(), 1) * d * f);
+        if (box) ENS(c->gRo, (size_t)std::max<size_t>(hp.r_uniq.size(), 1) * d * f);
     }
 #undef ENS
     return NGDB_OK;
@@ -325,9 +341,93 @@ int prepare_entities(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_tail
     return NGDB_OK;
 }
 
+// The intersections of one segment as jobs of the pooling kernels: centres (box == false:
+// X = Z[T_INTER], logits Att) or offsets of the box family (X = Z[T_NEG], MLP outputs Gate).
+int inter_jobs(ngdb_ctx_t* c, const ngdb_plan_t* pl, const Segment& sg, bool offsets, bool backward, InterJobs* ij) {
+    const HostPlan& hp = pl->hp;
+    const int d = c->cfg.d;
+    *ij = InterJobs{};
+    ij->d = d;
+    for (int g = sg.g_lo; g < sg.g_hi; ++g) {
+        const size_t mb = (size_t)hp.g_mlp_base[g] * d, ob = (size_t)hp.g_out_base[g] * d;
+        if (ij->count == INTER_MAX_JOBS) return fail(c, NGDB_ERR_UNSUPPORTED, "too many intersection classes in one level");
+        InterJob& jb = ij->job[ij->count++];
+        jb.X = ptr<float>(c->Z[offsets ? T_NEG : T_INTER]) + mb;
+        jb.Att = ptr<float>(offsets ? c->Gate : c->Att) + mb;
+        jb.n = hp.g_n[g]; jb.k = hp.g_nin[g];
+        if (!backward) {
+            jb.out = ptr<float>(offsets ? c->off : c->act) + ob;
+        } else {
+            jb.dY = ptr<float>(offsets ? c->doff : c->dact) + ob;
+            jb.dAtt = ptr<float>(offsets ? c->dGate : c->dAtt) + mb;
+            jb.Dx = ptr<float>(offsets ? c->DxO : c->Dx) + mb;
+        }
+    }
+    return NGDB_OK;
+}
+
+BoxProjArgs box_proj_args(ngdb_ctx_t* c, const ngdb_plan_t* pl, const Segment& sg) {
+    BoxProjArgs a{};
+    a.ref = pl->d_in_ref + sg.ref_off; a.gslot = pl->d_in_gslot + sg.ref_off; a.rel = pl->d_rel + sg.rel_off;
+    a.E = c->prm.E.p; a.Rc = c->prm.R.p; a.Ro = c->prm.Ro.p;
+    a.act_c = ptr<float>(c->act); a.act_o = ptr<float>(c->off);
+    a.dact_c = ptr<float>(c->dact); a.dact_o = ptr<float>(c->doff);
+    a.n = sg.rows; a.d = c->cfg.d; a.out_base = sg.out_base;
+    return a;
+}
+
+// Box family, forward: projections are one elementwise launch per group; an intersection runs two
+// MLPs over its inputs (attention logits from the centres, gate inputs from the offsets), grouped
+// into one launch per layer, then the two pooling kernels.
+int enqueue_forward_box(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t s) {
+    const int d = c->cfg.d, h = c->cfg.h;
+    for (int l = 1; l <= pl->hp.n_levels; ++l) {
+        const std::vector<Segment>& segs = pl->levels[l];
+        GemmArgs g1[GEMM_MAX_GROUP], g2[GEMM_MAX_GROUP];
+        int n = 0;
+        for (const Segment& sg : segs) {
+            if (sg.type == T_PROJ) {
+                Timed tm(c, NGDB_TK_INTER, s);
+                HIPCHK(c, launch_box_proj(box_proj_args(c, pl, sg), false, s));
+                continue;
+            }
+            if (sg.type != T_INTER || n + 2 > GEMM_MAX_GROUP) return fail(c, NGDB_ERR_UNSUPPORTED, "operator not available in the box family");
+            for (int part = 0; part < 2; ++part) {
+                const int t = part ? T_NEG : T_INTER;
+                const MlpRefs W = mlp_of(c->prm, t);
+                float* Hh = ptr<float>(c->H[t]) + (size_t)sg.mlp_base * h;
+                GemmArgs& a = g1[n];
+                a.a_ref = pl->d_in_ref + sg.ref_off; a.a_base0 = ptr<float>(part ? c->off : c->act);
+                a.a_base1 = c->prm.E.p;       // never taken: the plan holds no anchor below an intersection
+                a.a_copy = ptr<float>(c->Z[t]) + (size_t)sg.mlp_base * d; a.lda = d; a.B = W.Wa; a.ldb = d;
+                a.C = Hh; a.ldc = h; a.M = sg.rows; a.N = h; a.K = d; a.bias = W.ba; a.relu = true;
+                GemmArgs& b = g2[n];
+                b.A = Hh; b.lda = h; b.B = W.Wb; b.ldb = h; b.M = sg.rows; b.N = d; b.K = h; b.bias = W.bb; b.ldc = d;
+                b.C = ptr<float>(part ? c->Gate : c->Att) + (size_t)sg.mlp_base * d;
+                ++n;
+            }
+        }
+        if (n == 0) continue;
+        { Timed tm(c, NGDB_TK_GEMM_FWD, s); HIPCHK(c, launch_gemm_group(g1, n, s)); }
+        { Timed tm(c, NGDB_TK_GEMM_FWD, s); HIPCHK(c, launch_gemm_group(g2, n, s)); }
+        for (const Segment& sg : segs) {
+            if (sg.type != T_INTER) continue;
+            Timed tm(c, NGDB_TK_INTER, s);
+            InterJobs ij;
+            int rc = inter_jobs(c, pl, sg, false, false, &ij);
+            if (rc != NGDB_OK) return rc;
+            HIPCHK(c, launch_inter(ij, false, s));
+            if ((rc = inter_jobs(c, pl, sg, true, false, &ij)) != NGDB_OK) return rc;
+            HIPCHK(c, launch_box_offset(ij, false, s));
+        }
+    }
+    return NGDB_OK;
+}
+
 // forward over the plan's frontiers; results in c->act.  The type segments of one
 // depth are independent: they share one grouped launch per MLP layer.
 int enqueue_forward(ngdb_ctx_t* c, const ngdb_plan_t* pl, const EntRows& er, hipStream_t s) {
+    if (c->cfg.family == NGDB_FAMILY_BOX) return enqueue_forward_box(c, pl, s);
     const int d = c->cfg.d, h = c->cfg.h;
     for (int l = 1; l <= pl->hp.n_levels; ++l) {
         const std::vector<Segment>& segs = pl->levels[l];
@@ -370,8 +470,40 @@ int enqueue_forward(ngdb_ctx_t* c, const ngdb_plan_t* pl, const EntRows& er, hip
     return NGDB_OK;
 }
 
+// Gradients of the MLP tensors of the given types (their Z / H / dH buffers, dY = gradient of
+// the second layer's output): both weight matrices of every type in one grouped launch, the
+// biases as column sums.
+int enqueue_weight_grads(ngdb_ctx_t* c, const int* types, int nt, const size_t* rows, const float* const* dY,
+                         hipStream_t s) {
+    const int d = c->cfg.d, h = c->cfg.h;
+    float* gW = ptr<float>(c->gW);
+    Timed tm(c, NGDB_TK_WGRAD, s);
+    GemmArgs w[6];
+    ColsumJobs cs{};
+    for (int i = 0; i < nt; ++i) {
+        const int t = types[i], gs = gslot_of(t), r = (int)rows[i];
+        GemmArgs& wa = w[2 * i];       // dWa[h,d] = dH^T Z
+        wa.A = ptr<float>(c->dH[t]); wa.lda = h; wa.a_kcontig = false;
+        wa.B = ptr<float>(c->Z[t]); wa.ldb = d; wa.b_kcontig = false;
+        wa.C = gW + c->gw_off[gs + 0]; wa.ldc = d; wa.M = h; wa.N = d; wa.K = r;
+        GemmArgs& wb = w[2 * i + 1];   // dWb[d,h] = dY^T H
+        wb.A = dY[i]; wb.lda = d; wb.a_kcontig = false;
+        wb.B = ptr<float>(c->H[t]); wb.ldb = h; wb.b_kcontig = false;
+        wb.C = gW + c->gw_off[gs + 2]; wb.ldc = h; wb.M = d; wb.N = h; wb.K = r;
+        float* part = ptr<float>(c->colsum_part) + (size_t)(2 * i) * COLSUM_MAX_CHUNKS * std::max(d, h);
+        cs.job[cs.count++] = ColsumJob{ptr<float>(c->dH[t]), gW + c->gw_off[gs + 1], part, r, h, h, 0, 0};
+        cs.job[cs.count++] = ColsumJob{dY[i], gW + c->gw_off[gs + 3], part + (size_t)COLSUM_MAX_CHUNKS * std::max(d, h),
+                                       r, d, d, 0, 0};
+    }
+    HIPCHK(c, launch_gemm_group(w, 2 * nt, s));
+    HIPCHK(c, launch_colsums(cs, s));
+    return NGDB_OK;
+}
+
 // reversed frontiers, then the weight gradients of all three MLPs in one grouped launch
+int enqueue_backward_box(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t s);
 int enqueue_backward(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t s) {
+    if (c->cfg.family == NGDB_FAMILY_BOX) return enqueue_backward_box(c, pl, s);
     const int d = c->cfg.d, h = c->cfg.h;
     const HostPlan& hp = pl->hp;
     float* dact = ptr<float>(c->dact);
@@ -417,35 +549,62 @@ int enqueue_backward(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t s) {
         { Timed tm(c, NGDB_TK_GEMM_BWD, s); HIPCHK(c, launch_gemm_group(b1, n, s)); }
     }
     // weight gradients: one contraction per tensor over all rows of the type
+    const int types[3] = {T_PROJ, T_INTER, T_NEG};
     const size_t rows[3] = {(size_t)hp.n_proj, (size_t)hp.n_int_rows, (size_t)hp.n_neg};
     const float* dY[3] = {dact, ptr<float>(c->dAtt), dact + ((size_t)hp.n_proj + hp.n_inter) * d};
-    float* gW = ptr<float>(c->gW);
-    Timed tm(c, NGDB_TK_WGRAD, s);
-    GemmArgs w[6];
-    for (int t = 0; t < 3; ++t) {
-        const int gs = gslot_of(t);
-        const int r = (int)rows[t];
-        GemmArgs& wa = w[2 * t];       // dWa[h,d] = dH^T Z
-        wa.A = ptr<float>(c->dH[t]); wa.lda = h; wa.a_kcontig = false;
-        wa.B = ptr<float>(c->Z[t]); wa.ldb = d; wa.b_kcontig = false;
-        wa.C = gW + c->gw_off[gs + 0]; wa.ldc = d; wa.M = h; wa.N = d; wa.K = r;
-        GemmArgs& wb = w[2 * t + 1];   // dWb[d,h] = dY^T H
-        wb.A = dY[t]; wb.lda = d; wb.a_kcontig = false;
-        wb.B = ptr<float>(c->H[t]); wb.ldb = h; wb.b_kcontig = false;
-        wb.C = gW + c->gw_off[gs + 2]; wb.ldc = h; wb.M = d; wb.N = h; wb.K = r;
+    return enqueue_weight_grads(c, types, 3, rows, dY, s);
+}
+
+// Box family, backward: the reverse of enqueue_forward_box; the gradient of a projection's
+// input is the gradient of its output (copied to the input's rows, where the relation tables
+// pick it up too).
+int enqueue_backward_box(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t s) {
+    const int d = c->cfg.d, h = c->cfg.h;
+    const HostPlan& hp = pl->hp;
+    for (int l = hp.n_levels; l >= 1; --l) {
+        const std::vector<Segment>& segs = pl->levels[l];
+        GemmArgs b2[GEMM_MAX_GROUP], b1[GEMM_MAX_GROUP];
+        int n = 0;
+        for (const Segment& sg : segs) {
+            if (sg.type == T_PROJ) {
+                Timed tm(c, NGDB_TK_INTER, s);
+                HIPCHK(c, launch_box_proj(box_proj_args(c, pl, sg), true, s));
+                continue;
+            }
+            if (sg.type != T_INTER || n + 2 > GEMM_MAX_GROUP) return fail(c, NGDB_ERR_UNSUPPORTED, "operator not available in the box family");
+            {
+                Timed tm(c, NGDB_TK_INTER, s);
+                InterJobs ij;
+                int rc = inter_jobs(c, pl, sg, false, true, &ij);
+                if (rc != NGDB_OK) return rc;
+                HIPCHK(c, launch_inter(ij, true, s));
+                if ((rc = inter_jobs(c, pl, sg, true, true, &ij)) != NGDB_OK) return rc;
+                HIPCHK(c, launch_box_offset(ij, true, s));
+            }
+            for (int part = 0; part < 2; ++part) {
+                const int t = part ? T_NEG : T_INTER;
+                const MlpRefs W = mlp_of(c->prm, t);
+                const size_t mb = (size_t)sg.mlp_base;
+                const float* Hh = ptr<float>(c->H[t]) + mb * h;
+                float* dHh = ptr<float>(c->dH[t]) + mb * h;
+                GemmArgs& x = b2[n];
+                x.A = ptr<float>(part ? c->dGate : c->dAtt) + mb * d; x.lda = d; x.B = W.Wb; x.ldb = h; x.b_kcontig = false;
+                x.C = dHh; x.ldc = h; x.M = sg.rows; x.N = h; x.K = d; x.mask = Hh; x.ldmask = h;
+                GemmArgs& y = b1[n];
+                y.A = dHh; y.lda = h; y.B = W.Wa; y.ldb = d; y.b_kcontig = false;
+                y.C = ptr<float>(part ? c->doff : c->dact); y.ldc = d; y.M = sg.rows; y.N = d; y.K = h;
+                y.addend = ptr<float>(part ? c->DxO : c->Dx) + mb * d; y.ldadd = d; y.dst_row = pl->d_in_gslot + sg.ref_off;
+                ++n;
+            }
+        }
+        if (n == 0) continue;
+        { Timed tm(c, NGDB_TK_GEMM_BWD, s); HIPCHK(c, launch_gemm_group(b2, n, s)); }
+        { Timed tm(c, NGDB_TK_GEMM_BWD, s); HIPCHK(c, launch_gemm_group(b1, n, s)); }
     }
-    HIPCHK(c, launch_gemm_group(w, 6, s));
-    ColsumJobs cs{};
-    for (int t = 0; t < 3; ++t) {
-        const int gs = gslot_of(t);
-        const int r = (int)rows[t];
-        float* part = ptr<float>(c->colsum_part) + (size_t)(2 * t) * COLSUM_MAX_CHUNKS * std::max(d, h);
-        cs.job[cs.count++] = ColsumJob{ptr<float>(c->dH[t]), gW + c->gw_off[gs + 1], part, r, h, h, 0, 0};
-        cs.job[cs.count++] = ColsumJob{dY[t], gW + c->gw_off[gs + 3], part + (size_t)COLSUM_MAX_CHUNKS * std::max(d, h),
-                                       r, d, d, 0, 0};
-    }
-    HIPCHK(c, launch_colsums(cs, s));
-    return NGDB_OK;
+    const int types[2] = {T_INTER, T_NEG};
+    const size_t rows[2] = {(size_t)hp.n_int_rows, (size_t)hp.n_int_rows};
+    const float* dY[2] = {ptr<float>(c->dAtt), ptr<float>(c->dGate)};
+    return enqueue_weight_grads(c, types, 2, rows, dY, s);
 }
 
 int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, hipStream_t stream, float* d_loss,
@@ -488,6 +647,8 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
     sa.pos = er.pos; sa.cand = er.cand; sa.B = B; sa.C = K; sa.d = d; sa.max_branch = std::max(1, hp.max_branch);
     sa.gamma = c->cfg.gamma; sa.score = ptr<float>(c->score); sa.coef = ptr<float>(c->coef);
     sa.win = sem ? nullptr : ptr<int32_t>(c->win); sa.mask = sem ? c->mask.p : nullptr; sa.dact = ptr<float>(c->dact); sa.loss_terms = ptr<float>(c->loss_terms);
+    const bool box = c->cfg.family == NGDB_FAMILY_BOX;
+    if (box) { sa.off = ptr<float>(c->off); sa.doff = ptr<float>(c->doff); sa.alpha = c->cfg.box_alpha; }
     {
         Timed tm(c, NGDB_TK_SCORE, stream);
         hipError_t e = launch_score(sa, true, stream);
@@ -518,6 +679,7 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
     te.dact = ptr<float>(c->dact); te.act = ptr<float>(c->act); te.g_out = apply ? nullptr : ptr<float>(c->gE);
     if (sem) { te.mask = c->mask.p; te.g_bf16 = ptr<uint16_t>(c->g_bf16); }
     TableArgs tr = te;
+    if (box) { te.off = ptr<float>(c->off); te.alpha = c->cfg.box_alpha; }
     tr.g_bf16 = nullptr; tr.mask = nullptr;
     tr.P = c->prm.R.p; tr.Mo = c->prm.R.m; tr.Vo = c->prm.R.v;
     tr.uniq = pl->d_r_uniq; tr.seg_off = pl->d_r_seg_off; tr.n_uniq_dev = pl->d_n_r_uniq;
@@ -526,18 +688,25 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
     HIPCHK(c, L.fork(3));
     { Timed tm(c, NGDB_TK_TABLE_E, L.lane(0)); HIPCHK(c, launch_table_update(te, ah, L.lane(0))); }
     { Timed tm(c, NGDB_TK_TABLE_R, L.lane(1)); HIPCHK(c, launch_table_update(tr, ah, L.lane(1))); }
+    if (box) {   // relation offsets: the same segments over the offset gradients, gated by relu
+        TableArgs to = tr;
+        to.P = c->prm.Ro.p; to.Mo = c->prm.Ro.m; to.Vo = c->prm.Ro.v;
+        to.dact = ptr<float>(c->doff); to.relu_gate = true; to.g_out = apply ? nullptr : ptr<float>(c->gRo);
+        Timed tm(c, NGDB_TK_TABLE_R, L.lane(1));
+        HIPCHK(c, launch_table_update(to, ah, L.lane(1)));
+    }
     if (apply) {
         DenseAdamJob job{};
         const ngdb_tensor* ts[12] = {&c->prm.W1, &c->prm.b1, &c->prm.W2, &c->prm.b2, &c->prm.V1, &c->prm.c1,
                                      &c->prm.V2, &c->prm.c2, &c->prm.U1, &c->prm.u1, &c->prm.U2, &c->prm.u2};
         const int64_t hd = (int64_t)c->cfg.h * d;
         const int64_t sz[4] = {hd, c->cfg.h, hd, d};
-        for (int i = 0; i < 12; ++i) {
-            job.p[i] = ts[i]->p; job.m[i] = ts[i]->m; job.v[i] = ts[i]->v;
-            job.g[i] = ptr<float>(c->gW) + c->gw_off[i];
-            job.n[i] = sz[i % 4];
+        for (int i = box ? 4 : 0; i < 12; ++i) {   // the box family has no projection MLP
+            const int k = job.count++;
+            job.p[k] = ts[i]->p; job.m[k] = ts[i]->m; job.v[k] = ts[i]->v;
+            job.g[k] = ptr<float>(c->gW) + c->gw_off[i];
+            job.n[k] = sz[i % 4];
         }
-        job.count = 12;
         Timed tm(c, NGDB_TK_ADAM, L.lane(2));
         HIPCHK(c, launch_dense_adam(job, ah, L.lane(2)));
     }
@@ -573,7 +742,12 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
     gv.e_src = e_src;
     gv.gE = apply ? nullptr : ptr<float>(c->gE);
     gv.gR = apply ? nullptr : ptr<float>(c->gR);
-    for (int i = 0; i < 12; ++i) gv.g_mlp[i] = ptr<float>(c->gW) + c->gw_off[i];
+    for (int i = box ? 4 : 0; i < 12; ++i) gv.g_mlp[i] = ptr<float>(c->gW) + c->gw_off[i];
+    if (box) {
+        gv.gRo = apply ? nullptr : ptr<float>(c->gRo);
+        gv.off = ptr<float>(c->off);
+        gv.doff = ptr<float>(c->doff);
+    }
     gv.g_Wp = sem ? ptr<float>(c->gWp) : nullptr;
     gv.act = ptr<float>(c->act);
     gv.dact = ptr<float>(c->dact);
@@ -597,6 +771,9 @@ int ngdb_create(const ngdb_config* cfg, ngdb_ctx_t** out) {
         return NGDB_ERR_ARG;
     if (cfg->d_sem != 0 && ((cfg->d_sem & 63) || (cfg->d & 7))) return NGDB_ERR_ARG;
     if ((cfg->schedule != NGDB_SCHED_LEVEL && cfg->schedule != NGDB_SCHED_MAX_FILL) || cfg->b_max < 0) return NGDB_ERR_ARG;
+    if (cfg->family != NGDB_FAMILY_VEC && cfg->family != NGDB_FAMILY_BOX) return NGDB_ERR_ARG;
+    if (cfg->family == NGDB_FAMILY_BOX && (cfg->d_sem != 0 || !(cfg->box_alpha >= 0.f) || !std::isfinite(cfg->box_alpha)))
+        return NGDB_ERR_ARG;
     ngdb_ctx_t* c = new (std::nothrow) ngdb_ctx_s();
     if (!c) return NGDB_ERR_OOM;
     c->cfg = *cfg;
@@ -623,7 +800,8 @@ void ngdb_destroy(ngdb_ctx_t* c) {
                      &c->dH[1], &c->dH[2], &c->Att, &c->dAtt, &c->Dx, &c->score, &c->coef, &c->win, &c->mask,
                      &c->loss_terms, &c->rec_coef, &c->rec_row, &c->keys_a, &c->keys_b, &c->vals_a, &c->vals_b, &c->hist, &c->scan_tmp,
                      &c->uniq, &c->seg_off, &c->n_uniq, &c->gW, &c->gE, &c->gR, &c->colsum_part, &c->rank_dist, &c->rank_thr, &c->rank_count,
-                     &c->Wb, &c->Ef, &c->inv, &c->refs_sem, &c->g_bf16, &c->wp_partial, &c->gWp, &c->rank_ef};
+                     &c->Wb, &c->Ef, &c->inv, &c->refs_sem, &c->g_bf16, &c->wp_partial, &c->gWp, &c->rank_ef,
+                     &c->off, &c->doff, &c->Gate, &c->dGate, &c->DxO, &c->gRo};
     for (DevBuf* b : all) release(*b);
     for (int i = 0; i < 4; ++i) {
         if (c->side[i]) (void)hipStreamDestroy(c->side[i]);
@@ -647,8 +825,10 @@ void ngdb_destroy(ngdb_ctx_t* c) {
 
 int ngdb_bind_params(ngdb_ctx_t* c, const ngdb_params* p) {
     if (!c || !p) return NGDB_ERR_ARG;
-    const ngdb_tensor* ts[14] = {&p->E, &p->R, &p->W1, &p->b1, &p->W2, &p->b2, &p->V1,
-                                 &p->c1, &p->V2, &p->c2, &p->U1, &p->u1, &p->U2, &p->u2};
+    const bool box = c->cfg.family == NGDB_FAMILY_BOX;
+    const ngdb_tensor* ts[14] = {&p->E, &p->R, &p->V1, &p->c1, &p->V2, &p->c2, &p->U1, &p->u1, &p->U2, &p->u2,
+                                 box ? &p->Ro : &p->W1, box ? &p->Ro : &p->b1, box ? &p->Ro : &p->W2,
+                                 box ? &p->Ro : &p->b2};
     for (const ngdb_tensor* t : ts) {
         if (!t->p || !t->m || !t->v) return fail(c, NGDB_ERR_ARG, "null parameter or moment tensor");
         if (((uintptr_t)t->p | (uintptr_t)t->m | (uintptr_t)t->v) & 15)
@@ -727,6 +907,18 @@ int ngdb_plan(ngdb_ctx_t* c, const ngdb_query_batch* qb, ngdb_plan_t** out) {
     int rc = plan_host(qb, c->cfg.n_entities, c->cfg.n_relations, c->cfg.schedule, c->cfg.b_max, &pl, err);
     if (rc != NGDB_OK) return fail(c, rc, err);
     HostPlan& hp = pl->hp;
+    if (c->cfg.family == NGDB_FAMILY_BOX) {
+        bool ok = hp.n_neg == 0;
+        for (int g = 0; g < hp.n_groups && ok; ++g) {
+            if (hp.g_type[g] != NGDB_OP_INTER) continue;
+            const int n_ref = hp.g_n[g] * hp.g_nin[g];
+            for (int i = 0; i < n_ref && ok; ++i) ok = hp.in_ref[hp.g_ref_off[g] + i] >= 0;
+        }
+        if (!ok) {
+            delete pl;
+            return fail(c, NGDB_ERR_UNSUPPORTED, "box family: no negation, and an intersection input must be an operator output");
+        }
+    }
 
     // one upload: every device-side array, each padded to 16 bytes
     std::vector<int32_t> blob;
@@ -848,6 +1040,8 @@ int ngdb_score(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_cand, int3
         if (C <= 0 || !d_scores) return fail(c, NGDB_ERR_ARG, "candidate mode needs C > 0 and d_scores");
     } else if (topk < 1 || topk > NGDB_MAX_TOPK || !d_topk_ids || !d_topk_dist) {
         return fail(c, NGDB_ERR_ARG, "all-entity mode needs 1 <= topk <= NGDB_MAX_TOPK and both output arrays");
+    } else if (c->cfg.family == NGDB_FAMILY_BOX) {
+        return fail(c, NGDB_ERR_UNSUPPORTED, "the all-entity ranking is not available in the box family");
     }
     c->have_grads = false;
     const bool sem = c->cfg.d_sem > 0;
@@ -866,6 +1060,7 @@ int ngdb_score(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_cand, int3
         sa.act = ptr<float>(c->act); sa.E = er.rows; sa.root_off = pl->d_root_off; sa.root_slot = pl->d_root_slot;
         sa.pos = nullptr; sa.cand = er.cand; sa.B = pl->hp.n_queries; sa.C = C; sa.d = c->cfg.d;
         sa.max_branch = std::max(1, pl->hp.max_branch); sa.gamma = c->cfg.gamma; sa.score = d_scores;
+        if (c->cfg.family == NGDB_FAMILY_BOX) { sa.off = ptr<float>(c->off); sa.alpha = c->cfg.box_alpha; }
         hipError_t e;
         { Timed tm(c, NGDB_TK_SCORE, s); e = launch_score(sa, false, s); }
         if (e == hipErrorInvalidValue) return fail(c, NGDB_ERR_UNSUPPORTED, "embedding width / union branch count too large for the scoring kernel");
@@ -911,6 +1106,7 @@ int ngdb_rank_answers(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_ans
     if (n_ans < 0 || !d_ans_off || (n_ans > 0 && (!d_ans || !d_rank)))
         return fail(c, NGDB_ERR_ARG, "answer lists / rank output missing");
     if (pl->hp.n_queries > 65535) return fail(c, NGDB_ERR_UNSUPPORTED, "more than 65535 queries in one ranking call");
+    if (c->cfg.family == NGDB_FAMILY_BOX) return fail(c, NGDB_ERR_UNSUPPORTED, "filtered ranking is not available in the box family");
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool sem = c->cfg.d_sem > 0;
     c->have_grads = false;

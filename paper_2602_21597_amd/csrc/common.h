@@ -90,6 +90,22 @@ struct InterJobs {
     InterJob job[INTER_MAX_JOBS];
 };
 hipError_t launch_inter(const InterJobs& jobs, bool backward, hipStream_t s);
+// Box family, offset part of the intersections (same job layout: X = the inputs' offsets, Att =
+// the per-input outputs of the offset MLP).  Forward: out[i] = min_j x_j * sigmoid(mean_j att_j).
+// Backward: dAtt[j*n+i] = dy * min * g(1-g) / k;  Dx[j*n+i] = dy * g for the first j attaining
+// the minimum, 0 for the others.
+hipError_t launch_box_offset(const InterJobs& jobs, bool backward, hipStream_t s);
+// Box family, projections of one group: member i reads its input box through ref[i] (slot, or
+// -1-entity: centre E[e], offset 0) and writes (c + Rc[rel[i]], o + relu(Ro[rel[i]])) to slot
+// out_base + i.  Backward copies the gradient rows of slot out_base + i (centre and offset) to
+// the input's gradient rows gslot[i].
+struct BoxProjArgs {
+    const int32_t *ref, *gslot, *rel;
+    const float *E, *Rc, *Ro;
+    float *act_c, *act_o, *dact_c, *dact_o;
+    int n, d, out_base;
+};
+hipError_t launch_box_proj(const BoxProjArgs& a, bool backward, hipStream_t s);
 // out[c] = sum_m X[m*ld + c], c < cols, for several matrices in one launch pair (fixed
 // summation order); `part` is scratch of COLSUM_MAX_CHUNKS * cols floats per matrix
 constexpr int COLSUM_MAX_CHUNKS = 128;
@@ -145,6 +161,11 @@ struct ScoreArgs {
                                // (one of win / mask is set in training)
     float* dact;               // gradient arena (training only)
     float* loss_terms;         // [B] (training only)
+    // box family (off set): act holds the centres, off the offsets [n_slots, d]; the distance is
+    // sum relu(|e-c| - o) + alpha * sum min(|e-c|, o); doff receives dL/d(offset) of the roots
+    const float* off = nullptr;
+    float* doff = nullptr;
+    float alpha = 0.f;
 };
 hipError_t launch_score(const ScoreArgs& a, bool train, hipStream_t s);
 
@@ -210,6 +231,12 @@ struct TableArgs {
     // text-feature fusion: the row gradient is also left in g_bf16 [n_uniq, d] (bf16 bit
     // patterns) for the gradient of the projection
     uint16_t* g_bf16 = nullptr;
+    // box family: pair records carry rows of act (centres) and off (offsets); the contribution is
+    // rec_coef * w * sign(centre - table row), w = 1 where |centre - row| > offset, else alpha
+    const float* off = nullptr;
+    float alpha = 0.f;
+    // the row's gradient is multiplied by [table row > 0] (a table that is used through relu)
+    bool relu_gate = false;
 };
 // sorted contribution numbers -> records: c < n_rowsrc is gradient row row_base + c,
 // otherwise a (query, candidate) pair in the order [B positives | B*K negatives]

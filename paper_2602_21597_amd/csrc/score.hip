@@ -26,8 +26,11 @@ __device__ __forceinline__ void load_row(const ScoreArgs& a, int32_t e, int lane
     for (int ch = 0; ch < NCH; ++ch) dst[ch] = row[min(ch * 64 + lane, d4 - 1)];
 }
 
-// MASK (training with text features): sign codes per pair instead of the winning rows
-template <int NCH, int NW, bool TRAIN, bool MASK>
+// MASK (training with text features): sign codes per pair instead of the winning rows.
+// BOX: the query side is a box (centre from act, offset from off) and the distance is
+// sum relu(|e-c| - o) + alpha * sum min(|e-c|, o); in LDS the offsets of the branches follow
+// the centres and the offset gradients follow the centre gradients.
+template <int NCH, int NW, bool TRAIN, bool MASK, bool BOX>
 __global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
     extern __shared__ __attribute__((aligned(16))) float lds[];
     const int i = blockIdx.x;
@@ -38,24 +41,32 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
     const int has_pos = a.pos ? 1 : 0;
     const int CT = a.C + has_pos;
 
-    float4* ybr = reinterpret_cast<float4*>(lds);                    // [nb][d4]
-    float4* accs = ybr + (size_t)a.max_branch * d4;                  // [NW][nb][d4]   (TRAIN)
-    float* lossp = reinterpret_cast<float*>(accs + (TRAIN ? (size_t)NW * a.max_branch * d4 : 0));
+    constexpr int PARTS = BOX ? 2 : 1;                               // centre (and offset) per branch
+    float4* ybr = reinterpret_cast<float4*>(lds);                    // [PARTS][nb][d4]
+    float4* accs = ybr + (size_t)PARTS * a.max_branch * d4;          // [NW][PARTS][nb][d4]   (TRAIN)
+    float* lossp = reinterpret_cast<float*>(accs + (TRAIN ? (size_t)NW * PARTS * a.max_branch * d4 : 0));
+    const float4* obr = ybr + (size_t)nb * d4;                       // offsets (BOX)
 
-    for (int idx = tid; idx < nb * d4; idx += NW * 64) {
+    for (int idx = tid; idx < PARTS * nb * d4; idx += NW * 64) {
         const int b = idx / d4, c = idx - b * d4;
-        ybr[idx] = reinterpret_cast<const float4*>(a.act + (size_t)a.root_slot[r0 + b] * a.d)[c];
+        const float* src = (BOX && b >= nb) ? a.off + (size_t)a.root_slot[r0 + b - nb] * a.d
+                                            : a.act + (size_t)a.root_slot[r0 + b] * a.d;
+        ybr[idx] = reinterpret_cast<const float4*>(src)[c];
     }
-    float4* myacc = accs + (size_t)wave * nb * d4;
+    float4* myacc = accs + (size_t)wave * PARTS * nb * d4;
     if (TRAIN && nb > 1)
-        for (int idx = lane; idx < nb * d4; idx += 64) myacc[idx] = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int idx = lane; idx < PARTS * nb * d4; idx += 64) myacc[idx] = make_float4(0.f, 0.f, 0.f, 0.f);
     __syncthreads();
 
     const float inv2B = 1.f / (2.f * (float)a.B);
     const float invK = a.C > 0 ? 1.f / (float)a.C : 0.f;
-    float4 dyr[NCH];
+    float4 dyr[NCH], dor[BOX ? NCH : 1];
 #pragma unroll
-    for (int ch = 0; ch < NCH; ++ch) dyr[ch] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int ch = 0; ch < NCH; ++ch) {
+        dyr[ch] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (BOX) dor[ch] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    const float alpha = a.alpha;
     float lsum = 0.f;
 
     // The id of a candidate is requested two rounds ahead of its use and its row one round
@@ -78,8 +89,16 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
                 const int col = ch * 64 + lane;
                 if (col < d4) {
                     const float4 y = ybr[b * d4 + col];
-                    dist += (fabsf(y.x - cur[ch].x) + fabsf(y.y - cur[ch].y)) +
-                            (fabsf(y.z - cur[ch].z) + fabsf(y.w - cur[ch].w));
+                    const float ax = fabsf(y.x - cur[ch].x), ay = fabsf(y.y - cur[ch].y),
+                                az = fabsf(y.z - cur[ch].z), aw = fabsf(y.w - cur[ch].w);
+                    if (BOX) {
+                        const float4 o = obr[b * d4 + col];
+                        dist += ((fmaxf(ax - o.x, 0.f) + fmaxf(ay - o.y, 0.f)) +
+                                 (fmaxf(az - o.z, 0.f) + fmaxf(aw - o.w, 0.f))) +
+                                alpha * ((fminf(ax, o.x) + fminf(ay, o.y)) + (fminf(az, o.z) + fminf(aw, o.w)));
+                    } else {
+                        dist += (ax + ay) + (az + aw);
+                    }
                 }
             }
             dist = wave_sum(dist);
@@ -114,6 +133,25 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
                     g.y = coef * sy;
                     g.z = coef * sz;
                     g.w = coef * sw;
+                    if (BOX) {
+                        // outside coordinates pull the centre with weight 1 and widen the offset;
+                        // inside ones pull with weight alpha and leave the offset alone
+                        const float4 o = obr[bw * d4 + col];
+                        const bool ox = fabsf(y.x - cur[ch].x) > o.x, oy = fabsf(y.y - cur[ch].y) > o.y,
+                                   oz = fabsf(y.z - cur[ch].z) > o.z, ow = fabsf(y.w - cur[ch].w) > o.w;
+                        g.x *= ox ? 1.f : alpha; g.y *= oy ? 1.f : alpha;
+                        g.z *= oz ? 1.f : alpha; g.w *= ow ? 1.f : alpha;
+                        const float co = coef * (1.f - alpha);
+                        float4 go;
+                        go.x = ox ? co : 0.f; go.y = oy ? co : 0.f; go.z = oz ? co : 0.f; go.w = ow ? co : 0.f;
+                        if (nb == 1) {
+                            dor[ch].x += go.x; dor[ch].y += go.y; dor[ch].z += go.z; dor[ch].w += go.w;
+                        } else {
+                            float4 t = myacc[(nb + bw) * d4 + col];
+                            t.x += go.x; t.y += go.y; t.z += go.z; t.w += go.w;
+                            myacc[(nb + bw) * d4 + col] = t;
+                        }
+                    }
                     if (nb == 1) {
                         dyr[ch].x -= g.x; dyr[ch].y -= g.y; dyr[ch].z -= g.z; dyr[ch].w -= g.w;
                     } else {
@@ -140,19 +178,24 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
 #pragma unroll
             for (int ch = 0; ch < NCH; ++ch) {
                 const int col = ch * 64 + lane;
-                if (col < d4) myacc[col] = dyr[ch];
+                if (col < d4) {
+                    myacc[col] = dyr[ch];
+                    if (BOX) myacc[d4 + col] = dor[ch];
+                }
             }
         }
         if (lane == 0) lossp[wave] = lsum;
         __syncthreads();
-        for (int idx = tid; idx < nb * d4; idx += NW * 64) {
+        for (int idx = tid; idx < PARTS * nb * d4; idx += NW * 64) {
             float4 t = accs[idx];
             for (int w = 1; w < NW; ++w) {
-                const float4 u = accs[(size_t)w * nb * d4 + idx];
+                const float4 u = accs[(size_t)w * PARTS * nb * d4 + idx];
                 t.x += u.x; t.y += u.y; t.z += u.z; t.w += u.w;
             }
             const int b = idx / d4, cc = idx - b * d4;
-            reinterpret_cast<float4*>(a.dact + (size_t)a.root_slot[r0 + b] * a.d)[cc] = t;
+            float* dst = (BOX && b >= nb) ? a.doff + (size_t)a.root_slot[r0 + b - nb] * a.d
+                                          : a.dact + (size_t)a.root_slot[r0 + b] * a.d;
+            reinterpret_cast<float4*>(dst)[cc] = t;
         }
         if (tid == 0) {
             float l = 0.f;
@@ -162,22 +205,22 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
     }
 }
 
+template <int NCH, int NW, bool TRAIN, bool MASK, bool BOX>
+hipError_t launch_variant(const ScoreArgs& a, size_t lds, hipStream_t s) {
+    if (lds > 64 * 1024)
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(score_kernel<NCH, NW, TRAIN, MASK, BOX>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipLaunchKernelGGL((score_kernel<NCH, NW, TRAIN, MASK, BOX>), dim3(a.B), dim3(NW * 64), lds, s, a);
+    return hipGetLastError();
+}
+
 template <int NCH, int NW>
 hipError_t launch_nw(const ScoreArgs& a, bool train, size_t lds, hipStream_t s) {
-    if (train && a.mask) {
-        if (lds > 64 * 1024)
-            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(score_kernel<NCH, NW, true, true>),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        hipLaunchKernelGGL((score_kernel<NCH, NW, true, true>), dim3(a.B), dim3(NW * 64), lds, s, a);
-    } else if (train) {
-        if (lds > 64 * 1024)
-            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(score_kernel<NCH, NW, true, false>),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        hipLaunchKernelGGL((score_kernel<NCH, NW, true, false>), dim3(a.B), dim3(NW * 64), lds, s, a);
-    } else {
-        hipLaunchKernelGGL((score_kernel<NCH, NW, false, false>), dim3(a.B), dim3(NW * 64), lds, s, a);
-    }
-    return hipGetLastError();
+    if (a.off) return train ? launch_variant<NCH, NW, true, false, true>(a, lds, s)
+                            : launch_variant<NCH, NW, false, false, true>(a, lds, s);
+    if (train && a.mask) return launch_variant<NCH, NW, true, true, false>(a, lds, s);
+    if (train) return launch_variant<NCH, NW, true, false, false>(a, lds, s);
+    return launch_variant<NCH, NW, false, false, false>(a, lds, s);
 }
 
 template <int NCH>
@@ -185,7 +228,7 @@ hipError_t launch_nch(const ScoreArgs& a, bool train, hipStream_t s) {
     // enough wavefronts to cover the chip even for small batches
     const int nw = a.B >= 2048 ? 4 : (a.B >= 1024 ? 8 : 16);
     auto lds_for = [&](int w) {
-        return ((size_t)a.max_branch * a.d * (1 + (train ? w : 0)) + 16) * sizeof(float);
+        return ((size_t)(a.off ? 2 : 1) * a.max_branch * a.d * (1 + (train ? w : 0)) + 16) * sizeof(float);
     };
     const size_t cap = 150 * 1024;
     if (nw == 16 && lds_for(16) <= cap) return launch_nw<NCH, 16>(a, train, lds_for(16), s);
@@ -200,6 +243,7 @@ hipError_t launch_score(const ScoreArgs& a, bool train, hipStream_t s) {
     if (a.B <= 0) return hipSuccess;
     if (a.C + (a.pos ? 1 : 0) <= 0) return hipErrorInvalidValue;   // the kernel clamps into a non-empty candidate list
     if (train && (a.win == nullptr) == (a.mask == nullptr)) return hipErrorInvalidValue;   // exactly one of the two
+    if (a.off && (a.mask || (train && !a.doff))) return hipErrorInvalidValue;
     if (a.d <= 256) return launch_nch<1>(a, train, s);
     if (a.d <= 512) return launch_nch<2>(a, train, s);
     if (a.d <= 1024) return launch_nch<4>(a, train, s);

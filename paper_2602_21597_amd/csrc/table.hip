@@ -70,8 +70,10 @@ __device__ __forceinline__ uint32_t load_mask(const void* mask, size_t idx) {
 }
 
 // SEM (text-feature fusion): pair signs come from the sign codes, and the row gradient is
-// also stored as bf16 (input of the projection's gradient)
-template <int NCH, bool SEM>
+// also stored as bf16 (input of the projection's gradient).
+// BOX (box family, entity table): a pair's sign is weighted 1 where the row lies outside the
+// winning box in that coordinate and alpha where it lies inside.
+template <int NCH, bool SEM, bool BOX>
 __global__ __launch_bounds__(256) void table_kernel(const TableArgs a, const AdamHyper hp) {
     const int lane = threadIdx.x & 63;
     const int d4 = a.d >> 2;
@@ -135,7 +137,7 @@ __global__ __launch_bounds__(256) void table_kernel(const TableArgs a, const Ada
             }
             if (!SEM) {
                 for (int j0 = n_rows; j0 < n; j0 += G) {
-                    float4 x[G][NCH];
+                    float4 x[G][NCH], xo[BOX ? G : 1][NCH];
                     float cf[G];
 #pragma unroll
                     for (int q = 0; q < G; ++q) {
@@ -145,15 +147,30 @@ __global__ __launch_bounds__(256) void table_kernel(const TableArgs a, const Ada
                         const float4* srow = reinterpret_cast<const float4*>(a.act + (size_t)r * a.d);
 #pragma unroll
                         for (int ch = 0; ch < NCH; ++ch) x[q][ch] = srow[colc[ch]];
+                        if (BOX) {
+                            const float4* orow = reinterpret_cast<const float4*>(a.off + (size_t)r * a.d);
+#pragma unroll
+                            for (int ch = 0; ch < NCH; ++ch) xo[q][ch] = orow[colc[ch]];
+                        }
                     }
 #pragma unroll
                     for (int q = 0; q < G; ++q)
 #pragma unroll
                         for (int ch = 0; ch < NCH; ++ch) {
-                            g[ch].x += cf[q] * sgn(x[q][ch].x - p[ch].x);
-                            g[ch].y += cf[q] * sgn(x[q][ch].y - p[ch].y);
-                            g[ch].z += cf[q] * sgn(x[q][ch].z - p[ch].z);
-                            g[ch].w += cf[q] * sgn(x[q][ch].w - p[ch].w);
+                            if (BOX) {
+                                const float ca = cf[q] * a.alpha;
+                                const float dx = x[q][ch].x - p[ch].x, dy = x[q][ch].y - p[ch].y,
+                                            dz = x[q][ch].z - p[ch].z, dw = x[q][ch].w - p[ch].w;
+                                g[ch].x += (fabsf(dx) > xo[q][ch].x ? cf[q] : ca) * sgn(dx);
+                                g[ch].y += (fabsf(dy) > xo[q][ch].y ? cf[q] : ca) * sgn(dy);
+                                g[ch].z += (fabsf(dz) > xo[q][ch].z ? cf[q] : ca) * sgn(dz);
+                                g[ch].w += (fabsf(dw) > xo[q][ch].w ? cf[q] : ca) * sgn(dw);
+                            } else {
+                                g[ch].x += cf[q] * sgn(x[q][ch].x - p[ch].x);
+                                g[ch].y += cf[q] * sgn(x[q][ch].y - p[ch].y);
+                                g[ch].z += cf[q] * sgn(x[q][ch].z - p[ch].z);
+                                g[ch].w += cf[q] * sgn(x[q][ch].w - p[ch].w);
+                            }
                         }
                 }
                 continue;
@@ -187,6 +204,15 @@ __global__ __launch_bounds__(256) void table_kernel(const TableArgs a, const Ada
                 if (col_ok[ch])
                     brow[ch * 64 + lane] = make_uint2(bf16_bits(g[ch].x) | (bf16_bits(g[ch].y) << 16),
                                                       bf16_bits(g[ch].z) | (bf16_bits(g[ch].w) << 16));
+        }
+        if (a.relu_gate) {
+#pragma unroll
+            for (int ch = 0; ch < NCH; ++ch) {
+                g[ch].x = p[ch].x > 0.f ? g[ch].x : 0.f;
+                g[ch].y = p[ch].y > 0.f ? g[ch].y : 0.f;
+                g[ch].z = p[ch].z > 0.f ? g[ch].z : 0.f;
+                g[ch].w = p[ch].w > 0.f ? g[ch].w : 0.f;
+            }
         }
         if (!update) {
             float4* orow = reinterpret_cast<float4*>(a.g_out + (size_t)u * a.d);
@@ -228,11 +254,13 @@ hipError_t launch_table_update(const TableArgs& a, const AdamHyper& hp, hipStrea
     // the number of touched rows is only known on the device: a fixed grid walks them
     const int blocks = 256 * 8;
     if (a.d > 1024 || (a.g_bf16 != nullptr) != (a.mask != nullptr)) return hipErrorInvalidValue;
-    const bool sem = a.g_bf16 != nullptr;
-#define NGDB_TABLE(NCH)                                                                              \
-    do {                                                                                             \
-        if (sem) hipLaunchKernelGGL((table_kernel<NCH, true>), dim3(blocks), dim3(256), 0, s, a, hp); \
-        else hipLaunchKernelGGL((table_kernel<NCH, false>), dim3(blocks), dim3(256), 0, s, a, hp);   \
+    const bool sem = a.g_bf16 != nullptr, box = a.off != nullptr;
+    if (sem && (box || a.relu_gate)) return hipErrorInvalidValue;
+#define NGDB_TABLE(NCH)                                                                                      \
+    do {                                                                                                     \
+        if (sem) hipLaunchKernelGGL((table_kernel<NCH, true, false>), dim3(blocks), dim3(256), 0, s, a, hp); \
+        else if (box) hipLaunchKernelGGL((table_kernel<NCH, false, true>), dim3(blocks), dim3(256), 0, s, a, hp); \
+        else hipLaunchKernelGGL((table_kernel<NCH, false, false>), dim3(blocks), dim3(256), 0, s, a, hp);   \
     } while (0)
     if (a.d <= 256) NGDB_TABLE(1);
     else if (a.d <= 512) NGDB_TABLE(2);
