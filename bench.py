@@ -40,18 +40,21 @@ MEASURED_TRAFFIC = {
 }
 
 
-def cpu_baseline(cfg, kg, sample, sem_bits):
+def cpu_baseline(cfg, kg, sample, sem_bits, box_alpha=None):
     """The oracle as it stands, full steps (loss, gradients, Adam) on batches of `sample` queries
     until about 10 s of CPU time have passed (at most 16 steps), single process with BLAS held
     to one thread."""
+    from oracle import box as ob
     from oracle import model as om
     try:
         from threadpoolctl import threadpool_limits
     except Exception:                      # pragma: no cover
         threadpool_limits = None
-    P = om.to_f64(wl.make_params(cfg.N, cfg.R, cfg.d, cfg.h, cfg.seed + 3, d_sem=cfg.d_sem))
+    box = box_alpha is not None
+    P = om.to_f64(wl.make_box_params(cfg.N, cfg.R, cfg.d, cfg.h, cfg.seed + 3) if box else
+                  wl.make_params(cfg.N, cfg.R, cfg.d, cfg.h, cfg.seed + 3, d_sem=cfg.d_sem))
     st = om.new_state(P)
-    hp = dict(lr=cfg.lr, beta1=cfg.beta1, beta2=cfg.beta2, eps=cfg.eps, gamma=cfg.gamma)
+    hp = dict(lr=cfg.lr, beta1=cfg.beta1, beta2=cfg.beta2, eps=cfg.eps, gamma=cfg.gamma, alpha=box_alpha)
 
     def run():
         total, steps = 0.0, 0
@@ -59,7 +62,10 @@ def cpu_baseline(cfg, kg, sample, sem_bits):
             qb = wl.make_batch(kg, sample, cfg.mix, cfg.seed + 100 + steps)
             negs = wl.make_negatives(cfg.N, sample, cfg.K, cfg.seed + 200 + steps)
             t0 = time.perf_counter()
-            om.train_step(qb, negs, P, st, steps + 1, hp, sem_bits)
+            if box:
+                ob.train_step(qb, negs, P, st, steps + 1, hp)
+            else:
+                om.train_step(qb, negs, P, st, steps + 1, hp, sem_bits)
             total += time.perf_counter() - t0
             steps += 1
         return total, steps
@@ -79,7 +85,7 @@ def say(msg):
     print("[bench] " + msg, file=sys.stderr, flush=True)
 
 
-def kernel_models(cfg, pexp, touched):
+def kernel_models(cfg, pexp, touched, box=False):
     """Algorithmic work of one step per kernel class: what the method itself has to move or
     multiply, whatever the kernels do.  Returns {class: (bound, amount, peak, unit)} with
     amounts in bytes (hbm) or flops (mfma)."""
@@ -96,6 +102,9 @@ def kernel_models(cfg, pexp, touched):
     table_bytes = touched * 6 * row + n_contrib * 12 + pexp["n_anchor"] * row
     if sem:
         table_bytes += touched * (row + 2 * cfg.d)
+    if box:   # boxes at the roots are two rows wide; two MLPs over the inputs of the intersections, none elsewhere
+        score_bytes += pexp["n_roots"] * 2 * row
+        mlp_rows = 2 * pexp["n_int_rows"]
     mlp_flops = 4 * cfg.d * cfg.h * mlp_rows       # two layers, 2 flops per multiply-add
     models = {
         "score": ("hbm", score_bytes, HBM_PEAK_GBS, "GB/s"),
@@ -192,6 +201,10 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=-1, help="queries timed on the CPU oracle (0 = skip)")
     ap.add_argument("--schedule", choices=("level", "max_fill"), default="level",
                     help="order of execution of the operators (max_fill: the ready-set loop of Alg. 1)")
+    ap.add_argument("--family", choices=("vec", "box"), default="vec",
+                    help="operator family: the vector model of the headline workload, or box embeddings (Q2B "
+                         "operators) on the 9 negation-free structures of the same workload")
+    ap.add_argument("--box-alpha", type=float, default=0.02, help="weight of the inside distance (box family)")
     ap.add_argument("--bmax", type=int, default=0, help="largest batch of one Max-Fillness step, 0 = unbounded")
     ap.add_argument("--sampler", type=int, default=0, metavar="THREADS",
                     help="draw every batch (queries and negatives) inside the run with the library's online sampler "
@@ -210,6 +223,13 @@ def main():
         sys.exit(2)
 
     cfg = wl.get_config(args.config)
+    box = args.family == "box"
+    if box:
+        if cfg.d_sem or args.rank:
+            print("bench.py: the box family has no text features and no ranking pass", file=sys.stderr)
+            sys.exit(2)
+        import dataclasses
+        cfg = dataclasses.replace(cfg, mix={n: 1.0 / len(wl.EPFO9) for n in wl.EPFO9})
     say("generating the graph (N=%d, T=%d)" % (cfg.N, cfg.T))
     kg = wl.make_kg(cfg.N, cfg.R, cfg.T, cfg.alpha, cfg.seed)
     if args.rank:
@@ -219,14 +239,15 @@ def main():
     say("generating %d batches of %d queries, negatives, parameters" % (N_BATCHES, cfg.B))
     batches = [wl.make_batch(kg, cfg.B, cfg.mix, cfg.seed + 10 + i) for i in range(N_BATCHES)]
     negs_np = [wl.make_negatives(cfg.N, cfg.B, cfg.K, cfg.seed + 50 + i) for i in range(N_BATCHES)]
-    params = wl.make_params(cfg.N, cfg.R, cfg.d, cfg.h, cfg.seed + 3, d_sem=cfg.d_sem)
+    params = (wl.make_box_params(cfg.N, cfg.R, cfg.d, cfg.h, cfg.seed + 3) if box else
+              wl.make_params(cfg.N, cfg.R, cfg.d, cfg.h, cfg.seed + 3, d_sem=cfg.d_sem))
     sem_bits = wl.make_sem_features(cfg.N, cfg.d_sem, cfg.seed + 5) if cfg.d_sem else None
 
     # CPU oracle first, before this process touches the GPU
     default_sample = 512 if cfg.K <= 128 else (8 if cfg.d_sem else 64)
     sample = args.cpu_sample if args.cpu_sample >= 0 else min(cfg.B, default_sample)
     say("CPU oracle on %d queries" % sample)
-    cpu = cpu_baseline(cfg, kg, sample, sem_bits) if sample > 0 else None
+    cpu = cpu_baseline(cfg, kg, sample, sem_bits, args.box_alpha if box else None) if sample > 0 else None
     say("uploading parameters")
 
     import torch
@@ -234,7 +255,7 @@ def main():
     streams = args.streams or cfg.streams
     eng = Engine(cfg.N, cfg.R, cfg.d, cfg.h, cfg.gamma, lr=cfg.lr, beta1=cfg.beta1, beta2=cfg.beta2, eps=cfg.eps,
                  num_streams=streams, d_sem=cfg.d_sem, schedule={"level": 0, "max_fill": 1}[args.schedule],
-                 b_max=args.bmax)
+                 b_max=args.bmax, family=1 if box else 0, box_alpha=args.box_alpha)
     eng.bind_numpy(params, sem_bits=sem_bits)
     del params, sem_bits
     negs = [torch.from_numpy(n).cuda() for n in negs_np]
@@ -325,7 +346,7 @@ def main():
 
     # roofline per kernel class: algorithmic work of one step / measured time of the class per step.
     # The three contraction classes are launches of one kernel and are reported together as "gemm".
-    models = kernel_models(cfg, pexp, touched)
+    models = kernel_models(cfg, pexp, touched, box)
     kern = {}
     for name, (bound, amount, peak, unit) in models.items():
         ms, n = timing[name]
@@ -345,7 +366,7 @@ def main():
         k["frac"] = k["achieved"] / k["peak"]
     dom = max(kern, key=lambda k: kern[k]["ms_per_step"])
     kd = kern[dom]
-    traffic = MEASURED_TRAFFIC.get((cfg.index, dom))
+    traffic = None if box else MEASURED_TRAFFIC.get((cfg.index, dom))
     roofline = {"bound": kd["bound"], "kernel": dom, "achieved": kd["achieved"], "peak": kd["peak"],
                 "unit": kd["unit"], "frac": kd["frac"], "traffic": traffic,
                 "avg_us": kd["avg_us"], "launches_per_step": kd["launches_per_step"],
@@ -367,9 +388,11 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": "configs[%d] %s: N=%d R=%d d=%d h=%d B=%d K=%d%s, 14-structure mix, gamma=%g"
+        "config": {"workload": "configs[%d] %s: N=%d R=%d d=%d h=%d B=%d K=%d%s, %s, gamma=%g"
                    % (cfg.index, cfg.name, cfg.N, cfg.R, cfg.d, cfg.h, cfg.B, cfg.K,
-                      " d_sem=%d (bf16 text features)" % cfg.d_sem if cfg.d_sem else "", cfg.gamma),
+                      " d_sem=%d (bf16 text features)" % cfg.d_sem if cfg.d_sem else "",
+                      "box family (alpha=%g) on the 9 negation-free structures" % args.box_alpha if box
+                      else "14-structure mix", cfg.gamma),
                    "streams": streams,
                    "schedule": args.schedule if args.schedule == "level" else "max_fill, B_max=%s" % (args.bmax or "inf"),
                    "steps_per_batch": pexp["n_levels"], "peak_live_outputs": pexp["peak_live"],
