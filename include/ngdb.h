@@ -123,10 +123,15 @@ typedef struct ngdb_config {
     int32_t h;             /* hidden width of the three MLPs (multiple of 4)         */
     int32_t d_sem;         /* width of the frozen text features, 0 = none; otherwise
                               a multiple of 64, and d a multiple of 8                */
-    int32_t num_streams;   /* 1 = everything on the caller's stream; 2..4 = the
-                              independent operator groups of one depth run on this
-                              many library-owned streams (Sec. 4.3 "Multi-stream
-                              Operator Execution")                                    */
+    int32_t num_streams;   /* 1 = everything on the caller's stream; 2..4 = one
+                              library-owned stream takes the work that does not depend
+                              on the operator chain: the gradient index is built beside
+                              the forward pass and the embedding tables are updated
+                              beside the weight gradients (Sec. 4.3 "Multi-stream
+                              Operator Execution"; the operator groups of one depth
+                              already share one launch).  Results are identical, and
+                              everything is joined to the caller's stream before the
+                              call returns                                           */
     float gamma;
     float lr, beta1, beta2, eps;
     int32_t schedule;      /* NGDB_SCHED_* used by ngdb_plan                          */

@@ -65,10 +65,9 @@ struct ngdb_ctx_s {
     bool bound = false;
     int64_t step = 0;
     std::string err;
-    hipStream_t side[4]{};
+    hipStream_t side[1]{};          // library stream (num_streams > 1)
     hipEvent_t ev_fork = nullptr;
-    hipEvent_t ev_index = nullptr;
-    hipEvent_t ev_join[4]{};
+    hipEvent_t ev_join = nullptr;
     int n_side = 0;
     // workspace
     DevBuf act, dact, Z[3], H[3], dH[3], Att, dAtt, Dx;
@@ -180,38 +179,6 @@ MlpRefs mlp_of(const ngdb_params& p, int t) {
 }
 // order of ngdb_grad_view::g_mlp: W1 b1 W2 b2 | V1 c1 V2 c2 | U1 u1 U2 u2
 int gslot_of(int t) { return t == T_PROJ ? 0 : (t == T_NEG ? 4 : 8); }
-
-// Streams of one step: `main` is the caller's; with num_streams > 1 the type
-// segments of a level run on library streams between a fork and a join.
-struct Lanes {
-    ngdb_ctx_t* c;
-    hipStream_t main;
-    int forked = 0;
-    hipStream_t pick(int i) const { return c->n_side > 1 ? c->side[i % c->n_side] : main; }
-    hipError_t fork(int n) {
-        forked = 0;
-        if (c->n_side <= 1 || n <= 1) return hipSuccess;
-        hipError_t e = hipEventRecord(c->ev_fork, main);
-        if (e != hipSuccess) return e;
-        forked = std::min(n, c->n_side);
-        for (int i = 0; i < forked; ++i) {
-            e = hipStreamWaitEvent(c->side[i], c->ev_fork, 0);
-            if (e != hipSuccess) return e;
-        }
-        return hipSuccess;
-    }
-    hipStream_t lane(int i) const { return forked ? c->side[i % forked] : main; }
-    hipError_t join() {
-        for (int i = 0; i < forked; ++i) {
-            hipError_t e = hipEventRecord(c->ev_join[i], c->side[i]);
-            if (e != hipSuccess) return e;
-            e = hipStreamWaitEvent(main, c->ev_join[i], 0);
-            if (e != hipSuccess) return e;
-        }
-        forked = 0;
-        return hipSuccess;
-    }
-};
 
 int size_workspace(ngdb_ctx_t* c, const ngdb_plan_t* pl, int K, bool want_table_grads) {
     const HostPlan& hp = pl->hp;
@@ -470,12 +437,21 @@ int enqueue_forward(ngdb_ctx_t* c, const ngdb_plan_t* pl, const EntRows& er, hip
     return NGDB_OK;
 }
 
+struct WgradJob {   // what enqueue_weight_grads needs after a backward chain
+    int nt = 0;
+    int types[3]{};
+    size_t rows[3]{};
+    const float* dY[3]{};
+};
+
 // Gradients of the MLP tensors of the given types (their Z / H / dH buffers, dY = gradient of
 // the second layer's output): both weight matrices of every type in one grouped launch, the
 // biases as column sums.
-int enqueue_weight_grads(ngdb_ctx_t* c, const int* types, int nt, const size_t* rows, const float* const* dY,
-                         hipStream_t s) {
-    const int d = c->cfg.d, h = c->cfg.h;
+int enqueue_weight_grads(ngdb_ctx_t* c, const WgradJob& wj, hipStream_t s) {
+    const int d = c->cfg.d, h = c->cfg.h, nt = wj.nt;
+    const int* types = wj.types;
+    const size_t* rows = wj.rows;
+    const float* const* dY = wj.dY;
     float* gW = ptr<float>(c->gW);
     Timed tm(c, NGDB_TK_WGRAD, s);
     GemmArgs w[6];
@@ -500,10 +476,10 @@ int enqueue_weight_grads(ngdb_ctx_t* c, const int* types, int nt, const size_t* 
     return NGDB_OK;
 }
 
-// reversed frontiers, then the weight gradients of all three MLPs in one grouped launch
-int enqueue_backward_box(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t s);
-int enqueue_backward(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t s) {
-    if (c->cfg.family == NGDB_FAMILY_BOX) return enqueue_backward_box(c, pl, s);
+// reversed frontiers; *wj receives the inputs of the weight gradients (one grouped launch, later)
+int enqueue_backward_box(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t s, WgradJob* wj);
+int enqueue_backward(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t s, WgradJob* wj) {
+    if (c->cfg.family == NGDB_FAMILY_BOX) return enqueue_backward_box(c, pl, s, wj);
     const int d = c->cfg.d, h = c->cfg.h;
     const HostPlan& hp = pl->hp;
     float* dact = ptr<float>(c->dact);
@@ -549,16 +525,18 @@ int enqueue_backward(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t s) {
         { Timed tm(c, NGDB_TK_GEMM_BWD, s); HIPCHK(c, launch_gemm_group(b1, n, s)); }
     }
     // weight gradients: one contraction per tensor over all rows of the type
+    wj->nt = 3;
     const int types[3] = {T_PROJ, T_INTER, T_NEG};
     const size_t rows[3] = {(size_t)hp.n_proj, (size_t)hp.n_int_rows, (size_t)hp.n_neg};
     const float* dY[3] = {dact, ptr<float>(c->dAtt), dact + ((size_t)hp.n_proj + hp.n_inter) * d};
-    return enqueue_weight_grads(c, types, 3, rows, dY, s);
+    for (int i = 0; i < 3; ++i) { wj->types[i] = types[i]; wj->rows[i] = rows[i]; wj->dY[i] = dY[i]; }
+    return NGDB_OK;
 }
 
 // Box family, backward: the reverse of enqueue_forward_box; the gradient of a projection's
 // input is the gradient of its output (copied to the input's rows, where the relation tables
 // pick it up too).
-int enqueue_backward_box(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t s) {
+int enqueue_backward_box(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t s, WgradJob* wj) {
     const int d = c->cfg.d, h = c->cfg.h;
     const HostPlan& hp = pl->hp;
     for (int l = hp.n_levels; l >= 1; --l) {
@@ -601,10 +579,11 @@ int enqueue_backward_box(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t s) {
         { Timed tm(c, NGDB_TK_GEMM_BWD, s); HIPCHK(c, launch_gemm_group(b2, n, s)); }
         { Timed tm(c, NGDB_TK_GEMM_BWD, s); HIPCHK(c, launch_gemm_group(b1, n, s)); }
     }
-    const int types[2] = {T_INTER, T_NEG};
-    const size_t rows[2] = {(size_t)hp.n_int_rows, (size_t)hp.n_int_rows};
-    const float* dY[2] = {ptr<float>(c->dAtt), ptr<float>(c->dGate)};
-    return enqueue_weight_grads(c, types, 2, rows, dY, s);
+    wj->nt = 2;
+    wj->types[0] = T_INTER; wj->types[1] = T_NEG;
+    wj->rows[0] = wj->rows[1] = (size_t)hp.n_int_rows;
+    wj->dY[0] = ptr<float>(c->dAtt); wj->dY[1] = ptr<float>(c->dGate);
+    return NGDB_OK;
 }
 
 int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, hipStream_t stream, float* d_loss,
@@ -623,10 +602,12 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
 
     // 1. entity gradient index (depends only on the plan and the negatives)
     int32_t* e_src = nullptr;
-    // without text features the index is independent of the forward/backward passes: with library
-    // streams it runs beside them
+    // With a library stream two independent pieces leave the caller's stream: the index build runs
+    // beside the forward pass (without text features, where nothing before the tables needs it), and
+    // the table updates run beside the weight gradients and the dense Adam step.
     const bool sem = c->cfg.d_sem > 0;
-    const bool idx_aside = c->n_side && !sem;
+    const bool aside = c->n_side > 0;
+    const bool idx_aside = aside && !sem;
     hipStream_t s_idx = idx_aside ? c->side[0] : stream;
     if (idx_aside) {
         HIPCHK(c, hipEventRecord(c->ev_fork, stream));
@@ -635,7 +616,6 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
     EntRows er{};
     rc = prepare_entities(c, pl, d_neg, (int64_t)B * K, s_idx, stream, &e_src, &er);
     if (rc != NGDB_OK) return rc;
-    if (idx_aside) HIPCHK(c, hipEventRecord(c->ev_index, s_idx));
 
     // 2. forward frontiers
     rc = enqueue_forward(c, pl, er, stream);
@@ -655,10 +635,10 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
         if (e == hipErrorInvalidValue) return fail(c, NGDB_ERR_UNSUPPORTED, "embedding width / union branch count too large for the scoring kernel");
         HIPCHK(c, e);
     }
-    HIPCHK(c, launch_loss_reduce(ptr<float>(c->loss_terms), B, B > 0 ? 1.f / (2.f * B) : 0.f, d_loss, stream));
 
-    // 4. reversed frontiers + weight gradients
-    rc = enqueue_backward(c, pl, stream);
+    // 4. reversed frontiers
+    WgradJob wj;
+    rc = enqueue_backward(c, pl, stream, &wj);
     if (rc != NGDB_OK) return rc;
 
     // 5. table gradients (+ Adam), dense Adam
@@ -666,11 +646,17 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
     AdamHyper ah{c->cfg.lr, c->cfg.beta1, c->cfg.beta2, c->cfg.eps,
                  (float)(1.0 - std::pow((double)c->cfg.beta1, (double)t)),
                  (float)(1.0 - std::pow((double)c->cfg.beta2, (double)t))};
-    if (idx_aside) HIPCHK(c, hipStreamWaitEvent(stream, c->ev_index, 0));
+    hipStream_t s_tab = aside ? c->side[0] : stream;     // after the index on the same stream
+    if (aside) {
+        HIPCHK(c, hipEventRecord(c->ev_fork, stream));
+        HIPCHK(c, hipStreamWaitEvent(s_tab, c->ev_fork, 0));
+    }
+    // (the sum of the loss terms is off the critical path there)
+    HIPCHK(c, launch_loss_reduce(ptr<float>(c->loss_terms), B, B > 0 ? 1.f / (2.f * B) : 0.f, d_loss, s_tab));
     const int64_t n_contrib = (int64_t)hp.n_anchor + B + (int64_t)B * K;
     HIPCHK(c, launch_resolve(e_src, n_contrib, hp.n_anchor, hp.n_slots, B, K, ptr<float>(c->coef),
                              sem ? nullptr : ptr<int32_t>(c->win), ptr<float>(c->rec_coef), ptr<int32_t>(c->rec_row),
-                             stream));
+                             s_tab));
     TableArgs te{};
     te.P = c->prm.E.p; te.Mo = c->prm.E.m; te.Vo = c->prm.E.v;
     te.uniq = ptr<int32_t>(c->uniq); te.seg_off = ptr<int32_t>(c->seg_off);
@@ -684,17 +670,17 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
     tr.P = c->prm.R.p; tr.Mo = c->prm.R.m; tr.Vo = c->prm.R.v;
     tr.uniq = pl->d_r_uniq; tr.seg_off = pl->d_r_seg_off; tr.n_uniq_dev = pl->d_n_r_uniq;
     tr.rec_coef = nullptr; tr.rec_row = pl->d_r_rec; tr.g_out = apply ? nullptr : ptr<float>(c->gR);
-    Lanes L{c, stream};
-    HIPCHK(c, L.fork(3));
-    { Timed tm(c, NGDB_TK_TABLE_E, L.lane(0)); HIPCHK(c, launch_table_update(te, ah, L.lane(0))); }
-    { Timed tm(c, NGDB_TK_TABLE_R, L.lane(1)); HIPCHK(c, launch_table_update(tr, ah, L.lane(1))); }
+    { Timed tm(c, NGDB_TK_TABLE_E, s_tab); HIPCHK(c, launch_table_update(te, ah, s_tab)); }
+    { Timed tm(c, NGDB_TK_TABLE_R, s_tab); HIPCHK(c, launch_table_update(tr, ah, s_tab)); }
     if (box) {   // relation offsets: the same segments over the offset gradients, gated by relu
         TableArgs to = tr;
         to.P = c->prm.Ro.p; to.Mo = c->prm.Ro.m; to.Vo = c->prm.Ro.v;
         to.dact = ptr<float>(c->doff); to.relu_gate = true; to.g_out = apply ? nullptr : ptr<float>(c->gRo);
-        Timed tm(c, NGDB_TK_TABLE_R, L.lane(1));
-        HIPCHK(c, launch_table_update(to, ah, L.lane(1)));
+        Timed tm(c, NGDB_TK_TABLE_R, s_tab);
+        HIPCHK(c, launch_table_update(to, ah, s_tab));
     }
+    rc = enqueue_weight_grads(c, wj, stream);
+    if (rc != NGDB_OK) return rc;
     if (apply) {
         DenseAdamJob job{};
         const ngdb_tensor* ts[12] = {&c->prm.W1, &c->prm.b1, &c->prm.W2, &c->prm.b2, &c->prm.V1, &c->prm.c1,
@@ -707,10 +693,13 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
             job.g[k] = ptr<float>(c->gW) + c->gw_off[i];
             job.n[k] = sz[i % 4];
         }
-        Timed tm(c, NGDB_TK_ADAM, L.lane(2));
-        HIPCHK(c, launch_dense_adam(job, ah, L.lane(2)));
+        Timed tm(c, NGDB_TK_ADAM, stream);
+        HIPCHK(c, launch_dense_adam(job, ah, stream));
     }
-    HIPCHK(c, L.join());
+    if (aside) {
+        HIPCHK(c, hipEventRecord(c->ev_join, s_tab));
+        HIPCHK(c, hipStreamWaitEvent(stream, c->ev_join, 0));
+    }
     if (sem) {
         // gradient of the text projection over the touched rows, then its Adam step
         Timed tm(c, NGDB_TK_SEM, stream);
@@ -777,13 +766,11 @@ int ngdb_create(const ngdb_config* cfg, ngdb_ctx_t** out) {
     ngdb_ctx_t* c = new (std::nothrow) ngdb_ctx_s();
     if (!c) return NGDB_ERR_OOM;
     c->cfg = *cfg;
-    c->n_side = cfg->num_streams > 1 ? cfg->num_streams : 0;
+    c->n_side = cfg->num_streams > 1 ? 1 : 0;
     bool ok = true;
-    for (int i = 0; i < c->n_side && ok; ++i)
-        ok = hipStreamCreateWithFlags(&c->side[i], hipStreamNonBlocking) == hipSuccess &&
-             hipEventCreateWithFlags(&c->ev_join[i], hipEventDisableTiming) == hipSuccess;
+    if (c->n_side) ok = hipStreamCreateWithFlags(&c->side[0], hipStreamNonBlocking) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) == hipSuccess;
-    ok = ok && hipEventCreateWithFlags(&c->ev_index, hipEventDisableTiming) == hipSuccess;
     ok = ok && hipStreamCreateWithFlags(&c->upload, hipStreamNonBlocking) == hipSuccess;
     if (!ok) {
         ngdb_destroy(c);
@@ -803,12 +790,9 @@ void ngdb_destroy(ngdb_ctx_t* c) {
                      &c->Wb, &c->Ef, &c->inv, &c->refs_sem, &c->g_bf16, &c->wp_partial, &c->gWp, &c->rank_ef,
                      &c->off, &c->doff, &c->Gate, &c->dGate, &c->DxO, &c->gRo};
     for (DevBuf* b : all) release(*b);
-    for (int i = 0; i < 4; ++i) {
-        if (c->side[i]) (void)hipStreamDestroy(c->side[i]);
-        if (c->ev_join[i]) (void)hipEventDestroy(c->ev_join[i]);
-    }
+    if (c->side[0]) (void)hipStreamDestroy(c->side[0]);
+    if (c->ev_join) (void)hipEventDestroy(c->ev_join);
     if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
-    if (c->ev_index) (void)hipEventDestroy(c->ev_index);
     if (c->upload) (void)hipStreamDestroy(c->upload);
     for (PlanBlob& b : c->blob_pool) {
         if (b.dev) (void)hipFree(b.dev);

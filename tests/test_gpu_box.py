@@ -107,7 +107,7 @@ def test_box_candidate_scores():
 def test_box_fb15k237_shape_full_size():
     _say("box family at the FB15k-237 shape: N=15000 d=400 h=800 B=512 K=128")
     case = pb.BoxCase.from_config(1)
-    pb.check_forward_backward(case)
+    pb.check_forward_backward(case, eng=case.engine(num_streams=wl.get_config(1).streams))
 
 
 def test_box_errors():

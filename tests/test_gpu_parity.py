@@ -273,8 +273,9 @@ def test_fb15k237_shape_full_size():
     # the benchmark workload itself, in the launch configuration bench.py times
     _say("config 1 (B=512, K=128, d=400), forward_backward + 1 train step")
     case = par.Case.from_config(1)
-    par.check_forward_backward(case)
-    par.check_train_steps(case, steps=1)
+    streams = wl.get_config(1).streams                    # the launch configuration bench.py times
+    par.check_forward_backward(case, eng=case.engine(num_streams=streams))
+    par.check_train_steps(case, steps=1, num_streams=streams)
 
 
 def test_planning_on_a_second_thread_gives_the_same_parameters():

@@ -61,7 +61,7 @@ def _full_size_sampled(cfg, n_sample):
     B, K, d = cfg.B, cfg.K, cfg.d
 
     from paper_2602_21597_amd import Engine
-    eng = Engine(cfg.N, cfg.R, cfg.d, cfg.h, cfg.gamma, d_sem=cfg.d_sem)
+    eng = Engine(cfg.N, cfg.R, cfg.d, cfg.h, cfg.gamma, d_sem=cfg.d_sem, num_streams=cfg.streams)
     eng.bind_numpy(params, sem_bits=sem_bits)
     plan = eng.plan(qb)
     _say("plan + index, bit-exact")

@@ -76,7 +76,7 @@ class Config:
     eps: float = 1e-8
     mix: Dict[str, float] = field(default_factory=dict)
     d_sem: int = 0    # width of the frozen text feature (0 = none)
-    streams: int = 1  # HIP streams used for independent operator groups
+    streams: int = 2  # 1 = the caller's stream only; more = a library stream takes the independent work
     score_queries: int = 0   # all-entity ranking pass: number of queries
     topk: int = 0
 
@@ -87,7 +87,7 @@ class Config:
 
 CONFIGS: Tuple[Config, ...] = (
     Config("tiny", 0, N=1000, R=20, T=10_000, alpha=2.1, d=32, h=64, K=8, B=64,
-           gamma=12.0, mix=_uniform(("1p", "2p", "2i", "2in", "2u"))),
+           gamma=12.0, mix=_uniform(("1p", "2p", "2i", "2in", "2u")), streams=1),
     Config("fb15k237", 1, N=15_000, R=474, T=310_000, alpha=2.1, d=400, h=800,
            K=128, B=512, gamma=24.0, mix=_uniform(ALL14)),
     Config("nell", 2, N=63_000, R=400, T=140_000, alpha=2.1, d=400, h=800,
