@@ -122,9 +122,10 @@ VALU_PEAK_TOPS = 39.3     # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz, one fp32 op 
                           # (packed forms are switched off in this build)
 
 
-def rank_bench(args, cfg, kg, params, sem_bits):
+def rank_bench(args, cfg, kg, params, sem_bits, box=False):
     """All-entity ranking pass (ngdb_score without candidates): Q queries against every entity,
     top-10 by L1 distance.  One step = one pass.  Prints ONE JSON line."""
+    from oracle import box as ob
     from oracle import model as om
     from oracle import rank as orank
     Q, k = args.rank, 10
@@ -133,10 +134,10 @@ def rank_bench(args, cfg, kg, params, sem_bits):
     sample = args.cpu_sample if args.cpu_sample >= 0 else (2 if cfg.N <= 100000 else 0)
     if sample > 0:
         say("CPU oracle ranking of %d queries" % sample)
-        M = om.Model(params, cfg.gamma, sem_bits)
+        M = ob.BoxModel(params, cfg.gamma, args.box_alpha) if box else om.Model(params, cfg.gamma, sem_bits)
         t0 = time.perf_counter()
         for q in range(sample):
-            orank.topk_all(qb, q, M, k)
+            orank.topk_all(qb, q, M, k, ob.distances_all if box else orank.distances_all)
         dtc = time.perf_counter() - t0
         cpu = {"value": sample / dtc, "unit": "queries/s", "cores": os.cpu_count(), "kind": "oracle",
                "sample": "%d queries against all %d entities (fp64 numpy, BLAS threads as configured), %.1f s"
@@ -144,7 +145,8 @@ def rank_bench(args, cfg, kg, params, sem_bits):
         del M
     import torch
     from paper_2602_21597_amd import Engine
-    eng = Engine(cfg.N, cfg.R, cfg.d, cfg.h, cfg.gamma, d_sem=cfg.d_sem)
+    eng = Engine(cfg.N, cfg.R, cfg.d, cfg.h, cfg.gamma, d_sem=cfg.d_sem, family=1 if box else 0,
+                 box_alpha=args.box_alpha)
     eng.bind_numpy(params, sem_bits=sem_bits)
     plan = eng.plan(qb)
     rows = plan.export()["n_roots"]
@@ -170,8 +172,9 @@ def rank_bench(args, cfg, kg, params, sem_bits):
     for _ in range(args.steps):
         run()
     ms, n = eng.get_timing(reset=True)["score"]
-    # subtract and |.|-accumulate per coordinate, branch row and entity
-    ops = 2.0 * rows * cfg.N * cfg.d
+    # subtract and |.|-accumulate per coordinate, branch row and entity (box distance: subtract,
+    # scale, subtract the shrunk offset, maximum, accumulate)
+    ops = (5.0 if box else 2.0) * rows * cfg.N * cfg.d
     ach = ops / (ms / n * 1e-3) / 1e12
     what = "top-%d" % k if args.answers <= 0 else "filtered ranks of %d answers per query, MRR, Hit@k" % args.answers
     out = {"metric": "all-entity ranking queries/sec (forward + L1 distance to every entity + %s)" % what,
@@ -179,8 +182,8 @@ def rank_bench(args, cfg, kg, params, sem_bits):
            "ms_per_step": 1e3 * dt, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "f32", "data": "synthetic",
            "config": {"workload": "configs[%d] %s ranking pass: %d queries (%d branch rows) x N=%d entities, d=%d%s, top-%d"
-                      % (cfg.index, cfg.name, Q, rows, cfg.N, cfg.d,
-                         " d_sem=%d" % cfg.d_sem if cfg.d_sem else "", k), "evaluation": what},
+                      % (cfg.index, cfg.name + (" (box family, alpha=%g)" % args.box_alpha if box else ""), Q, rows,
+                         cfg.N, cfg.d, " d_sem=%d" % cfg.d_sem if cfg.d_sem else "", k), "evaluation": what},
            "roofline": {"bound": "alu", "kernel": "rank (distance tiles + %s%s)" % (
                             "top-k merge" if args.answers <= 0 else "closer-entity counts",
                             " + projection of every entity chunk" if cfg.d_sem else ""),
@@ -225,17 +228,18 @@ def main():
     cfg = wl.get_config(args.config)
     box = args.family == "box"
     if box:
-        if cfg.d_sem or args.rank:
-            print("bench.py: the box family has no text features and no ranking pass", file=sys.stderr)
+        if cfg.d_sem:
+            print("bench.py: the box family has no text features", file=sys.stderr)
             sys.exit(2)
         import dataclasses
         cfg = dataclasses.replace(cfg, mix={n: 1.0 / len(wl.EPFO9) for n in wl.EPFO9})
     say("generating the graph (N=%d, T=%d)" % (cfg.N, cfg.T))
     kg = wl.make_kg(cfg.N, cfg.R, cfg.T, cfg.alpha, cfg.seed)
     if args.rank:
-        params = wl.make_params(cfg.N, cfg.R, cfg.d, cfg.h, cfg.seed + 3, d_sem=cfg.d_sem)
+        params = (wl.make_box_params(cfg.N, cfg.R, cfg.d, cfg.h, cfg.seed + 3) if box else
+                  wl.make_params(cfg.N, cfg.R, cfg.d, cfg.h, cfg.seed + 3, d_sem=cfg.d_sem))
         sem_bits = wl.make_sem_features(cfg.N, cfg.d_sem, cfg.seed + 5) if cfg.d_sem else None
-        return rank_bench(args, cfg, kg, params, sem_bits)
+        return rank_bench(args, cfg, kg, params, sem_bits, box)
     say("generating %d batches of %d queries, negatives, parameters" % (N_BATCHES, cfg.B))
     batches = [wl.make_batch(kg, cfg.B, cfg.mix, cfg.seed + 10 + i) for i in range(N_BATCHES)]
     negs_np = [wl.make_negatives(cfg.N, cfg.B, cfg.K, cfg.seed + 50 + i) for i in range(N_BATCHES)]

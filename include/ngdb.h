@@ -46,8 +46,7 @@
  *   tensors       E, R, Ro [n_relations, d] (row-sparse Adam), V1 c1 V2 c2, U1 u1 U2 u2;
  *                 W1 b1 W2 b2, Wp and H_sem are not read.  An intersection input must be
  *                 an operator output (true of every pattern of Sec. 3.1).
- *   not available in this family: text features (d_sem must be 0), the all-entity mode
- *                 of ngdb_score and ngdb_rank_answers (NGDB_ERR_UNSUPPORTED).
+ *   not available in this family: text features (d_sem must be 0).
  *
  * Conventions
  *   - Every call returns 0 (NGDB_OK) or a negative error code; nothing throws
@@ -137,7 +136,7 @@ typedef struct ngdb_config {
     int32_t schedule;      /* NGDB_SCHED_* used by ngdb_plan                          */
     int32_t b_max;         /* largest batch of one Max-Fillness step, 0 = unbounded   */
     int32_t family;        /* NGDB_FAMILY_*                                           */
-    float box_alpha;       /* weight of the inside distance (box family), >= 0        */
+    float box_alpha;       /* weight of the inside distance (box family), 0..1        */
 } ngdb_config;
 
 /* A trainable tensor with its Adam moments (all device, fp32, same shape). */

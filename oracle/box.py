@@ -146,6 +146,19 @@ def score(C, O, rows, gamma, alpha):
     return gamma - dist[win, np.arange(dist.shape[1])], win
 
 
+def distances_all(batch, i, M, chunk=8192):
+    """Box distance of query i to every entity (minimum over its branches), [N]."""
+    fw = [forward(b, M) for b in dnf(query_tree(batch.query_nodes(i)))]
+    C = np.stack([c for c, _, _ in fw])
+    O = np.stack([o for _, o, _ in fw])
+    N = M.P["E"].shape[0]
+    out = np.empty(N, np.float64)
+    for lo in range(0, N, chunk):
+        hi = min(N, lo + chunk)
+        out[lo:hi] = box_distance(C, O, M.P["E"][lo:hi], M.alpha).min(axis=0)
+    return out
+
+
 def query_step(nodes, pos, negs, M, B, G=None):
     if any(op == OP_NEG for op, _, _ in nodes):
         raise Unsupported("the box family has no negation")

@@ -36,19 +36,20 @@ def distances_all(batch, i, M, chunk=8192):
     return out
 
 
-def topk_all(batch, i, M, k):
-    """(ids, distances) of the k nearest entities: full sort, ties by id."""
-    dist = distances_all(batch, i, M)
+def topk_all(batch, i, M, k, distances=distances_all):
+    """(ids, distances) of the k nearest entities: full sort, ties by id.  `distances` gives the
+    distance of query i to every entity (the box family passes its own)."""
+    dist = distances(batch, i, M)
     order = np.lexsort((np.arange(dist.shape[0]), dist))[:k]
     return order.astype(np.int64), dist[order]
 
 
-def filtered_ranks(batch, i, answers, M):
+def filtered_ranks(batch, i, answers, M, distances=distances_all):
     """Filtered rank of every listed answer of query i [the evaluation protocol behind the
     filtered MRR / Hit@k the paper reports, Sec. 5.3 and the large-KG table]: an answer's rank
     is 1 + the number of entities that are NOT listed answers of the query and lie strictly
     closer to the query than it does.  Returns (ranks [len(answers)], distances of the answers)."""
-    dist = distances_all(batch, i, M)
+    dist = distances(batch, i, M)
     answers = np.asarray(answers, np.int64)
     other = np.ones(dist.shape[0], bool)
     other[answers] = False

@@ -761,7 +761,7 @@ int ngdb_create(const ngdb_config* cfg, ngdb_ctx_t** out) {
     if (cfg->d_sem != 0 && ((cfg->d_sem & 63) || (cfg->d & 7))) return NGDB_ERR_ARG;
     if ((cfg->schedule != NGDB_SCHED_LEVEL && cfg->schedule != NGDB_SCHED_MAX_FILL) || cfg->b_max < 0) return NGDB_ERR_ARG;
     if (cfg->family != NGDB_FAMILY_VEC && cfg->family != NGDB_FAMILY_BOX) return NGDB_ERR_ARG;
-    if (cfg->family == NGDB_FAMILY_BOX && (cfg->d_sem != 0 || !(cfg->box_alpha >= 0.f) || !std::isfinite(cfg->box_alpha)))
+    if (cfg->family == NGDB_FAMILY_BOX && (cfg->d_sem != 0 || !(cfg->box_alpha >= 0.f && cfg->box_alpha <= 1.f)))
         return NGDB_ERR_ARG;
     ngdb_ctx_t* c = new (std::nothrow) ngdb_ctx_s();
     if (!c) return NGDB_ERR_OOM;
@@ -1024,8 +1024,6 @@ int ngdb_score(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_cand, int3
         if (C <= 0 || !d_scores) return fail(c, NGDB_ERR_ARG, "candidate mode needs C > 0 and d_scores");
     } else if (topk < 1 || topk > NGDB_MAX_TOPK || !d_topk_ids || !d_topk_dist) {
         return fail(c, NGDB_ERR_ARG, "all-entity mode needs 1 <= topk <= NGDB_MAX_TOPK and both output arrays");
-    } else if (c->cfg.family == NGDB_FAMILY_BOX) {
-        return fail(c, NGDB_ERR_UNSUPPORTED, "the all-entity ranking is not available in the box family");
     }
     c->have_grads = false;
     const bool sem = c->cfg.d_sem > 0;
@@ -1052,6 +1050,7 @@ int ngdb_score(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_cand, int3
     } else {
         // entity chunks: distances of every branch row to the chunk, then the running top-k
         const int N = c->cfg.n_entities, d = c->cfg.d, R = pl->hp.n_roots;
+        const float* box_off = c->cfg.family == NGDB_FAMILY_BOX ? ptr<float>(c->off) : nullptr;
         const int chunk = std::min(N, 1 << 16);
         const int ld = (chunk + 3) & ~3;
         rc = ensure(c, c->rank_dist, std::max<size_t>((size_t)R * ld * sizeof(float), 256));
@@ -1071,7 +1070,7 @@ int ngdb_score(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_cand, int3
                 HIPCHK(c, launch_sem_fuse(fa, s));
                 rows = ptr<float>(c->rank_ef);
             }
-            HIPCHK(c, launch_l1_tile(ptr<float>(c->act), pl->d_root_slot, R, rows, nullptr, cnt, d,
+            HIPCHK(c, launch_l1_tile(ptr<float>(c->act), box_off, c->cfg.box_alpha, pl->d_root_slot, R, rows, nullptr, cnt, d,
                                      ptr<float>(c->rank_dist), ld, s));
             HIPCHK(c, launch_topk_merge(ptr<float>(c->rank_dist), ld, pl->d_root_off, pl->hp.n_queries, e0, cnt, topk,
                                         e0 == 0, d_topk_dist, d_topk_ids, s));
@@ -1090,7 +1089,6 @@ int ngdb_rank_answers(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_ans
     if (n_ans < 0 || !d_ans_off || (n_ans > 0 && (!d_ans || !d_rank)))
         return fail(c, NGDB_ERR_ARG, "answer lists / rank output missing");
     if (pl->hp.n_queries > 65535) return fail(c, NGDB_ERR_UNSUPPORTED, "more than 65535 queries in one ranking call");
-    if (c->cfg.family == NGDB_FAMILY_BOX) return fail(c, NGDB_ERR_UNSUPPORTED, "filtered ranking is not available in the box family");
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool sem = c->cfg.d_sem > 0;
     c->have_grads = false;
@@ -1106,6 +1104,7 @@ int ngdb_rank_answers(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_ans
     if (rc != NGDB_OK) return rc;
     if (n_ans > 0) {
         const int N = c->cfg.n_entities, d = c->cfg.d, R = pl->hp.n_roots, B = pl->hp.n_queries;
+        const float* box_off = c->cfg.family == NGDB_FAMILY_BOX ? ptr<float>(c->off) : nullptr;
         const int chunk = std::min(std::max(N, n_ans), 1 << 16);
         const int ld = (chunk + 3) & ~3;
         if ((rc = ensure(c, c->rank_dist, std::max<size_t>((size_t)R * ld * sizeof(float), 256))) != NGDB_OK) return rc;
@@ -1130,7 +1129,7 @@ int ngdb_rank_answers(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_ans
                 rows = ptr<float>(c->rank_ef);
                 ids = nullptr;
             }
-            HIPCHK(c, launch_l1_tile(ptr<float>(c->act), pl->d_root_slot, R, rows, ids, cnt, d,
+            HIPCHK(c, launch_l1_tile(ptr<float>(c->act), box_off, c->cfg.box_alpha, pl->d_root_slot, R, rows, ids, cnt, d,
                                      ptr<float>(c->rank_dist), ld, s));
             HIPCHK(c, launch_answer_dist(ptr<float>(c->rank_dist), ld, pl->d_root_off, d_ans_off, B, a0, cnt, thr, s));
         }
@@ -1143,7 +1142,7 @@ int ngdb_rank_answers(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_ans
                 HIPCHK(c, launch_sem_fuse(fa, s));
                 rows = ptr<float>(c->rank_ef);
             }
-            HIPCHK(c, launch_l1_tile(ptr<float>(c->act), pl->d_root_slot, R, rows, nullptr, cnt, d,
+            HIPCHK(c, launch_l1_tile(ptr<float>(c->act), box_off, c->cfg.box_alpha, pl->d_root_slot, R, rows, nullptr, cnt, d,
                                      ptr<float>(c->rank_dist), ld, s));
             HIPCHK(c, launch_count_less(ptr<float>(c->rank_dist), ld, pl->d_root_off, d_ans_off, thr, B, cnt,
                                         ptr<int32_t>(c->rank_count), s));

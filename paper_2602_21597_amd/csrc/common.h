@@ -170,9 +170,10 @@ struct ScoreArgs {
 hipError_t launch_score(const ScoreArgs& a, bool train, hipStream_t s);
 
 // ---------------------------------------------------------------- ranking (rank.hip)
-// dist[r*ld + e] = ||act[row_ids[r]] - Emat[id(e)]||_1 for r < n_rows, e < n_ent; id(e) = ent_ids[e] or e
-hipError_t launch_l1_tile(const float* act, const int32_t* row_ids, int n_rows, const float* Emat,
-                          const int32_t* ent_ids, int n_ent, int d, float* dist, int ld, hipStream_t s);
+// dist[r*ld + e] = ||act[row_ids[r]] - Emat[id(e)]||_1 for r < n_rows, e < n_ent; id(e) = ent_ids[e] or e.
+// With off (box family, 0 <= alpha <= 1): the box distance of (act row, off row) to the entity row.
+hipError_t launch_l1_tile(const float* act, const float* off, float alpha, const int32_t* row_ids, int n_rows,
+                          const float* Emat, const int32_t* ent_ids, int n_ent, int d, float* dist, int ld, hipStream_t s);
 // filtered ranks of listed answers (answers of query q: ans_off[q]..ans_off[q+1]-1):
 // thr[a] = distance of answer a (column a - a0 of dist) to its query, min over the query's rows
 hipError_t launch_answer_dist(const float* dist, int ld, const int32_t* root_off, const int32_t* ans_off, int n_queries,

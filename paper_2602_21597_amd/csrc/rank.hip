@@ -26,18 +26,25 @@ constexpr int TQ = 128, TE = 128, DC = 16, LDT = 128 + 4;
 // entity e of the tile is row ent_ids[e] of Emat if ent_ids is given, else row e.  The
 // distance of a (row, entity) pair is summed by one lane over the coordinates in ascending
 // order, so its value does not depend on where in a tile, or in which launch, the pair falls.
-__global__ __launch_bounds__(256) void l1_tile_kernel(const float* __restrict__ act, const int32_t* __restrict__ row_ids,
+// BOX (box family): the row side is a box, centre from act and offset from off, and a coordinate
+// contributes relu(a - o) + alpha * min(a, o) = max(alpha * a, a - (1 - alpha) * o), a = |e - c|;
+// the offsets are staged already multiplied by (1 - alpha): five VALU operations per coordinate.
+template <bool BOX>
+__global__ __launch_bounds__(256) void l1_tile_kernel(const float* __restrict__ act, const float* __restrict__ off,
+                                                      float alpha, const int32_t* __restrict__ row_ids,
                                                       int n_rows, const float* __restrict__ Emat,
                                                       const int32_t* __restrict__ ent_ids, int n_ent, int d,
                                                       float* __restrict__ dist, int ld) {
     __shared__ __attribute__((aligned(16))) float Ys[2][DC][LDT];
     __shared__ __attribute__((aligned(16))) float Es[2][DC][LDT];
+    __shared__ __attribute__((aligned(16))) float Os[BOX ? 2 : 1][BOX ? DC : 1][LDT];
     const int tid = threadIdx.x;
     const int tx = tid & 15, ty = tid >> 4;
     const int e0 = blockIdx.x * TE, r0 = blockIdx.y * TQ;
 
     // loader: 128 rows x 16 coordinates = 512 float4, two per thread and operand
     const float* yrow[2];
+    const float* orow[2];
     const float* erow[2];
     int lrow[2], lkq[2];
 #pragma unroll
@@ -47,16 +54,19 @@ __global__ __launch_bounds__(256) void l1_tile_kernel(const float* __restrict__ 
         lkq[i] = idx & 3;
         const int r = min(r0 + lrow[i], n_rows - 1);          // clamped rows are computed and never stored
         yrow[i] = act + (size_t)row_ids[r] * d;
+        orow[i] = BOX ? off + (size_t)row_ids[r] * d : nullptr;
         const int ec = min(e0 + lrow[i], n_ent - 1);
         erow[i] = Emat + (size_t)(ent_ids ? ent_ids[ec] : ec) * d;
     }
-    float4 ry[2], re[2];
+    float4 ry[2], re[2], ro[2];
+    const float shrink = 1.f - alpha;
     auto issue = [&](int k0) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int kc = min(k0 + lkq[i] * 4, d - 4);
             ry[i] = *reinterpret_cast<const float4*>(yrow[i] + kc);
             re[i] = *reinterpret_cast<const float4*>(erow[i] + kc);
+            if (BOX) ro[i] = *reinterpret_cast<const float4*>(orow[i] + kc);
         }
     };
     auto stage = [&](int buf, int k0) {
@@ -70,6 +80,11 @@ __global__ __launch_bounds__(256) void l1_tile_kernel(const float* __restrict__ 
             Ys[buf][lkq[i] * 4 + 2][lrow[i]] = y.z; Ys[buf][lkq[i] * 4 + 3][lrow[i]] = y.w;
             Es[buf][lkq[i] * 4 + 0][lrow[i]] = e.x; Es[buf][lkq[i] * 4 + 1][lrow[i]] = e.y;
             Es[buf][lkq[i] * 4 + 2][lrow[i]] = e.z; Es[buf][lkq[i] * 4 + 3][lrow[i]] = e.w;
+            if (BOX) {
+                const float4 o = ok ? ro[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+                Os[buf][lkq[i] * 4 + 0][lrow[i]] = shrink * o.x; Os[buf][lkq[i] * 4 + 1][lrow[i]] = shrink * o.y;
+                Os[buf][lkq[i] * 4 + 2][lrow[i]] = shrink * o.z; Os[buf][lkq[i] * 4 + 3][lrow[i]] = shrink * o.w;
+            }
         }
     };
 
@@ -94,10 +109,23 @@ __global__ __launch_bounds__(256) void l1_tile_kernel(const float* __restrict__ 
             const float4 x1 = *reinterpret_cast<const float4*>(&Es[buf][k][tx * 8 + 4]);
             const float yv[8] = {y0.x, y0.y, y0.z, y0.w, y1.x, y1.y, y1.z, y1.w};
             const float ev[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+            if (BOX) {
+                const float4 o0 = *reinterpret_cast<const float4*>(&Os[buf][k][ty * 8]);
+                const float4 o1 = *reinterpret_cast<const float4*>(&Os[buf][k][ty * 8 + 4]);
+                const float ov[8] = {o0.x, o0.y, o0.z, o0.w, o1.x, o1.y, o1.z, o1.w};
 #pragma unroll
-            for (int i = 0; i < 8; ++i)
+                for (int i = 0; i < 8; ++i)
 #pragma unroll
-                for (int j = 0; j < 8; ++j) acc[i][j] += fabsf(yv[i] - ev[j]);
+                    for (int j = 0; j < 8; ++j) {
+                        const float a = fabsf(yv[i] - ev[j]);
+                        acc[i][j] += fmaxf(alpha * a, a - ov[i]);
+                    }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) acc[i][j] += fabsf(yv[i] - ev[j]);
+            }
         }
         if (kt + 1 < nk) stage(buf ^ 1, (kt + 1) * DC);
         __syncthreads();
@@ -332,12 +360,17 @@ __global__ __launch_bounds__(256) void fill_zero_i32_kernel(int32_t* p, int n) {
 
 }  // namespace
 
-hipError_t launch_l1_tile(const float* act, const int32_t* row_ids, int n_rows, const float* Emat,
-                          const int32_t* ent_ids, int n_ent, int d, float* dist, int ld, hipStream_t s) {
+hipError_t launch_l1_tile(const float* act, const float* off, float alpha, const int32_t* row_ids, int n_rows,
+                          const float* Emat, const int32_t* ent_ids, int n_ent, int d, float* dist, int ld, hipStream_t s) {
     if (n_rows <= 0 || n_ent <= 0) return hipSuccess;
-    if ((d & 3) || (ld & 3)) return hipErrorInvalidValue;
+    if ((d & 3) || (ld & 3) || (off && !(alpha >= 0.f && alpha <= 1.f))) return hipErrorInvalidValue;
     dim3 grid((n_ent + TE - 1) / TE, (n_rows + TQ - 1) / TQ);
-    hipLaunchKernelGGL(l1_tile_kernel, grid, dim3(256), 0, s, act, row_ids, n_rows, Emat, ent_ids, n_ent, d, dist, ld);
+    if (off)
+        hipLaunchKernelGGL((l1_tile_kernel<true>), grid, dim3(256), 0, s, act, off, alpha, row_ids, n_rows, Emat, ent_ids,
+                           n_ent, d, dist, ld);
+    else
+        hipLaunchKernelGGL((l1_tile_kernel<false>), grid, dim3(256), 0, s, act, off, alpha, row_ids, n_rows, Emat, ent_ids,
+                           n_ent, d, dist, ld);
     return hipGetLastError();
 }
 

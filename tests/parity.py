@@ -12,6 +12,7 @@ import numpy as np
 import workloads as wl
 from oracle import model as om
 from oracle import plan as oplan
+from oracle import rank as orank
 
 TOL = 1e-4
 PYTEST_CONFIG = None
@@ -89,6 +90,11 @@ class Case:
     def neg_dev(self, negs=None):
         import torch
         return torch.from_numpy(np.ascontiguousarray(self.negs if negs is None else negs, np.int32)).cuda()
+
+    distances_all = staticmethod(orank.distances_all)    # query -> distance to every entity
+
+    def model(self):
+        return om.Model(self.params, self.gamma, self.sem_bits)
 
     def oracle_grads(self, negs=None):
         M = om.Model(self.params, self.gamma, self.sem_bits)
@@ -321,3 +327,73 @@ def check_train_steps(case, steps=3, num_streams=1, tol=TOL):
             tol = tol_a
     plan.free()
     return eng
+
+
+def check_topk(case, k, n_check):
+    import torch
+    eng = case.engine()
+    plan = eng.plan(case.qb)
+    ids, dist = eng.rank_all(plan, k)
+    torch.cuda.synchronize()
+    ids, dist = ids.cpu().numpy(), dist.cpu().numpy()
+    M = case.model()
+    assert np.all(np.diff(dist, axis=1) >= 0)
+    for q in np.random.default_rng(1).choice(case.B, min(n_check, case.B), replace=False):
+        full = case.distances_all(case.qb, int(q), M)
+        ref_ids, ref_d = orank.topk_all(case.qb, int(q), M, k, case.distances_all)
+        assert_close(dist[q], ref_d, "top-k distances q%d" % q)
+        # a returned id is right if its true distance is within the k-th best (fp32 may swap near ties)
+        assert len(set(ids[q])) == k and ids[q].min() >= 0
+        assert np.all(full[ids[q]] <= ref_d[-1] * (1 + 1e-4)), "q%d" % q
+        assert_close(dist[q], full[ids[q]], "returned distances belong to returned ids q%d" % q)
+    plan.free()
+
+
+def check_filtered_ranks(case, seed, n_check=None):
+    """Answer lists: a few of the truly nearest entities (small ranks, mutual filtering) plus random
+    entities; one query without answers; scored prefix n_take shorter than the list for some."""
+    import torch
+    rng = np.random.default_rng(seed)
+    M = case.model()
+    B, N = case.B, case.N
+    lists, full = [], []
+    for q in range(B):
+        dist = case.distances_all(case.qb, q, M)
+        full.append(dist)
+        near = np.argsort(dist, kind="stable")[:12]
+        ans = list(rng.choice(near, int(rng.integers(0, 4)), replace=False)) + \
+            list(rng.choice(N, int(rng.integers(1, 5)), replace=False))
+        ans = list(dict.fromkeys(int(a) for a in ans))
+        lists.append([] if q == 1 else ans)
+    off = np.concatenate([[0], np.cumsum([len(l) for l in lists])]).astype(np.int32)
+    flat = np.asarray([a for l in lists for a in l], np.int32)
+    n_take = np.asarray([max(0, len(l) - (q % 3 == 0)) for q, l in enumerate(lists)], np.int32)
+    eng = case.engine()
+    plan = eng.plan(case.qb)
+    dev = lambda x: torch.from_numpy(x).cuda()
+    ranks, dist, metrics = eng.rank_answers(plan, dev(off), dev(flat), dev(n_take))
+    ranks, dist, metrics = ranks.cpu().numpy(), dist.cpu().numpy(), metrics.cpu().numpy()
+    exact = 0
+    for q in range(B):
+        a = np.asarray(lists[q], np.int64)
+        if not len(a):
+            continue
+        want, d_ref = orank.filtered_ranks(case.qb, q, a, M, case.distances_all)
+        got, d_got = ranks[off[q]:off[q + 1]], dist[off[q]:off[q + 1]]
+        assert_close(d_got, d_ref, "answer distances q%d" % q)
+        other = np.ones(N, bool)
+        other[a] = False
+        d_other = np.sort(full[q][other])
+        # fp32 distances: entities within 1e-5 (relative) of an answer may fall on either side
+        lo = 1 + np.searchsorted(d_other, d_ref * (1 - 1e-5), side="left")
+        hi = 1 + np.searchsorted(d_other, d_ref * (1 + 1e-5), side="left")
+        assert np.all((lo <= got) & (got <= hi)), "q%d: %r vs %r" % (q, got, want)   # exact wherever lo == hi
+        exact += int(np.sum(got == want))
+    assert exact >= 0.8 * len(flat)      # (in a table of 150 000 rows distances are denser than fp32 resolves)
+    # the metric kernel against the oracle's formula on the same ranks, scored prefixes only
+    want_m = orank.ranking_metrics([ranks[off[q]:off[q] + n_take[q]] for q in range(B)], ks=(1, 3, 10))
+    np.testing.assert_allclose(metrics, want_m, rtol=1e-5, atol=1e-7)
+    _, _, m_all = eng.rank_answers(plan, dev(off), dev(flat), None)
+    want_all = orank.ranking_metrics([ranks[off[q]:off[q + 1]] for q in range(B)], ks=(1, 3, 10))
+    np.testing.assert_allclose(m_all.cpu().numpy(), want_all, rtol=1e-5, atol=1e-7)
+    plan.free()

@@ -13,7 +13,8 @@ from oracle import box as ob
 from oracle import model as om
 from oracle import plan as oplan
 
-from .parity import (TAU_ABS, TAU_PRE, TAU_TIE, TOL, _adam_f64, assert_close, assert_rows_close, say)  # noqa: F401
+from .parity import (TAU_ABS, TAU_PRE, TAU_TIE, TOL, _adam_f64, assert_close, assert_rows_close, check_filtered_ranks,  # noqa: F401
+                     check_topk, say)
 
 TABLES = ob.TABLES
 
@@ -41,6 +42,9 @@ class BoxCase:
     def from_config(cls, idx, B=None, K=None, seed_offset=0):
         c = wl.get_config(idx)
         return cls(c.N, c.R, c.d, c.h, B or c.B, K or c.K, c.gamma, seed=c.seed + seed_offset, T=c.T, kg_alpha=c.alpha)
+
+    distances_all = staticmethod(ob.distances_all)
+    sem_bits = None
 
     def model(self):
         return ob.BoxModel(self.params, self.gamma, self.alpha)

@@ -87,6 +87,26 @@ def test_union_takes_the_closest_branch_and_negation_is_refused():
         ob.query_step([(0, 4, []), (1, 1, [0]), (om.OP_NEG, 0, [1])], 5, [1], M, 1)
 
 
+def test_distances_to_all_entities_by_explicit_loops_and_against_the_training_scores():
+    _, qb, negs, p = tiny(seed=5, N=40, B=9, K=3)
+    M = ob.BoxModel(p, 12.0, 0.25)
+    E = M.P["E"]
+    for i in range(qb.B):
+        got = ob.distances_all(qb, i, M, chunk=7)
+        boxes = [ob.forward(b, M)[:2] for b in om.dnf(qb.tree(i))]
+        for e in range(E.shape[0]):
+            best = np.inf
+            for c, o in boxes:
+                tot = 0.0
+                for j in range(E.shape[1]):
+                    a = abs(E[e, j] - c[j])
+                    tot += (a - o[j] if a > o[j] else 0.0) + 0.25 * min(a, o[j])
+                best = min(best, tot)
+            assert got[e] == pytest.approx(best, rel=1e-12)
+        _, s = ob.query_step(qb.query_nodes(i), int(qb.pos[i]), negs[i], M, qb.B)
+        np.testing.assert_allclose(12.0 - got[np.concatenate([[qb.pos[i]], negs[i]])], s, rtol=1e-13)
+
+
 def _torch_loss(qb, negs, P, gamma, alpha):
     """Independent re-statement with torch ops + autograd (per query, fp64)."""
     def ev(t):

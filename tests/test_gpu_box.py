@@ -104,6 +104,14 @@ def test_box_candidate_scores():
     pb.assert_close(got, want, "candidate scores")
 
 
+def test_box_all_entity_topk_and_filtered_ranks():
+    _say("box family: all-entity top-k (1 ragged chunk; 3 chunks of 65 536) and filtered ranks")
+    pb.check_topk(pb.BoxCase(1000, 20, 32, 64, 64, 8, 3.0, alpha=0.25, seed=12), 10, 32)
+    pb.check_topk(pb.BoxCase(150000, 40, 400, 800, 100, 2, 24.0, alpha=0.02, seed=13, T=400000), 10, 8)
+    pb.check_filtered_ranks(pb.BoxCase(1000, 20, 32, 64, 64, 8, 3.0, alpha=0.25, seed=14), 1)
+    pb.check_filtered_ranks(pb.BoxCase(150000, 20, 64, 128, 24, 2, 8.0, alpha=0.1, seed=15, T=300000), 2)
+
+
 def test_box_fb15k237_shape_full_size():
     _say("box family at the FB15k-237 shape: N=15000 d=400 h=800 B=512 K=128")
     case = pb.BoxCase.from_config(1)
@@ -118,15 +126,8 @@ def test_box_errors():
         with pytest.raises(NgdbError) as e:
             eng.plan(wl.batch_from_trees([tree], [0]))
         assert e.value.code == binding.ERR_UNSUPPORTED
-    import torch
     L = binding.lib()
-    plan = eng.plan(case.qb)
-    ids = torch.empty((case.B, 4), dtype=torch.int32, device="cuda")
-    dist = torch.empty((case.B, 4), dtype=torch.float32, device="cuda")
-    assert L.ngdb_score(eng.ctx, plan.handle, None, 0, 4, None, ids.data_ptr(), dist.data_ptr(), None) == binding.ERR_UNSUPPORTED
-    off = torch.zeros(case.B + 1, dtype=torch.int32, device="cuda")
-    assert L.ngdb_rank_answers(eng.ctx, plan.handle, off.data_ptr(), None, 0, None, None, None) == binding.ERR_UNSUPPORTED
-    for kw in (dict(d_sem=64), dict(box_alpha=-1.0), dict(box_alpha=float("nan"))):
+    for kw in (dict(d_sem=64), dict(box_alpha=-1.0), dict(box_alpha=1.5), dict(box_alpha=float("nan"))):
         with pytest.raises(NgdbError) as e:
             binding.Engine(100, 5, 32, 64, 2.0, family=binding.FAMILY_BOX, **kw)
         assert e.value.code == binding.ERR_ARG

@@ -108,95 +108,25 @@ def test_candidate_scores_against_oracle():
     par.assert_close(got, want, "candidate scores")
 
 
-def _check_topk(case, k, n_check):
-    import torch
-    eng = case.engine()
-    plan = eng.plan(case.qb)
-    ids, dist = eng.rank_all(plan, k)
-    torch.cuda.synchronize()
-    ids, dist = ids.cpu().numpy(), dist.cpu().numpy()
-    M = om.Model(case.params, case.gamma, case.sem_bits)
-    assert np.all(np.diff(dist, axis=1) >= 0)
-    for q in np.random.default_rng(1).choice(case.B, min(n_check, case.B), replace=False):
-        full = orank.distances_all(case.qb, int(q), M)
-        ref_ids, ref_d = orank.topk_all(case.qb, int(q), M, k)
-        par.assert_close(dist[q], ref_d, "top-k distances q%d" % q)
-        # a returned id is right if its true distance is within the k-th best (fp32 may swap near ties)
-        assert len(set(ids[q])) == k and ids[q].min() >= 0
-        assert np.all(full[ids[q]] <= ref_d[-1] * (1 + 1e-4)), "q%d" % q
-        par.assert_close(dist[q], full[ids[q]], "returned distances belong to returned ids q%d" % q)
-    plan.free()
-
-
 def test_all_entity_topk_small_and_ragged():
     _say("ngdb_score all-entity mode: N=1000 (one ragged chunk), k=10 and k=16; N=300 d=64, k=1")
-    _check_topk(par.Case.from_config(0), 10, 64)
-    _check_topk(par.Case.from_config(0), 16, 16)
-    _check_topk(par.Case(300, 9, 64, 128, 20, 2, 8.0, seed=31), 1, 20)
+    par.check_topk(par.Case.from_config(0), 10, 64)
+    par.check_topk(par.Case.from_config(0), 16, 16)
+    par.check_topk(par.Case(300, 9, 64, 128, 20, 2, 8.0, seed=31), 1, 20)
 
 
 def test_all_entity_topk_many_chunks():
     _say("ngdb_score all-entity mode: N=150000 (3 chunks), d=400, 200 queries incl. unions, k=10")
     case = par.Case(150000, 40, 400, 800, 200, 2, 24.0, seed=32, T=400000)
-    _check_topk(case, 10, 12)
+    par.check_topk(case, 10, 12)
 
 
 # ---------------------------------------------------------------- filtered ranks, MRR, Hit@k
-def _check_filtered_ranks(case, seed, n_check=None):
-    """Answer lists: a few of the truly nearest entities (small ranks, mutual filtering) plus random
-    entities; one query without answers; scored prefix n_take shorter than the list for some."""
-    import torch
-    rng = np.random.default_rng(seed)
-    M = om.Model(case.params, case.gamma, case.sem_bits)
-    B, N = case.B, case.N
-    lists, full = [], []
-    for q in range(B):
-        dist = orank.distances_all(case.qb, q, M)
-        full.append(dist)
-        near = np.argsort(dist, kind="stable")[:12]
-        ans = list(rng.choice(near, int(rng.integers(0, 4)), replace=False)) + \
-            list(rng.choice(N, int(rng.integers(1, 5)), replace=False))
-        ans = list(dict.fromkeys(int(a) for a in ans))
-        lists.append([] if q == 1 else ans)
-    off = np.concatenate([[0], np.cumsum([len(l) for l in lists])]).astype(np.int32)
-    flat = np.asarray([a for l in lists for a in l], np.int32)
-    n_take = np.asarray([max(0, len(l) - (q % 3 == 0)) for q, l in enumerate(lists)], np.int32)
-    eng = case.engine()
-    plan = eng.plan(case.qb)
-    dev = lambda x: torch.from_numpy(x).cuda()
-    ranks, dist, metrics = eng.rank_answers(plan, dev(off), dev(flat), dev(n_take))
-    ranks, dist, metrics = ranks.cpu().numpy(), dist.cpu().numpy(), metrics.cpu().numpy()
-    exact = 0
-    for q in range(B):
-        a = np.asarray(lists[q], np.int64)
-        if not len(a):
-            continue
-        want, d_ref = orank.filtered_ranks(case.qb, q, a, M)
-        got, d_got = ranks[off[q]:off[q + 1]], dist[off[q]:off[q + 1]]
-        par.assert_close(d_got, d_ref, "answer distances q%d" % q)
-        other = np.ones(N, bool)
-        other[a] = False
-        d_other = np.sort(full[q][other])
-        # fp32 distances: entities within 1e-5 (relative) of an answer may fall on either side
-        lo = 1 + np.searchsorted(d_other, d_ref * (1 - 1e-5), side="left")
-        hi = 1 + np.searchsorted(d_other, d_ref * (1 + 1e-5), side="left")
-        assert np.all((lo <= got) & (got <= hi)), "q%d: %r vs %r" % (q, got, want)   # exact wherever lo == hi
-        exact += int(np.sum(got == want))
-    assert exact >= 0.8 * len(flat)      # (in a table of 150 000 rows distances are denser than fp32 resolves)
-    # the metric kernel against the oracle's formula on the same ranks, scored prefixes only
-    want_m = orank.ranking_metrics([ranks[off[q]:off[q] + n_take[q]] for q in range(B)], ks=(1, 3, 10))
-    np.testing.assert_allclose(metrics, want_m, rtol=1e-5, atol=1e-7)
-    _, _, m_all = eng.rank_answers(plan, dev(off), dev(flat), None)
-    want_all = orank.ranking_metrics([ranks[off[q]:off[q + 1]] for q in range(B)], ks=(1, 3, 10))
-    np.testing.assert_allclose(m_all.cpu().numpy(), want_all, rtol=1e-5, atol=1e-7)
-    plan.free()
-
-
 def test_filtered_ranks_and_metrics():
     _say("ngdb_rank_answers: N=1000 (one chunk); N=150000 d=64 (3 chunks); with text features")
-    _check_filtered_ranks(par.Case.from_config(0), 1)
-    _check_filtered_ranks(par.Case(150000, 20, 64, 128, 24, 2, 8.0, seed=51, T=300000), 2)
-    _check_filtered_ranks(par.Case(1500, 10, 48, 96, 30, 4, 6.0, seed=45, d_sem=128), 3)
+    par.check_filtered_ranks(par.Case.from_config(0), 1)
+    par.check_filtered_ranks(par.Case(150000, 20, 64, 128, 24, 2, 8.0, seed=51, T=300000), 2)
+    par.check_filtered_ranks(par.Case(1500, 10, 48, 96, 30, 4, 6.0, seed=45, d_sem=128), 3)
 
 
 # ---------------------------------------------------------------- Max-Fillness schedule
@@ -257,8 +187,8 @@ def test_text_features_scores_and_ranking():
     want = orank.score_candidates(case.qb, cand, om.Model(case.params, case.gamma, case.sem_bits))
     par.assert_close(got, want, "candidate scores with text features")
     plan.free()
-    _check_topk(case, 10, 16)
-    _check_topk(par.Case(70000, 10, 64, 128, 30, 2, 8.0, seed=46, T=200000, d_sem=64), 5, 6)   # 2 entity chunks
+    par.check_topk(case, 10, 16)
+    par.check_topk(par.Case(70000, 10, 64, 128, 30, 2, 8.0, seed=46, T=200000, d_sem=64), 5, 6)   # 2 entity chunks
 
 
 def test_text_features_bad_widths_are_rejected():
