@@ -271,7 +271,7 @@ void ngdb_plan_free(ngdb_plan_t* plan);
 /* One training step (Alg. 1 lines 5-21): forward over the plan's frontiers,
  * L1 scores of every query against its positive and its K negatives, loss,
  * backward, segmented scatter-add of the table gradients, Adam on every bound
- * tensor, step count + 1.  d_neg: device [n_queries, K] entity ids (range is
+ * tensor, step count + 1.  d_neg: device [n_queries, K] entity ids, K >= 1 (range is
  * the caller's responsibility: ids index E directly).  d_loss: device, 1 float,
  * written on the stream.  No host synchronisation except when the workspace
  * has to grow (first call with a larger batch).                                  */

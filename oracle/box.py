@@ -38,14 +38,21 @@ class BoxModel:
 
 
 class Grads:
+    """Gradient accumulators; table gradients per touched row.  `mass` keeps, per row, the sum of
+    the largest entries of its contributions: projections are translations here, so an entity that
+    is an anchor of a query and one of its candidates receives two contributions that cancel, and
+    the accuracy a sum of fp32 terms can have is set by the terms, not by what is left of them."""
+
     def __init__(self, P):
         self.dense = {k: np.zeros_like(v) for k, v in P.items() if k not in TABLES}
         self.rows = {t: {} for t in TABLES}
+        self.mass = {t: {} for t in TABLES}
 
     def add_row(self, table, idx, vec):
         r = self.rows[table]
         idx = int(idx)
         r[idx] = r[idx] + vec if idx in r else np.array(vec, np.float64)
+        self.mass[table][idx] = self.mass[table].get(idx, 0.0) + float(np.abs(vec).max())
 
     def table_dense(self, table, shape):
         out = np.zeros(shape, np.float64)

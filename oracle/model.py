@@ -210,11 +210,14 @@ def min_abs_preactivation(tape):
 
 
 class Grads:
-    """Gradient accumulators.  Table gradients are kept per touched row."""
+    """Gradient accumulators.  Table gradients are kept per touched row; `mass` keeps, per row,
+    the sum of the largest entries of its contributions (contributions of opposite sign cancel;
+    the accuracy a sum of fp32 terms can have is set by the terms, not by what is left of them)."""
 
     def __init__(self, P):
         self.dense = {k: np.zeros_like(v) for k, v in P.items() if k not in ("E", "R")}
         self.rows = {"E": {}, "R": {}}
+        self.mass = {"E": {}, "R": {}}
 
     def add_row(self, table, idx, vec):
         r = self.rows[table]
@@ -223,6 +226,7 @@ class Grads:
             r[idx] = r[idx] + vec
         else:
             r[idx] = np.array(vec, np.float64)
+        self.mass[table][idx] = self.mass[table].get(idx, 0.0) + float(np.abs(vec).max())
 
     def table_dense(self, table, shape):
         out = np.zeros(shape, np.float64)

@@ -590,8 +590,8 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
              bool apply) {
     if (!c || !pl) return NGDB_ERR_ARG;
     if (!c->bound) return fail(c, NGDB_ERR_STATE, "parameters not bound");
-    if (K < 0 || (K > 0 && pl->hp.n_queries > 0 && !d_neg) || !d_loss)
-        return fail(c, NGDB_ERR_ARG, "bad negatives / loss pointer");
+    if (K < 1 || (pl->hp.n_queries > 0 && !d_neg) || !d_loss)
+        return fail(c, NGDB_ERR_ARG, "bad negatives (K >= 1 is required) / loss pointer");
     if (pl->n_entities != c->cfg.n_entities || !pl->d_blob)
         return fail(c, NGDB_ERR_ARG, "plan belongs to another configuration or was built without a device");
     const HostPlan& hp = pl->hp;

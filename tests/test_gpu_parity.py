@@ -294,6 +294,10 @@ def test_errors_are_reported_not_raised_as_faults():
     with pytest.raises(NgdbError) as e:
         fresh.train_step(p2, case.neg_dev())
     assert e.value.code == binding.ERR_STATE
+    loss = torch.zeros(1, device="cuda")
+    assert L.ngdb_train_step(eng.ctx, plan.handle, case.neg_dev().data_ptr(), 0, None, loss.data_ptr()) == binding.ERR_ARG
+    assert L.ngdb_train_step(eng.ctx, plan.handle, None, case.K, None, loss.data_ptr()) == binding.ERR_ARG
+    assert L.ngdb_train_step(eng.ctx, plan.handle, case.neg_dev().data_ptr(), case.K, None, None) == binding.ERR_ARG
     with pytest.raises(NgdbError) as e:
         binding.Engine(case.N, case.R, case.d, case.h, case.gamma, schedule=7)
     assert e.value.code == binding.ERR_ARG
