@@ -43,10 +43,16 @@ class Grads:
     is an anchor of a query and one of its candidates receives two contributions that cancel, and
     the accuracy a sum of fp32 terms can have is set by the terms, not by what is left of them."""
 
-    def __init__(self, P):
+    def __init__(self, P, track_sq=False):
         self.dense = {k: np.zeros_like(v) for k, v in P.items() if k not in TABLES}
+        self.dense_sq = {k: np.zeros_like(v) for k, v in self.dense.items()} if track_sq else None   # as in oracle.model
         self.rows = {t: {} for t in TABLES}
         self.mass = {t: {} for t in TABLES}
+
+    def add(self, name, val):
+        self.dense[name] += val
+        if self.dense_sq is not None:
+            self.dense_sq[name] += np.square(val)
 
     def add_row(self, table, idx, vec):
         r = self.rows[table]
@@ -132,9 +138,9 @@ def backward(tape, dc, do, M, G):
         for j in range(k):
             da = Wt[j] * (dc * C[j] - t_all)
             dca, dWa, dba, dWb, dbb = mlp_backward(da, ctapes[j], P["U1"], P["U2"])
-            G.dense["U1"] += dWa; G.dense["u1"] += dba; G.dense["U2"] += dWb; G.dense["u2"] += dbb
+            G.add("U1", dWa); G.add("u1", dba); G.add("U2", dWb); G.add("u2", dbb)
             doa, dWa, dba, dWb, dbb = mlp_backward(dpre / k, otapes[j], P["V1"], P["V2"])
-            G.dense["V1"] += dWa; G.dense["c1"] += dba; G.dense["V2"] += dWb; G.dense["c2"] += dbb
+            G.add("V1", dWa); G.add("c1", dba); G.add("V2", dWb); G.add("c2", dbb)
             backward(txs[j], Wt[j] * dc + dca, (arg == j) * do * gate + doa, M, G)
     else:
         raise ValueError(kind)
@@ -202,8 +208,8 @@ def query_step(nodes, pos, negs, M, B, G=None):
     return loss, s
 
 
-def batch_loss_and_grads(batch, negs, M, want_grads=True):
-    G = Grads(M.P) if want_grads else None
+def batch_loss_and_grads(batch, negs, M, want_grads=True, track_sq=False):
+    G = Grads(M.P, track_sq) if want_grads else None
     total, scores = 0.0, []
     for i in range(batch.B):
         l, s = query_step(batch.query_nodes(i), int(batch.pos[i]), negs[i], M, batch.B, G)
@@ -223,10 +229,10 @@ def adam_step(P, state, G, t, hp):
             P[table][i], m[i], v[i] = adam_update(P[table][i], m[i], v[i], g, t, **kw)
 
 
-def train_step(batch, negs, params, state, t, hp):
+def train_step(batch, negs, params, state, t, hp, track_sq=False):
     """One full step.  params/state are fp64 dicts updated in place; returns (loss, grads)."""
     M = BoxModel(params, hp["gamma"], hp["alpha"])
     M.P = params
-    loss, G, _ = batch_loss_and_grads(batch, negs, M)
+    loss, G, _ = batch_loss_and_grads(batch, negs, M, track_sq=track_sq)
     adam_step(params, state, G, t, hp)
     return loss, G

@@ -214,10 +214,18 @@ class Grads:
     the sum of the largest entries of its contributions (contributions of opposite sign cancel;
     the accuracy a sum of fp32 terms can have is set by the terms, not by what is left of them)."""
 
-    def __init__(self, P):
+    def __init__(self, P, track_sq=False):
         self.dense = {k: np.zeros_like(v) for k, v in P.items() if k not in ("E", "R")}
+        # optional, for tests: per element the sum of the squared contributions (the square root is
+        # the scale on which independent rounding errors of the contributions add up)
+        self.dense_sq = {k: np.zeros_like(v) for k, v in self.dense.items()} if track_sq else None
         self.rows = {"E": {}, "R": {}}
         self.mass = {"E": {}, "R": {}}
+
+    def add(self, name, val):
+        self.dense[name] += val
+        if self.dense_sq is not None:
+            self.dense_sq[name] += np.square(val)
 
     def add_row(self, table, idx, vec):
         r = self.rows[table]
@@ -239,7 +247,7 @@ def entity_backward(e, g, M, G):
     """Back-propagate g = dL/dEf[e] to the structural row and the text projection."""
     G.add_row("E", e, g)
     if M.sem_bits is not None:
-        G.dense["Wp"] += np.outer(g, M.sem(e))
+        G.add("Wp", np.outer(g, M.sem(e)))
 
 
 def backward(tape, dy, M, G):
@@ -250,19 +258,19 @@ def backward(tape, dy, M, G):
     elif kind == "p":
         _, r, tx, t = tape
         dz, dWa, dba, dWb, dbb = mlp_backward(dy, t, P["W1"], P["W2"])
-        G.dense["W1"] += dWa
-        G.dense["b1"] += dba
-        G.dense["W2"] += dWb
-        G.dense["b2"] += dbb
+        G.add("W1", dWa)
+        G.add("b1", dba)
+        G.add("W2", dWb)
+        G.add("b2", dbb)
         G.add_row("R", r, dz)
         backward(tx, dz, M, G)
     elif kind == "n":
         _, tx, t = tape
         dx, dWa, dba, dWb, dbb = mlp_backward(dy, t, P["V1"], P["V2"])
-        G.dense["V1"] += dWa
-        G.dense["c1"] += dba
-        G.dense["V2"] += dWb
-        G.dense["c2"] += dbb
+        G.add("V1", dWa)
+        G.add("c1", dba)
+        G.add("V2", dWb)
+        G.add("c2", dbb)
         backward(tx, dx, M, G)
     elif kind == "i":
         _, txs, tapes, X, Wt = tape
@@ -272,10 +280,10 @@ def backward(tape, dy, M, G):
         for k in range(X.shape[0]):
             da = Wt[k] * (dy * X[k] - t_all)
             dxa, dWa, dba, dWb, dbb = mlp_backward(da, tapes[k], P["U1"], P["U2"])
-            G.dense["U1"] += dWa
-            G.dense["u1"] += dba
-            G.dense["U2"] += dWb
-            G.dense["u2"] += dbb
+            G.add("U1", dWa)
+            G.add("u1", dba)
+            G.add("U2", dWb)
+            G.add("u2", dbb)
             backward(txs[k], Wt[k] * dy + dxa, M, G)
     else:
         raise ValueError(kind)
@@ -329,13 +337,13 @@ def query_step(nodes, pos, negs, M, B, G=None):
     return loss, s
 
 
-def batch_loss_and_grads(batch, negs, M, want_grads=True):
+def batch_loss_and_grads(batch, negs, M, want_grads=True, track_sq=False):
     """Sum over the queries of a batch, each handled on its own.
 
     batch: object with B, pos and query_nodes(i); negs: [B, K] ints.
     Returns (loss, Grads or None, list of per-query score vectors).
     """
-    G = Grads(M.P) if want_grads else None
+    G = Grads(M.P, track_sq) if want_grads else None
     total, scores = 0.0, []
     for i in range(batch.B):
         l, s = query_step(batch.query_nodes(i), int(batch.pos[i]), negs[i], M, batch.B, G)
@@ -375,10 +383,10 @@ def new_state(P):
     return {k: [np.zeros_like(v), np.zeros_like(v)] for k, v in P.items()}
 
 
-def train_step(batch, negs, params, state, t, hp, sem_bits=None):
+def train_step(batch, negs, params, state, t, hp, sem_bits=None, track_sq=False):
     """One full step.  params/state are fp64 dicts updated in place; returns the loss."""
     M = Model(params, hp["gamma"], sem_bits)
     M.P = params                                   # update the caller's arrays
-    loss, G, _ = batch_loss_and_grads(batch, negs, M)
+    loss, G, _ = batch_loss_and_grads(batch, negs, M, track_sq=track_sq)
     adam_step(params, state, G, t, hp)
     return loss, G

@@ -285,7 +285,7 @@ def check_train_steps(case, steps=3, num_streams=1, tol=TOL):
         b_p, b_m, b_v = eng.params_numpy("p"), eng.params_numpy("m"), eng.params_numpy("v")
         loss = eng.train_step(plan, nd)
         torch.cuda.synchronize()
-        ref_loss, G = om.train_step(case.qb, negs, P, state, t, case.hp, case.sem_bits)
+        ref_loss, G = om.train_step(case.qb, negs, P, state, t, case.hp, case.sem_bits, track_sq=True)
         a_p, a_m, a_v = eng.params_numpy("p"), eng.params_numpy("m"), eng.params_numpy("v")
         if case.B:
             assert abs(float(loss.cpu()[0]) - ref_loss) <= tol * abs(ref_loss)
@@ -318,20 +318,24 @@ def check_train_steps(case, steps=3, num_streams=1, tol=TOL):
             m0, v0 = state_ref_before[name]
             # rounding level of the gradient: bf16 for Wp; else that of dL/ds = sigmoid(s)-like, which
             # inherits the absolute error of the fp32 score (sums of d terms of size ~gamma: ~1e-5)
-            noise = 4e-3 if name == "Wp" else 1e-5
+            # (Wp: every term is rounded to bf16, 2^-9 relative; the errors add in quadrature, and over the
+            # 4e5 elements of the workload's Wp the largest of them is 4-5 standard deviations)
+            noise = 1e-2 if name == "Wp" else 1e-5
             if name in ("E", "R"):     # of a row sum: set by the sizes of its contributions (oracle Grads.mass)
                 mass = np.zeros((shapes[name][0], 1))
                 for i, v in G.mass[name].items():
                     mass[i, 0] = v
                 delta = noise * mass
-            else:
-                delta = noise * np.abs(gref).max()
+            else:                      # of a dense sum: independent errors of the terms add in quadrature
+                rms = np.sqrt(G.dense_sq[name])
+                delta = noise * np.maximum(rms, np.abs(gref).max() * 1e-3)
             hi = _adam_f64(before_ref[name], m0, v0, gref + delta, t, case.hp)[0]
             lo = _adam_f64(before_ref[name], m0, v0, gref - delta, t, case.hp)[0]
             upd_ref = P[name] - before_ref[name]
             scale = np.abs(upd_ref).max()
             keep = (np.abs(hi - lo) / 2 <= tol * scale)
-            keep |= (gref == 0.0) & (g_gpu[name] == 0.0)     # dead units: identical input to Adam
+            # dead units (no gradient now, none before): identical input to Adam
+            keep |= (gref == 0.0) & (g_gpu[name] == 0.0) & (m0 == 0.0) & (v0 == 0.0)
             if name in ("E", "R"):
                 keep &= touched[:, None]
                 n_all = int(touched.sum()) * shapes[name][1]
@@ -342,7 +346,10 @@ def check_train_steps(case, steps=3, num_streams=1, tol=TOL):
             bound = tol * scale + ulp
             assert np.all(err[keep] <= bound[keep]), \
                 "%s update: worst %.3g x bound" % (name, (err[keep] / bound[keep]).max())
-            assert keep.sum() >= 0.3 * n_all, "%s: only %d of %d elements are well conditioned" % (
+            # (a tensor whose terms largely cancel -- u1: the logit gradients of an intersection sum to
+            # zero over its inputs -- may keep fewer)
+            cancels = name not in ("E", "R") and np.abs(gref).max() < 0.05 * np.sqrt(G.dense_sq[name]).max()
+            assert cancels or keep.sum() >= 0.3 * n_all, "%s: only %d of %d elements are well conditioned" % (
                 name, keep.sum(), n_all)
             assert_close(a_m[name], state[name][0], "m " + name, tol)
             assert_close(a_v[name], state[name][1], "v " + name, 2 * tol)
