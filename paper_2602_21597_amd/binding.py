@@ -188,9 +188,10 @@ def _check(rc, ctx):
 
 def plan_host(n_entities, n_relations, qb, schedule=SCHED_LEVEL, b_max=0):
     """Host-only planning (no device needed); the plan can be exported, not executed."""
-    arrs = _BatchArrays(qb)
+    arrs = None if isinstance(qb, QueryBatchC) else _BatchArrays(qb)    # keeps the numpy arrays alive
+    c = qb if arrs is None else arrs.c
     h = C.c_void_p()
-    _check(lib().ngdb_plan_host_sched(int(n_entities), int(n_relations), C.byref(arrs.c), int(schedule), int(b_max),
+    _check(lib().ngdb_plan_host_sched(int(n_entities), int(n_relations), C.byref(c), int(schedule), int(b_max),
                                       C.byref(h)), None)
     return Plan(h)
 
