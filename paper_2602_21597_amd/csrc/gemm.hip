@@ -199,23 +199,27 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
         }
     }
 
-    // Epilogue operands of this thread's output elements are requested here, ahead of the k
-    // loop (clamped addresses, uniform flags): nothing is waited for after the last MFMA.
+    // Epilogue operands of this thread's output elements (clamped addresses, uniform flags).
+    // Small tiles (launches that are latency bound) request them here, ahead of the k loop, so
+    // that nothing is waited for after the last MFMA; large tiles request them after the loop:
+    // held across it they would cost the registers of a second resident wavefront per SIMD.
     constexpr int EPT = BM * BN / (NW * 64);
+    constexpr bool EARLY_EPILOGUE = BM * BN <= 32 * 32;
     float e_bias[EPT], e_mask[EPT], e_add[EPT];
     int e_orow[EPT];
     const bool has_bias = a.bias != nullptr, has_mask = a.mask != nullptr, has_addend = a.addend != nullptr,
                has_dst = a.dst_row != nullptr;
-#pragma unroll
-    for (int q = 0; q < EPT; ++q) {
-        const int e = tid + q * NW * 64;
-        const int lr = e / BN, lc = e % BN;
-        const int row = min(m0 + lr, a.M - 1), col = min(n0 + lc, a.N - 1);
-        e_bias[q] = has_bias ? a.bias[col] : 0.f;
-        e_mask[q] = has_mask ? a.mask[(size_t)row * a.ldmask + col] : 1.f;
-        e_add[q] = has_addend ? a.addend[(size_t)row * a.ldadd + col] : 0.f;
-        e_orow[q] = has_dst ? a.dst_row[row] : row;
+#define NGDB_LOAD_EPILOGUE()                                                                \
+    _Pragma("unroll") for (int q = 0; q < EPT; ++q) {                                      \
+        const int e = tid + q * NW * 64;                                                    \
+        const int lr = e / BN, lc = e % BN;                                                 \
+        const int row = min(m0 + lr, a.M - 1), col = min(n0 + lc, a.N - 1);                 \
+        e_bias[q] = has_bias ? a.bias[col] : 0.f;                                           \
+        e_mask[q] = has_mask ? a.mask[(size_t)row * a.ldmask + col] : 1.f;                  \
+        e_add[q] = has_addend ? a.addend[(size_t)row * a.ldadd + col] : 0.f;                \
+        e_orow[q] = has_dst ? a.dst_row[row] : row;                                         \
     }
+    if (EARLY_EPILOGUE) { NGDB_LOAD_EPILOGUE() }
 
     // A wavefront stages its tiles in its own LDS area and LDS executes a wavefront's
     // instructions in order, so the k loop needs no workgroup barrier: wavefronts run
@@ -257,6 +261,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[kk][i], bv[kk][j], acc[i][j], 0, 0, 0);
         __builtin_amdgcn_wave_barrier();        // reads of this tile before the next one is staged
     }
+    if (!EARLY_EPILOGUE) { NGDB_LOAD_EPILOGUE() }   // in flight during the reduction
+#undef NGDB_LOAD_EPILOGUE
     __syncthreads();                            // the staging areas are reused for the reduction
 
     // partial tiles -> LDS.  Accumulator layout of a 32x32 block: lane owns column
