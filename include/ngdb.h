@@ -360,7 +360,8 @@ int ngdb_debug_copy(void* d_dst, const void* d_src, size_t bytes, void* stream);
 #define NGDB_TK_INDEX     0   /* gradient index: radix sort + segment heads        */
 #define NGDB_TK_SEM       1   /* text features: fused rows and projection gradient */
 #define NGDB_TK_GEMM_FWD  2   /* forward MLP contractions                          */
-#define NGDB_TK_INTER     3   /* intersection pooling, forward and backward        */
+#define NGDB_TK_INTER     3   /* intersection pooling (box family: also projections
+                                 and offsets), forward and backward                */
 #define NGDB_TK_SCORE     4   /* fused L1 score + loss + dL/ds                     */
 #define NGDB_TK_GEMM_BWD  5   /* data-gradient contractions                        */
 #define NGDB_TK_WGRAD     6   /* weight-gradient contractions and bias sums        */
