@@ -37,6 +37,8 @@ MEASURED_TRAFFIC = {
     (1, "gemm"): 19.6e6,        # mean over the 17 contraction launches of a step (weight gradients: 88 MB)
     (3, "table_E"): 26.4e9,     # of which 9.75 GB written; 6.7 GB are re-reads of branch rows served by the caches
     (4, "sem"): 14.2e9,         # projection 16.2 GB + its gradient 12.1 GB per step, two launches
+    ("box", 1, "gemm"): 18.3e6,     # mean over the 9 contraction launches of a step
+    ("box", 3, "table_E"): 32.6e9,  # the winning branches' offset rows are re-read beside their centre rows
 }
 
 
@@ -370,7 +372,7 @@ def main():
         k["frac"] = k["achieved"] / k["peak"]
     dom = max(kern, key=lambda k: kern[k]["ms_per_step"])
     kd = kern[dom]
-    traffic = None if box else MEASURED_TRAFFIC.get((cfg.index, dom))
+    traffic = MEASURED_TRAFFIC.get(("box", cfg.index, dom) if box else (cfg.index, dom))
     roofline = {"bound": kd["bound"], "kernel": dom, "achieved": kd["achieved"], "peak": kd["peak"],
                 "unit": kd["unit"], "frac": kd["frac"], "traffic": traffic,
                 "avg_us": kd["avg_us"], "launches_per_step": kd["launches_per_step"],
