@@ -42,7 +42,7 @@ MEASURED_TRAFFIC = {
 }
 
 
-def cpu_baseline(cfg, kg, sample, sem_bits, box_alpha=None):
+def cpu_baseline(cfg, kg, sample, sem_bits, box_alpha=None, score_bf16=False):
     """The oracle as it stands, full steps (loss, gradients, Adam) on batches of `sample` queries
     until about 10 s of CPU time have passed (at most 16 steps), single process with BLAS held
     to one thread."""
@@ -67,7 +67,7 @@ def cpu_baseline(cfg, kg, sample, sem_bits, box_alpha=None):
             if box:
                 ob.train_step(qb, negs, P, st, steps + 1, hp)
             else:
-                om.train_step(qb, negs, P, st, steps + 1, hp, sem_bits)
+                om.train_step(qb, negs, P, st, steps + 1, hp, sem_bits, score_bf16=score_bf16)
             total += time.perf_counter() - t0
             steps += 1
         return total, steps
@@ -87,7 +87,7 @@ def say(msg):
     print("[bench] " + msg, file=sys.stderr, flush=True)
 
 
-def kernel_models(cfg, pexp, touched, box=False):
+def kernel_models(cfg, pexp, touched, box=False, score_bf16=False):
     """Algorithmic work of one step per kernel class: what the method itself has to move or
     multiply, whatever the kernels do.  Returns {class: (bound, amount, peak, unit)} with
     amounts in bytes (hbm) or flops (mfma)."""
@@ -104,6 +104,9 @@ def kernel_models(cfg, pexp, touched, box=False):
     table_bytes = touched * 6 * row + n_contrib * 12 + pexp["n_anchor"] * row
     if sem:
         table_bytes += touched * (row + 2 * cfg.d)
+    if score_bf16:   # candidate rows at 2 bytes per coordinate; the copy's row written with every touched row
+        score_bytes -= pairs * (row // 2)
+        table_bytes += touched * (row // 2)
     if box:   # boxes at the roots are two rows wide; two MLPs over the inputs of the intersections, none elsewhere
         score_bytes += pexp["n_roots"] * 2 * row
         mlp_rows = 2 * pexp["n_int_rows"]
@@ -209,6 +212,8 @@ def main():
     ap.add_argument("--family", choices=("vec", "box"), default="vec",
                     help="operator family: the vector model of the headline workload, or box embeddings (Q2B "
                          "operators) on the 9 negation-free structures of the same workload")
+    ap.add_argument("--score-bf16", action="store_true",
+                    help="candidate rows from a bf16 copy of the entity table (optional mode, not the headline)")
     ap.add_argument("--box-alpha", type=float, default=0.02, help="weight of the inside distance (box family)")
     ap.add_argument("--bmax", type=int, default=0, help="largest batch of one Max-Fillness step, 0 = unbounded")
     ap.add_argument("--sampler", type=int, default=0, metavar="THREADS",
@@ -253,7 +258,7 @@ def main():
     default_sample = 512 if cfg.K <= 128 else (8 if cfg.d_sem else 64)
     sample = args.cpu_sample if args.cpu_sample >= 0 else min(cfg.B, default_sample)
     say("CPU oracle on %d queries" % sample)
-    cpu = cpu_baseline(cfg, kg, sample, sem_bits, args.box_alpha if box else None) if sample > 0 else None
+    cpu = cpu_baseline(cfg, kg, sample, sem_bits, args.box_alpha if box else None, args.score_bf16) if sample > 0 else None
     say("uploading parameters")
 
     import torch
@@ -261,7 +266,7 @@ def main():
     streams = args.streams or cfg.streams
     eng = Engine(cfg.N, cfg.R, cfg.d, cfg.h, cfg.gamma, lr=cfg.lr, beta1=cfg.beta1, beta2=cfg.beta2, eps=cfg.eps,
                  num_streams=streams, d_sem=cfg.d_sem, schedule={"level": 0, "max_fill": 1}[args.schedule],
-                 b_max=args.bmax, family=1 if box else 0, box_alpha=args.box_alpha)
+                 b_max=args.bmax, family=1 if box else 0, box_alpha=args.box_alpha, score_bf16=args.score_bf16)
     eng.bind_numpy(params, sem_bits=sem_bits)
     del params, sem_bits
     negs = [torch.from_numpy(n).cuda() for n in negs_np]
@@ -352,7 +357,7 @@ def main():
 
     # roofline per kernel class: algorithmic work of one step / measured time of the class per step.
     # The three contraction classes are launches of one kernel and are reported together as "gemm".
-    models = kernel_models(cfg, pexp, touched, box)
+    models = kernel_models(cfg, pexp, touched, box, args.score_bf16)
     kern = {}
     for name, (bound, amount, peak, unit) in models.items():
         ms, n = timing[name]
@@ -372,7 +377,7 @@ def main():
         k["frac"] = k["achieved"] / k["peak"]
     dom = max(kern, key=lambda k: kern[k]["ms_per_step"])
     kd = kern[dom]
-    traffic = MEASURED_TRAFFIC.get(("box", cfg.index, dom) if box else (cfg.index, dom))
+    traffic = None if args.score_bf16 else MEASURED_TRAFFIC.get(("box", cfg.index, dom) if box else (cfg.index, dom))
     roofline = {"bound": kd["bound"], "kernel": dom, "achieved": kd["achieved"], "peak": kd["peak"],
                 "unit": kd["unit"], "frac": kd["frac"], "traffic": traffic,
                 "avg_us": kd["avg_us"], "launches_per_step": kd["launches_per_step"],
@@ -398,7 +403,8 @@ def main():
                    % (cfg.index, cfg.name, cfg.N, cfg.R, cfg.d, cfg.h, cfg.B, cfg.K,
                       " d_sem=%d (bf16 text features)" % cfg.d_sem if cfg.d_sem else "",
                       "box family (alpha=%g) on the 9 negation-free structures" % args.box_alpha if box
-                      else "14-structure mix", cfg.gamma),
+                      else "14-structure mix" + (", candidate rows from a bf16 copy of E" if args.score_bf16 else ""),
+                      cfg.gamma),
                    "streams": streams,
                    "schedule": args.schedule if args.schedule == "level" else "max_fill, B_max=%s" % (args.bmax or "inf"),
                    "steps_per_batch": pexp["n_levels"], "peak_live_outputs": pexp["peak_live"],

@@ -137,6 +137,15 @@ typedef struct ngdb_config {
     int32_t b_max;         /* largest batch of one Max-Fillness step, 0 = unbounded   */
     int32_t family;        /* NGDB_FAMILY_*                                           */
     float box_alpha;       /* weight of the inside distance (box family), 0..1        */
+    int32_t score_bf16;    /* 1: the scoring and ranking passes read candidate rows from a
+                              bf16 copy of E that the library keeps (half the gather
+                              bytes): s(q,e) = gamma - min_b ||y_b - bf16(E[e])||_1,
+                              rounded to nearest even; anchors and the optimiser use the
+                              fp32 rows, the gradient of a rounded row goes to its fp32
+                              row unchanged.  The copy is made by ngdb_bind_params and
+                              kept current by ngdb_train_step: bind again after writing
+                              to E from outside.  Vector family without text features
+                              only                                                     */
 } ngdb_config;
 
 /* A trainable tensor with its Adam moments (all device, fp32, same shape). */
@@ -239,6 +248,7 @@ typedef struct ngdb_grad_view {
     const float* gRo;           /* [n_r_uniq, d]   (forward_backward only)       */
     const float* off;           /* [n_slots, d] box offsets by slot (act holds the centres) */
     const float* doff;          /* [n_slots + n_anchor, d] dL/d(offset) by slot  */
+    const uint16_t* e_shadow;   /* [n_entities, d] the bf16 copy of E (score_bf16), else NULL */
 } ngdb_grad_view;
 
 /* Create a context (allocates streams and a small workspace).  cfg: host. */

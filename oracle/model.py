@@ -127,9 +127,12 @@ def dnf(tree):
 class Model:
     """Parameters in fp64 plus the entity-row rule Ef[e]."""
 
-    def __init__(self, params, gamma, sem_bits=None):
+    def __init__(self, params, gamma, sem_bits=None, score_bf16=False):
         self.P = to_f64(params)
         self.gamma = float(gamma)
+        # candidate rows (positives, negatives, ranking) read from a bf16 copy of E; anchors and
+        # the optimiser keep the fp32 rows; a rounded row passes its gradient on unchanged
+        self.score_bf16 = bool(score_bf16)
         self.sem_bits = sem_bits                 # [N, d_sem] uint16 bf16 patterns or None
         self.Wp_used = bf16_round(params["Wp"]) if sem_bits is not None else None
 
@@ -142,6 +145,10 @@ class Model:
         if self.sem_bits is not None:
             row = row + self.sem(e) @ self.Wp_used.T
         return row
+
+    def candidate(self, e):
+        """The row of entity e as the scoring and ranking passes read it."""
+        return bf16_round(self.P["E"][e]) if self.score_bf16 else self.entity(e)
 
 
 def mlp_forward(x, Wa, ba, Wb, bb):
@@ -317,7 +324,7 @@ def query_step(nodes, pos, negs, M, B, G=None):
         tapes.append(t)
     Y = np.stack(Ys)
     cand = np.concatenate([[pos], np.asarray(negs, np.int64)])
-    rows = M.entity(cand)
+    rows = M.candidate(cand)
     s, win = score(Y, rows, M.gamma)
     K = len(cand) - 1
     loss = pair_loss_terms(s[0], s[1:]) / (2.0 * B)
@@ -383,9 +390,9 @@ def new_state(P):
     return {k: [np.zeros_like(v), np.zeros_like(v)] for k, v in P.items()}
 
 
-def train_step(batch, negs, params, state, t, hp, sem_bits=None, track_sq=False):
+def train_step(batch, negs, params, state, t, hp, sem_bits=None, track_sq=False, score_bf16=False):
     """One full step.  params/state are fp64 dicts updated in place; returns the loss."""
-    M = Model(params, hp["gamma"], sem_bits)
+    M = Model(params, hp["gamma"], sem_bits, score_bf16)
     M.P = params                                   # update the caller's arrays
     loss, G, _ = batch_loss_and_grads(batch, negs, M, track_sq=track_sq)
     adam_step(params, state, G, t, hp)

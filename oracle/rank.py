@@ -19,7 +19,7 @@ def score_candidates(batch, cand, M):
     out = np.empty(cand.shape, np.float64)
     for i in range(batch.B):
         Y = query_embeddings(batch, i, M)
-        rows = M.entity(np.asarray(cand[i], np.int64))
+        rows = M.candidate(np.asarray(cand[i], np.int64))
         out[i] = M.gamma - np.abs(Y[:, None, :] - rows[None]).sum(axis=2).min(axis=0)
     return out
 
@@ -31,7 +31,7 @@ def distances_all(batch, i, M, chunk=8192):
     out = np.empty(N, np.float64)
     for lo in range(0, N, chunk):
         ids = np.arange(lo, min(N, lo + chunk))
-        rows = M.entity(ids)
+        rows = M.candidate(ids)
         out[lo:lo + len(ids)] = np.abs(Y[:, None, :] - rows[None]).sum(axis=2).min(axis=0)
     return out
 

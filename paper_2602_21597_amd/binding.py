@@ -32,7 +32,7 @@ class Config(C.Structure):
     _fields_ = [("n_entities", C.c_int32), ("n_relations", C.c_int32), ("d", C.c_int32), ("h", C.c_int32),
                 ("d_sem", C.c_int32), ("num_streams", C.c_int32), ("gamma", C.c_float), ("lr", C.c_float),
                 ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float), ("schedule", C.c_int32),
-                ("b_max", C.c_int32), ("family", C.c_int32), ("box_alpha", C.c_float)]
+                ("b_max", C.c_int32), ("family", C.c_int32), ("box_alpha", C.c_float), ("score_bf16", C.c_int32)]
 
 
 class Tensor(C.Structure):
@@ -68,7 +68,7 @@ class GradView(C.Structure):
                 ("gE", C.c_void_p), ("gR", C.c_void_p), ("g_mlp", C.c_void_p * 12), ("g_Wp", C.c_void_p),
                 ("act", C.c_void_p), ("dact", C.c_void_p), ("n_grad_rows", C.c_int32),
                 ("pair_score", C.c_void_p), ("loss_terms", C.c_void_p),
-                ("gRo", C.c_void_p), ("off", C.c_void_p), ("doff", C.c_void_p)]
+                ("gRo", C.c_void_p), ("off", C.c_void_p), ("doff", C.c_void_p), ("e_shadow", C.c_void_p)]
 
 
 TIMING_CLASSES = ("index", "sem", "gemm_fwd", "inter", "score", "gemm_bwd", "wgrad", "table_E", "table_R",
@@ -309,7 +309,7 @@ class Engine:
 
     def __init__(self, n_entities, n_relations, d, h, gamma, lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8,
                  d_sem=0, num_streams=1, device="cuda:0", schedule=SCHED_LEVEL, b_max=0, family=FAMILY_VEC,
-                 box_alpha=0.02):
+                 box_alpha=0.02, score_bf16=False):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("libngdb needs a GPU; there is no CPU path")
@@ -317,7 +317,7 @@ class Engine:
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
         self.cfg = Config(n_entities, n_relations, d, h, d_sem, num_streams, gamma, lr, beta1, beta2, eps,
-                          int(schedule), int(b_max), int(family), float(box_alpha))
+                          int(schedule), int(b_max), int(family), float(box_alpha), int(bool(score_bf16)))
         self.ctx = C.c_void_p()
         _check(lib().ngdb_create(C.byref(self.cfg), C.byref(self.ctx)), None)
         self.tensors = {}
@@ -433,6 +433,8 @@ class Engine:
             out["doff"] = copy_to_host(gv.doff, (gv.n_grad_rows, d), np.float32)
         if gv.gRo:
             out["gRo"] = copy_to_host(gv.gRo, (UR, d), np.float32)
+        if gv.e_shadow:
+            out["e_shadow"] = copy_to_host(gv.e_shadow, (self.cfg.n_entities, d), np.uint16)
         if gv.g_Wp:
             out["Wp"] = copy_to_host(gv.g_Wp, (d, self.cfg.d_sem), np.float32)
         return out

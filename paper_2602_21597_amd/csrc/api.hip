@@ -86,6 +86,7 @@ struct ngdb_ctx_s {
     // outputs of the offset MLP with their gradients, direct gradient of the inputs' offsets,
     // compact gradient of Ro.  The offset MLP (V1 c1 V2 c2) uses the Z/H/dH buffers of index T_NEG.
     DevBuf off, doff, Gate, dGate, DxO, gRo;
+    DevBuf Eb;          // bf16 copy of E for the scoring and ranking passes (score_bf16)
     size_t gw_off[13]{};
     hipStream_t upload = nullptr;        // plan uploads, independent of the compute streams
     std::vector<PlanBlob> blob_pool;
@@ -629,6 +630,7 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
     sa.win = sem ? nullptr : ptr<int32_t>(c->win); sa.mask = sem ? c->mask.p : nullptr; sa.dact = ptr<float>(c->dact); sa.loss_terms = ptr<float>(c->loss_terms);
     const bool box = c->cfg.family == NGDB_FAMILY_BOX;
     if (box) { sa.off = ptr<float>(c->off); sa.doff = ptr<float>(c->doff); sa.alpha = c->cfg.box_alpha; }
+    if (c->cfg.score_bf16) sa.E16 = ptr<uint16_t>(c->Eb);
     {
         Timed tm(c, NGDB_TK_SCORE, stream);
         hipError_t e = launch_score(sa, true, stream);
@@ -665,6 +667,7 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
     te.dact = ptr<float>(c->dact); te.act = ptr<float>(c->act); te.g_out = apply ? nullptr : ptr<float>(c->gE);
     if (sem) { te.mask = c->mask.p; te.g_bf16 = ptr<uint16_t>(c->g_bf16); }
     TableArgs tr = te;
+    if (c->cfg.score_bf16) te.shadow = ptr<uint16_t>(c->Eb);   // signs against the rounded rows; written only when updating
     if (box) { te.off = ptr<float>(c->off); te.alpha = c->cfg.box_alpha; }
     tr.g_bf16 = nullptr; tr.mask = nullptr;
     tr.P = c->prm.R.p; tr.Mo = c->prm.R.m; tr.Vo = c->prm.R.v;
@@ -737,6 +740,7 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
         gv.off = ptr<float>(c->off);
         gv.doff = ptr<float>(c->doff);
     }
+    gv.e_shadow = c->cfg.score_bf16 ? ptr<uint16_t>(c->Eb) : nullptr;
     gv.g_Wp = sem ? ptr<float>(c->gWp) : nullptr;
     gv.act = ptr<float>(c->act);
     gv.dact = ptr<float>(c->dact);
@@ -763,6 +767,8 @@ int ngdb_create(const ngdb_config* cfg, ngdb_ctx_t** out) {
     if (cfg->family != NGDB_FAMILY_VEC && cfg->family != NGDB_FAMILY_BOX) return NGDB_ERR_ARG;
     if (cfg->family == NGDB_FAMILY_BOX && (cfg->d_sem != 0 || !(cfg->box_alpha >= 0.f && cfg->box_alpha <= 1.f)))
         return NGDB_ERR_ARG;
+    if ((cfg->score_bf16 != 0 && cfg->score_bf16 != 1) || (cfg->score_bf16 && (cfg->family != NGDB_FAMILY_VEC || cfg->d_sem != 0)))
+        return NGDB_ERR_ARG;
     ngdb_ctx_t* c = new (std::nothrow) ngdb_ctx_s();
     if (!c) return NGDB_ERR_OOM;
     c->cfg = *cfg;
@@ -788,7 +794,7 @@ void ngdb_destroy(ngdb_ctx_t* c) {
                      &c->loss_terms, &c->rec_coef, &c->rec_row, &c->keys_a, &c->keys_b, &c->vals_a, &c->vals_b, &c->hist, &c->scan_tmp,
                      &c->uniq, &c->seg_off, &c->n_uniq, &c->gW, &c->gE, &c->gR, &c->colsum_part, &c->rank_dist, &c->rank_thr, &c->rank_count,
                      &c->Wb, &c->Ef, &c->inv, &c->refs_sem, &c->g_bf16, &c->wp_partial, &c->gWp, &c->rank_ef,
-                     &c->off, &c->doff, &c->Gate, &c->dGate, &c->DxO, &c->gRo};
+                     &c->off, &c->doff, &c->Gate, &c->dGate, &c->DxO, &c->gRo, &c->Eb};
     for (DevBuf* b : all) release(*b);
     if (c->side[0]) (void)hipStreamDestroy(c->side[0]);
     if (c->ev_join) (void)hipEventDestroy(c->ev_join);
@@ -825,6 +831,13 @@ int ngdb_bind_params(ngdb_ctx_t* c, const ngdb_params* p) {
             return fail(c, NGDB_ERR_ARG, "tensors must be 16-byte aligned");
     }
     if (p->step < 0) return fail(c, NGDB_ERR_ARG, "negative step count");
+    if (c->cfg.score_bf16) {   // the bf16 copy of the entity table
+        const size_t n = (size_t)c->cfg.n_entities * c->cfg.d;
+        int rc = ensure(c, c->Eb, n * sizeof(uint16_t));
+        if (rc != NGDB_OK) return rc;
+        HIPCHK(c, launch_cast_bf16(p->E.p, ptr<uint16_t>(c->Eb), (int64_t)n, nullptr));
+        HIPCHK(c, hipDeviceSynchronize());
+    }
     c->prm = *p;
     c->step = p->step;
     c->bound = true;
@@ -1043,6 +1056,7 @@ int ngdb_score(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_cand, int3
         sa.pos = nullptr; sa.cand = er.cand; sa.B = pl->hp.n_queries; sa.C = C; sa.d = c->cfg.d;
         sa.max_branch = std::max(1, pl->hp.max_branch); sa.gamma = c->cfg.gamma; sa.score = d_scores;
         if (c->cfg.family == NGDB_FAMILY_BOX) { sa.off = ptr<float>(c->off); sa.alpha = c->cfg.box_alpha; }
+        if (c->cfg.score_bf16) sa.E16 = ptr<uint16_t>(c->Eb);
         hipError_t e;
         { Timed tm(c, NGDB_TK_SCORE, s); e = launch_score(sa, false, s); }
         if (e == hipErrorInvalidValue) return fail(c, NGDB_ERR_UNSUPPORTED, "embedding width / union branch count too large for the scoring kernel");
@@ -1071,7 +1085,8 @@ int ngdb_score(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_cand, int3
                 rows = ptr<float>(c->rank_ef);
             }
             HIPCHK(c, launch_l1_tile(ptr<float>(c->act), box_off, c->cfg.box_alpha, pl->d_root_slot, R, rows, nullptr, cnt, d,
-                                     ptr<float>(c->rank_dist), ld, s));
+                                     ptr<float>(c->rank_dist), ld, s,
+                                     c->cfg.score_bf16 ? ptr<uint16_t>(c->Eb) + (size_t)e0 * d : nullptr));
             HIPCHK(c, launch_topk_merge(ptr<float>(c->rank_dist), ld, pl->d_root_off, pl->hp.n_queries, e0, cnt, topk,
                                         e0 == 0, d_topk_dist, d_topk_ids, s));
         }
@@ -1130,7 +1145,7 @@ int ngdb_rank_answers(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_ans
                 ids = nullptr;
             }
             HIPCHK(c, launch_l1_tile(ptr<float>(c->act), box_off, c->cfg.box_alpha, pl->d_root_slot, R, rows, ids, cnt, d,
-                                     ptr<float>(c->rank_dist), ld, s));
+                                     ptr<float>(c->rank_dist), ld, s, c->cfg.score_bf16 ? ptr<uint16_t>(c->Eb) : nullptr));
             HIPCHK(c, launch_answer_dist(ptr<float>(c->rank_dist), ld, pl->d_root_off, d_ans_off, B, a0, cnt, thr, s));
         }
         // entities strictly closer than each answer, chunk by chunk
@@ -1143,7 +1158,8 @@ int ngdb_rank_answers(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_ans
                 rows = ptr<float>(c->rank_ef);
             }
             HIPCHK(c, launch_l1_tile(ptr<float>(c->act), box_off, c->cfg.box_alpha, pl->d_root_slot, R, rows, nullptr, cnt, d,
-                                     ptr<float>(c->rank_dist), ld, s));
+                                     ptr<float>(c->rank_dist), ld, s,
+                                     c->cfg.score_bf16 ? ptr<uint16_t>(c->Eb) + (size_t)e0 * d : nullptr));
             HIPCHK(c, launch_count_less(ptr<float>(c->rank_dist), ld, pl->d_root_off, d_ans_off, thr, B, cnt,
                                         ptr<int32_t>(c->rank_count), s));
         }

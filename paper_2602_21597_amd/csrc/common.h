@@ -23,6 +23,17 @@ __device__ __forceinline__ float wave_sum(float v) {
 }
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (WAVE - 1); }
 __device__ __forceinline__ float sgn(float x) { return (float)((x > 0.f) - (x < 0.f)); }
+// bf16 bit patterns <-> fp32 (round to nearest, ties to even)
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float x) {
+    const uint32_t b = __float_as_uint(x);
+    return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ float bf16_round_f32(float x) { return __uint_as_float(f32_to_bf16_bits(x) << 16); }
+// 4 consecutive bf16 values (8 bytes) -> float4
+__device__ __forceinline__ float4 bf16x4_to_f32(uint2 v) {
+    return make_float4(__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xFFFF0000u), __uint_as_float(v.y << 16),
+                       __uint_as_float(v.y & 0xFFFF0000u));
+}
 // log(1+exp(x)) and 1/(1+exp(-x)) without overflow
 __device__ __forceinline__ float softplus_f(float x) { return fmaxf(x, 0.f) + log1pf(expf(-fabsf(x))); }
 __device__ __forceinline__ float sigmoid_f(float x) {
@@ -166,14 +177,18 @@ struct ScoreArgs {
     const float* off = nullptr;
     float* doff = nullptr;
     float alpha = 0.f;
+    // candidate rows from a bf16 copy of the table [N, d] (bit patterns) instead of E
+    const uint16_t* E16 = nullptr;
 };
 hipError_t launch_score(const ScoreArgs& a, bool train, hipStream_t s);
 
 // ---------------------------------------------------------------- ranking (rank.hip)
 // dist[r*ld + e] = ||act[row_ids[r]] - Emat[id(e)]||_1 for r < n_rows, e < n_ent; id(e) = ent_ids[e] or e.
 // With off (box family, 0 <= alpha <= 1): the box distance of (act row, off row) to the entity row.
+// With Emat16 (bf16 bit patterns, same shape and indexing as Emat) the entity rows are read from it.
 hipError_t launch_l1_tile(const float* act, const float* off, float alpha, const int32_t* row_ids, int n_rows,
-                          const float* Emat, const int32_t* ent_ids, int n_ent, int d, float* dist, int ld, hipStream_t s);
+                          const float* Emat, const int32_t* ent_ids, int n_ent, int d, float* dist, int ld, hipStream_t s,
+                          const uint16_t* Emat16 = nullptr);
 // filtered ranks of listed answers (answers of query q: ans_off[q]..ans_off[q+1]-1):
 // thr[a] = distance of answer a (column a - a0 of dist) to its query, min over the query's rows
 hipError_t launch_answer_dist(const float* dist, int ld, const int32_t* root_off, const int32_t* ans_off, int n_queries,
@@ -238,6 +253,9 @@ struct TableArgs {
     float alpha = 0.f;
     // the row's gradient is multiplied by [table row > 0] (a table that is used through relu)
     bool relu_gate = false;
+    // bf16 copy of the table [rows, d] that the scoring pass reads: pair signs are taken against
+    // the rounded row, and the updated row is rounded into the copy
+    uint16_t* shadow = nullptr;
 };
 // sorted contribution numbers -> records: c < n_rowsrc is gradient row row_base + c,
 // otherwise a (query, candidate) pair in the order [B positives | B*K negatives]

@@ -29,10 +29,12 @@ constexpr int TQ = 128, TE = 128, DC = 16, LDT = 128 + 4;
 // BOX (box family): the row side is a box, centre from act and offset from off, and a coordinate
 // contributes relu(a - o) + alpha * min(a, o) = max(alpha * a, a - (1 - alpha) * o), a = |e - c|;
 // the offsets are staged already multiplied by (1 - alpha): five VALU operations per coordinate.
+// Emat16 (if set): the entity rows are read from this bf16 copy of Emat.
 template <bool BOX>
 __global__ __launch_bounds__(256) void l1_tile_kernel(const float* __restrict__ act, const float* __restrict__ off,
                                                       float alpha, const int32_t* __restrict__ row_ids,
                                                       int n_rows, const float* __restrict__ Emat,
+                                                      const uint16_t* __restrict__ Emat16,
                                                       const int32_t* __restrict__ ent_ids, int n_ent, int d,
                                                       float* __restrict__ dist, int ld) {
     __shared__ __attribute__((aligned(16))) float Ys[2][DC][LDT];
@@ -46,6 +48,7 @@ __global__ __launch_bounds__(256) void l1_tile_kernel(const float* __restrict__ 
     const float* yrow[2];
     const float* orow[2];
     const float* erow[2];
+    const uint16_t* erow16[2];
     int lrow[2], lkq[2];
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
@@ -57,6 +60,7 @@ __global__ __launch_bounds__(256) void l1_tile_kernel(const float* __restrict__ 
         orow[i] = BOX ? off + (size_t)row_ids[r] * d : nullptr;
         const int ec = min(e0 + lrow[i], n_ent - 1);
         erow[i] = Emat + (size_t)(ent_ids ? ent_ids[ec] : ec) * d;
+        erow16[i] = Emat16 ? Emat16 + (size_t)(ent_ids ? ent_ids[ec] : ec) * d : nullptr;
     }
     float4 ry[2], re[2], ro[2];
     const float shrink = 1.f - alpha;
@@ -65,7 +69,8 @@ __global__ __launch_bounds__(256) void l1_tile_kernel(const float* __restrict__ 
         for (int i = 0; i < 2; ++i) {
             const int kc = min(k0 + lkq[i] * 4, d - 4);
             ry[i] = *reinterpret_cast<const float4*>(yrow[i] + kc);
-            re[i] = *reinterpret_cast<const float4*>(erow[i] + kc);
+            re[i] = Emat16 ? bf16x4_to_f32(*reinterpret_cast<const uint2*>(erow16[i] + kc))
+                           : *reinterpret_cast<const float4*>(erow[i] + kc);
             if (BOX) ro[i] = *reinterpret_cast<const float4*>(orow[i] + kc);
         }
     };
@@ -361,16 +366,17 @@ __global__ __launch_bounds__(256) void fill_zero_i32_kernel(int32_t* p, int n) {
 }  // namespace
 
 hipError_t launch_l1_tile(const float* act, const float* off, float alpha, const int32_t* row_ids, int n_rows,
-                          const float* Emat, const int32_t* ent_ids, int n_ent, int d, float* dist, int ld, hipStream_t s) {
+                          const float* Emat, const int32_t* ent_ids, int n_ent, int d, float* dist, int ld, hipStream_t s,
+                          const uint16_t* Emat16) {
     if (n_rows <= 0 || n_ent <= 0) return hipSuccess;
     if ((d & 3) || (ld & 3) || (off && !(alpha >= 0.f && alpha <= 1.f))) return hipErrorInvalidValue;
     dim3 grid((n_ent + TE - 1) / TE, (n_rows + TQ - 1) / TQ);
     if (off)
-        hipLaunchKernelGGL((l1_tile_kernel<true>), grid, dim3(256), 0, s, act, off, alpha, row_ids, n_rows, Emat, ent_ids,
-                           n_ent, d, dist, ld);
+        hipLaunchKernelGGL((l1_tile_kernel<true>), grid, dim3(256), 0, s, act, off, alpha, row_ids, n_rows, Emat, Emat16,
+                           ent_ids, n_ent, d, dist, ld);
     else
-        hipLaunchKernelGGL((l1_tile_kernel<false>), grid, dim3(256), 0, s, act, off, alpha, row_ids, n_rows, Emat, ent_ids,
-                           n_ent, d, dist, ld);
+        hipLaunchKernelGGL((l1_tile_kernel<false>), grid, dim3(256), 0, s, act, off, alpha, row_ids, n_rows, Emat, Emat16,
+                           ent_ids, n_ent, d, dist, ld);
     return hipGetLastError();
 }
 

@@ -19,18 +19,25 @@ __device__ __forceinline__ uint32_t sign_code(float s) { return s > 0.f ? 1u : (
 __device__ __forceinline__ int32_t cand_id(const ScoreArgs& a, int i, int has_pos, int c) {
     return (has_pos && c == 0) ? a.pos[i] : a.cand[(size_t)i * a.C + (c - has_pos)];
 }
-template <int NCH>
+template <int NCH, bool B16>
 __device__ __forceinline__ void load_row(const ScoreArgs& a, int32_t e, int lane, int d4, float4 (&dst)[NCH]) {
-    const float4* row = reinterpret_cast<const float4*>(a.E + (size_t)e * a.d);
+    if (B16) {   // the bf16 copy of the table: 8 bytes per lane and chunk
+        const uint2* row = reinterpret_cast<const uint2*>(a.E16 + (size_t)e * a.d);
 #pragma unroll
-    for (int ch = 0; ch < NCH; ++ch) dst[ch] = row[min(ch * 64 + lane, d4 - 1)];
+        for (int ch = 0; ch < NCH; ++ch) dst[ch] = bf16x4_to_f32(row[min(ch * 64 + lane, d4 - 1)]);
+    } else {
+        const float4* row = reinterpret_cast<const float4*>(a.E + (size_t)e * a.d);
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch) dst[ch] = row[min(ch * 64 + lane, d4 - 1)];
+    }
 }
 
 // MASK (training with text features): sign codes per pair instead of the winning rows.
 // BOX: the query side is a box (centre from act, offset from off) and the distance is
 // sum relu(|e-c| - o) + alpha * sum min(|e-c|, o); in LDS the offsets of the branches follow
 // the centres and the offset gradients follow the centre gradients.
-template <int NCH, int NW, bool TRAIN, bool MASK, bool BOX>
+// B16: candidate rows come from the bf16 copy of the table.
+template <int NCH, int NW, bool TRAIN, bool MASK, bool BOX, bool B16>
 __global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
     extern __shared__ __attribute__((aligned(16))) float lds[];
     const int i = blockIdx.x;
@@ -76,9 +83,9 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
     float4 cur[NCH], nxt[NCH];
     int c = wave;
     int32_t e_nxt = cand_id(a, i, has_pos, min(c + NW, CT - 1));
-    if (c < CT) load_row<NCH>(a, cand_id(a, i, has_pos, c), lane, d4, cur);
+    if (c < CT) load_row<NCH, B16>(a, cand_id(a, i, has_pos, c), lane, d4, cur);
     for (; c < CT; c += NW) {
-        load_row<NCH>(a, e_nxt, lane, d4, nxt);
+        load_row<NCH, B16>(a, e_nxt, lane, d4, nxt);
         e_nxt = cand_id(a, i, has_pos, min(c + 2 * NW, CT - 1));
         float best = INFINITY;
         int bw = 0;
@@ -205,12 +212,12 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
     }
 }
 
-template <int NCH, int NW, bool TRAIN, bool MASK, bool BOX>
+template <int NCH, int NW, bool TRAIN, bool MASK, bool BOX, bool B16 = false>
 hipError_t launch_variant(const ScoreArgs& a, size_t lds, hipStream_t s) {
     if (lds > 64 * 1024)
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(score_kernel<NCH, NW, TRAIN, MASK, BOX>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(score_kernel<NCH, NW, TRAIN, MASK, BOX, B16>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    hipLaunchKernelGGL((score_kernel<NCH, NW, TRAIN, MASK, BOX>), dim3(a.B), dim3(NW * 64), lds, s, a);
+    hipLaunchKernelGGL((score_kernel<NCH, NW, TRAIN, MASK, BOX, B16>), dim3(a.B), dim3(NW * 64), lds, s, a);
     return hipGetLastError();
 }
 
@@ -218,6 +225,8 @@ template <int NCH, int NW>
 hipError_t launch_nw(const ScoreArgs& a, bool train, size_t lds, hipStream_t s) {
     if (a.off) return train ? launch_variant<NCH, NW, true, false, true>(a, lds, s)
                             : launch_variant<NCH, NW, false, false, true>(a, lds, s);
+    if (a.E16) return train ? launch_variant<NCH, NW, true, false, false, true>(a, lds, s)
+                            : launch_variant<NCH, NW, false, false, false, true>(a, lds, s);
     if (train && a.mask) return launch_variant<NCH, NW, true, true, false>(a, lds, s);
     if (train) return launch_variant<NCH, NW, true, false, false>(a, lds, s);
     return launch_variant<NCH, NW, false, false, false>(a, lds, s);
@@ -244,6 +253,7 @@ hipError_t launch_score(const ScoreArgs& a, bool train, hipStream_t s) {
     if (a.C + (a.pos ? 1 : 0) <= 0) return hipErrorInvalidValue;   // the kernel clamps into a non-empty candidate list
     if (train && (a.win == nullptr) == (a.mask == nullptr)) return hipErrorInvalidValue;   // exactly one of the two
     if (a.off && (a.mask || (train && !a.doff))) return hipErrorInvalidValue;
+    if (a.E16 && (a.off || a.mask)) return hipErrorInvalidValue;     // plain vector family only
     if (a.d <= 256) return launch_nch<1>(a, train, s);
     if (a.d <= 512) return launch_nch<2>(a, train, s);
     if (a.d <= 1024) return launch_nch<4>(a, train, s);

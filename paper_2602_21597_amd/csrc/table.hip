@@ -55,10 +55,7 @@ __global__ __launch_bounds__(256) void resolve_kernel(const int32_t* __restrict_
 constexpr int G = 4;    // gradient rows in flight per wavefront
 constexpr int GP = 8;   // pairs in flight per wavefront
 
-__device__ __forceinline__ uint32_t bf16_bits(float x) {   // round to nearest, ties to even
-    const uint32_t b = __float_as_uint(x);
-    return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
-}
+__device__ __forceinline__ uint32_t bf16_bits(float x) { return f32_to_bf16_bits(x); }
 // sign code (1 = +, 2 = -, 0 = none) -> c, -c, 0
 __device__ __forceinline__ float signed_coef(uint32_t code, float c) { return code == 1u ? c : (code == 2u ? -c : 0.f); }
 
@@ -73,7 +70,9 @@ __device__ __forceinline__ uint32_t load_mask(const void* mask, size_t idx) {
 // also stored as bf16 (input of the projection's gradient).
 // BOX (box family, entity table): a pair's sign is weighted 1 where the row lies outside the
 // winning box in that coordinate and alpha where it lies inside.
-template <int NCH, bool SEM, bool BOX>
+// SH (plain vector family): the scoring pass reads a bf16 copy of the table; pair signs are taken
+// against the rounded row and the updated row is rounded into the copy.
+template <int NCH, bool SEM, bool BOX, bool SH>
 __global__ __launch_bounds__(256) void table_kernel(const TableArgs a, const AdamHyper hp) {
     const int lane = threadIdx.x & 63;
     const int d4 = a.d >> 2;
@@ -106,6 +105,16 @@ __global__ __launch_bounds__(256) void table_kernel(const TableArgs a, const Ada
             }
             g[ch] = zero4;
         }
+        // SH: the row as the scoring pass read it (rounded to bf16)
+        float4 psr[SH ? NCH : 1];
+        if (SH) {
+#pragma unroll
+            for (int ch = 0; ch < (SH ? NCH : 1); ++ch) {
+                psr[ch].x = bf16_round_f32(p[ch].x); psr[ch].y = bf16_round_f32(p[ch].y);
+                psr[ch].z = bf16_round_f32(p[ch].z); psr[ch].w = bf16_round_f32(p[ch].w);
+            }
+        }
+#define NGDB_PS(ch) (SH ? psr[SH ? (ch) : 0] : p[ch])
         for (int base = t0; base < t1; base += 64) {
             const int n = min(64, t1 - base);
             const int tl = base + min(lane, n - 1);
@@ -159,17 +168,17 @@ __global__ __launch_bounds__(256) void table_kernel(const TableArgs a, const Ada
                         for (int ch = 0; ch < NCH; ++ch) {
                             if (BOX) {
                                 const float ca = cf[q] * a.alpha;
-                                const float dx = x[q][ch].x - p[ch].x, dy = x[q][ch].y - p[ch].y,
-                                            dz = x[q][ch].z - p[ch].z, dw = x[q][ch].w - p[ch].w;
+                                const float dx = x[q][ch].x - NGDB_PS(ch).x, dy = x[q][ch].y - NGDB_PS(ch).y,
+                                            dz = x[q][ch].z - NGDB_PS(ch).z, dw = x[q][ch].w - NGDB_PS(ch).w;
                                 g[ch].x += (fabsf(dx) > xo[q][ch].x ? cf[q] : ca) * sgn(dx);
                                 g[ch].y += (fabsf(dy) > xo[q][ch].y ? cf[q] : ca) * sgn(dy);
                                 g[ch].z += (fabsf(dz) > xo[q][ch].z ? cf[q] : ca) * sgn(dz);
                                 g[ch].w += (fabsf(dw) > xo[q][ch].w ? cf[q] : ca) * sgn(dw);
                             } else {
-                                g[ch].x += cf[q] * sgn(x[q][ch].x - p[ch].x);
-                                g[ch].y += cf[q] * sgn(x[q][ch].y - p[ch].y);
-                                g[ch].z += cf[q] * sgn(x[q][ch].z - p[ch].z);
-                                g[ch].w += cf[q] * sgn(x[q][ch].w - p[ch].w);
+                                g[ch].x += cf[q] * sgn(x[q][ch].x - NGDB_PS(ch).x);
+                                g[ch].y += cf[q] * sgn(x[q][ch].y - NGDB_PS(ch).y);
+                                g[ch].z += cf[q] * sgn(x[q][ch].z - NGDB_PS(ch).z);
+                                g[ch].w += cf[q] * sgn(x[q][ch].w - NGDB_PS(ch).w);
                             }
                         }
                 }
@@ -234,10 +243,16 @@ __global__ __launch_bounds__(256) void table_kernel(const TableArgs a, const Ada
                 mrow[ch * 64 + lane] = m[ch];
                 vrow[ch * 64 + lane] = v[ch];
                 prow[ch * 64 + lane] = p[ch];
+                if (SH)
+                    reinterpret_cast<uint2*>(a.shadow + (size_t)row * a.d)[ch * 64 + lane] =
+                        make_uint2(bf16_bits(p[ch].x) | (bf16_bits(p[ch].y) << 16),
+                                   bf16_bits(p[ch].z) | (bf16_bits(p[ch].w) << 16));
             }
         }
     }
 }
+
+#undef NGDB_PS
 
 }  // namespace
 
@@ -256,11 +271,13 @@ hipError_t launch_table_update(const TableArgs& a, const AdamHyper& hp, hipStrea
     if (a.d > 1024 || (a.g_bf16 != nullptr) != (a.mask != nullptr)) return hipErrorInvalidValue;
     const bool sem = a.g_bf16 != nullptr, box = a.off != nullptr;
     if (sem && (box || a.relu_gate)) return hipErrorInvalidValue;
+    if (a.shadow && (sem || box)) return hipErrorInvalidValue;
 #define NGDB_TABLE(NCH)                                                                                      \
     do {                                                                                                     \
-        if (sem) hipLaunchKernelGGL((table_kernel<NCH, true, false>), dim3(blocks), dim3(256), 0, s, a, hp); \
-        else if (box) hipLaunchKernelGGL((table_kernel<NCH, false, true>), dim3(blocks), dim3(256), 0, s, a, hp); \
-        else hipLaunchKernelGGL((table_kernel<NCH, false, false>), dim3(blocks), dim3(256), 0, s, a, hp);   \
+        if (sem) hipLaunchKernelGGL((table_kernel<NCH, true, false, false>), dim3(blocks), dim3(256), 0, s, a, hp); \
+        else if (box) hipLaunchKernelGGL((table_kernel<NCH, false, true, false>), dim3(blocks), dim3(256), 0, s, a, hp); \
+        else if (a.shadow) hipLaunchKernelGGL((table_kernel<NCH, false, false, true>), dim3(blocks), dim3(256), 0, s, a, hp); \
+        else hipLaunchKernelGGL((table_kernel<NCH, false, false, false>), dim3(blocks), dim3(256), 0, s, a, hp);   \
     } while (0)
     if (a.d <= 256) NGDB_TABLE(1);
     else if (a.d <= 512) NGDB_TABLE(2);

@@ -48,9 +48,10 @@ def tol_of(name, tol):
 
 class Case:
     def __init__(self, N, R, d, h, B, K, gamma, mix=None, seed=0, T=None, alpha=2.1, trees=None, pos=None,
-                 d_sem=0, schedule="level", b_max=0):
+                 d_sem=0, schedule="level", b_max=0, score_bf16=False):
         self.N, self.R, self.d, self.h, self.B, self.K, self.gamma = N, R, d, h, B, K, gamma
         self.d_sem = d_sem
+        self.score_bf16 = score_bf16                     # candidate rows from a bf16 copy of E
         self.schedule, self.b_max = schedule, b_max      # order of execution: values must not depend on it
         self.hp = dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, gamma=gamma)
         self.params = wl.make_params(N, R, d, h, seed + 3, d_sem=d_sem)
@@ -64,7 +65,8 @@ class Case:
             qb = wl.make_batch(kg, B + B // 4 + 8, mix or {n: 1.0 for n in wl.configs.ALL14}, seed + 1)
         negs = wl.make_negatives(N, qb.B, K, seed + 2)
         self.qb, self.negs, self.n_redrawn = keep_clear_of_kinks(qb, negs, self.params, gamma, N, want, seed + 4,
-                                                                 strict=trees is None, sem_bits=self.sem_bits)
+                                                                 strict=trees is None, sem_bits=self.sem_bits,
+                                                                 score_bf16=score_bf16)
         self.B = self.qb.B
 
     @classmethod
@@ -77,13 +79,14 @@ class Case:
         """Another [B, K] draw of negatives, kept clear of the |.| kinks like the first."""
         negs = wl.make_negatives(self.N, self.B, self.K, seed)
         _, negs, _ = keep_clear_of_kinks(self.qb, negs, self.params, self.gamma, self.N, self.B, seed + 1,
-                                         strict=False, queries_are_clean=True, sem_bits=self.sem_bits)
+                                         strict=False, queries_are_clean=True, sem_bits=self.sem_bits,
+                                         score_bf16=self.score_bf16)
         return negs
 
     def engine(self, num_streams=1):
         from paper_2602_21597_amd import Engine
         eng = Engine(self.N, self.R, self.d, self.h, self.gamma, num_streams=num_streams, d_sem=self.d_sem,
-                     schedule={"level": 0, "max_fill": 1}[self.schedule], b_max=self.b_max)
+                     schedule={"level": 0, "max_fill": 1}[self.schedule], b_max=self.b_max, score_bf16=self.score_bf16)
         eng.bind_numpy(self.params, sem_bits=self.sem_bits)
         return eng
 
@@ -94,18 +97,18 @@ class Case:
     distances_all = staticmethod(orank.distances_all)    # query -> distance to every entity
 
     def model(self):
-        return om.Model(self.params, self.gamma, self.sem_bits)
+        return om.Model(self.params, self.gamma, self.sem_bits, self.score_bf16)
 
     def oracle_grads(self, negs=None):
-        M = om.Model(self.params, self.gamma, self.sem_bits)
+        M = self.model()
         return (M,) + om.batch_loss_and_grads(self.qb, self.negs if negs is None else negs, M)
 
 
 def keep_clear_of_kinks(qb, negs, params, gamma, N, want, seed, strict=True, queries_are_clean=False,
-                        sem_bits=None):
+                        sem_bits=None, score_bf16=False):
     """First `want` queries of qb that stay clear of every kink, with negatives
     that sit on an |.| kink redrawn.  Uses the oracle's forward pass only."""
-    M = om.Model(params, gamma, sem_bits)
+    M = om.Model(params, gamma, sem_bits, score_bf16)
     rng = np.random.default_rng(seed)
     negs = negs.copy()
     keep, redrawn = [], 0
@@ -117,10 +120,10 @@ def keep_clear_of_kinks(qb, negs, params, gamma, N, want, seed, strict=True, que
         ok = min(om.min_abs_preactivation(t) for _, t in fw) >= TAU_PRE
 
         def clear(e):
-            dist = np.abs(Y - M.entity(e)[None]).sum(axis=1)
+            dist = np.abs(Y - M.candidate(e)[None]).sum(axis=1)
             w = int(np.argmin(dist))
             tie = len(dist) > 1 and np.sort(dist)[1] - dist[w] < TAU_TIE
-            return (not tie) and np.abs(Y[w] - M.entity(e)).min() >= TAU_ABS
+            return (not tie) and np.abs(Y[w] - M.candidate(e)).min() >= TAU_ABS
 
         ok = queries_are_clean or (ok and clear(int(qb.pos[i])))
         if ok:
@@ -285,7 +288,8 @@ def check_train_steps(case, steps=3, num_streams=1, tol=TOL):
         b_p, b_m, b_v = eng.params_numpy("p"), eng.params_numpy("m"), eng.params_numpy("v")
         loss = eng.train_step(plan, nd)
         torch.cuda.synchronize()
-        ref_loss, G = om.train_step(case.qb, negs, P, state, t, case.hp, case.sem_bits, track_sq=True)
+        ref_loss, G = om.train_step(case.qb, negs, P, state, t, case.hp, case.sem_bits, track_sq=True,
+                                    score_bf16=case.score_bf16)
         a_p, a_m, a_v = eng.params_numpy("p"), eng.params_numpy("m"), eng.params_numpy("v")
         if case.B:
             assert abs(float(loss.cpu()[0]) - ref_loss) <= tol * abs(ref_loss)

@@ -199,6 +199,42 @@ def test_text_features_bad_widths_are_rejected():
         assert e.value.code == binding.ERR_ARG
 
 
+def _bf16_bits(x):
+    b = np.ascontiguousarray(x, np.float32).view(np.uint32)
+    return ((b + 0x7FFF + ((b >> 16) & 1)) >> 16).astype(np.uint16)
+
+
+def test_candidate_rows_from_a_bf16_copy_of_the_table():
+    _say("score_bf16: N=2000 d=100 h=72 B=90 K=7 and N=3000 d=400 h=800 B=150 K=19; copy stays the rounding of E")
+    import torch
+    small = par.Case(2000, 20, 100, 72, 90, 7, 12.0, seed=61, score_bf16=True)
+    par.check_forward_backward(small)
+    par.check_train_steps(small, steps=1, num_streams=2)
+    case = par.Case(3000, 30, 400, 800, 150, 19, 55.0, seed=62, score_bf16=True)
+    eng = par.check_forward_backward(case)
+    # the values are those of the rounded rows, not of the fp32 rows
+    g = eng.grads()
+    s_fp32 = np.stack(om.batch_loss_and_grads(case.qb, case.negs, om.Model(case.params, case.gamma), want_grads=False)[2])
+    assert np.abs(g["pair_score"].reshape(case.B, case.K + 1) - s_fp32).max() > 1e-3
+    np.testing.assert_array_equal(g["e_shadow"], _bf16_bits(case.params["E"]))
+    # three steps: the copy follows the table bit for bit; untouched rows keep theirs
+    plan = eng.plan(case.qb)
+    for t in range(3):
+        eng.train_step(plan, case.neg_dev(case.fresh_negs(7100 + t)))
+    torch.cuda.synchronize()
+    eng.forward_backward(plan, case.neg_dev())
+    np.testing.assert_array_equal(eng.grads()["e_shadow"], _bf16_bits(eng.params_numpy()["E"]))
+    # candidate scores and the all-entity ranking read the same rows
+    cand = wl.make_negatives(case.N, case.B, 9, 5)
+    M = case.model()
+    fresh = case.engine()
+    p2 = fresh.plan(case.qb)
+    got = fresh.score(p2, torch.from_numpy(cand).cuda()).cpu().numpy()
+    par.assert_close(got, orank.score_candidates(case.qb, cand, M), "candidate scores from the bf16 copy")
+    par.check_topk(case, 10, 8)
+    par.check_filtered_ranks(par.Case(1000, 20, 32, 64, 40, 8, 12.0, seed=63, score_bf16=True), 4)
+
+
 def test_fb15k237_shape_full_size():
     # the benchmark workload itself, in the launch configuration bench.py times
     _say("config 1 (B=512, K=128, d=400), forward_backward + 1 train step")
@@ -301,3 +337,7 @@ def test_errors_are_reported_not_raised_as_faults():
     with pytest.raises(NgdbError) as e:
         binding.Engine(case.N, case.R, case.d, case.h, case.gamma, schedule=7)
     assert e.value.code == binding.ERR_ARG
+    for kw in (dict(d_sem=64), dict(family=binding.FAMILY_BOX)):          # the bf16 copy: plain vector family only
+        with pytest.raises(NgdbError) as e:
+            binding.Engine(case.N, case.R, case.d, 64, case.gamma, score_bf16=True, **kw)
+        assert e.value.code == binding.ERR_ARG

@@ -168,7 +168,7 @@ def test_split_and_permutation_invariance():
 
 
 # ---------------------------------------------------------------- gradients
-def _torch_loss(qb, negs, P, gamma, sem=None):
+def _torch_loss(qb, negs, P, gamma, sem=None, cand_rows=None):
     """Independent re-statement with torch ops + autograd (per query, fp64)."""
     def ent(e):
         row = P["E"][e]
@@ -192,7 +192,8 @@ def _torch_loss(qb, negs, P, gamma, sem=None):
     for i in range(qb.B):
         Y = torch.stack([ev(b) for b in om.dnf(qb.tree(i))])
         cand = torch.tensor(np.concatenate([[qb.pos[i]], negs[i]]), dtype=torch.long)
-        dist = (Y[:, None, :] - ent(cand)[None]).abs().sum(-1).min(0).values
+        rows = cand_rows[cand] if cand_rows is not None else ent(cand)
+        dist = (Y[:, None, :] - rows[None]).abs().sum(-1).min(0).values
         s = gamma - dist
         total = total + (-torch.nn.functional.logsigmoid(s[0])
                          - torch.nn.functional.logsigmoid(-s[1:]).mean()) / (2 * qb.B)
@@ -238,6 +239,35 @@ def test_semantic_fuse_gradients_against_torch_autograd():
     assert loss == pytest.approx(float(tl), rel=1e-12)
     np.testing.assert_allclose(G.dense["Wp"], P["Wp"].grad.numpy(), rtol=1e-9, atol=1e-14)
     np.testing.assert_allclose(G.table_dense("E", p["E"].shape), P["E"].grad.numpy(), rtol=1e-9, atol=1e-14)
+
+
+def test_bf16_candidate_rows_against_torch():
+    """Scoring from a bf16 copy of E: the rounding is torch's; positives and negatives use the
+    rounded rows, anchors the exact ones, and the gradient of a rounded row goes to E unchanged."""
+    _, qb, negs, p, _ = tiny(seed=6, B=20, K=5)
+    a = int(qb.arg[0])                 # an entity that is anchor and negative
+    negs[2, 1] = a
+    M = om.Model(p, 12.0, score_bf16=True)
+    E32 = torch.tensor(p["E"])
+    assert np.array_equal(M.candidate(np.arange(p["E"].shape[0])), E32.bfloat16().double().numpy())
+    assert not np.array_equal(M.candidate(3), M.entity(3))
+    loss, G, _ = om.batch_loss_and_grads(qb, negs, M)
+    P = {k: torch.tensor(v, dtype=torch.float64, requires_grad=True) for k, v in p.items()}
+    rounded = (E32.bfloat16().double() - P["E"]).detach() + P["E"]          # straight-through
+    tl = _torch_loss(qb, negs, P, 12.0, cand_rows=rounded)
+    tl.backward()
+    assert loss == pytest.approx(float(tl.detach()), rel=1e-12)
+    exact_loss = om.batch_loss_and_grads(qb, negs, om.Model(p, 12.0), want_grads=False)[0]
+    assert abs(loss - exact_loss) > 1e-7 * abs(exact_loss)                   # the rounding is visible
+    for k in G.dense:
+        np.testing.assert_allclose(G.dense[k], P[k].grad.numpy(), rtol=1e-9, atol=1e-14, err_msg=k)
+    for tname in ("E", "R"):
+        np.testing.assert_allclose(G.table_dense(tname, p[tname].shape), P[tname].grad.numpy(),
+                                   rtol=1e-9, atol=1e-14, err_msg=tname)
+    # ranking reads the same rows
+    full = orank.distances_all(qb, 0, M)
+    s = orank.score_candidates(qb, negs, M)
+    np.testing.assert_allclose(12.0 - full[negs[0]], s[0], rtol=1e-13)
 
 
 def test_finite_differences_every_tensor():
