@@ -145,7 +145,7 @@ typedef struct ngdb_config {
                               row unchanged.  The copy is made by ngdb_bind_params and
                               kept current by ngdb_train_step: bind again after writing
                               to E from outside.  Vector family without text features
-                              only                                                     */
+                              only; d a multiple of 8                                  */
 } ngdb_config;
 
 /* A trainable tensor with its Adam moments (all device, fp32, same shape). */

@@ -767,7 +767,7 @@ int ngdb_create(const ngdb_config* cfg, ngdb_ctx_t** out) {
     if (cfg->family != NGDB_FAMILY_VEC && cfg->family != NGDB_FAMILY_BOX) return NGDB_ERR_ARG;
     if (cfg->family == NGDB_FAMILY_BOX && (cfg->d_sem != 0 || !(cfg->box_alpha >= 0.f && cfg->box_alpha <= 1.f)))
         return NGDB_ERR_ARG;
-    if ((cfg->score_bf16 != 0 && cfg->score_bf16 != 1) || (cfg->score_bf16 && (cfg->family != NGDB_FAMILY_VEC || cfg->d_sem != 0)))
+    if ((cfg->score_bf16 != 0 && cfg->score_bf16 != 1) || (cfg->score_bf16 && (cfg->family != NGDB_FAMILY_VEC || cfg->d_sem != 0 || (cfg->d & 7))))
         return NGDB_ERR_ARG;
     ngdb_ctx_t* c = new (std::nothrow) ngdb_ctx_s();
     if (!c) return NGDB_ERR_OOM;

@@ -19,12 +19,25 @@ __device__ __forceinline__ uint32_t sign_code(float s) { return s > 0.f ? 1u : (
 __device__ __forceinline__ int32_t cand_id(const ScoreArgs& a, int i, int has_pos, int c) {
     return (has_pos && c == 0) ? a.pos[i] : a.cand[(size_t)i * a.C + (c - has_pos)];
 }
+// The float4 piece of a row that lane holds in its register chunk ch.  fp32 rows: pieces 64
+// apart (a wavefront reads 1 KB per request).  bf16 rows (B16; two chunks per 16-byte load): a
+// lane owns 8 consecutive coordinates, so that a request again covers 1 KB of contiguous row.
+template <bool B16>
+__device__ __forceinline__ int col_of(int ch, int lane) {
+    return B16 ? (ch >> 1) * 128 + 2 * lane + (ch & 1) : ch * 64 + lane;
+}
+typedef uint32_t score_u32x4 __attribute__((ext_vector_type(4)));
 template <int NCH, bool B16>
 __device__ __forceinline__ void load_row(const ScoreArgs& a, int32_t e, int lane, int d4, float4 (&dst)[NCH]) {
-    if (B16) {   // the bf16 copy of the table: 8 bytes per lane and chunk
-        const uint2* row = reinterpret_cast<const uint2*>(a.E16 + (size_t)e * a.d);
+    if (B16) {   // the bf16 copy of the table: 16 bytes (8 coordinates) per lane and chunk pair; d % 8 == 0
+        const score_u32x4* row = reinterpret_cast<const score_u32x4*>(a.E16 + (size_t)e * a.d);
+        const int d8 = d4 >> 1;
 #pragma unroll
-        for (int ch = 0; ch < NCH; ++ch) dst[ch] = bf16x4_to_f32(row[min(ch * 64 + lane, d4 - 1)]);
+        for (int g = 0; g < NCH / 2; ++g) {
+            const score_u32x4 v = row[min(g * 64 + lane, d8 - 1)];
+            dst[2 * g] = bf16x4_to_f32(make_uint2(v[0], v[1]));
+            dst[2 * g + 1] = bf16x4_to_f32(make_uint2(v[2], v[3]));
+        }
     } else {
         const float4* row = reinterpret_cast<const float4*>(a.E + (size_t)e * a.d);
 #pragma unroll
@@ -93,7 +106,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
             float dist = 0.f;
 #pragma unroll
             for (int ch = 0; ch < NCH; ++ch) {
-                const int col = ch * 64 + lane;
+                const int col = col_of<B16>(ch, lane);
                 if (col < d4) {
                     const float4 y = ybr[b * d4 + col];
                     const float ax = fabsf(y.x - cur[ch].x), ay = fabsf(y.y - cur[ch].y),
@@ -128,7 +141,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
             uint32_t bits = 0;      // 2 bits per coordinate of this lane: 1 = positive, 2 = negative difference
 #pragma unroll
             for (int ch = 0; ch < NCH; ++ch) {
-                const int col = ch * 64 + lane;
+                const int col = col_of<B16>(ch, lane);
                 if (col < d4) {
                     const float4 y = ybr[bw * d4 + col];
                     const float sx = sgn(y.x - cur[ch].x), sy = sgn(y.y - cur[ch].y),
@@ -184,7 +197,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
         if (nb == 1) {
 #pragma unroll
             for (int ch = 0; ch < NCH; ++ch) {
-                const int col = ch * 64 + lane;
+                const int col = col_of<B16>(ch, lane);
                 if (col < d4) {
                     myacc[col] = dyr[ch];
                     if (BOX) myacc[d4 + col] = dor[ch];
@@ -254,7 +267,8 @@ hipError_t launch_score(const ScoreArgs& a, bool train, hipStream_t s) {
     if (train && (a.win == nullptr) == (a.mask == nullptr)) return hipErrorInvalidValue;   // exactly one of the two
     if (a.off && (a.mask || (train && !a.doff))) return hipErrorInvalidValue;
     if (a.E16 && (a.off || a.mask)) return hipErrorInvalidValue;     // plain vector family only
-    if (a.d <= 256) return launch_nch<1>(a, train, s);
+    if (a.E16 && (a.d & 7)) return hipErrorInvalidValue;            // 16-byte loads of bf16 rows
+    if (a.d <= 256 && !a.E16) return launch_nch<1>(a, train, s);    // (bf16 rows: chunks come in pairs)
     if (a.d <= 512) return launch_nch<2>(a, train, s);
     if (a.d <= 1024) return launch_nch<4>(a, train, s);
     return hipErrorInvalidValue;

@@ -205,9 +205,9 @@ def _bf16_bits(x):
 
 
 def test_candidate_rows_from_a_bf16_copy_of_the_table():
-    _say("score_bf16: N=2000 d=100 h=72 B=90 K=7 and N=3000 d=400 h=800 B=150 K=19; copy stays the rounding of E")
+    _say("score_bf16: N=2000 d=104 h=72 B=90 K=7 and N=3000 d=400 h=800 B=150 K=19; copy stays the rounding of E")
     import torch
-    small = par.Case(2000, 20, 100, 72, 90, 7, 12.0, seed=61, score_bf16=True)
+    small = par.Case(2000, 20, 104, 72, 90, 7, 12.0, seed=61, score_bf16=True)
     par.check_forward_backward(small)
     par.check_train_steps(small, steps=1, num_streams=2)
     case = par.Case(3000, 30, 400, 800, 150, 19, 55.0, seed=62, score_bf16=True)
@@ -337,7 +337,8 @@ def test_errors_are_reported_not_raised_as_faults():
     with pytest.raises(NgdbError) as e:
         binding.Engine(case.N, case.R, case.d, case.h, case.gamma, schedule=7)
     assert e.value.code == binding.ERR_ARG
-    for kw in (dict(d_sem=64), dict(family=binding.FAMILY_BOX)):          # the bf16 copy: plain vector family only
+    # the bf16 copy: plain vector family only, width a multiple of 8
+    for kw in (dict(d=32, d_sem=64), dict(d=32, family=binding.FAMILY_BOX), dict(d=36)):
         with pytest.raises(NgdbError) as e:
-            binding.Engine(case.N, case.R, case.d, 64, case.gamma, score_bf16=True, **kw)
+            binding.Engine(case.N, case.R, kw.pop("d"), 64, case.gamma, score_bf16=True, **kw)
         assert e.value.code == binding.ERR_ARG
