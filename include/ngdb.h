@@ -275,7 +275,8 @@ int ngdb_plan_host_sched(int32_t n_entities, int32_t n_relations, const ngdb_que
 int ngdb_plan_export(const ngdb_plan_t* plan, ngdb_plan_view* out);
 /* May be called right after the last step that uses the plan has been enqueued:
  * the plan's device buffer goes back to its context and is reused only after
- * that step has finished.  Free every plan before destroying its context.     */
+ * that step has finished.  A plan that outlives its context loses its device
+ * buffer there: it can still be exported and must still be freed, not executed. */
 void ngdb_plan_free(ngdb_plan_t* plan);
 
 /* One training step (Alg. 1 lines 5-21): forward over the plan's frontiers,

@@ -145,8 +145,9 @@ class _BatchArrays:
 
 
 class Plan:
-    def __init__(self, handle):
+    def __init__(self, handle, owner=None):
         self.handle = handle
+        self.owner = owner      # keeps the engine (the plan's context) alive as long as the plan
 
     def export(self):
         """All plan arrays as a dict of numpy int32 copies / ints."""
@@ -167,6 +168,7 @@ class Plan:
         if self.handle:
             lib().ngdb_plan_free(self.handle)
             self.handle = None
+        self.owner = None
 
     def __del__(self):
         try:
@@ -368,7 +370,7 @@ class Engine:
         c = qb if arrs is None else arrs.c
         h = C.c_void_p()
         _check(lib().ngdb_plan(self.ctx, C.byref(c), C.byref(h)), self.ctx)
-        return Plan(h)
+        return Plan(h, self)
 
     def _stream(self, stream):
         return C.c_void_p(stream.cuda_stream if stream is not None else

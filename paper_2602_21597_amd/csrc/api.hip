@@ -90,7 +90,8 @@ struct ngdb_ctx_s {
     size_t gw_off[13]{};
     hipStream_t upload = nullptr;        // plan uploads, independent of the compute streams
     std::vector<PlanBlob> blob_pool;
-    std::mutex mu;                       // guards blob_pool and err: planning may run on a second host thread
+    std::vector<ngdb_plan_t*> live_plans;   // plans that hold a device buffer of this context
+    std::mutex mu;                       // guards blob_pool, live_plans and err: planning may run on a second host thread
     // kernel timing
     uint32_t timing_mask = 0;
     struct Bracket { int cls; hipEvent_t a, b; };
@@ -800,6 +801,14 @@ void ngdb_destroy(ngdb_ctx_t* c) {
     if (c->ev_join) (void)hipEventDestroy(c->ev_join);
     if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
     if (c->upload) (void)hipStreamDestroy(c->upload);
+    // plans that outlive the context keep their host arrays (export, free) and lose their device buffer
+    for (ngdb_plan_t* pl : c->live_plans) {
+        c->blob_pool.push_back(pl->blob);
+        pl->blob = PlanBlob{};
+        pl->d_blob = nullptr;
+        pl->owner = nullptr;
+    }
+    c->live_plans.clear();
     for (PlanBlob& b : c->blob_pool) {
         if (b.dev) (void)hipFree(b.dev);
         if (b.pinned) (void)hipHostFree(b.pinned);
@@ -971,6 +980,10 @@ int ngdb_plan(ngdb_ctx_t* c, const ngdb_query_batch* qb, ngdb_plan_t** out) {
     }
     pl->owner = c;
     pl->blob = pb;
+    {
+        std::lock_guard<std::mutex> lk(c->mu);
+        c->live_plans.push_back(pl);
+    }
     pl->d_blob = pb.dev;
     pl->d_in_ref = pl->d_blob + o_ref; pl->d_in_gslot = pl->d_blob + o_gs; pl->d_rel = pl->d_blob + o_rel;
     pl->d_root_off = pl->d_blob + o_ro; pl->d_root_slot = pl->d_blob + o_rs; pl->d_pos = pl->d_blob + o_pos;
@@ -1000,9 +1013,11 @@ int ngdb_plan_export(const ngdb_plan_t* pl, ngdb_plan_view* v) {
 
 void ngdb_plan_free(ngdb_plan_t* pl) {
     if (!pl) return;
-    if (pl->owner && pl->blob.dev) {   // reused once last_use has passed
-        std::lock_guard<std::mutex> lk(pl->owner->mu);
-        pl->owner->blob_pool.push_back(pl->blob);
+    if (pl->owner) {   // the device buffer goes back to its context (reused once last_use has passed)
+        ngdb_ctx_t* c = pl->owner;
+        std::lock_guard<std::mutex> lk(c->mu);
+        c->live_plans.erase(std::remove(c->live_plans.begin(), c->live_plans.end(), pl), c->live_plans.end());
+        if (pl->blob.dev) c->blob_pool.push_back(pl->blob);
     }
     delete pl;
 }

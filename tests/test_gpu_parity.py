@@ -337,6 +337,15 @@ def test_errors_are_reported_not_raised_as_faults():
     with pytest.raises(NgdbError) as e:
         binding.Engine(case.N, case.R, case.d, case.h, case.gamma, schedule=7)
     assert e.value.code == binding.ERR_ARG
+    # a plan that outlives its context: still readable and freeable, no longer executable
+    short_lived = case.engine()
+    orphan = short_lived.plan(case.qb)
+    short_lived.close()
+    assert orphan.export()["n_queries"] == case.B
+    with pytest.raises(NgdbError) as e:
+        eng.train_step(orphan, case.neg_dev())
+    assert e.value.code == binding.ERR_ARG
+    orphan.free()
     # the bf16 copy: plain vector family only, width a multiple of 8
     for kw in (dict(d=32, d_sem=64), dict(d=32, family=binding.FAMILY_BOX), dict(d=36)):
         with pytest.raises(NgdbError) as e:
