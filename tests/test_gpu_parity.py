@@ -299,6 +299,57 @@ def test_sampled_batches_train_like_any_other():
         plan.free()
 
 
+@pytest.mark.parametrize("family", ["vec", "box"])
+def test_long_run_of_the_whole_pipeline_learns(family):
+    """600 steps of sampler -> planner thread -> train step with the library stream on: the steady
+    state of the plan-buffer pool, the events and the two streams; the loss of a fixed probe batch,
+    measured by the oracle on the parameters before and after, must fall."""
+    _say("600 steps, online sampler, planning on a second thread, library stream; %s family" % family)
+    import torch
+    from concurrent.futures import ThreadPoolExecutor
+    from oracle import box as ob
+    from paper_2602_21597_amd import Engine, Sampler, binding
+    c = wl.get_config(0)
+    box = family == "box"
+    kg = wl.make_kg(c.N, c.R, c.T, c.alpha, c.seed)
+    params = wl.make_box_params(c.N, c.R, c.d, c.h, 3) if box else wl.make_params(c.N, c.R, c.d, c.h, 3)
+    eng = Engine(c.N, c.R, c.d, c.h, 3.0, lr=3e-3, num_streams=2, family=binding.FAMILY_BOX if box else 0,
+                 box_alpha=0.25)
+    eng.bind_numpy(params)
+    names = list(wl.EPFO9 if box else wl.configs.ALL14)
+    smp = Sampler(c.N, c.R, kg.head, kg.rel, kg.tail, names, None, 11, 4)
+    probe = Sampler(c.N, c.R, kg.head, kg.rel, kg.tail, names, None, 12, 1).next(128, 16)
+
+    def probe_loss(p):
+        if box:
+            return ob.batch_loss_and_grads(probe, probe.negs, ob.BoxModel(p, 3.0, 0.25), want_grads=False)[0]
+        return om.batch_loss_and_grads(probe, probe.negs, om.Model(p, 3.0), want_grads=False)[0]
+
+    before = probe_loss(eng.params_numpy())
+    B, K = 64, 16
+    pool = ThreadPoolExecutor(1)
+
+    def produce():
+        b = smp.next(B, K)
+        return eng.plan(b), torch.from_numpy(b.negs).pin_memory()
+
+    nxt = pool.submit(produce)
+    losses = []
+    for t in range(600):
+        plan, negs = nxt.result()
+        nxt = pool.submit(produce)
+        loss = eng.train_step(plan, negs.cuda(non_blocking=True))
+        plan.free()
+        if t % 100 == 99:
+            losses.append(float(loss.cpu()[0]))
+    nxt.result()[0].free()
+    pool.shutdown()
+    torch.cuda.synchronize()
+    assert eng.step_count() == 600 and np.all(np.isfinite(losses))
+    after = probe_loss(eng.params_numpy())
+    assert after < 0.9 * before, (before, after, losses)
+
+
 def test_errors_are_reported_not_raised_as_faults():
     from paper_2602_21597_amd import NgdbError, binding
     case = par.Case.from_config(0)
