@@ -20,9 +20,14 @@ def test_planner_and_sampler_under_sanitizers(tmp_path, flags):
     cmd = ["g++", "-std=c++17", "-O1", "-g", flags, "-fno-omit-frame-pointer", "-I" + os.path.join(ROOT, "include"),
            "-I" + CSRC, os.path.join(HERE, "host_sanitize_driver.cpp"), os.path.join(CSRC, "planner.cpp"),
            os.path.join(CSRC, "sampler.cpp"), "-lpthread", "-o", exe]
-    subprocess.run(cmd, check=True, capture_output=True, timeout=300)
+    built = subprocess.run(cmd, capture_output=True, text=True, timeout=300)
+    if built.returncode != 0 and ("cannot find -l" in built.stderr or "No such file" in built.stderr):
+        pytest.skip("sanitizer runtime library not installed: " + built.stderr.strip().splitlines()[-1])
+    assert built.returncode == 0, built.stderr[-4000:]
     env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1")
     out = subprocess.run([exe], capture_output=True, text=True, timeout=300, env=env)
+    if out.returncode != 0 and ("runtime does not come first" in out.stderr or "unexpected memory mapping" in out.stderr):
+        pytest.skip("the sanitizer runtime cannot start in this environment: " + out.stderr.strip().splitlines()[0])
     assert out.returncode == 0, out.stdout[-2000:] + out.stderr[-4000:]
     assert "ok" in out.stdout.splitlines()[-1]
     assert "malformed: rc -1" in out.stdout and "range: rc -3" in out.stdout
