@@ -5,7 +5,6 @@ import pytest
 
 import workloads as wl
 from oracle import box as ob
-from oracle import model as om
 from tests import parity_box as pb
 
 pytestmark = pytest.mark.gpu

@@ -362,7 +362,6 @@ def test_errors_are_reported_not_raised_as_faults():
         eng.train_step(host_plan, case.neg_dev())
     assert e.value.code == binding.ERR_ARG
     # ranking calls: a plan without a device, top-k out of range, answer lists without output
-    import ctypes as C
     import torch
     L = binding.lib()
     plan = eng.plan(case.qb)
