@@ -333,9 +333,13 @@ int ngdb_rank_metrics(const int32_t* d_rank, const int32_t* d_ans_off, const int
  * its own random stream (seed, batch number, query number): batches do not depend on
  * n_threads.  ngdb_sampler_next fills `batch` (and *neg: host [n_queries, K] uniform entity
  * ids; *template_id: host [n_queries] index into the names) with arrays owned by the sampler,
- * valid until the call after the next one on it (two sets of buffers take turns, so batch
- * t can be planned while batch t+1 is drawn); the batch can go straight to ngdb_plan.  One sampler must
- * not be used from two threads at once (it may run beside a context's calls).            */
+ * valid until the call after the next one on it; the batch can go straight to ngdb_plan.
+ * After a call has returned batch t the sampler's own threads draw batch t+1 with the same
+ * sizes in the background (three sets of buffers take turns), so a caller that asks for equal
+ * sizes call after call waits only for what is not drawn yet; a call with other sizes drops
+ * the batch read ahead and draws its own (the stream of batches is the same either way).
+ * One sampler must not be used from two threads at once (it may run beside a context's
+ * calls).                                                                                */
 typedef struct ngdb_sampler_s ngdb_sampler_t;
 int ngdb_sampler_create(int32_t n_entities, int32_t n_relations, int64_t n_triples,
                         const int32_t* head, const int32_t* rel, const int32_t* tail,

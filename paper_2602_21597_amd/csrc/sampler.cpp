@@ -328,9 +328,54 @@ struct ngdb_sampler_s {
     int n_threads = 1;
     std::unique_ptr<Workers> workers;   // n_threads - 1 helpers; the caller's thread works too
     std::vector<Query> queries;         // per query scratch, reused
-    BatchArrays out[2];                 // two sets taking turns: a batch stays valid over the next call
+    BatchArrays out[3];                 // three sets taking turns: a batch stays valid over the next call
+                                        // while the one after it is already being drawn
     std::string err;
+    // Read-ahead: after a call has returned batch t, a coordinator thread draws batch t+1 (same
+    // sizes) with the helpers, so that the next call usually finds its batch ready.  The batches
+    // are functions of (seed, batch number, query number): reading ahead changes nothing in them.
+    std::thread coordinator;
+    std::mutex pm;
+    std::condition_variable pcv;
+    bool pf_requested = false, pf_done = false, pf_stop = false;   // guarded by pm
+    uint64_t pf_no = 0;
+    int pf_B = 0, pf_K = 0, pf_rc = NGDB_OK;
+
+    ~ngdb_sampler_s() {
+        if (coordinator.joinable()) {
+            {
+                std::lock_guard<std::mutex> lk(pm);
+                pf_stop = true;
+            }
+            pcv.notify_all();
+            coordinator.join();
+        }
+    }
 };
+
+namespace {
+int fill_batch(ngdb_sampler_s* s, uint64_t batch_no, int32_t B, int32_t K, BatchArrays& o);
+
+void coordinator_loop(ngdb_sampler_s* s) {
+    for (;;) {
+        uint64_t no;
+        int B, K;
+        {
+            std::unique_lock<std::mutex> lk(s->pm);
+            s->pcv.wait(lk, [&] { return s->pf_stop || (s->pf_requested && !s->pf_done); });
+            if (s->pf_stop) return;
+            no = s->pf_no; B = s->pf_B; K = s->pf_K;
+        }
+        const int rc = fill_batch(s, no, B, K, s->out[no % 3]);
+        {
+            std::lock_guard<std::mutex> lk(s->pm);
+            s->pf_rc = rc;
+            s->pf_done = true;
+        }
+        s->pcv.notify_all();
+    }
+}
+}  // namespace
 
 extern "C" {
 
@@ -402,6 +447,7 @@ int ngdb_sampler_create(int32_t N, int32_t R, int64_t T, const int32_t* head, co
     s->n_threads = n_threads;
     try {
         if (n_threads > 1) s->workers.reset(new Workers(n_threads - 1));
+        s->coordinator = std::thread(coordinator_loop, s);
     } catch (...) {
         delete s;
         return NGDB_ERR_OOM;
@@ -412,11 +458,10 @@ int ngdb_sampler_create(int32_t N, int32_t R, int64_t T, const int32_t* head, co
 
 void ngdb_sampler_destroy(ngdb_sampler_t* s) { delete s; }
 
-int ngdb_sampler_next(ngdb_sampler_t* s, int32_t B, int32_t K, ngdb_query_batch* batch, const int32_t** neg,
-                      const uint8_t** template_id) {
-    if (!s || !batch || B < 0 || K < 0 || (K > 0 && !neg)) return NGDB_ERR_ARG;
-    const uint64_t batch_no = s->batch_no++;
-    BatchArrays& o = s->out[batch_no & 1];
+extern "C++" {
+namespace {
+// draws batch number batch_no into o (the calling thread works beside the helpers)
+int fill_batch(ngdb_sampler_s* s, uint64_t batch_no, int32_t B, int32_t K, BatchArrays& o) {
     std::vector<int> failed;
     try {
         if ((int)s->queries.size() < B) s->queries.resize((size_t)B);
@@ -494,6 +539,37 @@ int ngdb_sampler_next(ngdb_sampler_t* s, int32_t B, int32_t K, ngdb_query_batch*
         }
     } catch (const std::bad_alloc&) {
         return NGDB_ERR_OOM;
+    }
+    return NGDB_OK;
+}
+}  // namespace
+}  // extern "C++"
+
+int ngdb_sampler_next(ngdb_sampler_t* s, int32_t B, int32_t K, ngdb_query_batch* batch, const int32_t** neg,
+                      const uint8_t** template_id) {
+    if (!s || !batch || B < 0 || K < 0 || (K > 0 && !neg)) return NGDB_ERR_ARG;
+    const uint64_t batch_no = s->batch_no++;
+    BatchArrays& o = s->out[batch_no % 3];
+    int rc;
+    bool ready = false;
+    {   // a batch read ahead by the coordinator?
+        std::unique_lock<std::mutex> lk(s->pm);
+        if (s->pf_requested) {
+            s->pcv.wait(lk, [&] { return s->pf_done; });
+            ready = s->pf_no == batch_no && s->pf_B == B && s->pf_K == K;
+            rc = s->pf_rc;
+            s->pf_requested = s->pf_done = false;
+        }
+    }
+    if (!ready) rc = fill_batch(s, batch_no, B, K, o);     // first call, or other sizes than read ahead
+    if (rc != NGDB_OK) return rc;
+    if (s->coordinator.joinable()) {   // read ahead: the next batch with the same sizes
+        {
+            std::lock_guard<std::mutex> lk(s->pm);
+            s->pf_no = batch_no + 1; s->pf_B = B; s->pf_K = K;
+            s->pf_requested = true; s->pf_done = false;
+        }
+        s->pcv.notify_all();
     }
     batch->n_queries = B;
     batch->node_off = o.node_off.data();

@@ -28,7 +28,22 @@ int main() {
                 if (rc) { printf("plan rc %d %s\n", rc, err.c_str()); return 1; }
             }
         }
-        ngdb_sampler_destroy(s);
+        // equal sizes call after call: the library reads the next batch ahead while this one is in
+        // use; a batch must stay unchanged over the call that follows it
+        uint64_t sum_prev = 0; const int32_t* arg_prev = nullptr; int64_t n_prev = 0;
+        for (int it = 0; it < 12; ++it) {
+            ngdb_query_batch qb; const int32_t* neg; const uint8_t* tid;
+            rc = ngdb_sampler_next(s, 300, 16, &qb, &neg, &tid);
+            if (rc) { printf("next rc %d %s\n", rc, ngdb_sampler_last_error(s)); return 1; }
+            if (arg_prev) {
+                uint64_t again = 0;
+                for (int64_t i = 0; i < n_prev; ++i) again = again * 1000003u + (uint32_t)arg_prev[i];
+                if (again != sum_prev) { printf("batch %d changed during the next call\n", it - 1); return 1; }
+            }
+            n_prev = qb.node_off[qb.n_queries]; arg_prev = qb.arg; sum_prev = 0;
+            for (int64_t i = 0; i < n_prev; ++i) sum_prev = sum_prev * 1000003u + (uint32_t)arg_prev[i];
+        }
+        ngdb_sampler_destroy(s);     // with a batch being read ahead
     }
     // malformed batches must be rejected, not crash
     {

@@ -101,6 +101,25 @@ def test_batches_do_not_depend_on_thread_count_and_differ_from_each_other(kg):
     assert not np.array_equal(other.pos, first.pos)
 
 
+def test_read_ahead_does_not_change_the_batches_and_keeps_one_valid_over_the_next_call(kg):
+    """Batch t is a function of (seed, t, sizes): a sampler that is asked for other sizes in
+    between (its read-ahead is dropped each time) gives the same batches as one asked for equal
+    sizes throughout (read-ahead used); a raw batch stays unchanged over the following call."""
+    steady, mixed = make(kg, seed=5), make(kg, seed=5, n_threads=3)
+    for t in range(6):
+        a = steady.next(200, 6)
+        b = mixed.next(200, 6) if t % 2 else mixed.next(17 + t, 2)
+        if t % 2:
+            for f in ("node_off", "op", "arg", "in_off", "in_idx", "pos", "negs"):
+                assert np.array_equal(getattr(a, f), getattr(b, f)), (t, f)
+    s = make(kg, seed=6)
+    c0, n0 = s.next_raw(128, 9)
+    keep = n0.copy()
+    s.next_raw(128, 9)
+    assert np.array_equal(n0, keep)
+    s.close()                                            # with a batch being read ahead
+
+
 def test_template_mixture_follows_the_weights(kg):
     s = make(kg, ["1p", "2i", "pni"], [0.6, 0.3, 0.1], seed=3)
     names = []
