@@ -49,6 +49,12 @@ __device__ __forceinline__ void load_row(const ScoreArgs& a, int32_t e, int lane
 // BOX: the query side is a box (centre from act, offset from off) and the distance is
 // sum relu(|e-c| - o) + alpha * sum min(|e-c|, o); in LDS the offsets of the branches follow
 // the centres and the offset gradients follow the centre gradients.
+// Gradients of the query side: a wavefront keeps those of branch 0 in registers and those of the
+// other branches (unions) in LDS accumulators of its own.  At the end the registers are summed
+// over the wavefronts: in workgroups of four wavefronts (large batches, where occupancy decides)
+// one after the other into the LDS area that held the branch rows, so that LDS per workgroup
+// stays small enough for eight wavefronts per SIMD; in larger workgroups (small batches) through
+// a staging area per wavefront and one barrier.
 // B16: candidate rows come from the bf16 copy of the table.
 template <int NCH, int NW, bool TRAIN, bool MASK, bool BOX, bool B16>
 __global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
@@ -63,8 +69,10 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
 
     constexpr int PARTS = BOX ? 2 : 1;                               // centre (and offset) per branch
     float4* ybr = reinterpret_cast<float4*>(lds);                    // [PARTS][nb][d4]
-    float4* accs = ybr + (size_t)PARTS * a.max_branch * d4;          // [NW][PARTS][nb][d4]   (TRAIN)
-    float* lossp = reinterpret_cast<float*>(accs + (TRAIN ? (size_t)NW * PARTS * a.max_branch * d4 : 0));
+    float4* accs = ybr + (size_t)PARTS * a.max_branch * d4;          // [NW][PARTS][nb-1][d4]   (TRAIN)
+    constexpr bool SEQ = NW <= 4;                                    // how branch 0 is summed over the wavefronts
+    float4* stage = accs + (TRAIN ? (size_t)NW * PARTS * (a.max_branch - 1) * d4 : 0);   // [NW][PARTS][d4]  (!SEQ)
+    float* lossp = reinterpret_cast<float*>(stage + (TRAIN && !SEQ ? (size_t)NW * PARTS * d4 : 0));
     const float4* obr = ybr + (size_t)nb * d4;                       // offsets (BOX)
 
     for (int idx = tid; idx < PARTS * nb * d4; idx += NW * 64) {
@@ -73,9 +81,10 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
                                             : a.act + (size_t)a.root_slot[r0 + b] * a.d;
         ybr[idx] = reinterpret_cast<const float4*>(src)[c];
     }
-    float4* myacc = accs + (size_t)wave * PARTS * nb * d4;
-    if (TRAIN && nb > 1)
-        for (int idx = lane; idx < PARTS * nb * d4; idx += 64) myacc[idx] = make_float4(0.f, 0.f, 0.f, 0.f);
+    const int nx = nb - 1;                                           // branches kept in LDS
+    float4* myacc = accs + (size_t)wave * PARTS * nx * d4;           // [PARTS][nx][d4]
+    if (TRAIN)
+        for (int idx = lane; idx < PARTS * nx * d4; idx += 64) myacc[idx] = make_float4(0.f, 0.f, 0.f, 0.f);
     __syncthreads();
 
     const float inv2B = 1.f / (2.f * (float)a.B);
@@ -164,20 +173,20 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
                         const float co = coef * (1.f - alpha);
                         float4 go;
                         go.x = ox ? co : 0.f; go.y = oy ? co : 0.f; go.z = oz ? co : 0.f; go.w = ow ? co : 0.f;
-                        if (nb == 1) {
+                        if (bw == 0) {
                             dor[ch].x += go.x; dor[ch].y += go.y; dor[ch].z += go.z; dor[ch].w += go.w;
                         } else {
-                            float4 t = myacc[(nb + bw) * d4 + col];
+                            float4 t = myacc[(nx + bw - 1) * d4 + col];
                             t.x += go.x; t.y += go.y; t.z += go.z; t.w += go.w;
-                            myacc[(nb + bw) * d4 + col] = t;
+                            myacc[(nx + bw - 1) * d4 + col] = t;
                         }
                     }
-                    if (nb == 1) {
+                    if (bw == 0) {
                         dyr[ch].x -= g.x; dyr[ch].y -= g.y; dyr[ch].z -= g.z; dyr[ch].w -= g.w;
                     } else {
-                        float4 t = myacc[bw * d4 + col];
+                        float4 t = myacc[(bw - 1) * d4 + col];
                         t.x -= g.x; t.y -= g.y; t.z -= g.z; t.w -= g.w;
-                        myacc[bw * d4 + col] = t;
+                        myacc[(bw - 1) * d4 + col] = t;
                     }
                 }
             }
@@ -194,27 +203,72 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
     }
 
     if (TRAIN) {
-        if (nb == 1) {
+        if (lane == 0) lossp[wave] = lsum;
+        // branch 0: summed over the wavefronts in a fixed order, either through the staging area or
+        // in turn into the area of the branch rows, which nobody reads any more after the first barrier
+        float4* red = ybr;                                           // [PARTS][d4]  (SEQ)
+        const int root0 = a.root_slot[r0];
+        if (!SEQ) {
 #pragma unroll
             for (int ch = 0; ch < NCH; ++ch) {
                 const int col = col_of<B16>(ch, lane);
                 if (col < d4) {
-                    myacc[col] = dyr[ch];
-                    if (BOX) myacc[d4 + col] = dor[ch];
+                    stage[(size_t)wave * PARTS * d4 + col] = dyr[ch];
+                    if (BOX) stage[(size_t)wave * PARTS * d4 + d4 + col] = dor[ch];
+                }
+            }
+            __syncthreads();
+            for (int idx = tid; idx < PARTS * d4; idx += NW * 64) {
+                float4 t = stage[idx];
+                for (int w = 1; w < NW; ++w) {
+                    const float4 u = stage[(size_t)w * PARTS * d4 + idx];
+                    t.x += u.x; t.y += u.y; t.z += u.z; t.w += u.w;
+                }
+                const int part = idx / d4, cc = idx - part * d4;
+                reinterpret_cast<float4*>((part ? a.doff : a.dact) + (size_t)root0 * a.d)[cc] = t;
+            }
+        }
+        for (int w = 0; SEQ && w < NW; ++w) {
+            __syncthreads();
+            if (wave == w) {
+#pragma unroll
+                for (int ch = 0; ch < NCH; ++ch) {
+                    const int col = col_of<B16>(ch, lane);
+                    if (col < d4) {
+                        float4 t = dyr[ch];
+                        if (w > 0) {
+                            const float4 u = red[col];
+                            t.x += u.x; t.y += u.y; t.z += u.z; t.w += u.w;
+                        }
+                        red[col] = t;
+                        if (BOX) {
+                            float4 q = dor[ch];
+                            if (w > 0) {
+                                const float4 u = red[d4 + col];
+                                q.x += u.x; q.y += u.y; q.z += u.z; q.w += u.w;
+                            }
+                            red[d4 + col] = q;
+                        }
+                    }
                 }
             }
         }
-        if (lane == 0) lossp[wave] = lsum;
         __syncthreads();
-        for (int idx = tid; idx < PARTS * nb * d4; idx += NW * 64) {
+        for (int idx = tid; SEQ && idx < PARTS * d4; idx += NW * 64) {
+            const int part = idx / d4, cc = idx - part * d4;
+            float* dst = (part ? a.doff : a.dact) + (size_t)root0 * a.d;
+            reinterpret_cast<float4*>(dst)[cc] = red[idx];
+        }
+        // the other branches: sum of the wavefronts' LDS accumulators
+        for (int idx = tid; idx < PARTS * nx * d4; idx += NW * 64) {
             float4 t = accs[idx];
             for (int w = 1; w < NW; ++w) {
-                const float4 u = accs[(size_t)w * PARTS * nb * d4 + idx];
+                const float4 u = accs[(size_t)w * PARTS * nx * d4 + idx];
                 t.x += u.x; t.y += u.y; t.z += u.z; t.w += u.w;
             }
-            const int b = idx / d4, cc = idx - b * d4;
-            float* dst = (BOX && b >= nb) ? a.doff + (size_t)a.root_slot[r0 + b - nb] * a.d
-                                          : a.dact + (size_t)a.root_slot[r0 + b] * a.d;
+            const int b = idx / d4, cc = idx - b * d4;              // b over [PARTS][nx]
+            float* dst = (BOX && b >= nx) ? a.doff + (size_t)a.root_slot[r0 + 1 + b - nx] * a.d
+                                          : a.dact + (size_t)a.root_slot[r0 + 1 + b] * a.d;
             reinterpret_cast<float4*>(dst)[cc] = t;
         }
         if (tid == 0) {
@@ -250,7 +304,8 @@ hipError_t launch_nch(const ScoreArgs& a, bool train, hipStream_t s) {
     // enough wavefronts to cover the chip even for small batches
     const int nw = a.B >= 2048 ? 4 : (a.B >= 1024 ? 8 : 16);
     auto lds_for = [&](int w) {
-        return ((size_t)(a.off ? 2 : 1) * a.max_branch * a.d * (1 + (train ? w : 0)) + 16) * sizeof(float);
+        const int per_wave = a.max_branch - 1 + (w <= 4 ? 0 : 1);   // union accumulators (+ staging)
+        return ((size_t)(a.off ? 2 : 1) * a.d * (a.max_branch + (train ? w * per_wave : 0)) + 16) * sizeof(float);
     };
     const size_t cap = 150 * 1024;
     if (nw == 16 && lds_for(16) <= cap) return launch_nw<NCH, 16>(a, train, lds_for(16), s);
