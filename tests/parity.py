@@ -58,14 +58,14 @@ class Case:
         self.sem_bits = wl.make_sem_features(N, d_sem, seed + 5) if d_sem else None
         if trees is not None:
             qb = wl.batch_from_trees(trees, pos)
-            want = qb.B
+            want = B or qb.B                             # B > 0: the first B of the trees that are clear of kinks
         else:
             kg = wl.make_kg(N, R, T or 10 * N, alpha, seed)
             want = B
             qb = wl.make_batch(kg, B + B // 4 + 8, mix or {n: 1.0 for n in wl.configs.ALL14}, seed + 1)
         negs = wl.make_negatives(N, qb.B, K, seed + 2)
         self.qb, self.negs, self.n_redrawn = keep_clear_of_kinks(qb, negs, self.params, gamma, N, want, seed + 4,
-                                                                 strict=trees is None, sem_bits=self.sem_bits,
+                                                                 strict=trees is None or B > 0, sem_bits=self.sem_bits,
                                                                  score_bf16=score_bf16)
         self.B = self.qb.B
 

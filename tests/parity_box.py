@@ -28,14 +28,14 @@ class BoxCase:
         self.params = wl.make_box_params(N, R, d, h, seed + 3)
         if trees is not None:
             qb = wl.batch_from_trees(trees, pos)
-            want = qb.B
+            want = B or qb.B                             # B > 0: the first B of the trees that are clear of kinks
         else:
             kg = wl.make_kg(N, R, T or 10 * N, kg_alpha, seed)
             want = B
             qb = wl.make_batch(kg, B + B // 4 + 8, mix or {n: 1.0 for n in wl.EPFO9}, seed + 1)
         negs = wl.make_negatives(N, qb.B, K, seed + 2)
         self.qb, self.negs, self.n_redrawn = keep_clear_of_kinks(qb, negs, self.model(), N, want, seed + 4,
-                                                                 strict=trees is None)
+                                                                 strict=trees is None or B > 0)
         self.B = self.qb.B
 
     @classmethod

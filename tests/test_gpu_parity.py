@@ -75,6 +75,48 @@ def test_general_shapes_wide_intersections_and_unions():
     par.check_train_steps(par.Case(N, R, 64, 128, 0, 6, 8.0, seed=13, trees=trees, pos=pos), steps=2)
 
 
+@pytest.mark.parametrize("B", [1100, 2100])
+def test_scoring_workgroup_shapes_with_unions(B):
+    """Batches of 1024..2047 and of 2048 and more queries take the scoring kernel with 8 and with 4
+    wavefronts per workgroup (other sums of the gradients over the wavefronts than the small
+    batches of the other tests); unions of 2 and 3 branches at every position of the batch."""
+    _say("B=%d: 1p / 2i / 2u / 3-way union / up / 2in, d=36 h=24 K=3; both families, text features" % B)
+    from tests import parity_box as pb
+    rng = np.random.default_rng(B)
+    N, R = 900, 11
+
+    def proj(depth=1):
+        t = ("e", int(rng.integers(N)))
+        for _ in range(depth):
+            t = ("p", int(rng.integers(R)), t)
+        return t
+
+    def tree(kind, box):
+        if kind == 0:
+            return proj(1 + int(rng.integers(2)))
+        if kind == 1:
+            return ("i", proj(), proj())
+        if kind == 2:
+            return ("u", proj(), proj())
+        if kind == 3:
+            return ("u", proj(), proj(2), proj())
+        if kind == 4:
+            return ("p", int(rng.integers(R)), ("u", proj(), proj()))
+        return ("i", proj(), proj()) if box else ("i", proj(), ("n", proj()))
+
+    for box in (False, True):
+        trees = [tree(int(rng.integers(6)), box) for _ in range(B + B // 2)]      # spares for those on a kink
+        pos = [int(rng.integers(N)) for _ in trees]
+        if box:
+            cases = [pb.BoxCase(N, R, 36, 24, B, 3, 6.0, alpha=0.2, seed=B + 1, trees=trees, pos=pos)]
+        else:
+            cases = [par.Case(N, R, 36, 24, B, 3, 6.0, seed=B + 2, trees=trees, pos=pos),
+                     par.Case(N, R, 40, 24, B, 3, 6.0, seed=B + 3, trees=trees, pos=pos, d_sem=64)]
+        for case in cases:
+            assert case.B == B
+            (pb if box else par).check_forward_backward(case)
+
+
 def test_degenerate_batches():
     _say("single query; all negatives equal; anchor = positive = negative; empty batch")
     one = par.Case(100, 5, 32, 64, 0, 5, 6.0, seed=14, trees=[("p", 1, ("e", 2))], pos=[3])
