@@ -356,11 +356,16 @@ const char* ngdb_sampler_last_error(const ngdb_sampler_t* sampler);
  * b_kcontig else B[k*ldb+n].  Then, in this order and each only if its pointer
  * is not NULL (relu: flag): + bias[n]; relu; zero where mask[m*ldmask+n] <= 0;
  * + addend[m*ldadd+n]; row m is stored at C row dst_row[m].  Leading dimensions
- * and the contiguous extents must be multiples of 4.                            */
+ * and the contiguous extents must be multiples of 4.  arith: 0 = as the training
+ * step chooses, 1 = fp32 matrix instructions, 2 = every fp32 operand as the exact
+ * sum of three bf16 values and the six largest of the nine partial products on
+ * the bf16 matrix instructions with fp32 accumulation (the rest is below 2^-26 of
+ * a product; always in the kernel's small tiles).                                 */
 int ngdb_debug_gemm(const float* A, const float* B, float* C, int32_t M, int32_t N, int32_t K,
                     int32_t lda, int32_t ldb, int32_t ldc, int32_t a_kcontig, int32_t b_kcontig,
                     const float* bias, int32_t relu, const float* mask, int32_t ldmask,
-                    const float* addend, int32_t ldadd, const int32_t* dst_row, void* stream);
+                    const float* addend, int32_t ldadd, const int32_t* dst_row, int32_t arith,
+                    void* stream);
 
 /* A plain device-to-device copy kernel (16 bytes per thread and step) of `bytes`
  * bytes, a multiple of 16: the reference point for scaling hardware traffic

@@ -104,7 +104,7 @@ def load_library(path=LIB_PATH):
         "ngdb_sampler_destroy": (None, [vp]),
         "ngdb_sampler_last_error": (C.c_char_p, [vp]),
         "ngdb_debug_gemm": (C.c_int, [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, i32, vp, i32, vp, i32,
-                                      vp, vp]),
+                                      vp, i32, vp]),
         "ngdb_debug_copy": (C.c_int, [vp, vp, C.c_size_t, vp]),
         "ngdb_set_timing": (C.c_int, [vp, C.c_uint32]),
         "ngdb_get_timing": (C.c_int, [vp, C.POINTER(Timing), C.c_int]),
@@ -206,14 +206,14 @@ def copy_to_host(dev_ptr, shape, dtype):
 
 
 def debug_gemm(A, B, M, N, K, a_kcontig=True, b_kcontig=True, bias=None, relu=False, mask=None, addend=None,
-               dst_row=None, out_rows=None):
+               dst_row=None, out_rows=None, arith=0):
     """Runs the library's contraction kernel on torch device tensors; returns C [out_rows or M, N]."""
     import torch
     Cm = torch.zeros((out_rows or M, N), dtype=torch.float32, device=A.device)
     p = lambda t: t.data_ptr() if t is not None else None
     ld = lambda t: int(t.stride(0)) if t is not None else 0
     _check(lib().ngdb_debug_gemm(p(A), p(B), p(Cm), M, N, K, ld(A), ld(B), ld(Cm), int(a_kcontig), int(b_kcontig),
-                                 p(bias), int(relu), p(mask), ld(mask), p(addend), ld(addend), p(dst_row),
+                                 p(bias), int(relu), p(mask), ld(mask), p(addend), ld(addend), p(dst_row), int(arith),
                                  C.c_void_p(torch.cuda.current_stream().cuda_stream)), None)
     torch.cuda.synchronize()
     return Cm

@@ -1195,12 +1195,13 @@ int ngdb_rank_metrics(const int32_t* d_rank, const int32_t* d_ans_off, const int
 int ngdb_debug_gemm(const float* A, const float* B, float* C, int32_t M, int32_t N, int32_t K, int32_t lda,
                     int32_t ldb, int32_t ldc, int32_t a_kcontig, int32_t b_kcontig, const float* bias, int32_t relu,
                     const float* mask, int32_t ldmask, const float* addend, int32_t ldadd, const int32_t* dst_row,
-                    void* stream) {
-    if (!A || !B || !C || M < 0 || N < 0 || K < 0) return NGDB_ERR_ARG;
+                    int32_t arith, void* stream) {
+    if (!A || !B || !C || M < 0 || N < 0 || K < 0 || arith < 0 || arith > 2) return NGDB_ERR_ARG;
     GemmArgs g;
     g.A = A; g.B = B; g.C = C; g.M = M; g.N = N; g.K = K; g.lda = lda; g.ldb = ldb; g.ldc = ldc;
     g.a_kcontig = a_kcontig != 0; g.b_kcontig = b_kcontig != 0; g.bias = bias; g.relu = relu != 0;
     g.mask = mask; g.ldmask = ldmask; g.addend = addend; g.ldadd = ldadd; g.dst_row = dst_row;
+    g.arith = arith;
     const hipError_t e = launch_gemm(g, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? NGDB_OK : (e == hipErrorInvalidValue ? NGDB_ERR_ARG : NGDB_ERR_HIP);
 }

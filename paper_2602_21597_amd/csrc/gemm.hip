@@ -21,9 +21,13 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 constexpr int BK = 16;    // k extent of one staged tile
 constexpr int PAD = 4;    // keeps LDS rows 16-byte aligned and spreads banks
 
-template <int BM, int BN, int NW>
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <int BM, int BN, int NW, bool SPLIT = false>
 struct Smem {
-    static constexpr int STAGE = NW * BK * (BM + PAD + BN + PAD);      // floats
+    // SPLIT: per wavefront and operand three bf16 pieces of a [32][BK] tile
+    static constexpr int STAGE = SPLIT ? NW * 2 * 3 * 32 * BK / 2 : NW * BK * (BM + PAD + BN + PAD);   // floats
     static constexpr int NR = NW > 4 ? NW / 2 : NW;                    // partial tiles held in LDS at once
     static constexpr int REDUCE = NR * BM * (BN + 1);
     static constexpr int FLOATS = STAGE > REDUCE ? STAGE : REDUCE;
@@ -124,9 +128,76 @@ __device__ __forceinline__ void stage_b(const GemmArgs& a, float* __restrict__ d
     }
 }
 
-template <int BM, int BN, int NW, bool AK, bool BKC>
+// An fp32 value is the exact sum of three bf16 values: x rounded to bf16, the remainder rounded
+// to bf16, and what is then left (at most 6 bits).  Rounding is to nearest (the hardware
+// conversion), so the pieces carry signs of their own and nothing is biased: with pieces cut off
+// instead, every product would come out a little short, and the scores, whose loss weights
+// depend on them exponentially, would shift in one direction.  A product of two fp32 values is a
+// sum of nine bf16 products, of which the six largest are kept; the three left out are below
+// 2^-26 of the product.  bf16 products are exact in the fp32 accumulator of the matrix unit,
+// which multiplies bf16 sixteen times as fast as fp32.
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t cvt_pk(float first, float second) {   // first in the lower half
+    const floatx2 v = {first, second};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+// pieces of two values, packed pairwise: h, m, l words
+__device__ __forceinline__ void split2(float a, float b, uint32_t& h, uint32_t& m, uint32_t& l) {
+    h = cvt_pk(a, b);
+    const float ra = a - __uint_as_float(h << 16), rb = b - __uint_as_float(h & 0xffff0000u);
+    m = cvt_pk(ra, rb);
+    l = cvt_pk(ra - __uint_as_float(m << 16), rb - __uint_as_float(m & 0xffff0000u));
+}
+struct Pieces {
+    uint2 h, m, l;     // 4 consecutive k each, bf16 bit patterns
+};
+__device__ __forceinline__ Pieces split3(float4 v) {
+    Pieces p;
+    split2(v.x, v.y, p.h.x, p.m.x, p.l.x);
+    split2(v.z, v.w, p.h.y, p.m.y, p.l.y);
+    return p;
+}
+// Pieces of a [32][BK] tile in LDS: 16-byte units (8 consecutive k of a row); unit index
+// = k-half * 32 + row, piece after piece -- the operand layout of the 32x32x16 bf16 MFMA
+// (lane = k-half * 32 + row reads unit `lane`).
+__device__ __forceinline__ void store_pieces(uint16_t* tile, int row, int kq, const Pieces& p) {
+    uint16_t* at = tile + ((kq >> 1) * 32 + row) * 8 + (kq & 1) * 4;
+    *reinterpret_cast<uint2*>(at) = p.h;
+    *reinterpret_cast<uint2*>(at + 512) = p.m;
+    *reinterpret_cast<uint2*>(at + 1024) = p.l;
+}
+
+// Operand stored with k as the slow index ([K][X], X = rows or columns of the output): a lane
+// takes two consecutive k of four consecutive x (8 lanes cover 128 contiguous bytes), so that
+// the pieces of a (k, k+1) pair fill one 32-bit word of the tile.
+__device__ __forceinline__ void issue_strided(const float* base, int ld, int K, int X, int k0, int x0, int lane,
+                                              float4 (&r)[2]) {
+    const int gk = k0 + 2 * (lane >> 3), gx = min(x0 + (lane & 7) * 4, X - 4);
+    r[0] = *reinterpret_cast<const float4*>(base + (size_t)min(gk, K - 1) * ld + gx);
+    r[1] = *reinterpret_cast<const float4*>(base + (size_t)min(gk + 1, K - 1) * ld + gx);
+}
+__device__ __forceinline__ void stage_strided(uint16_t* tile, int K, int X, int k0, int x0, int lane,
+                                              const float4 (&r)[2]) {
+    const int kp = lane >> 3, q = lane & 7;
+    const bool okx = x0 + q * 4 < X;
+    const bool ok0 = okx && k0 + 2 * kp < K, ok1 = okx && k0 + 2 * kp + 1 < K;
+    const float e[4] = {r[0].x, r[0].y, r[0].z, r[0].w}, o[4] = {r[1].x, r[1].y, r[1].z, r[1].w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        uint32_t h, m, l;
+        split2(ok0 ? e[j] : 0.f, ok1 ? o[j] : 0.f, h, m, l);
+        uint32_t* at = reinterpret_cast<uint32_t*>(tile + ((kp >> 2) * 32 + q * 4 + j) * 8 + (kp & 3) * 2);
+        at[0] = h;
+        at[256] = m;
+        at[512] = l;
+    }
+}
+
+template <int BM, int BN, int NW, bool AK, bool BKC, bool SPLIT = false>
 __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
-    __shared__ __attribute__((aligned(16))) float smem[Smem<BM, BN, NW>::FLOATS];
+    static_assert(!SPLIT || (BM == 32 && BN == 32 && BK == 16), "split path: 32x32 tiles");
+    __shared__ __attribute__((aligned(16))) float smem[Smem<BM, BN, NW, SPLIT>::FLOATS];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
@@ -158,8 +229,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
     const bool first_n_tile = n0 == 0;
     constexpr int TM = BM / 32, TN = BN / 32;
     constexpr int LDA = BM + PAD, LDB = BN + PAD;
-    float* As = smem + wave * BK * (LDA + LDB);     // [BK][LDA] of this wavefront
-    float* Bs = As + BK * LDA;                      // [BK][LDB]
+    float* As = smem + (SPLIT ? wave * 1536 : wave * BK * (LDA + LDB));     // [BK][LDA] of this wavefront
+    float* Bs = As + (SPLIT ? 768 : BK * LDA);                                // [BK][LDB]
 
     floatx16 acc[TM][TN];
 #pragma unroll
@@ -227,18 +298,66 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
     const int nk = (a.K + BK - 1) / BK;
     const int rounds = nk > wave ? (nk - wave + NW - 1) / NW : 0;
     int kcur = wave * BK;
-    if (rounds > 0) {
-        issue_a<BM, LA, AK>(a, lane, m0, kcur, has_add, arow, aadd, ra, rd);
-        issue_b<BN, LB, BKC>(a, lane, n0, kcur, rb);
+#define NGDB_ISSUE()                                                                         \
+    if (SPLIT && !AK) issue_strided(a.A, a.lda, a.K, a.M, kcur, m0, lane, reinterpret_cast<float4(&)[2]>(ra));   \
+    else issue_a<BM, LA, AK>(a, lane, m0, kcur, has_add, arow, aadd, ra, rd);               \
+    if (SPLIT && !BKC) issue_strided(a.B, a.ldb, a.K, a.N, kcur, n0, lane, reinterpret_cast<float4(&)[2]>(rb)); \
+    else issue_b<BN, LB, BKC>(a, lane, n0, kcur, rb);
+    if (rounds > 0) { NGDB_ISSUE() }
+    for (int it = 0; SPLIT && it < rounds; ++it) {
+        uint16_t* Ap = reinterpret_cast<uint16_t*>(As);
+        uint16_t* Bp = reinterpret_cast<uint16_t*>(Bs);
+        if (!AK) stage_strided(Ap, a.K, a.M, kcur, m0, lane, reinterpret_cast<const float4(&)[2]>(ra));
+#pragma unroll
+        for (int i = 0; AK && i < LA; ++i) {
+            const int idx = lane + i * 64;
+            const int m = idx / (BK / 4), kq = idx % (BK / 4);
+            const int gk = kcur + kq * 4;
+            float4 v = ra[i];
+            if (has_add) { v.x += rd[i].x; v.y += rd[i].y; v.z += rd[i].z; v.w += rd[i].w; }
+            const bool ok = avalid[i] && gk < a.K;
+            v.x = ok ? v.x : 0.f; v.y = ok ? v.y : 0.f; v.z = ok ? v.z : 0.f; v.w = ok ? v.w : 0.f;
+            if (copy_out && ok) *reinterpret_cast<float4*>(a.a_copy + (size_t)(m0 + m) * a.lda + gk) = v;
+            store_pieces(Ap, m, kq, split3(v));
+        }
+        if (!BKC) stage_strided(Bp, a.K, a.N, kcur, n0, lane, reinterpret_cast<const float4(&)[2]>(rb));
+#pragma unroll
+        for (int i = 0; BKC && i < LB; ++i) {
+            const int idx = lane + i * 64;
+            const int n = idx / (BK / 4), kq = idx % (BK / 4);
+            float4 v = rb[i];
+            const bool ok = n0 + n < a.N && kcur + kq * 4 < a.K;
+            v.x = ok ? v.x : 0.f; v.y = ok ? v.y : 0.f; v.z = ok ? v.z : 0.f; v.w = ok ? v.w : 0.f;
+            store_pieces(Bp, n, kq, split3(v));
+        }
+        __builtin_amdgcn_wave_barrier();
+        if (it + 1 < rounds) {
+            kcur = ((it + 1) * NW + wave) * BK;
+            NGDB_ISSUE()
+        }
+        bf16x8 ap[3], bp[3];
+#pragma unroll
+        for (int q = 0; q < 3; ++q) {
+            ap[q] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Ap + q * 512 + lane * 8));
+            bp[q] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Bp + q * 512 + lane * 8));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // smallest products first
+        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[2], bp[0], acc[0][0], 0, 0, 0);
+        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[0], bp[2], acc[0][0], 0, 0, 0);
+        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[1], bp[1], acc[0][0], 0, 0, 0);
+        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[1], bp[0], acc[0][0], 0, 0, 0);
+        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[0], bp[1], acc[0][0], 0, 0, 0);
+        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[0], bp[0], acc[0][0], 0, 0, 0);
+        __builtin_amdgcn_wave_barrier();
     }
-    for (int it = 0; it < rounds; ++it) {
+    for (int it = 0; !SPLIT && it < rounds; ++it) {
         stage_a<BM, LA, LDA, AK>(a, As, lane, m0, kcur, has_add, copy_out, avalid, ra, rd);
         stage_b<BN, LB, LDB, BKC>(a, Bs, lane, n0, kcur, rb);
         __builtin_amdgcn_wave_barrier();        // staged tile before its reads (compiler ordering only)
         if (it + 1 < rounds) {
             kcur = ((it + 1) * NW + wave) * BK;
-            issue_a<BM, LA, AK>(a, lane, m0, kcur, has_add, arow, aadd, ra, rd);
-            issue_b<BN, LB, BKC>(a, lane, n0, kcur, rb);
+            NGDB_ISSUE()
         }
         // all LDS operand reads of the tile are issued before the first MFMA, so that the
         // matrix pipe never waits for an LDS round trip between k steps
@@ -263,11 +382,12 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
     }
     if (!EARLY_EPILOGUE) { NGDB_LOAD_EPILOGUE() }   // in flight during the reduction
 #undef NGDB_LOAD_EPILOGUE
+#undef NGDB_ISSUE
     __syncthreads();                            // the staging areas are reused for the reduction
 
     // partial tiles -> LDS.  Accumulator layout of a 32x32 block: lane owns column
     // (lane & 31) and rows 8*(r/4) + 4*(lane/32) + r%4, r = 0..15.
-    constexpr int NR = Smem<BM, BN, NW>::NR;
+    constexpr int NR = Smem<BM, BN, NW, SPLIT>::NR;
     float* red = smem + (wave % NR) * BM * (BN + 1);
 #define NGDB_ACC_TO_LDS()                                                                   \
     _Pragma("unroll") for (int i = 0; i < TM; ++i)                                         \
@@ -312,7 +432,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
     }
 }
 
-template <int BM, int BN, int NW>
+template <int BM, int BN, int NW, bool SPLIT = false>
 hipError_t dispatch_layout(GemmGroup& g, hipStream_t s) {
     int tiles = 0;
     for (int i = 0; i < g.count; ++i) {
@@ -323,11 +443,11 @@ hipError_t dispatch_layout(GemmGroup& g, hipStream_t s) {
     dim3 grid(tiles), block(NW * 64);
     const GemmArgs& a = g.p[0];
     if (a.a_kcontig && a.b_kcontig)
-        hipLaunchKernelGGL((gemm_kernel<BM, BN, NW, true, true>), grid, block, 0, s, g);
+        hipLaunchKernelGGL((gemm_kernel<BM, BN, NW, true, true, SPLIT>), grid, block, 0, s, g);
     else if (a.a_kcontig && !a.b_kcontig)
-        hipLaunchKernelGGL((gemm_kernel<BM, BN, NW, true, false>), grid, block, 0, s, g);
+        hipLaunchKernelGGL((gemm_kernel<BM, BN, NW, true, false, SPLIT>), grid, block, 0, s, g);
     else if (!a.a_kcontig && !a.b_kcontig)
-        hipLaunchKernelGGL((gemm_kernel<BM, BN, NW, false, false>), grid, block, 0, s, g);
+        hipLaunchKernelGGL((gemm_kernel<BM, BN, NW, false, false, SPLIT>), grid, block, 0, s, g);
     else
         return hipErrorInvalidValue;
     return hipGetLastError();
@@ -350,15 +470,26 @@ hipError_t launch_gemm_group(const GemmArgs* problems, int count, hipStream_t s)
         if (a.a_ref && !a.a_kcontig) return hipErrorInvalidValue;
         if (g.count && (a.a_kcontig != g.p[0].a_kcontig || a.b_kcontig != g.p[0].b_kcontig))
             return hipErrorInvalidValue;   // one operand layout per launch
+        if (g.count && a.arith != g.p[0].arith) return hipErrorInvalidValue;
         g.p[g.count++] = a;
         blocks_small += (long)((a.M + 31) / 32) * ((a.N + 63) / 64);
         max_k = std::max(max_k, a.K);
     }
     if (g.count == 0) return hipSuccess;
-    if (blocks_small >= 2048) return dispatch_layout<64, 64, 4>(g, s);
+    const int arith = g.p[0].arith;
+    if (blocks_small >= 2048 && arith != GEMM_SPLIT) return dispatch_layout<64, 64, 4>(g, s);
     // below that the launches of a step do not fill the chip: the smallest tile the MFMA block
     // allows spreads a launch over the most compute units (a tile's MFMA work runs on one)
     // (more than two such tiles per compute unit: 4 wavefronts per tile keep them all resident)
+    // fp32 operands as three bf16 pieces each (six bf16 MFMAs per k-tile instead of eight fp32
+    // ones that take twice as long each): launches whose A operand is k-contiguous, i.e. the
+    // forward and data-gradient contractions.  With k as the slow index of both operands (weight
+    // gradients) splitting and transposing the pieces costs more than the matrix unit saves.
+    // (with a k extent below 128 the matrix unit is idle either way and the splitting only adds work)
+    if (arith == GEMM_SPLIT || (arith == GEMM_AUTO && g.p[0].a_kcontig && max_k >= 128)) {
+        if (blocks_small * 2 > 512) return dispatch_layout<32, 32, 4, true>(g, s);
+        return dispatch_layout<32, 32, 8, true>(g, s);
+    }
     if (blocks_small * 2 > 512) return dispatch_layout<32, 32, 4>(g, s);
     return dispatch_layout<32, 32, 8>(g, s);
 }

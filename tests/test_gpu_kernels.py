@@ -5,7 +5,7 @@ import pytest
 pytestmark = pytest.mark.gpu
 
 
-def _gemm_case(M, N, K, a_k, b_k, seed, epilogue):
+def _gemm_case(M, N, K, a_k, b_k, seed, epilogue, arith=0):
     import torch
     from paper_2602_21597_amd import binding
     rng = np.random.default_rng(seed)
@@ -29,9 +29,10 @@ def _gemm_case(M, N, K, a_k, b_k, seed, epilogue):
         out_rows = M + 5
         kw = dict(bias=torch.from_numpy(bias).cuda(), relu=True, mask=torch.from_numpy(mask).cuda(),
                   addend=torch.from_numpy(addend).cuda(), dst_row=torch.from_numpy(perm).cuda())
-    got = binding.debug_gemm(At, Bt, M, N, K, a_kcontig=a_k, b_kcontig=b_k, out_rows=out_rows, **kw).cpu().numpy()
+    got = binding.debug_gemm(At, Bt, M, N, K, a_kcontig=a_k, b_kcontig=b_k, out_rows=out_rows, arith=arith,
+                             **kw).cpu().numpy()
     err = np.abs(got - want).max() / np.abs(want).max()
-    assert err < 2e-6 * max(1.0, np.sqrt(K) / 8), (M, N, K, a_k, b_k, epilogue, err)
+    assert err < 2e-6 * max(1.0, np.sqrt(K) / 8), (M, N, K, a_k, b_k, epilogue, arith, err)
 
 
 @pytest.mark.parametrize("layout", [(True, True), (True, False), (False, False)])
@@ -47,5 +48,28 @@ def test_contraction_kernel_all_layouts_and_tile_paths(layout):
         if a_k or b_k:
             K = (K + 3) // 4 * 4
         print("[case] gemm", M, N, K, layout, flush=True)
-        _gemm_case(M, N, K, a_k, b_k, seed=i, epilogue=False)
-        _gemm_case(M, N, K, a_k, b_k, seed=100 + i, epilogue=True)
+        # the arithmetic the training step takes for this layout and size, fp32 matrix
+        # instructions, and operands split into bf16 pieces: all to the same bound
+        for arith in (0, 1, 2):
+            _gemm_case(M, N, K, a_k, b_k, seed=i, epilogue=False, arith=arith)
+            _gemm_case(M, N, K, a_k, b_k, seed=100 + i, epilogue=True, arith=arith)
+
+
+def test_split_contraction_keeps_fp32_accuracy_where_bf16_alone_would_not():
+    """Operands with a wide spread of magnitudes and with values that need all 24 significand
+    bits: the split arithmetic must stay at the fp32 level (a single bf16 piece would be off
+    by 2^-9, two pieces by 2^-17)."""
+    import torch
+    from paper_2602_21597_amd import binding
+    rng = np.random.default_rng(7)
+    M, N, K = 96, 160, 528
+    A = (rng.standard_normal((M, K)) * np.exp2(rng.integers(-12, 12, (M, K)))).astype(np.float32)
+    B = (1.0 + rng.random((K, N)) * 2.0 ** -12).astype(np.float32)          # differ only in the low bits
+    want = A.astype(np.float64) @ B.astype(np.float64)
+    scale = np.abs(A).astype(np.float64) @ np.abs(B).astype(np.float64)     # no cancellation credit
+    for arith in (1, 2):
+        got = binding.debug_gemm(torch.from_numpy(A).cuda(), torch.from_numpy(np.ascontiguousarray(B.T)).cuda(),
+                                 M, N, K, arith=arith).cpu().numpy()
+        err = (np.abs(got - want) / scale).max()
+        print("[case] arith", arith, "error relative to sum |a||b|:", err, flush=True)
+        assert err < 2e-6, (arith, err)

@@ -189,7 +189,20 @@ def _full_size_sampled(cfg, n_sample):
     assert sorted(G.rows["E"]) == list(g["e_uniq"])
     ref_rows = np.stack([G.rows["E"][int(r)] for r in g["e_uniq"]])
     par.assert_close(g["gE"], ref_rows, "grad E")
-    par.assert_rows_close(g["gE"], ref_rows, "grad rows E")
+    # row by row, except rows of candidates that sit on an |.| kink of a query (some coordinate of
+    # the winning branch within fp32 rounding of the candidate's: either sign is a correct answer;
+    # this batch is not redrawn clear of kinks as the small cases are)
+    on_kink = set()
+    for q in range(24):
+        Y = np.stack([om.forward(b, M)[0] for b in om.dnf(sub.tree(q))])
+        cand = np.concatenate([[sub.pos[q]], sub_negs[q]])
+        rows = M.entity(cand)
+        win = np.abs(Y[:, None, :] - rows[None]).sum(axis=2).argmin(axis=0)
+        margin = np.abs(Y[win] - rows).min(axis=1)
+        on_kink.update(int(e) for e in cand[margin < par.TAU_ABS])
+    clear = np.array([int(r) not in on_kink for r in g["e_uniq"]])
+    assert clear.sum() >= 0.99 * len(clear)
+    par.assert_rows_close(g["gE"][clear], ref_rows[clear], "grad rows E")
     sp.free()
 
     _say("ranking: 1024 queries against all entities, top-10; 16 queries checked")
