@@ -27,7 +27,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 template <int BM, int BN, int NW, bool SPLIT = false>
 struct Smem {
     // SPLIT: per wavefront and operand three bf16 pieces of a [32][BK] tile
-    static constexpr int STAGE = SPLIT ? NW * 2 * 3 * 32 * BK / 2 : NW * BK * (BM + PAD + BN + PAD);   // floats
+    static constexpr int STAGE = SPLIT ? NW * (BM / 32 + BN / 32) * 768 : NW * BK * (BM + PAD + BN + PAD);   // floats
     static constexpr int NR = NW > 4 ? NW / 2 : NW;                    // partial tiles held in LDS at once
     static constexpr int REDUCE = NR * BM * (BN + 1);
     static constexpr int FLOATS = STAGE > REDUCE ? STAGE : REDUCE;
@@ -196,7 +196,7 @@ __device__ __forceinline__ void stage_strided(uint16_t* tile, int K, int X, int 
 
 template <int BM, int BN, int NW, bool AK, bool BKC, bool SPLIT = false>
 __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
-    static_assert(!SPLIT || (BM == 32 && BN == 32 && BK == 16), "split path: 32x32 tiles");
+    static_assert(!SPLIT || BK == 16, "split path: one 32x32x16 MFMA step per staged tile");
     __shared__ __attribute__((aligned(16))) float smem[Smem<BM, BN, NW, SPLIT>::FLOATS];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -229,8 +229,9 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
     const bool first_n_tile = n0 == 0;
     constexpr int TM = BM / 32, TN = BN / 32;
     constexpr int LDA = BM + PAD, LDB = BN + PAD;
-    float* As = smem + (SPLIT ? wave * 1536 : wave * BK * (LDA + LDB));     // [BK][LDA] of this wavefront
-    float* Bs = As + (SPLIT ? 768 : BK * LDA);                                // [BK][LDB]
+    // (SPLIT: per 32 rows of an operand three pieces of 512 bf16 each)
+    float* As = smem + (SPLIT ? wave * (TM + TN) * 768 : wave * BK * (LDA + LDB));     // [BK][LDA] of this wavefront
+    float* Bs = As + (SPLIT ? TM * 768 : BK * LDA);                                      // [BK][LDB]
 
     floatx16 acc[TM][TN];
 #pragma unroll
@@ -299,15 +300,28 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
     const int rounds = nk > wave ? (nk - wave + NW - 1) / NW : 0;
     int kcur = wave * BK;
 #define NGDB_ISSUE()                                                                         \
-    if (SPLIT && !AK) issue_strided(a.A, a.lda, a.K, a.M, kcur, m0, lane, reinterpret_cast<float4(&)[2]>(ra));   \
-    else issue_a<BM, LA, AK>(a, lane, m0, kcur, has_add, arow, aadd, ra, rd);               \
-    if (SPLIT && !BKC) issue_strided(a.B, a.ldb, a.K, a.N, kcur, n0, lane, reinterpret_cast<float4(&)[2]>(rb)); \
-    else issue_b<BN, LB, BKC>(a, lane, n0, kcur, rb);
+    if (SPLIT && !AK) {                                                                      \
+        _Pragma("unroll") for (int t = 0; t < TM; ++t)                                      \
+            issue_strided(a.A, a.lda, a.K, a.M, kcur, m0 + 32 * t, lane, reinterpret_cast<float4(&)[2]>(ra[2 * t])); \
+    } else {                                                                                 \
+        issue_a<BM, LA, AK>(a, lane, m0, kcur, has_add, arow, aadd, ra, rd);                \
+    }                                                                                        \
+    if (SPLIT && !BKC) {                                                                     \
+        _Pragma("unroll") for (int t = 0; t < TN; ++t)                                      \
+            issue_strided(a.B, a.ldb, a.K, a.N, kcur, n0 + 32 * t, lane, reinterpret_cast<float4(&)[2]>(rb[2 * t])); \
+    } else {                                                                                 \
+        issue_b<BN, LB, BKC>(a, lane, n0, kcur, rb);                                        \
+    }
     if (rounds > 0) { NGDB_ISSUE() }
     for (int it = 0; SPLIT && it < rounds; ++it) {
         uint16_t* Ap = reinterpret_cast<uint16_t*>(As);
         uint16_t* Bp = reinterpret_cast<uint16_t*>(Bs);
-        if (!AK) stage_strided(Ap, a.K, a.M, kcur, m0, lane, reinterpret_cast<const float4(&)[2]>(ra));
+        if (!AK) {
+#pragma unroll
+            for (int t = 0; t < TM; ++t)
+                stage_strided(Ap + t * 1536, a.K, a.M, kcur, m0 + 32 * t, lane,
+                              reinterpret_cast<const float4(&)[2]>(ra[2 * t]));
+        }
 #pragma unroll
         for (int i = 0; AK && i < LA; ++i) {
             const int idx = lane + i * 64;
@@ -318,9 +332,14 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
             const bool ok = avalid[i] && gk < a.K;
             v.x = ok ? v.x : 0.f; v.y = ok ? v.y : 0.f; v.z = ok ? v.z : 0.f; v.w = ok ? v.w : 0.f;
             if (copy_out && ok) *reinterpret_cast<float4*>(a.a_copy + (size_t)(m0 + m) * a.lda + gk) = v;
-            store_pieces(Ap, m, kq, split3(v));
+            store_pieces(Ap + (m >> 5) * 1536, m & 31, kq, split3(v));
         }
-        if (!BKC) stage_strided(Bp, a.K, a.N, kcur, n0, lane, reinterpret_cast<const float4(&)[2]>(rb));
+        if (!BKC) {
+#pragma unroll
+            for (int t = 0; t < TN; ++t)
+                stage_strided(Bp + t * 1536, a.K, a.N, kcur, n0 + 32 * t, lane,
+                              reinterpret_cast<const float4(&)[2]>(rb[2 * t]));
+        }
 #pragma unroll
         for (int i = 0; BKC && i < LB; ++i) {
             const int idx = lane + i * 64;
@@ -328,27 +347,35 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
             float4 v = rb[i];
             const bool ok = n0 + n < a.N && kcur + kq * 4 < a.K;
             v.x = ok ? v.x : 0.f; v.y = ok ? v.y : 0.f; v.z = ok ? v.z : 0.f; v.w = ok ? v.w : 0.f;
-            store_pieces(Bp, n, kq, split3(v));
+            store_pieces(Bp + (n >> 5) * 1536, n & 31, kq, split3(v));
         }
         __builtin_amdgcn_wave_barrier();
         if (it + 1 < rounds) {
             kcur = ((it + 1) * NW + wave) * BK;
             NGDB_ISSUE()
         }
-        bf16x8 ap[3], bp[3];
+        bf16x8 ap[TM][3], bp[TN][3];
 #pragma unroll
         for (int q = 0; q < 3; ++q) {
-            ap[q] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Ap + q * 512 + lane * 8));
-            bp[q] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Bp + q * 512 + lane * 8));
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                ap[i][q] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Ap + i * 1536 + q * 512 + lane * 8));
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                bp[j][q] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Bp + j * 1536 + q * 512 + lane * 8));
         }
         __builtin_amdgcn_sched_barrier(0);
-        // smallest products first
-        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[2], bp[0], acc[0][0], 0, 0, 0);
-        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[0], bp[2], acc[0][0], 0, 0, 0);
-        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[1], bp[1], acc[0][0], 0, 0, 0);
-        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[1], bp[0], acc[0][0], 0, 0, 0);
-        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[0], bp[1], acc[0][0], 0, 0, 0);
-        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[0], bp[0], acc[0][0], 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {   // smallest products first
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[i][2], bp[j][0], acc[i][j], 0, 0, 0);
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[i][0], bp[j][2], acc[i][j], 0, 0, 0);
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[i][1], bp[j][1], acc[i][j], 0, 0, 0);
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[i][1], bp[j][0], acc[i][j], 0, 0, 0);
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[i][0], bp[j][1], acc[i][j], 0, 0, 0);
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[i][0], bp[j][0], acc[i][j], 0, 0, 0);
+            }
         __builtin_amdgcn_wave_barrier();
     }
     for (int it = 0; !SPLIT && it < rounds; ++it) {
@@ -477,7 +504,13 @@ hipError_t launch_gemm_group(const GemmArgs* problems, int count, hipStream_t s)
     }
     if (g.count == 0) return hipSuccess;
     const int arith = g.p[0].arith;
-    if (blocks_small >= 2048 && arith != GEMM_SPLIT) return dispatch_layout<64, 64, 4>(g, s);
+    const bool auto_split = arith == GEMM_AUTO && g.p[0].a_kcontig && max_k >= 128;
+    if (blocks_small >= 2048 && arith != GEMM_SPLIT) {
+        // (in the large tile every staged value feeds two MFMA blocks: there the split pays for
+        // the weight gradients too)
+        const bool big_split = arith == GEMM_AUTO && max_k >= 128;
+        return big_split ? dispatch_layout<64, 64, 4, true>(g, s) : dispatch_layout<64, 64, 4>(g, s);
+    }
     // below that the launches of a step do not fill the chip: the smallest tile the MFMA block
     // allows spreads a launch over the most compute units (a tile's MFMA work runs on one)
     // (more than two such tiles per compute unit: 4 wavefronts per tile keep them all resident)
@@ -486,7 +519,7 @@ hipError_t launch_gemm_group(const GemmArgs* problems, int count, hipStream_t s)
     // forward and data-gradient contractions.  With k as the slow index of both operands (weight
     // gradients) splitting and transposing the pieces costs more than the matrix unit saves.
     // (with a k extent below 128 the matrix unit is idle either way and the splitting only adds work)
-    if (arith == GEMM_SPLIT || (arith == GEMM_AUTO && g.p[0].a_kcontig && max_k >= 128)) {
+    if (arith == GEMM_SPLIT || auto_split) {
         if (blocks_small * 2 > 512) return dispatch_layout<32, 32, 4, true>(g, s);
         return dispatch_layout<32, 32, 8, true>(g, s);
     }
