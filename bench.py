@@ -405,6 +405,8 @@ def main():
                       "box family (alpha=%g) on the 9 negation-free structures" % args.box_alpha if box
                       else "14-structure mix" + (", candidate rows from a bf16 copy of E" if args.score_bf16 else ""),
                       cfg.gamma),
+                   "contractions": "fp32 results; operands split exactly into three bf16 pieces, six partial products on "
+                                   "the bf16 MFMA with fp32 accumulation (fp32 MFMA for the small weight-gradient tiles)",
                    "streams": streams,
                    "schedule": args.schedule if args.schedule == "level" else "max_fill, B_max=%s" % (args.bmax or "inf"),
                    "steps_per_batch": pexp["n_levels"], "peak_live_outputs": pexp["peak_live"],
