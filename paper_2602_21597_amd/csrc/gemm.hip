@@ -505,7 +505,10 @@ hipError_t launch_gemm_group(const GemmArgs* problems, int count, hipStream_t s)
     if (g.count == 0) return hipSuccess;
     const int arith = g.p[0].arith;
     const bool auto_split = arith == GEMM_AUTO && g.p[0].a_kcontig && max_k >= 128;
-    if (blocks_small >= 2048 && arith != GEMM_SPLIT) {
+    // weight gradients (k = all rows of an operator type) of a mid-size step: the large tile with
+    // the split route beats the small tile with fp32 MFMAs although it leaves compute units idle
+    const bool wgrad_big_tile = arith == GEMM_AUTO && !g.p[0].a_kcontig && max_k >= 512 && blocks_small >= 512;
+    if ((blocks_small >= 2048 || wgrad_big_tile) && arith != GEMM_SPLIT) {
         // (in the large tile every staged value feeds two MFMA blocks: there the split pays for
         // the weight gradients too)
         const bool big_split = arith == GEMM_AUTO && max_k >= 128;
