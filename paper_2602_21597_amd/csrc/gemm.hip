@@ -274,9 +274,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
     // Epilogue operands of this thread's output elements (clamped addresses, uniform flags).
     // Small tiles (launches that are latency bound) request them here, ahead of the k loop, so
     // that nothing is waited for after the last MFMA; large tiles request them after the loop:
-    // held across it they would cost the registers of a second resident wavefront per SIMD.
+    // held across it they would cost the registers of a second resident wavefront per SIMD (the
+    // 4-wavefront small tile with split arithmetic likewise: 5 instead of 4 wavefronts per SIMD).
     constexpr int EPT = BM * BN / (NW * 64);
-    constexpr bool EARLY_EPILOGUE = BM * BN <= 32 * 32;
+    constexpr bool EARLY_EPILOGUE = BM * BN <= 32 * 32 && !(SPLIT && NW == 4);
     float e_bias[EPT], e_mask[EPT], e_add[EPT];
     int e_orow[EPT];
     const bool has_bias = a.bias != nullptr, has_mask = a.mask != nullptr, has_addend = a.addend != nullptr,
