@@ -34,7 +34,7 @@ CLASSES = ("index", "sem", "gemm_fwd", "inter", "score", "gemm_bwd", "wgrad", "t
 # HBM bytes per launch of a workload's dominant kernel from the rocprofv3 --pmc runs summarised
 # under profiles/ (FETCH_SIZE + WRITE_SIZE, scaled by the copy kernel): {(config, kernel): bytes}
 MEASURED_TRAFFIC = {
-    (1, "gemm"): 19.6e6,        # mean over the 17 contraction launches of a step (weight gradients: 88 MB)
+    (1, "gemm"): 19.7e6,        # mean over the 17 contraction launches of a step (weight gradients: 90 MB)
     (3, "table_E"): 26.4e9,     # of which 9.75 GB written; 6.7 GB are re-reads of branch rows served by the caches
     (4, "sem"): 14.2e9,         # projection 16.2 GB + its gradient 12.1 GB per step, two launches
     ("box", 1, "gemm"): 18.3e6,     # mean over the 9 contraction launches of a step
