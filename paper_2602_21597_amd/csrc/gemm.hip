@@ -27,7 +27,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 template <int BM, int BN, int NW, bool SPLIT = false>
 struct Smem {
     // SPLIT: per wavefront and operand three bf16 pieces of a [32][BK] tile
-    static constexpr int STAGE = SPLIT ? NW * (BM / 32 + BN / 32) * 768 : NW * BK * (BM + PAD + BN + PAD);   // floats
+    static constexpr int STAGE = SPLIT ? NW * (BM / 32 + BN / 32) * 960 : NW * BK * (BM + PAD + BN + PAD);   // floats
     static constexpr int NR = NW > 4 ? NW / 2 : NW;                    // partial tiles held in LDS at once
     static constexpr int REDUCE = NR * BM * (BN + 1);
     static constexpr int FLOATS = STAGE > REDUCE ? STAGE : REDUCE;
@@ -160,12 +160,19 @@ __device__ __forceinline__ Pieces split3(float4 v) {
 }
 // Pieces of a [32][BK] tile in LDS: 16-byte units (8 consecutive k of a row); unit index
 // = k-half * 32 + row, piece after piece -- the operand layout of the 32x32x16 bf16 MFMA
-// (lane = k-half * 32 + row reads unit `lane`).
+// (lane = k-half * 32 + row reads unit `lane`).  In the tiles of an operand that is staged from
+// its k-strided layout (GAPS) one unit is left empty after every four: the 32-bit stores of that
+// staging then spread over all banks (8-way conflicts without the gaps; the 64-bit stores of the
+// k-contiguous staging need none and are slower with them).  Room per piece: 80 units = 640
+// bf16 either way; the three pieces of 32 rows take 1920.
+template <bool GAPS>
+__device__ __forceinline__ int unit_at(int u) { return (GAPS ? u + (u >> 2) : u) * 8; }
+constexpr int PIECE = 640, SUBTILE = 3 * PIECE;
 __device__ __forceinline__ void store_pieces(uint16_t* tile, int row, int kq, const Pieces& p) {
-    uint16_t* at = tile + ((kq >> 1) * 32 + row) * 8 + (kq & 1) * 4;
+    uint16_t* at = tile + unit_at<false>((kq >> 1) * 32 + row) + (kq & 1) * 4;
     *reinterpret_cast<uint2*>(at) = p.h;
-    *reinterpret_cast<uint2*>(at + 512) = p.m;
-    *reinterpret_cast<uint2*>(at + 1024) = p.l;
+    *reinterpret_cast<uint2*>(at + PIECE) = p.m;
+    *reinterpret_cast<uint2*>(at + 2 * PIECE) = p.l;
 }
 
 // Operand stored with k as the slow index ([K][X], X = rows or columns of the output): a lane
@@ -187,10 +194,10 @@ __device__ __forceinline__ void stage_strided(uint16_t* tile, int K, int X, int 
     for (int j = 0; j < 4; ++j) {
         uint32_t h, m, l;
         split2(ok0 ? e[j] : 0.f, ok1 ? o[j] : 0.f, h, m, l);
-        uint32_t* at = reinterpret_cast<uint32_t*>(tile + ((kp >> 2) * 32 + q * 4 + j) * 8 + (kp & 3) * 2);
+        uint32_t* at = reinterpret_cast<uint32_t*>(tile + unit_at<true>((kp >> 2) * 32 + q * 4 + j) + (kp & 3) * 2);
         at[0] = h;
-        at[256] = m;
-        at[512] = l;
+        at[PIECE / 2] = m;
+        at[PIECE] = l;
     }
 }
 
@@ -229,9 +236,9 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
     const bool first_n_tile = n0 == 0;
     constexpr int TM = BM / 32, TN = BN / 32;
     constexpr int LDA = BM + PAD, LDB = BN + PAD;
-    // (SPLIT: per 32 rows of an operand three pieces of 512 bf16 each)
-    float* As = smem + (SPLIT ? wave * (TM + TN) * 768 : wave * BK * (LDA + LDB));     // [BK][LDA] of this wavefront
-    float* Bs = As + (SPLIT ? TM * 768 : BK * LDA);                                      // [BK][LDB]
+    // (SPLIT: per 32 rows of an operand three pieces, SUBTILE bf16 = 960 floats)
+    float* As = smem + (SPLIT ? wave * (TM + TN) * 960 : wave * BK * (LDA + LDB));     // [BK][LDA] of this wavefront
+    float* Bs = As + (SPLIT ? TM * 960 : BK * LDA);                                      // [BK][LDB]
 
     floatx16 acc[TM][TN];
 #pragma unroll
@@ -320,7 +327,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
         if (!AK) {
 #pragma unroll
             for (int t = 0; t < TM; ++t)
-                stage_strided(Ap + t * 1536, a.K, a.M, kcur, m0 + 32 * t, lane,
+                stage_strided(Ap + t * SUBTILE, a.K, a.M, kcur, m0 + 32 * t, lane,
                               reinterpret_cast<const float4(&)[2]>(ra[2 * t]));
         }
 #pragma unroll
@@ -333,12 +340,12 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
             const bool ok = avalid[i] && gk < a.K;
             v.x = ok ? v.x : 0.f; v.y = ok ? v.y : 0.f; v.z = ok ? v.z : 0.f; v.w = ok ? v.w : 0.f;
             if (copy_out && ok) *reinterpret_cast<float4*>(a.a_copy + (size_t)(m0 + m) * a.lda + gk) = v;
-            store_pieces(Ap + (m >> 5) * 1536, m & 31, kq, split3(v));
+            store_pieces(Ap + (m >> 5) * SUBTILE, m & 31, kq, split3(v));
         }
         if (!BKC) {
 #pragma unroll
             for (int t = 0; t < TN; ++t)
-                stage_strided(Bp + t * 1536, a.K, a.N, kcur, n0 + 32 * t, lane,
+                stage_strided(Bp + t * SUBTILE, a.K, a.N, kcur, n0 + 32 * t, lane,
                               reinterpret_cast<const float4(&)[2]>(rb[2 * t]));
         }
 #pragma unroll
@@ -348,7 +355,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
             float4 v = rb[i];
             const bool ok = n0 + n < a.N && kcur + kq * 4 < a.K;
             v.x = ok ? v.x : 0.f; v.y = ok ? v.y : 0.f; v.z = ok ? v.z : 0.f; v.w = ok ? v.w : 0.f;
-            store_pieces(Bp + (n >> 5) * 1536, n & 31, kq, split3(v));
+            store_pieces(Bp + (n >> 5) * SUBTILE, n & 31, kq, split3(v));
         }
         __builtin_amdgcn_wave_barrier();
         if (it + 1 < rounds) {
@@ -360,10 +367,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
         for (int q = 0; q < 3; ++q) {
 #pragma unroll
             for (int i = 0; i < TM; ++i)
-                ap[i][q] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Ap + i * 1536 + q * 512 + lane * 8));
+                ap[i][q] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Ap + i * SUBTILE + q * PIECE + unit_at<!AK>(lane)));
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-                bp[j][q] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Bp + j * 1536 + q * 512 + lane * 8));
+                bp[j][q] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Bp + j * SUBTILE + q * PIECE + unit_at<!BKC>(lane)));
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
