@@ -39,7 +39,8 @@ def _gemm_case(M, N, K, a_k, b_k, seed, epilogue, arith=0):
 def test_contraction_kernel_all_layouts_and_tile_paths(layout):
     a_k, b_k = layout
     shapes = [(1, 64, 32), (37, 800, 400), (290, 800, 400), (392, 400, 800), (987, 800, 400),
-              (64, 32, 64), (33, 36, 20), (5000, 800, 400), (6100, 800, 400), (130, 400, 1352)]
+              (64, 32, 64), (33, 36, 20), (5000, 800, 400), (6100, 800, 400), (130, 400, 1352),
+              (2400, 448, 640)]         # (the last: the large tile chosen for a mid-size weight-gradient launch)
     for i, (M, N, K) in enumerate(shapes):
         if not a_k:
             M = (M + 3) // 4 * 4        # the m-contiguous A layout needs M % 4 == 0
