@@ -359,7 +359,7 @@ const char* ngdb_sampler_last_error(const ngdb_sampler_t* sampler);
  * and the contiguous extents must be multiples of 4.  arith: 0 = as the training
  * step chooses, 1 = fp32 matrix instructions, 2 = every fp32 operand as the exact
  * sum of three bf16 values and the six largest of the nine partial products on
- * the bf16 matrix instructions with fp32 accumulation (the rest is below 2^-26 of
+ * the bf16 matrix instructions with fp32 accumulation (the rest is below 2^-23 of
  * a product; always in the kernel's small tiles).                                 */
 int ngdb_debug_gemm(const float* A, const float* B, float* C, int32_t M, int32_t N, int32_t K,
                     int32_t lda, int32_t ldb, int32_t ldc, int32_t a_kcontig, int32_t b_kcontig,

@@ -76,7 +76,7 @@ struct GemmArgs {
 };
 // GEMM_FP32: fp32 MFMA.  GEMM_SPLIT: every fp32 operand value as the exact sum of three bf16
 // values, the six largest of the nine partial products on the bf16 MFMA with fp32 accumulation
-// (what is left out is below 2^-26 of a product); tiles of 32x32 only.  GEMM_AUTO: GEMM_SPLIT
+// (what is left out is below 2^-23 of a product, about 2^-27 on average).  GEMM_AUTO: GEMM_SPLIT
 // where it is faster, else GEMM_FP32.
 constexpr int GEMM_AUTO = 0, GEMM_FP32 = 1, GEMM_SPLIT = 2;
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);

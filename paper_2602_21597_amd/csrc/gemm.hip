@@ -134,7 +134,8 @@ __device__ __forceinline__ void stage_b(const GemmArgs& a, float* __restrict__ d
 // instead, every product would come out a little short, and the scores, whose loss weights
 // depend on them exponentially, would shift in one direction.  A product of two fp32 values is a
 // sum of nine bf16 products, of which the six largest are kept; the three left out are below
-// 2^-26 of the product.  bf16 products are exact in the fp32 accumulator of the matrix unit,
+// 2^-23 of the product (second piece at most 2^-8, third at most 2^-16 of the value), with
+// either sign.  bf16 products are exact in the fp32 accumulator of the matrix unit,
 // which multiplies bf16 sixteen times as fast as fp32.
 typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
