@@ -312,10 +312,13 @@ int prepare_entities(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_tail
 
 // The intersections of one segment as jobs of the pooling kernels: centres (box == false:
 // X = Z[T_INTER], logits Att) or offsets of the box family (X = Z[T_NEG], MLP outputs Gate).
-int inter_jobs(ngdb_ctx_t* c, const ngdb_plan_t* pl, const Segment& sg, bool offsets, bool backward, InterJobs* ij) {
+// With `pool` the jobs are appended to it and the offset jobs flagged (both kinds in one launch).
+int inter_jobs(ngdb_ctx_t* c, const ngdb_plan_t* pl, const Segment& sg, bool offsets, bool backward, InterJobs* ij,
+               BoxPoolJobs* pool = nullptr) {
     const HostPlan& hp = pl->hp;
     const int d = c->cfg.d;
-    *ij = InterJobs{};
+    if (pool) ij = &pool->jobs;
+    else *ij = InterJobs{};
     ij->d = d;
     for (int g = sg.g_lo; g < sg.g_hi; ++g) {
         const size_t mb = (size_t)hp.g_mlp_base[g] * d, ob = (size_t)hp.g_out_base[g] * d;
@@ -324,6 +327,7 @@ int inter_jobs(ngdb_ctx_t* c, const ngdb_plan_t* pl, const Segment& sg, bool off
         jb.X = ptr<float>(c->Z[offsets ? T_NEG : T_INTER]) + mb;
         jb.Att = ptr<float>(offsets ? c->Gate : c->Att) + mb;
         jb.n = hp.g_n[g]; jb.k = hp.g_nin[g];
+        if (pool && offsets) pool->gate_mask |= 1u << (ij->count - 1);
         if (!backward) {
             jb.out = ptr<float>(offsets ? c->off : c->act) + ob;
         } else {
@@ -383,8 +387,15 @@ int enqueue_forward_box(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t s) {
             if (sg.type != T_INTER) continue;
             Timed tm(c, NGDB_TK_INTER, s);
             InterJobs ij;
-            int rc = inter_jobs(c, pl, sg, false, false, &ij);
-            if (rc != NGDB_OK) return rc;
+            int rc;
+            if (2 * (sg.g_hi - sg.g_lo) <= INTER_MAX_JOBS) {     // centre and offset jobs fit one launch
+                BoxPoolJobs pool{};
+                if ((rc = inter_jobs(c, pl, sg, false, false, nullptr, &pool)) != NGDB_OK) return rc;
+                if ((rc = inter_jobs(c, pl, sg, true, false, nullptr, &pool)) != NGDB_OK) return rc;
+                HIPCHK(c, launch_box_pool(pool, false, s));
+                continue;
+            }
+            if ((rc = inter_jobs(c, pl, sg, false, false, &ij)) != NGDB_OK) return rc;
             HIPCHK(c, launch_inter(ij, false, s));
             if ((rc = inter_jobs(c, pl, sg, true, false, &ij)) != NGDB_OK) return rc;
             HIPCHK(c, launch_box_offset(ij, false, s));
@@ -555,11 +566,18 @@ int enqueue_backward_box(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t s, Wg
             {
                 Timed tm(c, NGDB_TK_INTER, s);
                 InterJobs ij;
-                int rc = inter_jobs(c, pl, sg, false, true, &ij);
-                if (rc != NGDB_OK) return rc;
-                HIPCHK(c, launch_inter(ij, true, s));
-                if ((rc = inter_jobs(c, pl, sg, true, true, &ij)) != NGDB_OK) return rc;
-                HIPCHK(c, launch_box_offset(ij, true, s));
+                int rc;
+                if (2 * (sg.g_hi - sg.g_lo) <= INTER_MAX_JOBS) {
+                    BoxPoolJobs pool{};
+                    if ((rc = inter_jobs(c, pl, sg, false, true, nullptr, &pool)) != NGDB_OK) return rc;
+                    if ((rc = inter_jobs(c, pl, sg, true, true, nullptr, &pool)) != NGDB_OK) return rc;
+                    HIPCHK(c, launch_box_pool(pool, true, s));
+                } else {
+                    if ((rc = inter_jobs(c, pl, sg, false, true, &ij)) != NGDB_OK) return rc;
+                    HIPCHK(c, launch_inter(ij, true, s));
+                    if ((rc = inter_jobs(c, pl, sg, true, true, &ij)) != NGDB_OK) return rc;
+                    HIPCHK(c, launch_box_offset(ij, true, s));
+                }
             }
             for (int part = 0; part < 2; ++part) {
                 const int t = part ? T_NEG : T_INTER;

@@ -43,12 +43,8 @@ __global__ __launch_bounds__(256) void box_proj_kernel(const BoxProjArgs a) {
 // one thread per (member, coordinate); the cardinality classes of one level are the jobs of
 // one launch (blockIdx.y), inputs walked to the compile-time maximum under a predicate
 template <bool BWD>
-__global__ __launch_bounds__(256) void box_offset_kernel(const InterJobs jobs) {
-    const InterJob jb = jobs.job[blockIdx.y];
-    const int d = jobs.d, n = jb.n, k = jb.k;
-    const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= (size_t)n * d) return;
-    const int i = (int)(t / d), c = (int)(t % d);
+__device__ __forceinline__ void offset_pool(const InterJob& jb, int d, int i, int c) {
+    const int n = jb.n, k = jb.k;
     float mean = 0.f, mn = INFINITY;
     int arg = 0;
 #pragma unroll
@@ -81,6 +77,67 @@ __global__ __launch_bounds__(256) void box_offset_kernel(const InterJobs jobs) {
     }
 }
 
+// attention pooling of the centres (as inter_kernel of the vector family)
+template <bool BWD>
+__device__ __forceinline__ void centre_pool(const InterJob& jb, int d, int i, int c) {
+    const int n = jb.n, k = jb.k;
+    float a[NGDB_MAX_CARD], x[NGDB_MAX_CARD];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < NGDB_MAX_CARD; ++j) {
+        const size_t row = (size_t)min(j, k - 1) * n + i;
+        a[j] = jb.Att[row * d + c];
+        x[j] = jb.X[row * d + c];
+        if (j < k) mx = fmaxf(mx, a[j]);
+    }
+    float den = 0.f;
+#pragma unroll
+    for (int j = 0; j < NGDB_MAX_CARD; ++j) {
+        a[j] = j < k ? expf(a[j] - mx) : 0.f;
+        den += a[j];
+    }
+    const float inv = 1.f / den;
+    if (!BWD) {
+        float y = 0.f;
+#pragma unroll
+        for (int j = 0; j < NGDB_MAX_CARD; ++j) y += a[j] * inv * x[j];
+        jb.out[(size_t)i * d + c] = y;
+    } else {
+        const float dy = jb.dY[(size_t)i * d + c];
+        float tall = 0.f;
+#pragma unroll
+        for (int j = 0; j < NGDB_MAX_CARD; ++j) tall += a[j] * inv * x[j] * dy;
+#pragma unroll
+        for (int j = 0; j < NGDB_MAX_CARD; ++j) {
+            if (j < k) {
+                const size_t row = (size_t)j * n + i;
+                const float w = a[j] * inv;
+                jb.dAtt[row * d + c] = w * (dy * x[j] - tall);
+                jb.Dx[row * d + c] = w * dy;
+            }
+        }
+    }
+}
+
+template <bool BWD>
+__global__ __launch_bounds__(256) void box_offset_kernel(const InterJobs jobs) {
+    const InterJob jb = jobs.job[blockIdx.y];
+    const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= (size_t)jb.n * jobs.d) return;
+    offset_pool<BWD>(jb, jobs.d, (int)(t / jobs.d), (int)(t % jobs.d));
+}
+
+// centre and offset jobs of one level in one launch (the job kind is uniform per workgroup)
+template <bool BWD>
+__global__ __launch_bounds__(256) void box_pool_kernel(const BoxPoolJobs bj) {
+    const InterJob jb = bj.jobs.job[blockIdx.y];
+    const int d = bj.jobs.d;
+    const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= (size_t)jb.n * d) return;
+    if ((bj.gate_mask >> blockIdx.y) & 1u) offset_pool<BWD>(jb, d, (int)(t / d), (int)(t % d));
+    else centre_pool<BWD>(jb, d, (int)(t / d), (int)(t % d));
+}
+
 }  // namespace
 
 hipError_t launch_box_proj(const BoxProjArgs& a, bool backward, hipStream_t s) {
@@ -104,6 +161,21 @@ hipError_t launch_box_offset(const InterJobs& jobs, bool backward, hipStream_t s
     const dim3 grid((unsigned)((most + 255) / 256), jobs.count);
     if (backward) hipLaunchKernelGGL((box_offset_kernel<true>), grid, dim3(256), 0, s, jobs);
     else hipLaunchKernelGGL((box_offset_kernel<false>), grid, dim3(256), 0, s, jobs);
+    return hipGetLastError();
+}
+
+hipError_t launch_box_pool(const BoxPoolJobs& bj, bool backward, hipStream_t s) {
+    const InterJobs& jobs = bj.jobs;
+    if (jobs.count <= 0) return hipSuccess;
+    if (jobs.count > INTER_MAX_JOBS) return hipErrorInvalidValue;
+    size_t most = 0;
+    for (int i = 0; i < jobs.count; ++i) {
+        if (jobs.job[i].n <= 0 || jobs.job[i].k < 1 || jobs.job[i].k > NGDB_MAX_CARD) return hipErrorInvalidValue;
+        most = std::max(most, (size_t)jobs.job[i].n * jobs.d);
+    }
+    const dim3 grid((unsigned)((most + 255) / 256), jobs.count);
+    if (backward) hipLaunchKernelGGL((box_pool_kernel<true>), grid, dim3(256), 0, s, bj);
+    else hipLaunchKernelGGL((box_pool_kernel<false>), grid, dim3(256), 0, s, bj);
     return hipGetLastError();
 }
 
