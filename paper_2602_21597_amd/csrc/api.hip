@@ -349,6 +349,19 @@ BoxProjArgs box_proj_args(ngdb_ctx_t* c, const ngdb_plan_t* pl, const Segment& s
     return a;
 }
 
+// The projection group of a level that can ride in the level's pooling launch (they are
+// independent of each other): the first one, if an intersection segment with few enough
+// cardinality classes for the joint launch exists.
+const Segment* riding_projection(const std::vector<Segment>& segs) {
+    const Segment* proj = nullptr;
+    bool joint = false;
+    for (const Segment& sg : segs) {
+        if (sg.type == T_PROJ && !proj) proj = &sg;
+        if (sg.type == T_INTER && 2 * (sg.g_hi - sg.g_lo) <= INTER_MAX_JOBS) joint = true;
+    }
+    return joint ? proj : nullptr;
+}
+
 // Box family, forward: projections are one elementwise launch per group; an intersection runs two
 // MLPs over its inputs (attention logits from the centres, gate inputs from the offsets), grouped
 // into one launch per layer, then the two pooling kernels.
@@ -358,8 +371,10 @@ int enqueue_forward_box(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t s) {
         const std::vector<Segment>& segs = pl->levels[l];
         GemmArgs g1[GEMM_MAX_GROUP], g2[GEMM_MAX_GROUP];
         int n = 0;
+        const Segment* ride = riding_projection(segs);
         for (const Segment& sg : segs) {
             if (sg.type == T_PROJ) {
+                if (&sg == ride) continue;
                 Timed tm(c, NGDB_TK_INTER, s);
                 HIPCHK(c, launch_box_proj(box_proj_args(c, pl, sg), false, s));
                 continue;
@@ -392,6 +407,7 @@ int enqueue_forward_box(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t s) {
                 BoxPoolJobs pool{};
                 if ((rc = inter_jobs(c, pl, sg, false, false, nullptr, &pool)) != NGDB_OK) return rc;
                 if ((rc = inter_jobs(c, pl, sg, true, false, nullptr, &pool)) != NGDB_OK) return rc;
+                if (ride) { pool.has_proj = 1; pool.proj = box_proj_args(c, pl, *ride); ride = nullptr; }
                 HIPCHK(c, launch_box_pool(pool, false, s));
                 continue;
             }
@@ -556,8 +572,10 @@ int enqueue_backward_box(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t s, Wg
         const std::vector<Segment>& segs = pl->levels[l];
         GemmArgs b2[GEMM_MAX_GROUP], b1[GEMM_MAX_GROUP];
         int n = 0;
+        const Segment* ride = riding_projection(segs);
         for (const Segment& sg : segs) {
             if (sg.type == T_PROJ) {
+                if (&sg == ride) continue;
                 Timed tm(c, NGDB_TK_INTER, s);
                 HIPCHK(c, launch_box_proj(box_proj_args(c, pl, sg), true, s));
                 continue;
@@ -571,6 +589,7 @@ int enqueue_backward_box(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t s, Wg
                     BoxPoolJobs pool{};
                     if ((rc = inter_jobs(c, pl, sg, false, true, nullptr, &pool)) != NGDB_OK) return rc;
                     if ((rc = inter_jobs(c, pl, sg, true, true, nullptr, &pool)) != NGDB_OK) return rc;
+                    if (ride) { pool.has_proj = 1; pool.proj = box_proj_args(c, pl, *ride); ride = nullptr; }
                     HIPCHK(c, launch_box_pool(pool, true, s));
                 } else {
                     if ((rc = inter_jobs(c, pl, sg, false, true, &ij)) != NGDB_OK) return rc;

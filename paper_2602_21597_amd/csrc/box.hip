@@ -10,9 +10,8 @@ namespace ngdb {
 namespace {
 
 template <bool BWD>
-__global__ __launch_bounds__(256) void box_proj_kernel(const BoxProjArgs a) {
+__device__ __forceinline__ void proj_body(const BoxProjArgs& a, size_t t) {
     const int d4 = a.d >> 2;
-    const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= (size_t)a.n * d4) return;
     const int i = (int)(t / d4), c = (int)(t % d4);
     const size_t out = ((size_t)(a.out_base + i) * a.d >> 2) + c;
@@ -38,6 +37,11 @@ __global__ __launch_bounds__(256) void box_proj_kernel(const BoxProjArgs a) {
     o.x += fmaxf(ro.x, 0.f); o.y += fmaxf(ro.y, 0.f); o.z += fmaxf(ro.z, 0.f); o.w += fmaxf(ro.w, 0.f);
     reinterpret_cast<float4*>(a.act_c)[out] = x;
     reinterpret_cast<float4*>(a.act_o)[out] = o;
+}
+
+template <bool BWD>
+__global__ __launch_bounds__(256) void box_proj_kernel(const BoxProjArgs a) {
+    proj_body<BWD>(a, (size_t)blockIdx.x * blockDim.x + threadIdx.x);
 }
 
 // one thread per (member, coordinate); the cardinality classes of one level are the jobs of
@@ -130,9 +134,13 @@ __global__ __launch_bounds__(256) void box_offset_kernel(const InterJobs jobs) {
 // centre and offset jobs of one level in one launch (the job kind is uniform per workgroup)
 template <bool BWD>
 __global__ __launch_bounds__(256) void box_pool_kernel(const BoxPoolJobs bj) {
+    const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if ((int)blockIdx.y == bj.jobs.count) {     // the projections riding along
+        proj_body<BWD>(bj.proj, t);
+        return;
+    }
     const InterJob jb = bj.jobs.job[blockIdx.y];
     const int d = bj.jobs.d;
-    const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= (size_t)jb.n * d) return;
     if ((bj.gate_mask >> blockIdx.y) & 1u) offset_pool<BWD>(jb, d, (int)(t / d), (int)(t % d));
     else centre_pool<BWD>(jb, d, (int)(t / d), (int)(t % d));
@@ -173,7 +181,11 @@ hipError_t launch_box_pool(const BoxPoolJobs& bj, bool backward, hipStream_t s) 
         if (jobs.job[i].n <= 0 || jobs.job[i].k < 1 || jobs.job[i].k > NGDB_MAX_CARD) return hipErrorInvalidValue;
         most = std::max(most, (size_t)jobs.job[i].n * jobs.d);
     }
-    const dim3 grid((unsigned)((most + 255) / 256), jobs.count);
+    if (bj.has_proj) {
+        if (bj.proj.n <= 0 || (bj.proj.d & 3)) return hipErrorInvalidValue;
+        most = std::max(most, (size_t)bj.proj.n * (bj.proj.d >> 2));
+    }
+    const dim3 grid((unsigned)((most + 255) / 256), jobs.count + (bj.has_proj ? 1 : 0));
     if (backward) hipLaunchKernelGGL((box_pool_kernel<true>), grid, dim3(256), 0, s, bj);
     else hipLaunchKernelGGL((box_pool_kernel<false>), grid, dim3(256), 0, s, bj);
     return hipGetLastError();

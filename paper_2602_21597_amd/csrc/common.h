@@ -112,13 +112,7 @@ hipError_t launch_inter(const InterJobs& jobs, bool backward, hipStream_t s);
 // Backward: dAtt[j*n+i] = dy * min * g(1-g) / k;  Dx[j*n+i] = dy * g for the first j attaining
 // the minimum, 0 for the others.
 hipError_t launch_box_offset(const InterJobs& jobs, bool backward, hipStream_t s);
-// Both poolings of the box family's intersections in one launch: jobs flagged in gate_mask are
-// offset jobs (launch_box_offset), the others centre jobs (launch_inter).
-struct BoxPoolJobs {
-    InterJobs jobs;
-    uint32_t gate_mask;
-};
-hipError_t launch_box_pool(const BoxPoolJobs& jobs, bool backward, hipStream_t s);
+
 // Box family, projections of one group: member i reads its input box through ref[i] (slot, or
 // -1-entity: centre E[e], offset 0) and writes (c + Rc[rel[i]], o + relu(Ro[rel[i]])) to slot
 // out_base + i.  Backward copies the gradient rows of slot out_base + i (centre and offset) to
@@ -130,6 +124,17 @@ struct BoxProjArgs {
     int n, d, out_base;
 };
 hipError_t launch_box_proj(const BoxProjArgs& a, bool backward, hipStream_t s);
+// Both poolings of the box family's intersections in one launch: jobs flagged in gate_mask are
+// offset jobs (launch_box_offset), the others centre jobs (launch_inter).  With has_proj the
+// projections of a group of the same level (independent of the intersections) ride along as
+// one more job.
+struct BoxPoolJobs {
+    InterJobs jobs;
+    uint32_t gate_mask;
+    int has_proj;
+    BoxProjArgs proj;
+};
+hipError_t launch_box_pool(const BoxPoolJobs& jobs, bool backward, hipStream_t s);
 // out[c] = sum_m X[m*ld + c], c < cols, for several matrices in one launch pair (fixed
 // summation order); `part` is scratch of COLSUM_MAX_CHUNKS * cols floats per matrix
 constexpr int COLSUM_MAX_CHUNKS = 128;
