@@ -691,12 +691,11 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
         HIPCHK(c, hipEventRecord(c->ev_fork, stream));
         HIPCHK(c, hipStreamWaitEvent(s_tab, c->ev_fork, 0));
     }
-    // (the sum of the loss terms is off the critical path there)
-    HIPCHK(c, launch_loss_reduce(ptr<float>(c->loss_terms), B, B > 0 ? 1.f / (2.f * B) : 0.f, d_loss, s_tab));
+    // (the sum of the loss terms is off the critical path there, in the launch that resolves the records)
     const int64_t n_contrib = (int64_t)hp.n_anchor + B + (int64_t)B * K;
     HIPCHK(c, launch_resolve(e_src, n_contrib, hp.n_anchor, hp.n_slots, B, K, ptr<float>(c->coef),
                              sem ? nullptr : ptr<int32_t>(c->win), ptr<float>(c->rec_coef), ptr<int32_t>(c->rec_row),
-                             s_tab));
+                             ptr<float>(c->loss_terms), B > 0 ? 1.f / (2.f * B) : 0.f, d_loss, s_tab));
     TableArgs te{};
     te.P = c->prm.E.p; te.Mo = c->prm.E.m; te.Vo = c->prm.E.v;
     te.uniq = ptr<int32_t>(c->uniq); te.seg_off = ptr<int32_t>(c->seg_off);

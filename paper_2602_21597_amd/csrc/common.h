@@ -277,9 +277,11 @@ struct TableArgs {
 };
 // sorted contribution numbers -> records: c < n_rowsrc is gradient row row_base + c,
 // otherwise a (query, candidate) pair in the order [B positives | B*K negatives]
-// (win: winning rows per pair -> records carry act rows; null -> records carry pair numbers)
+// (win: winning rows per pair -> records carry act rows; null -> records carry pair numbers).
+// With loss_terms [B] the same launch also writes loss[0] = loss_scale * sum of the terms.
 hipError_t launch_resolve(const int32_t* src, int64_t n, int n_rowsrc, int row_base, int B, int K, const float* coef,
-                          const int32_t* win, float* rec_coef, int32_t* rec_row, hipStream_t s);
+                          const int32_t* win, float* rec_coef, int32_t* rec_row, const float* loss_terms,
+                          float loss_scale, float* loss, hipStream_t s);
 hipError_t launch_table_update(const TableArgs& a, const AdamHyper& hp, hipStream_t s);
 
 // ---------------------------------------------------------------- text-feature fusion (sem.hip)

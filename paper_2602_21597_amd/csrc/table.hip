@@ -27,12 +27,26 @@ namespace {
 
 // rec_row[t] >= 0: pair contribution (rec_coef[t] = dL/ds): the row of act of the pair's
 // winning branch if win is given, else the pair number; rec_row[t] < 0: row -1-rec_row[t]
-// of dact (gradient row, added as is)
+// of dact (gradient row, added as is).  With loss_terms, one more workgroup (the last) sums the
+// B per-query loss terms into loss[0] = loss_scale * sum (the step's loss; a launch saved).
 __global__ __launch_bounds__(256) void resolve_kernel(const int32_t* __restrict__ src, int64_t n, int n_rowsrc,
                                                       int row_base, int B, int K, const float* __restrict__ coef,
                                                       const int32_t* __restrict__ win, float* __restrict__ rec_coef,
-                                                      int32_t* __restrict__ rec_row) {
-    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < n; t += (int64_t)gridDim.x * blockDim.x) {
+                                                      int32_t* __restrict__ rec_row,
+                                                      const float* __restrict__ loss_terms, float loss_scale,
+                                                      float* __restrict__ loss) {
+    const int walkers = (int)gridDim.x - (loss_terms ? 1 : 0);
+    if ((int)blockIdx.x == walkers) {      // (only with loss_terms)
+        __shared__ float part[4];
+        float s = 0.f;
+        for (int i = threadIdx.x; i < B; i += 256) s += loss_terms[i];
+        s = wave_sum(s);
+        if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = s;
+        __syncthreads();
+        if (threadIdx.x == 0) loss[0] = loss_scale * ((part[0] + part[1]) + (part[2] + part[3]));
+        return;
+    }
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < n; t += (int64_t)walkers * blockDim.x) {
         const int32_t c = src[t];
         if (c < n_rowsrc) {
             rec_coef[t] = 0.f;
@@ -257,11 +271,12 @@ __global__ __launch_bounds__(256) void table_kernel(const TableArgs a, const Ada
 }  // namespace
 
 hipError_t launch_resolve(const int32_t* src, int64_t n, int n_rowsrc, int row_base, int B, int K, const float* coef,
-                          const int32_t* win, float* rec_coef, int32_t* rec_row, hipStream_t s) {
-    if (n <= 0) return hipSuccess;
-    const unsigned blocks = (unsigned)std::min<int64_t>((n + 255) / 256, 4096);
+                          const int32_t* win, float* rec_coef, int32_t* rec_row, const float* loss_terms,
+                          float loss_scale, float* loss, hipStream_t s) {
+    if (n <= 0) return loss_terms ? launch_loss_reduce(loss_terms, B, loss_scale, loss, s) : hipSuccess;
+    const unsigned blocks = (unsigned)std::min<int64_t>((n + 255) / 256, 4096) + (loss_terms ? 1 : 0);
     hipLaunchKernelGGL(resolve_kernel, dim3(blocks), dim3(256), 0, s, src, n, n_rowsrc, row_base, B, K, coef, win,
-                       rec_coef, rec_row);
+                       rec_coef, rec_row, loss_terms, loss_scale, loss);
     return hipGetLastError();
 }
 
