@@ -11,6 +11,11 @@
 // partial tiles are then summed through LDS in a fixed order (deterministic) and
 // the epilogue is applied to the sum.  The A operand can be assembled on the fly
 // from row references (gather of operator inputs fused into the first layer).
+//
+// Results are fp32 either way, but the products are formed on one of two routes: fp32
+// MFMA blocks, or (SPLIT) bf16 MFMA blocks on operands that are split, while a tile is
+// staged, into three bf16 pieces whose sum is the fp32 value exactly; six of the nine
+// partial products are kept.  The matrix unit then needs 2.7 times less time per tile.
 #include "common.h"
 
 namespace ngdb {
