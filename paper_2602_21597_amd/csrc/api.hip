@@ -710,14 +710,26 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
     tr.P = c->prm.R.p; tr.Mo = c->prm.R.m; tr.Vo = c->prm.R.v;
     tr.uniq = pl->d_r_uniq; tr.seg_off = pl->d_r_seg_off; tr.n_uniq_dev = pl->d_n_r_uniq;
     tr.rec_coef = nullptr; tr.rec_row = pl->d_r_rec; tr.g_out = apply ? nullptr : ptr<float>(c->gR);
-    { Timed tm(c, NGDB_TK_TABLE_E, s_tab); HIPCHK(c, launch_table_update(te, ah, s_tab)); }
-    { Timed tm(c, NGDB_TK_TABLE_R, s_tab); HIPCHK(c, launch_table_update(tr, ah, s_tab)); }
+    // in a small step the relation tables ride in the entity table's launch (a launch of their own
+    // each would add its latency to the tail of the step)
+    TableArgs small[2] = {tr, tr};
+    int n_small = 1;
+    small[0].shadow = nullptr; small[0].off = nullptr;
     if (box) {   // relation offsets: the same segments over the offset gradients, gated by relu
-        TableArgs to = tr;
+        TableArgs& to = small[n_small++];
+        to = small[0];
         to.P = c->prm.Ro.p; to.Mo = c->prm.Ro.m; to.Vo = c->prm.Ro.v;
         to.dact = ptr<float>(c->doff); to.relu_gate = true; to.g_out = apply ? nullptr : ptr<float>(c->gRo);
-        Timed tm(c, NGDB_TK_TABLE_R, s_tab);
-        HIPCHK(c, launch_table_update(to, ah, s_tab));
+    }
+    if (std::min<int64_t>(n_contrib, c->cfg.n_entities) <= 65536) {   // a small step: one launch for all tables
+        Timed tm(c, NGDB_TK_TABLE_E, s_tab);
+        HIPCHK(c, launch_table_update(te, ah, s_tab, small, n_small, c->cfg.n_relations));
+    } else {
+        { Timed tm(c, NGDB_TK_TABLE_E, s_tab); HIPCHK(c, launch_table_update(te, ah, s_tab)); }
+        for (int k = 0; k < n_small; ++k) {
+            Timed tm(c, NGDB_TK_TABLE_R, s_tab);
+            HIPCHK(c, launch_table_update(small[k], ah, s_tab));
+        }
     }
     rc = enqueue_weight_grads(c, wj, stream);
     if (rc != NGDB_OK) return rc;

@@ -282,7 +282,16 @@ struct TableArgs {
 hipError_t launch_resolve(const int32_t* src, int64_t n, int n_rowsrc, int row_base, int B, int K, const float* coef,
                           const int32_t* win, float* rec_coef, int32_t* rec_row, const float* loss_terms,
                           float loss_scale, float* loss, hipStream_t s);
-hipError_t launch_table_update(const TableArgs& a, const AdamHyper& hp, hipStream_t s);
+// Up to two small plain tables of the same width (no text features, box weights or bf16 copy: the
+// relation tables), updated by extra workgroups of the main table's launch (meant for small steps).
+struct TableTail {
+    int main_blocks;
+    int blocks[2];
+    TableArgs job[2];
+};
+// small[0..n_small): such tables, each of at most small_rows touched rows.
+hipError_t launch_table_update(const TableArgs& a, const AdamHyper& hp, hipStream_t s, const TableArgs* small = nullptr,
+                               int n_small = 0, int small_rows = 0);
 
 // ---------------------------------------------------------------- text-feature fusion (sem.hip)
 hipError_t launch_cast_bf16(const float* x, uint16_t* y, int64_t n, hipStream_t s);

@@ -20,6 +20,7 @@
 // chasing dependent indices per contribution; inside a segment the gradient rows
 // come first (anchors sort before positives and negatives), so the two kinds are
 // walked by two branch-free loops with several sources in flight.
+#include <algorithm>
 #include "common.h"
 
 namespace ngdb {
@@ -87,12 +88,10 @@ __device__ __forceinline__ uint32_t load_mask(const void* mask, size_t idx) {
 // SH (plain vector family): the scoring pass reads a bf16 copy of the table; pair signs are taken
 // against the rounded row and the updated row is rounded into the copy.
 template <int NCH, bool SEM, bool BOX, bool SH>
-__global__ __launch_bounds__(256) void table_kernel(const TableArgs a, const AdamHyper hp) {
+__device__ __forceinline__ void table_rows(const TableArgs& a, const AdamHyper& hp, int wave_global, int n_waves) {
     const int lane = threadIdx.x & 63;
     const int d4 = a.d >> 2;
     const int n_uniq = *a.n_uniq_dev;
-    const int wave_global = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-    const int n_waves = (gridDim.x * blockDim.x) >> 6;
     const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
     const bool update = a.g_out == nullptr;
     bool col_ok[NCH];
@@ -268,6 +267,39 @@ __global__ __launch_bounds__(256) void table_kernel(const TableArgs a, const Ada
 
 #undef NGDB_PS
 
+// Small steps (the launch, not the bytes, is what a table update costs there): the last
+// main_blocks workgroups walk the rows of the main table; the ones before them those of up to two
+// small plain tables of the same width (the relation tables, whose launches of their own would
+// each add their latency to the step's tail).  Large tables keep table_kernel: there this
+// kernel measured 3 % slower on the entity table than the launches it saves are worth.
+// one table per launch
+template <int NCH, bool SEM, bool BOX, bool SH>
+__global__ __launch_bounds__(256) void table_kernel(const TableArgs a, const AdamHyper hp) {
+    table_rows<NCH, SEM, BOX, SH>(a, hp, (int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6),
+                                  (int)((gridDim.x * blockDim.x) >> 6));
+}
+
+// (box family at d <= 512: every pair re-reads two cached rows, and a fourth wavefront per SIMD
+// costs more in cache misses than it hides: held at three)
+template <int NCH, bool SEM, bool BOX, bool SH>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (BOX && NCH == 2) ? 3 : 8)))
+void table_group_kernel(const TableArgs a, const TableTail tail, const AdamHyper hp) {
+    const int b = (int)blockIdx.x;
+    const int mb = b - tail.blocks[0] - tail.blocks[1];
+    if (mb >= 0) {
+        // (the wavefront's number is the same in all its lanes: kept in a scalar register)
+        table_rows<NCH, SEM, BOX, SH>(a, hp, __builtin_amdgcn_readfirstlane((int)((mb * blockDim.x + threadIdx.x) >> 6)),
+                                      tail.main_blocks * 4);
+        return;
+    }
+    const int k = b < tail.blocks[0] ? 0 : 1;
+    const int lb = k ? b - tail.blocks[0] : b;
+    table_rows<NCH, false, false, false>(tail.job[k], hp,
+                                         __builtin_amdgcn_readfirstlane((int)((lb * blockDim.x + threadIdx.x) >> 6)),
+                                         tail.blocks[k] * 4);
+}
+
+
 }  // namespace
 
 hipError_t launch_resolve(const int32_t* src, int64_t n, int n_rowsrc, int row_base, int B, int K, const float* coef,
@@ -280,24 +312,40 @@ hipError_t launch_resolve(const int32_t* src, int64_t n, int n_rowsrc, int row_b
     return hipGetLastError();
 }
 
-hipError_t launch_table_update(const TableArgs& a, const AdamHyper& hp, hipStream_t s) {
+hipError_t launch_table_update(const TableArgs& a, const AdamHyper& hp, hipStream_t s, const TableArgs* small,
+                               int n_small, int small_rows) {
     // the number of touched rows is only known on the device: a fixed grid walks them
-    const int blocks = 256 * 8;
+    TableTail tail{};
+    tail.main_blocks = 256 * 8;
+    if (n_small < 0 || n_small > 2 || (n_small > 0 && !small)) return hipErrorInvalidValue;
+    for (int k = 0; k < n_small; ++k) {
+        const TableArgs& t = small[k];
+        if (t.d != a.d || t.g_bf16 || t.mask || t.off || t.shadow) return hipErrorInvalidValue;   // plain tables only
+        tail.job[k] = t;
+        tail.blocks[k] = std::max(1, std::min(256, (small_rows + 3) / 4));
+    }
+    const int blocks = tail.main_blocks + tail.blocks[0] + tail.blocks[1];
     if (a.d > 1024 || (a.g_bf16 != nullptr) != (a.mask != nullptr)) return hipErrorInvalidValue;
     const bool sem = a.g_bf16 != nullptr, box = a.off != nullptr;
     if (sem && (box || a.relu_gate)) return hipErrorInvalidValue;
     if (a.shadow && (sem || box)) return hipErrorInvalidValue;
-#define NGDB_TABLE(NCH)                                                                                      \
-    do {                                                                                                     \
-        if (sem) hipLaunchKernelGGL((table_kernel<NCH, true, false, false>), dim3(blocks), dim3(256), 0, s, a, hp); \
-        else if (box) hipLaunchKernelGGL((table_kernel<NCH, false, true, false>), dim3(blocks), dim3(256), 0, s, a, hp); \
-        else if (a.shadow) hipLaunchKernelGGL((table_kernel<NCH, false, false, true>), dim3(blocks), dim3(256), 0, s, a, hp); \
-        else hipLaunchKernelGGL((table_kernel<NCH, false, false, false>), dim3(blocks), dim3(256), 0, s, a, hp);   \
+#define NGDB_TABLE_V(NCH, SEM_, BOX_, SH_)                                                                     \
+    do {                                                                                                      \
+        if (n_small) hipLaunchKernelGGL((table_group_kernel<NCH, SEM_, BOX_, SH_>), dim3(blocks), dim3(256), 0, s, a, tail, hp); \
+        else hipLaunchKernelGGL((table_kernel<NCH, SEM_, BOX_, SH_>), dim3(tail.main_blocks), dim3(256), 0, s, a, hp);       \
+    } while (0)
+#define NGDB_TABLE(NCH)                                   \
+    do {                                                  \
+        if (sem) NGDB_TABLE_V(NCH, true, false, false);   \
+        else if (box) NGDB_TABLE_V(NCH, false, true, false); \
+        else if (a.shadow) NGDB_TABLE_V(NCH, false, false, true); \
+        else NGDB_TABLE_V(NCH, false, false, false);      \
     } while (0)
     if (a.d <= 256) NGDB_TABLE(1);
     else if (a.d <= 512) NGDB_TABLE(2);
     else NGDB_TABLE(4);
 #undef NGDB_TABLE
+#undef NGDB_TABLE_V
     return hipGetLastError();
 }
 
