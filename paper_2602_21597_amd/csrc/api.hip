@@ -476,7 +476,9 @@ struct WgradJob {   // what enqueue_weight_grads needs after a backward chain
 // Gradients of the MLP tensors of the given types (their Z / H / dH buffers, dY = gradient of
 // the second layer's output): both weight matrices of every type in one grouped launch, the
 // biases as column sums.
-int enqueue_weight_grads(ngdb_ctx_t* c, const WgradJob& wj, hipStream_t s) {
+// With `open` the bias gradients are left as partial column sums (described in *open) for the
+// dense Adam launch to add up: one launch less on the step's tail.
+int enqueue_weight_grads(ngdb_ctx_t* c, const WgradJob& wj, hipStream_t s, ColsumJobs* open = nullptr) {
     const int d = c->cfg.d, h = c->cfg.h, nt = wj.nt;
     const int* types = wj.types;
     const size_t* rows = wj.rows;
@@ -501,7 +503,8 @@ int enqueue_weight_grads(ngdb_ctx_t* c, const WgradJob& wj, hipStream_t s) {
                                        r, d, d, 0, 0};
     }
     HIPCHK(c, launch_gemm_group(w, 2 * nt, s));
-    HIPCHK(c, launch_colsums(cs, s));
+    HIPCHK(c, launch_colsums(cs, s, open == nullptr));
+    if (open) *open = cs;
     return NGDB_OK;
 }
 
@@ -731,7 +734,8 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
             HIPCHK(c, launch_table_update(small[k], ah, s_tab));
         }
     }
-    rc = enqueue_weight_grads(c, wj, stream);
+    ColsumJobs open_sums{};
+    rc = enqueue_weight_grads(c, wj, stream, apply ? &open_sums : nullptr);
     if (rc != NGDB_OK) return rc;
     if (apply) {
         DenseAdamJob job{};
@@ -744,6 +748,12 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
             job.p[k] = ts[i]->p; job.m[k] = ts[i]->m; job.v[k] = ts[i]->v;
             job.g[k] = ptr<float>(c->gW) + c->gw_off[i];
             job.n[k] = sz[i % 4];
+            for (int q = 0; q < open_sums.count; ++q)     // a bias: its gradient is still in chunks
+                if (open_sums.job[q].out == job.g[k]) {
+                    job.gsum[k] = open_sums.job[q].out;
+                    job.g[k] = open_sums.job[q].part;
+                    job.chunks[k] = open_sums.job[q].chunks;
+                }
         }
         Timed tm(c, NGDB_TK_ADAM, stream);
         HIPCHK(c, launch_dense_adam(job, ah, stream));

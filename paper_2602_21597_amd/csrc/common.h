@@ -150,7 +150,9 @@ struct ColsumJobs {
     int count;
     ColsumJob job[COLSUM_MAX_JOBS];
 };
-hipError_t launch_colsums(ColsumJobs& jobs, hipStream_t s);
+// finish == false: only the partial sums (part[chunk * cols + c], chunks filled in); whoever
+// consumes them adds the chunks up in colsum_final_kernel's order.
+hipError_t launch_colsums(ColsumJobs& jobs, hipStream_t s, bool finish = true);
 hipError_t launch_fill_zero(float* p, size_t n, hipStream_t s);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 
@@ -164,6 +166,10 @@ struct DenseAdamJob {
     float* v[13];
     const float* g[13];
     int64_t n[13];
+    // chunks[t] > 0: g[t] holds that many partial column sums of n[t] columns each (launch_colsums
+    // without its last step); they are added up here, the sum also stored in gsum[t]
+    int chunks[13];
+    float* gsum[13];
     int count;
 };
 hipError_t launch_dense_adam(const DenseAdamJob& job, const AdamHyper& hp, hipStream_t s);

@@ -115,8 +115,24 @@ __global__ __launch_bounds__(256) void dense_adam_kernel(const DenseAdamJob job,
     float* __restrict__ v = job.v[t];
     const float* __restrict__ g = job.g[t];
     const int64_t n = job.n[t];
+    const int chunks = job.chunks[t];
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
-        const float gi = g[i];
+        float gi;
+        if (chunks > 0) {     // partial column sums, added up as colsum_final_kernel does
+            float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+            int k = 0;
+            for (; k + 4 <= chunks; k += 4) {
+                s0 += g[(size_t)(k + 0) * n + i];
+                s1 += g[(size_t)(k + 1) * n + i];
+                s2 += g[(size_t)(k + 2) * n + i];
+                s3 += g[(size_t)(k + 3) * n + i];
+            }
+            for (; k < chunks; ++k) s0 += g[(size_t)k * n + i];
+            gi = (s0 + s1) + (s2 + s3);
+            job.gsum[t][i] = gi;
+        } else {
+            gi = g[i];
+        }
         const float mi = hp.beta1 * m[i] + (1.f - hp.beta1) * gi;
         const float vi = hp.beta2 * v[i] + (1.f - hp.beta2) * gi * gi;
         m[i] = mi;
@@ -152,7 +168,7 @@ hipError_t launch_inter(const InterJobs& jobs, bool backward, hipStream_t s) {
     return hipGetLastError();
 }
 
-hipError_t launch_colsums(ColsumJobs& jobs, hipStream_t s) {
+hipError_t launch_colsums(ColsumJobs& jobs, hipStream_t s, bool finish) {
     if (jobs.count <= 0) return hipSuccess;
     int max_cols = 0, max_chunks = 1;
     for (int i = 0; i < jobs.count; ++i) {
@@ -163,6 +179,7 @@ hipError_t launch_colsums(ColsumJobs& jobs, hipStream_t s) {
         max_chunks = std::max(max_chunks, j.chunks);
     }
     hipLaunchKernelGGL(colsum_part_kernel, dim3((max_cols + 63) / 64, max_chunks, jobs.count), dim3(64, 4), 0, s, jobs);
+    if (!finish) return hipGetLastError();
     hipLaunchKernelGGL(colsum_final_kernel, dim3((max_cols + 255) / 256, jobs.count), dim3(256), 0, s, jobs);
     return hipGetLastError();
 }
