@@ -260,7 +260,7 @@ void ngdb_destroy(ngdb_ctx_t* ctx);
  * by ngdb_train_step.  Wp and H_sem are required iff d_sem > 0.                  */
 int ngdb_bind_params(ngdb_ctx_t* ctx, const ngdb_params* params);
 
-/* Queries -> operator-level frontiers and index arrays (Alg. 1 lines 1-4 and
+/* Queries -> operator-level frontiers and index arrays (Alg. 1, graph construction and
  * the pools of Sec. 4.1, resolved ahead of time level by level).  Host work
  * plus one upload; deterministic.  Ids are range-checked here (NGDB_ERR_RANGE).
  * The plan may be used for any number of steps on this context.                  */
@@ -279,7 +279,7 @@ int ngdb_plan_export(const ngdb_plan_t* plan, ngdb_plan_view* out);
  * buffer there: it can still be exported and must still be freed, not executed. */
 void ngdb_plan_free(ngdb_plan_t* plan);
 
-/* One training step (Alg. 1 lines 5-21): forward over the plan's frontiers,
+/* One training step (Alg. 1, the scheduling loop and the optimiser step): forward over the plan's frontiers,
  * L1 scores of every query against its positive and its K negatives, loss,
  * backward, segmented scatter-add of the table gradients, Adam on every bound
  * tensor, step count + 1.  d_neg: device [n_queries, K] entity ids, K >= 1 (range is
