@@ -68,3 +68,29 @@ def test_six_products_miss_at_most_2_to_minus_23_of_a_product():
     # a bf16 x bf16 product has at most 16 significant bits: exact in an fp32 accumulator
     prod = (pa[0] * pb[0]).astype(np.float32).astype(np.float64)
     assert np.array_equal(prod, pa[0] * pb[0])
+
+
+def test_a_dot_product_from_the_six_products_is_as_good_as_an_fp32_one():
+    """K = 800 terms, the six kept partial products summed in fp32 (any order of an fp32
+    accumulator) against a plain fp32 dot product, both measured on fp64."""
+    rng = np.random.default_rng(2)
+    n, K = 200, 800
+    a = (rng.standard_normal((n, K)) * 0.05).astype(np.float32)
+    b = (rng.standard_normal((n, K)) * 0.05).astype(np.float32)
+    exact = (a.astype(np.float64) * b.astype(np.float64)).sum(axis=1)
+    scale = (np.abs(a).astype(np.float64) * np.abs(b).astype(np.float64)).sum(axis=1)
+    pa, pb = pieces(a), pieces(b)
+    acc = np.zeros(n, np.float32)
+    # (the kernel adds the six products of a k-tile one after the other; here piece pair by piece pair:
+    # the error level is the same for either order)
+    for i, j in ((2, 0), (0, 2), (1, 1), (1, 0), (0, 1), (0, 0)):
+        prod = pa[i] * pb[j]                                           # exact: 16 significant bits
+        for k0 in range(0, K, 16):                                     # one MFMA step of 16 k at a time
+            acc = (acc + prod[:, k0:k0 + 16].sum(axis=1, dtype=np.float32)).astype(np.float32)
+    plain = np.zeros(n, np.float32)
+    for k in range(K):
+        plain = (plain + a[:, k] * b[:, k]).astype(np.float32)
+    err_split = np.abs(acc.astype(np.float64) - exact) / scale
+    err_plain = np.abs(plain.astype(np.float64) - exact) / scale
+    assert err_split.max() < 5e-7, err_split.max()
+    assert err_split.mean() <= 2.0 * err_plain.mean() + 1e-9, (err_split.mean(), err_plain.mean())
