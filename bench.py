@@ -385,6 +385,11 @@ def main():
                 "other": {k: {f: v[f] for f in ("bound", "achieved", "peak", "unit", "frac", "avg_us",
                                                 "launches_per_step", "ms_per_step")}
                           for k, v in kern.items() if k != dom}}
+    if dom == "gemm":
+        # fp32 contractions, priced against the fp32 matrix peak; the split route (six bf16 MFMAs per
+        # fp32 product block) has a ceiling of its own, the bf16 peak over six
+        roofline["peak_basis"] = ("fp32 MFMA peak; the bf16-split route's own ceiling is %.0f TFLOP/s (bf16 peak / 6)"
+                                  % (MFMA_BF16_PEAK_TF / 6.0))
 
     out = {
         "metric": "training queries/sec (fwd+bwd+Adam) at d=400, K=128 negatives; % of HBM peak",
