@@ -202,20 +202,6 @@ def forward(tree, M):
     raise Unsupported("forward() takes conjunctive trees; split unions with dnf()")
 
 
-def min_abs_preactivation(tape):
-    """Smallest |pre-activation| of any hidden unit met while evaluating a tree
-    (distance of the evaluation from a ReLU kink)."""
-    kind = tape[0]
-    if kind == "e":
-        return np.inf
-    if kind == "p":
-        return min(float(np.abs(tape[3][1]).min()), min_abs_preactivation(tape[2]))
-    if kind == "n":
-        return min(float(np.abs(tape[2][1]).min()), min_abs_preactivation(tape[1]))
-    return min(min(float(np.abs(t[1]).min()) for t in tape[2]),
-               min(min_abs_preactivation(t) for t in tape[1]))
-
-
 class Grads:
     """Gradient accumulators.  Table gradients are kept per touched row; `mass` keeps, per row,
     the sum of the largest entries of its contributions (contributions of opposite sign cancel;

@@ -48,13 +48,20 @@ def tol_of(name, tol):
 
 class Case:
     def __init__(self, N, R, d, h, B, K, gamma, mix=None, seed=0, T=None, alpha=2.1, trees=None, pos=None,
-                 d_sem=0, schedule="level", b_max=0, score_bf16=False):
+                 d_sem=0, schedule="level", b_max=0, score_bf16=False, params_edit=None, exact_kinks=False):
         self.N, self.R, self.d, self.h, self.B, self.K, self.gamma = N, R, d, h, B, K, gamma
         self.d_sem = d_sem
+        # exact_kinks: inputs that sit exactly on a kink (a pre-activation or a coordinate difference
+        # that is 0.0 on both sides, two branches at bit-identical distance) are allowed: there the
+        # stated rules decide (relu'(0) = 0, sign(0) = 0, lowest branch) and both sides must follow
+        # them; the margins still apply to everything that is merely close to a kink
+        self.exact_kinks = exact_kinks
         self.score_bf16 = score_bf16                     # candidate rows from a bf16 copy of E
         self.schedule, self.b_max = schedule, b_max      # order of execution: values must not depend on it
         self.hp = dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, gamma=gamma)
         self.params = wl.make_params(N, R, d, h, seed + 3, d_sem=d_sem)
+        if params_edit is not None:
+            params_edit(self.params)
         self.sem_bits = wl.make_sem_features(N, d_sem, seed + 5) if d_sem else None
         if trees is not None:
             qb = wl.batch_from_trees(trees, pos)
@@ -66,7 +73,7 @@ class Case:
         negs = wl.make_negatives(N, qb.B, K, seed + 2)
         self.qb, self.negs, self.n_redrawn = keep_clear_of_kinks(qb, negs, self.params, gamma, N, want, seed + 4,
                                                                  strict=trees is None or B > 0, sem_bits=self.sem_bits,
-                                                                 score_bf16=score_bf16)
+                                                                 score_bf16=score_bf16, exact_kinks=exact_kinks)
         self.B = self.qb.B
 
     @classmethod
@@ -80,7 +87,7 @@ class Case:
         negs = wl.make_negatives(self.N, self.B, self.K, seed)
         _, negs, _ = keep_clear_of_kinks(self.qb, negs, self.params, self.gamma, self.N, self.B, seed + 1,
                                          strict=False, queries_are_clean=True, sem_bits=self.sem_bits,
-                                         score_bf16=self.score_bf16)
+                                         score_bf16=self.score_bf16, exact_kinks=self.exact_kinks)
         return negs
 
     def engine(self, num_streams=1):
@@ -104,10 +111,32 @@ class Case:
         return (M,) + om.batch_loss_and_grads(self.qb, self.negs if negs is None else negs, M)
 
 
+def min_abs_preactivation(tape, skip_zero=False):
+    """Smallest |pre-activation| of any hidden unit met while the oracle evaluated a tree (`tape`
+    is what oracle.model.forward returns beside the embedding): the distance of the evaluation
+    from a ReLU kink.  skip_zero: units whose pre-activation is exactly 0.0 do not count."""
+    def least(pre):
+        a = np.abs(pre)
+        if skip_zero:
+            a = a[a > 0.0]
+        return float(a.min()) if a.size else np.inf
+
+    kind = tape[0]
+    if kind == "e":
+        return np.inf
+    if kind == "p":
+        return min(least(tape[3][1]), min_abs_preactivation(tape[2], skip_zero))
+    if kind == "n":
+        return min(least(tape[2][1]), min_abs_preactivation(tape[1], skip_zero))
+    return min(min(least(t[1]) for t in tape[2]),
+               min(min_abs_preactivation(t, skip_zero) for t in tape[1]))
+
+
 def keep_clear_of_kinks(qb, negs, params, gamma, N, want, seed, strict=True, queries_are_clean=False,
-                        sem_bits=None, score_bf16=False):
+                        sem_bits=None, score_bf16=False, exact_kinks=False):
     """First `want` queries of qb that stay clear of every kink, with negatives
-    that sit on an |.| kink redrawn.  Uses the oracle's forward pass only."""
+    that sit on an |.| kink redrawn.  Uses the oracle's forward pass only.
+    exact_kinks: values exactly on a kink (0.0, or two equal branch distances) are let through."""
     M = om.Model(params, gamma, sem_bits, score_bf16)
     rng = np.random.default_rng(seed)
     negs = negs.copy()
@@ -117,13 +146,17 @@ def keep_clear_of_kinks(qb, negs, params, gamma, N, want, seed, strict=True, que
             break
         fw = [om.forward(b, M) for b in om.dnf(qb.tree(i))]
         Y = np.stack([y for y, _ in fw])
-        ok = min(om.min_abs_preactivation(t) for _, t in fw) >= TAU_PRE
+        ok = min(min_abs_preactivation(t, exact_kinks) for _, t in fw) >= TAU_PRE
 
         def clear(e):
             dist = np.abs(Y - M.candidate(e)[None]).sum(axis=1)
             w = int(np.argmin(dist))
-            tie = len(dist) > 1 and np.sort(dist)[1] - dist[w] < TAU_TIE
-            return (not tie) and np.abs(Y[w] - M.candidate(e)).min() >= TAU_ABS
+            gap = np.sort(dist)[1] - dist[w] if len(dist) > 1 else np.inf
+            tie = gap < TAU_TIE and not (exact_kinks and gap == 0.0)
+            diff = np.abs(Y[w] - M.candidate(e))
+            if exact_kinks:
+                diff = diff[diff > 0.0]
+            return (not tie) and (diff.size == 0 or diff.min() >= TAU_ABS)
 
         ok = queries_are_clean or (ok and clear(int(qb.pos[i])))
         if ok:
@@ -254,6 +287,72 @@ def _dense_grads_from_gpu(g, plan_export, shapes):
     return out
 
 
+def check_update(name, t, hp, lib_before, lib_after, g_own, ref_before, ref_after, gref, delta, tol=TOL,
+                 cancels=False, dense_floor=None, exclude=None):
+    """One tensor's optimiser step, two ways (see check_train_steps).  All arrays hold the compared
+    elements only (tables: the touched rows, in one order on both sides).
+    lib_before / lib_after: the library's (p, m, v), fp32; g_own: the library's own gradient;
+    ref_before / ref_after: the oracle's (p, m, v), fp64; gref: the oracle's gradient; delta: the
+    rounding level of gref per element (or per row, broadcast); exclude: elements (B) must leave
+    out for a reason the caller states.  Returns (kept, eligible) of (B)."""
+    b_p, b_m, b_v = lib_before
+    a_p, a_m, a_v = lib_after
+    ulp = np.spacing(np.abs(b_p).astype(np.float32)).astype(np.float64)
+    # (A) optimiser alone, all elements
+    wp, wm, wv = _adam_f64(b_p, b_m, b_v, g_own, t, hp)
+    upd = wp - b_p
+    err = np.abs(a_p - wp)
+    assert np.all(err <= tol * max(np.abs(upd).max(), 1e-300) + ulp), \
+        "%s: Adam on own gradients, worst %.3g" % (name, err.max())
+    assert_close(a_m, wm, "m(own g) " + name, tol)
+    assert_close(a_v, wv, "v(own g) " + name, tol)
+    # (B) end to end
+    if name == "u2":     # zero gradient in exact arithmetic: direction is rounding noise
+        return None
+    if dense_floor is not None and np.abs(gref).max() < dense_floor:
+        return None      # the same for a tensor at the noise floor (see dense_gradient_floor)
+    tol_b = tol_of(name, tol)
+    p0, m0, v0 = ref_before
+    hi = _adam_f64(p0, m0, v0, gref + delta, t, hp)[0]
+    lo = _adam_f64(p0, m0, v0, gref - delta, t, hp)[0]
+    upd_ref = ref_after[0] - p0
+    scale = np.abs(upd_ref).max()
+    keep = (np.abs(hi - lo) / 2 <= tol_b * scale)
+    # dead units (no gradient now, none before): identical input to Adam
+    keep |= (gref == 0.0) & (g_own == 0.0) & (m0 == 0.0) & (v0 == 0.0)
+    eligible = keep.size
+    if exclude is not None:
+        keep &= ~np.broadcast_to(exclude, keep.shape)
+        eligible -= int(np.broadcast_to(exclude, keep.shape).sum())
+    upd_gpu = a_p.astype(np.float64) - b_p.astype(np.float64)
+    err = np.abs(upd_gpu - upd_ref)
+    bound = tol_b * scale + ulp
+    assert np.all(err[keep] <= bound[keep]), \
+        "%s update: worst %.3g x bound" % (name, (err[keep] / bound[keep]).max())
+    # (a tensor whose terms largely cancel -- u1: the logit gradients of an intersection sum to
+    # zero over its inputs -- may keep fewer)
+    assert cancels or keep.sum() >= 0.3 * eligible, "%s: only %d of %d elements are well conditioned" % (
+        name, keep.sum(), eligible)
+    assert_close(a_m, ref_after[1], "m " + name, tol_b)
+    assert_close(a_v, ref_after[2], "v " + name, 2 * tol_b)
+    return int(keep.sum()), int(eligible)
+
+
+def gradient_noise(name):
+    """Rounding level of a gradient relative to the scale of its terms: bf16 for Wp (every term is
+    rounded to bf16, 2^-9 relative; the errors add in quadrature, and over the 4e5 elements of the
+    workload's Wp the largest of them is 4-5 standard deviations); else that of dL/ds =
+    sigmoid(s)-like, which inherits the absolute error of the fp32 score (sums of d terms of size
+    ~gamma: ~1e-5)."""
+    return 1e-2 if name == "Wp" else 1e-5
+
+
+def report_kept(kept, where):
+    """Names, per tensor, how much of it check (B) compared end to end."""
+    say("%s: update check (B) compared, of each tensor's elements: %s" % (
+        where, ", ".join("%s %.1f%%" % (n, 100.0 * k / max(a, 1)) for n, (k, a) in kept.items())))
+
+
 def check_train_steps(case, steps=3, num_streams=1, tol=TOL):
     """Updates over a few steps with fresh negatives, two ways.
 
@@ -266,7 +365,8 @@ def check_train_steps(case, steps=3, num_streams=1, tol=TOL):
         update moves by more than the tolerance when the reference gradient is
         perturbed by 1e-5 of the largest gradient entry of the tensor (for the tables: of
         the summed sizes of the row's contributions, which set the fp32 rounding level of
-        their sum) are left out of (B) and counted; (A) still covers them.
+        their sum) are left out of (B) and counted; (A) still covers them.  The share of
+        every tensor that (B) compared is printed.
     An fp32 parameter near 0.1 stores an update of 1e-4 only to half an ulp of the
     parameter, so one ulp of the parameter is added to both bounds.
     """
@@ -294,70 +394,38 @@ def check_train_steps(case, steps=3, num_streams=1, tol=TOL):
         if case.B:
             assert abs(float(loss.cpu()[0]) - ref_loss) <= tol * abs(ref_loss)
         assert eng.step_count() == t
+        kept = {}
         for name in P:
-            ulp = np.spacing(np.abs(b_p[name]).astype(np.float32)).astype(np.float64)
             rows = slice(None)
-            if name in ("E", "R"):
+            table = name in ("E", "R")
+            if table:
                 touched = np.zeros(shapes[name][0], bool)
                 touched[touched_gpu[name]] = True
                 assert sorted(G.rows[name]) == list(np.flatnonzero(touched)), name + " touched rows"
                 for bb, aa in ((b_p, a_p), (b_m, a_m), (b_v, a_v)):
                     assert np.array_equal(aa[name][~touched], bb[name][~touched]), name + " untouched rows moved"
                 rows = touched
-            # (A) optimiser alone, all elements
-            wp, wm, wv = _adam_f64(b_p[name][rows], b_m[name][rows], b_v[name][rows], g_gpu[name][rows], t, case.hp)
-            upd = wp - b_p[name][rows]
-            err = np.abs(a_p[name][rows] - wp)
-            assert np.all(err <= tol * max(np.abs(upd).max(), 1e-300) + ulp[rows]), \
-                "%s: Adam on own gradients, worst %.3g" % (name, err.max())
-            assert_close(a_m[name][rows], wm, "m(own g) " + name, tol)
-            assert_close(a_v[name][rows], wv, "v(own g) " + name, tol)
-            # (B) end to end
-            if name == "u2":     # zero gradient in exact arithmetic: direction is rounding noise
-                continue
-            if name not in ("E", "R") and np.abs(G.dense[name]).max() < dense_gradient_floor(G.dense):
-                continue         # the same for a tensor at the noise floor (see dense_gradient_floor)
-            tol_a, tol = tol, tol_of(name, tol)
-            gref = G.table_dense(name, shapes[name]) if name in ("E", "R") else G.dense[name]
-            m0, v0 = state_ref_before[name]
-            # rounding level of the gradient: bf16 for Wp; else that of dL/ds = sigmoid(s)-like, which
-            # inherits the absolute error of the fp32 score (sums of d terms of size ~gamma: ~1e-5)
-            # (Wp: every term is rounded to bf16, 2^-9 relative; the errors add in quadrature, and over the
-            # 4e5 elements of the workload's Wp the largest of them is 4-5 standard deviations)
-            noise = 1e-2 if name == "Wp" else 1e-5
-            if name in ("E", "R"):     # of a row sum: set by the sizes of its contributions (oracle Grads.mass)
+            gref = G.table_dense(name, shapes[name]) if table else G.dense[name]
+            if table:     # of a row sum: set by the sizes of its contributions (oracle Grads.mass)
                 mass = np.zeros((shapes[name][0], 1))
                 for i, v in G.mass[name].items():
                     mass[i, 0] = v
-                delta = noise * mass
-            else:                      # of a dense sum: independent errors of the terms add in quadrature
+                delta = gradient_noise(name) * mass[rows]
+                cancels = False
+            else:         # of a dense sum: independent errors of the terms add in quadrature
                 rms = np.sqrt(G.dense_sq[name])
-                delta = noise * np.maximum(rms, np.abs(gref).max() * 1e-3)
-            hi = _adam_f64(before_ref[name], m0, v0, gref + delta, t, case.hp)[0]
-            lo = _adam_f64(before_ref[name], m0, v0, gref - delta, t, case.hp)[0]
-            upd_ref = P[name] - before_ref[name]
-            scale = np.abs(upd_ref).max()
-            keep = (np.abs(hi - lo) / 2 <= tol * scale)
-            # dead units (no gradient now, none before): identical input to Adam
-            keep |= (gref == 0.0) & (g_gpu[name] == 0.0) & (m0 == 0.0) & (v0 == 0.0)
-            if name in ("E", "R"):
-                keep &= touched[:, None]
-                n_all = int(touched.sum()) * shapes[name][1]
-            else:
-                n_all = keep.size
-            upd_gpu = a_p[name].astype(np.float64) - b_p[name].astype(np.float64)
-            err = np.abs(upd_gpu - upd_ref)
-            bound = tol * scale + ulp
-            assert np.all(err[keep] <= bound[keep]), \
-                "%s update: worst %.3g x bound" % (name, (err[keep] / bound[keep]).max())
-            # (a tensor whose terms largely cancel -- u1: the logit gradients of an intersection sum to
-            # zero over its inputs -- may keep fewer)
-            cancels = name not in ("E", "R") and np.abs(gref).max() < 0.05 * np.sqrt(G.dense_sq[name]).max()
-            assert cancels or keep.sum() >= 0.3 * n_all, "%s: only %d of %d elements are well conditioned" % (
-                name, keep.sum(), n_all)
-            assert_close(a_m[name], state[name][0], "m " + name, tol)
-            assert_close(a_v[name], state[name][1], "v " + name, 2 * tol)
-            tol = tol_a
+                delta = gradient_noise(name) * np.maximum(rms, np.abs(gref).max() * 1e-3)
+                cancels = np.abs(gref).max() < 0.05 * rms.max()
+            m0, v0 = state_ref_before[name]
+            res = check_update(name, t, case.hp, (b_p[name][rows], b_m[name][rows], b_v[name][rows]),
+                               (a_p[name][rows], a_m[name][rows], a_v[name][rows]), g_gpu[name][rows],
+                               (before_ref[name][rows], m0[rows], v0[rows]),
+                               (P[name][rows], state[name][0][rows], state[name][1][rows]), gref[rows], delta,
+                               tol=tol, cancels=cancels,
+                               dense_floor=None if table else dense_gradient_floor(G.dense))
+            if res is not None:
+                kept[name] = res
+        report_kept(kept, "step %d" % t)
     plan.free()
     return eng
 
@@ -422,6 +490,7 @@ def check_filtered_ranks(case, seed, n_check=None):
         hi = 1 + np.searchsorted(d_other, d_ref * (1 + 1e-5), side="left")
         assert np.all((lo <= got) & (got <= hi)), "q%d: %r vs %r" % (q, got, want)   # exact wherever lo == hi
         exact += int(np.sum(got == want))
+    say("filtered ranks: %d of %d equal to the oracle's exactly, the rest inside its fp32 band" % (exact, len(flat)))
     assert exact >= 0.8 * len(flat)      # (in a table of 150 000 rows distances are denser than fp32 resolves)
     # the metric kernel against the oracle's formula on the same ranks, scored prefixes only
     want_m = orank.ranking_metrics([ranks[off[q]:off[q] + n_take[q]] for q in range(B)], ks=(1, 3, 10))

@@ -12,6 +12,8 @@ def _gemm_case(M, N, K, a_k, b_k, seed, epilogue, arith=0):
     A = rng.standard_normal((M, K)).astype(np.float32)
     B = rng.standard_normal((K, N)).astype(np.float32)
     want = A.astype(np.float64) @ B.astype(np.float64)
+    # what bounds the error of every single output element: the sizes of its own terms
+    scale = np.abs(A).astype(np.float64) @ np.abs(B).astype(np.float64)
     At = torch.from_numpy(np.ascontiguousarray(A if a_k else A.T)).cuda()      # [M,K] or [K,M]
     Bt = torch.from_numpy(np.ascontiguousarray(B.T if b_k else B)).cuda()      # [N,K] or [K,N]
     kw = {}
@@ -23,16 +25,33 @@ def _gemm_case(M, N, K, a_k, b_k, seed, epilogue, arith=0):
         perm = rng.permutation(M + 5)[:M].astype(np.int32)
         want = np.maximum(want + bias, 0.0)
         want = np.where(mask > 0, want, 0.0) + addend
+        scale = scale + np.abs(bias)[None, :] + np.abs(addend)
         full = np.zeros((M + 5, N))
         full[perm] = want
         want = full
+        full = np.ones((M + 5, N))             # rows the kernel must leave untouched: exactly zero
+        full[perm] = scale
+        scale = full
         out_rows = M + 5
         kw = dict(bias=torch.from_numpy(bias).cuda(), relu=True, mask=torch.from_numpy(mask).cuda(),
                   addend=torch.from_numpy(addend).cuda(), dst_row=torch.from_numpy(perm).cuda())
     got = binding.debug_gemm(At, Bt, M, N, K, a_kcontig=a_k, b_kcontig=b_k, out_rows=out_rows, arith=arith,
                              **kw).cpu().numpy()
+    # element by element against the sum of |a||b| of that element (an error confined to a few
+    # elements of a ragged edge tile cannot hide behind the largest entry of the matrix), and,
+    # as before, against the largest entry
+    bound = 2e-6 * max(1.0, np.sqrt(K) / 8)
+    # (rounding errors of the K accumulation steps are relative to partial sums, which stay far
+    # below the sum of the absolute terms: a tenth of the matrix-wide bound)
+    worst = (np.abs(got - want) / scale).max()
+    assert worst < 0.1 * bound, (M, N, K, a_k, b_k, epilogue, arith, "per element", worst)
+    if epilogue:
+        untouched = np.ones(M + 5, bool)
+        untouched[perm] = False
+        assert not np.any(got[untouched]), "rows outside dst_row were written"
     err = np.abs(got - want).max() / np.abs(want).max()
-    assert err < 2e-6 * max(1.0, np.sqrt(K) / 8), (M, N, K, a_k, b_k, epilogue, arith, err)
+    assert err < bound, (M, N, K, a_k, b_k, epilogue, arith, err)
+    return worst
 
 
 @pytest.mark.parametrize("layout", [(True, True), (True, False), (False, False)])
@@ -51,9 +70,11 @@ def test_contraction_kernel_all_layouts_and_tile_paths(layout):
         print("[case] gemm", M, N, K, layout, flush=True)
         # the arithmetic the training step takes for this layout and size, fp32 matrix
         # instructions, and operands split into bf16 pieces: all to the same bound
+        worst = 0.0
         for arith in (0, 1, 2):
-            _gemm_case(M, N, K, a_k, b_k, seed=i, epilogue=False, arith=arith)
-            _gemm_case(M, N, K, a_k, b_k, seed=100 + i, epilogue=True, arith=arith)
+            worst = max(worst, _gemm_case(M, N, K, a_k, b_k, seed=i, epilogue=False, arith=arith))
+            worst = max(worst, _gemm_case(M, N, K, a_k, b_k, seed=100 + i, epilogue=True, arith=arith))
+        print("       worst element error / sum |a||b|: %.2e" % worst, flush=True)
 
 
 def test_split_contraction_keeps_fp32_accuracy_where_bf16_alone_would_not():
