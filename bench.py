@@ -199,6 +199,57 @@ def rank_bench(args, cfg, kg, params, sem_bits, box=False):
     print(json.dumps(out))
 
 
+def calibrate_hbm(args):
+    """What this machine delivers for the access patterns of the step's memory-bound kernels, without
+    their arithmetic (ngdb_debug_stream): plain copy / read / write of 4 GiB, the scoring kernel's
+    gather (B*(K+1) random rows of d floats out of an N-row table) and the table kernel's update
+    (the rows of three N-row tables that a step touches, in ascending order).  Shapes of --config.
+    Prints ONE JSON line; every figure is bytes moved / HIP-event time of 5 launches."""
+    import torch
+    from paper_2602_21597_amd import binding as nb
+    cfg = wl.get_config(args.config)
+    rng = np.random.default_rng(7)
+    dev = torch.device("cuda:0")
+    big = 1 << 32
+    src = torch.empty(big, dtype=torch.uint8, device=dev)
+    dst = torch.empty(big, dtype=torch.uint8, device=dev)
+    src.zero_(); dst.zero_()
+    sink = torch.zeros(4, dtype=torch.float32, device=dev)
+    table = torch.zeros((3, cfg.N, cfg.d), dtype=torch.float32, device=dev)
+    n_pairs = cfg.B * (cfg.K + 1)
+    gather_rows = torch.from_numpy(rng.integers(0, cfg.N, n_pairs, dtype=np.int32)).to(dev)
+    touched = np.unique(np.concatenate([gather_rows.cpu().numpy(), rng.integers(0, cfg.N, 2 * cfg.B, dtype=np.int32)]))
+    upd_rows = torch.from_numpy(touched.astype(np.int32)).to(dev)
+    row = 4 * cfg.d
+    cases = [
+        ("copy", lambda: nb.debug_stream(nb.STREAM_COPY, dst, src), 2 * big),
+        ("read", lambda: nb.debug_stream(nb.STREAM_READ, sink, src), big),
+        ("write", lambda: nb.debug_stream(nb.STREAM_WRITE, dst), big),
+        ("gather_rows", lambda: nb.debug_stream(nb.STREAM_GATHER, sink, table[0], gather_rows, cfg.d), n_pairs * row),
+        ("update_rows", lambda: nb.debug_stream(nb.STREAM_UPDATE, table, None, upd_rows, cfg.d,
+                                                nbytes=table.numel() * 4), len(touched) * 6 * row),
+        ("copy_nontemporal", lambda: nb.debug_stream(nb.STREAM_COPY_NT, dst, src), 2 * big),
+        ("update_rows_nontemporal", lambda: nb.debug_stream(nb.STREAM_UPDATE_NT, table, None, upd_rows, cfg.d,
+                                                            nbytes=table.numel() * 4), len(touched) * 6 * row),
+    ]
+    out = {"calibration": "HBM access patterns at the shapes of configs[%d] %s: N=%d d=%d, %d gathered rows, %d updated rows"
+                          % (cfg.index, cfg.name, cfg.N, cfg.d, n_pairs, len(touched)), "peak_GBs": HBM_PEAK_GBS}
+    for name, fn, nbytes in cases:
+        fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(5):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        gbs = 5 * nbytes / (a.elapsed_time(b) * 1e-3) / 1e9
+        out[name] = {"GBs": gbs, "frac_of_peak": gbs / HBM_PEAK_GBS, "bytes_per_launch": nbytes,
+                     "ms_per_launch": a.elapsed_time(b) / 5}
+        say("%s: %.0f GB/s" % (name, gbs))
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -226,11 +277,16 @@ def main():
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="also run the library's plain copy kernel on this many MiB, 5 times (reference "
                          "for scaling rocprofv3 traffic counters)")
+    ap.add_argument("--calibrate-hbm", action="store_true",
+                    help="instead of the step: plain copy / read / write and the row gather and row update "
+                         "patterns of the scoring and table kernels at the shapes of --config (no arithmetic)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus %d is not supported (no sharding, no collectives)"
               % args.gpus, file=sys.stderr)
         sys.exit(2)
+    if args.calibrate_hbm:
+        return calibrate_hbm(args)
 
     cfg = wl.get_config(args.config)
     box = args.family == "box"

@@ -372,6 +372,30 @@ int ngdb_debug_gemm(const float* A, const float* B, float* C, int32_t M, int32_t
  * counters and for the copy bandwidth of the machine.                           */
 int ngdb_debug_copy(void* d_dst, const void* d_src, size_t bytes, void* stream);
 
+/* Plain access patterns of the step's memory-bound kernels without their arithmetic, to measure
+ * what the machine delivers for each (all pointers device; every call moves what it says once):
+ *   NGDB_STREAM_COPY    d_dst[0..bytes) = d_src[0..bytes)                       (ngdb_debug_copy)
+ *   NGDB_STREAM_READ    reads d_src[0..bytes); d_dst: 4 bytes, left untouched
+ *   NGDB_STREAM_WRITE   writes d_dst[0..bytes)
+ *   NGDB_STREAM_GATHER  reads row d_rows[i], i < n_rows, of the fp32 table d_src [*, row_floats], one
+ *                       wavefront per row with the next row requested ahead (the scoring kernel's
+ *                       candidate gather); d_dst: 4 bytes, left untouched; bytes ignored
+ *   NGDB_STREAM_UPDATE  d_dst holds three fp32 tables [bytes/12/row_floats, row_floats] one after the
+ *                       other; row d_rows[i] of each is read and written back (+1), one wavefront
+ *                       per row (the table kernel's parameter / moment traffic)
+ *   NGDB_STREAM_COPY_NT / NGDB_STREAM_UPDATE_NT   the same two with non-temporal loads and stores
+ * bytes a multiple of 16; row_floats a multiple of 4, at most 1024; row ids are the caller's
+ * responsibility.                                                                          */
+#define NGDB_STREAM_COPY   0
+#define NGDB_STREAM_READ   1
+#define NGDB_STREAM_WRITE  2
+#define NGDB_STREAM_GATHER 3
+#define NGDB_STREAM_UPDATE 4
+#define NGDB_STREAM_COPY_NT   5
+#define NGDB_STREAM_UPDATE_NT 6
+int ngdb_debug_stream(int32_t mode, void* d_dst, const void* d_src, size_t bytes, const int32_t* d_rows,
+                      int64_t n_rows, int32_t row_floats, void* stream);
+
 /* Kernel timing with HIP events recorded on the stream each kernel is launched
  * on.  Classes whose bit is set in class_mask are bracketed by an event pair at
  * every launch (NGDB_TK_INDEX brackets the whole index build); everything else
@@ -392,6 +416,13 @@ int ngdb_debug_copy(void* d_dst, const void* d_src, size_t bytes, void* stream);
 typedef struct ngdb_timing {
     double ms[NGDB_TK_COUNT];         /* summed elapsed time per class             */
     int64_t brackets[NGDB_TK_COUNT];  /* number of event pairs per class           */
+    /* The contraction launches of a class (GEMM_FWD, GEMM_BWD, WGRAD), by the matrix instructions
+     * they ran on: [.][0] fp32 instructions; [.][1] bf16 instructions on operands split into three
+     * pieces, which execute six bf16 products per fp32 product.  route_flop counts algorithmic work,
+     * 2*M*N*K per contraction.                                                              */
+    double route_ms[NGDB_TK_COUNT][2];
+    int64_t route_launches[NGDB_TK_COUNT][2];
+    double route_flop[NGDB_TK_COUNT][2];
 } ngdb_timing;
 int ngdb_set_timing(ngdb_ctx_t* ctx, uint32_t class_mask);
 int ngdb_get_timing(ngdb_ctx_t* ctx, ngdb_timing* out, int reset);

@@ -76,7 +76,8 @@ TIMING_CLASSES = ("index", "sem", "gemm_fwd", "inter", "score", "gemm_bwd", "wgr
 
 
 class Timing(C.Structure):
-    _fields_ = [("ms", C.c_double * 10), ("brackets", C.c_int64 * 10)]
+    _fields_ = [("ms", C.c_double * 10), ("brackets", C.c_int64 * 10), ("route_ms", (C.c_double * 2) * 10),
+                ("route_launches", (C.c_int64 * 2) * 10), ("route_flop", (C.c_double * 2) * 10)]
 
 
 def load_library(path=LIB_PATH):
@@ -106,6 +107,7 @@ def load_library(path=LIB_PATH):
         "ngdb_debug_gemm": (C.c_int, [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, i32, vp, i32, vp, i32,
                                       vp, i32, vp]),
         "ngdb_debug_copy": (C.c_int, [vp, vp, C.c_size_t, vp]),
+        "ngdb_debug_stream": (C.c_int, [i32, vp, vp, C.c_size_t, vp, i64, i32, vp]),
         "ngdb_set_timing": (C.c_int, [vp, C.c_uint32]),
         "ngdb_get_timing": (C.c_int, [vp, C.POINTER(Timing), C.c_int]),
         "ngdb_copy_to_host": (C.c_int, [vp, vp, C.c_size_t]),
@@ -225,6 +227,22 @@ def debug_copy(dst, src):
     nbytes = src.numel() * src.element_size()
     _check(lib().ngdb_debug_copy(dst.data_ptr(), src.data_ptr(), nbytes,
                                  C.c_void_p(torch.cuda.current_stream().cuda_stream)), None)
+    return nbytes
+
+
+STREAM_COPY, STREAM_READ, STREAM_WRITE, STREAM_GATHER, STREAM_UPDATE, STREAM_COPY_NT, STREAM_UPDATE_NT = range(7)
+
+
+def debug_stream(mode, dst, src=None, rows=None, row_floats=0, nbytes=None):
+    """One launch of a calibration access pattern (ngdb_debug_stream) on torch device tensors."""
+    import torch
+    if nbytes is None:
+        ref = src if mode in (STREAM_COPY, STREAM_READ, STREAM_COPY_NT) else dst
+        nbytes = ref.numel() * ref.element_size()
+    _check(lib().ngdb_debug_stream(int(mode), dst.data_ptr(), src.data_ptr() if src is not None else None, int(nbytes),
+                                   rows.data_ptr() if rows is not None else None,
+                                   int(rows.numel()) if rows is not None else 0, int(row_floats),
+                                   C.c_void_p(torch.cuda.current_stream().cuda_stream)), None)
     return nbytes
 
 
@@ -461,6 +479,9 @@ class Engine:
         """{class: (total ms, number of brackets)} since the last reset (waits for the device)."""
         t = Timing()
         _check(lib().ngdb_get_timing(self.ctx, C.byref(t), 1 if reset else 0), self.ctx)
+        self.last_routes = {n: {r: (t.route_ms[i][k], int(t.route_launches[i][k]), t.route_flop[i][k])
+                                for k, r in enumerate(("fp32", "bf16_split"))}
+                            for i, n in enumerate(TIMING_CLASSES)}
         return {n: (t.ms[i], int(t.brackets[i])) for i, n in enumerate(TIMING_CLASSES)}
 
     def n_touched_entities(self):

@@ -94,7 +94,7 @@ struct ngdb_ctx_s {
     std::mutex mu;                       // guards blob_pool, live_plans and err: planning may run on a second host thread
     // kernel timing
     uint32_t timing_mask = 0;
-    struct Bracket { int cls; hipEvent_t a, b; };
+    struct Bracket { int cls; hipEvent_t a, b; int route; double flop; };
     std::vector<Bracket> brackets;
     std::vector<hipEvent_t> spare_events;
     ngdb_timing timing{};
@@ -144,10 +144,19 @@ struct Timed {
         b = take_event(c);
         if (!a || !b) { b = nullptr; return; }
         (void)hipEventRecord(a, s);
-        c->brackets.push_back({cls, a, b});
+        c->brackets.push_back({cls, a, b, -1, 0.0});
+    }
+    // a contraction launch: the instructions it ran on and its algorithmic work
+    void work(int route, double flop) {
+        if (!b) return;
+        c->brackets.back().route = route == GEMM_SPLIT ? 1 : 0;
+        c->brackets.back().flop = flop;
     }
     ~Timed() { if (b) (void)hipEventRecord(b, s); }
 };
+
+// One grouped contraction launch, bracketed as class `cls`.
+int gemm_timed(ngdb_ctx_t* c, int cls, const GemmArgs* g, int n, hipStream_t s);
 
 int ensure(ngdb_ctx_t* c, DevBuf& b, size_t bytes) {
     if (bytes <= b.cap) return NGDB_OK;
@@ -170,6 +179,17 @@ void release(DevBuf& b) {
 
 template <class T>
 T* ptr(const DevBuf& b) { return static_cast<T*>(b.p); }
+
+int gemm_timed(ngdb_ctx_t* c, int cls, const GemmArgs* g, int n, hipStream_t s) {
+    Timed tm(c, cls, s);
+    int route = GEMM_FP32;
+    HIPCHK(c, launch_gemm_group(g, n, s, &route));
+    double flop = 0.0;
+    for (int i = 0; i < n; ++i)
+        if (g[i].M > 0 && g[i].N > 0) flop += 2.0 * g[i].M * g[i].N * g[i].K;
+    tm.work(route, flop);
+    return NGDB_OK;
+}
 
 struct MlpRefs {
     const float *Wa, *ba, *Wb, *bb;
@@ -396,8 +416,9 @@ int enqueue_forward_box(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t s) {
             }
         }
         if (n == 0) continue;
-        { Timed tm(c, NGDB_TK_GEMM_FWD, s); HIPCHK(c, launch_gemm_group(g1, n, s)); }
-        { Timed tm(c, NGDB_TK_GEMM_FWD, s); HIPCHK(c, launch_gemm_group(g2, n, s)); }
+        int rc_g;
+        if ((rc_g = gemm_timed(c, NGDB_TK_GEMM_FWD, g1, n, s)) != NGDB_OK) return rc_g;
+        if ((rc_g = gemm_timed(c, NGDB_TK_GEMM_FWD, g2, n, s)) != NGDB_OK) return rc_g;
         for (const Segment& sg : segs) {
             if (sg.type != T_INTER) continue;
             Timed tm(c, NGDB_TK_INTER, s);
@@ -420,10 +441,23 @@ int enqueue_forward_box(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t s) {
     return NGDB_OK;
 }
 
-// forward over the plan's frontiers; results in c->act.  The type segments of one
+// Device memory the forward pass of the vector family writes: operator outputs by slot, and per
+// type the gathered first-layer inputs, the hidden rows and (intersections) the logits.
+struct FwdSpace {
+    float* act;
+    float* Z[3];
+    float* H[3];
+    float* Att;
+};
+FwdSpace ctx_space(const ngdb_ctx_t* c) {
+    return FwdSpace{ptr<float>(c->act), {ptr<float>(c->Z[0]), ptr<float>(c->Z[1]), ptr<float>(c->Z[2])},
+                    {ptr<float>(c->H[0]), ptr<float>(c->H[1]), ptr<float>(c->H[2])}, ptr<float>(c->Att)};
+}
+
+// forward over the plan's frontiers; results in w.act.  The type segments of one
 // depth are independent: they share one grouped launch per MLP layer.
-int enqueue_forward(ngdb_ctx_t* c, const ngdb_plan_t* pl, const EntRows& er, hipStream_t s) {
-    if (c->cfg.family == NGDB_FAMILY_BOX) return enqueue_forward_box(c, pl, s);
+int enqueue_forward(ngdb_ctx_t* c, const ngdb_plan_t* pl, const EntRows& er, hipStream_t s, const FwdSpace& w) {
+    if (c->cfg.family == NGDB_FAMILY_BOX) return enqueue_forward_box(c, pl, s);   // (always on the context's buffers)
     const int d = c->cfg.d, h = c->cfg.h;
     for (int l = 1; l <= pl->hp.n_levels; ++l) {
         const std::vector<Segment>& segs = pl->levels[l];
@@ -431,22 +465,22 @@ int enqueue_forward(ngdb_ctx_t* c, const ngdb_plan_t* pl, const EntRows& er, hip
         int n = 0;
         for (const Segment& sg : segs) {
             const MlpRefs W = mlp_of(c->prm, sg.type);
-            float* Z = ptr<float>(c->Z[sg.type]) + (size_t)sg.mlp_base * d;
-            float* Hh = ptr<float>(c->H[sg.type]) + (size_t)sg.mlp_base * h;
+            float* Z = w.Z[sg.type] + (size_t)sg.mlp_base * d;
+            float* Hh = w.H[sg.type] + (size_t)sg.mlp_base * h;
             GemmArgs& a = g1[n];
             // first layer reads its rows through the plan's references and leaves a copy in Z
-            a.a_ref = er.refs + sg.ref_off; a.a_base0 = ptr<float>(c->act); a.a_base1 = er.rows;
+            a.a_ref = er.refs + sg.ref_off; a.a_base0 = w.act; a.a_base1 = er.rows;
             if (sg.rel_off >= 0) { a.a_add_idx = pl->d_rel + sg.rel_off; a.a_add = c->prm.R.p; }
             a.a_copy = Z; a.lda = d; a.B = W.Wa; a.ldb = d; a.C = Hh; a.ldc = h;
             a.M = sg.rows; a.N = h; a.K = d; a.bias = W.ba; a.relu = true;
             GemmArgs& b = g2[n];
             b.A = Hh; b.lda = h; b.B = W.Wb; b.ldb = h; b.M = sg.rows; b.N = d; b.K = h; b.bias = W.bb; b.ldc = d;
-            b.C = sg.type == T_INTER ? ptr<float>(c->Att) + (size_t)sg.mlp_base * d
-                                     : ptr<float>(c->act) + (size_t)sg.out_base * d;
+            b.C = sg.type == T_INTER ? w.Att + (size_t)sg.mlp_base * d : w.act + (size_t)sg.out_base * d;
             ++n;
         }
-        { Timed tm(c, NGDB_TK_GEMM_FWD, s); HIPCHK(c, launch_gemm_group(g1, n, s)); }
-        { Timed tm(c, NGDB_TK_GEMM_FWD, s); HIPCHK(c, launch_gemm_group(g2, n, s)); }
+        int rc_g;
+        if ((rc_g = gemm_timed(c, NGDB_TK_GEMM_FWD, g1, n, s)) != NGDB_OK) return rc_g;
+        if ((rc_g = gemm_timed(c, NGDB_TK_GEMM_FWD, g2, n, s)) != NGDB_OK) return rc_g;
         for (const Segment& sg : segs) {
             if (sg.type != T_INTER) continue;
             Timed tm(c, NGDB_TK_INTER, s);
@@ -456,8 +490,8 @@ int enqueue_forward(ngdb_ctx_t* c, const ngdb_plan_t* pl, const EntRows& er, hip
                 const size_t mb = (size_t)pl->hp.g_mlp_base[g] * d;
                 if (ij.count == INTER_MAX_JOBS) return fail(c, NGDB_ERR_UNSUPPORTED, "too many intersection classes in one level");
                 InterJob& jb = ij.job[ij.count++];
-                jb.X = ptr<float>(c->Z[T_INTER]) + mb; jb.Att = ptr<float>(c->Att) + mb;
-                jb.out = ptr<float>(c->act) + (size_t)pl->hp.g_out_base[g] * d;
+                jb.X = w.Z[T_INTER] + mb; jb.Att = w.Att + mb;
+                jb.out = w.act + (size_t)pl->hp.g_out_base[g] * d;
                 jb.n = pl->hp.g_n[g]; jb.k = pl->hp.g_nin[g];
             }
             HIPCHK(c, launch_inter(ij, false, s));
@@ -502,7 +536,13 @@ int enqueue_weight_grads(ngdb_ctx_t* c, const WgradJob& wj, hipStream_t s, Colsu
         cs.job[cs.count++] = ColsumJob{dY[i], gW + c->gw_off[gs + 3], part + (size_t)COLSUM_MAX_CHUNKS * std::max(d, h),
                                        r, d, d, 0, 0};
     }
-    HIPCHK(c, launch_gemm_group(w, 2 * nt, s));
+    {
+        int route = GEMM_FP32;
+        HIPCHK(c, launch_gemm_group(w, 2 * nt, s, &route));
+        double flop = 0.0;
+        for (int i = 0; i < 2 * nt; ++i) flop += 2.0 * w[i].M * w[i].N * w[i].K;
+        tm.work(route, flop);
+    }
     HIPCHK(c, launch_colsums(cs, s, open == nullptr));
     if (open) *open = cs;
     return NGDB_OK;
@@ -553,8 +593,9 @@ int enqueue_backward(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t s, WgradJ
             y.addend = addend; y.ldadd = d; y.dst_row = pl->d_in_gslot + sg.ref_off;
             ++n;
         }
-        { Timed tm(c, NGDB_TK_GEMM_BWD, s); HIPCHK(c, launch_gemm_group(b2, n, s)); }
-        { Timed tm(c, NGDB_TK_GEMM_BWD, s); HIPCHK(c, launch_gemm_group(b1, n, s)); }
+        int rc_g;
+        if ((rc_g = gemm_timed(c, NGDB_TK_GEMM_BWD, b2, n, s)) != NGDB_OK) return rc_g;
+        if ((rc_g = gemm_timed(c, NGDB_TK_GEMM_BWD, b1, n, s)) != NGDB_OK) return rc_g;
     }
     // weight gradients: one contraction per tensor over all rows of the type
     wj->nt = 3;
@@ -618,8 +659,9 @@ int enqueue_backward_box(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t s, Wg
             }
         }
         if (n == 0) continue;
-        { Timed tm(c, NGDB_TK_GEMM_BWD, s); HIPCHK(c, launch_gemm_group(b2, n, s)); }
-        { Timed tm(c, NGDB_TK_GEMM_BWD, s); HIPCHK(c, launch_gemm_group(b1, n, s)); }
+        int rc_g;
+        if ((rc_g = gemm_timed(c, NGDB_TK_GEMM_BWD, b2, n, s)) != NGDB_OK) return rc_g;
+        if ((rc_g = gemm_timed(c, NGDB_TK_GEMM_BWD, b1, n, s)) != NGDB_OK) return rc_g;
     }
     wj->nt = 2;
     wj->types[0] = T_INTER; wj->types[1] = T_NEG;
@@ -660,7 +702,7 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
     if (rc != NGDB_OK) return rc;
 
     // 2. forward frontiers
-    rc = enqueue_forward(c, pl, er, stream);
+    rc = enqueue_forward(c, pl, er, stream, ctx_space(c));
     if (rc != NGDB_OK) return rc;
 
     // 3. scores, loss terms, dL/ds, gradients of the branch embeddings
@@ -707,6 +749,8 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
     te.dact = ptr<float>(c->dact); te.act = ptr<float>(c->act); te.g_out = apply ? nullptr : ptr<float>(c->gE);
     if (sem) { te.mask = c->mask.p; te.g_bf16 = ptr<uint16_t>(c->g_bf16); }
     TableArgs tr = te;
+    // parameters + two moments beyond what the 256 MB last-level cache could keep between steps
+    te.streaming = (size_t)c->cfg.n_entities * d * 3 * sizeof(float) > ((size_t)512 << 20);
     if (c->cfg.score_bf16) te.shadow = ptr<uint16_t>(c->Eb);   // signs against the rounded rows; written only when updating
     if (box) { te.off = ptr<float>(c->off); te.alpha = c->cfg.box_alpha; }
     tr.g_bf16 = nullptr; tr.mask = nullptr;
@@ -1121,7 +1165,7 @@ int ngdb_score(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_cand, int3
         rc = prepare_entities(c, pl, d_cand, d_cand ? (int64_t)pl->hp.n_queries * C : 0, s, s, &e_src, &er);
         if (rc != NGDB_OK) return rc;
     }
-    rc = enqueue_forward(c, pl, er, s);
+    rc = enqueue_forward(c, pl, er, s, ctx_space(c));
     if (rc != NGDB_OK) return rc;
     if (d_cand) {
         ScoreArgs sa{};
@@ -1188,7 +1232,7 @@ int ngdb_rank_answers(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_ans
         rc = prepare_entities(c, pl, nullptr, 0, s, s, &e_src, &er);
         if (rc != NGDB_OK) return rc;
     }
-    rc = enqueue_forward(c, pl, er, s);
+    rc = enqueue_forward(c, pl, er, s, ctx_space(c));
     if (rc != NGDB_OK) return rc;
     if (n_ans > 0) {
         const int N = c->cfg.n_entities, d = c->cfg.d, R = pl->hp.n_roots, B = pl->hp.n_queries;
@@ -1270,6 +1314,14 @@ int ngdb_debug_copy(void* d_dst, const void* d_src, size_t bytes, void* stream) 
     return e == hipSuccess ? NGDB_OK : (e == hipErrorInvalidValue ? NGDB_ERR_ARG : NGDB_ERR_HIP);
 }
 
+int ngdb_debug_stream(int32_t mode, void* d_dst, const void* d_src, size_t bytes, const int32_t* d_rows, int64_t n_rows,
+                      int32_t row_floats, void* stream) {
+    if (!d_dst || (mode != NGDB_STREAM_WRITE && mode != NGDB_STREAM_UPDATE && mode != NGDB_STREAM_UPDATE_NT && !d_src)) return NGDB_ERR_ARG;
+    const hipError_t e = launch_stream_pattern(mode, d_dst, d_src, bytes, d_rows, n_rows, row_floats,
+                                               static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? NGDB_OK : (e == hipErrorInvalidValue ? NGDB_ERR_ARG : NGDB_ERR_HIP);
+}
+
 int ngdb_set_timing(ngdb_ctx_t* c, uint32_t class_mask) {
     if (!c) return NGDB_ERR_ARG;
     c->timing_mask = class_mask & ((1u << NGDB_TK_COUNT) - 1u);
@@ -1284,6 +1336,11 @@ int ngdb_get_timing(ngdb_ctx_t* c, ngdb_timing* out, int reset) {
         if (hipEventElapsedTime(&ms, b.a, b.b) == hipSuccess) {
             c->timing.ms[b.cls] += ms;
             c->timing.brackets[b.cls] += 1;
+            if (b.route >= 0) {
+                c->timing.route_ms[b.cls][b.route] += ms;
+                c->timing.route_launches[b.cls][b.route] += 1;
+                c->timing.route_flop[b.cls][b.route] += b.flop;
+            }
         }
         c->spare_events.push_back(b.a);
         c->spare_events.push_back(b.b);

@@ -34,6 +34,48 @@ __device__ __forceinline__ float4 bf16x4_to_f32(uint2 v) {
     return make_float4(__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xFFFF0000u), __uint_as_float(v.y << 16),
                        __uint_as_float(v.y & 0xFFFF0000u));
 }
+// Sum over the 64 lanes of a wavefront on the vector ALU alone (data-parallel primitives: adds inside
+// quads, inside rows of 16 lanes, then across the four rows through row broadcasts), returned in
+// every lane.  No LDS round trips: a chain of six ds_bpermute exchanges costs several hundred
+// cycles of latency per sum.  Fixed summation order.
+__device__ __forceinline__ float wave_sum_dpp(float v) {
+#define NGDB_DPP_ADD(ctrl, rows)                                                                        \
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), ctrl, rows, 0xf, false))
+    NGDB_DPP_ADD(0xB1, 0xf);    // quad_perm [1,0,3,2]: lane ^ 1
+    NGDB_DPP_ADD(0x4E, 0xf);    // quad_perm [2,3,0,1]: lane ^ 2
+    NGDB_DPP_ADD(0x141, 0xf);   // row_half_mirror: the other quad of the half row
+    NGDB_DPP_ADD(0x140, 0xf);   // row_mirror: the other half row -> every lane holds its row's sum
+    NGDB_DPP_ADD(0x142, 0xa);   // row_bcast15 into rows 1 and 3: sums of rows 0+1 and 2+3
+    NGDB_DPP_ADD(0x143, 0xc);   // row_bcast31 into rows 2 and 3: row 3 holds the total
+#undef NGDB_DPP_ADD
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
+// The value lane `l` holds, for an l that is the same in all lanes: a register read, where a
+// shuffle with a per-lane index would go through LDS hardware.
+__device__ __forceinline__ int32_t lane_value(int32_t v, int l) {
+    return __builtin_amdgcn_readlane(v, __builtin_amdgcn_readfirstlane(l));
+}
+__device__ __forceinline__ float lane_value(float v, int l) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), __builtin_amdgcn_readfirstlane(l)));
+}
+// Hardware transcendental approximations (about 1 ulp each; the results they feed are held to 1e-4).
+__device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
+__device__ __forceinline__ float fast_sqrt(float x) { return __builtin_amdgcn_sqrtf(x); }
+// exp(-a) for a >= 0
+__device__ __forceinline__ float fast_exp_neg(float a) { return __builtin_amdgcn_exp2f(a * -1.44269504088896341f); }
+// log(1 + e) for 0 <= e <= 1: the series where 1 + e would lose e's bits, else the hardware logarithm
+__device__ __forceinline__ float fast_log1p_unit(float e) {
+    const float series = e * (1.f - e * (0.5f - e * (1.f / 3.f)));
+    const float direct = __builtin_amdgcn_logf(1.f + e) * 0.693147180559945309f;
+    return e < 0.01f ? series : direct;
+}
+// sign(x) as -1, 0 or +1 in two instructions and without the condition register: x scaled by 2^252
+// is 0 for 0, at least 2^103 in size for every other finite x (denormals included), or infinite;
+// clamped to [-1, 1].  c * sign(x) then fuses into the accumulating multiply-add.
+__device__ __forceinline__ float sign_unit(float x) {
+    return __builtin_amdgcn_fmed3f(__builtin_ldexpf(x, 252), -1.f, 1.f);
+}
+__device__ __forceinline__ float signed_by(float c, float x) { return c * sign_unit(x); }
 // log(1+exp(x)) and 1/(1+exp(-x)) without overflow
 __device__ __forceinline__ float softplus_f(float x) { return fmaxf(x, 0.f) + log1pf(expf(-fabsf(x))); }
 __device__ __forceinline__ float sigmoid_f(float x) {
@@ -88,7 +130,8 @@ struct GemmGroup {
     int tile_start[GEMM_MAX_GROUP + 1];   // first workgroup of every problem
     GemmArgs p[GEMM_MAX_GROUP];
 };
-hipError_t launch_gemm_group(const GemmArgs* problems, int count, hipStream_t s);
+// *route (if given) receives the arithmetic the launch used: GEMM_FP32 or GEMM_SPLIT.
+hipError_t launch_gemm_group(const GemmArgs* problems, int count, hipStream_t s, int* route = nullptr);
 
 // ---------------------------------------------------------------- elementwise ops (ops.hip)
 // Intersections of one level, one job per cardinality class: n members with k inputs each,
@@ -155,6 +198,9 @@ struct ColsumJobs {
 hipError_t launch_colsums(ColsumJobs& jobs, hipStream_t s, bool finish = true);
 hipError_t launch_fill_zero(float* p, size_t n, hipStream_t s);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
+// calibration access patterns (ngdb_debug_stream)
+hipError_t launch_stream_pattern(int mode, void* dst, const void* src, size_t bytes, const int32_t* rows, int64_t n_rows,
+                                 int row_floats, hipStream_t s);
 
 struct AdamHyper {
     float lr, beta1, beta2, eps;
@@ -280,6 +326,9 @@ struct TableArgs {
     // bf16 copy of the table [rows, d] that the scoring pass reads: pair signs are taken against
     // the rounded row, and the updated row is rounded into the copy
     uint16_t* shadow = nullptr;
+    // the table and its moments are far larger than the caches: their rows move with non-temporal
+    // loads and stores (single-table launches only)
+    bool streaming = false;
 };
 // sorted contribution numbers -> records: c < n_rowsrc is gradient row row_base + c,
 // otherwise a (query, candidate) pair in the order [B positives | B*K negatives]

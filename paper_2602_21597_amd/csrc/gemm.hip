@@ -496,7 +496,8 @@ hipError_t dispatch_layout(GemmGroup& g, hipStream_t s) {
 
 }  // namespace
 
-hipError_t launch_gemm_group(const GemmArgs* problems, int count, hipStream_t s) {
+hipError_t launch_gemm_group(const GemmArgs* problems, int count, hipStream_t s, int* route) {
+    if (route) *route = GEMM_FP32;
     GemmGroup g{};
     long blocks_small = 0;
     int max_k = 0;
@@ -526,6 +527,7 @@ hipError_t launch_gemm_group(const GemmArgs* problems, int count, hipStream_t s)
         // (in the large tile every staged value feeds two MFMA blocks: there the split pays for
         // the weight gradients too)
         const bool big_split = arith == GEMM_AUTO && max_k >= 128;
+        if (route && big_split) *route = GEMM_SPLIT;
         return big_split ? dispatch_layout<64, 64, 4, true>(g, s) : dispatch_layout<64, 64, 4>(g, s);
     }
     // below that the launches of a step do not fill the chip: the smallest tile the MFMA block
@@ -537,6 +539,7 @@ hipError_t launch_gemm_group(const GemmArgs* problems, int count, hipStream_t s)
     // gradients) splitting and transposing the pieces costs more than the matrix unit saves.
     // (with a k extent below 128 the matrix unit is idle either way and the splitting only adds work)
     if (arith == GEMM_SPLIT || auto_split) {
+        if (route) *route = GEMM_SPLIT;
         if (blocks_small * 2 > 512) return dispatch_layout<32, 32, 4, true>(g, s);
         return dispatch_layout<32, 32, 8, true>(g, s);
     }
@@ -544,6 +547,6 @@ hipError_t launch_gemm_group(const GemmArgs* problems, int count, hipStream_t s)
     return dispatch_layout<32, 32, 8>(g, s);
 }
 
-hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) { return launch_gemm_group(&a, 1, s); }
+hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) { return launch_gemm_group(&a, 1, s, nullptr); }
 
 }  // namespace ngdb

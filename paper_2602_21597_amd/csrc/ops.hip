@@ -108,6 +108,96 @@ __global__ __launch_bounds__(256) void copy_kernel(float4* __restrict__ dst, con
         dst[i] = src[i];
 }
 
+// Calibration kernels: plain access patterns of the memory-bound kernels of the step, without their
+// arithmetic, to measure what this machine delivers for each pattern.
+__global__ __launch_bounds__(256) void read_kernel(const float4* __restrict__ src, size_t n, float* __restrict__ sink) {
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+        const float4 v = src[i];
+        acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    const float t = (acc.x + acc.y) + (acc.z + acc.w);
+    if (t == 1.2345e-30f) sink[0] = t;      // keeps the loads alive; never true for the calibration data
+}
+__global__ __launch_bounds__(256) void write_kernel(float4* __restrict__ dst, size_t n) {
+    const float4 v = make_float4(1.f, 2.f, 3.f, 4.f);
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+        dst[i] = v;
+}
+// One wavefront per listed row of a [*, row_floats] table, float4 pieces 64 lanes apart, the next
+// row requested before the current one is consumed (the scoring kernel's gather).
+template <int NCH>
+__global__ __launch_bounds__(256) void gather_rows_kernel(const float* __restrict__ table, const int32_t* __restrict__ rows,
+                                                         int64_t n_rows, int row_floats, float* __restrict__ sink) {
+    const int lane = threadIdx.x & 63, d4 = row_floats >> 2;
+    const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int64_t n_waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    float4 cur[NCH], nxt[NCH];
+    int64_t i = wave;
+    if (i < n_rows) {
+        const float4* r = reinterpret_cast<const float4*>(table + (size_t)rows[i] * row_floats);
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch) cur[ch] = r[min(ch * 64 + lane, d4 - 1)];
+    }
+    for (; i < n_rows; i += n_waves) {
+        const float4* r = reinterpret_cast<const float4*>(table + (size_t)rows[min(i + n_waves, n_rows - 1)] * row_floats);
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch) nxt[ch] = r[min(ch * 64 + lane, d4 - 1)];
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch) {
+            acc.x += cur[ch].x; acc.y += cur[ch].y; acc.z += cur[ch].z; acc.w += cur[ch].w;
+            cur[ch] = nxt[ch];
+        }
+    }
+    const float t = (acc.x + acc.y) + (acc.z + acc.w);
+    if (t == 1.2345e-30f) sink[0] = t;
+}
+// One wavefront per listed row: the row of each of three equally shaped tables (laid out one after
+// the other) is read and written back changed (the table kernel's traffic without its gradients).
+typedef float ops_f4 __attribute__((ext_vector_type(4)));
+template <bool NT>
+__device__ __forceinline__ float4 ld4(const float4* p) {
+    if (!NT) return *p;
+    const ops_f4 v = __builtin_nontemporal_load(reinterpret_cast<const ops_f4*>(p));
+    return make_float4(v[0], v[1], v[2], v[3]);
+}
+template <bool NT>
+__device__ __forceinline__ void st4(float4* p, float4 v) {
+    if (!NT) { *p = v; return; }
+    const ops_f4 t = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(t, reinterpret_cast<ops_f4*>(p));
+}
+__global__ __launch_bounds__(256) void copy_nt_kernel(float4* __restrict__ dst, const float4* __restrict__ src, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+        st4<true>(dst + i, ld4<true>(src + i));
+}
+template <int NCH, bool NT = false>
+__global__ __launch_bounds__(256) void update_rows_kernel(float* __restrict__ tables, size_t table_floats,
+                                                         const int32_t* __restrict__ rows, int64_t n_rows, int row_floats) {
+    const int lane = threadIdx.x & 63, d4 = row_floats >> 2;
+    const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int64_t n_waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    for (int64_t i = wave; i < n_rows; i += n_waves) {
+        const size_t at = (size_t)rows[i] * row_floats;
+        float4 x[3][NCH];
+#pragma unroll
+        for (int t = 0; t < 3; ++t)
+#pragma unroll
+            for (int ch = 0; ch < NCH; ++ch)
+                x[t][ch] = ld4<NT>(reinterpret_cast<const float4*>(tables + t * table_floats + at) + min(ch * 64 + lane, d4 - 1));
+#pragma unroll
+        for (int t = 0; t < 3; ++t)
+#pragma unroll
+            for (int ch = 0; ch < NCH; ++ch)
+                if (ch * 64 + lane < d4) {
+                    float4 v = x[t][ch];
+                    v.x += 1.f; v.y += 1.f; v.z += 1.f; v.w += 1.f;
+                    st4<NT>(reinterpret_cast<float4*>(tables + t * table_floats + at) + ch * 64 + lane, v);
+                }
+    }
+}
+
 __global__ __launch_bounds__(256) void dense_adam_kernel(const DenseAdamJob job, const AdamHyper hp) {
     const int t = blockIdx.y;
     float* __restrict__ p = job.p[t];
@@ -198,6 +288,46 @@ hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s) 
     const unsigned blocks = (unsigned)std::min<size_t>((n + 255) / 256, 256 * 32);
     hipLaunchKernelGGL(copy_kernel, dim3(blocks), dim3(256), 0, s, static_cast<float4*>(dst),
                        static_cast<const float4*>(src), n);
+    return hipGetLastError();
+}
+
+hipError_t launch_stream_pattern(int mode, void* dst, const void* src, size_t bytes, const int32_t* rows, int64_t n_rows,
+                                 int row_floats, hipStream_t s) {
+    const unsigned full = 256 * 32;      // workgroups of four wavefronts: eight wavefronts per SIMD everywhere
+    if (mode == 0) return launch_copy(dst, src, bytes, s);
+    if (mode == 1 || mode == 2) {
+        if (bytes & 15) return hipErrorInvalidValue;
+        const size_t n = bytes / 16;
+        const unsigned blocks = (unsigned)std::min<size_t>((n + 255) / 256, full);
+        if (mode == 1) hipLaunchKernelGGL(read_kernel, dim3(blocks), dim3(256), 0, s, static_cast<const float4*>(src), n,
+                                          static_cast<float*>(dst));
+        else hipLaunchKernelGGL(write_kernel, dim3(blocks), dim3(256), 0, s, static_cast<float4*>(dst), n);
+        return hipGetLastError();
+    }
+    if (mode == 5) {     // the copy with non-temporal loads and stores
+        if (bytes & 15) return hipErrorInvalidValue;
+        const size_t n = bytes / 16;
+        hipLaunchKernelGGL(copy_nt_kernel, dim3((unsigned)std::min<size_t>((n + 255) / 256, full)), dim3(256), 0, s,
+                           static_cast<float4*>(dst), static_cast<const float4*>(src), n);
+        return hipGetLastError();
+    }
+    if ((mode != 3 && mode != 4 && mode != 6) || !rows || n_rows <= 0 || row_floats < 4 || (row_floats & 3) || row_floats > 1024)
+        return hipErrorInvalidValue;
+    const unsigned blocks = (unsigned)std::min<int64_t>((n_rows + 3) / 4, full);
+    const int nch = row_floats <= 256 ? 1 : (row_floats <= 512 ? 2 : 4);
+#define NGDB_PATTERN(NCH)                                                                                          \
+    do {                                                                                                          \
+        if (mode == 3) hipLaunchKernelGGL((gather_rows_kernel<NCH>), dim3(blocks), dim3(256), 0, s,                \
+                                          static_cast<const float*>(src), rows, n_rows, row_floats, static_cast<float*>(dst)); \
+        else if (mode == 4) hipLaunchKernelGGL((update_rows_kernel<NCH>), dim3(blocks), dim3(256), 0, s,          \
+                                               static_cast<float*>(dst), bytes / 12, rows, n_rows, row_floats);    \
+        else hipLaunchKernelGGL((update_rows_kernel<NCH, true>), dim3(blocks), dim3(256), 0, s,                    \
+                                static_cast<float*>(dst), bytes / 12, rows, n_rows, row_floats);                   \
+    } while (0)
+    if (nch == 1) NGDB_PATTERN(1);
+    else if (nch == 2) NGDB_PATTERN(2);
+    else NGDB_PATTERN(4);
+#undef NGDB_PATTERN
     return hipGetLastError();
 }
 

@@ -130,7 +130,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
                     }
                 }
             }
-            dist = wave_sum(dist);
+            dist = wave_sum_dpp(dist);
             if (dist < best) {   // strict: equal distances keep the lower branch
                 best = dist;
                 bw = b;
@@ -141,8 +141,20 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
         if (lane == 0) a.score[pair] = s;
         if (TRAIN) {
             const bool is_pos = (c == 0);
-            const float coef = is_pos ? -sigmoid_f(-s) * inv2B : sigmoid_f(s) * inv2B * invK;
-            lsum += is_pos ? softplus_f(-s) : softplus_f(s) * invK;
+            // The positive contributes softplus(-s) with dL/ds = -sigmoid(-s)/(2B), a negative
+            // softplus(s)/K with dL/ds = sigmoid(s)/(2BK): with z = -s resp. s both are
+            // w * softplus(z) and +-w * sigmoid(z) / (2B).  One exponential serves both: with
+            // e = exp(-|z|), sigmoid(z) = 1/(1+e) or e/(1+e), softplus(z) = max(z, 0) + log(1+e).
+            // The hardware approximations (about 1 ulp, the argument of the exponential rounded
+            // once) keep dL/ds to a few 1e-6 relative; the correctly rounded library forms cost
+            // several hundred instructions per pair, every one of them on all 64 lanes.
+            const float z = is_pos ? -s : s;
+            const float wq = is_pos ? 1.f : invK;
+            const float e = fast_exp_neg(fabsf(z));
+            const float r = fast_rcp(1.f + e);
+            const float sig = z >= 0.f ? r : e * r;
+            const float coef = (is_pos ? -inv2B : inv2B) * wq * sig;
+            lsum += wq * (fmaxf(z, 0.f) + fast_log1p_unit(e));
             if (lane == 0) {
                 a.coef[pair] = coef;
                 if (!MASK) a.win[pair] = a.root_slot[r0 + bw];
@@ -153,21 +165,19 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
                 const int col = col_of<B16>(ch, lane);
                 if (col < d4) {
                     const float4 y = ybr[bw * d4 + col];
-                    const float sx = sgn(y.x - cur[ch].x), sy = sgn(y.y - cur[ch].y),
-                                sz = sgn(y.z - cur[ch].z), sw = sgn(y.w - cur[ch].w);
+                    const float tx = y.x - cur[ch].x, ty = y.y - cur[ch].y, tz = y.z - cur[ch].z, tw = y.w - cur[ch].w;
                     if (MASK)
-                        bits |= (sign_code(sx) | (sign_code(sy) << 2) | (sign_code(sz) << 4) | (sign_code(sw) << 6)) << (8 * ch);
-                    float4 g;
-                    g.x = coef * sx;
-                    g.y = coef * sy;
-                    g.z = coef * sz;
-                    g.w = coef * sw;
+                        bits |= (sign_code(tx) | (sign_code(ty) << 2) | (sign_code(tz) << 4) | (sign_code(tw) << 6)) << (8 * ch);
+                    float4 g;                                     // coef * sign(difference)
+                    g.x = signed_by(coef, tx);
+                    g.y = signed_by(coef, ty);
+                    g.z = signed_by(coef, tz);
+                    g.w = signed_by(coef, tw);
                     if (BOX) {
                         // outside coordinates pull the centre with weight 1 and widen the offset;
                         // inside ones pull with weight alpha and leave the offset alone
                         const float4 o = obr[bw * d4 + col];
-                        const bool ox = fabsf(y.x - cur[ch].x) > o.x, oy = fabsf(y.y - cur[ch].y) > o.y,
-                                   oz = fabsf(y.z - cur[ch].z) > o.z, ow = fabsf(y.w - cur[ch].w) > o.w;
+                        const bool ox = fabsf(tx) > o.x, oy = fabsf(ty) > o.y, oz = fabsf(tz) > o.z, ow = fabsf(tw) > o.w;
                         g.x *= ox ? 1.f : alpha; g.y *= oy ? 1.f : alpha;
                         g.z *= oz ? 1.f : alpha; g.w *= ow ? 1.f : alpha;
                         const float co = coef * (1.f - alpha);

@@ -87,13 +87,32 @@ __device__ __forceinline__ uint32_t load_mask(const void* mask, size_t idx) {
 // winning box in that coordinate and alpha where it lies inside.
 // SH (plain vector family): the scoring pass reads a bf16 copy of the table; pair signs are taken
 // against the rounded row and the updated row is rounded into the copy.
-template <int NCH, bool SEM, bool BOX, bool SH>
+// NT (tables far larger than the caches: every touched row is read once and written once per step):
+// parameter and moment rows move with non-temporal loads and stores.  Measured on the bare access
+// pattern (three rows read and written back per touched row, 2 M of 2.5 M rows): 4.8 against
+// 4.2 TB/s; on tables that fit the last-level cache the hint would push them out of it.
+typedef float table_f4 __attribute__((ext_vector_type(4)));
+template <bool NT>
+__device__ __forceinline__ float4 row_load(const float4* p) {
+    if (!NT) return *p;
+    const table_f4 v = __builtin_nontemporal_load(reinterpret_cast<const table_f4*>(p));
+    return make_float4(v[0], v[1], v[2], v[3]);
+}
+template <bool NT>
+__device__ __forceinline__ void row_store(float4* p, float4 v) {
+    if (!NT) { *p = v; return; }
+    const table_f4 t = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(t, reinterpret_cast<table_f4*>(p));
+}
+
+template <int NCH, bool SEM, bool BOX, bool SH, bool NT = false>
 __device__ __forceinline__ void table_rows(const TableArgs& a, const AdamHyper& hp, int wave_global, int n_waves) {
     const int lane = threadIdx.x & 63;
     const int d4 = a.d >> 2;
     const int n_uniq = *a.n_uniq_dev;
     const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
     const bool update = a.g_out == nullptr;
+    const float step1 = hp.lr / hp.bc1, ibc2 = 1.f / hp.bc2;   // lr / (1 - beta1^t), 1 / (1 - beta2^t): once per wavefront
     bool col_ok[NCH];
     int colc[NCH];
 #pragma unroll
@@ -102,22 +121,49 @@ __device__ __forceinline__ void table_rows(const TableArgs& a, const AdamHyper& 
         colc[ch] = min(ch * 64 + lane, d4 - 1);       // clamped: loads never branch
     }
 
+    // The wavefront's next row is requested while the current one is finished: its index entries
+    // during the walk over the current segment, its parameter and moment rows before the update
+    // arithmetic and the stores of the current row (the registers of the segment walk are free
+    // then).  Past the last row the requests repeat it and are not used.
+    int32_t row_n = 0;
+    int t0_n = 0, t1_n = 0;
+    float4 p_n[NCH], m_n[NCH], v_n[NCH];
+#define NGDB_FETCH_INDEX(uu)                                   \
+    do {                                                       \
+        const int uc = min((uu), n_uniq - 1);                  \
+        row_n = a.uniq[uc];                                    \
+        t0_n = a.seg_off[uc];                                  \
+        t1_n = a.seg_off[uc + 1];                              \
+    } while (0)
+#define NGDB_FETCH_ROWS()                                                                                      \
+    _Pragma("unroll") for (int ch = 0; ch < NCH; ++ch) {                                                      \
+        if (update || !SEM) p_n[ch] = row_load<NT>(reinterpret_cast<const float4*>(a.P + (size_t)row_n * a.d) + colc[ch]); \
+        if (update) {                                                                                          \
+            m_n[ch] = row_load<NT>(reinterpret_cast<const float4*>(a.Mo + (size_t)row_n * a.d) + colc[ch]);    \
+            v_n[ch] = row_load<NT>(reinterpret_cast<const float4*>(a.Vo + (size_t)row_n * a.d) + colc[ch]);    \
+        }                                                                                                      \
+    }
+    if (wave_global < n_uniq) {
+        NGDB_FETCH_INDEX(wave_global);
+        NGDB_FETCH_ROWS()
+    }
     for (int u = wave_global; u < n_uniq; u += n_waves) {
-        const int32_t row = a.uniq[u];
-        const int t0 = a.seg_off[u], t1 = a.seg_off[u + 1];
+        const int32_t row = row_n;
+        const int t0 = t0_n, t1 = t1_n;
         float4* prow = reinterpret_cast<float4*>(a.P + (size_t)row * a.d);
         float4* mrow = reinterpret_cast<float4*>(a.Mo + (size_t)row * a.d);
         float4* vrow = reinterpret_cast<float4*>(a.Vo + (size_t)row * a.d);
         float4 p[NCH], m[NCH], v[NCH], g[NCH];
 #pragma unroll
         for (int ch = 0; ch < NCH; ++ch) {
-            if (update || !SEM) p[ch] = prow[colc[ch]];
+            if (update || !SEM) p[ch] = p_n[ch];
             if (update) {
-                m[ch] = mrow[colc[ch]];
-                v[ch] = vrow[colc[ch]];
+                m[ch] = m_n[ch];
+                v[ch] = v_n[ch];
             }
             g[ch] = zero4;
         }
+        NGDB_FETCH_INDEX(u + n_waves);
         // SH: the row as the scoring pass read it (rounded to bf16)
         float4 psr[SH ? NCH : 1];
         if (SH) {
@@ -141,7 +187,7 @@ __device__ __forceinline__ void table_rows(const TableArgs& a, const AdamHyper& 
 #pragma unroll
                 for (int q = 0; q < G; ++q) {
                     const int j = min(j0 + q, n_rows - 1);
-                    const int32_t r = __shfl(my_row, j, 64);
+                    const int32_t r = lane_value(my_row, j);
                     wgt[q] = j0 + q < n_rows ? 1.f : 0.f;        // padding entries of the last group add nothing
                     const float4* srow = reinterpret_cast<const float4*>(a.dact + (size_t)(-1 - r) * a.d);
 #pragma unroll
@@ -164,8 +210,8 @@ __device__ __forceinline__ void table_rows(const TableArgs& a, const AdamHyper& 
 #pragma unroll
                     for (int q = 0; q < G; ++q) {
                         const int j = min(j0 + q, n - 1);
-                        const int32_t r = __shfl(my_row, j, 64);
-                        cf[q] = j0 + q < n ? __shfl(my_coef, j, 64) : 0.f;
+                        const int32_t r = lane_value(my_row, j);
+                        cf[q] = j0 + q < n ? lane_value(my_coef, j) : 0.f;
                         const float4* srow = reinterpret_cast<const float4*>(a.act + (size_t)r * a.d);
 #pragma unroll
                         for (int ch = 0; ch < NCH; ++ch) x[q][ch] = srow[colc[ch]];
@@ -183,15 +229,15 @@ __device__ __forceinline__ void table_rows(const TableArgs& a, const AdamHyper& 
                                 const float ca = cf[q] * a.alpha;
                                 const float dx = x[q][ch].x - NGDB_PS(ch).x, dy = x[q][ch].y - NGDB_PS(ch).y,
                                             dz = x[q][ch].z - NGDB_PS(ch).z, dw = x[q][ch].w - NGDB_PS(ch).w;
-                                g[ch].x += (fabsf(dx) > xo[q][ch].x ? cf[q] : ca) * sgn(dx);
-                                g[ch].y += (fabsf(dy) > xo[q][ch].y ? cf[q] : ca) * sgn(dy);
-                                g[ch].z += (fabsf(dz) > xo[q][ch].z ? cf[q] : ca) * sgn(dz);
-                                g[ch].w += (fabsf(dw) > xo[q][ch].w ? cf[q] : ca) * sgn(dw);
+                                g[ch].x += signed_by(fabsf(dx) > xo[q][ch].x ? cf[q] : ca, dx);
+                                g[ch].y += signed_by(fabsf(dy) > xo[q][ch].y ? cf[q] : ca, dy);
+                                g[ch].z += signed_by(fabsf(dz) > xo[q][ch].z ? cf[q] : ca, dz);
+                                g[ch].w += signed_by(fabsf(dw) > xo[q][ch].w ? cf[q] : ca, dw);
                             } else {
-                                g[ch].x += cf[q] * sgn(x[q][ch].x - NGDB_PS(ch).x);
-                                g[ch].y += cf[q] * sgn(x[q][ch].y - NGDB_PS(ch).y);
-                                g[ch].z += cf[q] * sgn(x[q][ch].z - NGDB_PS(ch).z);
-                                g[ch].w += cf[q] * sgn(x[q][ch].w - NGDB_PS(ch).w);
+                                g[ch].x += signed_by(cf[q], x[q][ch].x - NGDB_PS(ch).x);
+                                g[ch].y += signed_by(cf[q], x[q][ch].y - NGDB_PS(ch).y);
+                                g[ch].z += signed_by(cf[q], x[q][ch].z - NGDB_PS(ch).z);
+                                g[ch].w += signed_by(cf[q], x[q][ch].w - NGDB_PS(ch).w);
                             }
                         }
                 }
@@ -203,8 +249,8 @@ __device__ __forceinline__ void table_rows(const TableArgs& a, const AdamHyper& 
 #pragma unroll
                 for (int q = 0; q < GP; ++q) {
                     const int j = min(j0 + q, n - 1);
-                    const int32_t pair = __shfl(my_row, j, 64);
-                    cf[q] = j0 + q < n ? __shfl(my_coef, j, 64) : 0.f;
+                    const int32_t pair = lane_value(my_row, j);
+                    cf[q] = j0 + q < n ? lane_value(my_coef, j) : 0.f;
                     bits[q] = load_mask<NCH>(a.mask, (size_t)pair * 64 + lane);
                 }
 #pragma unroll
@@ -219,6 +265,7 @@ __device__ __forceinline__ void table_rows(const TableArgs& a, const AdamHyper& 
                     }
             }
         }
+        NGDB_FETCH_ROWS()
         if (SEM) {
             uint2* brow = reinterpret_cast<uint2*>(a.g_bf16 + (size_t)u * a.d);
 #pragma unroll
@@ -246,16 +293,19 @@ __device__ __forceinline__ void table_rows(const TableArgs& a, const AdamHyper& 
 #pragma unroll
         for (int ch = 0; ch < NCH; ++ch) {
             if (col_ok[ch]) {
+                // (reciprocal and square root by the hardware approximations, about 1 ulp each: the
+                // correctly rounded forms cost some sixty instructions per coordinate, which made
+                // this memory-bound kernel wait for its own arithmetic)
                 const float b1 = hp.beta1, b2 = hp.beta2;
 #define NGDB_ADAM(F)                                                             \
     m[ch].F = b1 * m[ch].F + (1.f - b1) * g[ch].F;                               \
     v[ch].F = b2 * v[ch].F + (1.f - b2) * g[ch].F * g[ch].F;                     \
-    p[ch].F -= hp.lr * (m[ch].F / hp.bc1) / (sqrtf(v[ch].F / hp.bc2) + hp.eps);
+    p[ch].F -= (step1 * m[ch].F) * fast_rcp(fast_sqrt(v[ch].F * ibc2) + hp.eps);
                 NGDB_ADAM(x) NGDB_ADAM(y) NGDB_ADAM(z) NGDB_ADAM(w)
 #undef NGDB_ADAM
-                mrow[ch * 64 + lane] = m[ch];
-                vrow[ch * 64 + lane] = v[ch];
-                prow[ch * 64 + lane] = p[ch];
+                row_store<NT>(mrow + ch * 64 + lane, m[ch]);
+                row_store<NT>(vrow + ch * 64 + lane, v[ch]);
+                row_store<NT>(prow + ch * 64 + lane, p[ch]);
                 if (SH)
                     reinterpret_cast<uint2*>(a.shadow + (size_t)row * a.d)[ch * 64 + lane] =
                         make_uint2(bf16_bits(p[ch].x) | (bf16_bits(p[ch].y) << 16),
@@ -266,6 +316,8 @@ __device__ __forceinline__ void table_rows(const TableArgs& a, const AdamHyper& 
 }
 
 #undef NGDB_PS
+#undef NGDB_FETCH_INDEX
+#undef NGDB_FETCH_ROWS
 
 // Small steps (the launch, not the bytes, is what a table update costs there): the last
 // main_blocks workgroups walk the rows of the main table; the ones before them those of up to two
@@ -273,9 +325,9 @@ __device__ __forceinline__ void table_rows(const TableArgs& a, const AdamHyper& 
 // each add their latency to the step's tail).  Large tables keep table_kernel: there this
 // kernel measured 3 % slower on the entity table than the launches it saves are worth.
 // one table per launch
-template <int NCH, bool SEM, bool BOX, bool SH>
+template <int NCH, bool SEM, bool BOX, bool SH, bool NT>
 __global__ __launch_bounds__(256) void table_kernel(const TableArgs a, const AdamHyper hp) {
-    table_rows<NCH, SEM, BOX, SH>(a, hp, (int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6),
+    table_rows<NCH, SEM, BOX, SH, NT>(a, hp, (int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6),
                                   (int)((gridDim.x * blockDim.x) >> 6));
 }
 
@@ -332,7 +384,8 @@ hipError_t launch_table_update(const TableArgs& a, const AdamHyper& hp, hipStrea
 #define NGDB_TABLE_V(NCH, SEM_, BOX_, SH_)                                                                     \
     do {                                                                                                      \
         if (n_small) hipLaunchKernelGGL((table_group_kernel<NCH, SEM_, BOX_, SH_>), dim3(blocks), dim3(256), 0, s, a, tail, hp); \
-        else hipLaunchKernelGGL((table_kernel<NCH, SEM_, BOX_, SH_>), dim3(tail.main_blocks), dim3(256), 0, s, a, hp);       \
+        else if (a.streaming) hipLaunchKernelGGL((table_kernel<NCH, SEM_, BOX_, SH_, true>), dim3(tail.main_blocks), dim3(256), 0, s, a, hp); \
+        else hipLaunchKernelGGL((table_kernel<NCH, SEM_, BOX_, SH_, false>), dim3(tail.main_blocks), dim3(256), 0, s, a, hp); \
     } while (0)
 #define NGDB_TABLE(NCH)                                   \
     do {                                                  \
