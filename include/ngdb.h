@@ -305,6 +305,25 @@ int ngdb_score(ngdb_ctx_t* ctx, const ngdb_plan_t* plan, const int32_t* d_cand, 
                int32_t topk, float* d_scores, int32_t* d_topk_ids, float* d_topk_dist,
                void* stream);
 
+/* ngdb_score in candidate mode for callers that cannot allocate device memory: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels and the same
+ * results as ngdb_score(ctx, plan, d_cand, C, 0, d_scores, NULL, NULL, stream), but the forward
+ * workspace (operator outputs, gathered inputs, hidden rows, attention logits) is a static array
+ * of NGDB_NOALLOC_SCRATCH_MIB MiB that lives in the library's device image, one copy per GPU,
+ * held until the process ends: the call makes no hipMalloc / hipFree, creates no events and
+ * never waits for the device.  A batch whose workspace (ngdb_score_noalloc_bytes) exceeds the
+ * array is refused with NGDB_ERR_ARG and a message in ngdb_last_error; vector family without
+ * text features only (else NGDB_ERR_UNSUPPORTED).  All contexts and calls on one GPU share the
+ * array: calls that overlap on one GPU (two streams, two threads, two contexts) race; the array
+ * keeps the last call's contents, and nothing in it has to start at zero (every row is written
+ * before it is read within a call).  The plan comes from ngdb_plan (which may allocate), the
+ * parameters from ngdb_bind_params; d_cand and d_scores as for ngdb_score.                    */
+#define NGDB_NOALLOC_SCRATCH_MIB 32
+int ngdb_score_noalloc(ngdb_ctx_t* ctx, const ngdb_plan_t* plan, const int32_t* d_cand, int32_t C,
+                       float* d_scores, void* stream);
+/* Bytes of that workspace the plan needs (0 for NULL arguments). */
+size_t ngdb_score_noalloc_bytes(const ngdb_ctx_t* ctx, const ngdb_plan_t* plan);
+
 /* Evaluation (the filtered MRR / Hit@k the paper reports, Sec. 5.3): forward, then for
  * every listed answer of every query its filtered rank
  *     1 + #{entities that are not listed answers of the query and lie strictly closer}.

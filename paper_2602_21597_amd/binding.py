@@ -98,6 +98,8 @@ def load_library(path=LIB_PATH):
         "ngdb_forward_backward": (C.c_int, [vp, vp, vp, i32, vp, vp]),
         "ngdb_get_grads": (C.c_int, [vp, C.POINTER(GradView)]),
         "ngdb_score": (C.c_int, [vp, vp, vp, i32, i32, vp, vp, vp, vp]),
+        "ngdb_score_noalloc": (C.c_int, [vp, vp, vp, i32, vp, vp]),
+        "ngdb_score_noalloc_bytes": (C.c_size_t, [vp, vp]),
         "ngdb_rank_answers": (C.c_int, [vp, vp, vp, vp, i32, vp, vp, vp]),
         "ngdb_rank_metrics": (C.c_int, [vp, vp, vp, i32, vp, vp]),
         "ngdb_sampler_create": (C.c_int, [i32, i32, i64, vp, vp, vp, C.c_char_p, vp, C.c_uint64, i32, C.POINTER(vp)]),
@@ -467,6 +469,19 @@ class Engine:
         _check(lib().ngdb_score(self.ctx, plan.handle, cand.data_ptr(), int(cand.shape[1]), 0, out.data_ptr(),
                                 None, None, self._stream(stream)), self.ctx)
         return out
+
+    def score_noalloc(self, plan, cand, out, stream=None):
+        """ngdb_score_noalloc: like score(), into the caller's `out` [B, C] float32 device tensor; the
+        library allocates nothing (its forward workspace is a static device array)."""
+        t = self.torch
+        assert cand.dtype == t.int32 and cand.is_cuda and cand.is_contiguous() and cand.dim() == 2
+        assert out.dtype == t.float32 and out.is_cuda and out.is_contiguous() and out.shape == cand.shape
+        _check(lib().ngdb_score_noalloc(self.ctx, plan.handle, cand.data_ptr(), int(cand.shape[1]), out.data_ptr(),
+                                        self._stream(stream)), self.ctx)
+        return out
+
+    def score_noalloc_bytes(self, plan):
+        return int(lib().ngdb_score_noalloc_bytes(self.ctx, plan.handle))
 
     def set_timing(self, classes):
         """classes: iterable of names from TIMING_CLASSES (empty = off)."""

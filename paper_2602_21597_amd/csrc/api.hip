@@ -15,6 +15,8 @@
 
 using namespace ngdb;
 
+static __device__ __align__(256) unsigned char scratch[(size_t)NGDB_NOALLOC_SCRATCH_MIB << 20];
+
 namespace {
 
 struct DevBuf {
@@ -106,6 +108,15 @@ struct ngdb_ctx_s {
 namespace {
 
 thread_local std::string g_create_err;
+
+// Scratch of ngdb_score_noalloc: device memory that exists from the moment the library's code
+// object is loaded on a GPU until the process ends, one copy per GPU.  In host code the array's
+// name only stands for the symbol; its device address on a GPU is asked for once per device
+// (noalloc_scratch) and only that address is ever passed to kernels.
+constexpr size_t NOALLOC_BYTES = (size_t)NGDB_NOALLOC_SCRATCH_MIB << 20;
+constexpr int NOALLOC_MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+unsigned char* g_scratch_ptr[NOALLOC_MAX_DEVICES] = {};
 
 int fail(ngdb_ctx_t* c, int code, const std::string& msg) {
     if (c) {
@@ -854,6 +865,23 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
     return NGDB_OK;
 }
 
+// Device address of the scratch array on the current GPU (looked up on first use per device).
+hipError_t noalloc_scratch(unsigned char** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= NOALLOC_MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        unsigned char* p = nullptr;
+        e = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------------ C ABI
@@ -881,6 +909,8 @@ int ngdb_create(const ngdb_config* cfg, ngdb_ctx_t** out) {
     ok = ok && hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) == hipSuccess;
     ok = ok && hipStreamCreateWithFlags(&c->upload, hipStreamNonBlocking) == hipSuccess;
+    unsigned char* sp = nullptr;
+    ok = ok && noalloc_scratch(&sp) == hipSuccess;     // address of the static scratch on this GPU
     if (!ok) {
         ngdb_destroy(c);
         return NGDB_ERR_HIP;
@@ -1208,6 +1238,74 @@ int ngdb_score(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_cand, int3
                                         e0 == 0, d_topk_dist, d_topk_ids, s));
         }
     }
+    HIPCHK(c, hipEventRecord(pl->blob.last_use, s));
+    return NGDB_OK;
+}
+
+size_t ngdb_score_noalloc_bytes(const ngdb_ctx_t* c, const ngdb_plan_t* pl) {
+    if (!c || !pl) return 0;
+    const HostPlan& hp = pl->hp;
+    const size_t d = c->cfg.d, h = c->cfg.h, f = sizeof(float);
+    const size_t rows[3] = {(size_t)hp.n_proj, (size_t)hp.n_int_rows, (size_t)hp.n_neg};
+    auto up = [](size_t b) { return (b + 255) & ~size_t(255); };
+    size_t need = up((size_t)hp.n_slots * d * f) + up(rows[T_INTER] * d * f);
+    for (int t = 0; t < 3; ++t) need += up(rows[t] * d * f) + up(rows[t] * h * f);
+    return need;
+}
+
+int ngdb_score_noalloc(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_cand, int32_t C, float* d_scores,
+                       void* stream) {
+    if (!c || !pl) return NGDB_ERR_ARG;
+    if (!c->bound) return fail(c, NGDB_ERR_STATE, "parameters not bound");
+    if (pl->n_entities != c->cfg.n_entities || !pl->d_blob)
+        return fail(c, NGDB_ERR_ARG, "plan belongs to another configuration or was built without a device");
+    if (c->cfg.family != NGDB_FAMILY_VEC || c->cfg.d_sem != 0)
+        return fail(c, NGDB_ERR_UNSUPPORTED, "ngdb_score_noalloc: vector family without text features only");
+    if (!d_cand || C <= 0 || !d_scores) return fail(c, NGDB_ERR_ARG, "ngdb_score_noalloc needs candidates, C > 0 and d_scores");
+    const size_t need = ngdb_score_noalloc_bytes(c, pl);
+    if (need > NOALLOC_BYTES)
+        return fail(c, NGDB_ERR_ARG, "ngdb_score_noalloc: this batch needs " + std::to_string(need) +
+                                         " bytes of forward workspace, the static scratch holds " +
+                                         std::to_string(NOALLOC_BYTES) + " (NGDB_NOALLOC_SCRATCH_MIB)");
+    unsigned char* base = nullptr;
+    HIPCHK(c, noalloc_scratch(&base));
+    // carve the forward buffers out of the scratch; every row that is read was written earlier in
+    // this call (operator outputs before their consumers, copies and hidden rows by the launch
+    // before the one that reads them), so nothing has to be cleared
+    const HostPlan& hp = pl->hp;
+    const size_t d = c->cfg.d, h = c->cfg.h, f = sizeof(float);
+    const size_t rows[3] = {(size_t)hp.n_proj, (size_t)hp.n_int_rows, (size_t)hp.n_neg};
+    size_t at = 0;
+    auto take = [&](size_t bytes) {
+        float* p = reinterpret_cast<float*>(base + at);
+        at += (bytes + 255) & ~size_t(255);
+        return p;
+    };
+    FwdSpace w{};
+    w.act = take((size_t)hp.n_slots * d * f);
+    w.Att = take(rows[T_INTER] * d * f);
+    for (int t = 0; t < 3; ++t) {
+        w.Z[t] = take(rows[t] * d * f);
+        w.H[t] = take(rows[t] * h * f);
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    c->have_grads = false;
+    const uint32_t timing = c->timing_mask;     // event brackets would create events: off for this call
+    c->timing_mask = 0;
+    const EntRows er{c->prm.E.p, pl->d_in_ref, pl->d_pos, d_cand};
+    int rc = enqueue_forward(c, pl, er, s, w);
+    if (rc == NGDB_OK) {
+        ScoreArgs sa{};
+        sa.act = w.act; sa.E = er.rows; sa.root_off = pl->d_root_off; sa.root_slot = pl->d_root_slot;
+        sa.pos = nullptr; sa.cand = d_cand; sa.B = hp.n_queries; sa.C = C; sa.d = c->cfg.d;
+        sa.max_branch = std::max(1, hp.max_branch); sa.gamma = c->cfg.gamma; sa.score = d_scores;
+        if (c->cfg.score_bf16) sa.E16 = ptr<uint16_t>(c->Eb);
+        const hipError_t e = launch_score(sa, false, s);
+        if (e == hipErrorInvalidValue) rc = fail(c, NGDB_ERR_UNSUPPORTED, "embedding width / union branch count too large for the scoring kernel");
+        else if (e != hipSuccess) rc = fail(c, NGDB_ERR_HIP, std::string("scoring launch: ") + hipGetErrorString(e));
+    }
+    c->timing_mask = timing;
+    if (rc != NGDB_OK) return rc;
     HIPCHK(c, hipEventRecord(pl->blob.last_use, s));
     return NGDB_OK;
 }
