@@ -31,55 +31,82 @@ MFMA_F32_PEAK_TF = 157.3  # dense fp32 matrix, published
 MFMA_BF16_PEAK_TF = 2500.0
 N_BATCHES = 8
 CLASSES = ("index", "sem", "gemm_fwd", "inter", "score", "gemm_bwd", "wgrad", "table_E", "table_R", "adam")
-# HBM bytes per launch of a workload's dominant kernel from the rocprofv3 --pmc runs summarised
-# under profiles/ (FETCH_SIZE + WRITE_SIZE, scaled by the copy kernel): {(config, kernel): bytes}
-MEASURED_TRAFFIC = {
-    (1, "gemm"): 19.7e6,        # mean over the 17 contraction launches of a step (weight gradients: 90 MB)
-    (3, "table_E"): 26.4e9,     # of which 9.75 GB written; 6.7 GB are re-reads of branch rows served by the caches
-    (4, "sem"): 14.2e9,         # projection 16.2 GB + its gradient 12.1 GB per step, two launches
-    ("box", 1, "gemm"): 18.3e6,     # mean over the 9 contraction launches of a step
-    ("box", 3, "table_E"): 32.6e9,  # the winning branches' offset rows are re-read beside their centre rows
-}
 
-
-def cpu_baseline(cfg, kg, sample, sem_bits, box_alpha=None, score_bf16=False):
-    """The oracle as it stands, full steps (loss, gradients, Adam) on batches of `sample` queries
-    until about 10 s of CPU time have passed (at most 16 steps), single process with BLAS held
-    to one thread."""
+def _cpu_worker(job, barrier=None, out=None):
+    """One worker process of the CPU baseline: full oracle steps (loss, gradients, Adam) on its share
+    of every batch, BLAS held to one thread; inputs are built first, the steps start together."""
+    cfg, kg, sem_bits, box_alpha, score_bf16, share, n_steps, worker = job
     from oracle import box as ob
     from oracle import model as om
     try:
         from threadpoolctl import threadpool_limits
+        limit = threadpool_limits(limits=1)
     except Exception:                      # pragma: no cover
-        threadpool_limits = None
+        limit = None
     box = box_alpha is not None
     P = om.to_f64(wl.make_box_params(cfg.N, cfg.R, cfg.d, cfg.h, cfg.seed + 3) if box else
                   wl.make_params(cfg.N, cfg.R, cfg.d, cfg.h, cfg.seed + 3, d_sem=cfg.d_sem))
     st = om.new_state(P)
     hp = dict(lr=cfg.lr, beta1=cfg.beta1, beta2=cfg.beta2, eps=cfg.eps, gamma=cfg.gamma, alpha=box_alpha)
+    batches = [(wl.make_batch(kg, share, cfg.mix, cfg.seed + 100 + 977 * worker + k),
+                wl.make_negatives(cfg.N, share, cfg.K, cfg.seed + 200 + 977 * worker + k)) for k in range(n_steps)]
+    if barrier is not None:
+        barrier.wait()
+    t0 = time.time()
+    for k, (qb, negs) in enumerate(batches):
+        if box:
+            ob.train_step(qb, negs, P, st, k + 1, hp)
+        else:
+            om.train_step(qb, negs, P, st, k + 1, hp, sem_bits, score_bf16=score_bf16)
+    t1 = time.time()
+    del limit
+    if out is not None:
+        out.put((share * n_steps, t0, t1))
+    return share * n_steps, t0, t1
 
-    def run():
-        total, steps = 0.0, 0
-        while total < 10.0 and steps < 16:
-            qb = wl.make_batch(kg, sample, cfg.mix, cfg.seed + 100 + steps)
-            negs = wl.make_negatives(cfg.N, sample, cfg.K, cfg.seed + 200 + steps)
-            t0 = time.perf_counter()
-            if box:
-                ob.train_step(qb, negs, P, st, steps + 1, hp)
-            else:
-                om.train_step(qb, negs, P, st, steps + 1, hp, sem_bits, score_bf16=score_bf16)
-            total += time.perf_counter() - t0
-            steps += 1
-        return total, steps
 
-    if threadpool_limits is not None:
-        with threadpool_limits(limits=1):
-            dt, steps = run()
-    else:
-        dt, steps = run()
-    return {"value": sample * steps / dt, "unit": "queries/s", "cores": 1, "kind": "oracle",
-            "sample": "%d steps of %d queries of the same workload with all %d negatives (per-query fp64 numpy "
-                      "forward, loss, backward, Adam), %.1f s" % (steps, sample, cfg.K, dt)}
+def cpu_baseline(cfg, kg, sample, sem_bits, box_alpha=None, score_bf16=False, cores=None):
+    """The oracle as it stands on the host's cores: `sample` queries per step are split over one
+    worker process per core (forked before this process touches the GPU); every worker runs full
+    oracle steps (per-query fp64 numpy forward, loss, backward, Adam) on its share.  The figure is
+    all queries done / wall time from the common start of the steps to the end of the last worker."""
+    import multiprocessing as mp
+    cores = cores or host_cores()
+    cores = max(1, min(cores, sample))
+    share = max(1, sample // cores)
+    # a few queries on one core size the run: about 10 s of wall time, at most 8 steps
+    probe = min(share, 4)
+    _, t0, t1 = _cpu_worker((cfg, kg, sem_bits, box_alpha, score_bf16, probe, 1, 0))
+    n_steps = int(max(1, min(8, 10.0 / max((t1 - t0) / probe * share, 1e-9))))
+    ctx = mp.get_context("fork")
+    barrier, out = ctx.Barrier(cores), ctx.Queue()
+    procs = [ctx.Process(target=_cpu_worker, args=((cfg, kg, sem_bits, box_alpha, score_bf16, share, n_steps, w),
+                                                   barrier, out)) for w in range(cores)]
+    for pr in procs:
+        pr.start()
+    done = [out.get() for _ in procs]
+    for pr in procs:
+        pr.join()
+    wall = max(t for _, _, t in done) - min(t for _, t, _ in done)
+    queries = sum(q for q, _, _ in done)
+    return {"value": queries / wall, "unit": "queries/s", "cores": cores, "kind": "oracle",
+            "sample": "%d steps of %d queries of the same workload with all %d negatives, split over %d worker "
+                      "processes (one per core, %d queries each per step; per-query fp64 numpy forward, loss, backward, "
+                      "Adam), %.1f s wall, %.1f s of CPU time" % (n_steps, share * cores, cfg.K, cores, share, wall,
+                                                                  sum(b - a for _, a, b in done))}
+
+
+def host_cores():
+    """Cores this process may use: the scheduler's affinity mask, capped by the thread count the
+    environment configures for numerical libraries (the share of the machine that goes with one GPU)."""
+    try:
+        n = len(os.sched_getaffinity(0))
+    except Exception:                      # pragma: no cover
+        n = os.cpu_count() or 1
+    cap = os.environ.get("OMP_NUM_THREADS", "")
+    if cap.isdigit() and int(cap) > 0:
+        n = min(n, int(cap))
+    return max(1, n)
 
 
 def say(msg):
@@ -250,76 +277,47 @@ def calibrate_hbm(args):
     print(json.dumps(out))
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=1)
-    ap.add_argument("--streams", type=int, default=0, help="0 = the workload's default")
-    ap.add_argument("--cpu-sample", type=int, default=-1, help="queries timed on the CPU oracle (0 = skip)")
-    ap.add_argument("--schedule", choices=("level", "max_fill"), default="level",
-                    help="order of execution of the operators (max_fill: the ready-set loop of Alg. 1)")
-    ap.add_argument("--family", choices=("vec", "box"), default="vec",
-                    help="operator family: the vector model of the headline workload, or box embeddings (Q2B "
-                         "operators) on the 9 negation-free structures of the same workload")
-    ap.add_argument("--score-bf16", action="store_true",
-                    help="candidate rows from a bf16 copy of the entity table (optional mode, not the headline)")
-    ap.add_argument("--box-alpha", type=float, default=0.02, help="weight of the inside distance (box family)")
-    ap.add_argument("--bmax", type=int, default=0, help="largest batch of one Max-Fillness step, 0 = unbounded")
-    ap.add_argument("--sampler", type=int, default=0, metavar="THREADS",
-                    help="draw every batch (queries and negatives) inside the run with the library's online sampler "
-                         "on this many threads, instead of cycling pre-generated batches")
-    ap.add_argument("--rank", type=int, default=0, metavar="Q",
-                    help="time the all-entity ranking pass of Q queries instead of the training step")
-    ap.add_argument("--answers", type=int, default=0, metavar="A",
-                    help="with --rank: filtered ranks of A listed answers per query instead of the top-10")
-    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
-                    help="also run the library's plain copy kernel on this many MiB, 5 times (reference "
-                         "for scaling rocprofv3 traffic counters)")
-    ap.add_argument("--calibrate-hbm", action="store_true",
-                    help="instead of the step: plain copy / read / write and the row gather and row update "
-                         "patterns of the scoring and table kernels at the shapes of --config (no arithmetic)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU; --gpus %d is not supported (no sharding, no collectives)"
-              % args.gpus, file=sys.stderr)
-        sys.exit(2)
-    if args.calibrate_hbm:
-        return calibrate_hbm(args)
+PROFILE_NAMES = {1: "fb15k237", 2: "nell", 3: "wikikg2", 4: "text_features"}
 
-    cfg = wl.get_config(args.config)
-    box = args.family == "box"
-    if box:
-        if cfg.d_sem:
-            print("bench.py: the box family has no text features", file=sys.stderr)
-            sys.exit(2)
-        import dataclasses
-        cfg = dataclasses.replace(cfg, mix={n: 1.0 / len(wl.EPFO9) for n in wl.EPFO9})
-    say("generating the graph (N=%d, T=%d)" % (cfg.N, cfg.T))
-    kg = wl.make_kg(cfg.N, cfg.R, cfg.T, cfg.alpha, cfg.seed)
-    if args.rank:
-        params = (wl.make_box_params(cfg.N, cfg.R, cfg.d, cfg.h, cfg.seed + 3) if box else
-                  wl.make_params(cfg.N, cfg.R, cfg.d, cfg.h, cfg.seed + 3, d_sem=cfg.d_sem))
-        sem_bits = wl.make_sem_features(cfg.N, cfg.d_sem, cfg.seed + 5) if cfg.d_sem else None
-        return rank_bench(args, cfg, kg, params, sem_bits, box)
+
+def profile_figures(cfg, box):
+    """Per kernel class, what the tracked rocprofv3 summaries under profiles/ hold for this workload:
+    {class: {"avg_us": .., "launches_per_step": .., "traffic": bytes per launch (FETCH_SIZE + WRITE_SIZE,
+    scaled by the copy kernel)}}, from the lines `class <name> launches_per_step <n> avg_us <t>` of
+    train_step_<workload>_kernel_stats.txt and `traffic <name> <bytes>` of ..._hbm_traffic.txt."""
+    name = ("box_" if box else "") + PROFILE_NAMES.get(cfg.index, "")
+    out, files = {}, []
+    for kind in ("kernel_stats", "hbm_traffic"):
+        path = os.path.join(ROOT, "profiles", "train_step_%s_%s.txt" % (name, kind))
+        if not os.path.exists(path):
+            continue
+        files.append(os.path.relpath(path, ROOT))
+        for line in open(path):
+            w = line.split()
+            try:
+                if len(w) == 6 and w[0] == "class" and w[2] == "launches_per_step" and w[4] == "avg_us":
+                    out.setdefault(w[1], {}).update(launches_per_step=float(w[3]), avg_us=float(w[5]))
+                elif len(w) == 3 and w[0] == "traffic":
+                    out.setdefault(w[1], {})["traffic"] = float(w[2])
+            except ValueError:
+                pass
+    return out, files
+
+
+def measure_workload(cfg, args, kg, steps, warmup, box=False, streams=None):
+    """Runs the training step of one workload: K timed steps with planning inside the timed region,
+    the same steps with plans prebuilt, and once more with every kernel class bracketed by HIP
+    events.  Returns (figures for the JSON line, kernel classes with their rooflines)."""
+    import torch
+    from paper_2602_21597_amd import Engine
     say("generating %d batches of %d queries, negatives, parameters" % (N_BATCHES, cfg.B))
     batches = [wl.make_batch(kg, cfg.B, cfg.mix, cfg.seed + 10 + i) for i in range(N_BATCHES)]
     negs_np = [wl.make_negatives(cfg.N, cfg.B, cfg.K, cfg.seed + 50 + i) for i in range(N_BATCHES)]
     params = (wl.make_box_params(cfg.N, cfg.R, cfg.d, cfg.h, cfg.seed + 3) if box else
               wl.make_params(cfg.N, cfg.R, cfg.d, cfg.h, cfg.seed + 3, d_sem=cfg.d_sem))
     sem_bits = wl.make_sem_features(cfg.N, cfg.d_sem, cfg.seed + 5) if cfg.d_sem else None
-
-    # CPU oracle first, before this process touches the GPU
-    default_sample = 512 if cfg.K <= 128 else (8 if cfg.d_sem else 64)
-    sample = args.cpu_sample if args.cpu_sample >= 0 else min(cfg.B, default_sample)
-    say("CPU oracle on %d queries" % sample)
-    cpu = cpu_baseline(cfg, kg, sample, sem_bits, args.box_alpha if box else None, args.score_bf16) if sample > 0 else None
     say("uploading parameters")
-
-    import torch
-    from paper_2602_21597_amd import Engine
-    streams = args.streams or cfg.streams
+    streams = streams or args.streams or cfg.streams
     eng = Engine(cfg.N, cfg.R, cfg.d, cfg.h, cfg.gamma, lr=cfg.lr, beta1=cfg.beta1, beta2=cfg.beta2, eps=cfg.eps,
                  num_streams=streams, d_sem=cfg.d_sem, schedule={"level": 0, "max_fill": 1}[args.schedule],
                  b_max=args.bmax, family=1 if box else 0, box_alpha=args.box_alpha, score_bf16=args.score_bf16)
@@ -368,13 +366,13 @@ def main():
             plan.free()        # the library recycles the plan's buffers once the step has finished
 
     say("warm-up")
-    run_steps(0, args.warmup)
+    run_steps(0, warmup)
     torch.cuda.synchronize()
-    say("timing %d steps" % args.steps)
+    say("timing %d steps" % steps)
 
     # the timed region: K whole steps (planning included), nothing else on the device
     t0 = time.perf_counter()
-    run_steps(args.warmup, args.steps)
+    run_steps(warmup, steps)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
@@ -382,7 +380,7 @@ def main():
     plans = [eng.plan(b) for b in batches]
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    for i in range(args.steps):
+    for i in range(steps):
         eng.train_step(plans[i % N_BATCHES], negs[i % N_BATCHES], stream)
     torch.cuda.synchronize()
     dt_dev = time.perf_counter() - t1
@@ -391,15 +389,172 @@ def main():
     # the same steps once more with every kernel class bracketed by HIP events on its own stream
     eng.set_timing(CLASSES)
     eng.get_timing(reset=True)
-    for i in range(args.steps):
+    for i in range(steps):
         eng.train_step(plans[i % N_BATCHES], negs[i % N_BATCHES], stream)
     timing = eng.get_timing(reset=True)
+    routes = eng.last_routes
     eng.set_timing(())
     touched = eng.n_touched_entities()
-    pexp = plans[(args.steps - 1) % N_BATCHES].export()
+    pexp = plans[(steps - 1) % N_BATCHES].export()
+
+    # roofline per kernel class: algorithmic work of one step / measured time of the class per step.
+    # Contractions are reported by the matrix instructions their launches ran on: the fp32 ones
+    # against the fp32 matrix peak; the ones on split operands execute six bf16 products per fp32
+    # product and are priced with those executed flops against the bf16 matrix peak (their
+    # algorithmic rate is a sixth of that).
+    models = kernel_models(cfg, pexp, touched, box, args.score_bf16)
+    kern = {}
+    for name, (bound, amount, peak, unit) in models.items():
+        ms, n = timing[name]
+        if n and bound == "hbm" or (n and name == "sem"):
+            kern[name] = {"bound": bound, "ms_per_step": ms / steps, "launches_per_step": n / steps,
+                          "avg_us": 1e3 * ms / n, "work_per_step": amount, "unit": unit, "peak": peak}
+    for route, peak, factor in (("fp32", MFMA_F32_PEAK_TF, 1.0), ("bf16_split", MFMA_BF16_PEAK_TF, 6.0)):
+        ms = sum(routes[c][route][0] for c in ("gemm_fwd", "gemm_bwd", "wgrad"))
+        n = sum(routes[c][route][1] for c in ("gemm_fwd", "gemm_bwd", "wgrad"))
+        flop = sum(routes[c][route][2] for c in ("gemm_fwd", "gemm_bwd", "wgrad"))
+        if n:
+            kern["gemm_" + route] = {"bound": "mfma", "ms_per_step": ms / steps, "launches_per_step": n / steps,
+                                     "avg_us": 1e3 * ms / n, "work_per_step": factor * flop / steps, "unit": "TFLOP/s",
+                                     "peak": peak, "algorithmic_TFLOPs": flop / (ms * 1e-3) / 1e12,
+                                     "executed_per_algorithmic_flop": factor}
+    prof, prof_files = profile_figures(cfg, box)
+    for name, k in kern.items():
+        scale = 1e9 if k["bound"] == "hbm" else 1e12
+        k["achieved"] = k["work_per_step"] / (k["ms_per_step"] * 1e-3) / scale
+        k["frac"] = k["achieved"] / k["peak"]
+        k["algorithmic_work_per_launch"] = k["work_per_step"] / k["launches_per_step"]
+        pf = prof.get(name, {})
+        k["traffic"] = pf.get("traffic")
+        if "avg_us" in pf:      # the same class in the tracked rocprofv3 summary (kernel durations, no event brackets)
+            per_step_us = pf["avg_us"] * pf["launches_per_step"]
+            k["profile"] = {"avg_us": pf["avg_us"], "launches_per_step": pf["launches_per_step"],
+                            "frac": k["work_per_step"] / (per_step_us * 1e-6) / scale / k["peak"]}
+    res = {
+        "queries_per_s": cfg.B * steps / dt, "ms_per_step": 1e3 * dt / steps,
+        "device_only": {"queries_per_s": cfg.B * steps / dt_dev, "ms_per_step": 1e3 * dt_dev / steps,
+                        "note": "same steps with plans prebuilt"},
+        "workload": "configs[%d] %s: N=%d R=%d d=%d h=%d B=%d K=%d%s, %s, gamma=%g"
+                    % (cfg.index, cfg.name, cfg.N, cfg.R, cfg.d, cfg.h, cfg.B, cfg.K,
+                       " d_sem=%d (bf16 text features)" % cfg.d_sem if cfg.d_sem else "",
+                       "box family (alpha=%g) on the 9 negation-free structures" % args.box_alpha if box
+                       else "14-structure mix" + (", candidate rows from a bf16 copy of E" if args.score_bf16 else ""),
+                       cfg.gamma),
+        "streams": streams, "touched_entity_rows": touched, "steps_per_batch": pexp["n_levels"],
+        "peak_live_outputs": pexp["peak_live"], "operator_outputs": pexp["n_slots"],
+        "kernel_classes_ms_per_step": {k: v[0] / steps for k, v in timing.items()},
+        "profile_files": prof_files,
+    }
+    for p_ in plans:
+        p_.free()
+    del eng, negs, plans
+    torch.cuda.empty_cache()
+    return res, kern
+
+
+ROOFLINE_FIELDS = ("bound", "achieved", "peak", "unit", "frac", "traffic", "avg_us", "launches_per_step",
+                   "ms_per_step", "algorithmic_work_per_launch", "algorithmic_TFLOPs",
+                   "executed_per_algorithmic_flop", "profile")
+
+
+def roofline_of(kern):
+    """The class with the largest time per step as the line's roofline object, the others beside it."""
+    dom = max(kern, key=lambda k: kern[k]["ms_per_step"])
+    pick = lambda v: {f: v[f] for f in ROOFLINE_FIELDS if f in v}
+    out = dict(pick(kern[dom]), kernel=dom)
+    out["other"] = {k: pick(v) for k, v in kern.items() if k != dom}
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=1)
+    ap.add_argument("--streams", type=int, default=0, help="0 = the workload's default")
+    ap.add_argument("--cpu-sample", type=int, default=-1, help="queries per step timed on the CPU oracle (0 = skip)")
+    ap.add_argument("--others", default="", metavar="LIST",
+                    help="workloads measured beside the headline one and reported under other_workloads "
+                         "(comma separated config numbers; default: 2,3 beside config 1, none otherwise; 'none')")
+    ap.add_argument("--schedule", choices=("level", "max_fill"), default="level",
+                    help="order of execution of the operators (max_fill: the ready-set loop of Alg. 1)")
+    ap.add_argument("--family", choices=("vec", "box"), default="vec",
+                    help="operator family: the vector model of the headline workload, or box embeddings (Q2B "
+                         "operators) on the 9 negation-free structures of the same workload")
+    ap.add_argument("--score-bf16", action="store_true",
+                    help="candidate rows from a bf16 copy of the entity table (optional mode, not the headline)")
+    ap.add_argument("--box-alpha", type=float, default=0.02, help="weight of the inside distance (box family)")
+    ap.add_argument("--bmax", type=int, default=0, help="largest batch of one Max-Fillness step, 0 = unbounded")
+    ap.add_argument("--sampler", type=int, default=0, metavar="THREADS",
+                    help="draw every batch (queries and negatives) inside the run with the library's online sampler "
+                         "on this many threads, instead of cycling pre-generated batches")
+    ap.add_argument("--rank", type=int, default=0, metavar="Q",
+                    help="time the all-entity ranking pass of Q queries instead of the training step")
+    ap.add_argument("--answers", type=int, default=0, metavar="A",
+                    help="with --rank: filtered ranks of A listed answers per query instead of the top-10")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
+                    help="also run the library's plain copy kernel on this many MiB, 5 times (reference "
+                         "for scaling rocprofv3 traffic counters)")
+    ap.add_argument("--calibrate-hbm", action="store_true",
+                    help="instead of the step: plain copy / read / write and the row gather and row update "
+                         "patterns of the scoring and table kernels at the shapes of --config (no arithmetic)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus %d is not supported (no sharding, no collectives)"
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    if args.calibrate_hbm:
+        return calibrate_hbm(args)
+
+    cfg = wl.get_config(args.config)
+    box = args.family == "box"
+    if box:
+        if cfg.d_sem:
+            print("bench.py: the box family has no text features", file=sys.stderr)
+            sys.exit(2)
+        import dataclasses
+        cfg = dataclasses.replace(cfg, mix={n: 1.0 / len(wl.EPFO9) for n in wl.EPFO9})
+    say("generating the graph (N=%d, T=%d)" % (cfg.N, cfg.T))
+    kg = wl.make_kg(cfg.N, cfg.R, cfg.T, cfg.alpha, cfg.seed)
+    if args.rank:
+        params = (wl.make_box_params(cfg.N, cfg.R, cfg.d, cfg.h, cfg.seed + 3) if box else
+                  wl.make_params(cfg.N, cfg.R, cfg.d, cfg.h, cfg.seed + 3, d_sem=cfg.d_sem))
+        sem_bits = wl.make_sem_features(cfg.N, cfg.d_sem, cfg.seed + 5) if cfg.d_sem else None
+        return rank_bench(args, cfg, kg, params, sem_bits, box)
+
+    # CPU oracle first, on all host cores, before this process touches the GPU
+    default_sample = 512 if cfg.K <= 128 else (16 if cfg.d_sem else 64)
+    sample = args.cpu_sample if args.cpu_sample >= 0 else min(cfg.B, default_sample)
+    cpu = None
+    if sample > 0:
+        say("CPU oracle on %d queries per step, %d cores" % (sample, host_cores()))
+        sem_bits = wl.make_sem_features(cfg.N, cfg.d_sem, cfg.seed + 5) if cfg.d_sem else None
+        cpu = cpu_baseline(cfg, kg, sample, sem_bits, args.box_alpha if box else None, args.score_bf16)
+        del sem_bits
+
+    res, kern = measure_workload(cfg, args, kg, args.steps, args.warmup, box)
+    del kg
+
+    others = args.others or ("2,3" if args.config == 1 and not box and not args.sampler and not args.score_bf16 else "none")
+    other_workloads = {}
+    for idx in ([] if others == "none" else [int(x) for x in others.split(",")]):
+        ocfg = wl.get_config(idx)
+        say("other workload: configs[%d] %s; generating the graph (N=%d, T=%d)" % (idx, ocfg.name, ocfg.N, ocfg.T))
+        okg = wl.make_kg(ocfg.N, ocfg.R, ocfg.T, ocfg.alpha, ocfg.seed)
+        o_steps = args.steps if ocfg.K <= 128 else max(5, min(args.steps, 20))
+        ores, okern = measure_workload(ocfg, args, okg, o_steps, min(args.warmup, 5), False, streams=ocfg.streams)
+        del okg
+        pick = lambda v: {f: v[f] for f in ROOFLINE_FIELDS if f in v}
+        other_workloads["configs[%d]" % idx] = {
+            "workload": ores["workload"], "queries_per_s": ores["queries_per_s"], "ms_per_step": ores["ms_per_step"],
+            "steps": o_steps, "device_only": ores["device_only"], "streams": ores["streams"],
+            "touched_entity_rows": ores["touched_entity_rows"],
+            "kernels": {k: pick(v) for k, v in okern.items()}, "profile_files": ores["profile_files"]}
 
     copy_gbs = None
     if args.calibrate_copy:
+        import torch
         from paper_2602_21597_amd import binding
         src = torch.empty(args.calibrate_copy << 20, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
@@ -411,77 +566,40 @@ def main():
         torch.cuda.synchronize()
         copy_gbs = 2 * nb * 5 / (time.perf_counter() - tc) / 1e9
 
-    # roofline per kernel class: algorithmic work of one step / measured time of the class per step.
-    # The three contraction classes are launches of one kernel and are reported together as "gemm".
-    models = kernel_models(cfg, pexp, touched, box, args.score_bf16)
-    kern = {}
-    for name, (bound, amount, peak, unit) in models.items():
-        ms, n = timing[name]
-        if n:
-            kern[name] = {"bound": bound, "ms_per_step": ms / args.steps, "launches_per_step": n / args.steps,
-                          "avg_us": 1e3 * ms / n, "work_per_step": amount, "unit": unit, "peak": peak}
-    gemm = [kern.pop(k) for k in ("gemm_fwd", "gemm_bwd", "wgrad") if k in kern]
-    if gemm:
-        tot_ms = sum(g["ms_per_step"] for g in gemm)
-        n_l = sum(g["launches_per_step"] for g in gemm)
-        kern["gemm"] = {"bound": "mfma", "ms_per_step": tot_ms, "launches_per_step": n_l,
-                        "avg_us": 1e3 * tot_ms / n_l, "work_per_step": sum(g["work_per_step"] for g in gemm),
-                        "unit": "TFLOP/s", "peak": MFMA_F32_PEAK_TF}
-    for k in kern.values():
-        scale = 1e9 if k["bound"] == "hbm" else 1e12
-        k["achieved"] = k["work_per_step"] / (k["ms_per_step"] * 1e-3) / scale
-        k["frac"] = k["achieved"] / k["peak"]
-    dom = max(kern, key=lambda k: kern[k]["ms_per_step"])
-    kd = kern[dom]
-    traffic = None if args.score_bf16 else MEASURED_TRAFFIC.get(("box", cfg.index, dom) if box else (cfg.index, dom))
-    roofline = {"bound": kd["bound"], "kernel": dom, "achieved": kd["achieved"], "peak": kd["peak"],
-                "unit": kd["unit"], "frac": kd["frac"], "traffic": traffic,
-                "avg_us": kd["avg_us"], "launches_per_step": kd["launches_per_step"],
-                "algorithmic_work_per_launch": kd["work_per_step"] / kd["launches_per_step"],
-                "other": {k: {f: v[f] for f in ("bound", "achieved", "peak", "unit", "frac", "avg_us",
-                                                "launches_per_step", "ms_per_step")}
-                          for k, v in kern.items() if k != dom}}
-    if dom == "gemm":
-        # fp32 contractions, priced against the fp32 matrix peak; the split route (six bf16 MFMAs per
-        # fp32 product block) has a ceiling of its own, the bf16 peak over six
-        roofline["peak_basis"] = ("fp32 MFMA peak; the bf16-split route's own ceiling is %.0f TFLOP/s (bf16 peak / 6)"
-                                  % (MFMA_BF16_PEAK_TF / 6.0))
-
     out = {
         "metric": "training queries/sec (fwd+bwd+Adam) at d=400, K=128 negatives; % of HBM peak",
-        "value": cfg.B * args.steps / dt,
+        "value": res["queries_per_s"],
         "unit": "queries/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": 1e3 * dt / args.steps,
+        "ms_per_step": res["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": "configs[%d] %s: N=%d R=%d d=%d h=%d B=%d K=%d%s, %s, gamma=%g"
-                   % (cfg.index, cfg.name, cfg.N, cfg.R, cfg.d, cfg.h, cfg.B, cfg.K,
-                      " d_sem=%d (bf16 text features)" % cfg.d_sem if cfg.d_sem else "",
-                      "box family (alpha=%g) on the 9 negation-free structures" % args.box_alpha if box
-                      else "14-structure mix" + (", candidate rows from a bf16 copy of E" if args.score_bf16 else ""),
-                      cfg.gamma),
+        "config": {"workload": res["workload"],
                    "contractions": "fp32 results; operands split exactly into three bf16 pieces, six partial products on "
-                                   "the bf16 MFMA with fp32 accumulation (fp32 MFMA for the small weight-gradient tiles)",
-                   "streams": streams,
+                                   "the bf16 MFMA with fp32 accumulation (fp32 MFMA for small weight-gradient tiles)",
+                   "streams": res["streams"],
                    "schedule": args.schedule if args.schedule == "level" else "max_fill, B_max=%s" % (args.bmax or "inf"),
-                   "steps_per_batch": pexp["n_levels"], "peak_live_outputs": pexp["peak_live"],
-                   "operator_outputs": pexp["n_slots"],
+                   "steps_per_batch": res["steps_per_batch"], "peak_live_outputs": res["peak_live_outputs"],
+                   "operator_outputs": res["operator_outputs"],
                    "step": ("ngdb_sampler_next + " if args.sampler else "") +
                            "ngdb_plan of batch t+1 on a second host thread while ngdb_train_step of batch t is enqueued",
                    "batches": "online sampler, %d threads" % args.sampler if args.sampler else
                               "%d pre-generated batches cycled" % N_BATCHES,
-                   "touched_entity_rows": touched},
-        "device_only": {"queries_per_s": cfg.B * args.steps / dt_dev, "ms_per_step": 1e3 * dt_dev / args.steps,
-                        "note": "same steps with plans prebuilt"},
-        "roofline": roofline,
+                   "touched_entity_rows": res["touched_entity_rows"]},
+        "device_only": res["device_only"],
+        "roofline": roofline_of(kern),
+        "roofline_note": "achieved = algorithmic work of the class per step / HIP-event time of its launches on their own "
+                         "stream (contractions on split operands: executed bf16 flops, six per fp32 product, against the "
+                         "bf16 matrix peak); traffic and profile.* come from the rocprofv3 summaries named in profile_files",
+        "profile_files": res["profile_files"],
         "cpu_baseline": cpu,
-        "kernel_classes_ms_per_step": {k: v[0] / args.steps for k, v in timing.items()},
+        "kernel_classes_ms_per_step": res["kernel_classes_ms_per_step"],
+        "other_workloads": other_workloads,
     }
     if copy_gbs is not None:
         out["copy_kernel_GBs"] = copy_gbs
