@@ -444,6 +444,14 @@ def measure_workload(cfg, args, kg, steps, warmup, box=False, streams=None):
         "peak_live_outputs": pexp["peak_live"], "operator_outputs": pexp["n_slots"],
         "kernel_classes_ms_per_step": {k: v[0] / steps for k, v in timing.items()},
         "profile_files": prof_files,
+        # activation memory of a forward-only pass (ngdb_score, ngdb_rank_answers) over this batch: one row
+        # per operator output and MLP row, against outputs reclaimed once their consumer has run (eager
+        # reference counting, Sec. 4.3) with the per-type MLP buffers holding one step at a time
+        "forward_only_activation_bytes": {
+            "one_row_per_output": 4 * (pexp["n_slots"] * cfg.d + (pexp["n_proj"] + pexp["n_int_rows"] + pexp["n_neg"])
+                                       * (cfg.d + cfg.h) + pexp["n_int_rows"] * cfg.d),
+            "reclaimed": 4 * (pexp["n_f_rows"] * cfg.d + int(pexp["f_step_rows"].sum()) * (cfg.d + cfg.h)
+                              + int(pexp["f_step_rows"][1]) * cfg.d)},
     }
     for p_ in plans:
         p_.free()
@@ -550,6 +558,7 @@ def main():
             "workload": ores["workload"], "queries_per_s": ores["queries_per_s"], "ms_per_step": ores["ms_per_step"],
             "steps": o_steps, "device_only": ores["device_only"], "streams": ores["streams"],
             "touched_entity_rows": ores["touched_entity_rows"],
+            "forward_only_activation_bytes": ores["forward_only_activation_bytes"],
             "kernels": {k: pick(v) for k, v in okern.items()}, "profile_files": ores["profile_files"]}
 
     copy_gbs = None
@@ -590,7 +599,8 @@ def main():
                            "ngdb_plan of batch t+1 on a second host thread while ngdb_train_step of batch t is enqueued",
                    "batches": "online sampler, %d threads" % args.sampler if args.sampler else
                               "%d pre-generated batches cycled" % N_BATCHES,
-                   "touched_entity_rows": res["touched_entity_rows"]},
+                   "touched_entity_rows": res["touched_entity_rows"],
+                   "forward_only_activation_bytes": res["forward_only_activation_bytes"]},
         "device_only": res["device_only"],
         "roofline": roofline_of(kern),
         "roofline_note": "achieved = algorithmic work of the class per step / HIP-event time of its launches on their own "

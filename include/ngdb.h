@@ -54,7 +54,8 @@
  *   - "device" pointers are HIP device memory owned by the caller (row-major,
  *     contiguous, 16-byte aligned); the library borrows them.  "host" pointers
  *     are ordinary memory, borrowed only for the duration of the call.
- *   - The library keeps a private device workspace that grows on demand.
+ *   - The library keeps a private device workspace that grows on demand, or is allocated once
+ *     by ngdb_create from declared maxima (ngdb_config.b_max_queries).
  *   - A stream argument is a hipStream_t passed as void*; NULL = the null
  *     stream.  Calls that take a stream are asynchronous with respect to the
  *     host unless stated otherwise.  One context must not be used from two
@@ -146,6 +147,19 @@ typedef struct ngdb_config {
                               kept current by ngdb_train_step: bind again after writing
                               to E from outside.  Vector family without text features
                               only; d a multiple of 8                                  */
+    /* Declared maxima (all 0: the workspace grows on demand, and a step with a larger batch than
+     * any before waits for the device, frees and allocates).  With b_max_queries > 0 ngdb_create
+     * allocates the whole workspace and four plan buffers for batches of at most b_max_queries
+     * queries with at most k_max negatives / candidates per query and at most
+     * max_nodes_per_query nodes per query after the removal of unions (0 = 12, enough for the
+     * patterns of Sec. 3.1); from then on ngdb_plan (with at most four plans alive),
+     * ngdb_train_step and ngdb_score in candidate mode make no device allocation, no free and
+     * never wait for the device, and a batch beyond the maxima is refused with NGDB_ERR_ARG.
+     * The all-entity ranking calls and ngdb_forward_backward still allocate what only they need
+     * on first use.                                                                           */
+    int32_t b_max_queries;
+    int32_t k_max;
+    int32_t max_nodes_per_query;
 } ngdb_config;
 
 /* A trainable tensor with its Adam moments (all device, fp32, same shape). */
@@ -196,7 +210,8 @@ typedef struct ngdb_query_batch {
  *    -1-entity; in_gslot = the same as a gradient row;
  *  - MLP rows: PROJ/NEG rank inside the type; INTER group: g_mlp_base + j*n + i;
  *  - relation gradient index: stable grouping by relation id of the projections
- *    in slot order, r_src = gradient row of the projection's input.            */
+ *    in slot order, r_src = gradient row of the projection's input;
+ *  - f_row: see below.                                                          */
 typedef struct ngdb_plan_view {
     int32_t n_queries, n_groups, n_levels, n_slots, n_anchor;
     int32_t n_proj, n_inter, n_neg, n_int_rows, n_roots, n_refs, n_r_uniq;
@@ -222,6 +237,15 @@ typedef struct ngdb_plan_view {
     const int32_t* r_uniq;       /* [n_r_uniq] */
     const int32_t* r_seg_off;    /* [n_r_uniq+1] */
     const int32_t* r_src;        /* [n_proj] */
+    /* Forward-only passes (ngdb_score, ngdb_rank_answers) reclaim an operator output as soon as its
+     * consumer has run (Sec. 4.3, eager reference counting): f_row[s] is the storage row of output
+     * slot s when, step by step, every output takes the lowest free row (in group and member order)
+     * and the rows of the outputs a step consumed are free again after it; roots keep theirs.
+     * n_f_rows = rows used = peak_live; f_step_rows = the most MLP rows one step needs per type
+     * (projection, intersection inputs, negation): what the per-step buffers of such a pass hold. */
+    int32_t n_f_rows;
+    int32_t f_step_rows[3];
+    const int32_t* f_row;        /* [n_slots] */
 } ngdb_plan_view;
 
 /* Device-side results of the last ngdb_forward_backward / ngdb_train_step on a
@@ -448,6 +472,10 @@ int ngdb_get_timing(ngdb_ctx_t* ctx, ngdb_timing* out, int reset);
 
 /* Synchronous device-to-host copy of `bytes` bytes (waits for the device). */
 int ngdb_copy_to_host(void* h_dst, const void* d_src, size_t bytes);
+
+/* Device allocations (hipMalloc / hipHostMalloc) this context has made so far, for tests of the
+ * declared maxima of ngdb_config.                                                              */
+int64_t ngdb_debug_alloc_count(const ngdb_ctx_t* ctx);
 
 int64_t ngdb_step_count(const ngdb_ctx_t* ctx);
 const char* ngdb_strerror(int code);

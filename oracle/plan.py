@@ -31,6 +31,8 @@ planner must reproduce it bit for bit):
     order), its source being the gradient row of the projection's input.
     Entity table: anchors (anchor order), then one per query for the positive,
     then B*K for the negatives in row-major order.
+ 8. Storage rows of a forward-only pass with outputs reclaimed as soon as their consumer has
+    run: see forward_rows.
 """
 import numpy as np
 
@@ -223,6 +225,44 @@ def build_plan(batch, schedule="level", b_max=0):
         anchor_ent=i32([nodes[g]["arg"] for g in anchors]),
         r_uniq=i32(r_uniq), r_seg_off=i32(r_seg_off), r_src=i32(r_src),
     )
+
+
+def forward_rows(plan):
+    """Rows of a forward-only pass under eager reference counting [Sec. 4.3, Reclaim(T): a tensor
+    is reclaimed as soon as every operator that consumes it has run; Alg. 1, DecrementRefCounts].
+
+    A forward-only pass (scoring, ranking) needs an operator's output only until its consumer has
+    run, so outputs share storage rows.  Canonical assignment (the HIP library's planner must
+    reproduce it bit for bit): the plan's steps in order; in a step every output takes, in group and
+    member order, the lowest free row (a new row if none is free); when the step has run, the rows
+    of the outputs it consumed are free again.  Roots have no consumer and keep their rows.
+    Returns (f_row [n_slots]: row of every output slot, number of rows used, and per operator type
+    (projection, intersection, negation) the most MLP rows any one step needs)."""
+    import heapq
+    n_slots, L = int(plan["n_slots"]), int(plan["n_levels"])
+    f_row = np.full(n_slots, -1, np.int64)
+    free, n_rows = [], 0
+    step_rows = np.zeros(3, np.int64)
+    lo = plan["lvl_off"]
+    for l in range(1, L + 1):
+        groups = range(int(lo[l]), int(lo[l + 1]))
+        rows_now = np.zeros(3, np.int64)
+        for g in groups:
+            n, k, t = int(plan["g_n"][g]), int(plan["g_nin"][g]), int(plan["g_type"][g])
+            rows_now[{OP_PROJ: 0, OP_INTER: 1, OP_NEG: 2}[t]] += n * (k if t == OP_INTER else 1)
+            for i in range(n):
+                if free:
+                    row = heapq.heappop(free)
+                else:
+                    row, n_rows = n_rows, n_rows + 1
+                f_row[int(plan["g_out_base"][g]) + i] = row
+        for g in groups:
+            n, k, ro = int(plan["g_n"][g]), int(plan["g_nin"][g]), int(plan["g_ref_off"][g])
+            for ref in plan["in_ref"][ro:ro + k * n]:
+                if ref >= 0:
+                    heapq.heappush(free, int(f_row[ref]))
+        step_rows = np.maximum(step_rows, rows_now)
+    return f_row.astype(np.int32), n_rows, step_rows.astype(np.int32)
 
 
 def segment_index(keys):

@@ -32,7 +32,8 @@ class Config(C.Structure):
     _fields_ = [("n_entities", C.c_int32), ("n_relations", C.c_int32), ("d", C.c_int32), ("h", C.c_int32),
                 ("d_sem", C.c_int32), ("num_streams", C.c_int32), ("gamma", C.c_float), ("lr", C.c_float),
                 ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float), ("schedule", C.c_int32),
-                ("b_max", C.c_int32), ("family", C.c_int32), ("box_alpha", C.c_float), ("score_bf16", C.c_int32)]
+                ("b_max", C.c_int32), ("family", C.c_int32), ("box_alpha", C.c_float), ("score_bf16", C.c_int32),
+                ("b_max_queries", C.c_int32), ("k_max", C.c_int32), ("max_nodes_per_query", C.c_int32)]
 
 
 class Tensor(C.Structure):
@@ -58,7 +59,8 @@ _PLAN_ARRAYS = ("lvl_off", "g_level", "g_type", "g_nin", "g_n", "g_out_base", "g
 
 
 class PlanView(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in _PLAN_COUNTS] + [(n, C.POINTER(C.c_int32)) for n in _PLAN_ARRAYS]
+    _fields_ = ([(n, C.c_int32) for n in _PLAN_COUNTS] + [(n, C.POINTER(C.c_int32)) for n in _PLAN_ARRAYS] +
+                [("n_f_rows", C.c_int32), ("f_step_rows", C.c_int32 * 3), ("f_row", C.POINTER(C.c_int32))])
 
 
 class GradView(C.Structure):
@@ -114,6 +116,7 @@ def load_library(path=LIB_PATH):
         "ngdb_get_timing": (C.c_int, [vp, C.POINTER(Timing), C.c_int]),
         "ngdb_copy_to_host": (C.c_int, [vp, vp, C.c_size_t]),
         "ngdb_step_count": (i64, [vp]),
+        "ngdb_debug_alloc_count": (i64, [vp]),
         "ngdb_strerror": (C.c_char_p, [C.c_int]),
         "ngdb_last_error": (C.c_char_p, [vp]),
     }
@@ -166,6 +169,10 @@ class Plan:
             cnt = sizes.get(n, out["n_groups"])
             p = getattr(v, n)
             out[n] = np.ctypeslib.as_array(p, shape=(cnt,)).copy() if cnt else np.zeros(0, np.int32)
+        out["n_f_rows"] = int(v.n_f_rows)
+        out["f_step_rows"] = np.asarray(list(v.f_step_rows), np.int32)
+        out["f_row"] = (np.ctypeslib.as_array(v.f_row, shape=(out["n_slots"],)).copy() if out["n_slots"]
+                        else np.zeros(0, np.int32))
         return out
 
     def free(self):
@@ -331,7 +338,7 @@ class Engine:
 
     def __init__(self, n_entities, n_relations, d, h, gamma, lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8,
                  d_sem=0, num_streams=1, device="cuda:0", schedule=SCHED_LEVEL, b_max=0, family=FAMILY_VEC,
-                 box_alpha=0.02, score_bf16=False):
+                 box_alpha=0.02, score_bf16=False, b_max_queries=0, k_max=0, max_nodes_per_query=0):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("libngdb needs a GPU; there is no CPU path")
@@ -339,7 +346,8 @@ class Engine:
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
         self.cfg = Config(n_entities, n_relations, d, h, d_sem, num_streams, gamma, lr, beta1, beta2, eps,
-                          int(schedule), int(b_max), int(family), float(box_alpha), int(bool(score_bf16)))
+                          int(schedule), int(b_max), int(family), float(box_alpha), int(bool(score_bf16)),
+                          int(b_max_queries), int(k_max), int(max_nodes_per_query))
         self.ctx = C.c_void_p()
         _check(lib().ngdb_create(C.byref(self.cfg), C.byref(self.ctx)), None)
         self.tensors = {}
@@ -533,6 +541,10 @@ class Engine:
                                        n_take.data_ptr() if n_take is not None else None, B, out.data_ptr(), st),
                self.ctx)
         return ranks[:n_ans], dist[:n_ans], out
+
+    def alloc_count(self):
+        """Device allocations the context has made so far (ngdb_debug_alloc_count)."""
+        return int(lib().ngdb_debug_alloc_count(self.ctx))
 
     def step_count(self):
         return int(lib().ngdb_step_count(self.ctx))

@@ -57,6 +57,8 @@ struct ngdb_plan_s {
     const int32_t *d_in_ref = nullptr, *d_in_gslot = nullptr, *d_rel = nullptr, *d_root_off = nullptr,
                   *d_root_slot = nullptr, *d_pos = nullptr, *d_ekeys_head = nullptr, *d_r_uniq = nullptr,
                   *d_r_seg_off = nullptr, *d_r_src = nullptr, *d_r_rec = nullptr, *d_n_r_uniq = nullptr;
+    // forward-only passes with reclaimed outputs: references, output rows and root rows in storage rows
+    const int32_t *d_f_in_ref = nullptr, *d_f_row = nullptr, *d_f_root = nullptr;
     std::vector<std::vector<Segment>> levels;   // levels[l] for l = 1..n_levels (index 0 unused)
     int32_t n_entities = 0;
 };
@@ -65,6 +67,8 @@ struct ngdb_ctx_s {
     ngdb_config cfg{};
     ngdb_params prm{};
     bool bound = false;
+    bool presized = false;          // workspace allocated once from declared maxima: steps must not grow it
+    int64_t n_alloc = 0;            // device / pinned allocations made so far
     int64_t step = 0;
     std::string err;
     hipStream_t side[1]{};          // library stream (num_streams > 1)
@@ -169,8 +173,13 @@ struct Timed {
 // One grouped contraction launch, bracketed as class `cls`.
 int gemm_timed(ngdb_ctx_t* c, int cls, const GemmArgs* g, int n, hipStream_t s);
 
-int ensure(ngdb_ctx_t* c, DevBuf& b, size_t bytes) {
+// evaluation: a buffer only the ranking calls or ngdb_forward_backward use (allocated on first use
+// also under declared maxima)
+int ensure(ngdb_ctx_t* c, DevBuf& b, size_t bytes, bool evaluation = false) {
     if (bytes <= b.cap) return NGDB_OK;
+    if (c->presized && !evaluation)
+        return fail(c, NGDB_ERR_ARG, "the batch needs more workspace than the maxima declared at ngdb_create allow "
+                                     "(b_max_queries, k_max, max_nodes_per_query)");
     // growing: nothing may still be using the old allocation
     HIPCHK(c, hipDeviceSynchronize());
     if (b.p) HIPCHK(c, hipFree(b.p));
@@ -178,6 +187,7 @@ int ensure(ngdb_ctx_t* c, DevBuf& b, size_t bytes) {
     b.cap = 0;
     const size_t want = bytes + bytes / 4 + 256;
     HIPCHK(c, hipMalloc(&b.p, want));
+    ++c->n_alloc;
     b.cap = want;
     return NGDB_OK;
 }
@@ -212,6 +222,10 @@ MlpRefs mlp_of(const ngdb_params& p, int t) {
 }
 // order of ngdb_grad_view::g_mlp: W1 b1 W2 b2 | V1 c1 V2 c2 | U1 u1 U2 u2
 int gslot_of(int t) { return t == T_PROJ ? 0 : (t == T_NEG ? 4 : 8); }
+
+struct FwdBytes;
+FwdBytes forward_bytes(const ngdb_ctx_t* c, const ngdb_plan_t* pl, bool reclaim);
+int size_forward_only(ngdb_ctx_t* c, const ngdb_plan_t* pl, int64_t n_tail);
 
 int size_workspace(ngdb_ctx_t* c, const ngdb_plan_t* pl, int K, bool want_table_grads) {
     const HostPlan& hp = pl->hp;
@@ -287,9 +301,9 @@ int size_workspace(ngdb_ctx_t* c, const ngdb_plan_t* pl, int K, bool want_table_
     }
     if (want_table_grads) {
         const size_t urows = (size_t)std::min<int64_t>(nk, c->cfg.n_entities);
-        ENS(c->gE, urows * d * f);
-        ENS(c->gR, (size_t)std::max<size_t>(hp.r_uniq.size(), 1) * d * f);
-        if (box) ENS(c->gRo, (size_t)std::max<size_t>(hp.r_uniq.size(), 1) * d * f);
+        if ((rc = ensure(c, c->gE, urows * d * f, true)) != NGDB_OK) return rc;
+        if ((rc = ensure(c, c->gR, (size_t)std::max<size_t>(hp.r_uniq.size(), 1) * d * f, true)) != NGDB_OK) return rc;
+        if (box && (rc = ensure(c, c->gRo, (size_t)std::max<size_t>(hp.r_uniq.size(), 1) * d * f, true)) != NGDB_OK) return rc;
     }
 #undef ENS
     return NGDB_OK;
@@ -308,7 +322,7 @@ struct EntRows {
 // of its distinct entities and the references into them.  The index is left in the context's
 // buffers; *e_src receives the sorted contribution numbers.
 int prepare_entities(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_tail, int64_t n_tail, hipStream_t s_idx,
-                     hipStream_t stream, int32_t** e_src, EntRows* er) {
+                     hipStream_t stream, int32_t** e_src, EntRows* er, bool reclaim = false) {
     const HostPlan& hp = pl->hp;
     const int B = hp.n_queries, d = c->cfg.d, ds = c->cfg.d_sem;
     IndexBuffers ib{ptr<int32_t>(c->keys_a), ptr<int32_t>(c->keys_b), ptr<int32_t>(c->vals_a),
@@ -320,7 +334,7 @@ int prepare_entities(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_tail
                                       s_idx));
     }
     if (ds == 0) {
-        *er = EntRows{c->prm.E.p, pl->d_in_ref, pl->d_pos, d_tail};
+        *er = EntRows{c->prm.E.p, reclaim ? pl->d_f_in_ref : pl->d_in_ref, pl->d_pos, d_tail};
         return NGDB_OK;
     }
     // s_idx == stream in this mode: everything below needs the index
@@ -334,7 +348,7 @@ int prepare_entities(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_tail
     fa.n_rows_dev = ptr<int32_t>(c->n_uniq); fa.n_rows = (int)std::min<int64_t>(n_contrib, c->cfg.n_entities);
     fa.d = d; fa.ds = ds; fa.out = ptr<float>(c->Ef);
     HIPCHK(c, launch_sem_fuse(fa, stream));
-    HIPCHK(c, launch_translate_refs(pl->d_in_ref, pl->d_in_gslot, (int)hp.in_ref.size(), hp.n_slots,
+    HIPCHK(c, launch_translate_refs(reclaim ? pl->d_f_in_ref : pl->d_in_ref, pl->d_in_gslot, (int)hp.in_ref.size(), hp.n_slots,
                                     ptr<int32_t>(c->inv), ptr<int32_t>(c->refs_sem), stream));
     *er = EntRows{ptr<float>(c->Ef), ptr<int32_t>(c->refs_sem), ptr<int32_t>(c->inv) + hp.n_anchor,
                   ptr<int32_t>(c->inv) + hp.n_anchor + B};
@@ -454,15 +468,70 @@ int enqueue_forward_box(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t s) {
 
 // Device memory the forward pass of the vector family writes: operator outputs by slot, and per
 // type the gathered first-layer inputs, the hidden rows and (intersections) the logits.
+// reclaim (forward-only passes, Sec. 4.3 eager reference counting): an output is kept only until
+// its consumer has run -- act holds n_f_rows storage rows addressed through the plan's f_row map,
+// and Z / H / Att hold the rows of one step at a time (sizes: forward_bytes).
 struct FwdSpace {
     float* act;
     float* Z[3];
     float* H[3];
     float* Att;
+    bool reclaim;
 };
-FwdSpace ctx_space(const ngdb_ctx_t* c) {
+FwdSpace ctx_space(const ngdb_ctx_t* c, bool reclaim = false) {
     return FwdSpace{ptr<float>(c->act), {ptr<float>(c->Z[0]), ptr<float>(c->Z[1]), ptr<float>(c->Z[2])},
-                    {ptr<float>(c->H[0]), ptr<float>(c->H[1]), ptr<float>(c->H[2])}, ptr<float>(c->Att)};
+                    {ptr<float>(c->H[0]), ptr<float>(c->H[1]), ptr<float>(c->H[2])}, ptr<float>(c->Att), reclaim};
+}
+// Bytes of the buffers of a forward-only pass, in the order act, Att, then Z and H per type.
+struct FwdBytes { size_t act, att, z[3], h[3]; };
+FwdBytes forward_bytes(const ngdb_ctx_t* c, const ngdb_plan_t* pl, bool reclaim) {
+    const HostPlan& hp = pl->hp;
+    const size_t d = c->cfg.d, h = c->cfg.h, f = sizeof(float);
+    const size_t all[3] = {(size_t)hp.n_proj, (size_t)hp.n_int_rows, (size_t)hp.n_neg};
+    FwdBytes b{};
+    b.act = (size_t)(reclaim ? hp.n_f_rows : hp.n_slots) * d * f;
+    for (int t = 0; t < 3; ++t) {
+        const size_t rows = reclaim ? (size_t)hp.f_step_rows[t] : all[t];
+        b.z[t] = rows * d * f;
+        b.h[t] = rows * h * f;
+        if (t == T_INTER) b.att = rows * d * f;
+    }
+    return b;
+}
+
+// Workspace of a forward-only pass of the vector family: the activation buffers at their
+// reclaimed sizes; with text features also the index over [anchors | tail] and the fused rows.
+int size_forward_only(ngdb_ctx_t* c, const ngdb_plan_t* pl, int64_t n_tail) {
+    const HostPlan& hp = pl->hp;
+    const FwdBytes fb = forward_bytes(c, pl, true);
+    int rc;
+#define ENS(buf, bytes) if ((rc = ensure(c, buf, std::max<size_t>((bytes), 256))) != NGDB_OK) return rc
+    ENS(c->act, fb.act);
+    ENS(c->Att, fb.att);
+    for (int t = 0; t < 3; ++t) {
+        ENS(c->Z[t], fb.z[t]);
+        ENS(c->H[t], fb.h[t]);
+    }
+    if (c->cfg.d_sem > 0) {
+        const size_t d = c->cfg.d, ds = c->cfg.d_sem;
+        const int64_t nk = (int64_t)hp.n_anchor + hp.n_queries + n_tail;
+        const size_t urows = (size_t)std::min<int64_t>(nk, c->cfg.n_entities);
+        ENS(c->keys_a, (size_t)nk * 4);
+        ENS(c->keys_b, (size_t)nk * 4);
+        ENS(c->vals_a, (size_t)nk * 4);
+        ENS(c->vals_b, (size_t)nk * 4);
+        ENS(c->uniq, (size_t)nk * 4);
+        ENS(c->seg_off, ((size_t)nk + 1) * 4);
+        ENS(c->hist, index_hist_elems(nk) * 4);
+        ENS(c->scan_tmp, index_scan_tmp_elems(nk) * 4);
+        ENS(c->n_uniq, 256);
+        ENS(c->Wb, d * ds * sizeof(uint16_t));
+        ENS(c->Ef, urows * d * sizeof(float));
+        ENS(c->inv, (size_t)nk * 4);
+        ENS(c->refs_sem, hp.in_ref.size() * 4);
+    }
+#undef ENS
+    return NGDB_OK;
 }
 
 // forward over the plan's frontiers; results in w.act.  The type segments of one
@@ -476,8 +545,10 @@ int enqueue_forward(ngdb_ctx_t* c, const ngdb_plan_t* pl, const EntRows& er, hip
         int n = 0;
         for (const Segment& sg : segs) {
             const MlpRefs W = mlp_of(c->prm, sg.type);
-            float* Z = w.Z[sg.type] + (size_t)sg.mlp_base * d;
-            float* Hh = w.H[sg.type] + (size_t)sg.mlp_base * h;
+            // (with reclaimed outputs the per-type buffers hold this step's rows only)
+            const size_t row0 = w.reclaim ? 0 : (size_t)sg.mlp_base;
+            float* Z = w.Z[sg.type] + row0 * d;
+            float* Hh = w.H[sg.type] + row0 * h;
             GemmArgs& a = g1[n];
             // first layer reads its rows through the plan's references and leaves a copy in Z
             a.a_ref = er.refs + sg.ref_off; a.a_base0 = w.act; a.a_base1 = er.rows;
@@ -486,7 +557,14 @@ int enqueue_forward(ngdb_ctx_t* c, const ngdb_plan_t* pl, const EntRows& er, hip
             a.M = sg.rows; a.N = h; a.K = d; a.bias = W.ba; a.relu = true;
             GemmArgs& b = g2[n];
             b.A = Hh; b.lda = h; b.B = W.Wb; b.ldb = h; b.M = sg.rows; b.N = d; b.K = h; b.bias = W.bb; b.ldc = d;
-            b.C = sg.type == T_INTER ? w.Att + (size_t)sg.mlp_base * d : w.act + (size_t)sg.out_base * d;
+            if (sg.type == T_INTER) {
+                b.C = w.Att + row0 * d;
+            } else if (w.reclaim) {         // outputs go to their storage rows
+                b.C = w.act;
+                b.dst_row = pl->d_f_row + sg.out_base;
+            } else {
+                b.C = w.act + (size_t)sg.out_base * d;
+            }
             ++n;
         }
         int rc_g;
@@ -498,11 +576,16 @@ int enqueue_forward(ngdb_ctx_t* c, const ngdb_plan_t* pl, const EntRows& er, hip
             InterJobs ij{};
             ij.d = d;
             for (int g = sg.g_lo; g < sg.g_hi; ++g) {
-                const size_t mb = (size_t)pl->hp.g_mlp_base[g] * d;
+                const size_t mb = (size_t)(pl->hp.g_mlp_base[g] - (w.reclaim ? sg.mlp_base : 0)) * d;
                 if (ij.count == INTER_MAX_JOBS) return fail(c, NGDB_ERR_UNSUPPORTED, "too many intersection classes in one level");
                 InterJob& jb = ij.job[ij.count++];
                 jb.X = w.Z[T_INTER] + mb; jb.Att = w.Att + mb;
-                jb.out = w.act + (size_t)pl->hp.g_out_base[g] * d;
+                if (w.reclaim) {
+                    jb.out = w.act;
+                    jb.out_row = pl->d_f_row + pl->hp.g_out_base[g];
+                } else {
+                    jb.out = w.act + (size_t)pl->hp.g_out_base[g] * d;
+                }
                 jb.n = pl->hp.g_n[g]; jb.k = pl->hp.g_nin[g];
             }
             HIPCHK(c, launch_inter(ij, false, s));
@@ -691,6 +774,8 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
         return fail(c, NGDB_ERR_ARG, "plan belongs to another configuration or was built without a device");
     const HostPlan& hp = pl->hp;
     const int d = c->cfg.d, B = hp.n_queries;
+    if (c->presized && (K > c->cfg.k_max || B > c->cfg.b_max_queries))
+        return fail(c, NGDB_ERR_ARG, "batch beyond the maxima declared at ngdb_create (b_max_queries, k_max)");
     c->have_grads = false;
     int rc = size_workspace(c, pl, K, !apply);
     if (rc != NGDB_OK) return rc;
@@ -865,6 +950,46 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
     return NGDB_OK;
 }
 
+bool new_blob(ngdb_ctx_t* c, size_t cap, PlanBlob* pb) {
+    pb->cap = cap;
+    if (hipMalloc((void**)&pb->dev, cap * 4) != hipSuccess ||
+        hipHostMalloc((void**)&pb->pinned, cap * 4, hipHostMallocDefault) != hipSuccess ||
+        hipEventCreateWithFlags(&pb->last_use, hipEventDisableTiming) != hipSuccess) {
+        if (pb->dev) (void)hipFree(pb->dev);
+        if (pb->pinned) (void)hipHostFree(pb->pinned);
+        *pb = PlanBlob{};
+        return false;
+    }
+    c->n_alloc += 2;
+    return true;
+}
+
+// The whole workspace and four plan buffers for the largest batch the configuration declares
+// (b_max_queries queries of at most max_nodes_per_query nodes, k_max negatives): every count a plan
+// can reach is bounded by the number of nodes.
+int presize(ngdb_ctx_t* c) {
+    const size_t B = (size_t)c->cfg.b_max_queries, cap = B * (size_t)c->cfg.max_nodes_per_query;
+    if (cap > (size_t)INT32_MAX / 4 || B * ((size_t)c->cfg.k_max + 1) > (size_t)INT32_MAX)
+        return fail(c, NGDB_ERR_ARG, "declared maxima too large");
+    ngdb_plan_s most;
+    HostPlan& hp = most.hp;
+    hp.n_queries = (int32_t)B;
+    hp.n_slots = hp.n_anchor = hp.n_proj = hp.n_int_rows = hp.n_neg = hp.n_roots = (int32_t)cap;
+    hp.n_f_rows = (int32_t)cap;
+    for (int t = 0; t < 3; ++t) hp.f_step_rows[t] = (int32_t)cap;
+    hp.in_ref.resize(cap);
+    int rc = size_workspace(c, &most, c->cfg.k_max, false);
+    if (rc != NGDB_OK) return rc;
+    const size_t blob_cap = 10 * cap + 4 * B + 2 * (size_t)std::min<size_t>(cap, c->cfg.n_relations) + 256;
+    for (int i = 0; i < 4; ++i) {
+        PlanBlob pb;
+        if (!new_blob(c, blob_cap, &pb)) return fail(c, NGDB_ERR_OOM, "allocation of the plan buffers failed");
+        c->blob_pool.push_back(pb);
+    }
+    c->presized = true;
+    return NGDB_OK;
+}
+
 // Device address of the scratch array on the current GPU (looked up on first use per device).
 hipError_t noalloc_scratch(unsigned char** out) {
     int dev = -1;
@@ -900,9 +1025,13 @@ int ngdb_create(const ngdb_config* cfg, ngdb_ctx_t** out) {
         return NGDB_ERR_ARG;
     if ((cfg->score_bf16 != 0 && cfg->score_bf16 != 1) || (cfg->score_bf16 && (cfg->family != NGDB_FAMILY_VEC || cfg->d_sem != 0 || (cfg->d & 7))))
         return NGDB_ERR_ARG;
+    if (cfg->b_max_queries < 0 || cfg->k_max < 0 || cfg->max_nodes_per_query < 0 ||
+        (cfg->b_max_queries > 0 && cfg->k_max < 1) || (cfg->b_max_queries == 0 && (cfg->k_max || cfg->max_nodes_per_query)))
+        return NGDB_ERR_ARG;
     ngdb_ctx_t* c = new (std::nothrow) ngdb_ctx_s();
     if (!c) return NGDB_ERR_OOM;
     c->cfg = *cfg;
+    if (c->cfg.b_max_queries > 0 && c->cfg.max_nodes_per_query == 0) c->cfg.max_nodes_per_query = 12;
     c->n_side = cfg->num_streams > 1 ? 1 : 0;
     bool ok = true;
     if (c->n_side) ok = hipStreamCreateWithFlags(&c->side[0], hipStreamNonBlocking) == hipSuccess;
@@ -914,6 +1043,13 @@ int ngdb_create(const ngdb_config* cfg, ngdb_ctx_t** out) {
     if (!ok) {
         ngdb_destroy(c);
         return NGDB_ERR_HIP;
+    }
+    if (c->cfg.b_max_queries > 0) {
+        const int rc = presize(c);
+        if (rc != NGDB_OK) {
+            ngdb_destroy(c);
+            return rc;
+        }
     }
     *out = c;
     return NGDB_OK;
@@ -974,7 +1110,7 @@ int ngdb_bind_params(ngdb_ctx_t* c, const ngdb_params* p) {
     if (p->step < 0) return fail(c, NGDB_ERR_ARG, "negative step count");
     if (c->cfg.score_bf16) {   // the bf16 copy of the entity table
         const size_t n = (size_t)c->cfg.n_entities * c->cfg.d;
-        int rc = ensure(c, c->Eb, n * sizeof(uint16_t));
+        int rc = ensure(c, c->Eb, n * sizeof(uint16_t), true);
         if (rc != NGDB_OK) return rc;
         HIPCHK(c, launch_cast_bf16(p->E.p, ptr<uint16_t>(c->Eb), (int64_t)n, nullptr));
         HIPCHK(c, hipDeviceSynchronize());
@@ -1045,6 +1181,11 @@ int ngdb_plan(ngdb_ctx_t* c, const ngdb_query_batch* qb, ngdb_plan_t** out) {
     int rc = plan_host(qb, c->cfg.n_entities, c->cfg.n_relations, c->cfg.schedule, c->cfg.b_max, &pl, err);
     if (rc != NGDB_OK) return fail(c, rc, err);
     HostPlan& hp = pl->hp;
+    if (c->presized && (hp.n_queries > c->cfg.b_max_queries ||
+                        (size_t)hp.n_slots + hp.n_anchor > (size_t)c->cfg.b_max_queries * c->cfg.max_nodes_per_query)) {
+        delete pl;
+        return fail(c, NGDB_ERR_ARG, "batch beyond the maxima declared at ngdb_create (b_max_queries, max_nodes_per_query)");
+    }
     if (c->cfg.family == NGDB_FAMILY_BOX) {
         bool ok = hp.n_neg == 0;
         for (int g = 0; g < hp.n_groups && ok; ++g) {
@@ -1075,6 +1216,10 @@ int ngdb_plan(ngdb_ctx_t* c, const ngdb_query_batch* qb, ngdb_plan_t** out) {
                  o_rs = put(hp.root_slot), o_pos = put(hp.pos), o_ek = put(ekeys), o_ru = put(hp.r_uniq),
                  o_rso = put(hp.r_seg_off), o_rsrc = put(hp.r_src), o_rrec = put(r_rec),
                  o_nru = put(std::vector<int32_t>{(int32_t)hp.r_uniq.size()});
+    std::vector<int32_t> f_in_ref(hp.in_ref.size()), f_root(hp.root_slot.size());
+    for (size_t i = 0; i < f_in_ref.size(); ++i) f_in_ref[i] = hp.in_ref[i] >= 0 ? hp.f_row[hp.in_ref[i]] : hp.in_ref[i];
+    for (size_t i = 0; i < f_root.size(); ++i) f_root[i] = hp.f_row[hp.root_slot[i]];
+    const size_t o_fref = put(f_in_ref), o_frow = put(hp.f_row), o_froot = put(f_root);
     // a recycled blob (its last reader has finished) or a new one
     PlanBlob pb;
     {
@@ -1087,12 +1232,12 @@ int ngdb_plan(ngdb_ctx_t* c, const ngdb_query_batch* qb, ngdb_plan_t** out) {
             }
     }
     if (!pb.dev) {
-        pb.cap = blob.size() + blob.size() / 2 + 1024;
-        if (hipMalloc((void**)&pb.dev, pb.cap * 4) != hipSuccess ||
-            hipHostMalloc((void**)&pb.pinned, pb.cap * 4, hipHostMallocDefault) != hipSuccess ||
-            hipEventCreateWithFlags(&pb.last_use, hipEventDisableTiming) != hipSuccess) {
-            if (pb.dev) (void)hipFree(pb.dev);
-            if (pb.pinned) (void)hipHostFree(pb.pinned);
+        bool ok;
+        {
+            std::lock_guard<std::mutex> lk(c->mu);     // (the allocation counter)
+            ok = new_blob(c, blob.size() + blob.size() / 2 + 1024, &pb);
+        }
+        if (!ok) {
             delete pl;
             return fail(c, NGDB_ERR_OOM, "allocation for the plan failed");
         }
@@ -1121,6 +1266,7 @@ int ngdb_plan(ngdb_ctx_t* c, const ngdb_query_batch* qb, ngdb_plan_t** out) {
     pl->d_root_off = pl->d_blob + o_ro; pl->d_root_slot = pl->d_blob + o_rs; pl->d_pos = pl->d_blob + o_pos;
     pl->d_ekeys_head = pl->d_blob + o_ek; pl->d_r_uniq = pl->d_blob + o_ru; pl->d_r_seg_off = pl->d_blob + o_rso;
     pl->d_r_src = pl->d_blob + o_rsrc; pl->d_r_rec = pl->d_blob + o_rrec; pl->d_n_r_uniq = pl->d_blob + o_nru;
+    pl->d_f_in_ref = pl->d_blob + o_fref; pl->d_f_row = pl->d_blob + o_frow; pl->d_f_root = pl->d_blob + o_froot;
     *out = pl;
     return NGDB_OK;
 }
@@ -1140,6 +1286,9 @@ int ngdb_plan_export(const ngdb_plan_t* pl, ngdb_plan_view* v) {
     v->root_off = hp.root_off.data(); v->root_slot = hp.root_slot.data(); v->anchor_ent = hp.anchor_ent.data();
     v->pos = hp.pos.data(); v->r_uniq = hp.r_uniq.data(); v->r_seg_off = hp.r_seg_off.data();
     v->r_src = hp.r_src.data();
+    v->n_f_rows = hp.n_f_rows;
+    for (int k = 0; k < 3; ++k) v->f_step_rows[k] = hp.f_step_rows[k];
+    v->f_row = hp.f_row.data();
     return NGDB_OK;
 }
 
@@ -1187,19 +1336,26 @@ int ngdb_score(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_cand, int3
     }
     c->have_grads = false;
     const bool sem = c->cfg.d_sem > 0;
-    int rc = size_workspace(c, pl, d_cand ? C : 0, false);
+    // forward only: an operator output is reclaimed as soon as its consumer has run (Sec. 4.3);
+    // the box family keeps one row per output
+    const bool reclaim = c->cfg.family == NGDB_FAMILY_VEC;
+    const int64_t n_tail = d_cand ? (int64_t)pl->hp.n_queries * C : 0;
+    if (c->presized && d_cand && C > c->cfg.k_max)
+        return fail(c, NGDB_ERR_ARG, "more candidates per query than the k_max declared at ngdb_create");
+    int rc = reclaim ? size_forward_only(c, pl, n_tail) : size_workspace(c, pl, d_cand ? C : 0, false);
     if (rc != NGDB_OK) return rc;
-    EntRows er{c->prm.E.p, pl->d_in_ref, pl->d_pos, d_cand};
+    const int32_t* roots = reclaim ? pl->d_f_root : pl->d_root_slot;
+    EntRows er{c->prm.E.p, reclaim ? pl->d_f_in_ref : pl->d_in_ref, pl->d_pos, d_cand};
     if (sem) {   // fused rows of the anchors (and candidates) first
         int32_t* e_src = nullptr;
-        rc = prepare_entities(c, pl, d_cand, d_cand ? (int64_t)pl->hp.n_queries * C : 0, s, s, &e_src, &er);
+        rc = prepare_entities(c, pl, d_cand, n_tail, s, s, &e_src, &er, reclaim);
         if (rc != NGDB_OK) return rc;
     }
-    rc = enqueue_forward(c, pl, er, s, ctx_space(c));
+    rc = enqueue_forward(c, pl, er, s, ctx_space(c, reclaim));
     if (rc != NGDB_OK) return rc;
     if (d_cand) {
         ScoreArgs sa{};
-        sa.act = ptr<float>(c->act); sa.E = er.rows; sa.root_off = pl->d_root_off; sa.root_slot = pl->d_root_slot;
+        sa.act = ptr<float>(c->act); sa.E = er.rows; sa.root_off = pl->d_root_off; sa.root_slot = roots;
         sa.pos = nullptr; sa.cand = er.cand; sa.B = pl->hp.n_queries; sa.C = C; sa.d = c->cfg.d;
         sa.max_branch = std::max(1, pl->hp.max_branch); sa.gamma = c->cfg.gamma; sa.score = d_scores;
         if (c->cfg.family == NGDB_FAMILY_BOX) { sa.off = ptr<float>(c->off); sa.alpha = c->cfg.box_alpha; }
@@ -1214,10 +1370,10 @@ int ngdb_score(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_cand, int3
         const float* box_off = c->cfg.family == NGDB_FAMILY_BOX ? ptr<float>(c->off) : nullptr;
         const int chunk = std::min(N, 1 << 16);
         const int ld = (chunk + 3) & ~3;
-        rc = ensure(c, c->rank_dist, std::max<size_t>((size_t)R * ld * sizeof(float), 256));
+        rc = ensure(c, c->rank_dist, std::max<size_t>((size_t)R * ld * sizeof(float), 256), true);
         if (rc != NGDB_OK) return rc;
         if (sem) {
-            rc = ensure(c, c->rank_ef, (size_t)chunk * d * sizeof(float));
+            rc = ensure(c, c->rank_ef, (size_t)chunk * d * sizeof(float), true);
             if (rc != NGDB_OK) return rc;
         }
         Timed tm(c, NGDB_TK_SCORE, s);
@@ -1231,7 +1387,7 @@ int ngdb_score(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_cand, int3
                 HIPCHK(c, launch_sem_fuse(fa, s));
                 rows = ptr<float>(c->rank_ef);
             }
-            HIPCHK(c, launch_l1_tile(ptr<float>(c->act), box_off, c->cfg.box_alpha, pl->d_root_slot, R, rows, nullptr, cnt, d,
+            HIPCHK(c, launch_l1_tile(ptr<float>(c->act), box_off, c->cfg.box_alpha, roots, R, rows, nullptr, cnt, d,
                                      ptr<float>(c->rank_dist), ld, s,
                                      c->cfg.score_bf16 ? ptr<uint16_t>(c->Eb) + (size_t)e0 * d : nullptr));
             HIPCHK(c, launch_topk_merge(ptr<float>(c->rank_dist), ld, pl->d_root_off, pl->hp.n_queries, e0, cnt, topk,
@@ -1244,12 +1400,10 @@ int ngdb_score(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_cand, int3
 
 size_t ngdb_score_noalloc_bytes(const ngdb_ctx_t* c, const ngdb_plan_t* pl) {
     if (!c || !pl) return 0;
-    const HostPlan& hp = pl->hp;
-    const size_t d = c->cfg.d, h = c->cfg.h, f = sizeof(float);
-    const size_t rows[3] = {(size_t)hp.n_proj, (size_t)hp.n_int_rows, (size_t)hp.n_neg};
+    const FwdBytes fb = forward_bytes(c, pl, true);
     auto up = [](size_t b) { return (b + 255) & ~size_t(255); };
-    size_t need = up((size_t)hp.n_slots * d * f) + up(rows[T_INTER] * d * f);
-    for (int t = 0; t < 3; ++t) need += up(rows[t] * d * f) + up(rows[t] * h * f);
+    size_t need = up(fb.act) + up(fb.att);
+    for (int t = 0; t < 3; ++t) need += up(fb.z[t]) + up(fb.h[t]);
     return need;
 }
 
@@ -1269,12 +1423,12 @@ int ngdb_score_noalloc(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_ca
                                          std::to_string(NOALLOC_BYTES) + " (NGDB_NOALLOC_SCRATCH_MIB)");
     unsigned char* base = nullptr;
     HIPCHK(c, noalloc_scratch(&base));
-    // carve the forward buffers out of the scratch; every row that is read was written earlier in
-    // this call (operator outputs before their consumers, copies and hidden rows by the launch
-    // before the one that reads them), so nothing has to be cleared
+    // carve the forward buffers out of the scratch (outputs reclaimed once their consumer has run,
+    // per-step buffers: as in ngdb_score); every row that is read was written earlier in this call
+    // (operator outputs before their consumers, copies and hidden rows by the launch before the
+    // one that reads them), so nothing has to be cleared
     const HostPlan& hp = pl->hp;
-    const size_t d = c->cfg.d, h = c->cfg.h, f = sizeof(float);
-    const size_t rows[3] = {(size_t)hp.n_proj, (size_t)hp.n_int_rows, (size_t)hp.n_neg};
+    const FwdBytes fb = forward_bytes(c, pl, true);
     size_t at = 0;
     auto take = [&](size_t bytes) {
         float* p = reinterpret_cast<float*>(base + at);
@@ -1282,21 +1436,22 @@ int ngdb_score_noalloc(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_ca
         return p;
     };
     FwdSpace w{};
-    w.act = take((size_t)hp.n_slots * d * f);
-    w.Att = take(rows[T_INTER] * d * f);
+    w.reclaim = true;
+    w.act = take(fb.act);
+    w.Att = take(fb.att);
     for (int t = 0; t < 3; ++t) {
-        w.Z[t] = take(rows[t] * d * f);
-        w.H[t] = take(rows[t] * h * f);
+        w.Z[t] = take(fb.z[t]);
+        w.H[t] = take(fb.h[t]);
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
     c->have_grads = false;
     const uint32_t timing = c->timing_mask;     // event brackets would create events: off for this call
     c->timing_mask = 0;
-    const EntRows er{c->prm.E.p, pl->d_in_ref, pl->d_pos, d_cand};
+    const EntRows er{c->prm.E.p, pl->d_f_in_ref, pl->d_pos, d_cand};
     int rc = enqueue_forward(c, pl, er, s, w);
     if (rc == NGDB_OK) {
         ScoreArgs sa{};
-        sa.act = w.act; sa.E = er.rows; sa.root_off = pl->d_root_off; sa.root_slot = pl->d_root_slot;
+        sa.act = w.act; sa.E = er.rows; sa.root_off = pl->d_root_off; sa.root_slot = pl->d_f_root;
         sa.pos = nullptr; sa.cand = d_cand; sa.B = hp.n_queries; sa.C = C; sa.d = c->cfg.d;
         sa.max_branch = std::max(1, hp.max_branch); sa.gamma = c->cfg.gamma; sa.score = d_scores;
         if (c->cfg.score_bf16) sa.E16 = ptr<uint16_t>(c->Eb);
@@ -1322,25 +1477,27 @@ int ngdb_rank_answers(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_ans
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool sem = c->cfg.d_sem > 0;
     c->have_grads = false;
-    int rc = size_workspace(c, pl, 0, false);
+    const bool reclaim = c->cfg.family == NGDB_FAMILY_VEC;     // as in ngdb_score
+    int rc = reclaim ? size_forward_only(c, pl, 0) : size_workspace(c, pl, 0, false);
     if (rc != NGDB_OK) return rc;
-    EntRows er{c->prm.E.p, pl->d_in_ref, pl->d_pos, nullptr};
+    const int32_t* roots = reclaim ? pl->d_f_root : pl->d_root_slot;
+    EntRows er{c->prm.E.p, reclaim ? pl->d_f_in_ref : pl->d_in_ref, pl->d_pos, nullptr};
     if (sem) {
         int32_t* e_src = nullptr;
-        rc = prepare_entities(c, pl, nullptr, 0, s, s, &e_src, &er);
+        rc = prepare_entities(c, pl, nullptr, 0, s, s, &e_src, &er, reclaim);
         if (rc != NGDB_OK) return rc;
     }
-    rc = enqueue_forward(c, pl, er, s, ctx_space(c));
+    rc = enqueue_forward(c, pl, er, s, ctx_space(c, reclaim));
     if (rc != NGDB_OK) return rc;
     if (n_ans > 0) {
         const int N = c->cfg.n_entities, d = c->cfg.d, R = pl->hp.n_roots, B = pl->hp.n_queries;
         const float* box_off = c->cfg.family == NGDB_FAMILY_BOX ? ptr<float>(c->off) : nullptr;
         const int chunk = std::min(std::max(N, n_ans), 1 << 16);
         const int ld = (chunk + 3) & ~3;
-        if ((rc = ensure(c, c->rank_dist, std::max<size_t>((size_t)R * ld * sizeof(float), 256))) != NGDB_OK) return rc;
-        if ((rc = ensure(c, c->rank_count, (size_t)n_ans * 4)) != NGDB_OK) return rc;
-        if (!d_ans_dist && (rc = ensure(c, c->rank_thr, (size_t)n_ans * 4)) != NGDB_OK) return rc;
-        if (sem && (rc = ensure(c, c->rank_ef, (size_t)chunk * d * sizeof(float))) != NGDB_OK) return rc;
+        if ((rc = ensure(c, c->rank_dist, std::max<size_t>((size_t)R * ld * sizeof(float), 256), true)) != NGDB_OK) return rc;
+        if ((rc = ensure(c, c->rank_count, (size_t)n_ans * 4, true)) != NGDB_OK) return rc;
+        if (!d_ans_dist && (rc = ensure(c, c->rank_thr, (size_t)n_ans * 4, true)) != NGDB_OK) return rc;
+        if (sem && (rc = ensure(c, c->rank_ef, (size_t)chunk * d * sizeof(float), true)) != NGDB_OK) return rc;
         float* thr = d_ans_dist ? d_ans_dist : ptr<float>(c->rank_thr);
         Timed tm(c, NGDB_TK_SCORE, s);
         HIPCHK(c, launch_fill_zero_i32(ptr<int32_t>(c->rank_count), n_ans, s));
@@ -1359,7 +1516,7 @@ int ngdb_rank_answers(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_ans
                 rows = ptr<float>(c->rank_ef);
                 ids = nullptr;
             }
-            HIPCHK(c, launch_l1_tile(ptr<float>(c->act), box_off, c->cfg.box_alpha, pl->d_root_slot, R, rows, ids, cnt, d,
+            HIPCHK(c, launch_l1_tile(ptr<float>(c->act), box_off, c->cfg.box_alpha, roots, R, rows, ids, cnt, d,
                                      ptr<float>(c->rank_dist), ld, s, c->cfg.score_bf16 ? ptr<uint16_t>(c->Eb) : nullptr));
             HIPCHK(c, launch_answer_dist(ptr<float>(c->rank_dist), ld, pl->d_root_off, d_ans_off, B, a0, cnt, thr, s));
         }
@@ -1372,7 +1529,7 @@ int ngdb_rank_answers(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_ans
                 HIPCHK(c, launch_sem_fuse(fa, s));
                 rows = ptr<float>(c->rank_ef);
             }
-            HIPCHK(c, launch_l1_tile(ptr<float>(c->act), box_off, c->cfg.box_alpha, pl->d_root_slot, R, rows, nullptr, cnt, d,
+            HIPCHK(c, launch_l1_tile(ptr<float>(c->act), box_off, c->cfg.box_alpha, roots, R, rows, nullptr, cnt, d,
                                      ptr<float>(c->rank_dist), ld, s,
                                      c->cfg.score_bf16 ? ptr<uint16_t>(c->Eb) + (size_t)e0 * d : nullptr));
             HIPCHK(c, launch_count_less(ptr<float>(c->rank_dist), ld, pl->d_root_off, d_ans_off, thr, B, cnt,
@@ -1455,6 +1612,8 @@ int ngdb_copy_to_host(void* h_dst, const void* d_src, size_t bytes) {
     if (hipDeviceSynchronize() != hipSuccess) return NGDB_ERR_HIP;
     return hipMemcpy(h_dst, d_src, bytes, hipMemcpyDeviceToHost) == hipSuccess ? NGDB_OK : NGDB_ERR_HIP;
 }
+
+int64_t ngdb_debug_alloc_count(const ngdb_ctx_t* c) { return c ? c->n_alloc : -1; }
 
 int64_t ngdb_step_count(const ngdb_ctx_t* c) { return c ? c->step : -1; }
 

@@ -143,6 +143,7 @@ struct InterJob {
     const float *X, *Att, *dY;
     float *out, *dAtt, *Dx;
     int n, k;
+    const int32_t* out_row;   // forward: member i is written to row out_row[i] of out (null: row i)
 };
 struct InterJobs {
     int count;

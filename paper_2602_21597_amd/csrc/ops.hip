@@ -38,7 +38,7 @@ __global__ __launch_bounds__(256) void inter_kernel(const InterJobs jobs) {
         float y = 0.f;
 #pragma unroll
         for (int j = 0; j < NGDB_MAX_CARD; ++j) y += a[j] * inv * x[j];
-        jb.out[(size_t)i * d + c] = y;
+        jb.out[(size_t)(jb.out_row ? jb.out_row[i] : i) * d + c] = y;
     } else {
         const float dy = jb.dY[(size_t)i * d + c];
         float tall = 0.f;

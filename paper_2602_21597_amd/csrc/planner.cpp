@@ -11,6 +11,8 @@
 #include "planner.h"
 
 #include <algorithm>
+#include <functional>
+#include <queue>
 #include <climits>
 #include <numeric>
 
@@ -422,6 +424,40 @@ int build_plan(const ngdb_query_batch& qb, int32_t N, int32_t R, int32_t schedul
     segment_index(rkeys, R, P.r_uniq, P.r_seg_off, order);
     P.r_src.resize(P.n_proj);
     for (int32_t s = 0; s < P.n_proj; ++s) P.r_src[s] = rsrc[order[s]];
+
+    // 7. rows of a forward-only pass under eager reference counting (Sec. 4.3, Reclaim(T); Alg. 1,
+    // DecrementRefCounts): the steps in order; every output of a step takes, in group and member
+    // order, the lowest free row (a new one if none is free); when the step has run, the rows of
+    // the outputs it consumed are free again.  Every output has one consumer (queries are trees);
+    // roots have none and keep their rows.
+    P.f_row.assign(P.n_slots, -1);
+    std::priority_queue<int32_t, std::vector<int32_t>, std::greater<int32_t>> free_rows;
+    P.n_f_rows = 0;
+    for (int32_t l = 1; l <= P.n_levels; ++l) {
+        int32_t rows_now[3] = {0, 0, 0};
+        for (int32_t g = P.lvl_off[l]; g < P.lvl_off[l + 1]; ++g) {
+            const int32_t t = P.g_type[g];
+            rows_now[t == NGDB_OP_PROJ ? 0 : (t == NGDB_OP_INTER ? 1 : 2)] += P.g_n[g] * (t == NGDB_OP_INTER ? P.g_nin[g] : 1);
+            for (int32_t m = 0; m < P.g_n[g]; ++m) {
+                int32_t row;
+                if (!free_rows.empty()) {
+                    row = free_rows.top();
+                    free_rows.pop();
+                } else {
+                    row = P.n_f_rows++;
+                }
+                P.f_row[P.g_out_base[g] + m] = row;
+            }
+        }
+        for (int32_t g = P.lvl_off[l]; g < P.lvl_off[l + 1]; ++g) {
+            const int32_t n_ref = P.g_n[g] * P.g_nin[g];
+            for (int32_t k = 0; k < n_ref; ++k) {
+                const int32_t ref = P.in_ref[P.g_ref_off[g] + k];
+                if (ref >= 0) free_rows.push(P.f_row[ref]);
+            }
+        }
+        for (int k = 0; k < 3; ++k) P.f_step_rows[k] = std::max(P.f_step_rows[k], rows_now[k]);
+    }
     return NGDB_OK;
 }
 

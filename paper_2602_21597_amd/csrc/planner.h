@@ -19,6 +19,12 @@ struct HostPlan {
     std::vector<int32_t> root_off, root_slot;
     std::vector<int32_t> anchor_ent, pos;
     std::vector<int32_t> r_uniq, r_seg_off, r_src;
+    // forward-only passes with eager reference counting (Sec. 4.3): storage row of every output
+    // slot when a row is reused once the output's consumer has run, the number of rows that takes
+    // (= peak_live), and per type (projection, intersection, negation) the most MLP rows of one step
+    std::vector<int32_t> f_row;
+    int32_t n_f_rows = 0;
+    int32_t f_step_rows[3] = {0, 0, 0};
 };
 
 // Returns NGDB_OK or an error code; `err` receives the reason.

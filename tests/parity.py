@@ -232,6 +232,9 @@ def check_forward_backward(case, eng=None, tol=TOL):
     got_plan = plan.export()
     for k in ref_plan:
         assert np.array_equal(np.asarray(got_plan[k]), np.asarray(ref_plan[k])), "plan." + k
+    f_row, n_rows, step_rows = oplan.forward_rows(ref_plan)
+    assert np.array_equal(got_plan["f_row"], f_row) and got_plan["n_f_rows"] == n_rows, "plan.f_row"
+    assert np.array_equal(got_plan["f_step_rows"], step_rows), "plan.f_step_rows"
 
     loss = eng.forward_backward(plan, case.neg_dev())
     torch.cuda.synchronize()

@@ -150,6 +150,30 @@ def test_candidate_scores_against_oracle():
     par.assert_close(got, want, "candidate scores")
 
 
+@pytest.mark.parametrize("schedule,b_max,d_sem", [("level", 0, 0), ("max_fill", 0, 0), ("max_fill", 7, 0), ("level", 0, 64)])
+def test_forward_only_passes_reclaim_outputs(schedule, b_max, d_sem):
+    """ngdb_score keeps an operator output only until its consumer has run (eager reference
+    counting): fewer storage rows than outputs, the rows of the oracle's assignment, and scores
+    bit-identical to those of the training pass, which keeps every output."""
+    _say("forward-only pass with reclaimed outputs: %s schedule, B_max %d, d_sem %d" % (schedule, b_max, d_sem))
+    import torch
+    case = par.Case(2000, 20, 104, 72, 90, 7, 12.0, seed=61, schedule=schedule, b_max=b_max, d_sem=d_sem)
+    eng = case.engine()
+    plan = eng.plan(case.qb)
+    pe = plan.export()
+    f_row, n_rows, step_rows = oplan.forward_rows(oplan.build_plan(case.qb, schedule, b_max))
+    assert np.array_equal(pe["f_row"], f_row) and pe["n_f_rows"] == n_rows == pe["peak_live"] < pe["n_slots"]
+    assert np.array_equal(pe["f_step_rows"], step_rows)
+    nd = case.neg_dev()
+    eng.forward_backward(plan, nd)
+    torch.cuda.synchronize()
+    kept_all = eng.grads()["pair_score"].reshape(case.B, case.K + 1)[:, 1:]
+    got = eng.score(plan, nd).cpu().numpy()
+    assert np.array_equal(got, kept_all)
+    par.assert_close(got, orank.score_candidates(case.qb, case.negs, case.model()), "candidate scores")
+    plan.free()
+
+
 def test_all_entity_topk_small_and_ragged():
     _say("ngdb_score all-entity mode: N=1000 (one ragged chunk), k=10 and k=16; N=300 d=64, k=1")
     par.check_topk(par.Case.from_config(0), 10, 64)
@@ -339,6 +363,54 @@ def test_sampled_batches_train_like_any_other():
         par.assert_close(eng.grads()["pair_score"].reshape(b.B, 7), np.stack(ref_scores), "scores")
         assert abs(float(loss.cpu()[0]) - ref_loss) <= 1e-4 * abs(ref_loss)
         plan.free()
+
+
+def test_declared_maxima_steps_allocate_nothing():
+    """With b_max_queries / k_max declared, ngdb_create allocates everything: 50 steps of sampled batches
+    of varying sizes (planning, training, candidate scoring) make no device allocation, the
+    parameters end up bit-identical to those of a context that grows on demand, and a batch beyond
+    the maxima is refused."""
+    _say("declared maxima: 50 steps of varying batch sizes allocate nothing; same results as growing on demand")
+    import torch
+    from paper_2602_21597_amd import Engine, Sampler
+    from paper_2602_21597_amd.binding import NgdbError, ERR_ARG
+    c = wl.get_config(0)
+    kg = wl.make_kg(c.N, c.R, c.T, c.alpha, c.seed)
+    params = wl.make_params(c.N, c.R, c.d, c.h, 3)
+    fixed = Engine(c.N, c.R, c.d, c.h, c.gamma, num_streams=2, b_max_queries=96, k_max=16)
+    grows = Engine(c.N, c.R, c.d, c.h, c.gamma, num_streams=2)
+    fixed.bind_numpy(params)
+    grows.bind_numpy(params)
+    n0 = fixed.alloc_count()
+    assert n0 > 0
+    smp = Sampler(c.N, c.R, kg.head, kg.rel, kg.tail, list(wl.configs.ALL14), None, 21, 2)
+    rng = np.random.default_rng(4)
+    for t in range(50):
+        b = smp.next(int(rng.integers(1, 97)), int(rng.integers(1, 17)))
+        negs = torch.from_numpy(b.negs).cuda()
+        for eng in (fixed, grows):
+            plan = eng.plan(b)
+            eng.train_step(plan, negs)
+            if t % 10 == 0:
+                eng.score(plan, negs)
+            plan.free()
+    torch.cuda.synchronize()
+    assert fixed.alloc_count() == n0, "a step allocated device memory although maxima were declared"
+    assert grows.alloc_count() > 0
+    pf, pg = fixed.params_numpy(), grows.params_numpy()
+    for k in pf:
+        assert np.array_equal(pf[k], pg[k]), k
+    too_many = smp.next(97, 4)
+    with pytest.raises(NgdbError) as ei:
+        fixed.plan(too_many)
+    assert ei.value.code == ERR_ARG
+    ok = smp.next(20, 16)
+    plan = fixed.plan(ok)
+    with pytest.raises(NgdbError) as ei:
+        fixed.train_step(plan, torch.zeros((20, 17), dtype=torch.int32, device="cuda"))
+    assert ei.value.code == ERR_ARG
+    plan.free()
+    assert fixed.alloc_count() == n0
 
 
 @pytest.mark.parametrize("family", ["vec", "box"])

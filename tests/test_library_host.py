@@ -35,6 +35,10 @@ def same_plan(a, b):
     for k in b:
         assert np.array_equal(np.asarray(a[k]), np.asarray(b[k])), k
     assert a["n_refs"] == len(b["in_ref"]) and a["n_r_uniq"] == len(b["r_uniq"])
+    # rows of a forward-only pass with outputs reclaimed once their consumer has run
+    f_row, n_rows, step_rows = oplan.forward_rows(b)
+    assert np.array_equal(a["f_row"], f_row) and a["n_f_rows"] == n_rows == a["peak_live"]
+    assert np.array_equal(a["f_step_rows"], step_rows)
     assert a["n_queries"] == len(a["pos"]) == len(b["root_off"]) - 1
 
 

@@ -184,6 +184,78 @@ def test_max_fillness_hand_worked_schedule():
     assert list(lvl["g_level"]) == [1, 2, 2, 2] and lvl["peak_live"] == 7
 
 
+def test_forward_rows_hand_worked():
+    """The three queries above, outputs reclaimed when their consumer has run.  Output slots are
+    type-major: unbounded p1 p4 p6 p9 = 0..3, p2 = 4, i7 = 5, n10 = 6.  Step 1 fills rows 0..3; step 2
+    (p2) finds no free row: row 4, then p1's row 0 is free; step 3 (i7) takes row 0 and frees rows 1
+    and 2 (p4, p6); step 4 (n10) takes row 1: five rows, the peak of live outputs.
+    B_max = 3: step 1 p1 p4 p6 = slots and rows 0..2; step 2 runs p2 (slot 3) and p9 (slot 4) into
+    rows 3 and 4 and frees row 0; step 3 i7 -> row 0, frees 1 and 2; step 4 n10 -> row 1.
+    Level-synchronous: p2, i7 and n10 run in one step beside their inputs: seven rows, no reuse."""
+    trees = [("p", 1, ("p", 0, ("e", 1))), ("i", ("p", 2, ("e", 2)), ("p", 3, ("e", 3))), ("n", ("p", 4, ("e", 4)))]
+    qb = wl.batch_from_trees(trees, [5, 6, 7])
+    for b_max in (0, 3):
+        plan = oplan.build_plan(qb, "max_fill", b_max)
+        f_row, n_rows, step_rows = oplan.forward_rows(plan)
+        assert list(f_row) == [0, 1, 2, 3, 4, 0, 1] and n_rows == 5 == plan["peak_live"]
+        assert list(step_rows) == ([4, 2, 1] if b_max == 0 else [3, 2, 1])
+    f_row, n_rows, step_rows = oplan.forward_rows(oplan.build_plan(qb))
+    assert list(f_row) == list(range(7)) and n_rows == 7 and list(step_rows) == [4, 2, 1]
+
+
+@pytest.mark.parametrize("schedule,b_max", [("level", 0), ("max_fill", 0), ("max_fill", 7)])
+def test_forward_rows_no_row_is_read_after_it_was_reassigned(kg, schedule, b_max):
+    """Replaying the steps with one value cell per row: every input row still holds the output it is
+    read for, every root's row holds the root at the end, the rows used equal the peak of live
+    outputs, and executing the plan through these rows gives the per-query embeddings."""
+    qb = wl.make_batch(kg, 60, {n: 1.0 for n in CENSUS}, 12)
+    plan = oplan.build_plan(qb, schedule, b_max)
+    f_row, n_rows, step_rows = oplan.forward_rows(plan)
+    assert n_rows == plan["peak_live"] and f_row.min() == 0 and f_row.max() == n_rows - 1
+    p = wl.make_params(400, 12, 8, 16, 5)
+    M = om.Model(p, 12.0)
+    Pm = M.P
+    holder = np.full(n_rows, -1)
+    A = np.zeros((n_rows, 8))
+    lo = plan["lvl_off"]
+    rows_seen = np.zeros(3, int)
+    for l in range(1, plan["n_levels"] + 1):
+        new = {}
+        rows_now = np.zeros(3, int)
+        for g in range(lo[l], lo[l + 1]):
+            t, k, n = (int(plan[x][g]) for x in ("g_type", "g_nin", "g_n"))
+            rows_now[[P, I, N].index(t)] += n * (k if t == I else 1)
+            ro, ob = int(plan["g_ref_off"][g]), int(plan["g_out_base"][g])
+            refs = plan["in_ref"][ro:ro + k * n].reshape(k, n)
+            for i in range(n):
+                for r in refs[:, i]:
+                    assert r < 0 or holder[f_row[r]] == r, "row reassigned before its reader ran"
+                xs = [A[f_row[r]] if r >= 0 else Pm["E"][-1 - r] for r in refs[:, i]]
+                if t == P:
+                    rr = int(plan["rel"][int(plan["g_rel_off"][g]) + i])
+                    y = om.mlp_forward(xs[0] + Pm["R"][rr], Pm["W1"], Pm["b1"], Pm["W2"], Pm["b2"])[0]
+                elif t == N:
+                    y = om.mlp_forward(xs[0], Pm["V1"], Pm["c1"], Pm["V2"], Pm["c2"])[0]
+                else:
+                    att = np.stack([om.mlp_forward(x, Pm["U1"], Pm["u1"], Pm["U2"], Pm["u2"])[0] for x in xs])
+                    w = np.exp(att - att.max(0))
+                    w /= w.sum(0)
+                    y = (w * np.stack(xs)).sum(0)
+                new[ob + i] = y
+        for s_, y in new.items():          # the outputs of a step are written when its inputs have been read
+            assert holder[f_row[s_]] == -1 or holder[f_row[s_]] not in plan["root_slot"]
+            holder[f_row[s_]] = s_
+            A[f_row[s_]] = y
+        rows_seen = np.maximum(rows_seen, rows_now)
+    assert list(rows_seen) == list(step_rows)
+    for q in range(qb.B):
+        br = om.dnf(qb.tree(q))
+        slots = plan["root_slot"][plan["root_off"][q]:plan["root_off"][q + 1]]
+        for b, s_ in zip(br, slots):
+            assert holder[f_row[s_]] == s_
+            np.testing.assert_allclose(A[f_row[s_]], om.forward(b, M)[0], rtol=1e-12, atol=1e-14)
+
+
 CLASS_ORDER = [(P, 1)] + [(I, k) for k in range(2, 9)] + [(N, 1)]
 
 

@@ -32,7 +32,7 @@ def test_score_noalloc_matches_score_on_two_calls_in_a_row():
         par.assert_close(got, orank.score_candidates(qb, cand_np, M), "candidate scores (no-alloc entry)")
         plan.free()
     # a batch beyond the static array is refused, with the sizes in the message
-    big = par.Case(3000, 30, 400, 800, 1500, 2, 24.0, seed=62)
+    big = par.Case(3000, 30, 400, 800, 3000, 1, 24.0, seed=62)
     eng2 = big.engine()
     plan = eng2.plan(big.qb)
     assert eng2.score_noalloc_bytes(plan) > 32 << 20
