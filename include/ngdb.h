@@ -320,7 +320,8 @@ int ngdb_forward_backward(ngdb_ctx_t* ctx, const ngdb_plan_t* plan, const int32_
 int ngdb_get_grads(ngdb_ctx_t* ctx, ngdb_grad_view* out);
 
 /* Forward only (Sec. 3.2: rank entities by f(q,e)).
- *  candidate mode (d_cand != NULL): d_cand device [n_queries, C] entity ids;
+ *  candidate mode (d_cand != NULL): d_cand device [n_queries, C] entity ids, every one in
+ *    [0, n_entities): they index E on the device and are not checked (as d_neg);
  *    d_scores device [n_queries, C] receives s(q_i, cand).
  *  all-entity mode (d_cand == NULL): for every query the topk entities of
  *    smallest L1 distance, ascending, ties to the lower id, into
