@@ -817,6 +817,26 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
         HIPCHK(c, e);
     }
 
+    // The records of the table pass (and the sum of the loss terms, in the same launch) depend on
+    // the scoring pass only.  In a large step, where the table pass on the library stream ends the
+    // step, they are resolved beside the backward pass; in a small step the extra fork costs more
+    // than the launch it hides.
+    hipStream_t s_tab = aside ? c->side[0] : stream;     // after the index on the same stream
+    const int64_t n_contrib = (int64_t)hp.n_anchor + B + (int64_t)B * K;
+    const bool small_step = std::min<int64_t>(n_contrib, c->cfg.n_entities) <= 65536;
+    const bool resolve_early = aside && !small_step;
+    auto resolve_records = [&]() -> int {
+        HIPCHK(c, launch_resolve(e_src, n_contrib, hp.n_anchor, hp.n_slots, B, K, ptr<float>(c->coef),
+                                 sem ? nullptr : ptr<int32_t>(c->win), ptr<float>(c->rec_coef), ptr<int32_t>(c->rec_row),
+                                 ptr<float>(c->loss_terms), B > 0 ? 1.f / (2.f * B) : 0.f, d_loss, s_tab));
+        return NGDB_OK;
+    };
+    if (resolve_early) {
+        HIPCHK(c, hipEventRecord(c->ev_fork, stream));
+        HIPCHK(c, hipStreamWaitEvent(s_tab, c->ev_fork, 0));
+        if ((rc = resolve_records()) != NGDB_OK) return rc;
+    }
+
     // 4. reversed frontiers
     WgradJob wj;
     rc = enqueue_backward(c, pl, stream, &wj);
@@ -827,16 +847,12 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
     AdamHyper ah{c->cfg.lr, c->cfg.beta1, c->cfg.beta2, c->cfg.eps,
                  (float)(1.0 - std::pow((double)c->cfg.beta1, (double)t)),
                  (float)(1.0 - std::pow((double)c->cfg.beta2, (double)t))};
-    hipStream_t s_tab = aside ? c->side[0] : stream;     // after the index on the same stream
     if (aside) {
         HIPCHK(c, hipEventRecord(c->ev_fork, stream));
         HIPCHK(c, hipStreamWaitEvent(s_tab, c->ev_fork, 0));
     }
     // (the sum of the loss terms is off the critical path there, in the launch that resolves the records)
-    const int64_t n_contrib = (int64_t)hp.n_anchor + B + (int64_t)B * K;
-    HIPCHK(c, launch_resolve(e_src, n_contrib, hp.n_anchor, hp.n_slots, B, K, ptr<float>(c->coef),
-                             sem ? nullptr : ptr<int32_t>(c->win), ptr<float>(c->rec_coef), ptr<int32_t>(c->rec_row),
-                             ptr<float>(c->loss_terms), B > 0 ? 1.f / (2.f * B) : 0.f, d_loss, s_tab));
+    if (!resolve_early && (rc = resolve_records()) != NGDB_OK) return rc;
     TableArgs te{};
     te.P = c->prm.E.p; te.Mo = c->prm.E.m; te.Vo = c->prm.E.v;
     te.uniq = ptr<int32_t>(c->uniq); te.seg_off = ptr<int32_t>(c->seg_off);
@@ -864,7 +880,7 @@ int run_step(ngdb_ctx_t* c, const ngdb_plan_t* pl, const int32_t* d_neg, int K, 
         to.P = c->prm.Ro.p; to.Mo = c->prm.Ro.m; to.Vo = c->prm.Ro.v;
         to.dact = ptr<float>(c->doff); to.relu_gate = true; to.g_out = apply ? nullptr : ptr<float>(c->gRo);
     }
-    if (std::min<int64_t>(n_contrib, c->cfg.n_entities) <= 65536) {   // a small step: one launch for all tables
+    if (small_step) {   // one launch for all tables
         Timed tm(c, NGDB_TK_TABLE_E, s_tab);
         HIPCHK(c, launch_table_update(te, ah, s_tab, small, n_small, c->cfg.n_relations));
     } else {
