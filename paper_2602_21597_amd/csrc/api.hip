@@ -83,6 +83,12 @@ struct ngdb_ctx_s {
     DevBuf rank_thr, rank_count;   // filtered ranks: distance of every listed answer, entities closer than it
     DevBuf colsum_part; // 6 scratch areas of the bias-gradient column sums
     DevBuf gW;          // gradients of the 12 MLP tensors, packed
+    // The six weight matrices of the vector family's MLPs as ready-made B operands of the contraction
+    // kernel (bf16 pieces in MFMA lane order), in both orientations: rebuilt at the start of every
+    // forward pass, so they are never older than the weights the pass reads.
+    DevBuf w_pieces;
+    const uint16_t* wp[3][4]{};     // per type: Wa forward, Wb forward, Wb backward (dH = dY Wb), Wa backward (dZ = dH Wa)
+    bool have_pieces = false;
     DevBuf gE, gR;      // compact table gradients (ngdb_forward_backward only)
     // text-feature fusion: bf16 copy of Wp, fused rows of the touched entities, position of every
     // contribution's entity in that list, operator references redirected to it, bf16 row gradients,
@@ -227,12 +233,46 @@ struct FwdBytes;
 FwdBytes forward_bytes(const ngdb_ctx_t* c, const ngdb_plan_t* pl, bool reclaim);
 int size_forward_only(ngdb_ctx_t* c, const ngdb_plan_t* pl, int64_t n_tail);
 
+
+// bytes of the split weights: per type two operands of ceil(h/32) x ceil(d/16) tiles and two of ceil(d/32) x ceil(h/16)
+size_t weight_pieces_bytes(const ngdb_ctx_t* c) {
+    if (c->cfg.family != NGDB_FAMILY_VEC) return 0;
+    return 3 * 2 * (pieces_elems(c->cfg.h, c->cfg.d) + pieces_elems(c->cfg.d, c->cfg.h)) * sizeof(uint16_t);
+}
+// Splits the weights of the three MLPs for this pass (one launch).  Without the buffer (a context
+// that never sized a workspace) the contractions split their B operands themselves.
+int make_weight_pieces(ngdb_ctx_t* c, hipStream_t s) {
+    c->have_pieces = false;
+    if (c->cfg.family != NGDB_FAMILY_VEC || c->w_pieces.cap < weight_pieces_bytes(c) || !c->w_pieces.p) return NGDB_OK;
+    const int d = c->cfg.d, h = c->cfg.h;
+    if ((d & 3) || (h & 3)) return NGDB_OK;   // the split reads rows as float4
+    uint16_t* at = ptr<uint16_t>(c->w_pieces);
+    PieceJobs J{};
+    for (int t = 0; t < 3; ++t) {
+        const MlpRefs W = mlp_of(c->prm, t);
+        // Wa [h][d]: rows as n = forward operand of H = X Wa^T; columns as n = backward operand of dZ = dH Wa
+        PieceJob& ja = J.job[J.count++];
+        ja.W = W.Wa; ja.R = h; ja.C = d;
+        c->wp[t][0] = ja.out_rk = at; at += pieces_elems(h, d);
+        c->wp[t][3] = ja.out_ck = at; at += pieces_elems(d, h);
+        // Wb [d][h]: rows as n = forward operand of Y = H Wb^T; columns as n = backward operand of dH = dY Wb
+        PieceJob& jw = J.job[J.count++];
+        jw.W = W.Wb; jw.R = d; jw.C = h;
+        c->wp[t][1] = jw.out_rk = at; at += pieces_elems(d, h);
+        c->wp[t][2] = jw.out_ck = at; at += pieces_elems(h, d);
+    }
+    HIPCHK(c, launch_weight_pieces(J, s));
+    c->have_pieces = true;
+    return NGDB_OK;
+}
+
 int size_workspace(ngdb_ctx_t* c, const ngdb_plan_t* pl, int K, bool want_table_grads) {
     const HostPlan& hp = pl->hp;
     const size_t d = c->cfg.d, h = c->cfg.h, f = sizeof(float);
     const size_t rows[3] = {(size_t)hp.n_proj, (size_t)hp.n_int_rows, (size_t)hp.n_neg};
     int rc;
 #define ENS(buf, bytes) if ((rc = ensure(c, buf, std::max<size_t>((bytes), 256))) != NGDB_OK) return rc
+    ENS(c->w_pieces, weight_pieces_bytes(c));
     ENS(c->act, (size_t)hp.n_slots * d * f);
     ENS(c->dact, ((size_t)hp.n_slots + hp.n_anchor) * d * f);
     for (int t = 0; t < 3; ++t) {
@@ -506,6 +546,7 @@ int size_forward_only(ngdb_ctx_t* c, const ngdb_plan_t* pl, int64_t n_tail) {
     const FwdBytes fb = forward_bytes(c, pl, true);
     int rc;
 #define ENS(buf, bytes) if ((rc = ensure(c, buf, std::max<size_t>((bytes), 256))) != NGDB_OK) return rc
+    ENS(c->w_pieces, weight_pieces_bytes(c));
     ENS(c->act, fb.act);
     ENS(c->Att, fb.att);
     for (int t = 0; t < 3; ++t) {
@@ -539,6 +580,11 @@ int size_forward_only(ngdb_ctx_t* c, const ngdb_plan_t* pl, int64_t n_tail) {
 int enqueue_forward(ngdb_ctx_t* c, const ngdb_plan_t* pl, const EntRows& er, hipStream_t s, const FwdSpace& w) {
     if (c->cfg.family == NGDB_FAMILY_BOX) return enqueue_forward_box(c, pl, s);   // (always on the context's buffers)
     const int d = c->cfg.d, h = c->cfg.h;
+    {
+        Timed tm(c, NGDB_TK_GEMM_FWD, s);
+        int rc_p = make_weight_pieces(c, s);
+        if (rc_p != NGDB_OK) return rc_p;
+    }
     for (int l = 1; l <= pl->hp.n_levels; ++l) {
         const std::vector<Segment>& segs = pl->levels[l];
         GemmArgs g1[3], g2[3];
@@ -557,6 +603,10 @@ int enqueue_forward(ngdb_ctx_t* c, const ngdb_plan_t* pl, const EntRows& er, hip
             a.M = sg.rows; a.N = h; a.K = d; a.bias = W.ba; a.relu = true;
             GemmArgs& b = g2[n];
             b.A = Hh; b.lda = h; b.B = W.Wb; b.ldb = h; b.M = sg.rows; b.N = d; b.K = h; b.bias = W.bb; b.ldc = d;
+            if (c->have_pieces) {
+                a.b_pieces = c->wp[sg.type][0]; a.b_kt = (d + 15) / 16;
+                b.b_pieces = c->wp[sg.type][1]; b.b_kt = (h + 15) / 16;
+            }
             if (sg.type == T_INTER) {
                 b.C = w.Att + row0 * d;
             } else if (w.reclaim) {         // outputs go to their storage rows
@@ -685,6 +735,10 @@ int enqueue_backward(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t s, WgradJ
             y.A = dHh; y.lda = h; y.B = W.Wa; y.ldb = d; y.b_kcontig = false;
             y.C = dact; y.ldc = d; y.M = sg.rows; y.N = d; y.K = h;
             y.addend = addend; y.ldadd = d; y.dst_row = pl->d_in_gslot + sg.ref_off;
+            if (c->have_pieces) {
+                x.b_pieces = c->wp[sg.type][2]; x.b_kt = (d + 15) / 16;
+                y.b_pieces = c->wp[sg.type][3]; y.b_kt = (h + 15) / 16;
+            }
             ++n;
         }
         int rc_g;
@@ -1077,7 +1131,7 @@ void ngdb_destroy(ngdb_ctx_t* c) {
     DevBuf* all[] = {&c->act, &c->dact, &c->Z[0], &c->Z[1], &c->Z[2], &c->H[0], &c->H[1], &c->H[2], &c->dH[0],
                      &c->dH[1], &c->dH[2], &c->Att, &c->dAtt, &c->Dx, &c->score, &c->coef, &c->win, &c->mask,
                      &c->loss_terms, &c->rec_coef, &c->rec_row, &c->keys_a, &c->keys_b, &c->vals_a, &c->vals_b, &c->hist, &c->scan_tmp,
-                     &c->uniq, &c->seg_off, &c->n_uniq, &c->gW, &c->gE, &c->gR, &c->colsum_part, &c->rank_dist, &c->rank_thr, &c->rank_count,
+                     &c->uniq, &c->seg_off, &c->n_uniq, &c->gW, &c->w_pieces, &c->gE, &c->gR, &c->colsum_part, &c->rank_dist, &c->rank_thr, &c->rank_count,
                      &c->Wb, &c->Ef, &c->inv, &c->refs_sem, &c->g_bf16, &c->wp_partial, &c->gWp, &c->rank_ef,
                      &c->off, &c->doff, &c->Gate, &c->dGate, &c->DxO, &c->gRo, &c->Eb};
     for (DevBuf* b : all) release(*b);

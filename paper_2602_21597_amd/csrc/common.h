@@ -115,6 +115,8 @@ struct GemmArgs {
     int ldadd = 0;
     const int32_t* dst_row = nullptr;
     int arith = 0;                 // GEMM_AUTO / GEMM_FP32 / GEMM_SPLIT: how the products are formed
+    const uint16_t* b_pieces = nullptr;
+    int b_kt = 0;
 };
 // GEMM_FP32: fp32 MFMA.  GEMM_SPLIT: every fp32 operand value as the exact sum of three bf16
 // values, the six largest of the nine partial products on the bf16 MFMA with fp32 accumulation
@@ -132,6 +134,24 @@ struct GemmGroup {
 };
 // *route (if given) receives the arithmetic the launch used: GEMM_FP32 or GEMM_SPLIT.
 hipError_t launch_gemm_group(const GemmArgs* problems, int count, hipStream_t s, int* route = nullptr);
+
+// A row-major matrix W [R][C] as B operand of the bf16 MFMA block in both forms, each value split
+// into three bf16 pieces, stored tile by tile (32 n x 16 k) in lane order and zero beyond the
+// matrix: out_rk holds B[n = row][k = column] (ceil(R/32) x ceil(C/16) tiles), out_ck holds
+// B[n = column][k = row] (ceil(C/32) x ceil(R/16) tiles).  C a multiple of 4.
+constexpr int PIECE_MAX_JOBS = 6;
+struct PieceJob {
+    const float* W;
+    uint16_t *out_rk, *out_ck;
+    int R, C;
+};
+struct PieceJobs {
+    int count;
+    PieceJob job[PIECE_MAX_JOBS];
+    int block0[PIECE_MAX_JOBS + 1];
+};
+inline size_t pieces_elems(int N, int K) { return (size_t)((N + 31) / 32) * ((K + 15) / 16) * 1536; }
+hipError_t launch_weight_pieces(PieceJobs& jobs, hipStream_t s);
 
 // ---------------------------------------------------------------- elementwise ops (ops.hip)
 // Intersections of one level, one job per cardinality class: n members with k inputs each,

@@ -29,10 +29,10 @@ constexpr int PAD = 4;    // keeps LDS rows 16-byte aligned and spreads banks
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-template <int BM, int BN, int NW, bool SPLIT = false>
+template <int BM, int BN, int NW, bool SPLIT = false, bool BP = false>
 struct Smem {
-    // SPLIT: per wavefront and operand three bf16 pieces of a [32][BK] tile
-    static constexpr int STAGE = SPLIT ? NW * (BM / 32 + BN / 32) * 960 : NW * BK * (BM + PAD + BN + PAD);   // floats
+    // SPLIT: per wavefront and operand three bf16 pieces of a [32][BK] tile (BP: the A operand only)
+    static constexpr int STAGE = SPLIT ? NW * (BM / 32 + (BP ? 0 : BN / 32)) * 960 : NW * BK * (BM + PAD + BN + PAD);   // floats
     static constexpr int NR = NW > 4 ? NW / 2 : NW;                    // partial tiles held in LDS at once
     static constexpr int REDUCE = NR * BM * (BN + 1);
     static constexpr int FLOATS = STAGE > REDUCE ? STAGE : REDUCE;
@@ -207,10 +207,79 @@ __device__ __forceinline__ void stage_strided(uint16_t* tile, int K, int X, int 
     }
 }
 
-template <int BM, int BN, int NW, bool AK, bool BKC, bool SPLIT = false>
+// Weight matrices as ready-made B operands of the bf16 MFMA block: the three bf16 pieces of every
+// value (see split3), laid out tile by tile in the order the lanes of a wavefront consume them.
+// Tile (nb, kt) covers rows n = nb*32 .. +31 and k = kt*16 .. +15 of the operand B[n][k]; it holds
+// per piece 64 x 16 bytes: lane l's eight values B[nb*32 + (l & 31)][kt*16 + (l >> 5)*8 + 0..7].
+// A wavefront fetches a piece of a tile with one fully coalesced 1 KiB load straight into the
+// registers of the MFMA: no staging through LDS, no arithmetic.  Tiles beyond the matrix (the
+// launcher pads the tile grid to what its kernels walk) hold zeros, so the consumers need no bounds.
+constexpr int WTILE = 3 * 512;            // bf16 values of one tile
+// One workgroup reads a block of 32 rows x 64 columns of a row-major matrix W [R][C] (coalesced),
+// and writes the tiles that block contributes to both operand forms: B[n = row][k = column]
+// (four tiles along k) and B[n = column][k = row] (two tile rows x two k-tiles).
+__global__ __launch_bounds__(256) void weight_pieces_kernel(const PieceJobs J) {
+    __shared__ float blk[32][65];
+    int j = 0;
+#pragma unroll
+    for (int i = 1; i < PIECE_MAX_JOBS; ++i)
+        if (i < J.count && (int)blockIdx.x >= J.block0[i]) j = i;
+    PieceJob jb = J.job[0];
+#pragma unroll
+    for (int i = 1; i < PIECE_MAX_JOBS; ++i)
+        if (i == j) jb = J.job[i];
+    const int b = (int)blockIdx.x - J.block0[j];
+    const int cblocks = (jb.C + 63) / 64;
+    const int r0 = (b / cblocks) * 32, c0 = (b % cblocks) * 64;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {         // 512 float4 of the block, 16 per row
+        const int idx = tid + q * 256, r = idx >> 4, c4 = (idx & 15) * 4;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (r0 + r < jb.R && c0 + c4 < jb.C) v = *reinterpret_cast<const float4*>(jb.W + (size_t)(r0 + r) * jb.C + c0 + c4);
+        blk[r][c4 + 0] = v.x; blk[r][c4 + 1] = v.y; blk[r][c4 + 2] = v.z; blk[r][c4 + 3] = v.w;
+    }
+    __syncthreads();
+    float v[8];
+    // B[n = row][k = column]: wavefront w writes k-tile w of the block
+    {
+        const int kt = c0 / 16 + wave, KT = (jb.C + 15) / 16;
+        if (kt < KT) {
+            const int n = lane & 31, kk = wave * 16 + (lane >> 5) * 8;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = blk[n][kk + e];
+            const Pieces p0 = split3(make_float4(v[0], v[1], v[2], v[3])), p1 = split3(make_float4(v[4], v[5], v[6], v[7]));
+            uint16_t* out = jb.out_rk + ((size_t)(r0 / 32) * KT + kt) * WTILE + lane * 8;
+            *reinterpret_cast<uint4*>(out) = make_uint4(p0.h.x, p0.h.y, p1.h.x, p1.h.y);
+            *reinterpret_cast<uint4*>(out + 512) = make_uint4(p0.m.x, p0.m.y, p1.m.x, p1.m.y);
+            *reinterpret_cast<uint4*>(out + 1024) = make_uint4(p0.l.x, p0.l.y, p1.l.x, p1.l.y);
+        }
+    }
+    // B[n = column][k = row]: wavefront w writes tile row w / 2, k-tile w % 2 of the block
+    {
+        const int nb = c0 / 32 + (wave >> 1), kt = r0 / 16 + (wave & 1), KT = (jb.R + 15) / 16;
+        if (nb < (jb.C + 31) / 32 && kt < KT) {
+            const int n = (wave >> 1) * 32 + (lane & 31), kk = (wave & 1) * 16 + (lane >> 5) * 8;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = blk[kk + e][n];
+            const Pieces p0 = split3(make_float4(v[0], v[1], v[2], v[3])), p1 = split3(make_float4(v[4], v[5], v[6], v[7]));
+            uint16_t* out = jb.out_ck + ((size_t)nb * KT + kt) * WTILE + lane * 8;
+            *reinterpret_cast<uint4*>(out) = make_uint4(p0.h.x, p0.h.y, p1.h.x, p1.h.y);
+            *reinterpret_cast<uint4*>(out + 512) = make_uint4(p0.m.x, p0.m.y, p1.m.x, p1.m.y);
+            *reinterpret_cast<uint4*>(out + 1024) = make_uint4(p0.l.x, p0.l.y, p1.l.x, p1.l.y);
+        }
+    }
+}
+
+__device__ __forceinline__ bf16x8 piece_at(const uint16_t* tile, int q, int lane) {
+    return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(tile + q * 512 + lane * 8));
+}
+
+template <int BM, int BN, int NW, bool AK, bool BKC, bool SPLIT = false, int PF = 1, bool BP = false>
 __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
+    static_assert(!BP || (SPLIT && AK), "B operand from split pieces: split route with k-contiguous A only");
     static_assert(!SPLIT || BK == 16, "split path: one 32x32x16 MFMA step per staged tile");
-    __shared__ __attribute__((aligned(16))) float smem[Smem<BM, BN, NW, SPLIT>::FLOATS];
+    __shared__ __attribute__((aligned(16))) float smem[Smem<BM, BN, NW, SPLIT, BP>::FLOATS];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
@@ -243,7 +312,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
     constexpr int TM = BM / 32, TN = BN / 32;
     constexpr int LDA = BM + PAD, LDB = BN + PAD;
     // (SPLIT: per 32 rows of an operand three pieces, SUBTILE bf16 = 960 floats)
-    float* As = smem + (SPLIT ? wave * (TM + TN) * 960 : wave * BK * (LDA + LDB));     // [BK][LDA] of this wavefront
+    float* As = smem + (SPLIT ? wave * (TM + (BP ? 0 : TN)) * 960 : wave * BK * (LDA + LDB));     // [BK][LDA] of this wavefront
     float* Bs = As + (SPLIT ? TM * 960 : BK * LDA);                                      // [BK][LDB]
 
     floatx16 acc[TM][TN];
@@ -256,7 +325,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
 
     constexpr int LA = BM * BK / 4 / 64;   // float4 per lane per tile
     constexpr int LB = BN * BK / 4 / 64;
-    float4 ra[LA], rd[LA], rb[LB];
+    float4 ra[PF][LA], rd[PF][LA], rb[PF][LB];
+    bf16x8 bq[PF][BP ? BN / 32 : 1][3];       // BP: the B operand blocks of a tile, ready for the MFMA
     const bool has_add = AK && a.a_ref != nullptr && a.a_add_idx != nullptr;   // uniform
     const bool copy_out = AK && a.a_copy != nullptr && first_n_tile;           // uniform
 
@@ -290,7 +360,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
     // held across it they would cost the registers of a second resident wavefront per SIMD (the
     // 4-wavefront small tile with split arithmetic likewise: 5 instead of 4 wavefronts per SIMD).
     constexpr int EPT = BM * BN / (NW * 64);
-    constexpr bool EARLY_EPILOGUE = BM * BN <= 32 * 32 && !(SPLIT && NW == 4);
+    constexpr bool EARLY_EPILOGUE = BM * BN <= 32 * 32 && !(SPLIT && NW == 4) && PF == 1;
     float e_bias[EPT], e_mask[EPT], e_add[EPT];
     int e_orow[EPT];
     const bool has_bias = a.bias != nullptr, has_mask = a.mask != nullptr, has_addend = a.addend != nullptr,
@@ -312,70 +382,89 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
     // independently (their memory waits do not line up) and only over the tiles they own.
     const int nk = (a.K + BK - 1) / BK;
     const int rounds = nk > wave ? (nk - wave + NW - 1) / NW : 0;
-    int kcur = wave * BK;
-#define NGDB_ISSUE()                                                                         \
+#define NGDB_ISSUE(u, kc)                                                                    \
     if (SPLIT && !AK) {                                                                      \
         _Pragma("unroll") for (int t = 0; t < TM; ++t)                                      \
-            issue_strided(a.A, a.lda, a.K, a.M, kcur, m0 + 32 * t, lane, reinterpret_cast<float4(&)[2]>(ra[2 * t])); \
+            issue_strided(a.A, a.lda, a.K, a.M, kc, m0 + 32 * t, lane, reinterpret_cast<float4(&)[2]>(ra[u][2 * t])); \
     } else {                                                                                 \
-        issue_a<BM, LA, AK>(a, lane, m0, kcur, has_add, arow, aadd, ra, rd);                \
+        issue_a<BM, LA, AK>(a, lane, m0, kc, has_add, arow, aadd, ra[u], rd[u]);            \
     }                                                                                        \
-    if (SPLIT && !BKC) {                                                                     \
+    if (BP) {                                                                                \
+        _Pragma("unroll") for (int j = 0; j < BN / 32; ++j)                                 \
+            _Pragma("unroll") for (int q = 0; q < 3; ++q)                                   \
+                bq[u][BP ? j : 0][q] = piece_at(a.b_pieces + ((size_t)(n0 / 32 + j) * a.b_kt + (kc) / BK) * WTILE, q, lane); \
+    } else if (SPLIT && !BKC) {                                                              \
         _Pragma("unroll") for (int t = 0; t < TN; ++t)                                      \
-            issue_strided(a.B, a.ldb, a.K, a.N, kcur, n0 + 32 * t, lane, reinterpret_cast<float4(&)[2]>(rb[2 * t])); \
+            issue_strided(a.B, a.ldb, a.K, a.N, kc, n0 + 32 * t, lane, reinterpret_cast<float4(&)[2]>(rb[u][2 * t])); \
     } else {                                                                                 \
-        issue_b<BN, LB, BKC>(a, lane, n0, kcur, rb);                                        \
+        issue_b<BN, LB, BKC>(a, lane, n0, kc, rb[u]);                                       \
     }
-    if (rounds > 0) { NGDB_ISSUE() }
-    for (int it = 0; SPLIT && it < rounds; ++it) {
+#pragma unroll
+    for (int u = 0; u < PF; ++u)
+        if (u < rounds) {
+            const int kc = (u * NW + wave) * BK;
+            NGDB_ISSUE(u, kc)
+        }
+    for (int it0 = 0; SPLIT && it0 < rounds; it0 += PF) {
+#pragma unroll
+      for (int u = 0; u < PF; ++u) {
+        const int it = it0 + u;
+        if (it >= rounds) break;
+        const int kcur = (it * NW + wave) * BK;
         uint16_t* Ap = reinterpret_cast<uint16_t*>(As);
         uint16_t* Bp = reinterpret_cast<uint16_t*>(Bs);
         if (!AK) {
 #pragma unroll
             for (int t = 0; t < TM; ++t)
                 stage_strided(Ap + t * SUBTILE, a.K, a.M, kcur, m0 + 32 * t, lane,
-                              reinterpret_cast<const float4(&)[2]>(ra[2 * t]));
+                              reinterpret_cast<const float4(&)[2]>(ra[u][2 * t]));
         }
 #pragma unroll
         for (int i = 0; AK && i < LA; ++i) {
             const int idx = lane + i * 64;
             const int m = idx / (BK / 4), kq = idx % (BK / 4);
             const int gk = kcur + kq * 4;
-            float4 v = ra[i];
-            if (has_add) { v.x += rd[i].x; v.y += rd[i].y; v.z += rd[i].z; v.w += rd[i].w; }
+            float4 v = ra[u][i];
+            if (has_add) { v.x += rd[u][i].x; v.y += rd[u][i].y; v.z += rd[u][i].z; v.w += rd[u][i].w; }
             const bool ok = avalid[i] && gk < a.K;
             v.x = ok ? v.x : 0.f; v.y = ok ? v.y : 0.f; v.z = ok ? v.z : 0.f; v.w = ok ? v.w : 0.f;
             if (copy_out && ok) *reinterpret_cast<float4*>(a.a_copy + (size_t)(m0 + m) * a.lda + gk) = v;
             store_pieces(Ap + (m >> 5) * SUBTILE, m & 31, kq, split3(v));
         }
-        if (!BKC) {
+        if (!BKC && !BP) {
 #pragma unroll
             for (int t = 0; t < TN; ++t)
                 stage_strided(Bp + t * SUBTILE, a.K, a.N, kcur, n0 + 32 * t, lane,
-                              reinterpret_cast<const float4(&)[2]>(rb[2 * t]));
+                              reinterpret_cast<const float4(&)[2]>(rb[u][2 * t]));
         }
 #pragma unroll
-        for (int i = 0; BKC && i < LB; ++i) {
+        for (int i = 0; BKC && !BP && i < LB; ++i) {
             const int idx = lane + i * 64;
             const int n = idx / (BK / 4), kq = idx % (BK / 4);
-            float4 v = rb[i];
+            float4 v = rb[u][i];
             const bool ok = n0 + n < a.N && kcur + kq * 4 < a.K;
             v.x = ok ? v.x : 0.f; v.y = ok ? v.y : 0.f; v.z = ok ? v.z : 0.f; v.w = ok ? v.w : 0.f;
             store_pieces(Bp + (n >> 5) * SUBTILE, n & 31, kq, split3(v));
         }
         __builtin_amdgcn_wave_barrier();
-        if (it + 1 < rounds) {
-            kcur = ((it + 1) * NW + wave) * BK;
-            NGDB_ISSUE()
-        }
         bf16x8 ap[TM][3], bp[TN][3];
+        if (BP) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int q = 0; q < 3; ++q) bp[j][q] = bq[u][BP ? j : 0][q];
+        }
+        if (it + PF < rounds) {           // the registers of this tile are free again
+            const int kc = ((it + PF) * NW + wave) * BK;
+            NGDB_ISSUE(u, kc)
+        }
 #pragma unroll
         for (int q = 0; q < 3; ++q) {
 #pragma unroll
             for (int i = 0; i < TM; ++i)
                 ap[i][q] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Ap + i * SUBTILE + q * PIECE + unit_at<!AK>(lane)));
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
+            for (int j = 0; !BP && j < TN; ++j)
                 bp[j][q] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Bp + j * SUBTILE + q * PIECE + unit_at<!BKC>(lane)));
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -391,14 +480,20 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[i][0], bp[j][0], acc[i][j], 0, 0, 0);
             }
         __builtin_amdgcn_wave_barrier();
+      }
     }
-    for (int it = 0; !SPLIT && it < rounds; ++it) {
-        stage_a<BM, LA, LDA, AK>(a, As, lane, m0, kcur, has_add, copy_out, avalid, ra, rd);
-        stage_b<BN, LB, LDB, BKC>(a, Bs, lane, n0, kcur, rb);
+    for (int it0 = 0; !SPLIT && it0 < rounds; it0 += PF) {
+#pragma unroll
+      for (int u = 0; u < PF; ++u) {
+        const int it = it0 + u;
+        if (it >= rounds) break;
+        const int kcur = (it * NW + wave) * BK;
+        stage_a<BM, LA, LDA, AK>(a, As, lane, m0, kcur, has_add, copy_out, avalid, ra[u], rd[u]);
+        stage_b<BN, LB, LDB, BKC>(a, Bs, lane, n0, kcur, rb[u]);
         __builtin_amdgcn_wave_barrier();        // staged tile before its reads (compiler ordering only)
-        if (it + 1 < rounds) {
-            kcur = ((it + 1) * NW + wave) * BK;
-            NGDB_ISSUE()
+        if (it + PF < rounds) {
+            const int kc = ((it + PF) * NW + wave) * BK;
+            NGDB_ISSUE(u, kc)
         }
         // all LDS operand reads of the tile are issued before the first MFMA, so that the
         // matrix pipe never waits for an LDS round trip between k steps
@@ -420,6 +515,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[kk][i], bv[kk][j], acc[i][j], 0, 0, 0);
         __builtin_amdgcn_wave_barrier();        // reads of this tile before the next one is staged
+      }
     }
     if (!EARLY_EPILOGUE) { NGDB_LOAD_EPILOGUE() }   // in flight during the reduction
 #undef NGDB_LOAD_EPILOGUE
@@ -428,7 +524,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
 
     // partial tiles -> LDS.  Accumulator layout of a 32x32 block: lane owns column
     // (lane & 31) and rows 8*(r/4) + 4*(lane/32) + r%4, r = 0..15.
-    constexpr int NR = Smem<BM, BN, NW, SPLIT>::NR;
+    constexpr int NR = Smem<BM, BN, NW, SPLIT, BP>::NR;
     float* red = smem + (wave % NR) * BM * (BN + 1);
 #define NGDB_ACC_TO_LDS()                                                                   \
     _Pragma("unroll") for (int i = 0; i < TM; ++i)                                         \
@@ -494,6 +590,18 @@ hipError_t dispatch_layout(GemmGroup& g, hipStream_t s) {
     return hipGetLastError();
 }
 
+template <int NW>
+hipError_t dispatch_pieces(GemmGroup& g, hipStream_t s) {
+    int tiles = 0;
+    for (int i = 0; i < g.count; ++i) {
+        g.tile_start[i] = tiles;
+        tiles += (((g.p[i].M + 31) / 32) * ((g.p[i].N + 31) / 32) + 7) / 8 * 8;
+    }
+    for (int i = g.count; i <= GEMM_MAX_GROUP; ++i) g.tile_start[i] = tiles;
+    hipLaunchKernelGGL((gemm_kernel<32, 32, NW, true, true, true, 1, true>), dim3(tiles), dim3(NW * 64), 0, s, g);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_gemm_group(const GemmArgs* problems, int count, hipStream_t s, int* route) {
@@ -540,6 +648,13 @@ hipError_t launch_gemm_group(const GemmArgs* problems, int count, hipStream_t s,
     // (with a k extent below 128 the matrix unit is idle either way and the splitting only adds work)
     if (arith == GEMM_SPLIT || auto_split) {
         if (route) *route = GEMM_SPLIT;
+        // every B operand comes ready-made (weights split once per pass): no staging of B at all
+        bool all_pieces = g.p[0].a_kcontig;
+        for (int i = 0; i < g.count; ++i) all_pieces = all_pieces && g.p[i].b_pieces != nullptr && g.p[i].b_kt >= (g.p[i].K + 15) / 16;
+        if (all_pieces) {
+            if (blocks_small * 2 > 512) return dispatch_pieces<4>(g, s);
+            return dispatch_pieces<8>(g, s);
+        }
         if (blocks_small * 2 > 512) return dispatch_layout<32, 32, 4, true>(g, s);
         return dispatch_layout<32, 32, 8, true>(g, s);
     }
@@ -548,5 +663,19 @@ hipError_t launch_gemm_group(const GemmArgs* problems, int count, hipStream_t s,
 }
 
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) { return launch_gemm_group(&a, 1, s, nullptr); }
+
+hipError_t launch_weight_pieces(PieceJobs& J, hipStream_t s) {
+    if (J.count <= 0) return hipSuccess;
+    if (J.count > PIECE_MAX_JOBS) return hipErrorInvalidValue;
+    int blocks = 0;
+    for (int i = 0; i < J.count; ++i) {
+        if ((J.job[i].C & 3) || J.job[i].R <= 0 || J.job[i].C <= 0) return hipErrorInvalidValue;
+        J.block0[i] = blocks;
+        blocks += ((J.job[i].R + 31) / 32) * ((J.job[i].C + 63) / 64);
+    }
+    J.block0[J.count] = blocks;
+    hipLaunchKernelGGL(weight_pieces_kernel, dim3(blocks), dim3(256), 0, s, J);
+    return hipGetLastError();
+}
 
 }  // namespace ngdb
