@@ -411,6 +411,20 @@ int ngdb_debug_gemm(const float* A, const float* B, float* C, int32_t M, int32_t
                     const float* addend, int32_t ldadd, const int32_t* dst_row, int32_t arith,
                     void* stream);
 
+/* The two launches of one operator MLP as the training step chains them when every operand
+ * it prepares once is read as bf16 pieces (used by tests; Sec. 4.1 batched kernels).  All
+ * pointers device fp32, row-major: W1 [h,d], W2 [d,h], H [M,h] and Y [M,d] outputs.
+ *   backward = 0: H = relu(X W1^T + b1), Y = H W2^T + b2              (X [M,d])
+ *   backward = 1: H = X W2 where mask > 0, else 0; Y = H W1           (X [M,d], mask [M,h])
+ * Both weight matrices are split once into three bf16 pieces per value in both operand
+ * forms; the first launch leaves H also as pieces where the step would (launches of at most
+ * 256 tiles of 32 x 32 outputs), and the second then reads them as its A operand.  *used
+ * (host, may be NULL): bit 0 weights read as pieces, bit 1 H read as pieces.  d and h
+ * multiples of 4.  Allocates and frees its own scratch and waits for the stream.          */
+int ngdb_debug_mlp(const float* X, const float* W1, const float* b1, const float* W2, const float* b2,
+                   const float* mask, float* H, float* Y, int32_t M, int32_t d, int32_t h,
+                   int32_t backward, int32_t* used, void* stream);
+
 /* A plain device-to-device copy kernel (16 bytes per thread and step) of `bytes`
  * bytes, a multiple of 16: the reference point for scaling hardware traffic
  * counters and for the copy bandwidth of the machine.                           */

@@ -108,6 +108,7 @@ def load_library(path=LIB_PATH):
         "ngdb_sampler_next": (C.c_int, [vp, i32, i32, C.POINTER(QueryBatchC), C.POINTER(vp), C.POINTER(vp)]),
         "ngdb_sampler_destroy": (None, [vp]),
         "ngdb_sampler_last_error": (C.c_char_p, [vp]),
+        "ngdb_debug_mlp": (C.c_int, [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, C.POINTER(C.c_int32), vp]),
         "ngdb_debug_gemm": (C.c_int, [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, i32, vp, i32, vp, i32,
                                       vp, i32, vp]),
         "ngdb_debug_copy": (C.c_int, [vp, vp, C.c_size_t, vp]),
@@ -228,6 +229,21 @@ def debug_gemm(A, B, M, N, K, a_kcontig=True, b_kcontig=True, bias=None, relu=Fa
                                  C.c_void_p(torch.cuda.current_stream().cuda_stream)), None)
     torch.cuda.synchronize()
     return Cm
+
+
+def debug_mlp(X, W1, b1, W2, b2, mask=None, backward=False):
+    """The two chained launches of one operator MLP with operands as bf16 pieces (ngdb_debug_mlp) on
+    torch device tensors; returns (H, Y, used)."""
+    import torch
+    M, d = X.shape
+    h = W1.shape[0]
+    H = torch.zeros((M, h), dtype=torch.float32, device=X.device)
+    Y = torch.zeros((M, d), dtype=torch.float32, device=X.device)
+    used = C.c_int32(0)
+    p = lambda t: t.data_ptr() if t is not None else None
+    _check(lib().ngdb_debug_mlp(p(X), p(W1), p(b1), p(W2), p(b2), p(mask), p(H), p(Y), M, d, h, int(backward),
+                                C.byref(used), C.c_void_p(torch.cuda.current_stream().cuda_stream)), None)
+    return H, Y, used.value
 
 
 def debug_copy(dst, src):

@@ -89,6 +89,10 @@ struct ngdb_ctx_s {
     DevBuf w_pieces;
     const uint16_t* wp[3][4]{};     // per type: Wa forward, Wb forward, Wb backward (dH = dY Wb), Wa backward (dZ = dH Wa)
     bool have_pieces = false;
+    // The hidden activations of one depth (forward) or their gradients (backward) once more as bf16
+    // pieces in tile order: written by the first launch of a layer pair, read as A operand by the
+    // second, then free again.  Only steps whose launches use the small tile get that far.
+    DevBuf h_pieces;
     DevBuf gE, gR;      // compact table gradients (ngdb_forward_backward only)
     // text-feature fusion: bf16 copy of Wp, fused rows of the touched entities, position of every
     // contribution's entity in that list, operator references redirected to it, bf16 row gradients,
@@ -177,7 +181,7 @@ struct Timed {
 };
 
 // One grouped contraction launch, bracketed as class `cls`.
-int gemm_timed(ngdb_ctx_t* c, int cls, const GemmArgs* g, int n, hipStream_t s);
+int gemm_timed(ngdb_ctx_t* c, int cls, const GemmArgs* g, int n, hipStream_t s, bool* emitted = nullptr);
 
 // evaluation: a buffer only the ranking calls or ngdb_forward_backward use (allocated on first use
 // also under declared maxima)
@@ -207,10 +211,10 @@ void release(DevBuf& b) {
 template <class T>
 T* ptr(const DevBuf& b) { return static_cast<T*>(b.p); }
 
-int gemm_timed(ngdb_ctx_t* c, int cls, const GemmArgs* g, int n, hipStream_t s) {
+int gemm_timed(ngdb_ctx_t* c, int cls, const GemmArgs* g, int n, hipStream_t s, bool* emitted) {
     Timed tm(c, cls, s);
     int route = GEMM_FP32;
-    HIPCHK(c, launch_gemm_group(g, n, s, &route));
+    HIPCHK(c, launch_gemm_group(g, n, s, &route, emitted));
     double flop = 0.0;
     for (int i = 0; i < n; ++i)
         if (g[i].M > 0 && g[i].N > 0) flop += 2.0 * g[i].M * g[i].N * g[i].K;
@@ -239,6 +243,40 @@ size_t weight_pieces_bytes(const ngdb_ctx_t* c) {
     if (c->cfg.family != NGDB_FAMILY_VEC) return 0;
     return 3 * 2 * (pieces_elems(c->cfg.h, c->cfg.d) + pieces_elems(c->cfg.d, c->cfg.h)) * sizeof(uint16_t);
 }
+// Room for the hidden rows of one depth as pieces: blocks of 32 rows per segment, k-tiles in pairs.
+constexpr size_t H_PIECES_MAX_ROWS = 2048;      // launches over more rows do not write pieces
+int h_pieces_kt(const ngdb_ctx_t* c) { return 2 * ((c->cfg.h + 31) / 32); }
+size_t h_pieces_bytes(const ngdb_ctx_t* c, const HostPlan& hp) {
+    if (c->cfg.family != NGDB_FAMILY_VEC) return 0;
+    const size_t rows = std::min<size_t>((size_t)hp.n_proj + hp.n_int_rows + hp.n_neg, H_PIECES_MAX_ROWS);
+    return (rows / 32 + 3) * h_pieces_kt(c) * 1536 * sizeof(uint16_t);
+}
+// Hands the segments of one depth their places in h_pieces (as output of `first`, as A operand of
+// `second` once the launch of `first` reports that it wrote them).
+struct HiddenPieces {
+    uint16_t* at[3] = {};
+    int kt = 0;
+};
+HiddenPieces place_hidden_pieces(ngdb_ctx_t* c, GemmArgs* first, int n) {
+    HiddenPieces hpc;
+    if (!c->have_pieces || !c->h_pieces.p) return hpc;
+    hpc.kt = h_pieces_kt(c);
+    const size_t tile_row = (size_t)hpc.kt * 1536;
+    size_t blocks = 0;
+    for (int i = 0; i < n; ++i) blocks += (size_t)(first[i].M + 31) / 32;
+    if (blocks * tile_row * sizeof(uint16_t) > c->h_pieces.cap) return hpc;
+    uint16_t* at = ptr<uint16_t>(c->h_pieces);
+    for (int i = 0; i < n; ++i) {
+        hpc.at[i] = first[i].c_pieces = at;
+        first[i].c_kt = hpc.kt;
+        at += (size_t)((first[i].M + 31) / 32) * tile_row;
+    }
+    return hpc;
+}
+void take_hidden_pieces(const HiddenPieces& hpc, GemmArgs* second, int n) {
+    for (int i = 0; i < n; ++i) { second[i].a_pieces = hpc.at[i]; second[i].a_kt = hpc.kt; }
+}
+
 // Splits the weights of the three MLPs for this pass (one launch).  Without the buffer (a context
 // that never sized a workspace) the contractions split their B operands themselves.
 int make_weight_pieces(ngdb_ctx_t* c, hipStream_t s) {
@@ -273,6 +311,7 @@ int size_workspace(ngdb_ctx_t* c, const ngdb_plan_t* pl, int K, bool want_table_
     int rc;
 #define ENS(buf, bytes) if ((rc = ensure(c, buf, std::max<size_t>((bytes), 256))) != NGDB_OK) return rc
     ENS(c->w_pieces, weight_pieces_bytes(c));
+    ENS(c->h_pieces, h_pieces_bytes(c, hp));
     ENS(c->act, (size_t)hp.n_slots * d * f);
     ENS(c->dact, ((size_t)hp.n_slots + hp.n_anchor) * d * f);
     for (int t = 0; t < 3; ++t) {
@@ -547,6 +586,7 @@ int size_forward_only(ngdb_ctx_t* c, const ngdb_plan_t* pl, int64_t n_tail) {
     int rc;
 #define ENS(buf, bytes) if ((rc = ensure(c, buf, std::max<size_t>((bytes), 256))) != NGDB_OK) return rc
     ENS(c->w_pieces, weight_pieces_bytes(c));
+    ENS(c->h_pieces, h_pieces_bytes(c, hp));
     ENS(c->act, fb.act);
     ENS(c->Att, fb.att);
     for (int t = 0; t < 3; ++t) {
@@ -618,7 +658,10 @@ int enqueue_forward(ngdb_ctx_t* c, const ngdb_plan_t* pl, const EntRows& er, hip
             ++n;
         }
         int rc_g;
-        if ((rc_g = gemm_timed(c, NGDB_TK_GEMM_FWD, g1, n, s)) != NGDB_OK) return rc_g;
+        const HiddenPieces hpc = place_hidden_pieces(c, g1, n);
+        bool emitted = false;
+        if ((rc_g = gemm_timed(c, NGDB_TK_GEMM_FWD, g1, n, s, &emitted)) != NGDB_OK) return rc_g;
+        if (emitted) take_hidden_pieces(hpc, g2, n);
         if ((rc_g = gemm_timed(c, NGDB_TK_GEMM_FWD, g2, n, s)) != NGDB_OK) return rc_g;
         for (const Segment& sg : segs) {
             if (sg.type != T_INTER) continue;
@@ -742,7 +785,10 @@ int enqueue_backward(ngdb_ctx_t* c, const ngdb_plan_t* pl, hipStream_t s, WgradJ
             ++n;
         }
         int rc_g;
-        if ((rc_g = gemm_timed(c, NGDB_TK_GEMM_BWD, b2, n, s)) != NGDB_OK) return rc_g;
+        const HiddenPieces hpc = place_hidden_pieces(c, b2, n);
+        bool emitted = false;
+        if ((rc_g = gemm_timed(c, NGDB_TK_GEMM_BWD, b2, n, s, &emitted)) != NGDB_OK) return rc_g;
+        if (emitted) take_hidden_pieces(hpc, b1, n);
         if ((rc_g = gemm_timed(c, NGDB_TK_GEMM_BWD, b1, n, s)) != NGDB_OK) return rc_g;
     }
     // weight gradients: one contraction per tensor over all rows of the type
@@ -1131,7 +1177,7 @@ void ngdb_destroy(ngdb_ctx_t* c) {
     DevBuf* all[] = {&c->act, &c->dact, &c->Z[0], &c->Z[1], &c->Z[2], &c->H[0], &c->H[1], &c->H[2], &c->dH[0],
                      &c->dH[1], &c->dH[2], &c->Att, &c->dAtt, &c->Dx, &c->score, &c->coef, &c->win, &c->mask,
                      &c->loss_terms, &c->rec_coef, &c->rec_row, &c->keys_a, &c->keys_b, &c->vals_a, &c->vals_b, &c->hist, &c->scan_tmp,
-                     &c->uniq, &c->seg_off, &c->n_uniq, &c->gW, &c->w_pieces, &c->gE, &c->gR, &c->colsum_part, &c->rank_dist, &c->rank_thr, &c->rank_count,
+                     &c->uniq, &c->seg_off, &c->n_uniq, &c->gW, &c->w_pieces, &c->h_pieces, &c->gE, &c->gR, &c->colsum_part, &c->rank_dist, &c->rank_thr, &c->rank_count,
                      &c->Wb, &c->Ef, &c->inv, &c->refs_sem, &c->g_bf16, &c->wp_partial, &c->gWp, &c->rank_ef,
                      &c->off, &c->doff, &c->Gate, &c->dGate, &c->DxO, &c->gRo, &c->Eb};
     for (DevBuf* b : all) release(*b);
@@ -1630,6 +1676,46 @@ int ngdb_debug_gemm(const float* A, const float* B, float* C, int32_t M, int32_t
     g.mask = mask; g.ldmask = ldmask; g.addend = addend; g.ldadd = ldadd; g.dst_row = dst_row;
     g.arith = arith;
     const hipError_t e = launch_gemm(g, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? NGDB_OK : (e == hipErrorInvalidValue ? NGDB_ERR_ARG : NGDB_ERR_HIP);
+}
+
+int ngdb_debug_mlp(const float* X, const float* W1, const float* b1, const float* W2, const float* b2, const float* mask,
+                   float* H, float* Y, int32_t M, int32_t d, int32_t h, int32_t backward, int32_t* used, void* stream) {
+    if (!X || !W1 || !W2 || !H || !Y || M < 1 || d < 4 || h < 4 || (d & 3) || (h & 3) || (backward && !mask)) return NGDB_ERR_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int kt = 2 * ((h + 31) / 32);
+    const size_t w_elems = 2 * (pieces_elems(h, d) + pieces_elems(d, h));
+    const size_t h_elems = (size_t)((M + 31) / 32) * kt * 1536;
+    uint16_t* buf = nullptr;
+    if (hipMalloc(&buf, (w_elems + h_elems) * sizeof(uint16_t)) != hipSuccess) return NGDB_ERR_OOM;
+    PieceJobs J{};
+    J.count = 2;
+    J.job[0].W = W1; J.job[0].R = h; J.job[0].C = d;
+    J.job[0].out_rk = buf; J.job[0].out_ck = buf + pieces_elems(h, d);
+    J.job[1].W = W2; J.job[1].R = d; J.job[1].C = h;
+    J.job[1].out_rk = J.job[0].out_ck + pieces_elems(d, h); J.job[1].out_ck = J.job[1].out_rk + pieces_elems(d, h);
+    uint16_t* hp = buf + w_elems;
+    GemmArgs first, second;
+    first.A = X; first.lda = d; first.M = M; first.N = h; first.K = d; first.C = H; first.ldc = h;
+    second.A = H; second.lda = h; second.M = M; second.N = d; second.K = h; second.C = Y; second.ldc = d;
+    first.arith = second.arith = GEMM_SPLIT;
+    first.c_pieces = hp; first.c_kt = kt;
+    if (!backward) {
+        first.B = W1; first.ldb = d; first.bias = b1; first.relu = true; first.b_pieces = J.job[0].out_rk; first.b_kt = (d + 15) / 16;
+        second.B = W2; second.ldb = h; second.bias = b2; second.b_pieces = J.job[1].out_rk; second.b_kt = (h + 15) / 16;
+    } else {
+        first.B = W2; first.ldb = h; first.b_kcontig = false; first.mask = mask; first.ldmask = h;
+        first.b_pieces = J.job[1].out_ck; first.b_kt = (d + 15) / 16;
+        second.B = W1; second.ldb = d; second.b_kcontig = false; second.b_pieces = J.job[0].out_ck; second.b_kt = (h + 15) / 16;
+    }
+    bool emitted = false;
+    hipError_t e = launch_weight_pieces(J, s);
+    if (e == hipSuccess) e = launch_gemm_group(&first, 1, s, nullptr, &emitted);
+    if (e == hipSuccess && emitted) { second.a_pieces = hp; second.a_kt = kt; }
+    if (e == hipSuccess) e = launch_gemm_group(&second, 1, s, nullptr, nullptr);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    (void)hipFree(buf);
+    if (used) *used = 1 | (emitted ? 2 : 0);
     return e == hipSuccess ? NGDB_OK : (e == hipErrorInvalidValue ? NGDB_ERR_ARG : NGDB_ERR_HIP);
 }
 

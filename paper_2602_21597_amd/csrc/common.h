@@ -117,6 +117,13 @@ struct GemmArgs {
     int arith = 0;                 // GEMM_AUTO / GEMM_FP32 / GEMM_SPLIT: how the products are formed
     const uint16_t* b_pieces = nullptr;
     int b_kt = 0;
+    // The same for A (rows of A in blocks of 32: tile (m / 32, k / 16), a_kt tiles per block row), and
+    // for the output, written once more in that form where c_pieces is given (c_kt tiles per block
+    // row, at least 2 * ceil(N / 32); no dst_row) for the launch that reads it as its A operand.
+    const uint16_t* a_pieces = nullptr;
+    int a_kt = 0;
+    uint16_t* c_pieces = nullptr;
+    int c_kt = 0;
 };
 // GEMM_FP32: fp32 MFMA.  GEMM_SPLIT: every fp32 operand value as the exact sum of three bf16
 // values, the six largest of the nine partial products on the bf16 MFMA with fp32 accumulation
@@ -132,8 +139,10 @@ struct GemmGroup {
     int tile_start[GEMM_MAX_GROUP + 1];   // first workgroup of every problem
     GemmArgs p[GEMM_MAX_GROUP];
 };
-// *route (if given) receives the arithmetic the launch used: GEMM_FP32 or GEMM_SPLIT.
-hipError_t launch_gemm_group(const GemmArgs* problems, int count, hipStream_t s, int* route = nullptr);
+// *route (if given) receives the arithmetic the launch used: GEMM_FP32 or GEMM_SPLIT; *emitted (if
+// given) whether the launch wrote c_pieces (only the kernels that read their B operand as pieces do,
+// in launches of at most 256 small tiles, and only if every problem of the group asks for it).
+hipError_t launch_gemm_group(const GemmArgs* problems, int count, hipStream_t s, int* route = nullptr, bool* emitted = nullptr);
 
 // A row-major matrix W [R][C] as B operand of the bf16 MFMA block in both forms, each value split
 // into three bf16 pieces, stored tile by tile (32 n x 16 k) in lane order and zero beyond the

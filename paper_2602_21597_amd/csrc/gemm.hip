@@ -29,10 +29,11 @@ constexpr int PAD = 4;    // keeps LDS rows 16-byte aligned and spreads banks
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-template <int BM, int BN, int NW, bool SPLIT = false, bool BP = false>
+template <int BM, int BN, int NW, bool SPLIT = false, bool BP = false, bool AP = false>
 struct Smem {
-    // SPLIT: per wavefront and operand three bf16 pieces of a [32][BK] tile (BP: the A operand only)
-    static constexpr int STAGE = SPLIT ? NW * (BM / 32 + (BP ? 0 : BN / 32)) * 960 : NW * BK * (BM + PAD + BN + PAD);   // floats
+    // SPLIT: per wavefront and operand three bf16 pieces of a [32][BK] tile (BP, AP: that operand
+    // comes ready-made from global memory and is not staged)
+    static constexpr int STAGE = SPLIT ? NW * ((AP ? 0 : BM / 32) + (BP ? 0 : BN / 32)) * 960 : NW * BK * (BM + PAD + BN + PAD);   // floats
     static constexpr int NR = NW > 4 ? NW / 2 : NW;                    // partial tiles held in LDS at once
     static constexpr int REDUCE = NR * BM * (BN + 1);
     static constexpr int FLOATS = STAGE > REDUCE ? STAGE : REDUCE;
@@ -275,11 +276,12 @@ __device__ __forceinline__ bf16x8 piece_at(const uint16_t* tile, int q, int lane
     return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(tile + q * 512 + lane * 8));
 }
 
-template <int BM, int BN, int NW, bool AK, bool BKC, bool SPLIT = false, int PF = 1, bool BP = false>
+template <int BM, int BN, int NW, bool AK, bool BKC, bool SPLIT = false, int PF = 1, bool BP = false, bool AP = false>
 __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
     static_assert(!BP || (SPLIT && AK), "B operand from split pieces: split route with k-contiguous A only");
+    static_assert(!AP || (BP && BM == 32), "A operand from split pieces: with B from pieces, one block of rows");
     static_assert(!SPLIT || BK == 16, "split path: one 32x32x16 MFMA step per staged tile");
-    __shared__ __attribute__((aligned(16))) float smem[Smem<BM, BN, NW, SPLIT, BP>::FLOATS];
+    __shared__ __attribute__((aligned(16))) float smem[Smem<BM, BN, NW, SPLIT, BP, AP>::FLOATS];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
@@ -312,8 +314,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
     constexpr int TM = BM / 32, TN = BN / 32;
     constexpr int LDA = BM + PAD, LDB = BN + PAD;
     // (SPLIT: per 32 rows of an operand three pieces, SUBTILE bf16 = 960 floats)
-    float* As = smem + (SPLIT ? wave * (TM + (BP ? 0 : TN)) * 960 : wave * BK * (LDA + LDB));     // [BK][LDA] of this wavefront
-    float* Bs = As + (SPLIT ? TM * 960 : BK * LDA);                                      // [BK][LDB]
+    float* As = smem + (SPLIT ? wave * ((AP ? 0 : TM) + (BP ? 0 : TN)) * 960 : wave * BK * (LDA + LDB));     // [BK][LDA] of this wavefront
+    float* Bs = As + (SPLIT ? (AP ? 0 : TM) * 960 : BK * LDA);                                      // [BK][LDB]
 
     floatx16 acc[TM][TN];
 #pragma unroll
@@ -327,6 +329,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
     constexpr int LB = BN * BK / 4 / 64;
     float4 ra[PF][LA], rd[PF][LA], rb[PF][LB];
     bf16x8 bq[PF][BP ? BN / 32 : 1][3];       // BP: the B operand blocks of a tile, ready for the MFMA
+    bf16x8 aq[PF][3];                         // AP: the A operand block likewise
     const bool has_add = AK && a.a_ref != nullptr && a.a_add_idx != nullptr;   // uniform
     const bool copy_out = AK && a.a_copy != nullptr && first_n_tile;           // uniform
 
@@ -340,7 +343,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
         arow[i] = a.A;
         aadd[i] = a.A;
         avalid[i] = false;
-        if (AK) {
+        if (AK && !AP) {
             const int gm = m0 + (lane + i * 64) / (BK / 4);
             avalid[i] = gm < a.M;
             const int gmc = min(gm, a.M - 1);
@@ -383,7 +386,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
     const int nk = (a.K + BK - 1) / BK;
     const int rounds = nk > wave ? (nk - wave + NW - 1) / NW : 0;
 #define NGDB_ISSUE(u, kc)                                                                    \
-    if (SPLIT && !AK) {                                                                      \
+    if (AP) {                                                                                \
+        _Pragma("unroll") for (int q = 0; q < 3; ++q)                                       \
+            aq[u][q] = piece_at(a.a_pieces + ((size_t)(m0 / 32) * a.a_kt + (kc) / BK) * WTILE, q, lane); \
+    } else if (SPLIT && !AK) {                                                                      \
         _Pragma("unroll") for (int t = 0; t < TM; ++t)                                      \
             issue_strided(a.A, a.lda, a.K, a.M, kc, m0 + 32 * t, lane, reinterpret_cast<float4(&)[2]>(ra[u][2 * t])); \
     } else {                                                                                 \
@@ -420,7 +426,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
                               reinterpret_cast<const float4(&)[2]>(ra[u][2 * t]));
         }
 #pragma unroll
-        for (int i = 0; AK && i < LA; ++i) {
+        for (int i = 0; AK && !AP && i < LA; ++i) {
             const int idx = lane + i * 64;
             const int m = idx / (BK / 4), kq = idx % (BK / 4);
             const int gk = kcur + kq * 4;
@@ -446,8 +452,12 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
             v.x = ok ? v.x : 0.f; v.y = ok ? v.y : 0.f; v.z = ok ? v.z : 0.f; v.w = ok ? v.w : 0.f;
             store_pieces(Bp + (n >> 5) * SUBTILE, n & 31, kq, split3(v));
         }
-        __builtin_amdgcn_wave_barrier();
+        if (!AP) __builtin_amdgcn_wave_barrier();
         bf16x8 ap[TM][3], bp[TN][3];
+        if (AP) {
+#pragma unroll
+            for (int q = 0; q < 3; ++q) ap[0][q] = aq[u][q];
+        }
         if (BP) {
 #pragma unroll
             for (int j = 0; j < TN; ++j)
@@ -461,7 +471,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
 #pragma unroll
         for (int q = 0; q < 3; ++q) {
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+            for (int i = 0; !AP && i < TM; ++i)
                 ap[i][q] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Ap + i * SUBTILE + q * PIECE + unit_at<!AK>(lane)));
 #pragma unroll
             for (int j = 0; !BP && j < TN; ++j)
@@ -479,7 +489,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[i][0], bp[j][1], acc[i][j], 0, 0, 0);
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[i][0], bp[j][0], acc[i][j], 0, 0, 0);
             }
-        __builtin_amdgcn_wave_barrier();
+        if (!AP) __builtin_amdgcn_wave_barrier();
       }
     }
     for (int it0 = 0; !SPLIT && it0 < rounds; it0 += PF) {
@@ -524,7 +534,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
 
     // partial tiles -> LDS.  Accumulator layout of a 32x32 block: lane owns column
     // (lane & 31) and rows 8*(r/4) + 4*(lane/32) + r%4, r = 0..15.
-    constexpr int NR = Smem<BM, BN, NW, SPLIT, BP>::NR;
+    constexpr int NR = Smem<BM, BN, NW, SPLIT, BP, AP>::NR;
     float* red = smem + (wave % NR) * BM * (BN + 1);
 #define NGDB_ACC_TO_LDS()                                                                   \
     _Pragma("unroll") for (int i = 0; i < TM; ++i)                                         \
@@ -554,6 +564,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
     __syncthreads();
 
     // epilogue: the partial tiles are summed, the operands requested before the k loop applied
+    const bool emit = a.c_pieces != nullptr;    // uniform
 #pragma unroll
     for (int q = 0; q < EPT; ++q) {
         const int e = tid + q * NW * 64;
@@ -565,7 +576,27 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
         if (a.relu) v = fmaxf(v, 0.f);
         v = e_mask[q] > 0.f ? v : 0.f;
         v += e_add[q];
-        if (m0 + lr < a.M && n0 + lc < a.N) a.C[(size_t)e_orow[q] * a.ldc + n0 + lc] = v;
+        const bool inside = m0 + lr < a.M && n0 + lc < a.N;
+        if (inside) a.C[(size_t)e_orow[q] * a.ldc + n0 + lc] = v;
+        // (a slot of the first partial tile is read by the thread that owns the element only)
+        if (BM == 32 && BN == 32 && SPLIT && emit) smem[lr * (BN + 1) + lc] = inside ? v : 0.f;
+    }
+    // The output once more as bf16 pieces in tile order (zero beyond the matrix), for the launch that
+    // takes it as its A operand: block row m0/32, k-tiles n0/16 and n0/16 + 1; a lane of the first
+    // two wavefronts splits eight consecutive values of a row.
+    if (BM == 32 && BN == 32 && SPLIT && emit) {
+        __syncthreads();
+        if (tid < 128) {
+            const int lr = tid & 31, u = tid >> 5;
+            float x[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) x[j] = smem[lr * (BN + 1) + u * 8 + j];
+            const Pieces p0 = split3(make_float4(x[0], x[1], x[2], x[3])), p1 = split3(make_float4(x[4], x[5], x[6], x[7]));
+            uint16_t* out = a.c_pieces + ((size_t)(m0 / 32) * a.c_kt + n0 / 16 + (u >> 1)) * WTILE + ((u & 1) * 32 + lr) * 8;
+            *reinterpret_cast<uint4*>(out) = make_uint4(p0.h.x, p0.h.y, p1.h.x, p1.h.y);
+            *reinterpret_cast<uint4*>(out + 512) = make_uint4(p0.m.x, p0.m.y, p1.m.x, p1.m.y);
+            *reinterpret_cast<uint4*>(out + 1024) = make_uint4(p0.l.x, p0.l.y, p1.l.x, p1.l.y);
+        }
     }
 }
 
@@ -590,7 +621,7 @@ hipError_t dispatch_layout(GemmGroup& g, hipStream_t s) {
     return hipGetLastError();
 }
 
-template <int NW>
+template <int NW, bool AP>
 hipError_t dispatch_pieces(GemmGroup& g, hipStream_t s) {
     int tiles = 0;
     for (int i = 0; i < g.count; ++i) {
@@ -598,15 +629,17 @@ hipError_t dispatch_pieces(GemmGroup& g, hipStream_t s) {
         tiles += (((g.p[i].M + 31) / 32) * ((g.p[i].N + 31) / 32) + 7) / 8 * 8;
     }
     for (int i = g.count; i <= GEMM_MAX_GROUP; ++i) g.tile_start[i] = tiles;
-    hipLaunchKernelGGL((gemm_kernel<32, 32, NW, true, true, true, 1, true>), dim3(tiles), dim3(NW * 64), 0, s, g);
+    hipLaunchKernelGGL((gemm_kernel<32, 32, NW, true, true, true, AP ? 2 : 1, true, AP>), dim3(tiles), dim3(NW * 64), 0, s, g);
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_gemm_group(const GemmArgs* problems, int count, hipStream_t s, int* route) {
+hipError_t launch_gemm_group(const GemmArgs* problems, int count, hipStream_t s, int* route, bool* emitted) {
     if (route) *route = GEMM_FP32;
+    if (emitted) *emitted = false;
     GemmGroup g{};
+    uint16_t* c_pieces[GEMM_MAX_GROUP] = {};
     long blocks_small = 0;
     int max_k = 0;
     for (int i = 0; i < count; ++i) {
@@ -621,7 +654,9 @@ hipError_t launch_gemm_group(const GemmArgs* problems, int count, hipStream_t s,
         if (g.count && (a.a_kcontig != g.p[0].a_kcontig || a.b_kcontig != g.p[0].b_kcontig))
             return hipErrorInvalidValue;   // one operand layout per launch
         if (g.count && a.arith != g.p[0].arith) return hipErrorInvalidValue;
-        g.p[g.count++] = a;
+        c_pieces[g.count] = a.c_pieces;
+        g.p[g.count] = a;
+        g.p[g.count++].c_pieces = nullptr;    // (only the kernels chosen below for ready-made B operands write them)
         blocks_small += (long)((a.M + 31) / 32) * ((a.N + 63) / 64);
         max_k = std::max(max_k, a.K);
     }
@@ -652,8 +687,21 @@ hipError_t launch_gemm_group(const GemmArgs* problems, int count, hipStream_t s,
         bool all_pieces = g.p[0].a_kcontig;
         for (int i = 0; i < g.count; ++i) all_pieces = all_pieces && g.p[i].b_pieces != nullptr && g.p[i].b_kt >= (g.p[i].K + 15) / 16;
         if (all_pieces) {
-            if (blocks_small * 2 > 512) return dispatch_pieces<4>(g, s);
-            return dispatch_pieces<8>(g, s);
+            // ... and the A operand too where the launch before left its output as pieces
+            bool a_too = true;
+            for (int i = 0; i < g.count; ++i)
+                a_too = a_too && g.p[i].a_pieces != nullptr && !g.p[i].a_ref && !g.p[i].a_copy && g.p[i].a_kt >= (g.p[i].K + 15) / 16;
+            // (only from launches that leave compute units idle: in a larger one the extra stores cost
+            // more than the launch after it saves)
+            if (emitted && blocks_small * 2 <= 512) {
+                *emitted = true;
+                for (int i = 0; i < g.count; ++i)
+                    *emitted = *emitted && c_pieces[i] != nullptr && !g.p[i].dst_row && g.p[i].c_kt >= 2 * ((g.p[i].N + 31) / 32);
+                for (int i = 0; i < g.count; ++i)
+                    if (*emitted) g.p[i].c_pieces = c_pieces[i];
+            }
+            if (blocks_small * 2 > 512) return a_too ? dispatch_pieces<4, true>(g, s) : dispatch_pieces<4, false>(g, s);
+            return a_too ? dispatch_pieces<8, true>(g, s) : dispatch_pieces<8, false>(g, s);
         }
         if (blocks_small * 2 > 512) return dispatch_layout<32, 32, 4, true>(g, s);
         return dispatch_layout<32, 32, 8, true>(g, s);

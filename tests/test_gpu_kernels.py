@@ -77,6 +77,55 @@ def test_contraction_kernel_all_layouts_and_tile_paths(layout):
         print("       worst element error / sum |a||b|: %.2e" % worst, flush=True)
 
 
+@pytest.mark.parametrize("shape", [(1, 400, 800), (37, 400, 800), (200, 400, 800), (630, 400, 800), (987, 400, 800),
+                                   (45, 72, 136), (300, 36, 20), (96, 128, 64)])
+def test_mlp_chain_with_operands_as_pieces(shape):
+    """Forward and backward launch pairs of one MLP with the weights split once and the hidden rows
+    handed on as pieces, against numpy in fp64, element by element against the sum of |a||b|."""
+    import torch
+    from paper_2602_21597_amd import binding
+    M, d, h = shape
+    rng = np.random.default_rng(M + d)
+    X = rng.standard_normal((M, d)).astype(np.float32)
+    W1 = (rng.standard_normal((h, d)) / np.sqrt(d)).astype(np.float32)
+    W2 = (rng.standard_normal((d, h)) / np.sqrt(h)).astype(np.float32)
+    b1 = rng.standard_normal(h).astype(np.float32)
+    b2 = rng.standard_normal(d).astype(np.float32)
+    mask = rng.standard_normal((M, h)).astype(np.float32)
+    f = lambda a: torch.from_numpy(a).cuda()
+    X64, W164, W264 = X.astype(np.float64), W1.astype(np.float64), W2.astype(np.float64)
+    bar = 0.1 * 2e-6 * max(1.0, np.sqrt(max(d, h)) / 8)
+    for backward in (False, True):
+        print("[case] mlp chain", shape, "backward" if backward else "forward", flush=True)
+        H, Y, used = binding.debug_mlp(f(X), f(W1), f(b1), f(W2), f(b2), mask=f(mask), backward=backward)
+        H, Y = H.cpu().numpy(), Y.cpu().numpy()
+        assert used & 1, "the weights were not read as pieces"
+        small = ((M + 31) // 32) * ((h + 63) // 64) * 2 <= 512
+        assert bool(used & 2) == small, ("hidden rows as pieces", used, small)
+        if not backward:
+            pre = X64 @ W164.T + b1
+            wantH = np.maximum(pre, 0.0)
+            scaleH = np.abs(X64) @ np.abs(W164.T) + np.abs(b1)
+            # a hidden value rounded to zero or not at a pre-activation within rounding of zero: either is right
+            free = np.abs(pre) < bar * scaleH
+            W2x, scale2 = W264.T, np.abs(W264.T)
+            add = b2
+        else:
+            wantH = np.where(mask > 0, X64 @ W264, 0.0)
+            scaleH = np.abs(X64) @ np.abs(W264)
+            free = np.zeros_like(wantH, bool)
+            W2x, scale2 = W164, np.abs(W164)
+            add = 0.0
+        errH = np.abs(H - wantH) / scaleH
+        assert errH[~free].max() < bar, ("H", shape, backward, errH[~free].max())
+        # the second launch against the first one's own (fp32) output: its operand, whichever form it took
+        wantY = H.astype(np.float64) @ W2x + add
+        scaleY = np.abs(H).astype(np.float64) @ scale2 + np.abs(add)
+        errY = (np.abs(Y - wantY) / np.maximum(scaleY, 1e-30)).max()
+        assert errY < bar, ("Y", shape, backward, errY)
+        print("       worst element error / sum |a||b|: H %.2e  Y %.2e  (pieces of H: %s)" % (errH[~free].max(), errY, bool(used & 2)), flush=True)
+
+
 def test_split_contraction_keeps_fp32_accuracy_where_bf16_alone_would_not():
     """Operands with a wide spread of magnitudes and with values that need all 24 significand
     bits: the split arithmetic must stay at the fp32 level (a single bf16 piece would be off
