@@ -45,6 +45,17 @@ struct Smem {
 // loads: addresses are clamped into the operand, never branched on, and nothing
 // touches the loaded values before the tile is staged, so the loads of the next
 // tile stay in flight while the current one is multiplied.
+// A 16-byte load from global memory.  Row pointers picked at run time among several bases lose their
+// address space, and the loads through them would be FLAT ones: those count as LDS operations as
+// well, so every LDS read of the current tile would wait for the tile requested ahead.
+// (through a built-in vector type: float4 is a class, and copying one goes through a generic reference)
+__device__ __forceinline__ float4 load_global4(const float* p) {
+    typedef float floatx4 __attribute__((ext_vector_type(4)));
+    typedef const floatx4 __attribute__((address_space(1))) * global_floatx4;
+    const floatx4 v = *(global_floatx4)p;
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+
 template <int BM, int LA, bool AK>
 __device__ __forceinline__ void issue_a(const GemmArgs& a, int lane, int m0, int k0, bool has_add,
                                         const float* const (&arow)[LA], const float* const (&aadd)[LA],
@@ -54,11 +65,11 @@ __device__ __forceinline__ void issue_a(const GemmArgs& a, int lane, int m0, int
         const int idx = lane + i * 64;
         if (AK) {
             const int gkc = min(k0 + (idx % (BK / 4)) * 4, a.K - 4);
-            ra[i] = *reinterpret_cast<const float4*>(arow[i] + gkc);
-            if (has_add) rd[i] = *reinterpret_cast<const float4*>(aadd[i] + gkc);
+            ra[i] = load_global4(arow[i] + gkc);
+            if (has_add) rd[i] = load_global4(aadd[i] + gkc);
         } else {
             const int gk = k0 + idx / (BM / 4), gm = m0 + (idx % (BM / 4)) * 4;
-            ra[i] = *reinterpret_cast<const float4*>(a.A + (size_t)min(gk, a.K - 1) * a.lda + min(gm, a.M - 4));
+            ra[i] = load_global4(a.A + (size_t)min(gk, a.K - 1) * a.lda + min(gm, a.M - 4));
         }
     }
 }
@@ -76,7 +87,7 @@ __device__ __forceinline__ void issue_b(const GemmArgs& a, int lane, int n0, int
             const int gk = k0 + idx / (BN / 4), gn = n0 + (idx % (BN / 4)) * 4;
             p = a.B + (size_t)min(gk, a.K - 1) * a.ldb + min(gn, a.N - 4);
         }
-        rb[i] = *reinterpret_cast<const float4*>(p);
+        rb[i] = load_global4(p);
     }
 }
 
@@ -188,8 +199,8 @@ __device__ __forceinline__ void store_pieces(uint16_t* tile, int row, int kq, co
 __device__ __forceinline__ void issue_strided(const float* base, int ld, int K, int X, int k0, int x0, int lane,
                                               float4 (&r)[2]) {
     const int gk = k0 + 2 * (lane >> 3), gx = min(x0 + (lane & 7) * 4, X - 4);
-    r[0] = *reinterpret_cast<const float4*>(base + (size_t)min(gk, K - 1) * ld + gx);
-    r[1] = *reinterpret_cast<const float4*>(base + (size_t)min(gk + 1, K - 1) * ld + gx);
+    r[0] = load_global4(base + (size_t)min(gk, K - 1) * ld + gx);
+    r[1] = load_global4(base + (size_t)min(gk + 1, K - 1) * ld + gx);
 }
 __device__ __forceinline__ void stage_strided(uint16_t* tile, int K, int X, int k0, int x0, int lane,
                                               const float4 (&r)[2]) {
@@ -272,8 +283,9 @@ __global__ __launch_bounds__(256) void weight_pieces_kernel(const PieceJobs J) {
     }
 }
 
-__device__ __forceinline__ bf16x8 piece_at(const uint16_t* tile, int q, int lane) {
-    return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(tile + q * 512 + lane * 8));
+// (at: the lane's place in the first piece of a tile)
+__device__ __forceinline__ bf16x8 piece_at(const uint16_t* at, int q) {
+    return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(at + q * 512));
 }
 
 template <int BM, int BN, int NW, bool AK, bool BKC, bool SPLIT = false, int PF = 1, bool BP = false, bool AP = false>
@@ -385,37 +397,57 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
     // independently (their memory waits do not line up) and only over the tiles they own.
     const int nk = (a.K + BK - 1) / BK;
     const int rounds = nk > wave ? (nk - wave + NW - 1) / NW : 0;
-#define NGDB_ISSUE(u, kc)                                                                    \
+    // (operands that come as fp32 values, to be staged, and operands that come as pieces)
+#define NGDB_ISSUE_VALUES(u, kc)                                                             \
     if (AP) {                                                                                \
-        _Pragma("unroll") for (int q = 0; q < 3; ++q)                                       \
-            aq[u][q] = piece_at(a.a_pieces + ((size_t)(m0 / 32) * a.a_kt + (kc) / BK) * WTILE, q, lane); \
-    } else if (SPLIT && !AK) {                                                                      \
+    } else if (SPLIT && !AK) {                                                               \
         _Pragma("unroll") for (int t = 0; t < TM; ++t)                                      \
             issue_strided(a.A, a.lda, a.K, a.M, kc, m0 + 32 * t, lane, reinterpret_cast<float4(&)[2]>(ra[u][2 * t])); \
     } else {                                                                                 \
         issue_a<BM, LA, AK>(a, lane, m0, kc, has_add, arow, aadd, ra[u], rd[u]);            \
     }                                                                                        \
     if (BP) {                                                                                \
-        _Pragma("unroll") for (int j = 0; j < BN / 32; ++j)                                 \
-            _Pragma("unroll") for (int q = 0; q < 3; ++q)                                   \
-                bq[u][BP ? j : 0][q] = piece_at(a.b_pieces + ((size_t)(n0 / 32 + j) * a.b_kt + (kc) / BK) * WTILE, q, lane); \
     } else if (SPLIT && !BKC) {                                                              \
         _Pragma("unroll") for (int t = 0; t < TN; ++t)                                      \
             issue_strided(a.B, a.ldb, a.K, a.N, kc, n0 + 32 * t, lane, reinterpret_cast<float4(&)[2]>(rb[u][2 * t])); \
     } else {                                                                                 \
         issue_b<BN, LB, BKC>(a, lane, n0, kc, rb[u]);                                       \
     }
+#define NGDB_ISSUE_PIECES(u, kc, live)                                                       \
+    if (AP) {                                                                                \
+        const uint16_t* at = (live) ? a.a_pieces + ((size_t)(m0 / 32) * a.a_kt + (kc) / BK) * WTILE + lane * 8 : a.a_pieces; \
+        _Pragma("unroll") for (int q = 0; q < 3; ++q) aq[u][q] = piece_at(at, q);           \
+    }                                                                                        \
+    if (BP) {                                                                                \
+        _Pragma("unroll") for (int j = 0; j < BN / 32; ++j) {                               \
+            const uint16_t* at = (live) ? a.b_pieces + ((size_t)(n0 / 32 + j) * a.b_kt + (kc) / BK) * WTILE + lane * 8 : a.b_pieces; \
+            _Pragma("unroll") for (int q = 0; q < 3; ++q) bq[u][BP ? j : 0][q] = piece_at(at, q); \
+        }                                                                                    \
+    }
+    // PF tiles are in flight per wavefront.  With more than one, every stage of the loop requests
+    // its next tile whether or not there is one (beyond the end: the first k-tile once more for the
+    // staged values, one 16-byte word for all lanes for the pieces, neither used): with the same
+    // loads on every path the compiler can wait for a stage's own loads alone (vmcnt = what was
+    // requested after them), where a request under a condition makes it wait for everything outstanding.
 #pragma unroll
-    for (int u = 0; u < PF; ++u)
-        if (u < rounds) {
-            const int kc = (u * NW + wave) * BK;
-            NGDB_ISSUE(u, kc)
+    for (int u = 0; u < PF; ++u) {
+        const bool live = u < rounds;
+        const int kc = live ? (u * NW + wave) * BK : 0;
+        if (SPLIT && PF > 1) {
+            NGDB_ISSUE_VALUES(u, kc)
+            NGDB_ISSUE_PIECES(u, kc, live)
+        } else if (live) {
+            NGDB_ISSUE_VALUES(u, kc)
+            NGDB_ISSUE_PIECES(u, kc, true)
         }
+    }
     for (int it0 = 0; SPLIT && it0 < rounds; it0 += PF) {
 #pragma unroll
       for (int u = 0; u < PF; ++u) {
         const int it = it0 + u;
-        if (it >= rounds) break;
+        const bool live_next = it + PF < rounds;
+        const int knext = live_next ? ((it + PF) * NW + wave) * BK : 0;
+        if (it < rounds) {
         const int kcur = (it * NW + wave) * BK;
         uint16_t* Ap = reinterpret_cast<uint16_t*>(As);
         uint16_t* Bp = reinterpret_cast<uint16_t*>(Bs);
@@ -453,6 +485,9 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
             store_pieces(Bp + (n >> 5) * SUBTILE, n & 31, kq, split3(v));
         }
         if (!AP) __builtin_amdgcn_wave_barrier();
+        // Operands that came as pieces are multiplied from the registers they were loaded into, and
+        // those registers are requested again only after the MFMAs: copied aside first, the compiler
+        // would load into temporaries and wait for them in the middle of the MFMAs.
         bf16x8 ap[TM][3], bp[TN][3];
         if (AP) {
 #pragma unroll
@@ -464,10 +499,9 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
 #pragma unroll
                 for (int q = 0; q < 3; ++q) bp[j][q] = bq[u][BP ? j : 0][q];
         }
-        if (it + PF < rounds) {           // the registers of this tile are free again
-            const int kc = ((it + PF) * NW + wave) * BK;
-            NGDB_ISSUE(u, kc)
-        }
+        // the staged values' registers are free again: their next tile is under way during the MFMAs
+        // (one tile in flight: nothing for the compiler to count, and no request beyond the end)
+        if (PF == 1 && live_next) { NGDB_ISSUE_VALUES(u, knext) }
 #pragma unroll
         for (int q = 0; q < 3; ++q) {
 #pragma unroll
@@ -490,6 +524,12 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[i][0], bp[j][0], acc[i][j], 0, 0, 0);
             }
         if (!AP) __builtin_amdgcn_wave_barrier();
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (PF > 1) { NGDB_ISSUE_VALUES(u, knext) }
+        if (PF > 1 || live_next) {
+            NGDB_ISSUE_PIECES(u, knext, live_next)
+        }
       }
     }
     for (int it0 = 0; !SPLIT && it0 < rounds; it0 += PF) {
@@ -503,7 +543,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
         __builtin_amdgcn_wave_barrier();        // staged tile before its reads (compiler ordering only)
         if (it + PF < rounds) {
             const int kc = ((it + PF) * NW + wave) * BK;
-            NGDB_ISSUE(u, kc)
+            NGDB_ISSUE_VALUES(u, kc)
         }
         // all LDS operand reads of the tile are issued before the first MFMA, so that the
         // matrix pipe never waits for an LDS round trip between k steps
@@ -529,7 +569,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
     }
     if (!EARLY_EPILOGUE) { NGDB_LOAD_EPILOGUE() }   // in flight during the reduction
 #undef NGDB_LOAD_EPILOGUE
-#undef NGDB_ISSUE
+#undef NGDB_ISSUE_VALUES
+#undef NGDB_ISSUE_PIECES
     __syncthreads();                            // the staging areas are reused for the reduction
 
     // partial tiles -> LDS.  Accumulator layout of a 32x32 block: lane owns column
@@ -621,15 +662,16 @@ hipError_t dispatch_layout(GemmGroup& g, hipStream_t s) {
     return hipGetLastError();
 }
 
-template <int NW, bool AP>
+template <int NW, bool AP, int PF>
 hipError_t dispatch_pieces(GemmGroup& g, hipStream_t s) {
+    constexpr int BM = 32, BN = 32;
     int tiles = 0;
     for (int i = 0; i < g.count; ++i) {
         g.tile_start[i] = tiles;
-        tiles += (((g.p[i].M + 31) / 32) * ((g.p[i].N + 31) / 32) + 7) / 8 * 8;
+        tiles += (((g.p[i].M + BM - 1) / BM) * ((g.p[i].N + BN - 1) / BN) + 7) / 8 * 8;
     }
     for (int i = g.count; i <= GEMM_MAX_GROUP; ++i) g.tile_start[i] = tiles;
-    hipLaunchKernelGGL((gemm_kernel<32, 32, NW, true, true, true, AP ? 2 : 1, true, AP>), dim3(tiles), dim3(NW * 64), 0, s, g);
+    hipLaunchKernelGGL((gemm_kernel<BM, BN, NW, true, true, true, PF, true, AP>), dim3(tiles), dim3(NW * 64), 0, s, g);
     return hipGetLastError();
 }
 
@@ -700,8 +742,8 @@ hipError_t launch_gemm_group(const GemmArgs* problems, int count, hipStream_t s,
                 for (int i = 0; i < g.count; ++i)
                     if (*emitted) g.p[i].c_pieces = c_pieces[i];
             }
-            if (blocks_small * 2 > 512) return a_too ? dispatch_pieces<4, true>(g, s) : dispatch_pieces<4, false>(g, s);
-            return a_too ? dispatch_pieces<8, true>(g, s) : dispatch_pieces<8, false>(g, s);
+            if (blocks_small * 2 > 512) return a_too ? dispatch_pieces<4, true, 2>(g, s) : dispatch_pieces<4, false, 1>(g, s);
+            return a_too ? dispatch_pieces<8, true, 2>(g, s) : dispatch_pieces<8, false, 1>(g, s);
         }
         if (blocks_small * 2 > 512) return dispatch_layout<32, 32, 4, true>(g, s);
         return dispatch_layout<32, 32, 8, true>(g, s);
