@@ -448,82 +448,82 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
         const bool live_next = it + PF < rounds;
         const int knext = live_next ? ((it + PF) * NW + wave) * BK : 0;
         if (it < rounds) {
-        const int kcur = (it * NW + wave) * BK;
-        uint16_t* Ap = reinterpret_cast<uint16_t*>(As);
-        uint16_t* Bp = reinterpret_cast<uint16_t*>(Bs);
-        if (!AK) {
+            const int kcur = (it * NW + wave) * BK;
+            uint16_t* Ap = reinterpret_cast<uint16_t*>(As);
+            uint16_t* Bp = reinterpret_cast<uint16_t*>(Bs);
+            if (!AK) {
 #pragma unroll
-            for (int t = 0; t < TM; ++t)
-                stage_strided(Ap + t * SUBTILE, a.K, a.M, kcur, m0 + 32 * t, lane,
-                              reinterpret_cast<const float4(&)[2]>(ra[u][2 * t]));
-        }
-#pragma unroll
-        for (int i = 0; AK && !AP && i < LA; ++i) {
-            const int idx = lane + i * 64;
-            const int m = idx / (BK / 4), kq = idx % (BK / 4);
-            const int gk = kcur + kq * 4;
-            float4 v = ra[u][i];
-            if (has_add) { v.x += rd[u][i].x; v.y += rd[u][i].y; v.z += rd[u][i].z; v.w += rd[u][i].w; }
-            const bool ok = avalid[i] && gk < a.K;
-            v.x = ok ? v.x : 0.f; v.y = ok ? v.y : 0.f; v.z = ok ? v.z : 0.f; v.w = ok ? v.w : 0.f;
-            if (copy_out && ok) *reinterpret_cast<float4*>(a.a_copy + (size_t)(m0 + m) * a.lda + gk) = v;
-            store_pieces(Ap + (m >> 5) * SUBTILE, m & 31, kq, split3(v));
-        }
-        if (!BKC && !BP) {
-#pragma unroll
-            for (int t = 0; t < TN; ++t)
-                stage_strided(Bp + t * SUBTILE, a.K, a.N, kcur, n0 + 32 * t, lane,
-                              reinterpret_cast<const float4(&)[2]>(rb[u][2 * t]));
-        }
-#pragma unroll
-        for (int i = 0; BKC && !BP && i < LB; ++i) {
-            const int idx = lane + i * 64;
-            const int n = idx / (BK / 4), kq = idx % (BK / 4);
-            float4 v = rb[u][i];
-            const bool ok = n0 + n < a.N && kcur + kq * 4 < a.K;
-            v.x = ok ? v.x : 0.f; v.y = ok ? v.y : 0.f; v.z = ok ? v.z : 0.f; v.w = ok ? v.w : 0.f;
-            store_pieces(Bp + (n >> 5) * SUBTILE, n & 31, kq, split3(v));
-        }
-        if (!AP) __builtin_amdgcn_wave_barrier();
-        // Operands that came as pieces are multiplied from the registers they were loaded into, and
-        // those registers are requested again only after the MFMAs: copied aside first, the compiler
-        // would load into temporaries and wait for them in the middle of the MFMAs.
-        bf16x8 ap[TM][3], bp[TN][3];
-        if (AP) {
-#pragma unroll
-            for (int q = 0; q < 3; ++q) ap[0][q] = aq[u][q];
-        }
-        if (BP) {
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int q = 0; q < 3; ++q) bp[j][q] = bq[u][BP ? j : 0][q];
-        }
-        // the staged values' registers are free again: their next tile is under way during the MFMAs
-        // (one tile in flight: nothing for the compiler to count, and no request beyond the end)
-        if (PF == 1 && live_next) { NGDB_ISSUE_VALUES(u, knext) }
-#pragma unroll
-        for (int q = 0; q < 3; ++q) {
-#pragma unroll
-            for (int i = 0; !AP && i < TM; ++i)
-                ap[i][q] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Ap + i * SUBTILE + q * PIECE + unit_at<!AK>(lane)));
-#pragma unroll
-            for (int j = 0; !BP && j < TN; ++j)
-                bp[j][q] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Bp + j * SUBTILE + q * PIECE + unit_at<!BKC>(lane)));
-        }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {   // smallest products first
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[i][2], bp[j][0], acc[i][j], 0, 0, 0);
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[i][0], bp[j][2], acc[i][j], 0, 0, 0);
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[i][1], bp[j][1], acc[i][j], 0, 0, 0);
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[i][1], bp[j][0], acc[i][j], 0, 0, 0);
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[i][0], bp[j][1], acc[i][j], 0, 0, 0);
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[i][0], bp[j][0], acc[i][j], 0, 0, 0);
+                for (int t = 0; t < TM; ++t)
+                    stage_strided(Ap + t * SUBTILE, a.K, a.M, kcur, m0 + 32 * t, lane,
+                                  reinterpret_cast<const float4(&)[2]>(ra[u][2 * t]));
             }
-        if (!AP) __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int i = 0; AK && !AP && i < LA; ++i) {
+                const int idx = lane + i * 64;
+                const int m = idx / (BK / 4), kq = idx % (BK / 4);
+                const int gk = kcur + kq * 4;
+                float4 v = ra[u][i];
+                if (has_add) { v.x += rd[u][i].x; v.y += rd[u][i].y; v.z += rd[u][i].z; v.w += rd[u][i].w; }
+                const bool ok = avalid[i] && gk < a.K;
+                v.x = ok ? v.x : 0.f; v.y = ok ? v.y : 0.f; v.z = ok ? v.z : 0.f; v.w = ok ? v.w : 0.f;
+                if (copy_out && ok) *reinterpret_cast<float4*>(a.a_copy + (size_t)(m0 + m) * a.lda + gk) = v;
+                store_pieces(Ap + (m >> 5) * SUBTILE, m & 31, kq, split3(v));
+            }
+            if (!BKC && !BP) {
+#pragma unroll
+                for (int t = 0; t < TN; ++t)
+                    stage_strided(Bp + t * SUBTILE, a.K, a.N, kcur, n0 + 32 * t, lane,
+                                  reinterpret_cast<const float4(&)[2]>(rb[u][2 * t]));
+            }
+#pragma unroll
+            for (int i = 0; BKC && !BP && i < LB; ++i) {
+                const int idx = lane + i * 64;
+                const int n = idx / (BK / 4), kq = idx % (BK / 4);
+                float4 v = rb[u][i];
+                const bool ok = n0 + n < a.N && kcur + kq * 4 < a.K;
+                v.x = ok ? v.x : 0.f; v.y = ok ? v.y : 0.f; v.z = ok ? v.z : 0.f; v.w = ok ? v.w : 0.f;
+                store_pieces(Bp + (n >> 5) * SUBTILE, n & 31, kq, split3(v));
+            }
+            if (!AP) __builtin_amdgcn_wave_barrier();
+            // Operands that came as pieces are multiplied from the registers they were loaded into, and
+            // those registers are requested again only after the MFMAs: copied aside first, the compiler
+            // would load into temporaries and wait for them in the middle of the MFMAs.
+            bf16x8 ap[TM][3], bp[TN][3];
+            if (AP) {
+#pragma unroll
+                for (int q = 0; q < 3; ++q) ap[0][q] = aq[u][q];
+            }
+            if (BP) {
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int q = 0; q < 3; ++q) bp[j][q] = bq[u][BP ? j : 0][q];
+            }
+            // the staged values' registers are free again: their next tile is under way during the MFMAs
+            // (one tile in flight: nothing for the compiler to count, and no request beyond the end)
+            if (PF == 1 && live_next) { NGDB_ISSUE_VALUES(u, knext) }
+#pragma unroll
+            for (int q = 0; q < 3; ++q) {
+#pragma unroll
+                for (int i = 0; !AP && i < TM; ++i)
+                    ap[i][q] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Ap + i * SUBTILE + q * PIECE + unit_at<!AK>(lane)));
+#pragma unroll
+                for (int j = 0; !BP && j < TN; ++j)
+                    bp[j][q] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Bp + j * SUBTILE + q * PIECE + unit_at<!BKC>(lane)));
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {   // smallest products first
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[i][2], bp[j][0], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[i][0], bp[j][2], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[i][1], bp[j][1], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[i][1], bp[j][0], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[i][0], bp[j][1], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[i][0], bp[j][0], acc[i][j], 0, 0, 0);
+                }
+            if (!AP) __builtin_amdgcn_wave_barrier();
         }
         __builtin_amdgcn_sched_barrier(0);
         if (PF > 1) { NGDB_ISSUE_VALUES(u, knext) }
