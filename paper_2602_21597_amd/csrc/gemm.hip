@@ -16,6 +16,10 @@
 // MFMA blocks, or (SPLIT) bf16 MFMA blocks on operands that are split, while a tile is
 // staged, into three bf16 pieces whose sum is the fp32 value exactly; six of the nine
 // partial products are kept.  The matrix unit then needs 2.7 times less time per tile.
+// On the split route the small tile can take operands that were split beforehand (BP: the
+// weights, once per pass, by weight_pieces_kernel; AP: the hidden rows, by the epilogue of
+// the launch that produced them): such pieces lie in global memory tile by tile in the lane
+// order of the MFMA and go from there straight into its operand registers.
 #include "common.h"
 
 namespace ngdb {
