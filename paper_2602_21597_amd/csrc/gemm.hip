@@ -38,7 +38,9 @@ struct Smem {
     // SPLIT: per wavefront and operand three bf16 pieces of a [32][BK] tile (BP, AP: that operand
     // comes ready-made from global memory and is not staged)
     static constexpr int STAGE = SPLIT ? NW * ((AP ? 0 : BM / 32) + (BP ? 0 : BN / 32)) * 960 : NW * BK * (BM + PAD + BN + PAD);   // floats
-    static constexpr int NR = NW > 4 ? NW / 2 : NW;                    // partial tiles held in LDS at once
+    // partial tiles held in LDS at once: all of them in the small tile (one barrier less than folding
+    // the upper half of the wavefronts into the lower half first, 34 KB for eight)
+    static constexpr int NR = (NW > 4 && BM * BN > 32 * 32) ? NW / 2 : NW;
     static constexpr int REDUCE = NR * BM * (BN + 1);
     static constexpr int FLOATS = STAGE > REDUCE ? STAGE : REDUCE;
 };
