@@ -312,10 +312,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmGroup g) {
             first = g.tile_start[i];
             last = g.tile_start[i + 1];
         }
-    GemmArgs a = g.p[0];
-#pragma unroll
-    for (int i = 1; i < GEMM_MAX_GROUP; ++i)
-        if (i == p) a = g.p[i];
+    const GemmArgs& a = g.p[p];        // (the group lies in the kernel argument segment: a scalar load at a uniform offset)
     // Workgroups are dealt round-robin to the 8 dies, each with its own L2.  Every problem
     // owns a multiple of 8 workgroups, and die x takes the x-th eighth of the problem's
     // tiles, ordered so that this eighth is a slab along the longer output side: a die then
