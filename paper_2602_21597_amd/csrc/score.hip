@@ -56,7 +56,11 @@ __device__ __forceinline__ void load_row(const ScoreArgs& a, int32_t e, int lane
 // stays small enough for eight wavefronts per SIMD; in larger workgroups (small batches) through
 // a staging area per wavefront and one barrier.
 // B16: candidate rows come from the bf16 copy of the table.
-template <int NCH, int NW, bool TRAIN, bool MASK, bool BOX, bool B16>
+// STASH: the per-pair results (score, dL/ds, winning branch) are kept in LDS and written after the
+// candidate loop.  Stores under a lane condition inside the loop would make every wait in it a wait
+// for everything outstanding (the compiler cannot count requests that may or may not be issued),
+// the row requested ahead included.
+template <int NCH, int NW, bool TRAIN, bool MASK, bool BOX, bool B16, bool STASH>
 __global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
     extern __shared__ __attribute__((aligned(16))) float lds[];
     const int i = blockIdx.x;
@@ -73,6 +77,9 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
     constexpr bool SEQ = NW <= 4;                                    // how branch 0 is summed over the wavefronts
     float4* stage = accs + (TRAIN ? (size_t)NW * PARTS * (a.max_branch - 1) * d4 : 0);   // [NW][PARTS][d4]  (!SEQ)
     float* lossp = reinterpret_cast<float*>(stage + (TRAIN && !SEQ ? (size_t)NW * PARTS * d4 : 0));
+    float* out_s = lossp + 16;                                       // [CT] scores          (STASH)
+    float* out_c = out_s + CT;                                       // [CT] dL/ds           (STASH, TRAIN)
+    int* out_b = reinterpret_cast<int*>(out_c + CT);                 // [CT] winning branch  (STASH, TRAIN, no MASK)
     const float4* obr = ybr + (size_t)nb * d4;                       // offsets (BOX)
 
     for (int idx = tid; idx < PARTS * nb * d4; idx += NW * 64) {
@@ -99,9 +106,10 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
     float lsum = 0.f;
 
     // The id of a candidate is requested two rounds ahead of its use and its row one round
-    // ahead, so that a row request never waits for its id (a second row in flight per
-    // wavefront costs more in occupancy than it hides).  Requests past the end repeat the
-    // last candidate (clamped, no branches around loads).
+    // ahead, so that a row request never waits for its id (more rows in flight per wavefront,
+    // three sets of row registers used in turn, gain 1 % on long candidate lists and lose 20 %
+    // on short ones).  Requests past the end repeat the last candidate (clamped, no branches
+    // around loads).
     float4 cur[NCH], nxt[NCH];
     int c = wave;
     int32_t e_nxt = cand_id(a, i, has_pos, min(c + NW, CT - 1));
@@ -138,7 +146,8 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
         }
         const float s = a.gamma - best;
         const size_t pair = (size_t)i * CT + c;
-        if (lane == 0) a.score[pair] = s;
+        if (STASH) out_s[c] = s;                 // (every lane the same value to the same word)
+        else if (lane == 0) a.score[pair] = s;
         if (TRAIN) {
             const bool is_pos = (c == 0);
             // The positive contributes softplus(-s) with dL/ds = -sigmoid(-s)/(2B), a negative
@@ -155,7 +164,10 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
             const float sig = z >= 0.f ? r : e * r;
             const float coef = (is_pos ? -inv2B : inv2B) * wq * sig;
             lsum += wq * (fmaxf(z, 0.f) + fast_log1p_unit(e));
-            if (lane == 0) {
+            if (STASH) {
+                out_c[c] = coef;
+                if (!MASK) out_b[c] = bw;
+            } else if (lane == 0) {
                 a.coef[pair] = coef;
                 if (!MASK) a.win[pair] = a.root_slot[r0 + bw];
             }
@@ -212,6 +224,17 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
         for (int ch = 0; ch < NCH; ++ch) cur[ch] = nxt[ch];
     }
 
+    if (STASH) {
+        __syncthreads();
+        for (int idx = tid; idx < CT; idx += NW * 64) {
+            const size_t pair = (size_t)i * CT + idx;
+            a.score[pair] = out_s[idx];
+            if (TRAIN) {
+                a.coef[pair] = out_c[idx];
+                if (!MASK) a.win[pair] = a.root_slot[r0 + out_b[idx]];
+            }
+        }
+    }
     if (TRAIN) {
         if (lane == 0) lossp[wave] = lsum;
         // branch 0: summed over the wavefronts in a fixed order, either through the staging area or
@@ -289,13 +312,22 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(const ScoreArgs a) {
     }
 }
 
+constexpr int STASH_MAX_PAIRS = 4096;     // pairs per query whose results fit the LDS stash (48 KB)
+template <int NCH, int NW, bool TRAIN, bool MASK, bool BOX, bool B16, bool STASH>
+hipError_t launch_stash(const ScoreArgs& a, size_t lds, hipStream_t s) {
+    if (lds > 64 * 1024)
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(score_kernel<NCH, NW, TRAIN, MASK, BOX, B16, STASH>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipLaunchKernelGGL((score_kernel<NCH, NW, TRAIN, MASK, BOX, B16, STASH>), dim3(a.B), dim3(NW * 64), lds, s, a);
+    return hipGetLastError();
+}
 template <int NCH, int NW, bool TRAIN, bool MASK, bool BOX, bool B16 = false>
 hipError_t launch_variant(const ScoreArgs& a, size_t lds, hipStream_t s) {
-    if (lds > 64 * 1024)
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(score_kernel<NCH, NW, TRAIN, MASK, BOX, B16>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    hipLaunchKernelGGL((score_kernel<NCH, NW, TRAIN, MASK, BOX, B16>), dim3(a.B), dim3(NW * 64), lds, s, a);
-    return hipGetLastError();
+    const int CT = a.C + (a.pos ? 1 : 0);
+    const size_t stash = (size_t)CT * (TRAIN ? 3 : 1) * sizeof(float);
+    if (CT <= STASH_MAX_PAIRS && lds + stash <= 150 * 1024)
+        return launch_stash<NCH, NW, TRAIN, MASK, BOX, B16, true>(a, lds + stash, s);
+    return launch_stash<NCH, NW, TRAIN, MASK, BOX, B16, false>(a, lds, s);
 }
 
 template <int NCH, int NW>

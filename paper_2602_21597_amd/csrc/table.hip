@@ -105,13 +105,16 @@ __device__ __forceinline__ void row_store(float4* p, float4 v) {
     __builtin_nontemporal_store(t, reinterpret_cast<table_f4*>(p));
 }
 
-template <int NCH, bool SEM, bool BOX, bool SH, bool NT = false>
+// UPD: the pass applies Adam (known when the kernel is chosen; otherwise a.g_out decides at run time).
+// With the choice open, the stores of either path count as "maybe issued" for the compiler, and the
+// wait for the next row's parameter rows, requested before them, also waits for the stores.
+template <int NCH, bool SEM, bool BOX, bool SH, bool NT = false, bool UPD = false>
 __device__ __forceinline__ void table_rows(const TableArgs& a, const AdamHyper& hp, int wave_global, int n_waves) {
     const int lane = threadIdx.x & 63;
     const int d4 = a.d >> 2;
     const int n_uniq = *a.n_uniq_dev;
     const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
-    const bool update = a.g_out == nullptr;
+    const bool update = UPD || a.g_out == nullptr;
     const float step1 = hp.lr / hp.bc1, ibc2 = 1.f / hp.bc2;   // lr / (1 - beta1^t), 1 / (1 - beta2^t): once per wavefront
     bool col_ok[NCH];
     int colc[NCH];
@@ -283,16 +286,27 @@ __device__ __forceinline__ void table_rows(const TableArgs& a, const AdamHyper& 
                 g[ch].w = p[ch].w > 0.f ? g[ch].w : 0.f;
             }
         }
+        // Stores without a lane condition (plain rows of tables that stay in the caches): the lanes
+        // past the end of the row hold, through their clamped loads, the values of its last four
+        // coordinates and write those once more.  Under a condition the stores may or may not be
+        // issued as far as the compiler can tell, and the next row's wait for its parameter rows,
+        // requested before them, becomes a wait for the stores too.  (With text features the sign
+        // codes of those lanes are not the last column's; tables streamed from HBM are faster with
+        // that wait: 4.32 against 4.49 ms at 2 M touched rows.)
+        constexpr bool ALL_LANES = !SEM && !NT;
         if (!update) {
             float4* orow = reinterpret_cast<float4*>(a.g_out + (size_t)u * a.d);
 #pragma unroll
-            for (int ch = 0; ch < NCH; ++ch)
-                if (col_ok[ch]) orow[ch * 64 + lane] = g[ch];
+            for (int ch = 0; ch < NCH; ++ch) {
+                if (ALL_LANES) orow[colc[ch]] = g[ch];
+                else if (col_ok[ch]) orow[ch * 64 + lane] = g[ch];
+            }
             continue;
         }
 #pragma unroll
         for (int ch = 0; ch < NCH; ++ch) {
-            if (col_ok[ch]) {
+            const int at = ALL_LANES ? colc[ch] : ch * 64 + lane;
+            if (ALL_LANES || col_ok[ch]) {
                 // (reciprocal and square root by the hardware approximations, about 1 ulp each: the
                 // correctly rounded forms cost some sixty instructions per coordinate, which made
                 // this memory-bound kernel wait for its own arithmetic)
@@ -303,11 +317,11 @@ __device__ __forceinline__ void table_rows(const TableArgs& a, const AdamHyper& 
     p[ch].F -= (step1 * m[ch].F) * fast_rcp(fast_sqrt(v[ch].F * ibc2) + hp.eps);
                 NGDB_ADAM(x) NGDB_ADAM(y) NGDB_ADAM(z) NGDB_ADAM(w)
 #undef NGDB_ADAM
-                row_store<NT>(mrow + ch * 64 + lane, m[ch]);
-                row_store<NT>(vrow + ch * 64 + lane, v[ch]);
-                row_store<NT>(prow + ch * 64 + lane, p[ch]);
+                row_store<NT>(mrow + at, m[ch]);
+                row_store<NT>(vrow + at, v[ch]);
+                row_store<NT>(prow + at, p[ch]);
                 if (SH)
-                    reinterpret_cast<uint2*>(a.shadow + (size_t)row * a.d)[ch * 64 + lane] =
+                    reinterpret_cast<uint2*>(a.shadow + (size_t)row * a.d)[at] =
                         make_uint2(bf16_bits(p[ch].x) | (bf16_bits(p[ch].y) << 16),
                                    bf16_bits(p[ch].z) | (bf16_bits(p[ch].w) << 16));
             }
@@ -325,30 +339,30 @@ __device__ __forceinline__ void table_rows(const TableArgs& a, const AdamHyper& 
 // each add their latency to the step's tail).  Large tables keep table_kernel: there this
 // kernel measured 3 % slower on the entity table than the launches it saves are worth.
 // one table per launch
-template <int NCH, bool SEM, bool BOX, bool SH, bool NT>
+template <int NCH, bool SEM, bool BOX, bool SH, bool NT, bool UPD>
 __global__ __launch_bounds__(256) void table_kernel(const TableArgs a, const AdamHyper hp) {
-    table_rows<NCH, SEM, BOX, SH, NT>(a, hp, (int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6),
+    table_rows<NCH, SEM, BOX, SH, NT, UPD>(a, hp, (int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6),
                                   (int)((gridDim.x * blockDim.x) >> 6));
 }
 
 // (box family at d <= 512: every pair re-reads two cached rows, and a fourth wavefront per SIMD
 // costs more in cache misses than it hides: held at three)
-template <int NCH, bool SEM, bool BOX, bool SH>
+template <int NCH, bool SEM, bool BOX, bool SH, bool UPD>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (BOX && NCH == 2) ? 3 : 8)))
 void table_group_kernel(const TableArgs a, const TableTail tail, const AdamHyper hp) {
     const int b = (int)blockIdx.x;
     const int mb = b - tail.blocks[0] - tail.blocks[1];
     if (mb >= 0) {
         // (the wavefront's number is the same in all its lanes: kept in a scalar register)
-        table_rows<NCH, SEM, BOX, SH>(a, hp, __builtin_amdgcn_readfirstlane((int)((mb * blockDim.x + threadIdx.x) >> 6)),
-                                      tail.main_blocks * 4);
+        table_rows<NCH, SEM, BOX, SH, false, UPD>(a, hp, __builtin_amdgcn_readfirstlane((int)((mb * blockDim.x + threadIdx.x) >> 6)),
+                                                  tail.main_blocks * 4);
         return;
     }
     const int k = b < tail.blocks[0] ? 0 : 1;
     const int lb = k ? b - tail.blocks[0] : b;
-    table_rows<NCH, false, false, false>(tail.job[k], hp,
-                                         __builtin_amdgcn_readfirstlane((int)((lb * blockDim.x + threadIdx.x) >> 6)),
-                                         tail.blocks[k] * 4);
+    table_rows<NCH, false, false, false, false, UPD>(tail.job[k], hp,
+                                                     __builtin_amdgcn_readfirstlane((int)((lb * blockDim.x + threadIdx.x) >> 6)),
+                                                     tail.blocks[k] * 4);
 }
 
 
@@ -381,11 +395,18 @@ hipError_t launch_table_update(const TableArgs& a, const AdamHyper& hp, hipStrea
     const bool sem = a.g_bf16 != nullptr, box = a.off != nullptr;
     if (sem && (box || a.relu_gate)) return hipErrorInvalidValue;
     if (a.shadow && (sem || box)) return hipErrorInvalidValue;
+    bool upd = a.g_out == nullptr;        // every table of the launch is updated in place
+    for (int k = 0; k < n_small; ++k) upd = upd && small[k].g_out == nullptr;
+#define NGDB_TABLE_U(NCH, SEM_, BOX_, SH_, UPD_)                                                              \
+    do {                                                                                                      \
+        if (n_small) hipLaunchKernelGGL((table_group_kernel<NCH, SEM_, BOX_, SH_, UPD_>), dim3(blocks), dim3(256), 0, s, a, tail, hp); \
+        else if (a.streaming) hipLaunchKernelGGL((table_kernel<NCH, SEM_, BOX_, SH_, true, false>), dim3(tail.main_blocks), dim3(256), 0, s, a, hp); \
+        else hipLaunchKernelGGL((table_kernel<NCH, SEM_, BOX_, SH_, false, UPD_>), dim3(tail.main_blocks), dim3(256), 0, s, a, hp); \
+    } while (0)
 #define NGDB_TABLE_V(NCH, SEM_, BOX_, SH_)                                                                     \
     do {                                                                                                      \
-        if (n_small) hipLaunchKernelGGL((table_group_kernel<NCH, SEM_, BOX_, SH_>), dim3(blocks), dim3(256), 0, s, a, tail, hp); \
-        else if (a.streaming) hipLaunchKernelGGL((table_kernel<NCH, SEM_, BOX_, SH_, true>), dim3(tail.main_blocks), dim3(256), 0, s, a, hp); \
-        else hipLaunchKernelGGL((table_kernel<NCH, SEM_, BOX_, SH_, false>), dim3(tail.main_blocks), dim3(256), 0, s, a, hp); \
+        if (upd) NGDB_TABLE_U(NCH, SEM_, BOX_, SH_, true);                                                    \
+        else NGDB_TABLE_U(NCH, SEM_, BOX_, SH_, false);                                                       \
     } while (0)
 #define NGDB_TABLE(NCH)                                   \
     do {                                                  \
@@ -399,6 +420,7 @@ hipError_t launch_table_update(const TableArgs& a, const AdamHyper& hp, hipStrea
     else NGDB_TABLE(4);
 #undef NGDB_TABLE
 #undef NGDB_TABLE_V
+#undef NGDB_TABLE_U
     return hipGetLastError();
 }
 
