@@ -148,6 +148,14 @@ def test_candidate_scores_against_oracle():
     got = eng.score(plan, torch.from_numpy(cand).cuda()).cpu().numpy()
     want = orank.score_candidates(case.qb, cand, om.Model(case.params, 10.0))
     par.assert_close(got, want, "candidate scores")
+    # a candidate list too long for the kernel's stash of per-pair results (its other store path)
+    _say("ngdb_score candidate mode, 4500 candidates per query")
+    few = case.qb.select(list(range(12)))
+    plan = eng.plan(few)
+    cand = wl.make_negatives(500, 12, 4500, 5)
+    got = eng.score(plan, torch.from_numpy(cand).cuda()).cpu().numpy()
+    want = orank.score_candidates(few, cand, om.Model(case.params, 10.0))
+    par.assert_close(got, want, "candidate scores, long lists")
 
 
 @pytest.mark.parametrize("schedule,b_max,d_sem", [("level", 0, 0), ("max_fill", 0, 0), ("max_fill", 7, 0), ("level", 0, 64)])
