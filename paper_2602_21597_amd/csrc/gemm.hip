@@ -711,7 +711,12 @@ hipError_t launch_gemm_group(const GemmArgs* problems, int count, hipStream_t s,
     // weight gradients (k = all rows of an operator type) of a mid-size step: the large tile with
     // the split route beats the small tile with fp32 MFMAs although it leaves compute units idle
     const bool wgrad_big_tile = arith == GEMM_AUTO && !g.p[0].a_kcontig && max_k >= 512 && blocks_small >= 512;
-    if ((blocks_small >= 2048 || wgrad_big_tile) && arith != GEMM_SPLIT) {
+    // (with the B operands ready-made the small tile holds its own up to twice the size: 0.516 + 0.388
+    // against 0.537 + 0.416 ms for the forward and backward launches of 4096 queries at h = 800)
+    bool b_ready = g.p[0].a_kcontig;
+    for (int i = 0; i < g.count; ++i) b_ready = b_ready && g.p[i].b_pieces != nullptr && g.p[i].b_kt >= (g.p[i].K + 15) / 16;
+    const long big_at = b_ready && auto_split ? 4096 : 2048;
+    if ((blocks_small >= big_at || wgrad_big_tile) && arith != GEMM_SPLIT) {
         // (in the large tile every staged value feeds two MFMA blocks: there the split pays for
         // the weight gradients too)
         const bool big_split = arith == GEMM_AUTO && max_k >= 128;
